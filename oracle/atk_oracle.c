@@ -1,0 +1,219 @@
+/*
+ * CPU ORACLE for the generalized two-stage approximate Top-K.
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT PRODUCT CODE.  Only the tests, the smoke
+ * check and the benchmark's "cpu_baseline" leg may call it.  It shares no code,
+ * header, table or helper with the HIP library and must stay that way.
+ *
+ * What it computes is the definition of the method written out literally
+ * (paper Section 6.1, Steps 1-4), with no blocking, fusion or early exit:
+ *
+ *   Step 1  bucket i of a row holds the elements whose position n satisfies
+ *           n mod B == i  (0-based form of G_i = {a_{i+jB}}; Section 6.1 and
+ *           the [batch, N/B, B] view of Section 6.3).
+ *   Step 2  T_i = the K' greatest elements of bucket i.
+ *   Step 3  S   = union of all T_i            (B*K' elements).
+ *   Step 4  output = the K greatest elements of S, listed greatest first.
+ *
+ * "Greatest" needs a total order.  The paper leaves ties open (its listing is
+ * explicitly unstable); this build fixes them: element a comes before element
+ * b when value(a) > value(b), or the values compare equal and index(a) <
+ * index(b).  Values are compared numerically (so -0.0 equals +0.0 and the
+ * index decides); outputs carry the stored bits of the chosen element.
+ * Precondition: no NaN in the input (checked, returns -2).
+ *
+ * bf16 inputs are widened to binary32 before comparing (exact and order
+ * preserving; the promotion rule of Section 6.3's listing).
+ *
+ * The exact Top-K (the K greatest of all N elements in the same order) is the
+ * B = 1, K' = K case of the definition and is also provided on its own, written
+ * separately, so the two can be checked against each other.
+ *
+ * Rows are independent (the batch axis is the only parallel axis in the
+ * paper); the row loop carries an OpenMP pragma and nothing else is tuned.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+typedef struct {
+    float value;   /* numeric value used for comparisons */
+    int32_t index; /* position n inside the row */
+} element_t;
+
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+
+static float widen(const void *row, int dtype, int64_t n)
+{
+    if (dtype == ORACLE_F32) {
+        return ((const float *)row)[n];
+    } else {
+        uint32_t bits = (uint32_t)((const uint16_t *)row)[n] << 16;
+        float f;
+        memcpy(&f, &bits, sizeof f);
+        return f;
+    }
+}
+
+static size_t elem_size(int dtype) { return dtype == ORACLE_F32 ? 4 : 2; }
+
+/* qsort comparator: negative when a is "greater" (comes first). */
+static int greater_first(const void *pa, const void *pb)
+{
+    const element_t *a = (const element_t *)pa;
+    const element_t *b = (const element_t *)pb;
+    if (a->value > b->value) return -1;
+    if (a->value < b->value) return 1;
+    if (a->index < b->index) return -1;
+    if (a->index > b->index) return 1;
+    return 0;
+}
+
+static void store_output(const void *row, int dtype, const element_t *e,
+                         void *out_vals, int32_t *out_idx, int64_t pos)
+{
+    /* the stored bits of the chosen element, not a re-encoding of its value */
+    size_t es = elem_size(dtype);
+    memcpy((char *)out_vals + (size_t)pos * es,
+           (const char *)row + (size_t)e->index * es, es);
+    out_idx[pos] = e->index;
+}
+
+/* rows run in parallel; a failure in any of them is recorded once */
+static void set_status(int *status, int code)
+{
+#pragma omp atomic write
+    *status = code;
+}
+
+int atk_oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* Returns 0, -1 on bad arguments, -2 when a NaN is found, -3 on allocation failure. */
+static int check_args(const void *values, int dtype, int64_t rows, int64_t N,
+                      int64_t row_stride, int64_t K, int64_t Kp, int64_t B)
+{
+    if (!values || (dtype != ORACLE_F32 && dtype != ORACLE_BF16)) return -1;
+    if (rows < 0 || N <= 0 || row_stride < N || N > 2147483647LL) return -1;
+    if (B < 1 || N % B != 0) return -1;
+    if (Kp < 1 || Kp > K || Kp > N / B) return -1;
+    if (K > B * Kp || K > N) return -1;
+    return 0;
+}
+
+/*
+ * Stage 1 alone (Steps 1-2): survivors in the paper's physical layout
+ * [rows, K', B] (Section 6.3): plane k holds, for every bucket, its k-th
+ * greatest element.  surv_vals has the input dtype, surv_idx is int32.
+ */
+int atk_oracle_stage1(const void *values, int dtype, int64_t rows, int64_t N,
+                      int64_t row_stride, int64_t Kp, int64_t B,
+                      void *surv_vals, int32_t *surv_idx)
+{
+    int rc = check_args(values, dtype, rows, N, row_stride, Kp, Kp, B);
+    if (rc) return rc;
+    int64_t per_bucket = N / B;
+    int status = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t r = 0; r < rows; ++r) {
+        const char *row = (const char *)values + (size_t)r * row_stride * elem_size(dtype);
+        element_t *bucket = (element_t *)malloc(sizeof(element_t) * (size_t)per_bucket);
+        if (!bucket) { set_status(&status, -3); continue; }
+        for (int64_t b = 0; b < B; ++b) {
+            for (int64_t j = 0; j < per_bucket; ++j) {
+                int64_t n = b + j * B;
+                bucket[j].value = widen(row, dtype, n);
+                bucket[j].index = (int32_t)n;
+                if (isnan(bucket[j].value)) set_status(&status, -2);
+            }
+            qsort(bucket, (size_t)per_bucket, sizeof(element_t), greater_first);
+            for (int64_t k = 0; k < Kp; ++k) {
+                int64_t pos = k * B + b;
+                store_output(row, dtype, &bucket[k],
+                             (char *)surv_vals + (size_t)r * B * Kp * elem_size(dtype),
+                             surv_idx + r * B * Kp, pos);
+            }
+        }
+        free(bucket);
+    }
+    return status;
+}
+
+/* Steps 1-4. out_vals: [rows, K] in the input dtype; out_idx: [rows, K] int32. */
+int atk_oracle_approx_topk(const void *values, int dtype, int64_t rows, int64_t N,
+                           int64_t row_stride, int64_t K, int64_t Kp, int64_t B,
+                           void *out_vals, int32_t *out_idx)
+{
+    int rc = check_args(values, dtype, rows, N, row_stride, K, Kp, B);
+    if (rc) return rc;
+    int64_t per_bucket = N / B;
+    int status = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t r = 0; r < rows; ++r) {
+        const char *row = (const char *)values + (size_t)r * row_stride * elem_size(dtype);
+        element_t *bucket = (element_t *)malloc(sizeof(element_t) * (size_t)per_bucket);
+        element_t *selected = (element_t *)malloc(sizeof(element_t) * (size_t)(B * Kp));
+        if (!bucket || !selected) { set_status(&status, -3); free(bucket); free(selected); continue; }
+        int64_t n_selected = 0;
+        for (int64_t b = 0; b < B; ++b) {
+            /* Step 1: gather bucket b */
+            for (int64_t j = 0; j < per_bucket; ++j) {
+                int64_t n = b + j * B;
+                bucket[j].value = widen(row, dtype, n);
+                bucket[j].index = (int32_t)n;
+                if (isnan(bucket[j].value)) set_status(&status, -2);
+            }
+            /* Step 2: its K' greatest */
+            qsort(bucket, (size_t)per_bucket, sizeof(element_t), greater_first);
+            /* Step 3: union */
+            for (int64_t k = 0; k < Kp; ++k) selected[n_selected++] = bucket[k];
+        }
+        /* Step 4: sort the union, keep the first K */
+        qsort(selected, (size_t)n_selected, sizeof(element_t), greater_first);
+        for (int64_t k = 0; k < K; ++k)
+            store_output(row, dtype, &selected[k],
+                         (char *)out_vals + (size_t)r * K * elem_size(dtype),
+                         out_idx + r * K, k);
+        free(bucket);
+        free(selected);
+    }
+    return status;
+}
+
+/* Exact Top-K: the K greatest of all N elements of each row, greatest first. */
+int atk_oracle_topk(const void *values, int dtype, int64_t rows, int64_t N,
+                    int64_t row_stride, int64_t K, void *out_vals, int32_t *out_idx)
+{
+    if (!values || (dtype != ORACLE_F32 && dtype != ORACLE_BF16)) return -1;
+    if (rows < 0 || N <= 0 || row_stride < N || N > 2147483647LL) return -1;
+    if (K < 1 || K > N) return -1;
+    int status = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t r = 0; r < rows; ++r) {
+        const char *row = (const char *)values + (size_t)r * row_stride * elem_size(dtype);
+        element_t *all = (element_t *)malloc(sizeof(element_t) * (size_t)N);
+        if (!all) { set_status(&status, -3); continue; }
+        for (int64_t n = 0; n < N; ++n) {
+            all[n].value = widen(row, dtype, n);
+            all[n].index = (int32_t)n;
+            if (isnan(all[n].value)) set_status(&status, -2);
+        }
+        qsort(all, (size_t)N, sizeof(element_t), greater_first);
+        for (int64_t k = 0; k < K; ++k)
+            store_output(row, dtype, &all[k],
+                         (char *)out_vals + (size_t)r * K * elem_size(dtype),
+                         out_idx + r * K, k);
+        free(all);
+    }
+    return status;
+}
