@@ -1,0 +1,122 @@
+/*
+ * atk.h -- C ABI of libatk: generalized two-stage approximate Top-K on AMD MI355X (gfx950).
+ *
+ * The method (arXiv 2506.04165, Section 6.1): every row of length N is split into B buckets,
+ * bucket i holding the positions n with n mod B == i (Step 1); stage 1 keeps the K' greatest
+ * elements of every bucket (Step 2); stage 2 returns the K greatest of the B*K' survivors in
+ * descending order (Steps 3-4).  K' = 1 is the original algorithm of Section 5.
+ *
+ * Ordering.  The paper leaves ties open.  This library fixes one total order everywhere:
+ * element a precedes element b when value(a) > value(b), or the values compare equal (so
+ * -0.0 == +0.0) and index(a) < index(b).  Every result is therefore unique and can be compared
+ * bit for bit.  Precondition: the input holds no NaN (behaviour with NaN is unspecified but
+ * memory safe).
+ *
+ * Conventions for every entry point below
+ *   - all data pointers are DEVICE pointers to memory owned by the caller; the library never
+ *     allocates, frees or keeps device memory, and never synchronises: work is enqueued on
+ *     `stream` (a hipStream_t passed as void*, NULL = the default stream) and the call returns;
+ *   - `values` is row-major [rows, N] with `row_stride` elements between consecutive rows
+ *     (row_stride >= N); outputs are dense row-major;
+ *   - dtype: ATK_F32 = IEEE binary32, ATK_BF16 = bfloat16 (compared after exact widening to
+ *     binary32, Section 6.3); output values have the input dtype and are the stored bits of the
+ *     selected elements; indices are int32 positions inside the row;
+ *   - the return value is an atk_status; arguments are validated on the host before anything
+ *     is launched, so every error below can be provoked without a GPU;
+ *   - rows == 0 is legal and does nothing.
+ */
+#ifndef ATK_H_
+#define ATK_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum atk_dtype { ATK_F32 = 0, ATK_BF16 = 1 } atk_dtype;
+
+typedef enum atk_status {
+    ATK_OK = 0,
+    /* null pointer, rows < 0, N <= 0, N >= 2^31, row_stride < N, B < 1, B does not divide N
+     * (Section 6.3 requires equal buckets), K' < 1, K' > K (abstract: 1 <= K' <= K), K' > N/B,
+     * K > B*K', K > N, K < 1, misaligned pointer */
+    ATK_INVALID_ARG = 1,
+    /* legal by the definition but outside what the kernels cover (see atk_approx_topk) */
+    ATK_UNSUPPORTED = 2,
+    ATK_WORKSPACE_TOO_SMALL = 3,
+    /* a HIP call failed; atk_last_hip_error() holds its text */
+    ATK_HIP_ERROR = 4
+} atk_status;
+
+typedef enum atk_op { ATK_OP_APPROX_TOPK = 0, ATK_OP_TOPK = 1, ATK_OP_STAGE1 = 2 } atk_op;
+
+/*
+ * Two-stage approximate Top-K (Section 6.1 Steps 1-4; stage 1 as Section 6.3, stage 2 exact).
+ *   values     [rows, N] device, dtype as given
+ *   K, Kprime, B   the paper's K, K' and number of buckets; 1 <= K' <= min(K, N/B), B | N,
+ *                  K <= B*K'
+ *   out_vals   [rows, K] device, input dtype, descending in the total order
+ *   out_idx    [rows, K] device, int32
+ *   workspace  device scratch of at least atk_workspace_bytes(ATK_OP_APPROX_TOPK, ...) bytes, or
+ *              NULL when that is 0 (it is 0 whenever stage 2 runs fused in the stage-1 launch,
+ *              i.e. when the B*K' survivors of a row fit in LDS; otherwise survivors go through
+ *              this buffer and a second launch finishes)
+ * ATK_UNSUPPORTED: K' > 32 unless K' == K (then the exact kernel runs); B*K' > 32768;
+ * K > 2048 on the exact and unfused routes.
+ */
+int atk_approx_topk(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride,
+                    int K, int Kprime, int B, void* out_vals, int32_t* out_idx,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Exact Top-K of every row under the same total order (the comparison system of Section 7; also
+ * what the method reduces to at K' = K or B = 1).  Arguments as above.  ATK_UNSUPPORTED: K > 2048.
+ */
+int atk_topk(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride, int K,
+             void* out_vals, int32_t* out_idx, void* workspace, size_t workspace_bytes,
+             void* stream);
+
+/*
+ * Stage 1 alone (Section 6.1 Steps 1-2): the survivors, in the physical layout of Section 6.3:
+ *   surv_vals  [rows, K', B] device, input dtype: plane k holds every bucket's k-th greatest
+ *   surv_idx   [rows, K', B] device, int32
+ * This is the first launch of the unfused path and the hook for testing stage 1 on its own.
+ */
+int atk_approx_topk_stage1(const void* values, int dtype, int64_t rows, int64_t N,
+                           int64_t row_stride, int Kprime, int B, void* surv_vals,
+                           int32_t* surv_idx, void* stream);
+
+/* Scratch bytes the given operation needs (0 when it runs without); SIZE_MAX on illegal
+ * arguments.  Host only. */
+size_t atk_workspace_bytes(int op, int dtype, int64_t rows, int64_t N, int K, int Kprime, int B);
+
+/*
+ * Expected recall of the method under uniformly random placement of the Top-K (Theorem 1):
+ *   1 - (B/K) * sum_{r=K'+1}^{min(K,N/B)} (r-K') C(K,r) C(N-K,N/B-r) / C(N,N/B).
+ * Host only, double precision via log-gamma; returns a negative value on illegal arguments.
+ */
+double atk_expected_recall(int64_t N, int64_t B, int64_t K, int64_t Kprime);
+
+/*
+ * Writes a one-line description of how atk_approx_topk would run the given problem (kernel
+ * variant, lanes per row, workgroup shape, LDS and workspace bytes) into buf.  Host only; for
+ * logs and tests.  Returns the status atk_approx_topk would return for these arguments.
+ */
+int atk_describe_plan(int dtype, int64_t rows, int64_t N, int K, int Kprime, int B, char* buf,
+                      size_t buflen);
+
+/* Static, human-readable name of a status code. */
+const char* atk_status_string(int status);
+
+/* Text of the most recent HIP error seen by this thread's calls ("" if none). */
+const char* atk_last_hip_error(void);
+
+/* Library version, e.g. "0.1.0". */
+const char* atk_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ATK_H_ */

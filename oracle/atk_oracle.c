@@ -86,8 +86,8 @@ static void store_output(const void *row, int dtype, const element_t *e,
 /* rows run in parallel; a failure in any of them is recorded once */
 static void set_status(int *status, int code)
 {
-#pragma omp atomic write
-    *status = code;
+#pragma omp critical(atk_oracle_status)
+    { *status = code; }
 }
 
 int atk_oracle_num_threads(void)

@@ -13,6 +13,7 @@ def __getattr__(name):
     # (input generators, build) work before anything is compiled
     if name in ("binding", "approx_topk", "topk", "approx_topk_stage1", "expected_recall",
                 "workspace_bytes", "status_string", "AtkError"):
-        from . import binding
+        import importlib
+        binding = importlib.import_module(__name__ + ".binding")
         return binding if name == "binding" else getattr(binding, name)
     raise AttributeError(name)

@@ -1,0 +1,169 @@
+"""ctypes binding to libatk.so -- argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU, passes their
+device pointers and the current HIP stream through the C ABI declared in
+``include/atk.h`` and returns torch tensors.  No step of the method runs here;
+if the shared library is missing the import fails loudly (there is no CPU
+fallback).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libatk.so")
+
+F32, BF16 = 0, 1
+OK, INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP_ERROR = range(5)
+OP_APPROX_TOPK, OP_TOPK, OP_STAGE1 = 0, 1, 2
+SIZE_MAX = ctypes.c_size_t(-1).value
+
+EXPORTS = [
+    "atk_approx_topk", "atk_topk", "atk_approx_topk_stage1", "atk_workspace_bytes",
+    "atk_expected_recall", "atk_describe_plan", "atk_status_string", "atk_last_hip_error",
+    "atk_version",
+]
+
+
+class AtkError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        name = status_string(status)
+        extra = f": {last_hip_error()}" if status == HIP_ERROR else ""
+        super().__init__(f"{what} failed with {name}{extra}")
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2506_04165_amd.build` "
+            "(this package has no CPU fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    i64, vp, ci, sz = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    lib.atk_approx_topk.argtypes = [vp, ci, i64, i64, i64, ci, ci, ci, vp, vp, vp, sz, vp]
+    lib.atk_approx_topk.restype = ci
+    lib.atk_topk.argtypes = [vp, ci, i64, i64, i64, ci, vp, vp, vp, sz, vp]
+    lib.atk_topk.restype = ci
+    lib.atk_approx_topk_stage1.argtypes = [vp, ci, i64, i64, i64, ci, ci, vp, vp, vp]
+    lib.atk_approx_topk_stage1.restype = ci
+    lib.atk_workspace_bytes.argtypes = [ci, ci, i64, i64, ci, ci, ci]
+    lib.atk_workspace_bytes.restype = sz
+    lib.atk_expected_recall.argtypes = [i64, i64, i64, i64]
+    lib.atk_expected_recall.restype = ctypes.c_double
+    lib.atk_describe_plan.argtypes = [ci, i64, i64, ci, ci, ci, ctypes.c_char_p, sz]
+    lib.atk_describe_plan.restype = ci
+    lib.atk_status_string.argtypes = [ci]
+    lib.atk_status_string.restype = ctypes.c_char_p
+    lib.atk_last_hip_error.restype = ctypes.c_char_p
+    lib.atk_version.restype = ctypes.c_char_p
+    return lib
+
+
+lib = _load()
+
+
+def status_string(status: int) -> str:
+    return lib.atk_status_string(int(status)).decode()
+
+
+def last_hip_error() -> str:
+    return lib.atk_last_hip_error().decode()
+
+
+def version() -> str:
+    return lib.atk_version().decode()
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}: float32 or bfloat16")
+
+
+def _check_input(values: torch.Tensor):
+    if values.dim() != 2:
+        raise ValueError("values must be [rows, N]")
+    if not values.is_cuda:
+        raise ValueError("values must live on the GPU (this library has no CPU path)")
+    if values.stride(1) != 1:
+        raise ValueError("values must be contiguous along the last axis")
+    rows, N = values.shape
+    stride = values.stride(0) if rows > 1 else max(values.stride(0), N)
+    return rows, N, stride
+
+
+def _stream_ptr(device) -> int:
+    return torch.cuda.current_stream(device).cuda_stream
+
+
+def workspace_bytes(op: int, dtype: torch.dtype, rows: int, N: int, K: int, Kprime: int, B: int) -> int:
+    code = F32 if dtype == torch.float32 else BF16
+    return int(lib.atk_workspace_bytes(op, code, rows, N, K, Kprime, B))
+
+
+def describe_plan(dtype: torch.dtype, rows: int, N: int, K: int, Kprime: int, B: int):
+    code = F32 if dtype == torch.float32 else BF16
+    buf = ctypes.create_string_buffer(512)
+    st = lib.atk_describe_plan(code, rows, N, K, Kprime, B, buf, 512)
+    return st, buf.value.decode()
+
+
+def expected_recall(N: int, B: int, K: int, Kprime: int) -> float:
+    return float(lib.atk_expected_recall(N, B, K, Kprime))
+
+
+def approx_topk(values: torch.Tensor, K: int, Kprime: int, B: int, out=None, workspace=None):
+    """Two-stage approximate Top-K of every row.  Returns (vals[rows,K], idx[rows,K] int32)."""
+    rows, N, stride = _check_input(values)
+    code = _dtype_code(values)
+    if out is None:
+        out_vals = torch.empty((rows, K), dtype=values.dtype, device=values.device)
+        out_idx = torch.empty((rows, K), dtype=torch.int32, device=values.device)
+    else:
+        out_vals, out_idx = out
+    need = lib.atk_workspace_bytes(OP_APPROX_TOPK, code, rows, N, K, Kprime, B)
+    ws_ptr, ws_bytes = None, 0
+    if need != SIZE_MAX and need > 0:
+        if workspace is None or workspace.numel() * workspace.element_size() < need:
+            workspace = torch.empty(need, dtype=torch.uint8, device=values.device)
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    st = lib.atk_approx_topk(values.data_ptr(), code, rows, N, stride, K, Kprime, B,
+                             out_vals.data_ptr(), out_idx.data_ptr(), ws_ptr, ws_bytes,
+                             _stream_ptr(values.device))
+    if st != OK:
+        raise AtkError(st, "atk_approx_topk")
+    return out_vals, out_idx
+
+
+def topk(values: torch.Tensor, K: int, out=None):
+    """Exact Top-K of every row under the library's total order."""
+    rows, N, stride = _check_input(values)
+    code = _dtype_code(values)
+    if out is None:
+        out_vals = torch.empty((rows, K), dtype=values.dtype, device=values.device)
+        out_idx = torch.empty((rows, K), dtype=torch.int32, device=values.device)
+    else:
+        out_vals, out_idx = out
+    st = lib.atk_topk(values.data_ptr(), code, rows, N, stride, K, out_vals.data_ptr(),
+                      out_idx.data_ptr(), None, 0, _stream_ptr(values.device))
+    if st != OK:
+        raise AtkError(st, "atk_topk")
+    return out_vals, out_idx
+
+
+def approx_topk_stage1(values: torch.Tensor, Kprime: int, B: int):
+    """Stage 1 only: survivors (vals[rows,K',B], idx[rows,K',B] int32)."""
+    rows, N, stride = _check_input(values)
+    code = _dtype_code(values)
+    sv = torch.empty((rows, Kprime, B), dtype=values.dtype, device=values.device)
+    si = torch.empty((rows, Kprime, B), dtype=torch.int32, device=values.device)
+    st = lib.atk_approx_topk_stage1(values.data_ptr(), code, rows, N, stride, Kprime, B,
+                                    sv.data_ptr(), si.data_ptr(), _stream_ptr(values.device))
+    if st != OK:
+        raise AtkError(st, "atk_approx_topk_stage1")
+    return sv, si

@@ -1,0 +1,350 @@
+// C ABI of libatk: argument validation, launch planning and dispatch (host code only).
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <string>
+
+#include "../../include/atk.h"
+#include "approx_instances.h"
+#include "approx_kernel.h"
+#include "topk_exact.h"
+
+namespace atk {
+
+// ---- compiled kernel variants -------------------------------------------------------------
+using LaunchFn = hipError_t (*)(const ApproxParams&, int, int, size_t, hipStream_t);
+struct Variant { int dtype, KP, V, R; LaunchFn fn; };
+
+#define ATK_X(TAG, T, KP, V, R) extern template hipError_t launch_approx<T, KP, V, R>(const ApproxParams&, int, int, size_t, hipStream_t);
+ATK_ALL_INSTANCES(ATK_X)
+#undef ATK_X
+
+static const Variant kVariants[] = {
+#define ATK_X(TAG, T, KP, V, R) {TAG, KP, V, R, &launch_approx<T, KP, V, R>},
+    ATK_ALL_INSTANCES(ATK_X)
+#undef ATK_X
+};
+
+// The variant with the given list length and lists per lane; `vector_ok(V)` says whether
+// V-element loads are legal for this problem.  The widest legal load wins.
+template <typename Pred>
+static const Variant* find_variant(int dtype, int KP, int NL, Pred vector_ok) {
+    const Variant* best = nullptr;
+    for (const Variant& v : kVariants)
+        if (v.dtype == dtype && v.KP == KP && v.V * v.R == NL && vector_ok(v.V) &&
+            (!best || v.V > best->V))
+            best = &v;
+    return best;
+}
+
+// ---- limits -------------------------------------------------------------------------------
+constexpr int kMaxListLen = 32;          // longest K'-list kept in registers
+constexpr int kMaxEntriesPerLane = 32;   // V*R*KP
+constexpr int kMaxLanes = 1024;
+constexpr size_t kLdsBudget = 64 * 1024; // dynamic LDS per workgroup used by the fused kernel
+constexpr int kExactCap = 4096;          // exact kernel: LDS key buffer
+constexpr int kExactMaxK = 2048;
+
+static thread_local std::string g_last_hip_error;
+
+static int pow2_ceil(int64_t x) { int p = 1; while (p < x) p <<= 1; return p; }
+static int pow2_floor(int64_t x) { int p = 1; while ((int64_t)p * 2 <= x) p <<= 1; return p; }
+static int ilog2(int x) { int l = 0; while ((1 << l) < x) ++l; return l; }
+static bool is_pow2(int64_t x) { return x > 0 && (x & (x - 1)) == 0; }
+static int elem_size(int dtype) { return dtype == ATK_F32 ? 4 : 2; }
+
+static int env_int(const char* name, int fallback) {
+    const char* s = std::getenv(name);
+    return (s && *s) ? std::atoi(s) : fallback;
+}
+
+// ---- validation (host only; every error can be provoked without a GPU) ----------------------
+static int validate_common(const void* values, int dtype, int64_t rows, int64_t N,
+                           int64_t row_stride) {
+    if (dtype != ATK_F32 && dtype != ATK_BF16) return ATK_UNSUPPORTED;
+    if (rows < 0 || rows > 0x7fffffff || N <= 0 || N > 0x7fffffffLL || row_stride < N)
+        return ATK_INVALID_ARG;
+    if (rows > 0 && !values) return ATK_INVALID_ARG;
+    if ((uintptr_t)values % elem_size(dtype)) return ATK_INVALID_ARG;
+    return ATK_OK;
+}
+
+static int validate_method(int64_t N, int K, int Kp, int B) {
+    if (B < 1 || N % B != 0) return ATK_INVALID_ARG;             // equal buckets (Section 6.3)
+    if (Kp < 1 || Kp > K || (int64_t)Kp > N / B) return ATK_INVALID_ARG;   // 1 <= K' <= K
+    if (K < 1 || (int64_t)K > (int64_t)B * Kp || (int64_t)K > N) return ATK_INVALID_ARG;
+    return ATK_OK;
+}
+
+// ---- launch plan --------------------------------------------------------------------------
+struct Plan {
+    int status = ATK_OK;
+    bool route_exact = false;   // K' == K: the method is the exact Top-K (Section 1)
+    bool fused = true;
+    const Variant* var = nullptr;
+    int G = 0, rows_per_wg = 1, S = 0, nsteps = 0, owners = 1, seg = 0, Cpad = 0;
+    int block = 0, grid = 0;
+    size_t lds = 0;
+    size_t workspace = 0;
+};
+
+static int list_len_for(int Kp) {
+    static const int lens[] = {1, 2, 3, 4, 6, 8, 16, 32};
+    for (int l : lens) if (l >= Kp) return l;
+    return 0;
+}
+
+// Choose how lanes map to buckets.  `stage1_only` plans the survivor-writing launch.
+static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride,
+                      int K, int Kp, int B, bool stage1_only) {
+    Plan pl;
+    const int es = elem_size(dtype);
+    const int KP = list_len_for(Kp);
+    if (KP == 0 || KP > kMaxListLen) {
+        if (Kp == K && !stage1_only) { pl.route_exact = true; return pl; }
+        pl.status = ATK_UNSUPPORTED;
+        return pl;
+    }
+    int maxNL = kMaxEntriesPerLane / KP;
+    if (maxNL > 16) maxNL = 16;
+    maxNL = pow2_floor(maxNL);
+
+    // lanes we would like on one row: about 224 elements per lane, within [64, 1024]
+    int Gd = pow2_floor(N / 224 > 0 ? N / 224 : 1);
+    if (Gd < 64) Gd = 64;
+    if (Gd > kMaxLanes) Gd = kMaxLanes;
+    Gd = env_int("ATK_LANES_PER_ROW", Gd);
+    if (!is_pow2(Gd) || Gd > kMaxLanes) { pl.status = ATK_INVALID_ARG; return pl; }
+
+    auto aligned_for = [&](int V) {
+        return B % V == 0 && row_stride % V == 0 && ((uintptr_t)values % (size_t)(V * es)) == 0;
+    };
+
+    int G = 0, NL = 1, owners = 1;
+    const bool want_shared = B < Gd && B < 64 && is_pow2(B);
+    if (want_shared) {
+        // several lanes per bucket; partial lists merged through LDS
+        G = Gd;
+        while (G > B && (N % G != 0)) G >>= 1;
+        // keep partial lists + candidates inside the LDS budget
+        while (G > B && (size_t)(pow2_ceil((int64_t)(G / B) * KP) * B + pow2_ceil((int64_t)B * Kp)) * 8 > kLdsBudget)
+            G >>= 1;
+        if (G > B) { owners = G / B; NL = 1; }
+        else G = 0;
+    }
+    if (G == 0) {
+        owners = 1;
+        G = B >= Gd ? Gd : pow2_ceil(B);
+        if (G > kMaxLanes) G = kMaxLanes;
+        for (;;) {
+            NL = pow2_ceil((B + G - 1) / G);
+            if (NL <= maxNL) break;
+            if (G >= kMaxLanes) { pl.status = ATK_UNSUPPORTED; return pl; }
+            G <<= 1;
+        }
+    }
+    pl.var = find_variant(dtype, KP, NL, aligned_for);
+    if (!pl.var) { pl.status = ATK_UNSUPPORTED; return pl; }
+    const int V = pl.var->V;
+    pl.G = G;
+    pl.owners = owners;
+    pl.S = owners > 1 ? G * V : B;
+    pl.nsteps = (int)(N / pl.S);
+    pl.seg = owners > 1 ? pow2_ceil((int64_t)owners * KP) : 0;
+    pl.Cpad = pow2_ceil((int64_t)B * Kp);
+
+    // rows per workgroup: fill 256 lanes when one row needs fewer
+    int rpw = G >= 256 ? 1 : 256 / G;
+    while (rpw > 1 && rpw / 2 >= rows) rpw >>= 1;
+    auto lds_for = [&](int r) {
+        size_t keys = 0;
+        if (owners > 1) keys = (size_t)r * ((size_t)pl.Cpad + (size_t)B * pl.seg);
+        else if (!stage1_only) keys = (size_t)r * pl.Cpad;
+        return keys * 8;
+    };
+    while (rpw > 1 && lds_for(rpw) > kLdsBudget) rpw >>= 1;
+    if (G * rpw < 64) rpw = 64 / G;          // never launch less than a wavefront
+    pl.rows_per_wg = rpw;
+    pl.lds = lds_for(rpw);
+    pl.block = G * rpw;
+    pl.grid = (int)((rows + rpw - 1) / rpw);
+    pl.fused = !stage1_only && pl.lds <= kLdsBudget;
+    if (!stage1_only && !pl.fused) {
+        // survivors go through memory: values (input dtype) + int32 indices
+        pl.workspace = (size_t)rows * B * Kp * (es + 4);
+        pl.lds = owners > 1 ? lds_for(rpw) : 0;
+        if (pl.lds > kLdsBudget) { pl.status = ATK_UNSUPPORTED; return pl; }
+        if (K > kExactMaxK) { pl.status = ATK_UNSUPPORTED; return pl; }
+    }
+    if (stage1_only && pl.lds > kLdsBudget) { pl.status = ATK_UNSUPPORTED; return pl; }
+    return pl;
+}
+
+static ApproxParams params_from(const Plan& pl, const void* values, int64_t rows, int64_t N,
+                                int64_t row_stride, int K, int Kp, int B) {
+    ApproxParams p{};
+    p.values = values;
+    p.row_stride = row_stride;
+    p.rows = (int)rows; p.N = (int)N; p.K = K; p.Kprime = Kp; p.B = B;
+    p.G = pl.G; p.log2G = ilog2(pl.G);
+    p.rows_per_wg = pl.rows_per_wg;
+    p.S = pl.S; p.nsteps = pl.nsteps; p.owners = pl.owners; p.seg = pl.seg; p.Cpad = pl.Cpad;
+    return p;
+}
+
+static int hip_fail(hipError_t e) {
+    g_last_hip_error = hipGetErrorString(e);
+    return ATK_HIP_ERROR;
+}
+
+static int exact_threads(int64_t N) {
+    int t = pow2_ceil((N + 15) / 16);
+    if (t < 64) t = 64;
+    if (t > 1024) t = 1024;
+    return t;
+}
+
+static int run_exact(const void* values, const int32_t* payload, int dtype, int64_t rows, int64_t N,
+                     int64_t row_stride, int K, void* out_vals, int32_t* out_idx, hipStream_t st) {
+    if (K > kExactMaxK) return ATK_UNSUPPORTED;
+    TopkParams tp{};
+    tp.values = values; tp.payload = payload; tp.row_stride = row_stride;
+    tp.rows = (int)rows; tp.N = (int)N; tp.K = K; tp.cap = kExactCap;
+    tp.out_vals = out_vals; tp.out_idx = out_idx;
+    hipError_t e = launch_topk_exact(tp, dtype, exact_threads(N), st);
+    return e == hipSuccess ? ATK_OK : hip_fail(e);
+}
+
+}  // namespace atk
+
+using namespace atk;
+
+extern "C" {
+
+int atk_approx_topk(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride,
+                    int K, int Kprime, int B, void* out_vals, int32_t* out_idx,
+                    void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = validate_common(values, dtype, rows, N, row_stride);
+    if (rc) return rc;
+    rc = validate_method(N, K, Kprime, B);
+    if (rc) return rc;
+    if (rows > 0 && (!out_vals || !out_idx)) return ATK_INVALID_ARG;
+    if ((uintptr_t)out_vals % elem_size(dtype) || (uintptr_t)out_idx % 4) return ATK_INVALID_ARG;
+    Plan pl = make_plan(values, dtype, rows, N, row_stride, K, Kprime, B, false);
+    if (pl.status) return pl.status;
+    if (pl.route_exact && K > kExactMaxK) return ATK_UNSUPPORTED;
+    if (pl.workspace > 0 && (!workspace || workspace_bytes < pl.workspace))
+        return ATK_WORKSPACE_TOO_SMALL;
+    if (rows == 0) return ATK_OK;
+    hipStream_t st = (hipStream_t)stream;
+    if (pl.route_exact)
+        return run_exact(values, nullptr, dtype, rows, N, row_stride, K, out_vals, out_idx, st);
+
+    ApproxParams p = params_from(pl, values, rows, N, row_stride, K, Kprime, B);
+    if (pl.fused) {
+        p.mode = 0;
+        p.out_vals = out_vals; p.out_idx = out_idx;
+        hipError_t e = pl.var->fn(p, pl.grid, pl.block, pl.lds, st);
+        return e == hipSuccess ? ATK_OK : hip_fail(e);
+    }
+    // unfused: survivors [rows, K', B] through the workspace, then exact Top-K over them
+    const int64_t C = (int64_t)B * Kprime;
+    char* ws = (char*)workspace;
+    int32_t* surv_idx = (int32_t*)ws;                                  // 4-byte part first
+    void* surv_vals = ws + (size_t)rows * C * 4;
+    p.mode = 1;
+    p.surv_vals = surv_vals; p.surv_idx = surv_idx;
+    hipError_t e = pl.var->fn(p, pl.grid, pl.block, pl.lds, st);
+    if (e != hipSuccess) return hip_fail(e);
+    return run_exact(surv_vals, surv_idx, dtype, rows, C, C, K, out_vals, out_idx, st);
+}
+
+int atk_topk(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride, int K,
+             void* out_vals, int32_t* out_idx, void* workspace, size_t workspace_bytes,
+             void* stream) {
+    (void)workspace; (void)workspace_bytes;
+    int rc = validate_common(values, dtype, rows, N, row_stride);
+    if (rc) return rc;
+    if (K < 1 || (int64_t)K > N) return ATK_INVALID_ARG;
+    if (rows > 0 && (!out_vals || !out_idx)) return ATK_INVALID_ARG;
+    if ((uintptr_t)out_vals % elem_size(dtype) || (uintptr_t)out_idx % 4) return ATK_INVALID_ARG;
+    if (K > kExactMaxK) return ATK_UNSUPPORTED;
+    if (rows == 0) return ATK_OK;
+    return run_exact(values, nullptr, dtype, rows, N, row_stride, K, out_vals, out_idx,
+                     (hipStream_t)stream);
+}
+
+int atk_approx_topk_stage1(const void* values, int dtype, int64_t rows, int64_t N,
+                           int64_t row_stride, int Kprime, int B, void* surv_vals,
+                           int32_t* surv_idx, void* stream) {
+    int rc = validate_common(values, dtype, rows, N, row_stride);
+    if (rc) return rc;
+    // stage 1 has no K of its own: any K in [K', B*K'] makes the same survivors
+    rc = validate_method(N, Kprime, Kprime, B);
+    if (rc) return rc;
+    if (rows > 0 && (!surv_vals || !surv_idx)) return ATK_INVALID_ARG;
+    if ((uintptr_t)surv_vals % elem_size(dtype) || (uintptr_t)surv_idx % 4) return ATK_INVALID_ARG;
+    Plan pl = make_plan(values, dtype, rows, N, row_stride, Kprime, Kprime, B, true);
+    if (pl.status) return pl.status;
+    if (rows == 0) return ATK_OK;
+    ApproxParams p = params_from(pl, values, rows, N, row_stride, Kprime, Kprime, B);
+    p.mode = 1;
+    p.surv_vals = surv_vals; p.surv_idx = surv_idx;
+    hipError_t e = pl.var->fn(p, pl.grid, pl.block, pl.lds, (hipStream_t)stream);
+    return e == hipSuccess ? ATK_OK : hip_fail(e);
+}
+
+size_t atk_workspace_bytes(int op, int dtype, int64_t rows, int64_t N, int K, int Kprime, int B) {
+    if (dtype != ATK_F32 && dtype != ATK_BF16) return SIZE_MAX;
+    if (rows < 0 || N <= 0 || N > 0x7fffffffLL) return SIZE_MAX;
+    if (op == ATK_OP_TOPK) return (K < 1 || K > N) ? SIZE_MAX : 0;
+    if (op == ATK_OP_STAGE1) return validate_method(N, Kprime, Kprime, B) ? SIZE_MAX : 0;
+    if (op != ATK_OP_APPROX_TOPK) return SIZE_MAX;
+    if (validate_method(N, K, Kprime, B)) return SIZE_MAX;
+    // alignment of the real buffers is not known here; assume the allocator's (>= 16 bytes)
+    Plan pl = make_plan(nullptr, dtype, rows, N, N, K, Kprime, B, false);
+    if (pl.status) return SIZE_MAX;
+    return pl.workspace;
+}
+
+int atk_describe_plan(int dtype, int64_t rows, int64_t N, int K, int Kprime, int B, char* buf,
+                      size_t buflen) {
+    if (!buf || buflen == 0) return ATK_INVALID_ARG;
+    buf[0] = 0;
+    if (dtype != ATK_F32 && dtype != ATK_BF16) return ATK_UNSUPPORTED;
+    if (rows < 0 || N <= 0 || N > 0x7fffffffLL) return ATK_INVALID_ARG;
+    int rc = validate_method(N, K, Kprime, B);
+    if (rc) return rc;
+    Plan pl = make_plan(nullptr, dtype, rows, N, N, K, Kprime, B, false);
+    if (pl.status) return pl.status;
+    if (pl.route_exact) {
+        std::snprintf(buf, buflen, "exact(K'=K) threads=%d", exact_threads(N));
+        return ATK_OK;
+    }
+    std::snprintf(buf, buflen,
+                  "%s KP=%d V=%d R=%d lanes_per_row=%d rows_per_wg=%d block=%d grid=%d step=%d "
+                  "steps=%d owners=%d seg=%d cand=%d lds=%zu workspace=%zu",
+                  pl.fused ? "fused" : "unfused", pl.var->KP, pl.var->V, pl.var->R, pl.G,
+                  pl.rows_per_wg, pl.block, pl.grid, pl.S, pl.nsteps, pl.owners, pl.seg, pl.Cpad,
+                  pl.lds, pl.workspace);
+    return ATK_OK;
+}
+
+const char* atk_status_string(int status) {
+    switch (status) {
+        case ATK_OK: return "ATK_OK";
+        case ATK_INVALID_ARG: return "ATK_INVALID_ARG";
+        case ATK_UNSUPPORTED: return "ATK_UNSUPPORTED";
+        case ATK_WORKSPACE_TOO_SMALL: return "ATK_WORKSPACE_TOO_SMALL";
+        case ATK_HIP_ERROR: return "ATK_HIP_ERROR";
+        default: return "ATK_UNKNOWN_STATUS";
+    }
+}
+
+const char* atk_last_hip_error(void) { return g_last_hip_error.c_str(); }
+
+const char* atk_version(void) { return "0.1.0"; }
+
+}  // extern "C"

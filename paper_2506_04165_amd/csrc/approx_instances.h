@@ -1,0 +1,44 @@
+// The list of compiled (dtype, KP, V, R) variants of the fused kernel.
+//   KP  list length held in registers (>= the requested K'; shorter requests use a prefix)
+//   V   consecutive elements per load, R loads per step; V*R lists per lane
+// Register budget: V*R*KP <= 32 list entries per lane.
+#pragma once
+
+// X(DTYPE_TAG, C++ type, KP, V, R)
+#define ATK_INSTANCES_NL1(X, TAG, T, V, R) \
+    X(TAG, T, 1, V, R) X(TAG, T, 2, V, R) X(TAG, T, 3, V, R) X(TAG, T, 4, V, R) \
+    X(TAG, T, 6, V, R) X(TAG, T, 8, V, R) X(TAG, T, 16, V, R) X(TAG, T, 32, V, R)
+#define ATK_INSTANCES_NL2(X, TAG, T, V, R) \
+    X(TAG, T, 1, V, R) X(TAG, T, 2, V, R) X(TAG, T, 3, V, R) X(TAG, T, 4, V, R) \
+    X(TAG, T, 6, V, R) X(TAG, T, 8, V, R) X(TAG, T, 16, V, R)
+#define ATK_INSTANCES_NL4(X, TAG, T, V, R) \
+    X(TAG, T, 1, V, R) X(TAG, T, 2, V, R) X(TAG, T, 3, V, R) X(TAG, T, 4, V, R) \
+    X(TAG, T, 6, V, R) X(TAG, T, 8, V, R)
+#define ATK_INSTANCES_NL8(X, TAG, T, V, R) \
+    X(TAG, T, 1, V, R) X(TAG, T, 2, V, R) X(TAG, T, 3, V, R) X(TAG, T, 4, V, R)
+#define ATK_INSTANCES_NL16(X, TAG, T, V, R) \
+    X(TAG, T, 1, V, R) X(TAG, T, 2, V, R)
+
+#define ATK_INSTANCES_F32_SMALL(X) \
+    ATK_INSTANCES_NL1(X, 0, float, 1, 1) ATK_INSTANCES_NL2(X, 0, float, 2, 1)
+#define ATK_INSTANCES_F32_WIDE(X) \
+    ATK_INSTANCES_NL4(X, 0, float, 4, 1) ATK_INSTANCES_NL8(X, 0, float, 4, 2) \
+    ATK_INSTANCES_NL16(X, 0, float, 4, 4)
+#define ATK_INSTANCES_BF16_SMALL(X) \
+    ATK_INSTANCES_NL1(X, 1, bf16_t, 1, 1) ATK_INSTANCES_NL2(X, 1, bf16_t, 2, 1)
+#define ATK_INSTANCES_BF16_WIDE(X) \
+    ATK_INSTANCES_NL4(X, 1, bf16_t, 4, 1) ATK_INSTANCES_NL8(X, 1, bf16_t, 8, 1) \
+    ATK_INSTANCES_NL16(X, 1, bf16_t, 8, 2)
+
+// single-element loads with several loads per step: for rows whose base address, stride or
+// bucket count rule out vector loads
+#define ATK_INSTANCES_F32_UNALIGNED(X) \
+    ATK_INSTANCES_NL2(X, 0, float, 1, 2) ATK_INSTANCES_NL4(X, 0, float, 1, 4) \
+    ATK_INSTANCES_NL8(X, 0, float, 1, 8) ATK_INSTANCES_NL16(X, 0, float, 1, 16)
+#define ATK_INSTANCES_BF16_UNALIGNED(X) \
+    ATK_INSTANCES_NL2(X, 1, bf16_t, 1, 2) ATK_INSTANCES_NL4(X, 1, bf16_t, 1, 4) \
+    ATK_INSTANCES_NL8(X, 1, bf16_t, 1, 8) ATK_INSTANCES_NL16(X, 1, bf16_t, 1, 16)
+
+#define ATK_ALL_INSTANCES(X) \
+    ATK_INSTANCES_F32_SMALL(X) ATK_INSTANCES_F32_WIDE(X) ATK_INSTANCES_F32_UNALIGNED(X) \
+    ATK_INSTANCES_BF16_SMALL(X) ATK_INSTANCES_BF16_WIDE(X) ATK_INSTANCES_BF16_UNALIGNED(X)

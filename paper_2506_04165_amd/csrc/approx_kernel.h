@@ -1,0 +1,243 @@
+// Fused two-stage approximate Top-K kernel (Section 6.1 Steps 1-4 in one launch).
+//
+// Work decomposition (ours; the paper's TPU kernel vectorises across buckets and walks the
+// grid sequentially, neither of which carries over):
+//   * a "group" of G lanes owns one row; a workgroup holds rows_per_wg groups;
+//   * per step the group reads `S` consecutive elements of its row, lane t taking R loads of
+//     V consecutive elements at offsets (r*G + t)*V; S is a multiple of B, so the bucket a
+//     given register slot sees never changes and the K'-lists live in VGPRs with static
+//     indexing (Section 6.3's "lists stay in registers" remark, without the state loads);
+//   * S == B ("one owner"): every bucket belongs to exactly one slot of one lane, the lists
+//     are final as they stand.  S == G*V == m*B ("m owners", small B): m lanes hold partial
+//     lists of the same bucket; they are merged per bucket through LDS before stage 2;
+//   * the update of one list with one element is Algorithm 1 restated for the fixed order:
+//     compare the element with every entry (element on the left, so no dependency chain),
+//     then each entry takes its upper neighbour, the element, or itself.  Elements arrive in
+//     increasing index per slot, so a strict compare keeps the lower index on ties; empty
+//     entries are NaN and the compare is written as !(x <= entry) so that anything, a real
+//     -inf included, displaces them;
+//   * survivors become 64-bit keys in LDS, a workgroup-wide bitonic sort orders each row's
+//     B*K' candidates, and the first K are decoded and written out (stage 2).
+//   * mode 1 writes the survivors in the [rows, K', B] layout of Section 6.3 instead.
+#pragma once
+#include "atk_device.h"
+
+namespace atk {
+
+struct ApproxParams {
+    const void* values;
+    int64_t row_stride;   // elements
+    int rows, N, K, Kprime, B;
+    int G;                // lanes per row (power of two)
+    int log2G;
+    int rows_per_wg;
+    int S;                // elements consumed per step by one group: max(B, G*V)
+    int nsteps;           // N / S
+    int owners;           // lanes*slots sharing a bucket: S / B
+    int seg;              // owners > 1: power of two >= owners*KP, LDS keys per bucket
+    int Cpad;             // power of two >= B*K', LDS keys per row for stage 2
+    int mode;             // 0: stage 2 fused, write out_*; 1: write survivors to surv_*
+    void* out_vals;
+    int32_t* out_idx;
+    void* surv_vals;
+    int32_t* surv_idx;
+};
+
+// Plain two-way select on values; written as a function of values so that it is emitted as a
+// select (v_cndmask) and never as a divergent branch.
+template <typename T>
+__device__ __forceinline__ T sel(bool c, T a, T b) { return c ? a : b; }
+
+// One list update (Algorithm 1, branch-free, 5K'-2 lane operations).
+template <int KP>
+__device__ __forceinline__ void list_insert(float (&val)[KP], int32_t (&stp)[KP], float x, int32_t step) {
+    bool c[KP];
+#pragma unroll
+    for (int k = 0; k < KP; ++k) c[k] = !(x <= val[k]);
+#pragma unroll
+    for (int k = KP - 1; k >= 1; --k) {
+        const float v0 = sel(c[k], x, val[k]);
+        const int32_t s0 = sel(c[k], step, stp[k]);
+        val[k] = sel(c[k - 1], val[k - 1], v0);
+        stp[k] = sel(c[k - 1], stp[k - 1], s0);
+    }
+    val[0] = sel(c[0], x, val[0]);
+    stp[0] = sel(c[0], step, stp[0]);
+    // keep the updates of different lists apart: interleaving them buys nothing (the compares
+    // of one update are already independent) and multiplies the live compare masks
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+template <typename DT, int KP, int V, int R>
+struct ApproxKernel {
+    static constexpr int NL = V * R;
+    static constexpr int DW = (V * elem<DT>::size + 3) / 4;           // dwords per load
+    static constexpr int U_ = 32 / (R * DW);
+    static constexpr int U = U_ < 1 ? 1 : (U_ > 16 ? 16 : U_);        // steps in flight
+    using VL = vec_load<DT, V>;
+    using vec_t = typename VL::vec_t;
+
+    __device__ static void run(const ApproxParams& p, uint64_t* lds) {
+        const int tid = threadIdx.x;
+        const int g = tid >> p.log2G;
+        const int t = tid & (p.G - 1);
+        const int row = blockIdx.x * p.rows_per_wg + g;
+        const bool row_ok = row < p.rows;
+        const char* rowp = (const char*)p.values +
+                           (size_t)(row_ok ? row : 0) * p.row_stride * elem<DT>::size;
+
+        float val[NL][KP];
+        int32_t stp[NL][KP];
+        const float empty = __builtin_nanf("");
+#pragma unroll
+        for (int l = 0; l < NL; ++l)
+#pragma unroll
+            for (int k = 0; k < KP; ++k) { val[l][k] = empty; stp[l][k] = 0; }
+
+        int off[R];
+        bool slot_ok[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int o = (r * p.G + t) * V;
+            slot_ok[r] = o < p.S;
+            off[r] = slot_ok[r] ? o : 0;    // idle slots re-read offset 0; their lists are dropped
+        }
+
+        // ---- stage 1: stream the row once -------------------------------------------------
+        int s = 0;
+        for (; s + U <= p.nsteps; s += U) {
+            vec_t buf[U][R];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+                    buf[u][r] = VL::load(rowp + ((size_t)(s + u) * p.S + off[r]) * elem<DT>::size);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int v = 0; v < V; ++v)
+                        list_insert<KP>(val[r * V + v], stp[r * V + v],
+                                        __uint_as_float(VL::bits(buf[u][r], v)), s + u);
+        }
+        for (; s < p.nsteps; ++s) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                vec_t x = VL::load(rowp + ((size_t)s * p.S + off[r]) * elem<DT>::size);
+#pragma unroll
+                for (int v = 0; v < V; ++v)
+                    list_insert<KP>(val[r * V + v], stp[r * V + v],
+                                    __uint_as_float(VL::bits(x, v)), s);
+            }
+        }
+
+        // ---- survivors -> LDS keys (or straight to memory for one-owner mode 1) ---------------
+        const int C = p.B * p.Kprime;
+        uint64_t* cand = lds + (size_t)g * p.Cpad;                    // per-row stage-2 segment
+        if (p.owners == 1) {
+            if (p.mode == 0) {
+                for (int i = C + t; i < p.Cpad; i += p.G) cand[i] = 0;
+            }
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const bool live = slot_ok[r] && row_ok;
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+                    const int bucket = off[r] + v;
+#pragma unroll
+                    for (int k = 0; k < KP; ++k) {
+                        if (!live || k >= p.Kprime) continue;
+                        const uint32_t n = (uint32_t)stp[r * V + v][k] * (uint32_t)p.S + bucket;
+                        const uint32_t b = __float_as_uint(val[r * V + v][k]);
+                        if (p.mode == 0) {
+                            cand[bucket * p.Kprime + k] = make_key(b, n);
+                        } else {
+                            const int64_t o = ((int64_t)row * p.Kprime + k) * p.B + bucket;
+                            elem<DT>::store_bits(p.surv_vals, o, b);
+                            p.surv_idx[o] = (int32_t)n;
+                        }
+                    }
+                }
+            }
+            if (p.mode != 0) return;
+            if (!row_ok) { for (int i = t; i < C; i += p.G) cand[i] = 0; }
+            __syncthreads();
+        } else {
+            // m owners per bucket: partial lists -> [bucket][owner*KP + k], sort each bucket's
+            // segment, keep its first K'.  Partial lists may be short: NaN entries become key 0.
+            uint64_t* part = lds + (size_t)p.rows_per_wg * p.Cpad + (size_t)g * p.B * p.seg;
+            for (int i = t; i < p.B * p.seg; i += p.G) part[i] = 0;
+            for (int i = C + t; i < p.Cpad; i += p.G) cand[i] = 0;
+            __syncthreads();
+            if (row_ok) {
+#pragma unroll
+                for (int v = 0; v < V; ++v) {           // R == 1 in this mode
+                    const int e = off[0] + v;
+                    const int bucket = e % p.B, owner = e / p.B;
+#pragma unroll
+                    for (int k = 0; k < KP; ++k) {
+                        const float f = val[v][k];
+                        const uint32_t n = (uint32_t)stp[v][k] * (uint32_t)p.S + e;
+                        if (f == f)                     // NaN marks an empty entry
+                            part[(size_t)bucket * p.seg + owner * KP + k] = make_key(__float_as_uint(f), n);
+                    }
+                }
+            }
+            __syncthreads();
+            lds_bitonic_sort_desc(lds + (size_t)p.rows_per_wg * p.Cpad,
+                                  p.rows_per_wg * p.B * p.seg, p.seg);
+            for (int i = t; i < C; i += p.G) {
+                const int bucket = i / p.Kprime, k = i - bucket * p.Kprime;
+                const uint64_t key = part[(size_t)bucket * p.seg + k];
+                if (p.mode == 0) {
+                    cand[i] = key;
+                } else if (row_ok) {
+                    const uint32_t n = key_index(key);
+                    uint32_t b = key_value_bits(key);
+                    if (b == 0) b = elem<DT>::load_bits(rowp, n);      // which zero it was
+                    const int64_t o = ((int64_t)row * p.Kprime + k) * p.B + bucket;
+                    elem<DT>::store_bits(p.surv_vals, o, b);
+                    p.surv_idx[o] = (int32_t)n;
+                }
+            }
+            if (p.mode != 0) return;
+            __syncthreads();
+        }
+
+        // ---- stage 2: exact Top-K of each row's candidates --------------------------------------
+        lds_bitonic_sort_desc(lds, p.rows_per_wg * p.Cpad, p.Cpad);
+        if (row_ok) {
+            for (int i = t; i < p.K; i += p.G) {
+                const uint64_t key = cand[i];
+                const uint32_t n = key_index(key);
+                uint32_t b = key_value_bits(key);
+                if (b == 0) b = elem<DT>::load_bits(rowp, n);          // which zero it was
+                elem<DT>::store_bits(p.out_vals, (int64_t)row * p.K + i, b);
+                p.out_idx[(int64_t)row * p.K + i] = (int32_t)n;
+            }
+        }
+    }
+};
+
+template <typename DT, int KP, int V, int R>
+__global__ void __launch_bounds__(1024) approx_topk_kernel(ApproxParams p) {
+    extern __shared__ uint64_t atk_lds[];
+    ApproxKernel<DT, KP, V, R>::run(p, atk_lds);
+}
+
+// Host-side launcher, one explicit instantiation per supported (dtype, KP, V, R).
+template <typename DT, int KP, int V, int R>
+hipError_t launch_approx(const ApproxParams& p, int grid, int block, size_t lds_bytes,
+                         hipStream_t stream);
+
+#define ATK_DEFINE_LAUNCH(DT, KP, V, R)                                                         \
+    template <>                                                                                 \
+    hipError_t launch_approx<DT, KP, V, R>(const ApproxParams& p, int grid, int block,          \
+                                           size_t lds_bytes, hipStream_t stream) {              \
+        hipLaunchKernelGGL((approx_topk_kernel<DT, KP, V, R>), dim3(grid), dim3(block),        \
+                           lds_bytes, stream, p);                                               \
+        return hipGetLastError();                                                               \
+    }
+
+}  // namespace atk

@@ -1,0 +1,20 @@
+// Exact Top-K launcher (radix selection + LDS sort); see topk_exact.hip.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace atk {
+
+struct TopkParams {
+    const void* values;       // [rows, row_stride] elements of the given dtype
+    const int32_t* payload;   // optional [rows, row_stride] original indices (survivor mode)
+    int64_t row_stride;
+    int rows, N, K;
+    int cap;                  // LDS key buffer capacity (power of two, >= 1024, > K)
+    void* out_vals;
+    int32_t* out_idx;
+};
+
+hipError_t launch_topk_exact(const TopkParams& p, int dtype, int threads, hipStream_t stream);
+
+}  // namespace atk

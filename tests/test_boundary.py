@@ -1,0 +1,133 @@
+"""CPU-only checks of the C-ABI boundary: the library loads, exports what include/atk.h
+declares, rejects bad arguments on the host (no GPU needed: validation happens before any
+launch), and its host-side helpers agree with the oracle's theory."""
+import ctypes
+import os
+import re
+
+import pytest
+import torch
+
+from oracle import oracle
+from paper_2506_04165_amd import binding as atk
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x100000  # a non-null, 16-byte aligned "device pointer"; never dereferenced on error paths
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "atk.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(atk_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert len(names) >= 9
+    for n in names:
+        assert hasattr(atk.lib, n), n
+    assert sorted(atk.EXPORTS) == names
+
+
+def test_status_strings_and_version():
+    assert atk.status_string(0) == "ATK_OK"
+    assert atk.status_string(1) == "ATK_INVALID_ARG"
+    assert atk.status_string(2) == "ATK_UNSUPPORTED"
+    assert atk.status_string(3) == "ATK_WORKSPACE_TOO_SMALL"
+    assert atk.status_string(4) == "ATK_HIP_ERROR"
+    assert atk.status_string(99) == "ATK_UNKNOWN_STATUS"
+    assert re.match(r"\d+\.\d+\.\d+", atk.version())
+
+
+def call_approx(values=FAKE, dtype=0, rows=4, N=4096, stride=None, K=32, Kp=4, B=64,
+                out_vals=FAKE, out_idx=FAKE, ws=None, ws_bytes=0):
+    stride = N if stride is None else stride
+    return atk.lib.atk_approx_topk(values, dtype, rows, N, stride, K, Kp, B, out_vals, out_idx,
+                                   ws, ws_bytes, None)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(values=None), dict(out_vals=None), dict(out_idx=None),
+    dict(rows=-1), dict(N=0), dict(N=2**31), dict(stride=100),
+    dict(B=0), dict(B=63),                 # B must divide N
+    dict(Kp=0), dict(Kp=33),               # 1 <= K' <= K
+    dict(B=1024, Kp=5, K=32),              # K' > N/B
+    dict(K=300),                           # K > B*K'
+    dict(K=0),
+    dict(values=FAKE + 2),                 # misaligned for fp32
+    dict(out_idx=FAKE + 2),
+])
+def test_invalid_arguments(kw):
+    assert call_approx(**kw) == atk.INVALID_ARG
+
+
+def test_unsupported_arguments():
+    assert call_approx(dtype=7) == atk.UNSUPPORTED
+    # K' beyond the register lists (and not the K'=K case)
+    assert call_approx(N=65536, K=128, Kp=40, B=64) == atk.UNSUPPORTED
+    # more buckets than the widest mapping covers
+    assert call_approx(N=262144, K=1024, Kp=1, B=65536) == atk.UNSUPPORTED
+
+
+def test_rows_zero_is_ok_without_gpu():
+    assert call_approx(rows=0, values=None, out_vals=None, out_idx=None) == atk.OK
+    assert atk.lib.atk_topk(None, 0, 0, 128, 128, 4, None, None, None, 0, None) == atk.OK
+    assert atk.lib.atk_approx_topk_stage1(None, 0, 0, 128, 128, 2, 8, None, None, None) == atk.OK
+
+
+def test_topk_and_stage1_validation():
+    assert atk.lib.atk_topk(FAKE, 0, 2, 128, 128, 0, FAKE, FAKE, None, 0, None) == atk.INVALID_ARG
+    assert atk.lib.atk_topk(FAKE, 0, 2, 128, 128, 129, FAKE, FAKE, None, 0, None) == atk.INVALID_ARG
+    assert atk.lib.atk_topk(FAKE, 0, 2, 8192, 8192, 4096, FAKE, FAKE, None, 0, None) == atk.UNSUPPORTED
+    assert atk.lib.atk_topk(None, 0, 2, 128, 128, 4, FAKE, FAKE, None, 0, None) == atk.INVALID_ARG
+    st1 = atk.lib.atk_approx_topk_stage1
+    assert st1(FAKE, 0, 2, 128, 128, 3, 64, FAKE, FAKE, None) == atk.INVALID_ARG   # K' > N/B
+    assert st1(FAKE, 0, 2, 128, 128, 1, 5, FAKE, FAKE, None) == atk.INVALID_ARG    # B does not divide N
+    assert st1(FAKE, 0, 2, 128, 128, 1, 8, None, FAKE, None) == atk.INVALID_ARG
+
+
+def test_workspace_query_and_too_small():
+    f32 = torch.float32
+    # fused cases need no workspace
+    assert atk.workspace_bytes(atk.OP_APPROX_TOPK, f32, 256, 1048576, 128, 4, 1024) == 0
+    assert atk.workspace_bytes(atk.OP_TOPK, f32, 4, 4096, 32, 0, 0) == 0
+    # survivors beyond LDS go through memory: rows * B*K' * (4 + 4) bytes
+    need = atk.workspace_bytes(atk.OP_APPROX_TOPK, f32, 8, 65536, 128, 16, 1024)
+    assert need == 8 * 1024 * 16 * 8
+    assert call_approx(rows=8, N=65536, K=128, Kp=16, B=1024, ws=None, ws_bytes=0) == atk.WORKSPACE_TOO_SMALL
+    assert call_approx(rows=8, N=65536, K=128, Kp=16, B=1024, ws=FAKE, ws_bytes=need - 1) == atk.WORKSPACE_TOO_SMALL
+    # illegal arguments
+    assert atk.workspace_bytes(atk.OP_APPROX_TOPK, f32, 4, 4096, 32, 4, 63) == atk.SIZE_MAX
+    assert atk.workspace_bytes(99, f32, 4, 4096, 32, 4, 64) == atk.SIZE_MAX
+
+
+def test_plans_for_benchmark_configs_are_fused_single_launch():
+    from paper_2506_04165_amd.workloads import WORKLOADS
+    for w in WORKLOADS.values():
+        for B, Kp in w.params:
+            st, text = atk.describe_plan(w.dtype, w.rows, w.N, w.K, Kp, B)
+            assert st == atk.OK, (w.name, B, Kp)
+            assert text.startswith("fused"), (w.name, B, Kp, text)
+            assert "workspace=0" in text
+
+
+@pytest.mark.parametrize("N,B,K,Kp", [(4096, 64, 32, 1), (4096, 64, 32, 4), (14336, 128, 287, 4),
+                                      (262144, 1024, 1024, 4), (1048576, 4096, 128, 1),
+                                      (65536, 256, 256, 8), (256000, 512, 64, 2), (4096, 64, 32, 32)])
+def test_expected_recall_matches_exact_rational_evaluation(N, B, K, Kp):
+    # the library's log-gamma evaluation of Theorem 1 against the oracle's exact fractions
+    assert atk.expected_recall(N, B, K, Kp) == pytest.approx(oracle.expected_recall(N, B, K, Kp), abs=1e-9)
+
+
+def test_expected_recall_rejects_bad_arguments():
+    assert atk.expected_recall(4096, 63, 32, 1) < 0
+    assert atk.expected_recall(0, 1, 1, 1) < 0
+    assert atk.expected_recall(4096, 64, 5000, 1) < 0
+
+
+def test_binding_refuses_cpu_tensors():
+    x = torch.zeros(2, 128)
+    with pytest.raises(ValueError):
+        atk.approx_topk(x, 4, 1, 8)
+    with pytest.raises(ValueError):
+        atk.topk(x, 4)

@@ -1,0 +1,309 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, bit for bit.
+
+Bar: integer/index work and fp compare-and-select only, so every output must be identical:
+same int32 indices, same stored value bits, same order (ties toward the lowest index).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle
+from paper_2506_04165_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def atk():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2506_04165_amd import binding
+    return binding
+
+
+def bits(t: torch.Tensor) -> np.ndarray:
+    t = t.detach().cpu().contiguous()
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).numpy().view(np.uint16)
+    return t.view(torch.int32).numpy().view(np.uint32)
+
+
+def host_bits(x: np.ndarray) -> np.ndarray:
+    return x if x.dtype == np.uint16 else x.view(np.uint32)
+
+
+def check_approx(atk, x: torch.Tensor, K, Kp, B, rows_to_check=None):
+    """x: host tensor.  Runs the HIP path on all rows, the oracle on `rows_to_check` (all if None)."""
+    xd = x.to(DEV)
+    gv, gi = atk.approx_topk(xd, K, Kp, B)
+    torch.cuda.synchronize()
+    sel = np.arange(x.shape[0]) if rows_to_check is None else np.asarray(rows_to_check)
+    xh = workloads.to_numpy_bits(x)[sel]
+    ov, oi = oracle.approx_topk(xh, K, Kp, B)
+    gi_h = gi.cpu().numpy()[sel]
+    gv_h = bits(gv)[sel]
+    assert np.array_equal(gi_h, oi), f"indices differ (K={K}, K'={Kp}, B={B})"
+    assert np.array_equal(gv_h, host_bits(ov)), f"values differ (K={K}, K'={Kp}, B={B})"
+    return gv, gi
+
+
+def check_exact(atk, x: torch.Tensor, K, rows_to_check=None):
+    xd = x.to(DEV)
+    gv, gi = atk.topk(xd, K)
+    torch.cuda.synchronize()
+    sel = np.arange(x.shape[0]) if rows_to_check is None else np.asarray(rows_to_check)
+    ov, oi = oracle.topk(workloads.to_numpy_bits(x)[sel], K)
+    assert np.array_equal(gi.cpu().numpy()[sel], oi), f"exact indices differ (K={K})"
+    assert np.array_equal(bits(gv)[sel], host_bits(ov)), f"exact values differ (K={K})"
+    return gv, gi
+
+
+def check_stage1(atk, x: torch.Tensor, Kp, B):
+    sv, si = atk.approx_topk_stage1(x.to(DEV), Kp, B)
+    torch.cuda.synchronize()
+    ov, oi = oracle.stage1(workloads.to_numpy_bits(x), Kp, B)
+    assert np.array_equal(si.cpu().numpy(), oi), f"stage-1 indices differ (K'={Kp}, B={B})"
+    assert np.array_equal(bits(sv), host_bits(ov)), f"stage-1 values differ (K'={Kp}, B={B})"
+
+
+# ---------------------------------------------------------------------------------------
+# the five workloads at sizes the oracle finishes in seconds (several tiles + ragged tails)
+# ---------------------------------------------------------------------------------------
+
+def test_c1_tiny_all_params(atk):
+    w = workloads.WORKLOADS["c1_tiny"]
+    x = workloads.make("c1_tiny", seed=1)
+    ev, ei = check_exact(atk, x, w.K)
+    for B, Kp in w.params:
+        gv, gi = check_approx(atk, x, w.K, Kp, B)
+        check_stage1(atk, x, Kp, B)
+        if Kp == w.K:   # K' = K and B = 1 must both give the exact Top-K
+            assert torch.equal(gi, ei) and torch.equal(gv, ev)
+
+
+@pytest.mark.parametrize("rows", [1, 37])
+def test_c2_ffn_reduced_rows(atk, rows):
+    w = workloads.WORKLOADS["c2_ffn"]
+    x = workloads.make("c2_ffn", seed=2, rows=rows)
+    for B, Kp in w.params:
+        check_approx(atk, x, w.K, Kp, B)
+    check_stage1(atk, x, 4, 128)
+    check_exact(atk, x, w.K)
+
+
+def test_c3_vocab_reduced_rows(atk):
+    w = workloads.WORKLOADS["c3_vocab"]
+    x = workloads.make("c3_vocab", seed=3, rows=5)
+    for B, Kp in w.params:
+        check_approx(atk, x, w.K, Kp, B)
+    check_exact(atk, x, w.K)
+
+
+def test_c4_mips_reduced_rows(atk):
+    w = workloads.WORKLOADS["c4_mips"]
+    x = workloads.make("c4_mips", seed=4, rows=3)
+    for B, Kp in w.params:
+        check_approx(atk, x, w.K, Kp, B)
+    check_stage1(atk, x, 1, 4096)
+    check_exact(atk, x, w.K)
+
+
+def test_c5_adversarial_reduced_rows(atk):
+    w = workloads.WORKLOADS["c5_adversarial"]
+    x = workloads.make("c5_adversarial", seed=5, rows=6)   # 3 sorted-adversarial + 3 heavy-tie rows
+    for B, Kp in w.params:
+        check_approx(atk, x, w.K, Kp, B)
+    check_stage1(atk, x, 8, 256)
+    check_exact(atk, x, w.K)
+
+
+# ---------------------------------------------------------------------------------------
+# edge cases of the method and of the launch geometry
+# ---------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("B,Kp,K", [
+    (1, 16, 16), (2, 8, 16), (4, 3, 12), (8, 2, 9), (16, 1, 16), (32, 4, 100),   # several lanes per bucket
+    (64, 1, 64), (64, 5, 200), (64, 7, 33), (128, 12, 500), (256, 20, 1000),     # list length > K'
+    (512, 2, 1024), (2048, 1, 77), (4096, 2, 2), (8192, 1, 2048),                # many buckets
+])
+def test_parameter_sweep_fp32(atk, B, Kp, K):
+    x = workloads.gaussian(5, 16384, seed=100 + B + Kp)
+    check_approx(atk, x, K, Kp, B)
+    check_stage1(atk, x, Kp, B)
+
+
+@pytest.mark.parametrize("B,Kp,K", [(1, 8, 8), (8, 4, 20), (64, 8, 287), (128, 4, 287),
+                                    (256, 3, 700), (1024, 1, 287), (2048, 2, 64), (7168, 1, 287)])
+def test_parameter_sweep_bf16(atk, B, Kp, K):
+    x = workloads.gaussian(9, 14336, seed=200 + B + Kp, dtype=torch.bfloat16)
+    check_approx(atk, x, K, Kp, B)
+    check_stage1(atk, x, Kp, B)
+
+
+@pytest.mark.parametrize("N,B,Kp,K", [(1344, 448, 2, 600), (900, 3, 30, 40), (900, 100, 9, 900),
+                                      (210, 7, 30, 210), (1000, 125, 1, 100), (96, 96, 1, 50),
+                                      (6, 3, 2, 5), (1, 1, 1, 1), (64, 64, 1, 64)])
+def test_bucket_counts_that_are_not_powers_of_two_and_tiny_rows(atk, N, B, Kp, K):
+    x = workloads.gaussian(3, N, seed=300 + N + B)
+    check_approx(atk, x, K, Kp, B)
+    check_stage1(atk, x, Kp, B)
+    xb = workloads.gaussian(3, N, seed=301 + N + B, dtype=torch.bfloat16)
+    check_approx(atk, xb, K, Kp, B)
+
+
+def test_kprime_equals_k_and_single_bucket_are_exact(atk):
+    x = workloads.gaussian(4, 8192, seed=7)
+    for K, Kp, B in [(32, 32, 64), (32, 32, 1), (20, 20, 256), (100, 100, 64), (100, 100, 1),
+                     (50, 50, 128)]:
+        gv, gi = check_approx(atk, x, K, Kp, B)
+        ev, ei = check_exact(atk, x, K)
+        assert torch.equal(gi, ei) and torch.equal(gv, ev)
+
+
+def test_signed_zeros_minus_inf_and_ties(atk):
+    # signed zeros: equal in the order, stored bits returned
+    x = torch.full((2, 256), -1.0)
+    x[0, [10, 40, 77]] = -0.0
+    x[0, [3, 50]] = 0.0
+    x[1, 5] = -0.0
+    for K, Kp, B in [(5, 5, 1), (5, 2, 16), (5, 1, 64), (4, 4, 256 // 4)]:
+        check_approx(atk, x, K, Kp, B)
+    check_exact(atk, x, 6)
+    check_stage1(atk, x, 2, 16)
+    xb = x.to(torch.bfloat16)
+    check_approx(atk, xb, 5, 2, 16)
+    check_exact(atk, xb, 6)
+    # rows that are almost entirely -inf: real -inf elements are legitimate outputs
+    y = torch.full((3, 4096), float("-inf"))
+    y[0, [7, 50, 4000]] = torch.tensor([1.0, 2.0, 3.0])
+    y[1, 100] = float("inf")
+    for K, Kp, B in [(64, 2, 64), (64, 1, 64), (16, 16, 1), (300, 8, 64), (40, 4, 16)]:
+        check_approx(atk, y, K, Kp, B)
+        check_stage1(atk, y, Kp, B)
+    check_exact(atk, y, 64)
+    # heavy ties: 2, 3 and 16 distinct values
+    for symbols in (1, 2, 3, 16):
+        z = workloads.heavy_ties(4, 8192, seed=symbols, symbols=symbols)
+        for K, Kp, B in [(256, 1, 256), (256, 8, 256), (256, 32, 64), (100, 4, 32), (50, 50, 1)]:
+            check_approx(atk, z, K, Kp, B)
+        check_exact(atk, z, 256)
+        check_exact(atk, z.to(torch.bfloat16), 2048)
+
+
+def test_row_stride_and_views(atk):
+    big = workloads.gaussian(6, 4096 + 64, seed=11).to(DEV)
+    view = big[:, 32:32 + 4096]            # row stride 4160, base offset 128 bytes
+    gv, gi = atk.approx_topk(view, 32, 4, 64)
+    ev, ei = atk.topk(view, 32)
+    torch.cuda.synchronize()
+    xh = view.cpu().contiguous().numpy()
+    ov, oi = oracle.approx_topk(xh, 32, 4, 64)
+    assert np.array_equal(gi.cpu().numpy(), oi) and np.array_equal(gv.cpu().numpy(), ov)
+    ov, oi = oracle.topk(xh, 32)
+    assert np.array_equal(ei.cpu().numpy(), oi) and np.array_equal(ev.cpu().numpy(), ov)
+    # an odd element offset forces the single-element-load variants
+    view2 = big[:, 1:1 + 4096]
+    gv, gi = atk.approx_topk(view2, 100, 2, 2048)
+    torch.cuda.synchronize()
+    ov, oi = oracle.approx_topk(view2.cpu().contiguous().numpy(), 100, 2, 2048)
+    assert np.array_equal(gi.cpu().numpy(), oi) and np.array_equal(gv.cpu().numpy(), ov)
+
+
+def test_zero_rows(atk):
+    x = torch.empty((0, 1024), device=DEV)
+    v, i = atk.approx_topk(x, 8, 1, 64)
+    assert v.shape == (0, 8) and i.shape == (0, 8)
+    v, i = atk.topk(x, 8)
+    assert v.shape == (0, 8)
+
+
+def test_unfused_path_through_workspace(atk):
+    # B*K' = 16384 survivors per row do not fit the fused kernel's LDS: two launches + workspace
+    N, B, Kp, K = 65536, 1024, 16, 300
+    st, text = atk.describe_plan(torch.float32, 4, N, K, Kp, B)
+    assert st == atk.OK and text.startswith("unfused")
+    x = workloads.gaussian(4, N, seed=12)
+    check_approx(atk, x, K, Kp, B)
+    x = workloads.heavy_ties(3, N, seed=13, symbols=4)
+    check_approx(atk, x, K, Kp, B)
+    xb = workloads.gaussian(4, N, seed=14, dtype=torch.bfloat16)
+    check_approx(atk, xb, K, Kp, B)
+
+
+def test_exact_topk_sizes(atk):
+    for N, K in [(1, 1), (63, 63), (64, 1), (1000, 1000), (5000, 2048), (100000, 7), (300000, 1500)]:
+        x = workloads.gaussian(3, N, seed=400 + N % 97)
+        check_exact(atk, x, K)
+    # all-equal row: every digit of the value is shared, the index digits decide
+    x = torch.zeros(2, 70000)
+    check_exact(atk, x, 100)
+    x = workloads.heavy_ties(2, 200000, seed=8, symbols=2).to(torch.bfloat16)
+    check_exact(atk, x, 2000)
+
+
+def test_results_do_not_depend_on_launch_geometry(atk, monkeypatch):
+    # the same problem under different lanes-per-row choices must give identical bits
+    x = workloads.gaussian(7, 32768, seed=21).to(DEV)
+    ref = None
+    for lanes in (64, 128, 256, 512, 1024):
+        monkeypatch.setenv("ATK_LANES_PER_ROW", str(lanes))
+        for (K, Kp, B) in [(64, 2, 512), (64, 4, 16)]:
+            v, i = atk.approx_topk(x, K, Kp, B)
+            torch.cuda.synchronize()
+            key = (K, Kp, B)
+            if ref is None:
+                ref = {}
+            if key not in ref:
+                ref[key] = (v.clone(), i.clone())
+            else:
+                assert torch.equal(ref[key][1], i) and torch.equal(ref[key][0], v), (lanes, key)
+    monkeypatch.delenv("ATK_LANES_PER_ROW")
+
+
+# ---------------------------------------------------------------------------------------
+# full benchmark sizes, in the launch configuration bench.py times: oracle on sampled rows,
+# structural properties on every row
+# ---------------------------------------------------------------------------------------
+
+def check_properties(xd, gv, gi, K, Kp, B):
+    rows, N = xd.shape
+    gi64 = gi.long()
+    assert int(gi64.min()) >= 0 and int(gi64.max()) < N
+    gathered = torch.gather(xd, 1, gi64)
+    assert torch.equal(gathered.view(torch.int16 if xd.dtype == torch.bfloat16 else torch.int32),
+                       gv.view(torch.int16 if xd.dtype == torch.bfloat16 else torch.int32))
+    vf = gv.float()
+    assert bool((vf[:, :-1] >= vf[:, 1:]).all())
+    tie = vf[:, :-1] == vf[:, 1:]
+    assert bool((gi64[:, :-1][tie] < gi64[:, 1:][tie]).all())
+    # distinct indices; at most K' per bucket
+    srt = torch.sort(gi64, dim=1).values
+    assert bool((srt[:, 1:] != srt[:, :-1]).all())
+    counts = torch.zeros(rows, B, dtype=torch.int32, device=xd.device)
+    counts.scatter_add_(1, gi64 % B, torch.ones_like(gi64, dtype=torch.int32))
+    assert int(counts.max()) <= Kp
+
+
+@pytest.mark.parametrize("name", ["c2_ffn", "c3_vocab", "c4_mips", "c5_adversarial"])
+def test_full_size_sampled_rows_and_properties(atk, name):
+    w = workloads.WORKLOADS[name]
+    xd = workloads.make(name, seed=1, device=DEV)
+    assert xd.shape == (w.rows, w.N)
+    rng = np.random.default_rng(5)
+    n_sample = {"c2_ffn": 24, "c3_vocab": 6, "c4_mips": 3, "c5_adversarial": 8}[name]
+    sel = np.sort(np.concatenate([[0, w.rows - 1], rng.choice(w.rows, n_sample - 2, replace=False)]))
+    xh = workloads.to_numpy_bits(xd[torch.from_numpy(sel).to(DEV)])
+    for B, Kp in w.params:
+        gv, gi = atk.approx_topk(xd, w.K, Kp, B)
+        torch.cuda.synchronize()
+        check_properties(xd, gv, gi, w.K, Kp, B)
+        ov, oi = oracle.approx_topk(xh, w.K, Kp, B)
+        assert np.array_equal(gi.cpu().numpy()[sel], oi), (name, B, Kp)
+        assert np.array_equal(bits(gv)[sel], host_bits(ov)), (name, B, Kp)
+    gv, gi = atk.topk(xd, w.K)
+    torch.cuda.synchronize()
+    check_properties(xd, gv, gi, w.K, w.K, 1)
+    ov, oi = oracle.topk(xh, w.K)
+    assert np.array_equal(gi.cpu().numpy()[sel], oi), name
+    assert np.array_equal(bits(gv)[sel], host_bits(ov)), name
