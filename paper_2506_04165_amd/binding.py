@@ -14,7 +14,8 @@ import os
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libatk.so")
+# ATK_LIB_PATH lets a developer point the binding at an experimental build of the same library
+LIB_PATH = os.environ.get("ATK_LIB_PATH") or os.path.join(_PKG, "libatk.so")
 
 F32, BF16 = 0, 1
 OK, INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP_ERROR = range(5)

@@ -21,6 +21,7 @@ ARCH = "gfx950"
 SOURCES = [
     "api.hip",
     "topk_exact.hip",
+    "approx_finish.hip",
     "approx_inst_f32_small.hip",
     "approx_inst_f32_wide.hip",
     "approx_inst_bf16_small.hip",
@@ -41,13 +42,14 @@ def _headers_mtime() -> float:
     return max(os.path.getmtime(p) for p in paths)
 
 
-def _compile(src: str, force: bool) -> str:
+def _compile(src: str, force: bool, extra=(), objdir: str = OBJ) -> str:
     path = os.path.join(CSRC, src)
-    obj = os.path.join(OBJ, src.rsplit(".", 1)[0] + ".o")
+    obj = os.path.join(objdir, src.rsplit(".", 1)[0] + ".o")
     stale = (force or not os.path.exists(obj)
              or os.path.getmtime(obj) < max(os.path.getmtime(path), _headers_mtime()))
     if stale:
-        cmd = ["hipcc"] + HIP_FLAGS + (["-x", "hip"] if src.endswith(".hip") else []) + ["-c", path, "-o", obj]
+        cmd = (["hipcc"] + HIP_FLAGS + list(extra) + (["-x", "hip"] if src.endswith(".hip") else [])
+               + ["-c", path, "-o", obj])
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError(f"hipcc failed on {src}:\n{r.stdout}\n{r.stderr}")
@@ -58,16 +60,27 @@ def _compile(src: str, force: bool) -> str:
     return obj
 
 
-def build(force: bool = False, jobs: int | None = None) -> str:
-    os.makedirs(OBJ, exist_ok=True)
+def build(force: bool = False, jobs: int | None = None, extra=(), out: str = LIB) -> str:
+    """Compile and link.  `extra` adds compiler flags (e.g. -D switches for an experiment) and
+    `out` names the library to write; the default is the product library."""
+    objdir = OBJ if out == LIB else OBJ + "_" + os.path.basename(out).replace(".", "_")
+    os.makedirs(objdir, exist_ok=True)
     jobs = jobs or min(8, os.cpu_count() or 1)
     with concurrent.futures.ThreadPoolExecutor(jobs) as ex:
-        objs = list(ex.map(lambda s: _compile(s, force), SOURCES))
-    if force or not os.path.exists(LIB) or any(os.path.getmtime(o) > os.path.getmtime(LIB) for o in objs):
-        cmd = ["hipcc", "-shared", "-fPIC", f"--offload-arch={ARCH}", "-o", LIB] + objs
+        objs = list(ex.map(lambda s: _compile(s, force, extra, objdir), SOURCES))
+    if force or not os.path.exists(out) or any(os.path.getmtime(o) > os.path.getmtime(out) for o in objs):
+        cmd = ["hipcc", "-shared", "-fPIC", f"--offload-arch={ARCH}", "-o", out] + objs
         subprocess.run(cmd, check=True)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":
-    print(build(force="--force" in sys.argv))
+    args = [a for a in sys.argv[1:] if a != "--force"]
+    out = LIB
+    extra = []
+    for a in args:
+        if a.startswith("--out="):
+            out = os.path.abspath(a[6:])
+        else:
+            extra.append(a)
+    print(build(force="--force" in sys.argv, extra=extra, out=out))

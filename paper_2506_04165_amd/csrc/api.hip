@@ -8,6 +8,7 @@
 
 #include "../../include/atk.h"
 #include "approx_instances.h"
+#include "approx_finish.h"
 #include "approx_kernel.h"
 #include "topk_exact.h"
 
@@ -46,6 +47,10 @@ constexpr int kMaxLanes = 1024;
 constexpr size_t kLdsBudget = 64 * 1024; // dynamic LDS per workgroup used by the fused kernel
 constexpr int kExactCap = 4096;          // exact kernel: LDS key buffer
 constexpr int kExactMaxK = 2048;
+constexpr int64_t kTargetWaves = 2048;   // 256 CUs x 4 SIMDs x 2 waves: below this the chip idles
+constexpr int kMinSegmentSteps = 32;     // do not cut a row into pieces shorter than this
+constexpr int kMaxSegments = 64;
+constexpr size_t kMinSplitBytes = 4u << 20;
 
 static thread_local std::string g_last_hip_error;
 
@@ -87,7 +92,8 @@ struct Plan {
     int G = 0, rows_per_wg = 1, S = 0, nsteps = 0, owners = 1, seg = 0, Cpad = 0;
     int block = 0, grid = 0;
     size_t lds = 0;
-    size_t workspace = 0;
+    size_t workspace = 0;       // bytes the plan needs (0: none)
+    int nseg = 1, seg_steps = 0;  // > 1: rows are cut into segments, finished by a second launch
 };
 
 static int list_len_for(int Kp) {
@@ -97,8 +103,10 @@ static int list_len_for(int Kp) {
 }
 
 // Choose how lanes map to buckets.  `stage1_only` plans the survivor-writing launch.
+// `ws_avail` is the workspace the caller offers (SIZE_MAX when only asking what would be used):
+// splitting rows is an optimisation and is dropped when the workspace is too small for it.
 static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride,
-                      int K, int Kp, int B, bool stage1_only) {
+                      int K, int Kp, int B, bool stage1_only, size_t ws_avail = SIZE_MAX) {
     Plan pl;
     const int es = elem_size(dtype);
     const int KP = list_len_for(Kp);
@@ -165,6 +173,8 @@ static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, in
         return keys * 8;
     };
     while (rpw > 1 && lds_for(rpw) > kLdsBudget) rpw >>= 1;
+    // the kernel addresses a lane's row by a 32-bit byte offset from the workgroup's first row
+    while (rpw > 1 && (uint64_t)rpw * (uint64_t)row_stride * es >= (1ull << 31)) rpw >>= 1;
     if (G * rpw < 64) rpw = 64 / G;          // never launch less than a wavefront
     pl.rows_per_wg = rpw;
     pl.lds = lds_for(rpw);
@@ -179,6 +189,34 @@ static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, in
         if (K > kExactMaxK) { pl.status = ATK_UNSUPPORTED; return pl; }
     }
     if (stage1_only && pl.lds > kLdsBudget) { pl.status = ATK_UNSUPPORTED; return pl; }
+
+    // Too few rows to fill the chip: cut every row into segments streamed by separate
+    // workgroups (aim: at least 2 waves on each of the 1024 SIMDs), merged by a finishing launch.
+    if (pl.fused && owners == 1 && G >= 64 && rows > 0) {
+        const int64_t waves = (int64_t)pl.grid * (pl.block / 64);
+        int want = (int)((kTargetWaves + waves - 1) / waves);
+        const int max_by_len = pl.nsteps / kMinSegmentSteps;
+        if (want > max_by_len) want = max_by_len;
+        if (want > kMaxSegments) want = kMaxSegments;
+        want = env_int("ATK_SEGMENTS", want);
+        if (want > pl.nsteps) want = pl.nsteps;
+        if (want > 1) {
+            const int seg_steps = (pl.nsteps + want - 1) / want;
+            const int nseg = (pl.nsteps + seg_steps - 1) / seg_steps;
+            const size_t ws = (size_t)rows * nseg * Kp * B * 8;
+            // worth it only for real streams, and only while the partial lists stay a small
+            // fraction of the bytes streamed
+            const size_t in_bytes = (size_t)rows * N * es;
+            const bool forced = std::getenv("ATK_SEGMENTS") != nullptr;
+            const bool pays = in_bytes >= kMinSplitBytes && ws * 8 <= in_bytes;
+            if (nseg > 1 && ws <= ws_avail && (pays || forced)) {
+                pl.nseg = nseg;
+                pl.seg_steps = seg_steps;
+                pl.workspace = ws;
+                pl.lds = 0;     // the streaming launch keeps nothing in LDS
+            }
+        }
+    }
     return pl;
 }
 
@@ -232,17 +270,33 @@ int atk_approx_topk(const void* values, int dtype, int64_t rows, int64_t N, int6
     if (rc) return rc;
     if (rows > 0 && (!out_vals || !out_idx)) return ATK_INVALID_ARG;
     if ((uintptr_t)out_vals % elem_size(dtype) || (uintptr_t)out_idx % 4) return ATK_INVALID_ARG;
-    Plan pl = make_plan(values, dtype, rows, N, row_stride, K, Kprime, B, false);
+    Plan pl = make_plan(values, dtype, rows, N, row_stride, K, Kprime, B, false,
+                        workspace ? workspace_bytes : 0);
     if (pl.status) return pl.status;
     if (pl.route_exact && K > kExactMaxK) return ATK_UNSUPPORTED;
     if (pl.workspace > 0 && (!workspace || workspace_bytes < pl.workspace))
         return ATK_WORKSPACE_TOO_SMALL;
+    if ((uintptr_t)workspace % 8) return ATK_INVALID_ARG;
     if (rows == 0) return ATK_OK;
     hipStream_t st = (hipStream_t)stream;
     if (pl.route_exact)
         return run_exact(values, nullptr, dtype, rows, N, row_stride, K, out_vals, out_idx, st);
 
     ApproxParams p = params_from(pl, values, rows, N, row_stride, K, Kprime, B);
+    if (pl.nseg > 1) {
+        // split path: partial lists of every (row, segment) through the workspace
+        p.mode = 2;
+        p.nseg = pl.nseg; p.seg_steps = pl.seg_steps;
+        p.part_keys = (uint64_t*)workspace;
+        hipError_t e = pl.var->fn(p, pl.grid, pl.block, 0, st);
+        if (e != hipSuccess) return hip_fail(e);
+        FinishParams f{};
+        f.part_keys = (const uint64_t*)workspace; f.values = values; f.row_stride = row_stride;
+        f.rows = (int)rows; f.K = K; f.Kprime = Kprime; f.B = B; f.nseg = pl.nseg; f.Cpad = pl.Cpad;
+        f.out_vals = out_vals; f.out_idx = out_idx;
+        e = launch_finish(f, dtype, pl.var->KP, st);
+        return e == hipSuccess ? ATK_OK : hip_fail(e);
+    }
     if (pl.fused) {
         p.mode = 0;
         p.out_vals = out_vals; p.out_idx = out_idx;
@@ -324,11 +378,11 @@ int atk_describe_plan(int dtype, int64_t rows, int64_t N, int K, int Kprime, int
         return ATK_OK;
     }
     std::snprintf(buf, buflen,
-                  "%s KP=%d V=%d R=%d lanes_per_row=%d rows_per_wg=%d block=%d grid=%d step=%d "
+                  "%s KP=%d V=%d R=%d lanes_per_row=%d rows_per_wg=%d block=%d grid=%dx%d step=%d "
                   "steps=%d owners=%d seg=%d cand=%d lds=%zu workspace=%zu",
-                  pl.fused ? "fused" : "unfused", pl.var->KP, pl.var->V, pl.var->R, pl.G,
-                  pl.rows_per_wg, pl.block, pl.grid, pl.S, pl.nsteps, pl.owners, pl.seg, pl.Cpad,
-                  pl.lds, pl.workspace);
+                  pl.nseg > 1 ? "split" : (pl.fused ? "fused" : "unfused"), pl.var->KP, pl.var->V,
+                  pl.var->R, pl.G, pl.rows_per_wg, pl.block, pl.grid, pl.nseg, pl.S, pl.nsteps,
+                  pl.owners, pl.seg, pl.Cpad, pl.lds, pl.workspace);
     return ATK_OK;
 }
 

@@ -1,0 +1,22 @@
+// Second launch of the split path: merges the per-segment partial lists of every bucket and
+// runs stage 2.  See approx_finish.hip.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace atk {
+
+struct FinishParams {
+    const uint64_t* part_keys;   // [rows, nseg, K', B] keys written by the streaming launch
+    const void* values;          // the input, only read to tell -0.0 from +0.0
+    int64_t row_stride;
+    int rows, K, Kprime, B, nseg;
+    int Cpad;                    // power of two >= B*K'
+    void* out_vals;
+    int32_t* out_idx;
+};
+
+// KP: compiled list length (>= Kprime), one of 1,2,3,4,6,8,16,32
+hipError_t launch_finish(const FinishParams& p, int dtype, int KP, hipStream_t stream);
+
+}  // namespace atk

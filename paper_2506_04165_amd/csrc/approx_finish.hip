@@ -1,0 +1,77 @@
+// Finish of the split path.  When a batch has too few rows to fill the chip, every row is cut
+// into segments that separate workgroups stream (Section 6.1 Steps 1-2 on a part of each
+// bucket); what is left to do per row is
+//   * Step 2 proper: per bucket, the K' greatest of the union of its per-segment lists.  One
+//     thread owns a bucket, reads the nseg*K' keys (coalesced across buckets) and keeps the
+//     K' greatest in registers.  Keys carry the index, so ties need no special care;
+//   * Steps 3-4: the B*K' merged keys go to LDS, a bitonic sort orders them, K are written.
+#include "approx_finish.h"
+#include "atk_device.h"
+
+namespace atk {
+namespace {
+
+template <typename DT, int KP>
+__global__ void __launch_bounds__(1024) approx_finish_kernel(FinishParams p) {
+    extern __shared__ uint64_t cand[];
+    const int tid = threadIdx.x, T = blockDim.x;
+    const int row = blockIdx.x;
+    const int C = p.B * p.Kprime;
+    for (int i = C + tid; i < p.Cpad; i += T) cand[i] = 0;
+    const uint64_t* part = p.part_keys + (size_t)row * p.nseg * p.Kprime * p.B;
+    for (int b = tid; b < p.B; b += T) {
+        uint64_t top[KP];
+#pragma unroll
+        for (int j = 0; j < KP; ++j) top[j] = 0;
+        for (int q = 0; q < p.nseg; ++q) {
+            for (int k = 0; k < p.Kprime; ++k) {
+                const uint64_t key = part[((size_t)q * p.Kprime + k) * p.B + b];
+                bool c[KP];
+#pragma unroll
+                for (int j = 0; j < KP; ++j) c[j] = key > top[j];
+#pragma unroll
+                for (int j = KP - 1; j >= 1; --j) top[j] = c[j - 1] ? top[j - 1] : (c[j] ? key : top[j]);
+                top[0] = c[0] ? key : top[0];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < KP; ++j)
+            if (j < p.Kprime) cand[b * p.Kprime + j] = top[j];
+    }
+    __syncthreads();
+    lds_bitonic_sort_desc(cand, p.Cpad, p.Cpad);
+    const char* rowp = (const char*)p.values + (size_t)row * p.row_stride * elem<DT>::size;
+    for (int i = tid; i < p.K; i += T) {
+        const uint64_t key = cand[i];
+        const uint32_t n = key_index(key);
+        uint32_t bits = key_value_bits(key);
+        if (bits == 0) bits = elem<DT>::load_bits(rowp, n);     // which zero it was
+        elem<DT>::store_bits(p.out_vals, (int64_t)row * p.K + i, bits);
+        p.out_idx[(int64_t)row * p.K + i] = (int32_t)n;
+    }
+}
+
+template <typename DT>
+hipError_t launch_for(const FinishParams& p, int KP, int threads, hipStream_t stream) {
+    const size_t lds = (size_t)p.Cpad * 8;
+    const dim3 grid(p.rows), block(threads);
+    switch (KP) {
+#define ATK_CASE(N) case N: hipLaunchKernelGGL((approx_finish_kernel<DT, N>), grid, block, lds, stream, p); break;
+        ATK_CASE(1) ATK_CASE(2) ATK_CASE(3) ATK_CASE(4) ATK_CASE(6) ATK_CASE(8) ATK_CASE(16) ATK_CASE(32)
+#undef ATK_CASE
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_finish(const FinishParams& p, int dtype, int KP, hipStream_t stream) {
+    int threads = 64;
+    while (threads < p.B && threads < 1024) threads <<= 1;
+    if (threads < 256 && p.Cpad >= 1024) threads = 256;     // the sort wants more lanes than buckets
+    return dtype == 0 ? launch_for<float>(p, KP, threads, stream)
+                      : launch_for<bf16_t>(p, KP, threads, stream);
+}
+
+}  // namespace atk

@@ -36,7 +36,11 @@ struct ApproxParams {
     int owners;           // lanes*slots sharing a bucket: S / B
     int seg;              // owners > 1: power of two >= owners*KP, LDS keys per bucket
     int Cpad;             // power of two >= B*K', LDS keys per row for stage 2
-    int mode;             // 0: stage 2 fused, write out_*; 1: write survivors to surv_*
+    int mode;             // 0: stage 2 fused, write out_*; 1: write survivors to surv_*;
+                          // 2: this workgroup covers one segment of its row, write partial keys
+    int nseg;             // mode 2: segments per row (gridDim.y)
+    int seg_steps;        // mode 2: steps per segment (the last one may be shorter)
+    uint64_t* part_keys;  // mode 2: [rows, nseg, K', B] keys, 0 = empty entry
     void* out_vals;
     int32_t* out_idx;
     void* surv_vals;
@@ -63,9 +67,6 @@ __device__ __forceinline__ void list_insert(float (&val)[KP], int32_t (&stp)[KP]
     }
     val[0] = sel(c[0], x, val[0]);
     stp[0] = sel(c[0], step, stp[0]);
-    // keep the updates of different lists apart: interleaving them buys nothing (the compares
-    // of one update are already independent) and multiplies the live compare masks
-    __builtin_amdgcn_sched_barrier(0);
 }
 
 template <typename DT, int KP, int V, int R>
@@ -103,15 +104,32 @@ struct ApproxKernel {
             off[r] = slot_ok[r] ? o : 0;    // idle slots re-read offset 0; their lists are dropped
         }
 
-        // ---- stage 1: stream the row once -------------------------------------------------
-        int s = 0;
-        for (; s + U <= p.nsteps; s += U) {
+        // ---- stage 1: stream the row (or this workgroup's segment of it) once ------------------
+        // A load address is (uniform base of the step, in a buffer descriptor) + (per-lane
+        // 32-bit byte offset), so streaming needs no vector address arithmetic.  U steps are
+        // loaded back to back and then consumed in order; other waves cover the wait.
+        constexpr int ES = elem<DT>::size;
+        const char* wg_base = (const char*)p.values +
+                              (size_t)blockIdx.x * p.rows_per_wg * p.row_stride * ES;
+        const uint32_t step_bytes = (uint32_t)p.S * ES;
+        uint32_t lane_off[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            lane_off[r] = (uint32_t)(((size_t)(row_ok ? g : 0) * p.row_stride + off[r]) * ES);
+
+        int s = 0, s_end = p.nsteps;
+        if (p.mode == 2) {
+            s = blockIdx.y * p.seg_steps;
+            s_end = min(p.nsteps, s + p.seg_steps);
+        }
+        for (; s + U <= s_end; s += U) {
+            const buffer_rsrc rs = make_rsrc(wg_base + (size_t)s * step_bytes);
             vec_t buf[U][R];
 #pragma unroll
             for (int u = 0; u < U; ++u)
 #pragma unroll
                 for (int r = 0; r < R; ++r)
-                    buf[u][r] = VL::load(rowp + ((size_t)(s + u) * p.S + off[r]) * elem<DT>::size);
+                    buf[u][r] = VL::load(rs, lane_off[r], (uint32_t)u * step_bytes);
 #pragma unroll
             for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -121,10 +139,11 @@ struct ApproxKernel {
                         list_insert<KP>(val[r * V + v], stp[r * V + v],
                                         __uint_as_float(VL::bits(buf[u][r], v)), s + u);
         }
-        for (; s < p.nsteps; ++s) {
+        for (; s < s_end; ++s) {
+            const buffer_rsrc rs = make_rsrc(wg_base + (size_t)s * step_bytes);
 #pragma unroll
             for (int r = 0; r < R; ++r) {
-                vec_t x = VL::load(rowp + ((size_t)s * p.S + off[r]) * elem<DT>::size);
+                vec_t x = VL::load(rs, lane_off[r], 0);
 #pragma unroll
                 for (int v = 0; v < V; ++v)
                     list_insert<KP>(val[r * V + v], stp[r * V + v],
@@ -152,6 +171,11 @@ struct ApproxKernel {
                         const uint32_t b = __float_as_uint(val[r * V + v][k]);
                         if (p.mode == 0) {
                             cand[bucket * p.Kprime + k] = make_key(b, n);
+                        } else if (p.mode == 2) {
+                            // a segment shorter than K' steps leaves NaN (empty) entries
+                            const float f = val[r * V + v][k];
+                            const int64_t o = (((int64_t)row * p.nseg + blockIdx.y) * p.Kprime + k) * p.B + bucket;
+                            p.part_keys[o] = (f == f) ? make_key(b, n) : 0;
                         } else {
                             const int64_t o = ((int64_t)row * p.Kprime + k) * p.B + bucket;
                             elem<DT>::store_bits(p.surv_vals, o, b);
@@ -235,7 +259,8 @@ hipError_t launch_approx(const ApproxParams& p, int grid, int block, size_t lds_
     template <>                                                                                 \
     hipError_t launch_approx<DT, KP, V, R>(const ApproxParams& p, int grid, int block,          \
                                            size_t lds_bytes, hipStream_t stream) {              \
-        hipLaunchKernelGGL((approx_topk_kernel<DT, KP, V, R>), dim3(grid), dim3(block),        \
+        hipLaunchKernelGGL((approx_topk_kernel<DT, KP, V, R>),                                  \
+                           dim3(grid, p.mode == 2 ? p.nseg : 1), dim3(block),                   \
                            lds_bytes, stream, p);                                               \
         return hipGetLastError();                                                               \
     }

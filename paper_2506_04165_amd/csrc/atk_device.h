@@ -59,9 +59,47 @@ template <> struct vec_bytes<4>  { using type = uint32_t; };
 template <> struct vec_bytes<8>  { using type = uint2; };
 template <> struct vec_bytes<16> { using type = uint4; };
 
+// Buffer addressing: a 128-bit resource descriptor in SGPRs names a uniform base address; a
+// load adds a per-lane 32-bit byte offset (VGPR) and a uniform 32-bit byte offset (SGPR), so
+// streaming a row costs no vector address arithmetic at all.
+using buffer_rsrc = __amdgpu_buffer_rsrc_t;
+__device__ __forceinline__ buffer_rsrc make_rsrc(const void* uniform_base) {
+    // raw buffer (stride 0), 2^32-1 addressable bytes, 32-bit data format
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(uniform_base), 0, 0xffffffff, 0x00020000);
+}
+// Cache policy of the streaming loads: every input byte is read exactly once, so the loads
+// are marked non-temporal (aux bit 1) and do not displace useful lines from the caches.
+#ifndef ATK_LOAD_AUX
+#define ATK_LOAD_AUX 2
+#endif
+template <int BYTES> struct buffer_load;
+template <> struct buffer_load<2> {
+    __device__ static uint16_t run(buffer_rsrc r, uint32_t voff, uint32_t soff) {
+        return __builtin_amdgcn_raw_buffer_load_b16(r, voff, soff, ATK_LOAD_AUX);
+    }
+};
+template <> struct buffer_load<4> {
+    __device__ static uint32_t run(buffer_rsrc r, uint32_t voff, uint32_t soff) {
+        return __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, ATK_LOAD_AUX);
+    }
+};
+template <> struct buffer_load<8> {
+    __device__ static uint2 run(buffer_rsrc r, uint32_t voff, uint32_t soff) {
+        return __builtin_bit_cast(uint2, __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, ATK_LOAD_AUX));
+    }
+};
+template <> struct buffer_load<16> {
+    __device__ static uint4 run(buffer_rsrc r, uint32_t voff, uint32_t soff) {
+        return __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, ATK_LOAD_AUX));
+    }
+};
+
 template <typename DT, int V> struct vec_load {
-    using vec_t = typename vec_bytes<V * elem<DT>::size>::type;
-    __device__ static vec_t load(const void* p) { return *(const vec_t*)p; }
+    static constexpr int bytes = V * elem<DT>::size;
+    using vec_t = typename vec_bytes<bytes>::type;
+    __device__ static vec_t load(buffer_rsrc r, uint32_t lane_bytes, uint32_t uniform_bytes) {
+        return buffer_load<bytes>::run(r, lane_bytes, uniform_bytes);
+    }
     // binary32 bit pattern of element v of the vector
     __device__ static uint32_t bits(const vec_t& x, int v) {
         if constexpr (sizeof(vec_t) == 2) {

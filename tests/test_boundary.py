@@ -111,6 +111,20 @@ def test_plans_for_benchmark_configs_are_fused_single_launch():
             assert "workspace=0" in text
 
 
+def test_few_long_rows_are_split_over_workgroups():
+    # 8 rows of 262144 (the shape of the paper's Table 1) cannot fill 256 CUs one row per
+    # workgroup: rows are cut into segments and the plan asks for a workspace for the partial lists
+    st, text = atk.describe_plan(torch.float32, 8, 262144, 1024, 4, 1024)
+    assert st == atk.OK and text.startswith("split"), text
+    need = atk.workspace_bytes(atk.OP_APPROX_TOPK, torch.float32, 8, 262144, 1024, 4, 1024)
+    nseg = int(re.search(r"grid=\d+x(\d+)", text).group(1))
+    assert nseg > 1 and need == 8 * nseg * 4 * 1024 * 8
+    # the split is an optimisation: without a workspace the call is still legal (validation only
+    # here: rows=0 launches nothing)
+    assert call_approx(rows=0, N=262144, K=1024, Kp=4, B=1024, values=None, out_vals=None,
+                       out_idx=None) == atk.OK
+
+
 @pytest.mark.parametrize("N,B,K,Kp", [(4096, 64, 32, 1), (4096, 64, 32, 4), (14336, 128, 287, 4),
                                       (262144, 1024, 1024, 4), (1048576, 4096, 128, 1),
                                       (65536, 256, 256, 8), (256000, 512, 64, 2), (4096, 64, 32, 32)])
