@@ -208,7 +208,9 @@ static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, in
             // fraction of the bytes streamed
             const size_t in_bytes = (size_t)rows * N * es;
             const bool forced = std::getenv("ATK_SEGMENTS") != nullptr;
-            const bool pays = in_bytes >= kMinSplitBytes && ws * 8 <= in_bytes;
+            // (when most of the chip would idle, partial lists up to half the input are fine)
+            const size_t ws_cap = waves * 2 <= kTargetWaves ? in_bytes / 2 : in_bytes / 8;
+            const bool pays = in_bytes >= kMinSplitBytes && ws <= ws_cap;
             if (nseg > 1 && ws <= ws_avail && (pays || forced)) {
                 pl.nseg = nseg;
                 pl.seg_steps = seg_steps;
