@@ -93,7 +93,8 @@ def bench_workload(name, steps, warmup, with_cpu_baseline, only_params=None):
 
     # exact Top-K on the same inputs (the comparison system)
     exact_steps = max(3, steps // 4)
-    ex = time_steps(lambda i: atk.topk(xs[i], w.K, out=(out_v, out_i)), copies, exact_steps, 1)
+    ex = time_steps(lambda i: atk.topk(xs[i], w.K, out=(out_v, out_i)), copies, exact_steps,
+                    max(1, warmup // 4))
     ev, ei = atk.topk(xs[0], w.K)
     exact = {"kernel_ms_avg": ex["kernel_ms_avg"], "rows_per_s": w.rows / (ex["kernel_ms_avg"] * 1e-3),
              "achieved_gbps": alg / (ex["kernel_ms_avg"] * 1e-3) / 1e9,
@@ -160,8 +161,9 @@ def cpu_baseline(name, xd, B, Kp):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    # a step is a fraction of a millisecond; the clocks need ~20 ms of work to settle
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--workload", default=None, help="only this workload (also becomes the headline)")
     ap.add_argument("--params", default=None, help="with --workload: only this 'B,Kprime' setting")
     ap.add_argument("--headline-only", action="store_true", help="skip the other configurations")

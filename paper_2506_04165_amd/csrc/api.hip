@@ -44,11 +44,11 @@ static const Variant* find_variant(int dtype, int KP, int NL, Pred vector_ok) {
 constexpr int kMaxListLen = 32;          // longest K'-list kept in registers
 constexpr int kMaxEntriesPerLane = 32;   // V*R*KP
 constexpr int kMaxLanes = 1024;
-constexpr size_t kLdsBudget = 64 * 1024; // dynamic LDS per workgroup used by the fused kernel
+constexpr size_t kLdsBudget = 144 * 1024; // dynamic LDS per workgroup (the CU has 160 KB)
 constexpr int kExactCap = 4096;          // exact kernel: LDS key buffer
 constexpr int kExactMaxK = 2048;
 constexpr int64_t kTargetWaves = 2048;   // 256 CUs x 4 SIMDs x 2 waves: below this the chip idles
-constexpr int kMinSegmentSteps = 32;     // do not cut a row into pieces shorter than this
+constexpr int kMinSegmentSteps = 8;      // do not cut a row into pieces shorter than this
 constexpr int kMaxSegments = 64;
 constexpr size_t kMinSplitBytes = 4u << 20;
 
@@ -91,6 +91,8 @@ struct Plan {
     const Variant* var = nullptr;
     int G = 0, rows_per_wg = 1, S = 0, nsteps = 0, owners = 1, seg = 0, Cpad = 0;
     int block = 0, grid = 0;
+    int tail = 0;               // see ApproxParams::tail
+    size_t aux_offset = 0;      // LDS keys before the auxiliary region
     size_t lds = 0;
     size_t workspace = 0;       // bytes the plan needs (0: none)
     int nseg = 1, seg_steps = 0;  // > 1: rows are cut into segments, finished by a second launch
@@ -166,11 +168,16 @@ static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, in
     // rows per workgroup: fill 256 lanes when one row needs fewer
     int rpw = G >= 256 ? 1 : 256 / G;
     while (rpw > 1 && rpw / 2 >= rows) rpw >>= 1;
+    // LDS: [candidates of every row of the workgroup][auxiliary: partial lists of shared
+    // buckets, later reused as scratch of the selection]
+    const bool wave_tail = !stage1_only && G >= 64 && pl.Cpad <= kWaveSortMaxKeys;
     auto lds_for = [&](int r) {
-        size_t keys = 0;
-        if (owners > 1) keys = (size_t)r * ((size_t)pl.Cpad + (size_t)B * pl.seg);
-        else if (!stage1_only) keys = (size_t)r * pl.Cpad;
-        return keys * 8;
+        size_t cand = 0, aux = 0;
+        if (owners > 1) { cand = (size_t)r * pl.Cpad; aux = (size_t)r * B * pl.seg; }
+        else if (!stage1_only) cand = (size_t)r * pl.Cpad;
+        if (!stage1_only && r == 1 && pl.Cpad > 1024 && aux * 8 < (size_t)kSelectScratchBytes)
+            aux = (kSelectScratchBytes + 7) / 8;
+        return (cand + aux) * 8;
     };
     while (rpw > 1 && lds_for(rpw) > kLdsBudget) rpw >>= 1;
     // the kernel addresses a lane's row by a 32-bit byte offset from the workgroup's first row
@@ -178,6 +185,8 @@ static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, in
     if (G * rpw < 64) rpw = 64 / G;          // never launch less than a wavefront
     pl.rows_per_wg = rpw;
     pl.lds = lds_for(rpw);
+    pl.aux_offset = (size_t)rpw * pl.Cpad;
+    pl.tail = wave_tail ? 1 : (rpw == 1 ? 2 : 0);
     pl.block = G * rpw;
     pl.grid = (int)((rows + rpw - 1) / rpw);
     pl.fused = !stage1_only && pl.lds <= kLdsBudget;
@@ -198,23 +207,24 @@ static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, in
         const int max_by_len = pl.nsteps / kMinSegmentSteps;
         if (want > max_by_len) want = max_by_len;
         if (want > kMaxSegments) want = kMaxSegments;
-        want = env_int("ATK_SEGMENTS", want);
+        // worth it only for real streams, and only while the partial lists stay a small
+        // fraction of the bytes streamed (half of them when most of the chip would idle)
+        const size_t in_bytes = (size_t)rows * N * es;
+        const size_t per_seg = (size_t)rows * Kp * B * 8;
+        size_t ws_cap = waves * 2 <= kTargetWaves ? in_bytes / 2 : in_bytes / 8;
+        if (ws_cap > ws_avail) ws_cap = ws_avail;
+        if ((size_t)want > ws_cap / per_seg) want = (int)(ws_cap / per_seg);
+        if (in_bytes < kMinSplitBytes) want = 1;
+        const int forced = env_int("ATK_SEGMENTS", 0);
+        if (forced > 0 && (size_t)forced * per_seg <= ws_avail) want = forced;
         if (want > pl.nsteps) want = pl.nsteps;
         if (want > 1) {
             const int seg_steps = (pl.nsteps + want - 1) / want;
             const int nseg = (pl.nsteps + seg_steps - 1) / seg_steps;
-            const size_t ws = (size_t)rows * nseg * Kp * B * 8;
-            // worth it only for real streams, and only while the partial lists stay a small
-            // fraction of the bytes streamed
-            const size_t in_bytes = (size_t)rows * N * es;
-            const bool forced = std::getenv("ATK_SEGMENTS") != nullptr;
-            // (when most of the chip would idle, partial lists up to half the input are fine)
-            const size_t ws_cap = waves * 2 <= kTargetWaves ? in_bytes / 2 : in_bytes / 8;
-            const bool pays = in_bytes >= kMinSplitBytes && ws <= ws_cap;
-            if (nseg > 1 && ws <= ws_avail && (pays || forced)) {
+            if (nseg > 1) {
                 pl.nseg = nseg;
                 pl.seg_steps = seg_steps;
-                pl.workspace = ws;
+                pl.workspace = (size_t)nseg * per_seg;
                 pl.lds = 0;     // the streaming launch keeps nothing in LDS
             }
         }
@@ -231,6 +241,7 @@ static ApproxParams params_from(const Plan& pl, const void* values, int64_t rows
     p.G = pl.G; p.log2G = ilog2(pl.G);
     p.rows_per_wg = pl.rows_per_wg;
     p.S = pl.S; p.nsteps = pl.nsteps; p.owners = pl.owners; p.seg = pl.seg; p.Cpad = pl.Cpad;
+    p.aux_offset = (int)pl.aux_offset; p.tail = pl.tail;
     return p;
 }
 
@@ -381,10 +392,10 @@ int atk_describe_plan(int dtype, int64_t rows, int64_t N, int K, int Kprime, int
     }
     std::snprintf(buf, buflen,
                   "%s KP=%d V=%d R=%d lanes_per_row=%d rows_per_wg=%d block=%d grid=%dx%d step=%d "
-                  "steps=%d owners=%d seg=%d cand=%d lds=%zu workspace=%zu",
+                  "steps=%d owners=%d seg=%d cand=%d tail=%d lds=%zu workspace=%zu",
                   pl.nseg > 1 ? "split" : (pl.fused ? "fused" : "unfused"), pl.var->KP, pl.var->V,
                   pl.var->R, pl.G, pl.rows_per_wg, pl.block, pl.grid, pl.nseg, pl.S, pl.nsteps,
-                  pl.owners, pl.seg, pl.Cpad, pl.lds, pl.workspace);
+                  pl.owners, pl.seg, pl.Cpad, pl.tail, pl.lds, pl.workspace);
     return ATK_OK;
 }
 

@@ -4,9 +4,11 @@
 //   * Step 2 proper: per bucket, the K' greatest of the union of its per-segment lists.  One
 //     thread owns a bucket, reads the nseg*K' keys (coalesced across buckets) and keeps the
 //     K' greatest in registers.  Keys carry the index, so ties need no special care;
-//   * Steps 3-4: the B*K' merged keys go to LDS, a bitonic sort orders them, K are written.
+//   * Steps 3-4: the B*K' merged keys go to LDS; radix selection thins them out, one wavefront
+//     sorts what is left in registers and writes the first K.
 #include "approx_finish.h"
 #include "atk_device.h"
+#include "select_sort.h"
 
 namespace atk {
 namespace {
@@ -39,24 +41,19 @@ __global__ void __launch_bounds__(1024) approx_finish_kernel(FinishParams p) {
             if (j < p.Kprime) cand[b * p.Kprime + j] = top[j];
     }
     __syncthreads();
-    lds_bitonic_sort_desc(cand, p.Cpad, p.Cpad);
     const char* rowp = (const char*)p.values + (size_t)row * p.row_stride * elem<DT>::size;
-    for (int i = tid; i < p.K; i += T) {
-        const uint64_t key = cand[i];
-        const uint32_t n = key_index(key);
-        uint32_t bits = key_value_bits(key);
-        if (bits == 0) bits = elem<DT>::load_bits(rowp, n);     // which zero it was
-        elem<DT>::store_bits(p.out_vals, (int64_t)row * p.K + i, bits);
-        p.out_idx[(int64_t)row * p.K + i] = (int32_t)n;
-    }
+    wg_topk_from_lds<DT>(cand, p.Cpad, p.K, cand + p.Cpad, rowp, p.out_vals, p.out_idx,
+                         (int64_t)row * p.K);
 }
 
 template <typename DT>
 hipError_t launch_for(const FinishParams& p, int KP, int threads, hipStream_t stream) {
-    const size_t lds = (size_t)p.Cpad * 8;
+    const size_t lds = (size_t)p.Cpad * 8 + (p.Cpad > kWaveSortMaxKeys ? kSelectScratchBytes : 0);
     const dim3 grid(p.rows), block(threads);
     switch (KP) {
-#define ATK_CASE(N) case N: hipLaunchKernelGGL((approx_finish_kernel<DT, N>), grid, block, lds, stream, p); break;
+#define ATK_CASE(N) case N:                                                                       \
+        allow_large_lds((const void*)approx_finish_kernel<DT, N>, lds);                           \
+        hipLaunchKernelGGL((approx_finish_kernel<DT, N>), grid, block, lds, stream, p); break;
         ATK_CASE(1) ATK_CASE(2) ATK_CASE(3) ATK_CASE(4) ATK_CASE(6) ATK_CASE(8) ATK_CASE(16) ATK_CASE(32)
 #undef ATK_CASE
         default: return hipErrorInvalidValue;

@@ -21,6 +21,7 @@
 //   * mode 1 writes the survivors in the [rows, K', B] layout of Section 6.3 instead.
 #pragma once
 #include "atk_device.h"
+#include "select_sort.h"
 
 namespace atk {
 
@@ -36,8 +37,13 @@ struct ApproxParams {
     int owners;           // lanes*slots sharing a bucket: S / B
     int seg;              // owners > 1: power of two >= owners*KP, LDS keys per bucket
     int Cpad;             // power of two >= B*K', LDS keys per row for stage 2
+    int aux_offset;       // LDS keys before the auxiliary region (partial lists / select scratch)
     int mode;             // 0: stage 2 fused, write out_*; 1: write survivors to surv_*;
                           // 2: this workgroup covers one segment of its row, write partial keys
+    int tail;             // mode 0, how stage 2 runs: 0 generic LDS sort of every row of the
+                          // workgroup; 1 at most 1024 candidates per row, sorted in registers by
+                          // the first wavefront of the row's group; 2 one row per workgroup,
+                          // radix selection + wave sort
     int nseg;             // mode 2: segments per row (gridDim.y)
     int seg_steps;        // mode 2: steps per segment (the last one may be shorter)
     uint64_t* part_keys;  // mode 2: [rows, nseg, K', B] keys, 0 = empty entry
@@ -190,7 +196,7 @@ struct ApproxKernel {
         } else {
             // m owners per bucket: partial lists -> [bucket][owner*KP + k], sort each bucket's
             // segment, keep its first K'.  Partial lists may be short: NaN entries become key 0.
-            uint64_t* part = lds + (size_t)p.rows_per_wg * p.Cpad + (size_t)g * p.B * p.seg;
+            uint64_t* part = lds + p.aux_offset + (size_t)g * p.B * p.seg;
             for (int i = t; i < p.B * p.seg; i += p.G) part[i] = 0;
             for (int i = C + t; i < p.Cpad; i += p.G) cand[i] = 0;
             __syncthreads();
@@ -209,8 +215,7 @@ struct ApproxKernel {
                 }
             }
             __syncthreads();
-            lds_bitonic_sort_desc(lds + (size_t)p.rows_per_wg * p.Cpad,
-                                  p.rows_per_wg * p.B * p.seg, p.seg);
+            lds_bitonic_sort_desc(lds + p.aux_offset, p.rows_per_wg * p.B * p.seg, p.seg);
             for (int i = t; i < C; i += p.G) {
                 const int bucket = i / p.Kprime, k = i - bucket * p.Kprime;
                 const uint64_t key = part[(size_t)bucket * p.seg + k];
@@ -230,6 +235,18 @@ struct ApproxKernel {
         }
 
         // ---- stage 2: exact Top-K of each row's candidates --------------------------------------
+        if (p.tail == 1) {
+            // few candidates: the first wavefront of every row's group sorts them in registers
+            if (t < kWave && row_ok)
+                wave_sort_dispatch<DT>(cand, p.Cpad, p.K, rowp, p.out_vals, p.out_idx, (int64_t)row * p.K);
+            return;
+        }
+        if (p.tail == 2) {
+            // one row per workgroup: thin the candidates out by radix selection, wave-sort the rest
+            wg_topk_from_lds<DT>(lds, p.Cpad, p.K, lds + p.aux_offset, rowp, p.out_vals, p.out_idx,
+                                 (int64_t)row * p.K);
+            return;
+        }
         lds_bitonic_sort_desc(lds, p.rows_per_wg * p.Cpad, p.Cpad);
         if (row_ok) {
             for (int i = t; i < p.K; i += p.G) {
@@ -259,6 +276,7 @@ hipError_t launch_approx(const ApproxParams& p, int grid, int block, size_t lds_
     template <>                                                                                 \
     hipError_t launch_approx<DT, KP, V, R>(const ApproxParams& p, int grid, int block,          \
                                            size_t lds_bytes, hipStream_t stream) {              \
+        allow_large_lds((const void*)approx_topk_kernel<DT, KP, V, R>, lds_bytes);              \
         hipLaunchKernelGGL((approx_topk_kernel<DT, KP, V, R>),                                  \
                            dim3(grid, p.mode == 2 ? p.nseg : 1), dim3(block),                   \
                            lds_bytes, stream, p);                                               \

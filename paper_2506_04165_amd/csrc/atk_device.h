@@ -131,6 +131,12 @@ __device__ __forceinline__ void lds_bitonic_sort_desc(uint64_t* a, int total, in
     }
 }
 
+// Host: kernels that ask for more than 64 KB of dynamic LDS have to say so first.
+inline void allow_large_lds(const void* kernel, size_t lds_bytes) {
+    if (lds_bytes > 64 * 1024)
+        (void)hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+}
+
 __device__ __forceinline__ int next_pow2(int x) {
     int p = 1;
     while (p < x) p <<= 1;

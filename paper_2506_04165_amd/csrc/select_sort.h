@@ -1,0 +1,232 @@
+// Stage 2 building blocks: exact Top-K of keys that already sit in LDS or registers
+// (Section 6.1 Step 4: sort the merged survivors, keep the first K).
+//
+//   WaveSort<R>      bitonic sort of 64*R keys held R per lane in the registers of one
+//                    wavefront: compare-exchanges between registers of a lane are plain
+//                    selects, those between lanes fetch the partner's key with a cross-lane
+//                    shuffle.  No LDS traffic, no barriers.
+//   wg_topk_from_lds workgroup-level Top-K of n keys in LDS.  Small inputs go straight to a
+//                    wave sort.  Larger ones are first cut down by radix selection (an LDS
+//                    histogram over the leading value bits finds the digit that holds the K-th
+//                    key; keys above it are certain members, keys inside it candidates) and only
+//                    the members and candidates are sorted.  A full LDS bitonic sort remains
+//                    as the fallback for inputs the selection cannot thin out (heavy ties).
+#pragma once
+#include "atk_device.h"
+
+namespace atk {
+
+constexpr int kWaveSortMaxR = 16;                       // up to 1024 keys per wavefront
+constexpr int kWaveSortMaxKeys = kWave * kWaveSortMaxR;
+constexpr int kSelectBins = 2048;
+// LDS scratch wg_topk_from_lds needs next to the keys when n > kWaveSortMaxKeys:
+// a compaction buffer of kWaveSortMaxKeys keys (the histogram aliases it) + control words.
+constexpr int kSelectScratchBytes = kWaveSortMaxKeys * 8 + 128;
+
+template <int R>
+struct WaveSort {
+    static constexpr int LOGN = (R == 1 ? 6 : R == 2 ? 7 : R == 4 ? 8 : R == 8 ? 9 : 10);
+    static_assert(R == 1 || R == 2 || R == 4 || R == 8 || R == 16, "R must be 1,2,4,8,16");
+
+    // Element e = lane*R + j lives in k[j] of `lane`.  After the call e is the rank: k[j] of
+    // lane l is the (l*R + j)-th greatest key.
+    __device__ static void sort(uint64_t (&k)[R]) {
+        const int lane = __lane_id();
+#pragma unroll
+        for (int lk = 1; lk <= LOGN; ++lk) {
+            const int kk = 1 << lk;
+#pragma unroll
+            for (int lj = lk - 1; lj >= 0; --lj) {
+                const int jj = 1 << lj;
+                if (jj < R) {
+                    // partners are registers j and j|jj of the same lane
+#pragma unroll
+                    for (int j = 0; j < R; ++j) {
+                        if (j & jj) continue;
+                        // descending block when bit kk of e is clear
+                        const bool desc = kk < R ? ((j & kk) == 0)
+                                                 : (kk >= kWave * R ? true : ((lane & (kk / R)) == 0));
+                        const uint64_t a = k[j], b = k[j | jj];
+                        const bool sw = (a < b) == desc;
+                        k[j] = sw ? b : a;
+                        k[j | jj] = sw ? a : b;
+                    }
+                } else {
+                    const int m = jj / R;                       // partner lane = lane ^ m
+                    const bool lower = (lane & m) == 0;
+                    const bool desc = kk >= kWave * R ? true : ((lane & (kk / R)) == 0);
+                    const bool want_max = lower == desc;
+#pragma unroll
+                    for (int j = 0; j < R; ++j) {
+                        const uint64_t a = k[j];
+                        const uint64_t b = __shfl_xor((unsigned long long)a, m, kWave);
+                        const bool take = (b > a) == want_max;   // a == b only for empty keys
+                        k[j] = (a == b) ? a : (take ? b : a);
+                    }
+                }
+            }
+        }
+    }
+};
+
+// Decode and write the first K of the sorted keys of one wavefront (rank e = lane*R + j).
+template <typename DT, int R>
+__device__ __forceinline__ void wave_write_topk(const uint64_t (&k)[R], int K, const void* rowp,
+                                                void* out_vals, int32_t* out_idx, int64_t out_base) {
+    const int lane = __lane_id();
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        const int e = lane * R + j;
+        if (e < K) {
+            const uint32_t n = key_index(k[j]);
+            uint32_t bits = key_value_bits(k[j]);
+            if (bits == 0) bits = elem<DT>::load_bits(rowp, n);      // which zero it was
+            elem<DT>::store_bits(out_vals, out_base + e, bits);
+            out_idx[out_base + e] = (int32_t)n;
+        }
+    }
+}
+
+// One wavefront sorts `n` (<= 64*R) keys read from LDS and writes the first K.
+template <typename DT, int R>
+__device__ __forceinline__ void wave_sort_from_lds(const uint64_t* keys, int n, int K, const void* rowp,
+                                                   void* out_vals, int32_t* out_idx, int64_t out_base) {
+    const int lane = __lane_id();
+    uint64_t k[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        const int i = j * kWave + lane;                 // any assignment will do: conflict-free
+        k[j] = i < n ? keys[i] : 0;
+    }
+    WaveSort<R>::sort(k);
+    wave_write_topk<DT, R>(k, K, rowp, out_vals, out_idx, out_base);
+}
+
+// Not inlined on purpose: the sorting networks are long, and every streaming kernel variant
+// that finishes in LDS shares this one copy per translation unit.
+template <typename DT>
+__device__ __noinline__ void wave_sort_dispatch(const uint64_t* keys, int n, int K, const void* rowp,
+                                                   void* out_vals, int32_t* out_idx, int64_t out_base) {
+    if (n <= 64)       wave_sort_from_lds<DT, 1>(keys, n, K, rowp, out_vals, out_idx, out_base);
+    else if (n <= 128) wave_sort_from_lds<DT, 2>(keys, n, K, rowp, out_vals, out_idx, out_base);
+    else if (n <= 256) wave_sort_from_lds<DT, 4>(keys, n, K, rowp, out_vals, out_idx, out_base);
+    else if (n <= 512) wave_sort_from_lds<DT, 8>(keys, n, K, rowp, out_vals, out_idx, out_base);
+    else               wave_sort_from_lds<DT, 16>(keys, n, K, rowp, out_vals, out_idx, out_base);
+}
+
+// Histogram pass of the radix selection over keys in LDS.  On return (all threads):
+//   digit   the value of the `bits`-wide digit at `shift` that holds the need-th greatest key
+//           among the keys matching (prefix, mask),
+//   above   how many matching keys have a greater digit (certain members),
+//   count   how many matching keys have exactly that digit.
+// hist: kSelectBins words, ctl: 32 words of LDS scratch.  Contains barriers.
+__device__ __forceinline__ void lds_select_digit(const uint64_t* keys, int n, uint64_t prefix,
+                                                 uint64_t mask, int shift, int bits, int need,
+                                                 uint32_t* hist, uint32_t* ctl,
+                                                 uint32_t& digit, uint32_t& above, uint32_t& count) {
+    const int tid = threadIdx.x, T = blockDim.x;
+    const uint32_t dmask = (1u << bits) - 1u;
+    for (int i = tid; i < kSelectBins; i += T) hist[i] = 0;
+    __syncthreads();
+    for (int i = tid; i < n; i += T) {
+        const uint64_t key = keys[i];
+        if (key != 0 && (key & mask) == prefix) atomicAdd(&hist[(uint32_t)(key >> shift) & dmask], 1u);
+    }
+    __syncthreads();
+    // suffix sums over bins: thread t owns bins [t*bpt, (t+1)*bpt)
+    const int bpt = (kSelectBins + T - 1) / T;
+    uint32_t mine = 0;
+    for (int i = 0; i < bpt; ++i) {
+        const int bin = tid * bpt + i;
+        if (bin < kSelectBins) mine += hist[bin];
+    }
+    const int lane = tid & (kWave - 1), wave = tid >> 6;
+    uint32_t suf = mine;                               // inclusive suffix sum inside the wave
+    for (int o = 1; o < kWave; o <<= 1) {
+        const uint32_t other = __shfl_down(suf, o, kWave);
+        if (lane + o < kWave) suf += other;
+    }
+    if (lane == 0) ctl[4 + wave] = suf;
+    __syncthreads();
+    uint32_t later = 0;                                // waves after mine
+    for (int w = wave + 1; w < (T + kWave - 1) / kWave; ++w) later += ctl[4 + w];
+    const uint32_t incl = suf + later, excl = incl - mine;
+    if (excl < (uint32_t)need && incl >= (uint32_t)need) {
+        uint32_t run = excl;
+        for (int i = bpt - 1; i >= 0; --i) {
+            const int bin = tid * bpt + i;
+            if (bin >= kSelectBins) continue;
+            const uint32_t c = hist[bin];
+            if (run + c >= (uint32_t)need) {
+                ctl[0] = (uint32_t)bin; ctl[1] = run; ctl[2] = c;
+                break;
+            }
+            run += c;
+        }
+    }
+    __syncthreads();
+    digit = ctl[0]; above = ctl[1]; count = ctl[2];
+    __syncthreads();
+}
+
+// Top-K (descending) of the n keys in LDS `keys` (n a power of two, key 0 = empty, at least K
+// real keys), written decoded to out_*[out_base + 0..K).  Called by every thread of the
+// workgroup; `scratch` is kSelectScratchBytes of LDS (unused when n <= kWaveSortMaxKeys).
+// The keys array is used as working storage.
+template <typename DT>
+__device__ __forceinline__ void wg_topk_from_lds(uint64_t* keys, int n, int K, void* scratch,
+                                                 const void* rowp, void* out_vals,
+                                                 int32_t* out_idx, int64_t out_base) {
+    const int tid = threadIdx.x, T = blockDim.x;
+    if (n <= kWaveSortMaxKeys) {
+        if (tid < kWave) wave_sort_dispatch<DT>(keys, n, K, rowp, out_vals, out_idx, out_base);
+        return;
+    }
+    if (K <= kWaveSortMaxKeys) {
+        uint64_t* buf = (uint64_t*)scratch;
+        uint32_t* hist = (uint32_t*)scratch;                          // aliases buf
+        uint32_t* ctl = (uint32_t*)((char*)scratch + kWaveSortMaxKeys * 8);
+        uint64_t prefix = 0, mask = 0;
+        int need = K, certain = 0;
+        bool fits = false;
+        // leading value bits: 11, 11, 10 (the low word of a key is the index)
+        const int shifts[3] = {53, 42, 32}, widths[3] = {11, 11, 10};
+        for (int d = 0; d < 3 && !fits; ++d) {
+            uint32_t digit, above, count;
+            lds_select_digit(keys, n, prefix, mask, shifts[d], widths[d], need, hist, ctl, digit, above, count);
+            certain += (int)above;
+            need -= (int)above;
+            prefix |= (uint64_t)digit << shifts[d];
+            mask |= (uint64_t)((1u << widths[d]) - 1u) << shifts[d];
+            fits = certain + (int)count <= kWaveSortMaxKeys;
+        }
+        if (fits) {
+            if (tid == 0) ctl[3] = 0;
+            __syncthreads();
+            // certain members and candidates -> buf (the histogram is dead by now)
+            for (int i = tid; i < n; i += T) {
+                const uint64_t key = keys[i];
+                if (key != 0 && (key & mask) >= prefix) {
+                    const uint32_t slot = atomicAdd(&ctl[3], 1u);
+                    if (slot < (uint32_t)kWaveSortMaxKeys) buf[slot] = key;
+                }
+            }
+            __syncthreads();
+            const int total = min((int)ctl[3], kWaveSortMaxKeys);
+            if (tid < kWave) wave_sort_dispatch<DT>(buf, total, K, rowp, out_vals, out_idx, out_base);
+            return;
+        }
+    }
+    // fallback: order everything
+    lds_bitonic_sort_desc(keys, n, n);
+    for (int i = tid; i < K; i += T) {
+        const uint64_t key = keys[i];
+        const uint32_t idx = key_index(key);
+        uint32_t bits = key_value_bits(key);
+        if (bits == 0) bits = elem<DT>::load_bits(rowp, idx);
+        elem<DT>::store_bits(out_vals, out_base + i, bits);
+        out_idx[out_base + i] = (int32_t)idx;
+    }
+}
+
+}  // namespace atk

@@ -10,9 +10,10 @@
 //   3. stop as soon as (certain members + keys matching the prefix) fit the LDS buffer --
 //      for continuous data that is after the first digit -- otherwise take the next digit
 //      (value bits first, then index bits, so ties end up resolved toward the lower index);
-//   4. one more pass gathers certain members and prefix matches into LDS, a bitonic sort
-//      orders them, the first K are written out.
+//   4. one more pass gathers certain members and prefix matches into LDS, where the same
+//      selection-then-wave-sort as in the fused kernel's stage 2 picks and orders the K.
 #include "atk_device.h"
+#include "select_sort.h"
 #include "topk_exact.h"
 
 namespace atk {
@@ -34,9 +35,11 @@ __device__ __forceinline__ uint64_t key_at(const void* rowp, const int32_t* payl
 template <typename DT, bool PAYLOAD>
 __global__ void __launch_bounds__(1024) topk_exact_kernel(TopkParams p) {
     extern __shared__ uint64_t lds64[];
-    // layout: [0, cap) key buffer (the histogram aliases its start), then 8 control words
+    // layout: [0, cap) key buffer (the histogram aliases its start), scratch of the final
+    // selection, then 32 control words
     uint32_t* hist = (uint32_t*)lds64;
-    uint32_t* ctl = (uint32_t*)(lds64 + p.cap);   // 0: digit  1: certain  2: count  3: fill  4..: wave sums
+    void* scratch = lds64 + p.cap;
+    uint32_t* ctl = (uint32_t*)((char*)scratch + kSelectScratchBytes);   // 0: digit  1: certain  2: count  3: fill  4..: wave sums
     const int tid = threadIdx.x, T = blockDim.x;
     const int row = blockIdx.x;
     const char* rowp = (const char*)p.values + (size_t)row * p.row_stride * elem<DT>::size;
@@ -112,20 +115,20 @@ __global__ void __launch_bounds__(1024) topk_exact_kernel(TopkParams p) {
     const int n2 = next_pow2(total);
     for (int i = total + tid; i < n2; i += T) lds64[i] = 0;
     __syncthreads();
+    if (!PAYLOAD) {
+        wg_topk_from_lds<DT>(lds64, n2, p.K, scratch, rowp, p.out_vals, p.out_idx, (int64_t)row * p.K);
+        return;
+    }
+    // survivor mode: the key's index is the original position, the value sits at the survivor's slot
     lds_bitonic_sort_desc(lds64, n2, n2);
     for (int i = tid; i < p.K; i += T) {
         const uint64_t key = lds64[i];
         const uint32_t idx = key_index(key);
         uint32_t b = key_value_bits(key);
-        if (PAYLOAD) {
-            // survivors: look the element up by position to return its stored bits
-            // (rare: only needed to tell -0.0 from +0.0)
-            if (b == 0) {
-                for (int n = 0; n < N; ++n)
-                    if ((uint32_t)payload[n] == idx) { b = elem<DT>::load_bits(rowp, n); break; }
-            }
-        } else if (b == 0) {
-            b = elem<DT>::load_bits(rowp, idx);
+        if (b == 0) {
+            // rare: look the survivor up by its index to tell -0.0 from +0.0
+            for (int n = 0; n < N; ++n)
+                if ((uint32_t)payload[n] == idx) { b = elem<DT>::load_bits(rowp, n); break; }
         }
         elem<DT>::store_bits(p.out_vals, (int64_t)row * p.K + i, b);
         p.out_idx[(int64_t)row * p.K + i] = (int32_t)idx;
@@ -135,7 +138,7 @@ __global__ void __launch_bounds__(1024) topk_exact_kernel(TopkParams p) {
 }  // namespace
 
 hipError_t launch_topk_exact(const TopkParams& p, int dtype, int threads, hipStream_t stream) {
-    const size_t lds = (size_t)p.cap * 8 + 32 * 4;
+    const size_t lds = (size_t)p.cap * 8 + kSelectScratchBytes + 32 * 4;
     const dim3 grid(p.rows), block(threads);
     const bool payload = p.payload != nullptr;
     if (dtype == 0) {

@@ -92,10 +92,10 @@ def test_workspace_query_and_too_small():
     assert atk.workspace_bytes(atk.OP_APPROX_TOPK, f32, 256, 1048576, 128, 4, 1024) == 0
     assert atk.workspace_bytes(atk.OP_TOPK, f32, 4, 4096, 32, 0, 0) == 0
     # survivors beyond LDS go through memory: rows * B*K' * (4 + 4) bytes
-    need = atk.workspace_bytes(atk.OP_APPROX_TOPK, f32, 8, 65536, 128, 16, 1024)
-    assert need == 8 * 1024 * 16 * 8
-    assert call_approx(rows=8, N=65536, K=128, Kp=16, B=1024, ws=None, ws_bytes=0) == atk.WORKSPACE_TOO_SMALL
-    assert call_approx(rows=8, N=65536, K=128, Kp=16, B=1024, ws=FAKE, ws_bytes=need - 1) == atk.WORKSPACE_TOO_SMALL
+    need = atk.workspace_bytes(atk.OP_APPROX_TOPK, f32, 8, 131072, 128, 16, 2048)
+    assert need == 8 * 2048 * 16 * 8
+    assert call_approx(rows=8, N=131072, K=128, Kp=16, B=2048, ws=None, ws_bytes=0) == atk.WORKSPACE_TOO_SMALL
+    assert call_approx(rows=8, N=131072, K=128, Kp=16, B=2048, ws=FAKE, ws_bytes=need - 1) == atk.WORKSPACE_TOO_SMALL
     # illegal arguments
     assert atk.workspace_bytes(atk.OP_APPROX_TOPK, f32, 4, 4096, 32, 4, 63) == atk.SIZE_MAX
     assert atk.workspace_bytes(99, f32, 4, 4096, 32, 4, 64) == atk.SIZE_MAX

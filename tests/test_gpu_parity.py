@@ -219,8 +219,8 @@ def test_zero_rows(atk):
 
 
 def test_unfused_path_through_workspace(atk):
-    # B*K' = 16384 survivors per row do not fit the fused kernel's LDS: two launches + workspace
-    N, B, Kp, K = 65536, 1024, 16, 300
+    # B*K' = 32768 survivors per row do not fit the fused kernel's LDS: two launches + workspace
+    N, B, Kp, K = 131072, 2048, 16, 300
     st, text = atk.describe_plan(torch.float32, 4, N, K, Kp, B)
     assert st == atk.OK and text.startswith("unfused")
     x = workloads.gaussian(4, N, seed=12)
@@ -229,6 +229,29 @@ def test_unfused_path_through_workspace(atk):
     check_approx(atk, x, K, Kp, B)
     xb = workloads.gaussian(4, N, seed=14, dtype=torch.bfloat16)
     check_approx(atk, xb, K, Kp, B)
+
+
+def test_split_path_few_long_rows(atk):
+    # the shape of the paper's Table 1: 8 rows x 262144, K=1024; rows are cut into segments
+    for dtype in (torch.float32, torch.bfloat16):
+        x = workloads.gaussian(8, 262144, seed=15, dtype=dtype)
+        for B, Kp in [(1024, 4), (8192, 1), (512, 6), (2048, 2)]:
+            st, text = atk.describe_plan(dtype, 8, 262144, 1024, Kp, B)
+            assert st == atk.OK
+            if (B, Kp) == (1024, 4):
+                assert text.startswith("split"), text
+            check_approx(atk, x, 1024, Kp, B)
+    # ties across segment boundaries, and a workspace that is too small (falls back to one launch)
+    z = workloads.heavy_ties(8, 262144, seed=16, symbols=3)
+    check_approx(atk, z, 1024, 4, 1024)
+    zd = z.to(DEV)
+    small = torch.empty(1024, dtype=torch.uint8, device=DEV)
+    v1, i1 = atk.approx_topk(zd, 1024, 4, 1024)
+    out = (torch.empty_like(v1), torch.empty_like(i1))
+    st = atk.lib.atk_approx_topk(zd.data_ptr(), 0, 8, 262144, 262144, 1024, 4, 1024,
+                                 out[0].data_ptr(), out[1].data_ptr(), small.data_ptr(), 1024, None)
+    torch.cuda.synchronize()
+    assert st == atk.OK and torch.equal(out[1], i1) and torch.equal(out[0], v1)
 
 
 def test_exact_topk_sizes(atk):
