@@ -38,7 +38,9 @@ PAPER_CONTEXT = {
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/),
 # keyed by (workload, B, K').  None = not measured.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    ("c4_mips", 1024, 4): 1074327000,   # profiles/approx_topk_c4_mips_B1024_Kp4.md
+}
 
 
 def algorithmic_bytes(rows, N, K, esize):
@@ -168,6 +170,9 @@ def main():
     ap.add_argument("--params", default=None, help="with --workload: only this 'B,Kprime' setting")
     ap.add_argument("--headline-only", action="store_true", help="skip the other configurations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain 1 GiB device copy a few times (reference kernel of known "
+                         "size for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE) and exit")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (rows are independent; sharding rows over "
@@ -178,6 +183,18 @@ def main():
     import torch
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     from paper_2506_04165_amd import workloads
+
+    if args.calibrate_copy:
+        nbytes = 1 << 30
+        src = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda:0").normal_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "plain copy", "launches": 3, "bytes_read_per_launch": nbytes,
+                          "bytes_written_per_launch": nbytes}))
+        return
 
     head_name, head_B, head_Kp = HEADLINE
     if args.workload:
