@@ -28,6 +28,7 @@ SOURCES = [
     "approx_inst_bf16_wide.hip",
     "approx_inst_f32_unaligned.hip",
     "approx_inst_bf16_unaligned.hip",
+    "approx_inst_bf16_packed.hip",
     "recall.cpp",
 ]
 

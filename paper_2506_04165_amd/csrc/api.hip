@@ -16,27 +16,30 @@ namespace atk {
 
 // ---- compiled kernel variants -------------------------------------------------------------
 using LaunchFn = hipError_t (*)(const ApproxParams&, int, int, size_t, hipStream_t);
-struct Variant { int dtype, KP, V, R; LaunchFn fn; };
+struct Variant { int dtype, KP, V, R; bool packed; LaunchFn fn; };
 
-#define ATK_X(TAG, T, KP, V, R) extern template hipError_t launch_approx<T, KP, V, R>(const ApproxParams&, int, int, size_t, hipStream_t);
+#define ATK_X(TAG, T, KP, V, R, P) extern template hipError_t launch_approx<T, KP, V, R, P>(const ApproxParams&, int, int, size_t, hipStream_t);
 ATK_ALL_INSTANCES(ATK_X)
 #undef ATK_X
 
 static const Variant kVariants[] = {
-#define ATK_X(TAG, T, KP, V, R) {TAG, KP, V, R, &launch_approx<T, KP, V, R>},
+#define ATK_X(TAG, T, KP, V, R, P) {TAG, KP, V, R, P, &launch_approx<T, KP, V, R, P>},
     ATK_ALL_INSTANCES(ATK_X)
 #undef ATK_X
 };
 
 // The variant with the given list length and lists per lane; `vector_ok(V)` says whether
 // V-element loads are legal for this problem.  The widest legal load wins.
+// `packed_ok`: the problem allows lists of packed 32-bit keys (preferred when compiled).
 template <typename Pred>
-static const Variant* find_variant(int dtype, int KP, int NL, Pred vector_ok) {
+static const Variant* find_variant(int dtype, int KP, int NL, bool packed_ok, Pred vector_ok) {
     const Variant* best = nullptr;
-    for (const Variant& v : kVariants)
-        if (v.dtype == dtype && v.KP == KP && v.V * v.R == NL && vector_ok(v.V) &&
-            (!best || v.V > best->V))
+    for (const Variant& v : kVariants) {
+        if (v.dtype != dtype || v.KP != KP || v.V * v.R != NL || !vector_ok(v.V)) continue;
+        if (v.packed && !packed_ok) continue;
+        if (!best || (v.packed && !best->packed) || (v.packed == best->packed && v.V > best->V))
             best = &v;
+    }
     return best;
 }
 
@@ -155,7 +158,9 @@ static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, in
             G <<= 1;
         }
     }
-    pl.var = find_variant(dtype, KP, NL, aligned_for);
+    // bf16 rows whose indices fit 16 bits: value and index share one 32-bit key
+    const bool packed_ok = dtype == ATK_BF16 && N <= 65536 && env_int("ATK_NO_PACKED", 0) == 0;
+    pl.var = find_variant(dtype, KP, NL, packed_ok, aligned_for);
     if (!pl.var) { pl.status = ATK_UNSUPPORTED; return pl; }
     const int V = pl.var->V;
     pl.G = G;
@@ -391,9 +396,10 @@ int atk_describe_plan(int dtype, int64_t rows, int64_t N, int K, int Kprime, int
         return ATK_OK;
     }
     std::snprintf(buf, buflen,
-                  "%s KP=%d V=%d R=%d lanes_per_row=%d rows_per_wg=%d block=%d grid=%dx%d step=%d "
+                  "%s%s KP=%d V=%d R=%d lanes_per_row=%d rows_per_wg=%d block=%d grid=%dx%d step=%d "
                   "steps=%d owners=%d seg=%d cand=%d tail=%d lds=%zu workspace=%zu",
-                  pl.nseg > 1 ? "split" : (pl.fused ? "fused" : "unfused"), pl.var->KP, pl.var->V,
+                  pl.nseg > 1 ? "split" : (pl.fused ? "fused" : "unfused"),
+                  pl.var->packed ? " packed" : "", pl.var->KP, pl.var->V,
                   pl.var->R, pl.G, pl.rows_per_wg, pl.block, pl.grid, pl.nseg, pl.S, pl.nsteps,
                   pl.owners, pl.seg, pl.Cpad, pl.tail, pl.lds, pl.workspace);
     return ATK_OK;

@@ -3,7 +3,7 @@
 #include "approx_instances.h"
 
 namespace atk {
-#define ATK_X(TAG, T, KP, V, R) ATK_DEFINE_LAUNCH(T, KP, V, R)
+#define ATK_X(TAG, T, KP, V, R, P) ATK_DEFINE_LAUNCH(T, KP, V, R, P)
 ATK_INSTANCES_F32_WIDE(ATK_X)
 #undef ATK_X
 }  // namespace atk

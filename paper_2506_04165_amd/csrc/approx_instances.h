@@ -4,41 +4,60 @@
 // Register budget: V*R*KP <= 32 list entries per lane.
 #pragma once
 
-// X(DTYPE_TAG, C++ type, KP, V, R)
-#define ATK_INSTANCES_NL1(X, TAG, T, V, R) \
-    X(TAG, T, 1, V, R) X(TAG, T, 2, V, R) X(TAG, T, 3, V, R) X(TAG, T, 4, V, R) \
-    X(TAG, T, 6, V, R) X(TAG, T, 8, V, R) X(TAG, T, 16, V, R) X(TAG, T, 32, V, R)
-#define ATK_INSTANCES_NL2(X, TAG, T, V, R) \
-    X(TAG, T, 1, V, R) X(TAG, T, 2, V, R) X(TAG, T, 3, V, R) X(TAG, T, 4, V, R) \
-    X(TAG, T, 6, V, R) X(TAG, T, 8, V, R) X(TAG, T, 16, V, R)
-#define ATK_INSTANCES_NL4(X, TAG, T, V, R) \
-    X(TAG, T, 1, V, R) X(TAG, T, 2, V, R) X(TAG, T, 3, V, R) X(TAG, T, 4, V, R) \
-    X(TAG, T, 6, V, R) X(TAG, T, 8, V, R)
-#define ATK_INSTANCES_NL8(X, TAG, T, V, R) \
-    X(TAG, T, 1, V, R) X(TAG, T, 2, V, R) X(TAG, T, 3, V, R) X(TAG, T, 4, V, R)
-#define ATK_INSTANCES_NL16(X, TAG, T, V, R) \
-    X(TAG, T, 1, V, R) X(TAG, T, 2, V, R)
+// X(DTYPE_TAG, C++ type, KP, V, R, PACKED)
+#define ATK_INSTANCES_NL1(X, TAG, T, V, R, P) \
+    X(TAG, T, 1, V, R, P) X(TAG, T, 2, V, R, P) X(TAG, T, 3, V, R, P) X(TAG, T, 4, V, R, P) \
+    X(TAG, T, 6, V, R, P) X(TAG, T, 8, V, R, P) X(TAG, T, 16, V, R, P) X(TAG, T, 32, V, R, P)
+#define ATK_INSTANCES_NL2(X, TAG, T, V, R, P) \
+    X(TAG, T, 1, V, R, P) X(TAG, T, 2, V, R, P) X(TAG, T, 3, V, R, P) X(TAG, T, 4, V, R, P) \
+    X(TAG, T, 6, V, R, P) X(TAG, T, 8, V, R, P) X(TAG, T, 16, V, R, P)
+#define ATK_INSTANCES_NL4(X, TAG, T, V, R, P) \
+    X(TAG, T, 1, V, R, P) X(TAG, T, 2, V, R, P) X(TAG, T, 3, V, R, P) X(TAG, T, 4, V, R, P) \
+    X(TAG, T, 6, V, R, P) X(TAG, T, 8, V, R, P)
+#define ATK_INSTANCES_NL8(X, TAG, T, V, R, P) \
+    X(TAG, T, 1, V, R, P) X(TAG, T, 2, V, R, P) X(TAG, T, 3, V, R, P) X(TAG, T, 4, V, R, P)
+#define ATK_INSTANCES_NL16(X, TAG, T, V, R, P) \
+    X(TAG, T, 1, V, R, P) X(TAG, T, 2, V, R, P)
 
 #define ATK_INSTANCES_F32_SMALL(X) \
-    ATK_INSTANCES_NL1(X, 0, float, 1, 1) ATK_INSTANCES_NL2(X, 0, float, 2, 1)
+    ATK_INSTANCES_NL1(X, 0, float, 1, 1, false) ATK_INSTANCES_NL2(X, 0, float, 2, 1, false)
 #define ATK_INSTANCES_F32_WIDE(X) \
-    ATK_INSTANCES_NL4(X, 0, float, 4, 1) ATK_INSTANCES_NL8(X, 0, float, 4, 2) \
-    ATK_INSTANCES_NL16(X, 0, float, 4, 4)
+    ATK_INSTANCES_NL4(X, 0, float, 4, 1, false) ATK_INSTANCES_NL8(X, 0, float, 4, 2, false) \
+    ATK_INSTANCES_NL16(X, 0, float, 4, 4, false)
 #define ATK_INSTANCES_BF16_SMALL(X) \
-    ATK_INSTANCES_NL1(X, 1, bf16_t, 1, 1) ATK_INSTANCES_NL2(X, 1, bf16_t, 2, 1)
+    ATK_INSTANCES_NL1(X, 1, bf16_t, 1, 1, false) ATK_INSTANCES_NL2(X, 1, bf16_t, 2, 1, false)
 #define ATK_INSTANCES_BF16_WIDE(X) \
-    ATK_INSTANCES_NL4(X, 1, bf16_t, 4, 1) ATK_INSTANCES_NL8(X, 1, bf16_t, 8, 1) \
-    ATK_INSTANCES_NL16(X, 1, bf16_t, 8, 2)
+    ATK_INSTANCES_NL4(X, 1, bf16_t, 4, 1, false) ATK_INSTANCES_NL8(X, 1, bf16_t, 8, 1, false) \
+    ATK_INSTANCES_NL16(X, 1, bf16_t, 8, 2, false)
 
 // single-element loads with several loads per step: for rows whose base address, stride or
 // bucket count rule out vector loads
 #define ATK_INSTANCES_F32_UNALIGNED(X) \
-    ATK_INSTANCES_NL2(X, 0, float, 1, 2) ATK_INSTANCES_NL4(X, 0, float, 1, 4) \
-    ATK_INSTANCES_NL8(X, 0, float, 1, 8) ATK_INSTANCES_NL16(X, 0, float, 1, 16)
+    ATK_INSTANCES_NL2(X, 0, float, 1, 2, false) ATK_INSTANCES_NL4(X, 0, float, 1, 4, false) \
+    ATK_INSTANCES_NL8(X, 0, float, 1, 8, false) ATK_INSTANCES_NL16(X, 0, float, 1, 16, false)
 #define ATK_INSTANCES_BF16_UNALIGNED(X) \
-    ATK_INSTANCES_NL2(X, 1, bf16_t, 1, 2) ATK_INSTANCES_NL4(X, 1, bf16_t, 1, 4) \
-    ATK_INSTANCES_NL8(X, 1, bf16_t, 1, 8) ATK_INSTANCES_NL16(X, 1, bf16_t, 1, 16)
+    ATK_INSTANCES_NL2(X, 1, bf16_t, 1, 2, false) ATK_INSTANCES_NL4(X, 1, bf16_t, 1, 4, false) \
+    ATK_INSTANCES_NL8(X, 1, bf16_t, 1, 8, false) ATK_INSTANCES_NL16(X, 1, bf16_t, 1, 16, false)
+
+// bf16 rows of at most 65536 elements with K' >= 2: lists of packed 32-bit keys
+#define ATK_PACKED_NL1(X, V, R) \
+    X(1, bf16_t, 2, V, R, true) X(1, bf16_t, 3, V, R, true) X(1, bf16_t, 4, V, R, true) \
+    X(1, bf16_t, 6, V, R, true) X(1, bf16_t, 8, V, R, true) X(1, bf16_t, 16, V, R, true) \
+    X(1, bf16_t, 32, V, R, true)
+#define ATK_PACKED_NL2(X, V, R) \
+    X(1, bf16_t, 2, V, R, true) X(1, bf16_t, 3, V, R, true) X(1, bf16_t, 4, V, R, true) \
+    X(1, bf16_t, 6, V, R, true) X(1, bf16_t, 8, V, R, true) X(1, bf16_t, 16, V, R, true)
+#define ATK_PACKED_NL4(X, V, R) \
+    X(1, bf16_t, 2, V, R, true) X(1, bf16_t, 3, V, R, true) X(1, bf16_t, 4, V, R, true) \
+    X(1, bf16_t, 6, V, R, true) X(1, bf16_t, 8, V, R, true)
+#define ATK_PACKED_NL8(X, V, R) \
+    X(1, bf16_t, 2, V, R, true) X(1, bf16_t, 3, V, R, true) X(1, bf16_t, 4, V, R, true)
+#define ATK_PACKED_NL16(X, V, R) X(1, bf16_t, 2, V, R, true)
+#define ATK_INSTANCES_BF16_PACKED(X) \
+    ATK_PACKED_NL1(X, 1, 1) ATK_PACKED_NL2(X, 2, 1) ATK_PACKED_NL4(X, 4, 1) \
+    ATK_PACKED_NL8(X, 8, 1) ATK_PACKED_NL16(X, 8, 2)
 
 #define ATK_ALL_INSTANCES(X) \
     ATK_INSTANCES_F32_SMALL(X) ATK_INSTANCES_F32_WIDE(X) ATK_INSTANCES_F32_UNALIGNED(X) \
-    ATK_INSTANCES_BF16_SMALL(X) ATK_INSTANCES_BF16_WIDE(X) ATK_INSTANCES_BF16_UNALIGNED(X)
+    ATK_INSTANCES_BF16_SMALL(X) ATK_INSTANCES_BF16_WIDE(X) ATK_INSTANCES_BF16_UNALIGNED(X) \
+    ATK_INSTANCES_BF16_PACKED(X)

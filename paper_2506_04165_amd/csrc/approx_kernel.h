@@ -58,24 +58,89 @@ struct ApproxParams {
 template <typename T>
 __device__ __forceinline__ T sel(bool c, T a, T b) { return c ? a : b; }
 
-// One list update (Algorithm 1, branch-free, 5K'-2 lane operations).
-template <int KP>
-__device__ __forceinline__ void list_insert(float (&val)[KP], int32_t (&stp)[KP], float x, int32_t step) {
-    bool c[KP];
-#pragma unroll
-    for (int k = 0; k < KP; ++k) c[k] = !(x <= val[k]);
-#pragma unroll
-    for (int k = KP - 1; k >= 1; --k) {
-        const float v0 = sel(c[k], x, val[k]);
-        const int32_t s0 = sel(c[k], step, stp[k]);
-        val[k] = sel(c[k - 1], val[k - 1], v0);
-        stp[k] = sel(c[k - 1], stp[k - 1], s0);
-    }
-    val[0] = sel(c[0], x, val[0]);
-    stp[0] = sel(c[0], step, stp[0]);
+// ---- per-lane K'-lists --------------------------------------------------------------------
+// Two representations of the same thing (the K' greatest elements a register slot has seen,
+// greatest first):
+//
+//  * value + step (any input): the list update is Algorithm 1 restated for the fixed order:
+//    compare the element with every entry (element on the left, so no dependency chain), then
+//    each entry takes its upper neighbour, the element, or itself; 5K'-2 lane operations.
+//    Empty entries are NaN and the test is !(x <= entry), so anything displaces them.
+//
+//  * packed 32-bit key (bf16 rows of at most 65536 elements): ordered 16-bit value in the high
+//    half, 0xFFFF - index in the low half.  Keys are distinct and "greater key" is exactly the
+//    total order, so the update is one max and K'-1 medians-of-three on integers -- K' lane
+//    operations -- and no index needs tracking.  Key 0 is the empty entry.
+template <bool PACKED, int KP, int NL> struct Lists;
+
+// median of three unsigned words.  Written as the instruction itself: the equivalent min/max
+// expression sends the optimizer into exponential work on chains of list updates.
+__device__ __forceinline__ uint32_t med3_u32(uint32_t a, uint32_t b, uint32_t c) {
+    uint32_t d;
+    asm("v_med3_u32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+    return d;
 }
 
-template <typename DT, int KP, int V, int R>
+template <int KP, int NL>
+struct Lists<false, KP, NL> {
+    static constexpr bool exact_bits = true;     // entries keep the stored bit pattern
+    float val[NL][KP];
+    int32_t stp[NL][KP];
+    __device__ __forceinline__ void init() {
+        const float empty = __builtin_nanf("");
+#pragma unroll
+        for (int l = 0; l < NL; ++l)
+#pragma unroll
+            for (int k = 0; k < KP; ++k) { val[l][k] = empty; stp[l][k] = 0; }
+    }
+    __device__ __forceinline__ void insert(int l, float x, int32_t step) {
+        bool c[KP];
+#pragma unroll
+        for (int k = 0; k < KP; ++k) c[k] = !(x <= val[l][k]);
+#pragma unroll
+        for (int k = KP - 1; k >= 1; --k) {
+            const float v0 = sel(c[k], x, val[l][k]);
+            const int32_t s0 = sel(c[k], step, stp[l][k]);
+            val[l][k] = sel(c[k - 1], val[l][k - 1], v0);
+            stp[l][k] = sel(c[k - 1], stp[l][k - 1], s0);
+        }
+        val[l][0] = sel(c[0], x, val[l][0]);
+        stp[l][0] = sel(c[0], step, stp[l][0]);
+    }
+    __device__ __forceinline__ bool valid(int l, int k) const { return val[l][k] == val[l][k]; }
+    __device__ __forceinline__ uint32_t bits(int l, int k) const { return __float_as_uint(val[l][k]); }
+    // e: offset of the slot inside a step, S: elements per step
+    __device__ __forceinline__ uint32_t index(int l, int k, uint32_t S, uint32_t e) const {
+        return (uint32_t)stp[l][k] * S + e;
+    }
+};
+
+template <int KP, int NL>
+struct Lists<true, KP, NL> {
+    static constexpr bool exact_bits = false;    // -0.0 is stored as +0.0
+    uint32_t key[NL][KP];
+    __device__ __forceinline__ void init() {
+#pragma unroll
+        for (int l = 0; l < NL; ++l)
+#pragma unroll
+            for (int k = 0; k < KP; ++k) key[l][k] = 0;
+    }
+    __device__ __forceinline__ void insert(int l, uint32_t x) {
+#pragma unroll
+        for (int k = KP - 1; k >= 1; --k)
+            key[l][k] = med3_u32(key[l][k - 1], key[l][k], x);
+        key[l][0] = max(key[l][0], x);
+    }
+    __device__ __forceinline__ bool valid(int l, int k) const { return key[l][k] != 0; }
+    __device__ __forceinline__ uint32_t bits(int l, int k) const {
+        return bits_from_ordered(key[l][k] & 0xffff0000u);
+    }
+    __device__ __forceinline__ uint32_t index(int l, int k, uint32_t, uint32_t) const {
+        return 0xffffu - (key[l][k] & 0xffffu);
+    }
+};
+
+template <typename DT, int KP, int V, int R, bool PACKED = false>
 struct ApproxKernel {
     static constexpr int NL = V * R;
     static constexpr int DW = (V * elem<DT>::size + 3) / 4;           // dwords per load
@@ -83,6 +148,34 @@ struct ApproxKernel {
     static constexpr int U = U_ < 1 ? 1 : (U_ > 16 ? 16 : U_);        // steps in flight
     using VL = vec_load<DT, V>;
     using vec_t = typename VL::vec_t;
+    static_assert(!PACKED || elem<DT>::size == 2, "packed keys are for 16-bit inputs");
+
+    // Feed the V elements of one load into their lists.
+    __device__ static __forceinline__ void consume(Lists<PACKED, KP, NL>& L, const vec_t& x, int r,
+                                                   int step, uint32_t S, uint32_t slot_off) {
+        if constexpr (!PACKED) {
+#pragma unroll
+            for (int v = 0; v < V; ++v)
+                L.insert(r * V + v, __uint_as_float(VL::bits(x, v)), step);
+        } else {
+            // c = 0xFFFF - (index of element 0 of this load); element v has low half c - v
+            const uint32_t c = 0xffffu - ((uint32_t)step * S + slot_off);
+            const uint32_t c80 = c + 0x80000000u;
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                uint32_t bv;                            // value in the high half, v in the low half
+                if constexpr (sizeof(vec_t) == 2) {
+                    bv = (uint32_t)x << 16;
+                } else {
+                    const uint32_t w = ((const uint32_t*)&x)[v >> 1];
+                    bv = (v & 1) ? ((w & 0xffff0000u) | (uint32_t)v) : ((w << 16) | (uint32_t)v);
+                }
+                const uint32_t t_neg = c - bv;                          // (0 - bits) | (c - v)
+                const uint32_t t_pos = bv + c80 - 2u * (uint32_t)v;     // (bits | 2^31) | (c - v)
+                L.insert(r * V + v, sel((int32_t)bv < 0, t_neg, t_pos));
+            }
+        }
+    }
 
     __device__ static void run(const ApproxParams& p, uint64_t* lds) {
         const int tid = threadIdx.x;
@@ -93,13 +186,8 @@ struct ApproxKernel {
         const char* rowp = (const char*)p.values +
                            (size_t)(row_ok ? row : 0) * p.row_stride * elem<DT>::size;
 
-        float val[NL][KP];
-        int32_t stp[NL][KP];
-        const float empty = __builtin_nanf("");
-#pragma unroll
-        for (int l = 0; l < NL; ++l)
-#pragma unroll
-            for (int k = 0; k < KP; ++k) { val[l][k] = empty; stp[l][k] = 0; }
+        Lists<PACKED, KP, NL> L;
+        L.init();
 
         int off[R];
         bool slot_ok[R];
@@ -140,20 +228,14 @@ struct ApproxKernel {
             for (int u = 0; u < U; ++u)
 #pragma unroll
                 for (int r = 0; r < R; ++r)
-#pragma unroll
-                    for (int v = 0; v < V; ++v)
-                        list_insert<KP>(val[r * V + v], stp[r * V + v],
-                                        __uint_as_float(VL::bits(buf[u][r], v)), s + u);
+                    consume(L, buf[u][r], r, s + u, (uint32_t)p.S, (uint32_t)off[r]);
         }
         for (; s < s_end; ++s) {
             const buffer_rsrc rs = make_rsrc(wg_base + (size_t)s * step_bytes);
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 vec_t x = VL::load(rs, lane_off[r], 0);
-#pragma unroll
-                for (int v = 0; v < V; ++v)
-                    list_insert<KP>(val[r * V + v], stp[r * V + v],
-                                    __uint_as_float(VL::bits(x, v)), s);
+                consume(L, x, r, s, (uint32_t)p.S, (uint32_t)off[r]);
             }
         }
 
@@ -173,16 +255,18 @@ struct ApproxKernel {
 #pragma unroll
                     for (int k = 0; k < KP; ++k) {
                         if (!live || k >= p.Kprime) continue;
-                        const uint32_t n = (uint32_t)stp[r * V + v][k] * (uint32_t)p.S + bucket;
-                        const uint32_t b = __float_as_uint(val[r * V + v][k]);
+                        const int l = r * V + v;
+                        const uint32_t n = L.index(l, k, (uint32_t)p.S, (uint32_t)bucket);
+                        uint32_t b = L.bits(l, k);
                         if (p.mode == 0) {
                             cand[bucket * p.Kprime + k] = make_key(b, n);
                         } else if (p.mode == 2) {
-                            // a segment shorter than K' steps leaves NaN (empty) entries
-                            const float f = val[r * V + v][k];
+                            // a segment shorter than K' steps leaves empty entries
                             const int64_t o = (((int64_t)row * p.nseg + blockIdx.y) * p.Kprime + k) * p.B + bucket;
-                            p.part_keys[o] = (f == f) ? make_key(b, n) : 0;
+                            p.part_keys[o] = L.valid(l, k) ? make_key(b, n) : 0;
                         } else {
+                            if (!Lists<PACKED, KP, NL>::exact_bits && b == 0)
+                                b = elem<DT>::load_bits(rowp, n);       // which zero it was
                             const int64_t o = ((int64_t)row * p.Kprime + k) * p.B + bucket;
                             elem<DT>::store_bits(p.surv_vals, o, b);
                             p.surv_idx[o] = (int32_t)n;
@@ -207,10 +291,9 @@ struct ApproxKernel {
                     const int bucket = e % p.B, owner = e / p.B;
 #pragma unroll
                     for (int k = 0; k < KP; ++k) {
-                        const float f = val[v][k];
-                        const uint32_t n = (uint32_t)stp[v][k] * (uint32_t)p.S + e;
-                        if (f == f)                     // NaN marks an empty entry
-                            part[(size_t)bucket * p.seg + owner * KP + k] = make_key(__float_as_uint(f), n);
+                        const uint32_t n = L.index(v, k, (uint32_t)p.S, (uint32_t)e);
+                        if (L.valid(v, k))
+                            part[(size_t)bucket * p.seg + owner * KP + k] = make_key(L.bits(v, k), n);
                     }
                 }
             }
@@ -261,23 +344,23 @@ struct ApproxKernel {
     }
 };
 
-template <typename DT, int KP, int V, int R>
+template <typename DT, int KP, int V, int R, bool PACKED>
 __global__ void __launch_bounds__(1024) approx_topk_kernel(ApproxParams p) {
     extern __shared__ uint64_t atk_lds[];
-    ApproxKernel<DT, KP, V, R>::run(p, atk_lds);
+    ApproxKernel<DT, KP, V, R, PACKED>::run(p, atk_lds);
 }
 
-// Host-side launcher, one explicit instantiation per supported (dtype, KP, V, R).
-template <typename DT, int KP, int V, int R>
+// Host-side launcher, one explicit instantiation per supported (dtype, KP, V, R, PACKED).
+template <typename DT, int KP, int V, int R, bool PACKED>
 hipError_t launch_approx(const ApproxParams& p, int grid, int block, size_t lds_bytes,
                          hipStream_t stream);
 
-#define ATK_DEFINE_LAUNCH(DT, KP, V, R)                                                         \
+#define ATK_DEFINE_LAUNCH(DT, KP, V, R, PACKED)                                                 \
     template <>                                                                                 \
-    hipError_t launch_approx<DT, KP, V, R>(const ApproxParams& p, int grid, int block,          \
-                                           size_t lds_bytes, hipStream_t stream) {              \
-        allow_large_lds((const void*)approx_topk_kernel<DT, KP, V, R>, lds_bytes);              \
-        hipLaunchKernelGGL((approx_topk_kernel<DT, KP, V, R>),                                  \
+    hipError_t launch_approx<DT, KP, V, R, PACKED>(const ApproxParams& p, int grid, int block,  \
+                                                   size_t lds_bytes, hipStream_t stream) {      \
+        allow_large_lds((const void*)approx_topk_kernel<DT, KP, V, R, PACKED>, lds_bytes);      \
+        hipLaunchKernelGGL((approx_topk_kernel<DT, KP, V, R, PACKED>),                          \
                            dim3(grid, p.mode == 2 ? p.nseg : 1), dim3(block),                   \
                            lds_bytes, stream, p);                                               \
         return hipGetLastError();                                                               \
