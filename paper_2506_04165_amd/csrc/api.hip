@@ -159,7 +159,10 @@ static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, in
         }
     }
     // bf16 rows whose indices fit 16 bits: value and index share one 32-bit key
-    const bool packed_ok = dtype == ATK_BF16 && N <= 65536 && env_int("ATK_NO_PACKED", 0) == 0;
+    // (such variants only exist for the plain fused route with at most 1024 candidates per row)
+    const bool packed_ok = dtype == ATK_BF16 && N <= 65536 && !stage1_only && owners == 1 &&
+                           G >= 64 && pow2_ceil((int64_t)B * Kp) <= kWaveSortMaxKeys &&
+                           env_int("ATK_NO_PACKED", 0) == 0;
     pl.var = find_variant(dtype, KP, NL, packed_ok, aligned_for);
     if (!pl.var) { pl.status = ATK_UNSUPPORTED; return pl; }
     const int V = pl.var->V;
@@ -179,6 +182,7 @@ static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, in
     auto lds_for = [&](int r) {
         size_t cand = 0, aux = 0;
         if (owners > 1) { cand = (size_t)r * pl.Cpad; aux = (size_t)r * B * pl.seg; }
+        else if (pl.var->packed) cand = (size_t)r * pl.Cpad / 2 + 1;     // 32-bit keys
         else if (!stage1_only) cand = (size_t)r * pl.Cpad;
         if (!stage1_only && r == 1 && pl.Cpad > 1024 && aux * 8 < (size_t)kSelectScratchBytes)
             aux = (kSelectScratchBytes + 7) / 8;
@@ -206,7 +210,7 @@ static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, in
 
     // Too few rows to fill the chip: cut every row into segments streamed by separate
     // workgroups (aim: at least 2 waves on each of the 1024 SIMDs), merged by a finishing launch.
-    if (pl.fused && owners == 1 && G >= 64 && rows > 0) {
+    if (pl.fused && owners == 1 && G >= 64 && rows > 0 && !pl.var->packed) {
         const int64_t waves = (int64_t)pl.grid * (pl.block / 64);
         int want = (int)((kTargetWaves + waves - 1) / waves);
         const int max_by_len = pl.nsteps / kMinSegmentSteps;

@@ -39,20 +39,20 @@
     ATK_INSTANCES_NL2(X, 1, bf16_t, 1, 2, false) ATK_INSTANCES_NL4(X, 1, bf16_t, 1, 4, false) \
     ATK_INSTANCES_NL8(X, 1, bf16_t, 1, 8, false) ATK_INSTANCES_NL16(X, 1, bf16_t, 1, 16, false)
 
-// bf16 rows of at most 65536 elements with K' >= 2: lists of packed 32-bit keys
+// bf16 rows of at most 65536 elements: lists of packed 32-bit keys
 #define ATK_PACKED_NL1(X, V, R) \
-    X(1, bf16_t, 2, V, R, true) X(1, bf16_t, 3, V, R, true) X(1, bf16_t, 4, V, R, true) \
+    X(1, bf16_t, 1, V, R, true) X(1, bf16_t, 2, V, R, true) X(1, bf16_t, 3, V, R, true) X(1, bf16_t, 4, V, R, true) \
     X(1, bf16_t, 6, V, R, true) X(1, bf16_t, 8, V, R, true) X(1, bf16_t, 16, V, R, true) \
     X(1, bf16_t, 32, V, R, true)
 #define ATK_PACKED_NL2(X, V, R) \
-    X(1, bf16_t, 2, V, R, true) X(1, bf16_t, 3, V, R, true) X(1, bf16_t, 4, V, R, true) \
+    X(1, bf16_t, 1, V, R, true) X(1, bf16_t, 2, V, R, true) X(1, bf16_t, 3, V, R, true) X(1, bf16_t, 4, V, R, true) \
     X(1, bf16_t, 6, V, R, true) X(1, bf16_t, 8, V, R, true) X(1, bf16_t, 16, V, R, true)
 #define ATK_PACKED_NL4(X, V, R) \
-    X(1, bf16_t, 2, V, R, true) X(1, bf16_t, 3, V, R, true) X(1, bf16_t, 4, V, R, true) \
+    X(1, bf16_t, 1, V, R, true) X(1, bf16_t, 2, V, R, true) X(1, bf16_t, 3, V, R, true) X(1, bf16_t, 4, V, R, true) \
     X(1, bf16_t, 6, V, R, true) X(1, bf16_t, 8, V, R, true)
 #define ATK_PACKED_NL8(X, V, R) \
-    X(1, bf16_t, 2, V, R, true) X(1, bf16_t, 3, V, R, true) X(1, bf16_t, 4, V, R, true)
-#define ATK_PACKED_NL16(X, V, R) X(1, bf16_t, 2, V, R, true)
+    X(1, bf16_t, 1, V, R, true) X(1, bf16_t, 2, V, R, true) X(1, bf16_t, 3, V, R, true) X(1, bf16_t, 4, V, R, true)
+#define ATK_PACKED_NL16(X, V, R) X(1, bf16_t, 1, V, R, true) X(1, bf16_t, 2, V, R, true)
 #define ATK_INSTANCES_BF16_PACKED(X) \
     ATK_PACKED_NL1(X, 1, 1) ATK_PACKED_NL2(X, 2, 1) ATK_PACKED_NL4(X, 4, 1) \
     ATK_PACKED_NL8(X, 8, 1) ATK_PACKED_NL16(X, 8, 2)

@@ -239,8 +239,28 @@ struct ApproxKernel {
             }
         }
 
-        // ---- survivors -> LDS keys (or straight to memory for one-owner mode 1) ---------------
         const int C = p.B * p.Kprime;
+        if constexpr (PACKED) {
+            // packed variants only run fused, one owner per bucket, at most 1024 candidates per
+            // row: the keys go to LDS as they are and the first wavefront of the row's group
+            // sorts them in registers
+            uint32_t* cand32 = (uint32_t*)lds + (size_t)g * p.Cpad;
+            for (int i = C + t; i < p.Cpad; i += p.G) cand32[i] = 0;
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int v = 0; v < V; ++v)
+#pragma unroll
+                    for (int k = 0; k < KP; ++k)
+                        if (slot_ok[r] && k < p.Kprime)
+                            cand32[(off[r] + v) * p.Kprime + k] = row_ok ? L.key[r * V + v][k] : 0;
+            __syncthreads();
+            if (t < kWave && row_ok)
+                wave_sort32_dispatch<DT>(cand32, p.Cpad, p.K, rowp, p.out_vals, p.out_idx, (int64_t)row * p.K);
+            return;
+        }
+
+        // ---- survivors -> LDS keys (or straight to memory for one-owner mode 1) ---------------
         uint64_t* cand = lds + (size_t)g * p.Cpad;                    // per-row stage-2 segment
         if (p.owners == 1) {
             if (p.mode == 0) {

@@ -23,14 +23,14 @@ constexpr int kSelectBins = 2048;
 // a compaction buffer of kWaveSortMaxKeys keys (the histogram aliases it) + control words.
 constexpr int kSelectScratchBytes = kWaveSortMaxKeys * 8 + 128;
 
-template <int R>
+template <int R, typename KeyT = uint64_t>
 struct WaveSort {
     static constexpr int LOGN = (R == 1 ? 6 : R == 2 ? 7 : R == 4 ? 8 : R == 8 ? 9 : 10);
     static_assert(R == 1 || R == 2 || R == 4 || R == 8 || R == 16, "R must be 1,2,4,8,16");
 
     // Element e = lane*R + j lives in k[j] of `lane`.  After the call e is the rank: k[j] of
     // lane l is the (l*R + j)-th greatest key.
-    __device__ static void sort(uint64_t (&k)[R]) {
+    __device__ static void sort(KeyT (&k)[R]) {
         const int lane = __lane_id();
 #pragma unroll
         for (int lk = 1; lk <= LOGN; ++lk) {
@@ -46,10 +46,16 @@ struct WaveSort {
                         // descending block when bit kk of e is clear
                         const bool desc = kk < R ? ((j & kk) == 0)
                                                  : (kk >= kWave * R ? true : ((lane & (kk / R)) == 0));
-                        const uint64_t a = k[j], b = k[j | jj];
-                        const bool sw = (a < b) == desc;
-                        k[j] = sw ? b : a;
-                        k[j | jj] = sw ? a : b;
+                        const KeyT a = k[j], b = k[j | jj];
+                        if constexpr (sizeof(KeyT) == 4) {
+                            const KeyT hi = max(a, b), lo = min(a, b);
+                            k[j] = desc ? hi : lo;
+                            k[j | jj] = desc ? lo : hi;
+                        } else {
+                            const bool sw = (a < b) == desc;
+                            k[j] = sw ? b : a;
+                            k[j | jj] = sw ? a : b;
+                        }
                     }
                 } else {
                     const int m = jj / R;                       // partner lane = lane ^ m
@@ -58,10 +64,15 @@ struct WaveSort {
                     const bool want_max = lower == desc;
 #pragma unroll
                     for (int j = 0; j < R; ++j) {
-                        const uint64_t a = k[j];
-                        const uint64_t b = __shfl_xor((unsigned long long)a, m, kWave);
-                        const bool take = (b > a) == want_max;   // a == b only for empty keys
-                        k[j] = (a == b) ? a : (take ? b : a);
+                        const KeyT a = k[j];
+                        if constexpr (sizeof(KeyT) == 4) {
+                            const KeyT b = __shfl_xor((unsigned)a, m, kWave);
+                            k[j] = want_max ? max(a, b) : min(a, b);
+                        } else {
+                            const KeyT b = __shfl_xor((unsigned long long)a, m, kWave);
+                            const bool take = (b > a) == want_max;   // a == b only for empty keys
+                            k[j] = (a == b) ? a : (take ? b : a);
+                        }
                     }
                 }
             }
@@ -112,6 +123,42 @@ __device__ __noinline__ void wave_sort_dispatch(const uint64_t* keys, int n, int
     else if (n <= 256) wave_sort_from_lds<DT, 4>(keys, n, K, rowp, out_vals, out_idx, out_base);
     else if (n <= 512) wave_sort_from_lds<DT, 8>(keys, n, K, rowp, out_vals, out_idx, out_base);
     else               wave_sort_from_lds<DT, 16>(keys, n, K, rowp, out_vals, out_idx, out_base);
+}
+
+// ---- packed 32-bit keys (bf16 rows of at most 65536 elements) ---------------------------------
+// key = ordered 16-bit value << 16 | (0xFFFF - index); 0 = empty.
+template <typename DT, int R>
+__device__ __forceinline__ void wave_sort32_from_lds(const uint32_t* keys, int n, int K, const void* rowp,
+                                                     void* out_vals, int32_t* out_idx, int64_t out_base) {
+    const int lane = __lane_id();
+    uint32_t k[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        const int i = j * kWave + lane;
+        k[j] = i < n ? keys[i] : 0;
+    }
+    WaveSort<R, uint32_t>::sort(k);
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        const int e = lane * R + j;
+        if (e < K) {
+            const uint32_t idx = 0xffffu - (k[j] & 0xffffu);
+            uint32_t bits = bits_from_ordered(k[j] & 0xffff0000u);
+            if (bits == 0) bits = elem<DT>::load_bits(rowp, idx);      // which zero it was
+            elem<DT>::store_bits(out_vals, out_base + e, bits);
+            out_idx[out_base + e] = (int32_t)idx;
+        }
+    }
+}
+
+template <typename DT>
+__device__ __noinline__ void wave_sort32_dispatch(const uint32_t* keys, int n, int K, const void* rowp,
+                                                  void* out_vals, int32_t* out_idx, int64_t out_base) {
+    if (n <= 64)       wave_sort32_from_lds<DT, 1>(keys, n, K, rowp, out_vals, out_idx, out_base);
+    else if (n <= 128) wave_sort32_from_lds<DT, 2>(keys, n, K, rowp, out_vals, out_idx, out_base);
+    else if (n <= 256) wave_sort32_from_lds<DT, 4>(keys, n, K, rowp, out_vals, out_idx, out_base);
+    else if (n <= 512) wave_sort32_from_lds<DT, 8>(keys, n, K, rowp, out_vals, out_idx, out_base);
+    else               wave_sort32_from_lds<DT, 16>(keys, n, K, rowp, out_vals, out_idx, out_base);
 }
 
 // Histogram pass of the radix selection over keys in LDS.  On return (all threads):
