@@ -184,7 +184,8 @@ static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, in
         if (owners > 1) { cand = (size_t)r * pl.Cpad; aux = (size_t)r * B * pl.seg; }
         else if (pl.var->packed) cand = (size_t)r * pl.Cpad / 2 + 1;     // 32-bit keys
         else if (!stage1_only) cand = (size_t)r * pl.Cpad;
-        if (!stage1_only && r == 1 && pl.Cpad > 1024 && aux * 8 < (size_t)kSelectScratchBytes)
+        if (!stage1_only && !pl.var->packed && r == 1 && pl.Cpad > 256 &&
+            aux * 8 < (size_t)kSelectScratchBytes)
             aux = (kSelectScratchBytes + 7) / 8;
         return (cand + aux) * 8;
     };
@@ -195,7 +196,7 @@ static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, in
     pl.rows_per_wg = rpw;
     pl.lds = lds_for(rpw);
     pl.aux_offset = (size_t)rpw * pl.Cpad;
-    pl.tail = wave_tail ? 1 : (rpw == 1 ? 2 : 0);
+    pl.tail = rpw == 1 ? 2 : (wave_tail ? 1 : 0);
     pl.block = G * rpw;
     pl.grid = (int)((rows + rpw - 1) / rpw);
     pl.fused = !stage1_only && pl.lds <= kLdsBudget;

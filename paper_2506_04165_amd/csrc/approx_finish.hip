@@ -48,7 +48,7 @@ __global__ void __launch_bounds__(1024) approx_finish_kernel(FinishParams p) {
 
 template <typename DT>
 hipError_t launch_for(const FinishParams& p, int KP, int threads, hipStream_t stream) {
-    const size_t lds = (size_t)p.Cpad * 8 + (p.Cpad > kWaveSortMaxKeys ? kSelectScratchBytes : 0);
+    const size_t lds = (size_t)p.Cpad * 8 + (p.Cpad > 256 ? kSelectScratchBytes : 0);
     const dim3 grid(p.rows), block(threads);
     switch (KP) {
 #define ATK_CASE(N) case N:                                                                       \

@@ -144,8 +144,14 @@ template <typename DT, int KP, int V, int R, bool PACKED = false>
 struct ApproxKernel {
     static constexpr int NL = V * R;
     static constexpr int DW = (V * elem<DT>::size + 3) / 4;           // dwords per load
-    static constexpr int U_ = 32 / (R * DW);
-    static constexpr int U = U_ < 1 ? 1 : (U_ > 16 ? 16 : U_);        // steps in flight
+#ifndef ATK_UMAX
+#define ATK_UMAX 16
+#endif
+#ifndef ATK_UDW
+#define ATK_UDW 32
+#endif
+    static constexpr int U_ = ATK_UDW / (R * DW);
+    static constexpr int U = U_ < 1 ? 1 : (U_ > ATK_UMAX ? ATK_UMAX : U_);        // steps in flight
     using VL = vec_load<DT, V>;
     using vec_t = typename VL::vec_t;
     static_assert(!PACKED || elem<DT>::size == 2, "packed keys are for 16-bit inputs");

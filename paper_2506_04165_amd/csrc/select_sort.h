@@ -19,7 +19,7 @@ namespace atk {
 constexpr int kWaveSortMaxR = 16;                       // up to 1024 keys per wavefront
 constexpr int kWaveSortMaxKeys = kWave * kWaveSortMaxR;
 constexpr int kSelectBins = 2048;
-// LDS scratch wg_topk_from_lds needs next to the keys when n > kWaveSortMaxKeys:
+// LDS scratch wg_topk_from_lds needs next to the keys when n > 256:
 // a compaction buffer of kWaveSortMaxKeys keys (the histogram aliases it) + control words.
 constexpr int kSelectScratchBytes = kWaveSortMaxKeys * 8 + 128;
 
@@ -218,14 +218,15 @@ __device__ __forceinline__ void lds_select_digit(const uint64_t* keys, int n, ui
 
 // Top-K (descending) of the n keys in LDS `keys` (n a power of two, key 0 = empty, at least K
 // real keys), written decoded to out_*[out_base + 0..K).  Called by every thread of the
-// workgroup; `scratch` is kSelectScratchBytes of LDS (unused when n <= kWaveSortMaxKeys).
+// workgroup; `scratch` is kSelectScratchBytes of LDS (unused when n <= 256).
 // The keys array is used as working storage.
 template <typename DT>
 __device__ __forceinline__ void wg_topk_from_lds(uint64_t* keys, int n, int K, void* scratch,
                                                  const void* rowp, void* out_vals,
                                                  int32_t* out_idx, int64_t out_base) {
     const int tid = threadIdx.x, T = blockDim.x;
-    if (n <= kWaveSortMaxKeys) {
+    // few keys, or most of them wanted: sort them all
+    if (n <= 256 || (n <= kWaveSortMaxKeys && 4 * K > n)) {
         if (tid < kWave) wave_sort_dispatch<DT>(keys, n, K, rowp, out_vals, out_idx, out_base);
         return;
     }
@@ -236,16 +237,19 @@ __device__ __forceinline__ void wg_topk_from_lds(uint64_t* keys, int n, int K, v
         uint64_t prefix = 0, mask = 0;
         int need = K, certain = 0;
         bool fits = false;
-        // leading value bits: 11, 11, 10 (the low word of a key is the index)
-        const int shifts[3] = {53, 42, 32}, widths[3] = {11, 11, 10};
-        for (int d = 0; d < 3 && !fits; ++d) {
+        // value bits first (11, 11, 10), then -- only when ties leave too many candidates --
+        // the index bits, so that the lowest indices win
+        const int shifts[6] = {53, 42, 32, 21, 10, 0}, widths[6] = {11, 11, 10, 11, 11, 10};
+        for (int d = 0; d < 6 && !fits; ++d) {
             uint32_t digit, above, count;
             lds_select_digit(keys, n, prefix, mask, shifts[d], widths[d], need, hist, ctl, digit, above, count);
             certain += (int)above;
             need -= (int)above;
             prefix |= (uint64_t)digit << shifts[d];
             mask |= (uint64_t)((1u << widths[d]) - 1u) << shifts[d];
-            fits = certain + (int)count <= kWaveSortMaxKeys;
+            // stop when members + candidates fit one wave sort; prefer a sort of at most 2K keys
+            fits = certain + (int)count <= kWaveSortMaxKeys &&
+                   (certain + (int)count <= 2 * K + 64 || d >= 2);
         }
         if (fits) {
             if (tid == 0) ctl[3] = 0;
