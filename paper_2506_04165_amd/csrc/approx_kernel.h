@@ -68,9 +68,9 @@ __device__ __forceinline__ T sel(bool c, T a, T b) { return c ? a : b; }
 //    Empty entries are NaN and the test is !(x <= entry), so anything displaces them.
 //
 //  * packed 32-bit key (bf16 rows of at most 65536 elements): ordered 16-bit value in the high
-//    half, 0xFFFF - index in the low half.  Keys are distinct and "greater key" is exactly the
-//    total order, so the update is one max and K'-1 medians-of-three on integers -- K' lane
-//    operations -- and no index needs tracking.  Key 0 is the empty entry.
+//    half, 0xFFFF - step in the low half.  Within one list keys are distinct and "greater key"
+//    is exactly the total order, so the update is one max and K'-1 medians-of-three on integers
+//    -- K' lane operations -- and no index needs tracking.  Key 0 is the empty entry.
 template <bool PACKED, int KP, int NL> struct Lists;
 
 // median of three unsigned words.  Written as the instruction itself: the equivalent min/max
@@ -135,8 +135,9 @@ struct Lists<true, KP, NL> {
     __device__ __forceinline__ uint32_t bits(int l, int k) const {
         return bits_from_ordered(key[l][k] & 0xffff0000u);
     }
-    __device__ __forceinline__ uint32_t index(int l, int k, uint32_t, uint32_t) const {
-        return 0xffffu - (key[l][k] & 0xffffu);
+    // the low half of a key is 0xFFFF - step; e: offset of the slot inside a step
+    __device__ __forceinline__ uint32_t index(int l, int k, uint32_t S, uint32_t e) const {
+        return (0xffffu - (key[l][k] & 0xffffu)) * S + e;
     }
 };
 
@@ -158,27 +159,33 @@ struct ApproxKernel {
 
     // Feed the V elements of one load into their lists.
     __device__ static __forceinline__ void consume(Lists<PACKED, KP, NL>& L, const vec_t& x, int r,
-                                                   int step, uint32_t S, uint32_t slot_off) {
+                                                   int step) {
         if constexpr (!PACKED) {
 #pragma unroll
             for (int v = 0; v < V; ++v)
                 L.insert(r * V + v, __uint_as_float(VL::bits(x, v)), step);
         } else {
-            // c = 0xFFFF - (index of element 0 of this load); element v has low half c - v
-            const uint32_t c = 0xffffu - ((uint32_t)step * S + slot_off);
-            const uint32_t c80 = c + 0x80000000u;
+            // Low half of every key of this step: 0xFFFF - step.  All elements of one list share
+            // the slot, so the step alone orders them; the position is rebuilt from it later.
+            uint32_t low;
+            asm("v_mov_b32 %0, %1" : "=v"(low) : "s"(0xffffu - (uint32_t)step));
+            if constexpr (sizeof(vec_t) == 2) {
+                L.insert(r * V, ordered_from_bits((uint32_t)x << 16) | low);
+            } else {
+                typedef short short2_t __attribute__((ext_vector_type(2)));
+                typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
 #pragma unroll
-            for (int v = 0; v < V; ++v) {
-                uint32_t bv;                            // value in the high half, v in the low half
-                if constexpr (sizeof(vec_t) == 2) {
-                    bv = (uint32_t)x << 16;
-                } else {
-                    const uint32_t w = ((const uint32_t*)&x)[v >> 1];
-                    bv = (v & 1) ? ((w & 0xffff0000u) | (uint32_t)v) : ((w << 16) | (uint32_t)v);
+                for (int d = 0; d < V / 2; ++d) {
+                    // two bf16 per dword: ordered 16-bit images of both with packed 16-bit ops
+                    // (sign fill, flip, and +1 on negatives so that -0.0 lands on +0.0's image)
+                    const uint32_t w = ((const uint32_t*)&x)[d];
+                    const uint32_t sg = __builtin_bit_cast(uint32_t, __builtin_bit_cast(short2_t, w) >> (short)15);
+                    const uint32_t fl = w ^ (sg | 0x80008000u);
+                    const uint32_t o = __builtin_bit_cast(
+                        uint32_t, __builtin_bit_cast(ushort2_t, fl) - __builtin_bit_cast(ushort2_t, sg));
+                    L.insert(r * V + 2 * d, (o << 16) | low);
+                    L.insert(r * V + 2 * d + 1, (o & 0xffff0000u) | low);
                 }
-                const uint32_t t_neg = c - bv;                          // (0 - bits) | (c - v)
-                const uint32_t t_pos = bv + c80 - 2u * (uint32_t)v;     // (bits | 2^31) | (c - v)
-                L.insert(r * V + v, sel((int32_t)bv < 0, t_neg, t_pos));
             }
         }
     }
@@ -234,14 +241,14 @@ struct ApproxKernel {
             for (int u = 0; u < U; ++u)
 #pragma unroll
                 for (int r = 0; r < R; ++r)
-                    consume(L, buf[u][r], r, s + u, (uint32_t)p.S, (uint32_t)off[r]);
+                    consume(L, buf[u][r], r, s + u);
         }
         for (; s < s_end; ++s) {
             const buffer_rsrc rs = make_rsrc(wg_base + (size_t)s * step_bytes);
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 vec_t x = VL::load(rs, lane_off[r], 0);
-                consume(L, x, r, s, (uint32_t)p.S, (uint32_t)off[r]);
+                consume(L, x, r, s);
             }
         }
 
@@ -258,8 +265,12 @@ struct ApproxKernel {
                 for (int v = 0; v < V; ++v)
 #pragma unroll
                     for (int k = 0; k < KP; ++k)
-                        if (slot_ok[r] && k < p.Kprime)
-                            cand32[(off[r] + v) * p.Kprime + k] = row_ok ? L.key[r * V + v][k] : 0;
+                        if (slot_ok[r] && k < p.Kprime) {
+                            // same value half, low half now 0xFFFF - position in the row
+                            const uint32_t n = L.index(r * V + v, k, (uint32_t)p.S, (uint32_t)(off[r] + v));
+                            const uint32_t key = (L.key[r * V + v][k] & 0xffff0000u) | (0xffffu - n);
+                            cand32[(off[r] + v) * p.Kprime + k] = row_ok ? key : 0;
+                        }
             __syncthreads();
             if (t < kWave && row_ok)
                 wave_sort32_dispatch<DT>(cand32, p.Cpad, p.K, rowp, p.out_vals, p.out_idx, (int64_t)row * p.K);
