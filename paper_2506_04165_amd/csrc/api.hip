@@ -261,7 +261,7 @@ static int hip_fail(hipError_t e) {
 }
 
 static int exact_threads(int64_t N) {
-    int t = pow2_ceil((N + 15) / 16);
+    int t = pow2_ceil((N + 63) / 64);     // about 64 elements per lane, more lanes for long rows
     if (t < 64) t = 64;
     if (t > 1024) t = 1024;
     return t;

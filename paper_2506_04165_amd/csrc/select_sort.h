@@ -161,24 +161,16 @@ __device__ __noinline__ void wave_sort32_dispatch(const uint32_t* keys, int n, i
     else               wave_sort32_from_lds<DT, 16>(keys, n, K, rowp, out_vals, out_idx, out_base);
 }
 
-// Histogram pass of the radix selection over keys in LDS.  On return (all threads):
-//   digit   the value of the `bits`-wide digit at `shift` that holds the need-th greatest key
-//           among the keys matching (prefix, mask),
-//   above   how many matching keys have a greater digit (certain members),
-//   count   how many matching keys have exactly that digit.
-// hist: kSelectBins words, ctl: 32 words of LDS scratch.  Contains barriers.
-__device__ __forceinline__ void lds_select_digit(const uint64_t* keys, int n, uint64_t prefix,
-                                                 uint64_t mask, int shift, int bits, int need,
-                                                 uint32_t* hist, uint32_t* ctl,
-                                                 uint32_t& digit, uint32_t& above, uint32_t& count) {
+// Walk a finished histogram from the top bin down.  On return (all threads):
+//   digit   the bin in which the running count reaches `need`,
+//   above   the total of the bins above it,
+//   count   the content of that bin.
+// Bins that no key of interest can fall into may hold anything as long as the bins from the
+// top down to the answer are exact.  hist: kSelectBins words, ctl: 32 words of LDS scratch.
+// Starts and ends with a barrier.
+__device__ __forceinline__ void hist_find_digit(const uint32_t* hist, uint32_t* ctl, int need,
+                                                uint32_t& digit, uint32_t& above, uint32_t& count) {
     const int tid = threadIdx.x, T = blockDim.x;
-    const uint32_t dmask = (1u << bits) - 1u;
-    for (int i = tid; i < kSelectBins; i += T) hist[i] = 0;
-    __syncthreads();
-    for (int i = tid; i < n; i += T) {
-        const uint64_t key = keys[i];
-        if (key != 0 && (key & mask) == prefix) atomicAdd(&hist[(uint32_t)(key >> shift) & dmask], 1u);
-    }
     __syncthreads();
     // suffix sums over bins: thread t owns bins [t*bpt, (t+1)*bpt)
     const int bpt = (kSelectBins + T - 1) / T;
@@ -214,6 +206,23 @@ __device__ __forceinline__ void lds_select_digit(const uint64_t* keys, int n, ui
     __syncthreads();
     digit = ctl[0]; above = ctl[1]; count = ctl[2];
     __syncthreads();
+}
+
+// Histogram pass of the radix selection over keys in LDS: the `bits`-wide digit at `shift` of
+// the keys matching (prefix, mask) is counted, then hist_find_digit answers.
+__device__ __forceinline__ void lds_select_digit(const uint64_t* keys, int n, uint64_t prefix,
+                                                 uint64_t mask, int shift, int bits, int need,
+                                                 uint32_t* hist, uint32_t* ctl,
+                                                 uint32_t& digit, uint32_t& above, uint32_t& count) {
+    const int tid = threadIdx.x, T = blockDim.x;
+    const uint32_t dmask = (1u << bits) - 1u;
+    for (int i = tid; i < kSelectBins; i += T) hist[i] = 0;
+    __syncthreads();
+    for (int i = tid; i < n; i += T) {
+        const uint64_t key = keys[i];
+        if (key != 0 && (key & mask) == prefix) atomicAdd(&hist[(uint32_t)(key >> shift) & dmask], 1u);
+    }
+    hist_find_digit(hist, ctl, need, digit, above, count);
 }
 
 // Top-K (descending) of the n keys in LDS `keys` (n a power of two, key 0 = empty, at least K

@@ -4,14 +4,19 @@
 // launch of the unfused path (Section 6.1 Step 4 on survivors that do not fit in LDS).
 //
 // Per row:
-//   1. histogram one digit of the keys that still match the known prefix (LDS atomics);
-//   2. walk the histogram from the top: digits above the one where the running count
-//      reaches the number still needed are certain members, that digit extends the prefix;
-//   3. stop as soon as (certain members + keys matching the prefix) fit the LDS buffer --
-//      for continuous data that is after the first digit -- otherwise take the next digit
-//      (value bits first, then index bits, so ties end up resolved toward the lower index);
-//   4. one more pass gathers certain members and prefix matches into LDS, where the same
+//   1. first pass: histogram of the leading 11 value bits (LDS atomics).  The row is taken in
+//      chunks; after the first chunk, and then at doubling distances, the histogram so far gives
+//      a lower bound (the digit at which K keys have already been seen): keys below it can no
+//      longer matter and skip the atomic, which removes nearly all of them and with them the
+//      bank conflicts of a peaked distribution;
+//   2. walk the histogram from the top: digits above the one where the running count reaches K
+//      are certain members, that digit becomes the prefix;
+//   3. while (certain members + keys matching the prefix) exceed the LDS buffer -- only with
+//      massive ties -- take the next digit (value bits first, then index bits, so ties resolve
+//      toward the lower index);
+//   4. a last pass gathers certain members and prefix matches into LDS, where the same
 //      selection-then-wave-sort as in the fused kernel's stage 2 picks and orders the K.
+// Two passes over the row for ordinary data: at most half of the HBM roofline by design.
 #include "atk_device.h"
 #include "select_sort.h"
 #include "topk_exact.h"
@@ -20,96 +25,133 @@ namespace atk {
 
 namespace {
 
-constexpr int kBins = 2048;
 constexpr int kNumDigits = 6;
 __device__ __constant__ int kDigitShift[kNumDigits] = {53, 42, 32, 21, 10, 0};
 __device__ __constant__ int kDigitBits[kNumDigits] = {11, 11, 10, 11, 11, 10};
 
-template <typename DT, bool PAYLOAD>
-__device__ __forceinline__ uint64_t key_at(const void* rowp, const int32_t* payload, int n) {
-    const uint32_t b = elem<DT>::load_bits(rowp, n);
-    const uint32_t idx = PAYLOAD ? (uint32_t)payload[n] : (uint32_t)n;
-    return make_key(b, idx);
+// Calls fn(bits, n) for every element n of the row: 16-byte vector loads when the row allows
+// (no payload, base and stride 16-byte aligned), element loads otherwise.  All threads take part.
+template <typename DT, bool VEC, typename F>
+__device__ __forceinline__ void for_each_element(const char* rowp, int begin, int end, F&& fn) {
+    const int tid = threadIdx.x, T = blockDim.x;
+    constexpr int VE = 16 / elem<DT>::size;
+    if constexpr (VEC) {
+        // begin is a multiple of VE
+        const int nvec = (end - begin) / VE;
+        const uint4* vp = (const uint4*)(rowp + (size_t)begin * elem<DT>::size);
+        constexpr int UN = 4;
+        int i = tid;
+        for (; i + (UN - 1) * T < nvec; i += UN * T) {
+            uint4 v[UN];
+#pragma unroll
+            for (int u = 0; u < UN; ++u) v[u] = vp[i + u * T];
+#pragma unroll
+            for (int u = 0; u < UN; ++u) {
+                const uint32_t* w = (const uint32_t*)&v[u];
+#pragma unroll
+                for (int e = 0; e < VE; ++e) {
+                    uint32_t b;
+                    if constexpr (elem<DT>::size == 4) b = w[e];
+                    else b = (e & 1) ? (w[e >> 1] & 0xffff0000u) : (w[e >> 1] << 16);
+                    fn(b, begin + (i + u * T) * VE + e);
+                }
+            }
+        }
+        for (; i < nvec; i += T) {
+            const uint4 v = vp[i];
+            const uint32_t* w = (const uint32_t*)&v;
+#pragma unroll
+            for (int e = 0; e < VE; ++e) {
+                uint32_t b;
+                if constexpr (elem<DT>::size == 4) b = w[e];
+                else b = (e & 1) ? (w[e >> 1] & 0xffff0000u) : (w[e >> 1] << 16);
+                fn(b, begin + i * VE + e);
+            }
+        }
+        for (int n = begin + nvec * VE + tid; n < end; n += T) fn(elem<DT>::load_bits(rowp, n), n);
+    } else {
+        for (int n = begin + tid; n < end; n += T) fn(elem<DT>::load_bits(rowp, n), n);
+    }
 }
 
-template <typename DT, bool PAYLOAD>
+template <typename DT, bool PAYLOAD, bool VEC>
 __global__ void __launch_bounds__(1024) topk_exact_kernel(TopkParams p) {
     extern __shared__ uint64_t lds64[];
     // layout: [0, cap) key buffer (the histogram aliases its start), scratch of the final
     // selection, then 32 control words
     uint32_t* hist = (uint32_t*)lds64;
     void* scratch = lds64 + p.cap;
-    uint32_t* ctl = (uint32_t*)((char*)scratch + kSelectScratchBytes);   // 0: digit  1: certain  2: count  3: fill  4..: wave sums
+    uint32_t* ctl = (uint32_t*)((char*)scratch + kSelectScratchBytes);   // 3: fill  4..: wave sums
     const int tid = threadIdx.x, T = blockDim.x;
     const int row = blockIdx.x;
     const char* rowp = (const char*)p.values + (size_t)row * p.row_stride * elem<DT>::size;
     const int32_t* payload = PAYLOAD ? p.payload + (size_t)row * p.row_stride : nullptr;
     const int N = p.N;
+    auto index_of = [&](int n) -> uint32_t { return PAYLOAD ? (uint32_t)payload[n] : (uint32_t)n; };
 
     uint64_t prefix = 0, mask = 0;
     int need = p.K;          // members still to be taken from the keys matching the prefix
     int certain = 0;         // members already known (keys above the prefix)
 
-    for (int d = 0; d < kNumDigits; ++d) {
-        const int shift = kDigitShift[d];
-        const uint32_t dmask = (1u << kDigitBits[d]) - 1u;
-        for (int i = tid; i < kBins; i += T) hist[i] = 0;
+    // ---- digit 0 with a rising lower bound ------------------------------------------------------
+    {
+        for (int i = tid; i < kSelectBins; i += T) hist[i] = 0;
         __syncthreads();
-        for (int n = tid; n < N; n += T) {
-            const uint64_t key = key_at<DT, PAYLOAD>(rowp, payload, n);
-            if ((key & mask) == prefix) atomicAdd(&hist[(uint32_t)(key >> shift) & dmask], 1u);
-        }
-        __syncthreads();
-        // suffix sums over bins: thread t owns bins [t*bpt, (t+1)*bpt)
-        const int bpt = kBins / T > 0 ? kBins / T : 1;
-        uint32_t mine = 0;
-        if (tid * bpt < kBins)
-            for (int i = 0; i < bpt; ++i) mine += hist[tid * bpt + i];
-        // inclusive suffix scan inside the wave (lane l gets the sum over lanes >= l)
-        const int lane = tid & (kWave - 1), wave = tid >> 6;
-        uint32_t suf = mine;
-        for (int o = 1; o < kWave; o <<= 1) {
-            const uint32_t other = __shfl_down(suf, o, kWave);
-            if (lane + o < kWave) suf += other;
-        }
-        if (lane == 0) ctl[4 + wave] = suf;
-        __syncthreads();
-        uint32_t above = 0;                          // sum over waves after mine
-        for (int w = wave + 1; w < (T >> 6); ++w) above += ctl[4 + w];
-        const uint32_t incl = suf + above, excl = incl - mine;
-        if (tid * bpt < kBins && excl < (uint32_t)need && incl >= (uint32_t)need) {
-            uint32_t run = excl;
-            for (int i = bpt - 1; i >= 0; --i) {
-                const uint32_t c = hist[tid * bpt + i];
-                if (run + c >= (uint32_t)need) {
-                    ctl[0] = (uint32_t)(tid * bpt + i);
-                    ctl[1] = run;                   // keys in higher digits: certain members
-                    ctl[2] = c;
-                    break;
-                }
-                run += c;
+        constexpr int VE = 16 / elem<DT>::size;
+        const int chunk = T * VE * 2;
+        uint32_t dmin = 0;
+        int next_update = chunk;
+        for (int base = 0; base < N; base += chunk) {
+            const int end = min(N, base + chunk);
+            for_each_element<DT, VEC>(rowp, base, end, [&](uint32_t b, int) {
+                const uint32_t d = ordered_from_bits(b) >> 21;
+                if (d >= dmin) atomicAdd(&hist[d], 1u);
+            });
+            if (end >= next_update && end < N) {
+                uint32_t digit, above, count;
+                hist_find_digit(hist, ctl, p.K, digit, above, count);
+                dmin = digit;                    // K keys at or above this digit exist already
+                next_update *= 2;
             }
         }
-        __syncthreads();
-        const uint32_t digit = ctl[0], more = ctl[1], count = ctl[2];
-        __syncthreads();
-        certain += (int)more;
-        need -= (int)more;
-        prefix |= (uint64_t)digit << shift;
-        mask |= (uint64_t)dmask << shift;
-        if (certain + (int)count <= p.cap) break;
-    }
-
-    // gather certain members and prefix matches
-    if (tid == 0) ctl[3] = 0;
-    __syncthreads();
-    for (int n = tid; n < N; n += T) {
-        const uint64_t key = key_at<DT, PAYLOAD>(rowp, payload, n);
-        if ((key & mask) >= prefix) {
-            const uint32_t slot = atomicAdd(&ctl[3], 1u);
-            if (slot < (uint32_t)p.cap) lds64[slot] = key;   // always true; keeps a logic slip memory safe
+        uint32_t digit, above, count;
+        hist_find_digit(hist, ctl, need, digit, above, count);
+        certain += (int)above;
+        need -= (int)above;
+        prefix = (uint64_t)digit << 53;
+        mask = (uint64_t)0x7ff << 53;
+        // ---- further digits, only when ties leave more than the buffer holds ---------------
+        for (int d = 1; d < kNumDigits && certain + (int)count > p.cap; ++d) {
+            const int shift = kDigitShift[d];
+            const uint32_t dmask = (1u << kDigitBits[d]) - 1u;
+            for (int i = tid; i < kSelectBins; i += T) hist[i] = 0;
+            __syncthreads();
+            for_each_element<DT, VEC>(rowp, 0, N, [&](uint32_t b, int n) {
+                const uint64_t key = make_key(b, index_of(n));
+                if ((key & mask) == prefix) atomicAdd(&hist[(uint32_t)(key >> shift) & dmask], 1u);
+            });
+            hist_find_digit(hist, ctl, need, digit, above, count);
+            certain += (int)above;
+            need -= (int)above;
+            prefix |= (uint64_t)digit << shift;
+            mask |= (uint64_t)dmask << shift;
         }
     }
+
+    // ---- gather certain members and prefix matches ----------------------------------------------
+    if (tid == 0) ctl[3] = 0;
+    __syncthreads();
+    for_each_element<DT, VEC>(rowp, 0, N, [&](uint32_t b, int n) {
+        // cheap reject on the value word before the full key is built
+        const uint32_t ord = ordered_from_bits(b);
+        if (ord >= (uint32_t)(prefix >> 32)) {
+            const uint64_t key = ((uint64_t)ord << 32) | (uint32_t)(~index_of(n));
+            if ((key & mask) >= prefix) {
+                const uint32_t slot = atomicAdd(&ctl[3], 1u);
+                if (slot < (uint32_t)p.cap) lds64[slot] = key;   // always true; keeps a slip memory safe
+            }
+        }
+    });
     __syncthreads();
     const int total = min((int)ctl[3], p.cap);
     const int n2 = next_pow2(total);
@@ -135,20 +177,22 @@ __global__ void __launch_bounds__(1024) topk_exact_kernel(TopkParams p) {
     }
 }
 
+template <typename DT>
+hipError_t launch_for(const TopkParams& p, int threads, hipStream_t stream) {
+    const size_t lds = (size_t)p.cap * 8 + kSelectScratchBytes + 32 * 4;
+    const dim3 grid(p.rows), block(threads);
+    const bool vec = p.payload == nullptr && ((uintptr_t)p.values % 16 == 0) &&
+                     ((p.row_stride * elem<DT>::size) % 16 == 0);
+    if (p.payload) hipLaunchKernelGGL((topk_exact_kernel<DT, true, false>), grid, block, lds, stream, p);
+    else if (vec)  hipLaunchKernelGGL((topk_exact_kernel<DT, false, true>), grid, block, lds, stream, p);
+    else           hipLaunchKernelGGL((topk_exact_kernel<DT, false, false>), grid, block, lds, stream, p);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_topk_exact(const TopkParams& p, int dtype, int threads, hipStream_t stream) {
-    const size_t lds = (size_t)p.cap * 8 + kSelectScratchBytes + 32 * 4;
-    const dim3 grid(p.rows), block(threads);
-    const bool payload = p.payload != nullptr;
-    if (dtype == 0) {
-        if (payload) hipLaunchKernelGGL((topk_exact_kernel<float, true>), grid, block, lds, stream, p);
-        else         hipLaunchKernelGGL((topk_exact_kernel<float, false>), grid, block, lds, stream, p);
-    } else {
-        if (payload) hipLaunchKernelGGL((topk_exact_kernel<bf16_t, true>), grid, block, lds, stream, p);
-        else         hipLaunchKernelGGL((topk_exact_kernel<bf16_t, false>), grid, block, lds, stream, p);
-    }
-    return hipGetLastError();
+    return dtype == 0 ? launch_for<float>(p, threads, stream) : launch_for<bf16_t>(p, threads, stream);
 }
 
 }  // namespace atk

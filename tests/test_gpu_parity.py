@@ -152,6 +152,21 @@ def test_bucket_counts_that_are_not_powers_of_two_and_tiny_rows(atk, N, B, Kp, K
     check_approx(atk, xb, K, Kp, B)
 
 
+@pytest.mark.parametrize("N,B,Kp,K", [(65536, 256, 4, 300), (65536, 1024, 1, 1000), (65536, 64, 16, 1024),
+                                      (65536, 512, 2, 512), (131072, 256, 4, 300), (32768, 128, 6, 700)])
+def test_bf16_packed_key_limits(atk, N, B, Kp, K):
+    # rows of up to 65536 bf16 elements run on packed 32-bit keys (positions 0..65535 must all
+    # be representable), longer rows on the general lists; ties are dense in bf16
+    st, text = atk.describe_plan(torch.bfloat16, 5, N, K, Kp, B)
+    assert st == atk.OK and (" packed" in text) == (N <= 65536), text
+    x = workloads.gaussian(5, N, seed=500 + B + Kp, dtype=torch.bfloat16)
+    x[0, N - 1] = 100.0        # the very last position must be able to win
+    x[1, :] = 1.5              # one value everywhere: the index alone decides
+    check_approx(atk, x, K, Kp, B)
+    z = workloads.heavy_ties(3, N, seed=501, symbols=5).to(torch.bfloat16)
+    check_approx(atk, z, K, Kp, B)
+
+
 def test_kprime_equals_k_and_single_bucket_are_exact(atk):
     x = workloads.gaussian(4, 8192, seed=7)
     for K, Kp, B in [(32, 32, 64), (32, 32, 1), (20, 20, 256), (100, 100, 64), (100, 100, 1),
