@@ -344,7 +344,7 @@ struct ApproxKernel {
                 } else if (row_ok) {
                     const uint32_t n = key_index(key);
                     uint32_t b = key_value_bits(key);
-                    if (b == 0) b = elem<DT>::load_bits(rowp, n);      // which zero it was
+                    if (b == 0 && key != 0) b = elem<DT>::load_bits(rowp, n);   // which zero it was
                     const int64_t o = ((int64_t)row * p.Kprime + k) * p.B + bucket;
                     elem<DT>::store_bits(p.surv_vals, o, b);
                     p.surv_idx[o] = (int32_t)n;
@@ -373,7 +373,7 @@ struct ApproxKernel {
                 const uint64_t key = cand[i];
                 const uint32_t n = key_index(key);
                 uint32_t b = key_value_bits(key);
-                if (b == 0) b = elem<DT>::load_bits(rowp, n);          // which zero it was
+                if (b == 0 && key != 0) b = elem<DT>::load_bits(rowp, n);       // which zero it was
                 elem<DT>::store_bits(p.out_vals, (int64_t)row * p.K + i, b);
                 p.out_idx[(int64_t)row * p.K + i] = (int32_t)n;
             }

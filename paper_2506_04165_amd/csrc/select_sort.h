@@ -91,7 +91,7 @@ __device__ __forceinline__ void wave_write_topk(const uint64_t (&k)[R], int K, c
         if (e < K) {
             const uint32_t n = key_index(k[j]);
             uint32_t bits = key_value_bits(k[j]);
-            if (bits == 0) bits = elem<DT>::load_bits(rowp, n);      // which zero it was
+            if (bits == 0 && k[j] != 0) bits = elem<DT>::load_bits(rowp, n);   // which zero it was
             elem<DT>::store_bits(out_vals, out_base + e, bits);
             out_idx[out_base + e] = (int32_t)n;
         }
@@ -144,7 +144,7 @@ __device__ __forceinline__ void wave_sort32_from_lds(const uint32_t* keys, int n
         if (e < K) {
             const uint32_t idx = 0xffffu - (k[j] & 0xffffu);
             uint32_t bits = bits_from_ordered(k[j] & 0xffff0000u);
-            if (bits == 0) bits = elem<DT>::load_bits(rowp, idx);      // which zero it was
+            if (bits == 0 && k[j] != 0) bits = elem<DT>::load_bits(rowp, idx);   // which zero it was
             elem<DT>::store_bits(out_vals, out_base + e, bits);
             out_idx[out_base + e] = (int32_t)idx;
         }
@@ -171,6 +171,7 @@ __device__ __noinline__ void wave_sort32_dispatch(const uint32_t* keys, int n, i
 __device__ __forceinline__ void hist_find_digit(const uint32_t* hist, uint32_t* ctl, int need,
                                                 uint32_t& digit, uint32_t& above, uint32_t& count) {
     const int tid = threadIdx.x, T = blockDim.x;
+    if (tid == 0) { ctl[0] = 0; ctl[1] = 0; ctl[2] = 0; }   // answer if fewer than `need` were counted
     __syncthreads();
     // suffix sums over bins: thread t owns bins [t*bpt, (t+1)*bpt)
     const int bpt = (kSelectBins + T - 1) / T;
@@ -283,7 +284,7 @@ __device__ __forceinline__ void wg_topk_from_lds(uint64_t* keys, int n, int K, v
         const uint64_t key = keys[i];
         const uint32_t idx = key_index(key);
         uint32_t bits = key_value_bits(key);
-        if (bits == 0) bits = elem<DT>::load_bits(rowp, idx);
+        if (bits == 0 && key != 0) bits = elem<DT>::load_bits(rowp, idx);
         elem<DT>::store_bits(out_vals, out_base + i, bits);
         out_idx[out_base + i] = (int32_t)idx;
     }

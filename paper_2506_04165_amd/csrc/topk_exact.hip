@@ -107,7 +107,8 @@ __global__ void __launch_bounds__(1024) topk_exact_kernel(TopkParams p) {
                 const uint32_t d = ordered_from_bits(b) >> 21;
                 if (d >= dmin) atomicAdd(&hist[d], 1u);
             });
-            if (end >= next_update && end < N) {
+            // (only once at least K keys have been counted: the walk needs K of them)
+            if (end >= next_update && end < N && end >= p.K) {
                 uint32_t digit, above, count;
                 hist_find_digit(hist, ctl, p.K, digit, above, count);
                 dmin = digit;                    // K keys at or above this digit exist already
@@ -167,7 +168,7 @@ __global__ void __launch_bounds__(1024) topk_exact_kernel(TopkParams p) {
         const uint64_t key = lds64[i];
         const uint32_t idx = key_index(key);
         uint32_t b = key_value_bits(key);
-        if (b == 0) {
+        if (b == 0 && key != 0) {
             // rare: look the survivor up by its index to tell -0.0 from +0.0
             for (int n = 0; n < N; ++n)
                 if ((uint32_t)payload[n] == idx) { b = elem<DT>::load_bits(rowp, n); break; }
