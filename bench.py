@@ -36,10 +36,19 @@ PAPER_CONTEXT = {
                                       "K'=1_unfused": 64, "K'=4_unfused": 22},
 }
 
-# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/),
-# keyed by (workload, B, K').  None = not measured.
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by a plain
+# copy of known size (profiles/approx_topk_<workload>_B<B>_Kp<K'>.md), keyed by (workload, B, K').
 MEASURED_TRAFFIC_BYTES = {
-    ("c4_mips", 1024, 4): 1074327000,   # profiles/approx_topk_c4_mips_B1024_Kp4.md
+    ("c4_mips", 1024, 4): 1074341377,
+    ("c4_mips", 4096, 1): 1074325890,
+    ("c2_ffn", 128, 4): 498426671,
+    ("c2_ffn", 1024, 1): 498597590,
+    ("c2_ffn", 64, 8): 498412119,
+    ("c3_vocab", 512, 4): 524953607,
+    ("c3_vocab", 512, 2): 524924648,
+    ("c5_adversarial", 256, 8): 271262102,
+    ("c5_adversarial", 256, 1): 270821811,
+    ("c5_adversarial", 256, 32): 271691131,
 }
 
 
