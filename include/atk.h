@@ -100,6 +100,30 @@ size_t atk_workspace_bytes(int op, int dtype, int64_t rows, int64_t N, int K, in
 double atk_expected_recall(int64_t N, int64_t B, int64_t K, int64_t Kprime);
 
 /*
+ * Parameter selection for a recall target (Section 6.3, appendix "Algorithm Parameter
+ * Selection"): among the configurations with K' in [1, max_kprime], B a divisor of N and a
+ * multiple of bucket_multiple, K' <= N/B and K <= B*K', whose expected recall (Theorem 1,
+ * closed form, no Monte Carlo) is at least recall_target, the one with the fewest stage-1
+ * survivors B*K' (the size of stage 2's input); on ties the smaller K'.  If none qualifies the
+ * exact Top-K is returned as K' = K, B = 1.  Suggested ceilings on MI355X, where stage 1 stays
+ * memory-bound: max_kprime 4 for fp32, 8 for bf16; bucket_multiple 64 (one wavefront).
+ * Host only.  expected_recall_out may be NULL.
+ */
+int atk_select_params(int64_t N, int K, double recall_target, int max_kprime, int bucket_multiple,
+                      int* Kprime_out, int* B_out, double* expected_recall_out);
+
+/*
+ * atk_approx_topk with K' and B chosen by atk_select_params(N, K, recall_target, ceiling for
+ * the dtype, 64): the paper's approx_top_k(array, K, recall_target) interface.  The chosen
+ * values are reported through Kprime_used / B_used (may be NULL).  Size the workspace with
+ * atk_workspace_bytes for the values atk_select_params returns.
+ */
+int atk_approx_topk_recall(const void* values, int dtype, int64_t rows, int64_t N,
+                           int64_t row_stride, int K, double recall_target, void* out_vals,
+                           int32_t* out_idx, void* workspace, size_t workspace_bytes,
+                           void* stream, int* Kprime_used, int* B_used);
+
+/*
  * Writes a one-line description of how atk_approx_topk would run the given problem (kernel
  * variant, lanes per row, workgroup shape, LDS and workspace bytes) into buf.  Host only; for
  * logs and tests.  Returns the status atk_approx_topk would return for these arguments.

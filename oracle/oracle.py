@@ -162,6 +162,28 @@ def buckets_for_recall_k1(N: int, K: int, r: float) -> float:
     return K / (2.0 * (1.0 - r + K / (2.0 * N)))
 
 
+def select_parameters(N: int, K: int, recall_target: float, allowed_kprime=(1, 2, 3, 4),
+                      bucket_multiple: int = 128):
+    """Parameter sweep of the appendix "Algorithm Parameter Selection", with the exact closed
+    form in place of the Monte-Carlo estimate: over K' in `allowed_kprime` and every divisor B
+    of N that is a multiple of `bucket_multiple`, with K' <= N/B and B*K' >= K, keep the
+    configuration with the fewest stage-1 survivors B*K' whose expected recall reaches the
+    target; on ties the smaller K'.  Plain exhaustive enumeration.  Returns (K', B) or None.
+    """
+    divisors = [d for d in range(1, N + 1) if N % d == 0] if N <= 4096 else sorted(
+        {d for i in range(1, int(math.isqrt(N)) + 1) if N % i == 0 for d in (i, N // i)})
+    best = None
+    for kp in sorted(allowed_kprime):
+        for B in divisors:
+            if B % bucket_multiple or B * kp < K or kp > N // B or kp > K:
+                continue
+            if best is not None and B * kp >= best[0]:
+                continue
+            if expected_recall(N, B, K, kp) >= recall_target:
+                best = (B * kp, kp, B)
+    return None if best is None else (best[1], best[2])
+
+
 def expected_recall_mc(N: int, B: int, K: int, Kprime: int, num_trials: int,
                        rng: np.random.Generator):
     """Monte-Carlo estimate of the same expectation (Section 6.2; appendix on parameter selection).

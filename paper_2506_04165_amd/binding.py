@@ -24,7 +24,7 @@ SIZE_MAX = ctypes.c_size_t(-1).value
 
 EXPORTS = [
     "atk_approx_topk", "atk_topk", "atk_approx_topk_stage1", "atk_workspace_bytes",
-    "atk_expected_recall", "atk_describe_plan", "atk_status_string", "atk_last_hip_error",
+    "atk_expected_recall", "atk_select_params", "atk_approx_topk_recall", "atk_describe_plan", "atk_status_string", "atk_last_hip_error",
     "atk_version",
 ]
 
@@ -54,6 +54,11 @@ def _load() -> ctypes.CDLL:
     lib.atk_workspace_bytes.restype = sz
     lib.atk_expected_recall.argtypes = [i64, i64, i64, i64]
     lib.atk_expected_recall.restype = ctypes.c_double
+    ip, dp = ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_double)
+    lib.atk_select_params.argtypes = [i64, ci, ctypes.c_double, ci, ci, ip, ip, dp]
+    lib.atk_select_params.restype = ci
+    lib.atk_approx_topk_recall.argtypes = [vp, ci, i64, i64, i64, ci, ctypes.c_double, vp, vp, vp, sz, vp, ip, ip]
+    lib.atk_approx_topk_recall.restype = ci
     lib.atk_describe_plan.argtypes = [ci, i64, i64, ci, ci, ci, ctypes.c_char_p, sz]
     lib.atk_describe_plan.restype = ci
     lib.atk_status_string.argtypes = [ci]
@@ -116,6 +121,39 @@ def describe_plan(dtype: torch.dtype, rows: int, N: int, K: int, Kprime: int, B:
 
 def expected_recall(N: int, B: int, K: int, Kprime: int) -> float:
     return float(lib.atk_expected_recall(N, B, K, Kprime))
+
+
+def select_params(N: int, K: int, recall_target: float, max_kprime: int = 4, bucket_multiple: int = 64):
+    """(K', B, expected recall) with the fewest stage-1 survivors meeting the recall target."""
+    kp, b, r = ctypes.c_int(0), ctypes.c_int(0), ctypes.c_double(0.0)
+    st = lib.atk_select_params(N, K, recall_target, max_kprime, bucket_multiple,
+                               ctypes.byref(kp), ctypes.byref(b), ctypes.byref(r))
+    if st != OK:
+        raise AtkError(st, "atk_select_params")
+    return kp.value, b.value, r.value
+
+
+def approx_topk_recall(values: torch.Tensor, K: int, recall_target: float, workspace=None):
+    """approx_top_k(array, K, recall_target): returns (vals, idx, K' used, B used)."""
+    rows, N, stride = _check_input(values)
+    code = _dtype_code(values)
+    kp, b, _ = select_params(N, K, recall_target, 8 if code == BF16 else 4, 64)
+    out_vals = torch.empty((rows, K), dtype=values.dtype, device=values.device)
+    out_idx = torch.empty((rows, K), dtype=torch.int32, device=values.device)
+    ws_ptr, ws_bytes = None, 0
+    if not (kp == K and b == 1):
+        need = lib.atk_workspace_bytes(OP_APPROX_TOPK, code, rows, N, K, kp, b)
+        if need != SIZE_MAX and need > 0:
+            if workspace is None or workspace.numel() * workspace.element_size() < need:
+                workspace = torch.empty(need, dtype=torch.uint8, device=values.device)
+            ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    kp_used, b_used = ctypes.c_int(0), ctypes.c_int(0)
+    st = lib.atk_approx_topk_recall(values.data_ptr(), code, rows, N, stride, K, recall_target,
+                                    out_vals.data_ptr(), out_idx.data_ptr(), ws_ptr, ws_bytes,
+                                    _stream_ptr(values.device), ctypes.byref(kp_used), ctypes.byref(b_used))
+    if st != OK:
+        raise AtkError(st, "atk_approx_topk_recall")
+    return out_vals, out_idx, kp_used.value, b_used.value
 
 
 def approx_topk(values: torch.Tensor, K: int, Kprime: int, B: int, out=None, workspace=None):

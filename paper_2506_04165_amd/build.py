@@ -30,6 +30,7 @@ SOURCES = [
     "approx_inst_bf16_unaligned.hip",
     "approx_inst_bf16_packed.hip",
     "recall.cpp",
+    "select_params.cpp",
 ]
 
 # packed fp32 instructions are disabled on purpose (they have misbehaved on the test machines)

@@ -338,6 +338,23 @@ int atk_approx_topk(const void* values, int dtype, int64_t rows, int64_t N, int6
     return run_exact(surv_vals, surv_idx, dtype, rows, C, C, K, out_vals, out_idx, st);
 }
 
+int atk_approx_topk_recall(const void* values, int dtype, int64_t rows, int64_t N,
+                           int64_t row_stride, int K, double recall_target, void* out_vals,
+                           int32_t* out_idx, void* workspace, size_t workspace_bytes,
+                           void* stream, int* Kprime_used, int* B_used) {
+    if (dtype != ATK_F32 && dtype != ATK_BF16) return ATK_UNSUPPORTED;
+    int kp = 0, b = 0;
+    int rc = atk_select_params(N, K, recall_target, dtype == ATK_BF16 ? 8 : 4, 64, &kp, &b, nullptr);
+    if (rc) return rc;
+    if (Kprime_used) *Kprime_used = kp;
+    if (B_used) *B_used = b;
+    if (kp == K && b == 1)   // nothing approximate reaches the target: exact Top-K
+        return atk_topk(values, dtype, rows, N, row_stride, K, out_vals, out_idx, workspace,
+                        workspace_bytes, stream);
+    return atk_approx_topk(values, dtype, rows, N, row_stride, K, kp, b, out_vals, out_idx,
+                           workspace, workspace_bytes, stream);
+}
+
 int atk_topk(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride, int K,
              void* out_vals, int32_t* out_idx, void* workspace, size_t workspace_bytes,
              void* stream) {

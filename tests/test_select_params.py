@@ -1,0 +1,80 @@
+"""Recall-target parameter selection (Section 6.3 last paragraph; appendix "Algorithm Parameter
+Selection"): the library's closed-form sweep against the oracle's exhaustive enumeration in
+exact arithmetic, and against the configurations the paper names."""
+import pytest
+import torch
+
+from oracle import oracle
+from paper_2506_04165_amd import binding as atk
+
+
+def test_configurations_named_in_the_paper():
+    # Section 7.1: for 95 % recall of the top 1024 of 262144, K'=1 needs 16384 survivors and
+    # K'=4 only 2048; Section 7.2 / Table 1: the 99 % configuration is K'=4 with 1024 buckets,
+    # against 65536 buckets for K'=1.  (Bucket counts are multiples of 128 there.)
+    N, K = 262144, 1024
+    kp, B, _ = atk.select_params(N, K, 0.95, max_kprime=1, bucket_multiple=128)
+    assert (kp, B) == (1, 16384)
+    kp, B, _ = atk.select_params(N, K, 0.95, max_kprime=4, bucket_multiple=128)
+    assert (kp, B) == (4, 512) and kp * B == 2048
+    kp, B, r = atk.select_params(N, K, 0.99, max_kprime=4, bucket_multiple=128)
+    assert (kp, B) == (4, 1024) and r >= 0.99
+    kp, B, _ = atk.select_params(N, K, 0.99, max_kprime=1, bucket_multiple=128)
+    assert (kp, B) == (1, 65536)
+
+
+@pytest.mark.parametrize("N,K", [(4096, 32), (14336, 287), (65536, 256), (15360, 480), (6000, 100)])
+@pytest.mark.parametrize("target", [0.8, 0.9, 0.95, 0.99])
+@pytest.mark.parametrize("max_kp,mult", [(1, 64), (4, 64), (8, 16), (4, 128)])
+def test_matches_exhaustive_enumeration(N, K, target, max_kp, mult):
+    want = oracle.select_parameters(N, K, target, tuple(range(1, max_kp + 1)), mult)
+    kp, B, r = atk.select_params(N, K, target, max_kp, mult)
+    if want is None:
+        assert (kp, B) == (K, 1) and r == 1.0        # nothing approximate qualifies: exact
+        return
+    assert (kp, B) == want
+    assert r >= target
+    assert r == pytest.approx(oracle.expected_recall(N, B, K, kp), abs=1e-9)
+    # minimality: the next smaller legal bucket count for this K' misses the target (or is illegal)
+    smaller = [d for d in range(mult, B, mult) if N % d == 0 and d * kp >= K and kp <= N // d]
+    if smaller:
+        assert oracle.expected_recall(N, smaller[-1], K, kp) < target
+
+
+def test_falls_back_to_exact_and_rejects_bad_arguments():
+    assert atk.select_params(4096, 32, 1.0, 1, 64)[:2] in ((1, 4096), (32, 1))
+    assert atk.select_params(1000, 10, 0.99, 4, 64)[:2] == (10, 1)    # no divisor of 1000 is a multiple of 64
+    import ctypes
+    a, c = ctypes.c_int(0), ctypes.c_int(0)
+    f = atk.lib.atk_select_params
+    assert f(0, 1, 0.9, 4, 64, ctypes.byref(a), ctypes.byref(c), None) == atk.INVALID_ARG
+    assert f(4096, 0, 0.9, 4, 64, ctypes.byref(a), ctypes.byref(c), None) == atk.INVALID_ARG
+    assert f(4096, 32, 0.0, 4, 64, ctypes.byref(a), ctypes.byref(c), None) == atk.INVALID_ARG
+    assert f(4096, 32, 1.5, 4, 64, ctypes.byref(a), ctypes.byref(c), None) == atk.INVALID_ARG
+    assert f(4096, 32, 0.9, 0, 64, ctypes.byref(a), ctypes.byref(c), None) == atk.INVALID_ARG
+    assert f(4096, 32, 0.9, 4, 64, None, ctypes.byref(c), None) == atk.INVALID_ARG
+
+
+@pytest.mark.gpu
+def test_recall_target_entry_point_runs_the_selected_configuration():
+    import numpy as np
+    from paper_2506_04165_amd import workloads
+    for dtype, N, K, target in [(torch.float32, 65536, 256, 0.95), (torch.bfloat16, 14336, 287, 0.95),
+                                (torch.float32, 262144, 1024, 0.99), (torch.float32, 4096, 32, 1.0)]:
+        x = workloads.gaussian(6, N, seed=77, dtype=dtype)
+        xd = x.to("cuda:0")
+        v, i, kp, B = atk.approx_topk_recall(xd, K, target)
+        torch.cuda.synchronize()
+        want = atk.select_params(N, K, target, 8 if dtype == torch.bfloat16 else 4, 64)
+        assert (kp, B) == want[:2]
+        xh = workloads.to_numpy_bits(x)
+        if (kp, B) == (K, 1):
+            ov, oi = oracle.topk(xh, K)
+        else:
+            ov, oi = oracle.approx_topk(xh, K, kp, B)
+        assert np.array_equal(i.cpu().numpy(), oi)
+        got = v.cpu().view(torch.int16).numpy().view(np.uint16) if dtype == torch.bfloat16 else v.cpu().numpy().view(np.uint32)
+        assert np.array_equal(got, ov if ov.dtype == np.uint16 else ov.view(np.uint32))
+        # the realised recall on random data is close to the target's expectation
+        _, ei = oracle.topk(xh, K)
+        assert oracle.index_recall(oi, ei).mean() >= target - 0.03
