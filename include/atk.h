@@ -131,6 +131,17 @@ int atk_approx_topk_recall(const void* values, int dtype, int64_t rows, int64_t 
 int atk_describe_plan(int dtype, int64_t rows, int64_t N, int K, int Kprime, int B, char* buf,
                       size_t buflen);
 
+/*
+ * Vector-ALU throughput probe (appendix "Estimating peak VPU throughput" redone for MI355X; the
+ * measurement behind the ridge point of Section 2.3 that bounds K').  Streams n_words int32
+ * words and applies `ops` dependent operations to each:
+ *   kind 0  out[i] = y_ops where (x, y) -> (y, x + y) is applied `ops` times to (x[i], y[i])
+ *   kind 1  out[i] = x[i] squared `ops` times                       (y is ignored, may be NULL)
+ * with wrap-around int32 arithmetic.  x, y, out: device pointers to n_words words.
+ */
+int atk_valu_probe(int kind, const void* x, const void* y, void* out, size_t n_words, int ops,
+                   void* stream);
+
 /* Static, human-readable name of a status code. */
 const char* atk_status_string(int status);
 

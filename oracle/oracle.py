@@ -223,3 +223,23 @@ def value_recall(vals_approx_f32: np.ndarray, vals_exact_f32: np.ndarray) -> np.
 def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
     """Widen raw bf16 bit patterns (uint16) to float32 (exact)."""
     return (bits.astype(np.uint32) << 16).view(np.float32)
+
+
+# --------------------------------------------------------------------------
+# Vector-throughput probe programs (appendix "Estimating peak VPU throughput")
+# --------------------------------------------------------------------------
+
+def valu_probe(kind: int, x: np.ndarray, y: np.ndarray, ops: int) -> np.ndarray:
+    """What the two probe programs compute, in wrap-around 32-bit arithmetic.
+
+    kind 0: `ops` steps of (x, y) -> (y, x + y), result y;  kind 1: x squared `ops` times.
+    """
+    a = x.astype(np.uint32).copy()
+    if kind == 0:
+        b = y.astype(np.uint32).copy()
+        for _ in range(ops):
+            a, b = b, a + b
+        return b
+    for _ in range(ops):
+        a = a * a
+    return a

@@ -24,7 +24,7 @@ SIZE_MAX = ctypes.c_size_t(-1).value
 
 EXPORTS = [
     "atk_approx_topk", "atk_topk", "atk_approx_topk_stage1", "atk_workspace_bytes",
-    "atk_expected_recall", "atk_select_params", "atk_approx_topk_recall", "atk_describe_plan", "atk_status_string", "atk_last_hip_error",
+    "atk_expected_recall", "atk_select_params", "atk_approx_topk_recall", "atk_describe_plan", "atk_valu_probe", "atk_status_string", "atk_last_hip_error",
     "atk_version",
 ]
 
@@ -59,6 +59,8 @@ def _load() -> ctypes.CDLL:
     lib.atk_select_params.restype = ci
     lib.atk_approx_topk_recall.argtypes = [vp, ci, i64, i64, i64, ci, ctypes.c_double, vp, vp, vp, sz, vp, ip, ip]
     lib.atk_approx_topk_recall.restype = ci
+    lib.atk_valu_probe.argtypes = [ci, vp, vp, vp, sz, ci, vp]
+    lib.atk_valu_probe.restype = ci
     lib.atk_describe_plan.argtypes = [ci, i64, i64, ci, ci, ci, ctypes.c_char_p, sz]
     lib.atk_describe_plan.restype = ci
     lib.atk_status_string.argtypes = [ci]
@@ -193,6 +195,17 @@ def topk(values: torch.Tensor, K: int, out=None):
     if st != OK:
         raise AtkError(st, "atk_topk")
     return out_vals, out_idx
+
+
+def valu_probe(kind: int, x: torch.Tensor, y, ops: int, out=None):
+    """Run the vector-ALU probe on int32 tensors (kind 0: fibonacci steps, 1: squarings)."""
+    if out is None:
+        out = torch.empty_like(x)
+    st = lib.atk_valu_probe(kind, x.data_ptr(), None if y is None else y.data_ptr(), out.data_ptr(),
+                            x.numel(), ops, _stream_ptr(x.device))
+    if st != OK:
+        raise AtkError(st, "atk_valu_probe")
+    return out
 
 
 def approx_topk_stage1(values: torch.Tensor, Kprime: int, B: int):
