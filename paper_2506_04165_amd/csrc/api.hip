@@ -160,9 +160,20 @@ static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, in
     }
     // bf16 rows whose indices fit 16 bits: value and index share one 32-bit key
     // (such variants only exist for the plain fused route with at most 1024 candidates per row)
-    const bool packed_ok = dtype == ATK_BF16 && N <= 65536 && !stage1_only && owners == 1 &&
-                           G >= 64 && pow2_ceil((int64_t)B * Kp) <= kWaveSortMaxKeys &&
-                           env_int("ATK_NO_PACKED", 0) == 0;
+    bool packed_ok = dtype == ATK_BF16 && N <= 65536 && !stage1_only && owners == 1 && G >= 64 &&
+                     pow2_ceil((int64_t)B * Kp) <= kWaveSortMaxKeys &&
+                     env_int("ATK_NO_PACKED", 0) == 0;
+    if (packed_ok && G == 64 && NL == 1 && is_pow2(B) && rows >= 1024 &&
+        env_int("ATK_LANES_PER_ROW", 0) == 0 && env_int("ATK_NO_SUBWAVE", 0) == 0) {
+        // many short rows with only 64 buckets: rather than 2-byte loads from 64 lanes, a wavefront
+        // works on several rows at once, each lane taking as many consecutive elements per load
+        // as its registers allow (measured: a gain only in this case)
+        for (int nl = maxNL < 8 ? maxNL : 8; nl > NL; nl >>= 1) {
+            if (B % nl != 0 || B / nl < 8) continue;
+            const Variant* v = find_variant(dtype, KP, nl, true, aligned_for);
+            if (v && v->packed) { NL = nl; G = B / nl; break; }
+        }
+    }
     pl.var = find_variant(dtype, KP, NL, packed_ok, aligned_for);
     if (!pl.var) { pl.status = ATK_UNSUPPORTED; return pl; }
     const int V = pl.var->V;

@@ -272,8 +272,22 @@ struct ApproxKernel {
                             cand32[(off[r] + v) * p.Kprime + k] = row_ok ? key : 0;
                         }
             __syncthreads();
-            if (t < kWave && row_ok)
-                wave_sort32_dispatch<DT>(cand32, p.Cpad, p.K, rowp, p.out_vals, p.out_idx, (int64_t)row * p.K);
+            if (p.G >= kWave) {
+                if (t < kWave && row_ok)
+                    wave_sort32_dispatch<DT>(cand32, p.Cpad, p.K, rowp, p.out_vals, p.out_idx,
+                                             (int64_t)row * p.K);
+            } else {
+                // several rows per wavefront: it sorts them one after the other
+                const int per_wave = kWave / p.G;
+                for (int j = 0; j < per_wave; ++j) {
+                    const int gl = (tid >> 6) * per_wave + j;
+                    const int rw = blockIdx.x * p.rows_per_wg + gl;
+                    if (rw < p.rows)
+                        wave_sort32_dispatch<DT>((const uint32_t*)lds + (size_t)gl * p.Cpad, p.Cpad, p.K,
+                                                 (const char*)p.values + (size_t)rw * p.row_stride * ES,
+                                                 p.out_vals, p.out_idx, (int64_t)rw * p.K);
+                }
+            }
             return;
         }
 

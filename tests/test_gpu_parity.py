@@ -167,6 +167,16 @@ def test_bf16_packed_key_limits(atk, N, B, Kp, K):
     check_approx(atk, z, K, Kp, B)
 
 
+@pytest.mark.parametrize("B,Kp,K", [(128, 4, 287), (64, 8, 300), (256, 2, 100), (64, 3, 64), (512, 2, 1000)])
+def test_many_short_bf16_rows_several_rows_per_wavefront(atk, B, Kp, K):
+    # >= 1024 short bf16 rows: groups of fewer than 64 lanes own a row, a wavefront holds several
+    # rows; 1030 rows leave the last workgroup partly empty
+    x = workloads.gaussian(1030, 2048, seed=600 + B, dtype=torch.bfloat16)
+    x[5, :] = -2.0          # a constant row: index order only
+    x[1029, 2047] = 50.0
+    check_approx(atk, x, K, Kp, B)
+
+
 def test_kprime_equals_k_and_single_bucket_are_exact(atk):
     x = workloads.gaussian(4, 8192, seed=7)
     for K, Kp, B in [(32, 32, 64), (32, 32, 1), (20, 20, 256), (100, 100, 64), (100, 100, 1),
