@@ -24,6 +24,12 @@
  *   - the return value is an atk_status; arguments are validated on the host before anything
  *     is launched, so every error below can be provoked without a GPU;
  *   - rows == 0 is legal and does nothing.
+ *
+ * Developer knobs (environment, read at every call; for experiments and tests, not for
+ * production): ATK_LANES_PER_ROW=<power of two <= 1024> lanes that share one row,
+ * ATK_SEGMENTS=<n> force n row segments on the split route, ATK_NO_PACKED=1 / ATK_NO_SUBWAVE=1
+ * switch the packed-key / several-rows-per-wavefront variants off, ATK_BATCH_MIN_KP=<k> list
+ * length from which sorted batches are used.  Results never depend on them.
  */
 #ifndef ATK_H_
 #define ATK_H_

@@ -30,6 +30,7 @@ SOURCES = [
     "approx_inst_f32_unaligned.hip",
     "approx_inst_bf16_unaligned.hip",
     "approx_inst_bf16_packed.hip",
+    "approx_inst_batched.hip",
     "recall.cpp",
     "select_params.cpp",
 ]

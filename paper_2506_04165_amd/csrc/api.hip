@@ -16,7 +16,7 @@ namespace atk {
 
 // ---- compiled kernel variants -------------------------------------------------------------
 using LaunchFn = hipError_t (*)(const ApproxParams&, int, int, size_t, hipStream_t);
-struct Variant { int dtype, KP, V, R; bool packed; LaunchFn fn; };
+struct Variant { int dtype, KP, V, R, rep; LaunchFn fn; bool packed() const { return rep == 1; } };
 
 #define ATK_X(TAG, T, KP, V, R, P) extern template hipError_t launch_approx<T, KP, V, R, P>(const ApproxParams&, int, int, size_t, hipStream_t);
 ATK_ALL_INSTANCES(ATK_X)
@@ -35,9 +35,9 @@ template <typename Pred>
 static const Variant* find_variant(int dtype, int KP, int NL, bool packed_ok, Pred vector_ok) {
     const Variant* best = nullptr;
     for (const Variant& v : kVariants) {
-        if (v.dtype != dtype || v.KP != KP || v.V * v.R != NL || !vector_ok(v.V)) continue;
-        if (v.packed && !packed_ok) continue;
-        if (!best || (v.packed && !best->packed) || (v.packed == best->packed && v.V > best->V))
+        if (v.dtype != dtype || v.KP != KP || v.V * v.R != NL || !vector_ok(v.V) || v.rep == 2) continue;
+        if (v.packed() && !packed_ok) continue;
+        if (!best || (v.packed() && !best->packed()) || (v.packed() == best->packed() && v.V > best->V))
             best = &v;
     }
     return best;
@@ -171,11 +171,20 @@ static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, in
         for (int nl = maxNL < 8 ? maxNL : 8; nl > NL; nl >>= 1) {
             if (B % nl != 0 || B / nl < 8) continue;
             const Variant* v = find_variant(dtype, KP, nl, true, aligned_for);
-            if (v && v->packed) { NL = nl; G = B / nl; break; }
+            if (v && v->packed()) { NL = nl; G = B / nl; break; }
         }
     }
     pl.var = find_variant(dtype, KP, NL, packed_ok, aligned_for);
     if (!pl.var) { pl.status = ATK_UNSUPPORTED; return pl; }
+    // Long lists with few buckets: sorted batches of 64-bit keys, one bucket per lane, cost about a
+    // third of the position-by-position update at K' = 32.
+    if (!pl.var->packed() && owners == 1 && KP >= env_int("ATK_BATCH_MIN_KP", 16) && B >= 64 && B <= 256) {
+        for (const Variant& v : kVariants)
+            if (v.rep == 2 && v.dtype == dtype && v.KP == KP) {
+                pl.var = &v; G = pow2_ceil(B); NL = 1;
+                break;
+            }
+    }
     const int V = pl.var->V;
     pl.G = G;
     pl.owners = owners;
@@ -193,9 +202,9 @@ static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, in
     auto lds_for = [&](int r) {
         size_t cand = 0, aux = 0;
         if (owners > 1) { cand = (size_t)r * pl.Cpad; aux = (size_t)r * B * pl.seg; }
-        else if (pl.var->packed) cand = (size_t)r * pl.Cpad / 2 + 1;     // 32-bit keys
+        else if (pl.var->packed()) cand = (size_t)r * pl.Cpad / 2 + 1;     // 32-bit keys
         else if (!stage1_only) cand = (size_t)r * pl.Cpad;
-        if (!stage1_only && !pl.var->packed && r == 1 && pl.Cpad > 256 &&
+        if (!stage1_only && !pl.var->packed() && r == 1 && pl.Cpad > 256 &&
             aux * 8 < (size_t)kSelectScratchBytes)
             aux = (kSelectScratchBytes + 7) / 8;
         return (cand + aux) * 8;
@@ -222,7 +231,7 @@ static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, in
 
     // Too few rows to fill the chip: cut every row into segments streamed by separate
     // workgroups (aim: at least 2 waves on each of the 1024 SIMDs), merged by a finishing launch.
-    if (pl.fused && owners == 1 && G >= 64 && rows > 0 && !pl.var->packed) {
+    if (pl.fused && owners == 1 && G >= 64 && rows > 0 && !pl.var->packed()) {
         const int64_t waves = (int64_t)pl.grid * (pl.block / 64);
         int want = (int)((kTargetWaves + waves - 1) / waves);
         const int max_by_len = pl.nsteps / kMinSegmentSteps;
@@ -432,7 +441,7 @@ int atk_describe_plan(int dtype, int64_t rows, int64_t N, int K, int Kprime, int
                   "%s%s KP=%d V=%d R=%d lanes_per_row=%d rows_per_wg=%d block=%d grid=%dx%d step=%d "
                   "steps=%d owners=%d seg=%d cand=%d tail=%d lds=%zu workspace=%zu",
                   pl.nseg > 1 ? "split" : (pl.fused ? "fused" : "unfused"),
-                  pl.var->packed ? " packed" : "", pl.var->KP, pl.var->V,
+                  pl.var->packed() ? " packed" : "", pl.var->KP, pl.var->V,
                   pl.var->R, pl.G, pl.rows_per_wg, pl.block, pl.grid, pl.nseg, pl.S, pl.nsteps,
                   pl.owners, pl.seg, pl.Cpad, pl.tail, pl.lds, pl.workspace);
     return ATK_OK;

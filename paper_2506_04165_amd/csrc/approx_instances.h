@@ -4,7 +4,8 @@
 // Register budget: V*R*KP <= 32 list entries per lane.
 #pragma once
 
-// X(DTYPE_TAG, C++ type, KP, V, R, PACKED)
+// X(DTYPE_TAG, C++ type, KP, V, R, REP)   REP: 0 value+step lists, 1 packed 32-bit keys,
+//                                          2 sorted batches of 64-bit keys
 #define ATK_INSTANCES_NL1(X, TAG, T, V, R, P) \
     X(TAG, T, 1, V, R, P) X(TAG, T, 2, V, R, P) X(TAG, T, 3, V, R, P) X(TAG, T, 4, V, R, P) \
     X(TAG, T, 6, V, R, P) X(TAG, T, 8, V, R, P) X(TAG, T, 16, V, R, P) X(TAG, T, 32, V, R, P)
@@ -20,44 +21,49 @@
     X(TAG, T, 1, V, R, P) X(TAG, T, 2, V, R, P)
 
 #define ATK_INSTANCES_F32_SMALL(X) \
-    ATK_INSTANCES_NL1(X, 0, float, 1, 1, false) ATK_INSTANCES_NL2(X, 0, float, 2, 1, false)
+    ATK_INSTANCES_NL1(X, 0, float, 1, 1, 0) ATK_INSTANCES_NL2(X, 0, float, 2, 1, 0)
 #define ATK_INSTANCES_F32_WIDE(X) \
-    ATK_INSTANCES_NL4(X, 0, float, 4, 1, false) ATK_INSTANCES_NL8(X, 0, float, 4, 2, false) \
-    ATK_INSTANCES_NL16(X, 0, float, 4, 4, false)
+    ATK_INSTANCES_NL4(X, 0, float, 4, 1, 0) ATK_INSTANCES_NL8(X, 0, float, 4, 2, 0) \
+    ATK_INSTANCES_NL16(X, 0, float, 4, 4, 0)
 #define ATK_INSTANCES_BF16_SMALL(X) \
-    ATK_INSTANCES_NL1(X, 1, bf16_t, 1, 1, false) ATK_INSTANCES_NL2(X, 1, bf16_t, 2, 1, false)
+    ATK_INSTANCES_NL1(X, 1, bf16_t, 1, 1, 0) ATK_INSTANCES_NL2(X, 1, bf16_t, 2, 1, 0)
 #define ATK_INSTANCES_BF16_WIDE(X) \
-    ATK_INSTANCES_NL4(X, 1, bf16_t, 4, 1, false) ATK_INSTANCES_NL8(X, 1, bf16_t, 8, 1, false) \
-    ATK_INSTANCES_NL16(X, 1, bf16_t, 8, 2, false)
+    ATK_INSTANCES_NL4(X, 1, bf16_t, 4, 1, 0) ATK_INSTANCES_NL8(X, 1, bf16_t, 8, 1, 0) \
+    ATK_INSTANCES_NL16(X, 1, bf16_t, 8, 2, 0)
 
 // single-element loads with several loads per step: for rows whose base address, stride or
 // bucket count rule out vector loads
 #define ATK_INSTANCES_F32_UNALIGNED(X) \
-    ATK_INSTANCES_NL2(X, 0, float, 1, 2, false) ATK_INSTANCES_NL4(X, 0, float, 1, 4, false) \
-    ATK_INSTANCES_NL8(X, 0, float, 1, 8, false) ATK_INSTANCES_NL16(X, 0, float, 1, 16, false)
+    ATK_INSTANCES_NL2(X, 0, float, 1, 2, 0) ATK_INSTANCES_NL4(X, 0, float, 1, 4, 0) \
+    ATK_INSTANCES_NL8(X, 0, float, 1, 8, 0) ATK_INSTANCES_NL16(X, 0, float, 1, 16, 0)
 #define ATK_INSTANCES_BF16_UNALIGNED(X) \
-    ATK_INSTANCES_NL2(X, 1, bf16_t, 1, 2, false) ATK_INSTANCES_NL4(X, 1, bf16_t, 1, 4, false) \
-    ATK_INSTANCES_NL8(X, 1, bf16_t, 1, 8, false) ATK_INSTANCES_NL16(X, 1, bf16_t, 1, 16, false)
+    ATK_INSTANCES_NL2(X, 1, bf16_t, 1, 2, 0) ATK_INSTANCES_NL4(X, 1, bf16_t, 1, 4, 0) \
+    ATK_INSTANCES_NL8(X, 1, bf16_t, 1, 8, 0) ATK_INSTANCES_NL16(X, 1, bf16_t, 1, 16, 0)
 
 // bf16 rows of at most 65536 elements: lists of packed 32-bit keys
 #define ATK_PACKED_NL1(X, V, R) \
-    X(1, bf16_t, 1, V, R, true) X(1, bf16_t, 2, V, R, true) X(1, bf16_t, 3, V, R, true) X(1, bf16_t, 4, V, R, true) \
-    X(1, bf16_t, 6, V, R, true) X(1, bf16_t, 8, V, R, true) X(1, bf16_t, 16, V, R, true) \
-    X(1, bf16_t, 32, V, R, true)
+    X(1, bf16_t, 1, V, R, 1) X(1, bf16_t, 2, V, R, 1) X(1, bf16_t, 3, V, R, 1) X(1, bf16_t, 4, V, R, 1) \
+    X(1, bf16_t, 6, V, R, 1) X(1, bf16_t, 8, V, R, 1) X(1, bf16_t, 16, V, R, 1) \
+    X(1, bf16_t, 32, V, R, 1)
 #define ATK_PACKED_NL2(X, V, R) \
-    X(1, bf16_t, 1, V, R, true) X(1, bf16_t, 2, V, R, true) X(1, bf16_t, 3, V, R, true) X(1, bf16_t, 4, V, R, true) \
-    X(1, bf16_t, 6, V, R, true) X(1, bf16_t, 8, V, R, true) X(1, bf16_t, 16, V, R, true)
+    X(1, bf16_t, 1, V, R, 1) X(1, bf16_t, 2, V, R, 1) X(1, bf16_t, 3, V, R, 1) X(1, bf16_t, 4, V, R, 1) \
+    X(1, bf16_t, 6, V, R, 1) X(1, bf16_t, 8, V, R, 1) X(1, bf16_t, 16, V, R, 1)
 #define ATK_PACKED_NL4(X, V, R) \
-    X(1, bf16_t, 1, V, R, true) X(1, bf16_t, 2, V, R, true) X(1, bf16_t, 3, V, R, true) X(1, bf16_t, 4, V, R, true) \
-    X(1, bf16_t, 6, V, R, true) X(1, bf16_t, 8, V, R, true)
+    X(1, bf16_t, 1, V, R, 1) X(1, bf16_t, 2, V, R, 1) X(1, bf16_t, 3, V, R, 1) X(1, bf16_t, 4, V, R, 1) \
+    X(1, bf16_t, 6, V, R, 1) X(1, bf16_t, 8, V, R, 1)
 #define ATK_PACKED_NL8(X, V, R) \
-    X(1, bf16_t, 1, V, R, true) X(1, bf16_t, 2, V, R, true) X(1, bf16_t, 3, V, R, true) X(1, bf16_t, 4, V, R, true)
-#define ATK_PACKED_NL16(X, V, R) X(1, bf16_t, 1, V, R, true) X(1, bf16_t, 2, V, R, true)
+    X(1, bf16_t, 1, V, R, 1) X(1, bf16_t, 2, V, R, 1) X(1, bf16_t, 3, V, R, 1) X(1, bf16_t, 4, V, R, 1)
+#define ATK_PACKED_NL16(X, V, R) X(1, bf16_t, 1, V, R, 1) X(1, bf16_t, 2, V, R, 1)
 #define ATK_INSTANCES_BF16_PACKED(X) \
     ATK_PACKED_NL1(X, 1, 1) ATK_PACKED_NL2(X, 2, 1) ATK_PACKED_NL4(X, 4, 1) \
     ATK_PACKED_NL8(X, 8, 1) ATK_PACKED_NL16(X, 8, 2)
 
+// large K', at most 256 buckets: sorted batches of 64-bit keys, one list per lane
+#define ATK_INSTANCES_BATCHED(X) \
+    X(0, float, 8, 1, 1, 2) X(0, float, 16, 1, 1, 2) X(0, float, 32, 1, 1, 2) \
+    X(1, bf16_t, 8, 1, 1, 2) X(1, bf16_t, 16, 1, 1, 2) X(1, bf16_t, 32, 1, 1, 2)
+
 #define ATK_ALL_INSTANCES(X) \
     ATK_INSTANCES_F32_SMALL(X) ATK_INSTANCES_F32_WIDE(X) ATK_INSTANCES_F32_UNALIGNED(X) \
     ATK_INSTANCES_BF16_SMALL(X) ATK_INSTANCES_BF16_WIDE(X) ATK_INSTANCES_BF16_UNALIGNED(X) \
-    ATK_INSTANCES_BF16_PACKED(X)
+    ATK_INSTANCES_BF16_PACKED(X) ATK_INSTANCES_BATCHED(X)

@@ -71,7 +71,7 @@ __device__ __forceinline__ T sel(bool c, T a, T b) { return c ? a : b; }
 //    half, 0xFFFF - step in the low half.  Within one list keys are distinct and "greater key"
 //    is exactly the total order, so the update is one max and K'-1 medians-of-three on integers
 //    -- K' lane operations -- and no index needs tracking.  Key 0 is the empty entry.
-template <bool PACKED, int KP, int NL> struct Lists;
+template <int REP, int KP, int NL> struct Lists;
 
 // median of three unsigned words.  Written as the instruction itself: the equivalent min/max
 // expression sends the optimizer into exponential work on chains of list updates.
@@ -82,7 +82,7 @@ __device__ __forceinline__ uint32_t med3_u32(uint32_t a, uint32_t b, uint32_t c)
 }
 
 template <int KP, int NL>
-struct Lists<false, KP, NL> {
+struct Lists<0, KP, NL> {
     static constexpr bool exact_bits = true;     // entries keep the stored bit pattern
     float val[NL][KP];
     int32_t stp[NL][KP];
@@ -116,7 +116,7 @@ struct Lists<false, KP, NL> {
 };
 
 template <int KP, int NL>
-struct Lists<true, KP, NL> {
+struct Lists<1, KP, NL> {
     static constexpr bool exact_bits = false;    // -0.0 is stored as +0.0
     uint32_t key[NL][KP];
     __device__ __forceinline__ void init() {
@@ -141,26 +141,81 @@ struct Lists<true, KP, NL> {
     }
 };
 
-template <typename DT, int KP, int V, int R, bool PACKED = false>
+//  * sorted batches of 64-bit keys (large K', one list per lane): K' consecutive elements of the
+//    slot are turned into keys (ordered value << 32 | ~step), sorted in registers by a bitonic
+//    network, and merged with the running list (element-wise max against the reversed batch
+//    gives a bitonic sequence holding the K' greatest of both; log2 K' more stages order it).
+//    About 11 compare-exchanges per element at K' = 32 instead of 32 list positions.
+template <int KP>
+__device__ __forceinline__ void reg_cex_desc(uint64_t& a, uint64_t& b) {   // a := greater
+    const bool sw = a < b;
+    const uint64_t hi = sw ? b : a, lo = sw ? a : b;
+    a = hi; b = lo;
+}
+template <int KP>
+__device__ __forceinline__ void reg_bitonic_merge_desc(uint64_t (&a)[KP]) {   // a bitonic -> descending
+#pragma unroll
+    for (int j = KP / 2; j >= 1; j >>= 1)
+#pragma unroll
+        for (int i = 0; i < KP; ++i)
+            if ((i & j) == 0) reg_cex_desc<KP>(a[i], a[i | j]);
+}
+template <int KP>
+__device__ __forceinline__ void reg_bitonic_sort_desc(uint64_t (&a)[KP]) {
+#pragma unroll
+    for (int k = 2; k <= KP; k <<= 1)
+#pragma unroll
+        for (int j = k / 2; j >= 1; j >>= 1)
+#pragma unroll
+            for (int i = 0; i < KP; ++i)
+                if ((i & j) == 0) {
+                    if ((i & k) == 0 || k == KP) reg_cex_desc<KP>(a[i], a[i | j]);
+                    else reg_cex_desc<KP>(a[i | j], a[i]);
+                }
+}
+
+template <int KP, int NL>
+struct Lists<2, KP, NL> {
+    static_assert(NL == 1, "sorted batches keep one list per lane");
+    static constexpr bool exact_bits = false;    // -0.0 is stored as +0.0
+    uint64_t key[KP];                            // descending, 0 = empty
+    __device__ __forceinline__ void init() {
+#pragma unroll
+        for (int k = 0; k < KP; ++k) key[k] = 0;
+    }
+    // batch: KP keys in any order (0 = none); afterwards key[] holds the KP greatest of both
+    __device__ __forceinline__ void merge(uint64_t (&batch)[KP]) {
+        reg_bitonic_sort_desc<KP>(batch);
+#pragma unroll
+        for (int k = 0; k < KP; ++k) key[k] = max(key[k], batch[KP - 1 - k]);
+        reg_bitonic_merge_desc<KP>(key);
+    }
+    __device__ __forceinline__ bool valid(int, int k) const { return key[k] != 0; }
+    __device__ __forceinline__ uint32_t bits(int, int k) const { return key_value_bits(key[k]); }
+    // the low word of a key is ~step; e: offset of the slot inside a step
+    __device__ __forceinline__ uint32_t index(int, int k, uint32_t S, uint32_t e) const {
+        return (~(uint32_t)key[k]) * S + e;
+    }
+};
+
+template <typename DT, int KP, int V, int R, int REP = 0>
 struct ApproxKernel {
+    static constexpr bool PACKED = REP == 1;
+    static constexpr bool BATCHED = REP == 2;
     static constexpr int NL = V * R;
     static constexpr int DW = (V * elem<DT>::size + 3) / 4;           // dwords per load
-#ifndef ATK_UMAX
-#define ATK_UMAX 16
-#endif
-#ifndef ATK_UDW
-#define ATK_UDW 32
-#endif
-    static constexpr int U_ = ATK_UDW / (R * DW);
-    static constexpr int U = U_ < 1 ? 1 : (U_ > ATK_UMAX ? ATK_UMAX : U_);        // steps in flight
+    static constexpr int U_ = 32 / (R * DW);                          // 32 dwords of loads in flight,
+    static constexpr int U = U_ < 1 ? 1 : (U_ > 16 ? 16 : U_);        // at most 16 steps
     using VL = vec_load<DT, V>;
     using vec_t = typename VL::vec_t;
     static_assert(!PACKED || elem<DT>::size == 2, "packed keys are for 16-bit inputs");
 
     // Feed the V elements of one load into their lists.
-    __device__ static __forceinline__ void consume(Lists<PACKED, KP, NL>& L, const vec_t& x, int r,
+    __device__ static __forceinline__ void consume(Lists<REP, KP, NL>& L, const vec_t& x, int r,
                                                    int step) {
-        if constexpr (!PACKED) {
+        if constexpr (BATCHED) {
+            (void)L; (void)x; (void)r; (void)step;       // batches are fed by the streaming loop
+        } else if constexpr (!PACKED) {
 #pragma unroll
             for (int v = 0; v < V; ++v)
                 L.insert(r * V + v, __uint_as_float(VL::bits(x, v)), step);
@@ -199,7 +254,7 @@ struct ApproxKernel {
         const char* rowp = (const char*)p.values +
                            (size_t)(row_ok ? row : 0) * p.row_stride * elem<DT>::size;
 
-        Lists<PACKED, KP, NL> L;
+        Lists<REP, KP, NL> L;
         L.init();
 
         int off[R];
@@ -229,6 +284,26 @@ struct ApproxKernel {
             s = blockIdx.y * p.seg_steps;
             s_end = min(p.nsteps, s + p.seg_steps);
         }
+        if constexpr (BATCHED) {
+            // K' steps at a time: load them, turn them into keys, sort-merge into the list
+            static_assert(V == 1 && R == 1, "sorted batches: one list per lane");
+            for (; s < s_end; s += KP) {
+                const buffer_rsrc rs = make_rsrc(wg_base + (size_t)s * step_bytes);
+                const int nb = min(KP, s_end - s);          // uniform: the last batch may be short
+                vec_t buf[KP];
+#pragma unroll
+                for (int u = 0; u < KP; ++u)
+                    buf[u] = VL::load(rs, lane_off[0], (uint32_t)(u < nb ? u : 0) * step_bytes);
+                uint64_t batch[KP];
+#pragma unroll
+                for (int u = 0; u < KP; ++u) {
+                    const uint64_t key = ((uint64_t)ordered_from_bits(VL::bits(buf[u], 0)) << 32) |
+                                         (uint32_t)(~(uint32_t)(s + u));
+                    batch[u] = u < nb ? key : 0;
+                }
+                L.merge(batch);
+            }
+        } else {
         for (; s + U <= s_end; s += U) {
             const buffer_rsrc rs = make_rsrc(wg_base + (size_t)s * step_bytes);
             vec_t buf[U][R];
@@ -250,6 +325,7 @@ struct ApproxKernel {
                 vec_t x = VL::load(rs, lane_off[r], 0);
                 consume(L, x, r, s);
             }
+        }
         }
 
         const int C = p.B * p.Kprime;
@@ -316,7 +392,7 @@ struct ApproxKernel {
                             const int64_t o = (((int64_t)row * p.nseg + blockIdx.y) * p.Kprime + k) * p.B + bucket;
                             p.part_keys[o] = L.valid(l, k) ? make_key(b, n) : 0;
                         } else {
-                            if (!Lists<PACKED, KP, NL>::exact_bits && b == 0)
+                            if (!Lists<REP, KP, NL>::exact_bits && b == 0)
                                 b = elem<DT>::load_bits(rowp, n);       // which zero it was
                             const int64_t o = ((int64_t)row * p.Kprime + k) * p.B + bucket;
                             elem<DT>::store_bits(p.surv_vals, o, b);
@@ -395,23 +471,25 @@ struct ApproxKernel {
     }
 };
 
-template <typename DT, int KP, int V, int R, bool PACKED>
-__global__ void __launch_bounds__(1024) approx_topk_kernel(ApproxParams p) {
+// The sorted-batch representation holds two K'-lists of 64-bit keys per lane and is only
+// launched with at most 256 lanes per workgroup, which lets it use the larger register budget.
+template <typename DT, int KP, int V, int R, int REP>
+__global__ void __launch_bounds__(REP == 2 ? 256 : 1024) approx_topk_kernel(ApproxParams p) {
     extern __shared__ uint64_t atk_lds[];
-    ApproxKernel<DT, KP, V, R, PACKED>::run(p, atk_lds);
+    ApproxKernel<DT, KP, V, R, REP>::run(p, atk_lds);
 }
 
-// Host-side launcher, one explicit instantiation per supported (dtype, KP, V, R, PACKED).
-template <typename DT, int KP, int V, int R, bool PACKED>
+// Host-side launcher, one explicit instantiation per supported (dtype, KP, V, R, REP).
+template <typename DT, int KP, int V, int R, int REP>
 hipError_t launch_approx(const ApproxParams& p, int grid, int block, size_t lds_bytes,
                          hipStream_t stream);
 
-#define ATK_DEFINE_LAUNCH(DT, KP, V, R, PACKED)                                                 \
+#define ATK_DEFINE_LAUNCH(DT, KP, V, R, REP)                                                    \
     template <>                                                                                 \
-    hipError_t launch_approx<DT, KP, V, R, PACKED>(const ApproxParams& p, int grid, int block,  \
+    hipError_t launch_approx<DT, KP, V, R, REP>(const ApproxParams& p, int grid, int block,     \
                                                    size_t lds_bytes, hipStream_t stream) {      \
-        allow_large_lds((const void*)approx_topk_kernel<DT, KP, V, R, PACKED>, lds_bytes);      \
-        hipLaunchKernelGGL((approx_topk_kernel<DT, KP, V, R, PACKED>),                          \
+        allow_large_lds((const void*)approx_topk_kernel<DT, KP, V, R, REP>, lds_bytes);         \
+        hipLaunchKernelGGL((approx_topk_kernel<DT, KP, V, R, REP>),                             \
                            dim3(grid, p.mode == 2 ? p.nseg : 1), dim3(block),                   \
                            lds_bytes, stream, p);                                               \
         return hipGetLastError();                                                               \

@@ -260,7 +260,7 @@ def test_split_path_few_long_rows(atk):
     # the shape of the paper's Table 1: 8 rows x 262144, K=1024; rows are cut into segments
     for dtype in (torch.float32, torch.bfloat16):
         x = workloads.gaussian(8, 262144, seed=15, dtype=dtype)
-        for B, Kp in [(1024, 4), (8192, 1), (512, 6), (2048, 2)]:
+        for B, Kp in [(1024, 4), (8192, 1), (512, 6), (2048, 2), (256, 16)]:
             st, text = atk.describe_plan(dtype, 8, 262144, 1024, Kp, B)
             assert st == atk.OK
             if (B, Kp) == (1024, 4):
