@@ -309,6 +309,29 @@ def test_results_do_not_depend_on_launch_geometry(atk, monkeypatch):
     monkeypatch.delenv("ATK_LANES_PER_ROW")
 
 
+def test_results_do_not_depend_on_the_list_representation(atk, monkeypatch):
+    # packed 32-bit keys vs value+step lists vs several rows per wavefront (bf16), and sorted
+    # batches vs position-by-position updates (fp32, K'=16): identical bits
+    xb = workloads.gaussian(1100, 4096, seed=22, dtype=torch.bfloat16).to(DEV)
+    for (K, Kp, B) in [(200, 4, 128), (300, 8, 64), (64, 1, 1024)]:
+        base = atk.approx_topk(xb, K, Kp, B)
+        for env in ({"ATK_NO_PACKED": "1"}, {"ATK_NO_SUBWAVE": "1"}, {"ATK_LANES_PER_ROW": "128"}):
+            for k, v in env.items():
+                monkeypatch.setenv(k, v)
+            other = atk.approx_topk(xb, K, Kp, B)
+            torch.cuda.synchronize()
+            for k in env:
+                monkeypatch.delenv(k)
+            assert torch.equal(base[1], other[1]) and torch.equal(base[0], other[0]), (K, Kp, B, env)
+    xf = workloads.gaussian(64, 32768, seed=23).to(DEV)
+    base = atk.approx_topk(xf, 500, 16, 128)
+    monkeypatch.setenv("ATK_BATCH_MIN_KP", "64")
+    other = atk.approx_topk(xf, 500, 16, 128)
+    torch.cuda.synchronize()
+    monkeypatch.delenv("ATK_BATCH_MIN_KP")
+    assert torch.equal(base[1], other[1]) and torch.equal(base[0], other[0])
+
+
 # ---------------------------------------------------------------------------------------
 # full benchmark sizes, in the launch configuration bench.py times: oracle on sampled rows,
 # structural properties on every row
