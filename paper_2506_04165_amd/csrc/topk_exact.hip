@@ -98,7 +98,8 @@ __global__ void __launch_bounds__(1024) topk_exact_kernel(TopkParams p) {
         for (int i = tid; i < kSelectBins; i += T) hist[i] = 0;
         __syncthreads();
         constexpr int VE = 16 / elem<DT>::size;
-        const int chunk = T * VE * 2;
+        // vectors per lane and chunk: more in flight on long rows, early lower bound on short ones
+        const int chunk = T * VE * (N >= 131072 ? 8 : (N >= 32768 ? 4 : 1));
         uint32_t dmin = 0;
         int next_update = chunk;
         for (int base = 0; base < N; base += chunk) {
