@@ -157,6 +157,15 @@ static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, in
             if (G >= kMaxLanes) { pl.status = ATK_UNSUPPORTED; return pl; }
             G <<= 1;
         }
+        // Short lists: half the lanes with twice the lists each (wider loads, fewer waves per row)
+        // measured 3-5 % faster as long as the chip stays full and a lane holds at most 8 entries.
+        if (env_int("ATK_LANES_PER_ROW", 0) == 0 && G >= 128 && NL * 2 * KP <= 8 && B % (NL * 2) == 0 &&
+            rows * (int64_t)(G / 2 / 64) >= kTargetWaves &&
+            find_variant(dtype, KP, NL * 2, false, aligned_for) != nullptr &&
+            find_variant(dtype, KP, NL * 2, false, aligned_for)->V > 1) {
+            G >>= 1;
+            NL <<= 1;
+        }
     }
     // bf16 rows whose indices fit 16 bits: value and index share one 32-bit key
     // (such variants only exist for the plain fused route with at most 1024 candidates per row)
