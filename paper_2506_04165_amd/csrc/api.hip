@@ -301,7 +301,12 @@ static int run_exact(const void* values, const int32_t* payload, int dtype, int6
     if (K > kExactMaxK) return ATK_UNSUPPORTED;
     TopkParams tp{};
     tp.values = values; tp.payload = payload; tp.row_stride = row_stride;
-    tp.rows = (int)rows; tp.N = (int)N; tp.K = K; tp.cap = kExactCap;
+    tp.rows = (int)rows; tp.N = (int)N; tp.K = K;
+    // LDS key buffer: room for 4K keys (members + candidates of the threshold digit), within
+    // [1024, 4096]; a small buffer lets more rows share a CU
+    tp.cap = pow2_ceil(4 * (int64_t)K);
+    if (tp.cap < 1024) tp.cap = 1024;
+    if (tp.cap > kExactCap) tp.cap = kExactCap;
     tp.out_vals = out_vals; tp.out_idx = out_idx;
     hipError_t e = launch_topk_exact(tp, dtype, exact_threads(N), st);
     return e == hipSuccess ? ATK_OK : hip_fail(e);
