@@ -243,6 +243,16 @@ def test_zero_rows(atk):
     assert v.shape == (0, 8)
 
 
+def test_largest_fused_candidate_set(atk):
+    # B*K' = 16384 candidates per row: the most the fused kernel keeps in LDS (128 KB of keys)
+    N, B, Kp, K = 32768, 2048, 8, 2000
+    st, text = atk.describe_plan(torch.float32, 3, N, K, Kp, B)
+    assert st == atk.OK and text.startswith("fused") and "cand=16384" in text, text
+    check_approx(atk, workloads.gaussian(3, N, seed=17), K, Kp, B)
+    check_approx(atk, workloads.heavy_ties(3, N, seed=18, symbols=7), K, Kp, B)
+    check_approx(atk, workloads.gaussian(3, N, seed=19, dtype=torch.bfloat16), K, Kp, B)
+
+
 def test_unfused_path_through_workspace(atk):
     # B*K' = 32768 survivors per row do not fit the fused kernel's LDS: two launches + workspace
     N, B, Kp, K = 131072, 2048, 16, 300
