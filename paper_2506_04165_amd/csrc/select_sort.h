@@ -23,61 +23,99 @@ constexpr int kSelectBins = 2048;
 // a compaction buffer of kWaveSortMaxKeys keys (the histogram aliases it) + control words.
 constexpr int kSelectScratchBytes = kWaveSortMaxKeys * 8 + 128;
 
+// Value of `x` in lane (lane ^ m).  Distances that a DPP pattern can express (neighbours in a
+// quad, mirror images inside 4, 8 or 16 lanes) are plain vector moves; the rest go through the
+// cross-lane permute.  m is a constant after unrolling, so only one form survives.
+__device__ __forceinline__ uint32_t lane_xor(uint32_t x, int m) {
+    if (m == 1) return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0xB1, 0xF, 0xF, true);   // quad_perm [1,0,3,2]
+    if (m == 2) return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0x4E, 0xF, 0xF, true);   // quad_perm [2,3,0,1]
+    if (m == 3) return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0x1B, 0xF, 0xF, true);   // quad_perm [3,2,1,0]
+    if (m == 7) return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0x141, 0xF, 0xF, true);  // row_half_mirror
+    if (m == 15) return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0x140, 0xF, 0xF, true); // row_mirror
+    return (uint32_t)__shfl_xor((unsigned)x, m, kWave);
+}
+template <typename KeyT>
+__device__ __forceinline__ KeyT lane_xor_key(KeyT x, int m) {
+    if constexpr (sizeof(KeyT) == 4) return lane_xor((uint32_t)x, m);
+    else return ((uint64_t)lane_xor((uint32_t)(x >> 32), m) << 32) | lane_xor((uint32_t)x, m);
+}
+
+// Bitonic sorting network in the form whose comparators all point the same way: level kk first
+// compares every element e with its mirror image e ^ (kk-1) inside the block, then with
+// e ^ (kk/4), ..., e ^ 1; the lower index always keeps the greater key.
 template <int R, typename KeyT = uint64_t>
 struct WaveSort {
-    static constexpr int LOGN = (R == 1 ? 6 : R == 2 ? 7 : R == 4 ? 8 : R == 8 ? 9 : 10);
+    static constexpr int LOGR = (R == 1 ? 0 : R == 2 ? 1 : R == 4 ? 2 : R == 8 ? 3 : 4);
+    static constexpr int LOGN = LOGR + 6;
     static_assert(R == 1 || R == 2 || R == 4 || R == 8 || R == 16, "R must be 1,2,4,8,16");
+
+    __device__ static __forceinline__ void cex(KeyT& hi, KeyT& lo) {     // hi := greater, lo := smaller
+        const KeyT a = hi, b = lo;
+        if constexpr (sizeof(KeyT) == 4) { hi = max(a, b); lo = min(a, b); }
+        else { const bool sw = a < b; hi = sw ? b : a; lo = sw ? a : b; }
+    }
+    // The greater (want_max) or the smaller of a and b; want_max differs from lane to lane.  The
+    // 32-bit form merges max and min through a lane mask (one v_bfi) so that no branch on
+    // want_max can be formed around a run of these.
+    __device__ static __forceinline__ KeyT pick(KeyT a, KeyT b, bool want_max) {
+        if constexpr (sizeof(KeyT) == 4) {
+            const uint32_t m = want_max ? 0xffffffffu : 0u;
+            return (m & max(a, b)) | (~m & min(a, b));
+        } else {
+            const bool take_b = (b > a) == want_max;
+            return take_b ? b : a;
+        }
+    }
+
+    // One half-cleaner step at element distance JJ.
+    template <int JJ>
+    __device__ static __forceinline__ void step(KeyT (&k)[R], int lane) {
+        if constexpr (JJ < R) {
+#pragma unroll
+            for (int j = 0; j < R; ++j)
+                if ((j & JJ) == 0) cex(k[j], k[j | JJ]);
+        } else {
+            constexpr int M = JJ / R;
+            const bool lower = (lane & M) == 0;
+#pragma unroll
+            for (int j = 0; j < R; ++j) k[j] = pick(k[j], lane_xor_key<KeyT>(k[j], M), lower);
+        }
+    }
+    template <int LJ>
+    __device__ static __forceinline__ void steps_down(KeyT (&k)[R], int lane) {
+        if constexpr (LJ >= 0) {
+            step<(1 << LJ)>(k, lane);
+            steps_down<LJ - 1>(k, lane);
+        }
+    }
+    // Level KK = 2^LK: the mirror step, then the half-cleaners; then the next level.  Templates
+    // rather than loops: every distance must be a compile-time constant (register indices, DPP
+    // patterns), whatever the unroller decides.
+    template <int LK>
+    __device__ static __forceinline__ void levels(KeyT (&k)[R], int lane) {
+        if constexpr (LK <= LOGN) {
+            constexpr int KK = 1 << LK;
+            if constexpr (KK <= R) {
+#pragma unroll
+                for (int j = 0; j < R; ++j)
+                    if ((j & (KK >> 1)) == 0) cex(k[j], k[j ^ (KK - 1)]);
+            } else {
+                constexpr int LM = KK / R - 1;                    // lane part of the mirror mask
+                const bool lower = (lane & ((KK >> 1) / R)) == 0;
+                KeyT recv[R];
+#pragma unroll
+                for (int j = 0; j < R; ++j) recv[j] = lane_xor_key<KeyT>(k[j ^ (R - 1)], LM);
+#pragma unroll
+                for (int j = 0; j < R; ++j) k[j] = pick(k[j], recv[j], lower);
+            }
+            steps_down<LK - 2>(k, lane);
+            levels<LK + 1>(k, lane);
+        }
+    }
 
     // Element e = lane*R + j lives in k[j] of `lane`.  After the call e is the rank: k[j] of
     // lane l is the (l*R + j)-th greatest key.
-    __device__ static void sort(KeyT (&k)[R]) {
-        const int lane = __lane_id();
-#pragma unroll
-        for (int lk = 1; lk <= LOGN; ++lk) {
-            const int kk = 1 << lk;
-#pragma unroll
-            for (int lj = lk - 1; lj >= 0; --lj) {
-                const int jj = 1 << lj;
-                if (jj < R) {
-                    // partners are registers j and j|jj of the same lane
-#pragma unroll
-                    for (int j = 0; j < R; ++j) {
-                        if (j & jj) continue;
-                        // descending block when bit kk of e is clear
-                        const bool desc = kk < R ? ((j & kk) == 0)
-                                                 : (kk >= kWave * R ? true : ((lane & (kk / R)) == 0));
-                        const KeyT a = k[j], b = k[j | jj];
-                        if constexpr (sizeof(KeyT) == 4) {
-                            const KeyT hi = max(a, b), lo = min(a, b);
-                            k[j] = desc ? hi : lo;
-                            k[j | jj] = desc ? lo : hi;
-                        } else {
-                            const bool sw = (a < b) == desc;
-                            k[j] = sw ? b : a;
-                            k[j | jj] = sw ? a : b;
-                        }
-                    }
-                } else {
-                    const int m = jj / R;                       // partner lane = lane ^ m
-                    const bool lower = (lane & m) == 0;
-                    const bool desc = kk >= kWave * R ? true : ((lane & (kk / R)) == 0);
-                    const bool want_max = lower == desc;
-#pragma unroll
-                    for (int j = 0; j < R; ++j) {
-                        const KeyT a = k[j];
-                        if constexpr (sizeof(KeyT) == 4) {
-                            const KeyT b = __shfl_xor((unsigned)a, m, kWave);
-                            k[j] = want_max ? max(a, b) : min(a, b);
-                        } else {
-                            const KeyT b = __shfl_xor((unsigned long long)a, m, kWave);
-                            const bool take = (b > a) == want_max;   // a == b only for empty keys
-                            k[j] = (a == b) ? a : (take ? b : a);
-                        }
-                    }
-                }
-            }
-        }
-    }
+    __device__ static void sort(KeyT (&k)[R]) { levels<1>(k, __lane_id()); }
 };
 
 // Decode and write the first K of the sorted keys of one wavefront (rank e = lane*R + j).
