@@ -7,8 +7,8 @@ no kernels, headers, helpers, tables or constants.
 Two parts:
 
 * thin ``ctypes`` bindings to ``atk_oracle.c`` (the definition of the method,
-  Section 6.1 Steps 1-4, written out with ``qsort``), taking and returning
-  NumPy arrays;
+  Section 6.1 Steps 1-4, written out with ``qsort``, and the same applied to the
+  inner products of Section 7.3), taking and returning NumPy arrays;
 * the theory of Section 6.2 / Theorem 1 in exact arithmetic: the closed-form
   expected recall, the K'=1 lower bound and bucket formula, a Monte-Carlo
   estimator of the same expectation, and the two recall measures used when
@@ -59,6 +59,10 @@ def _load():
         lib.atk_oracle_topk.argtypes = [vp, ci, i64, i64, i64, i64, vp, vp]
         lib.atk_oracle_topk.restype = ci
         lib.atk_oracle_num_threads.restype = ci
+        lib.atk_oracle_mips_scores.argtypes = [vp, vp, i64, i64, i64, vp]
+        lib.atk_oracle_mips_scores.restype = ci
+        lib.atk_oracle_mips_approx_topk.argtypes = [vp, vp, i64, i64, i64, i64, i64, i64, vp, vp]
+        lib.atk_oracle_mips_approx_topk.restype = ci
         _lib = lib
     return _lib
 
@@ -123,6 +127,41 @@ def stage1(values: np.ndarray, Kprime: int, B: int):
                                    sv.ctypes.data, si.ctypes.data)
     _raise(rc, "oracle stage1")
     return sv, si
+
+
+def _prep_vectors(queries: np.ndarray, database: np.ndarray):
+    if queries.ndim != 2 or database.ndim != 2 or queries.shape[1] != database.shape[1]:
+        raise ValueError("queries must be [Q, D] and database [N, D]")
+    if queries.dtype != np.uint16 or database.dtype != np.uint16:
+        raise TypeError("vectors are bf16 bit patterns held in uint16 arrays")
+    return np.ascontiguousarray(queries), np.ascontiguousarray(database)
+
+
+def mips_scores(queries: np.ndarray, database: np.ndarray) -> np.ndarray:
+    """Section 7.3: the [Q, N] inner products of bf16 vectors, each correctly rounded to float32."""
+    queries, database = _prep_vectors(queries, database)
+    Q, D = queries.shape
+    N = database.shape[0]
+    scores = np.empty((Q, N), dtype=np.float32)
+    rc = _load().atk_oracle_mips_scores(queries.ctypes.data, database.ctypes.data, Q, N, D,
+                                        scores.ctypes.data)
+    _raise(rc, "oracle mips_scores")
+    return scores
+
+
+def mips_approx_topk(queries: np.ndarray, database: np.ndarray, K: int, Kprime: int, B: int):
+    """Section 7.3: Steps 1-4 of Section 6.1 on every row of the score matrix, which is never
+    stored as a whole.  Returns (scores[Q,K] float32, idx[Q,K] int32)."""
+    queries, database = _prep_vectors(queries, database)
+    Q, D = queries.shape
+    N = database.shape[0]
+    out_vals = np.empty((Q, K), dtype=np.float32)
+    out_idx = np.empty((Q, K), dtype=np.int32)
+    rc = _load().atk_oracle_mips_approx_topk(queries.ctypes.data, database.ctypes.data, Q, N, D,
+                                             K, Kprime, B, out_vals.ctypes.data,
+                                             out_idx.ctypes.data)
+    _raise(rc, "oracle mips_approx_topk")
+    return out_vals, out_idx
 
 
 # --------------------------------------------------------------------------

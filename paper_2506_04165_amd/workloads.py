@@ -84,6 +84,29 @@ def mips_scores(rows: int, N: int, seed: int, device="cpu", dim: int = 128):
     return (q @ d.t()).contiguous()
 
 
+def mips_vectors(Q: int, N: int, seed: int, device="cpu", dim: int = 128, kind: str = "unit"):
+    """Query and database vectors for the matmul-fused entry point, as bf16 tensors [Q, dim] and
+    [N, dim] (Section 7.3: one million 128-dimensional vectors, 1024 queries).
+
+    kind "unit": Gaussian directions normalised to unit length, rounded to bf16 (inner products
+    near N(0, 1/dim)).  kind "integer": entries drawn from {-2,...,2}; every product and every
+    partial sum is a small integer, so the inner products are the same in any floating-point
+    format and any summation order, and they tie heavily.
+    """
+    g = _gen(seed, device)
+    if kind == "unit":
+        q = torch.randn(Q, dim, generator=g, device=device, dtype=torch.float32)
+        d = torch.randn(N, dim, generator=g, device=device, dtype=torch.float32)
+        q = q / q.norm(dim=1, keepdim=True)
+        d = d / d.norm(dim=1, keepdim=True)
+    elif kind == "integer":
+        q = torch.randint(-2, 3, (Q, dim), generator=g, device=device).to(torch.float32)
+        d = torch.randint(-2, 3, (N, dim), generator=g, device=device).to(torch.float32)
+    else:
+        raise ValueError(kind)
+    return q.to(torch.bfloat16).contiguous(), d.to(torch.bfloat16).contiguous()
+
+
 def adversarial_sorted(rows: int, N: int, seed: int, device="cpu", K: int = 256, B: int = 256,
                        hot_buckets: int = 4):
     """Ascending-sorted N(0,1) rows whose K greatest values all sit in `hot_buckets` adjacent
