@@ -138,6 +138,41 @@ int atk_describe_plan(int dtype, int64_t rows, int64_t N, int K, int Kprime, int
                       size_t buflen);
 
 /*
+ * Maximum inner-product search with the matrix product fused into stage 1 (Section 7.3; appendix
+ * "Matmul-fused implementation"): the rows whose approximate Top-K is wanted are the scores
+ *   score[r][n] = sum_d queries[r][d] * database[n][d],   r < Q, n < N,
+ * formed on the matrix cores with binary32 accumulation and consumed by the K'-list update of
+ * Section 6.1 Steps 1-2 (bucket of score n = n mod B) without ever being stored; Steps 3-4 follow
+ * in a second launch.  Same order and tie rule as atk_approx_topk on the score row.
+ *   queries    device, [Q, D] bf16, vectors contiguous, 16-byte aligned
+ *   database   device, [N, D] bf16, vectors contiguous, 16-byte aligned (vector-major, not the
+ *              [D, N] operand of the paper's listing)
+ *   dtype      ATK_BF16 (others: ATK_UNSUPPORTED);  D one of 64, 128, 256;  B a multiple of 32
+ *              dividing N;  1 <= K' <= min(K, N/B, 4);  K <= B*K' <= 16384
+ *   out_vals   device, [Q, K] binary32 scores, greatest first; a zero score is +0.0
+ *   out_idx    device, [Q, K] int32 database positions
+ *   workspace  device, at least atk_mips_workspace_bytes(...) bytes, 8-byte aligned; always
+ *              needed (partial lists); caller-owned, may be reused after the stream reaches
+ *              the end of this call
+ * Precondition: finite inputs (no NaN score).  A score differs from the exactly rounded inner
+ * product by the rounding of a binary32 accumulation of D products; results that hinge on
+ * scores closer than that are decided by the computed scores.
+ * Returns ATK_OK, ATK_INVALID_ARG, ATK_UNSUPPORTED, ATK_WORKSPACE_TOO_SMALL or ATK_HIP_ERROR;
+ * asynchronous on `stream`; Q == 0 is a legal no-op.
+ */
+int atk_mips_approx_topk(const void* queries, const void* database, int dtype, int64_t Q, int64_t N,
+                         int64_t D, int K, int Kprime, int B, float* out_vals, int32_t* out_idx,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* Workspace bytes atk_mips_approx_topk needs; SIZE_MAX on illegal or unsupported arguments.
+ * Host only. */
+size_t atk_mips_workspace_bytes(int dtype, int64_t Q, int64_t N, int64_t D, int K, int Kprime, int B);
+
+/* Launch plan of atk_mips_approx_topk as text (tile shape, grid, segments).  Host only. */
+int atk_mips_describe_plan(int dtype, int64_t Q, int64_t N, int64_t D, int K, int Kprime, int B,
+                           char* buf, size_t buflen);
+
+/*
  * Vector-ALU throughput probe (appendix "Estimating peak VPU throughput" redone for MI355X; the
  * measurement behind the ridge point of Section 2.3 that bounds K').  Streams n_words int32
  * words and applies `ops` dependent operations to each:

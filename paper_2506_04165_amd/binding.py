@@ -24,7 +24,8 @@ SIZE_MAX = ctypes.c_size_t(-1).value
 
 EXPORTS = [
     "atk_approx_topk", "atk_topk", "atk_approx_topk_stage1", "atk_workspace_bytes",
-    "atk_expected_recall", "atk_select_params", "atk_approx_topk_recall", "atk_describe_plan", "atk_valu_probe", "atk_status_string", "atk_last_hip_error",
+    "atk_expected_recall", "atk_select_params", "atk_approx_topk_recall", "atk_describe_plan", "atk_valu_probe",
+    "atk_mips_approx_topk", "atk_mips_workspace_bytes", "atk_mips_describe_plan", "atk_status_string", "atk_last_hip_error",
     "atk_version",
 ]
 
@@ -63,6 +64,12 @@ def _load() -> ctypes.CDLL:
     lib.atk_valu_probe.restype = ci
     lib.atk_describe_plan.argtypes = [ci, i64, i64, ci, ci, ci, ctypes.c_char_p, sz]
     lib.atk_describe_plan.restype = ci
+    lib.atk_mips_approx_topk.argtypes = [vp, vp, ci, i64, i64, i64, ci, ci, ci, vp, vp, vp, sz, vp]
+    lib.atk_mips_approx_topk.restype = ci
+    lib.atk_mips_workspace_bytes.argtypes = [ci, i64, i64, i64, ci, ci, ci]
+    lib.atk_mips_workspace_bytes.restype = sz
+    lib.atk_mips_describe_plan.argtypes = [ci, i64, i64, i64, ci, ci, ci, ctypes.c_char_p, sz]
+    lib.atk_mips_describe_plan.restype = ci
     lib.atk_status_string.argtypes = [ci]
     lib.atk_status_string.restype = ctypes.c_char_p
     lib.atk_last_hip_error.restype = ctypes.c_char_p
@@ -194,6 +201,48 @@ def topk(values: torch.Tensor, K: int, out=None):
                       out_idx.data_ptr(), None, 0, _stream_ptr(values.device))
     if st != OK:
         raise AtkError(st, "atk_topk")
+    return out_vals, out_idx
+
+
+def mips_workspace_bytes(Q: int, N: int, D: int, K: int, Kprime: int, B: int) -> int:
+    return int(lib.atk_mips_workspace_bytes(BF16, Q, N, D, K, Kprime, B))
+
+
+def mips_describe_plan(Q: int, N: int, D: int, K: int, Kprime: int, B: int):
+    buf = ctypes.create_string_buffer(512)
+    st = lib.atk_mips_describe_plan(BF16, Q, N, D, K, Kprime, B, buf, 512)
+    return st, buf.value.decode()
+
+
+def mips_approx_topk(queries: torch.Tensor, database: torch.Tensor, K: int, Kprime: int, B: int,
+                     out=None, workspace=None):
+    """Approximate Top-K of queries @ database.T without storing the scores (bf16 [Q,D], [N,D]).
+    Returns (scores[Q,K] float32, idx[Q,K] int32)."""
+    for t in (queries, database):
+        if not t.is_cuda:
+            raise ValueError("vectors must live on the GPU")
+        if t.dim() != 2 or t.dtype != torch.bfloat16 or not t.is_contiguous():
+            raise ValueError("vectors must be contiguous bf16 [count, D] tensors")
+    if queries.shape[1] != database.shape[1]:
+        raise ValueError("queries and database differ in D")
+    Q, D = queries.shape
+    N = database.shape[0]
+    if out is None:
+        out_vals = torch.empty((Q, K), dtype=torch.float32, device=queries.device)
+        out_idx = torch.empty((Q, K), dtype=torch.int32, device=queries.device)
+    else:
+        out_vals, out_idx = out
+    need = lib.atk_mips_workspace_bytes(BF16, Q, N, D, K, Kprime, B)
+    ws_ptr, ws_bytes = None, 0
+    if need != SIZE_MAX and need > 0:
+        if workspace is None or workspace.numel() * workspace.element_size() < need:
+            workspace = torch.empty(need, dtype=torch.uint8, device=queries.device)
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    st = lib.atk_mips_approx_topk(queries.data_ptr(), database.data_ptr(), BF16, Q, N, D, K, Kprime,
+                                  B, out_vals.data_ptr(), out_idx.data_ptr(), ws_ptr, ws_bytes,
+                                  _stream_ptr(queries.device))
+    if st != OK:
+        raise AtkError(st, "atk_mips_approx_topk")
     return out_vals, out_idx
 
 

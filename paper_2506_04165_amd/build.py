@@ -22,6 +22,7 @@ SOURCES = [
     "api.hip",
     "topk_exact.hip",
     "approx_finish.hip",
+    "mips_fused.hip",
     "valu_probe.hip",
     "approx_inst_f32_small.hip",
     "approx_inst_f32_wide.hip",

@@ -9,6 +9,7 @@
 #include "../../include/atk.h"
 #include "approx_instances.h"
 #include "approx_finish.h"
+#include "mips_fused.h"
 #include "approx_kernel.h"
 #include "topk_exact.h"
 
@@ -435,6 +436,94 @@ size_t atk_workspace_bytes(int op, int dtype, int64_t rows, int64_t N, int K, in
     Plan pl = make_plan(nullptr, dtype, rows, N, N, K, Kprime, B, false);
     if (pl.status) return SIZE_MAX;
     return pl.workspace;
+}
+
+// ---- matmul-fused path (Section 7.3) ---------------------------------------------------------
+namespace {
+
+struct MipsPlan {
+    int status = ATK_OK;
+    int KP = 0, nslab = 0, nqt = 0, nseg = 1, seg_steps = 0, Cpad = 0;
+    size_t workspace = 0;
+};
+
+constexpr int kMipsTargetWorkgroups = 512;   // 2 wavefronts per SIMD on 256 CUs
+constexpr int kMipsMinSegmentSteps = 64;     // shorter walks only refill lists
+
+MipsPlan make_mips_plan(int dtype, int64_t Q, int64_t N, int64_t D, int K, int Kprime, int B) {
+    MipsPlan pl;
+    if (Q < 0 || N <= 0 || N > 0x7fffffffLL || D <= 0) { pl.status = ATK_INVALID_ARG; return pl; }
+    if ((pl.status = validate_method(N, K, Kprime, B))) return pl;
+    if (dtype != ATK_BF16 || (D != 64 && D != 128 && D != 256) || B % kMipsSlab || Kprime > 4 ||
+        (int64_t)B * Kprime > 16384 || Q > 0x7fffffffLL / 2) {
+        pl.status = ATK_UNSUPPORTED;
+        return pl;
+    }
+    pl.KP = Kprime <= 2 ? Kprime : 4;
+    pl.nslab = B / kMipsSlab;
+    pl.nqt = (int)((Q + kMipsQueryTile - 1) / kMipsQueryTile);
+    const int nsteps = (int)(N / B);
+    const int64_t pairs = (int64_t)pl.nslab * (pl.nqt > 0 ? pl.nqt : 1);
+    int nseg = (int)((kMipsTargetWorkgroups + pairs - 1) / pairs);
+    nseg = std::min(nseg, std::max(1, nsteps / kMipsMinSegmentSteps));
+    nseg = std::max(1, std::min(nseg, 16));
+    pl.seg_steps = (nsteps + nseg - 1) / nseg;
+    pl.nseg = (nsteps + pl.seg_steps - 1) / pl.seg_steps;
+    pl.Cpad = (int)pow2_ceil((int64_t)B * Kprime);
+    pl.workspace = (size_t)Q * pl.nseg * Kprime * B * 8;
+    return pl;
+}
+
+}  // namespace
+
+size_t atk_mips_workspace_bytes(int dtype, int64_t Q, int64_t N, int64_t D, int K, int Kprime, int B) {
+    MipsPlan pl = make_mips_plan(dtype, Q, N, D, K, Kprime, B);
+    return pl.status ? SIZE_MAX : pl.workspace;
+}
+
+int atk_mips_approx_topk(const void* queries, const void* database, int dtype, int64_t Q, int64_t N,
+                         int64_t D, int K, int Kprime, int B, float* out_vals, int32_t* out_idx,
+                         void* workspace, size_t workspace_bytes, void* stream) {
+    MipsPlan pl = make_mips_plan(dtype, Q, N, D, K, Kprime, B);
+    if (pl.status) return pl.status;
+    if (Q == 0) return ATK_OK;
+    if (!queries || !database || !out_vals || !out_idx) return ATK_INVALID_ARG;
+    if ((uintptr_t)queries % 16 || (uintptr_t)database % 16 || (uintptr_t)out_vals % 4 ||
+        (uintptr_t)out_idx % 4)
+        return ATK_INVALID_ARG;
+    if (!workspace || workspace_bytes < pl.workspace) return ATK_WORKSPACE_TOO_SMALL;
+    if ((uintptr_t)workspace % 8) return ATK_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+
+    MipsParams p{};
+    p.queries = (const uint16_t*)queries; p.database = (const uint16_t*)database;
+    p.Q = (int)Q; p.N = (int)N; p.D = (int)D; p.Kprime = Kprime; p.B = B;
+    p.nsteps = (int)(N / B); p.nseg = pl.nseg; p.seg_steps = pl.seg_steps;
+    p.nslab = pl.nslab; p.nqt = pl.nqt;
+    p.part_keys = (uint64_t*)workspace;
+    hipError_t e = launch_mips_stage1(p, pl.KP, st);
+    if (e != hipSuccess) return hip_fail(e);
+
+    FinishParams f{};
+    f.part_keys = (const uint64_t*)workspace; f.values = nullptr; f.row_stride = 0;
+    f.rows = (int)Q; f.K = K; f.Kprime = Kprime; f.B = B; f.nseg = pl.nseg; f.Cpad = pl.Cpad;
+    f.out_vals = out_vals; f.out_idx = out_idx;
+    e = launch_finish(f, kFinishScores, pl.KP, st);
+    return e == hipSuccess ? ATK_OK : hip_fail(e);
+}
+
+int atk_mips_describe_plan(int dtype, int64_t Q, int64_t N, int64_t D, int K, int Kprime, int B,
+                           char* buf, size_t buflen) {
+    if (!buf || buflen == 0) return ATK_INVALID_ARG;
+    buf[0] = 0;
+    MipsPlan pl = make_mips_plan(dtype, Q, N, D, K, Kprime, B);
+    if (pl.status) return pl.status;
+    std::snprintf(buf, buflen,
+                  "mfma32x32x16 KP=%d slabs=%d query_tiles=%d segments=%d steps_per_segment=%d "
+                  "grid=%d block=256 cand=%d workspace=%zu",
+                  pl.KP, pl.nslab, pl.nqt, pl.nseg, pl.seg_steps, pl.nslab * pl.nqt * pl.nseg,
+                  pl.Cpad, pl.workspace);
+    return ATK_OK;
 }
 
 int atk_describe_plan(int dtype, int64_t rows, int64_t N, int K, int Kprime, int B, char* buf,

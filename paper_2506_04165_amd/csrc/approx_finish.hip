@@ -67,6 +67,7 @@ hipError_t launch_finish(const FinishParams& p, int dtype, int KP, hipStream_t s
     int threads = 64;
     while (threads < p.B && threads < 1024) threads <<= 1;
     if (threads < 256 && p.Cpad >= 1024) threads = 256;     // the sort wants more lanes than buckets
+    if (dtype == kFinishScores) return launch_for<score_t>(p, KP, threads, stream);
     return dtype == 0 ? launch_for<float>(p, KP, threads, stream)
                       : launch_for<bf16_t>(p, KP, threads, stream);
 }

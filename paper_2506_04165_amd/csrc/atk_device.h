@@ -52,6 +52,17 @@ template <> struct elem<bf16_t> {
     }
 };
 
+// binary32 scores that exist only inside keys (matmul-fused path): there is no stored array to
+// re-read, and a score that compares equal to zero is +0.0.
+struct score_t {};
+template <> struct elem<score_t> {
+    static constexpr int size = 4;
+    __device__ static uint32_t load_bits(const void*, int64_t) { return 0; }
+    __device__ static void store_bits(void* base, int64_t i, uint32_t b) {
+        ((uint32_t*)base)[i] = b;
+    }
+};
+
 // A load of V consecutive elements as one memory instruction (2, 4, 8 or 16 bytes).
 template <int BYTES> struct vec_bytes;
 template <> struct vec_bytes<2>  { using type = uint16_t; };

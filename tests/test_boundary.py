@@ -145,3 +145,32 @@ def test_binding_refuses_cpu_tensors():
         atk.approx_topk(x, 4, 1, 8)
     with pytest.raises(ValueError):
         atk.topk(x, 4)
+
+
+def test_mips_validation_and_plan():
+    m = atk.lib.atk_mips_approx_topk
+    BF = 1
+    ok = dict(Q=4, N=4096, D=128, K=64, Kp=2, B=64)
+    def call(queries=FAKE, database=FAKE, dtype=BF, out_vals=FAKE, out_idx=FAKE, ws=FAKE, ws_bytes=1 << 30, **kw):
+        a = dict(ok); a.update(kw)
+        return m(queries, database, dtype, a["Q"], a["N"], a["D"], a["K"], a["Kp"], a["B"],
+                 out_vals, out_idx, ws, ws_bytes, None)
+    assert call(Q=0, queries=None, database=None, out_vals=None, out_idx=None, ws=None, ws_bytes=0) == atk.OK
+    assert call(queries=None) == atk.INVALID_ARG
+    assert call(database=FAKE + 2) == atk.INVALID_ARG
+    assert call(N=4095) == atk.INVALID_ARG           # B does not divide N
+    assert call(K=200) == atk.INVALID_ARG            # K > B*K'
+    assert call(Kp=0) == atk.INVALID_ARG
+    assert call(D=0) == atk.INVALID_ARG
+    assert call(dtype=0) == atk.UNSUPPORTED          # fp32 vectors
+    assert call(D=96) == atk.UNSUPPORTED
+    assert call(B=16, K=16) == atk.UNSUPPORTED       # B not a multiple of 32
+    assert call(Kp=5, K=64) == atk.UNSUPPORTED
+    assert call(N=1 << 20, B=8192, Kp=4, K=64) == atk.UNSUPPORTED   # B*K' beyond stage 2's LDS
+    need = atk.mips_workspace_bytes(4, 4096, 128, 64, 2, 64)
+    assert need == 4 * 1 * 2 * 64 * 8
+    assert call(ws=None, ws_bytes=0) == atk.WORKSPACE_TOO_SMALL
+    assert call(ws_bytes=need - 1) == atk.WORKSPACE_TOO_SMALL
+    assert atk.mips_workspace_bytes(4, 4096, 96, 64, 2, 64) == atk.SIZE_MAX
+    st, text = atk.mips_describe_plan(1024, 1 << 20, 128, 1024, 4, 1024)
+    assert st == atk.OK and text.startswith("mfma32x32x16") and "workspace=67108864" in text
