@@ -467,6 +467,8 @@ MipsPlan make_mips_plan(int dtype, int64_t Q, int64_t N, int64_t D, int K, int K
     int nseg = (int)((kMipsTargetWorkgroups + pairs - 1) / pairs);
     nseg = std::min(nseg, std::max(1, nsteps / kMipsMinSegmentSteps));
     nseg = std::max(1, std::min(nseg, 16));
+    const int forced = env_int("ATK_MIPS_SEGMENTS", 0);          // developer knob
+    if (forced >= 1 && forced <= 64 && forced <= nsteps) nseg = forced;
     pl.seg_steps = (nsteps + nseg - 1) / nseg;
     pl.nseg = (nsteps + pl.seg_steps - 1) / pl.seg_steps;
     pl.Cpad = (int)pow2_ceil((int64_t)B * Kprime);

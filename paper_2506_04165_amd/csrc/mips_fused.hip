@@ -12,9 +12,9 @@
 //     the row operand of v_mfma_f32_32x32x16_bf16; the query fragments are the column operand
 //     and stay in registers for the whole walk.  Each wavefront computes a 32 (buckets) x 32
 //     (queries) tile of binary32 scores per step: D/16 matrix instructions;
-//   * every score then updates its list (Algorithm 1 restated, as in the streaming kernel).
-//     For K' > 2 the update is skipped when no lane of the wavefront beats the tail of its
-//     list: after the first few dozen steps most scores fall at that test;
+//   * every score then updates its list (Algorithm 1 restated, branch-free; see ScoreLists).
+//     Skipping the update when no lane of the wavefront beats its list's tail was measured and
+//     is slower: one lane in 64 nearly always does, and the branches serialise the updates;
 //   * when there are too few (slab, tile) pairs to fill the chip the walk is cut into
 //     segments run by different workgroups; the per-bucket merge of the partial lists and
 //     Steps 3-4 are the finishing launch shared with the split streaming path;
@@ -32,6 +32,44 @@ namespace {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte move
+
+// The K' greatest scores each accumulator register has seen, greatest first, with the step at
+// which each arrived.  Scores are finite, so the empty entry is -inf and the values need no
+// compare-and-select: entry k becomes the median of (entry k-1, entry k, score), the head the
+// maximum (Algorithm 1's shift, as a clamp).  Only the steps follow the compare results.  A
+// strict compare keeps the earlier (lower-index) element ahead on ties.  Written without
+// branches on purpose: the 16 updates of a step are independent and interleave.
+template <int KP>
+struct ScoreLists {
+    float val[16][KP];
+    int32_t stp[16][KP];
+    __device__ __forceinline__ void init() {
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+#pragma unroll
+            for (int k = 0; k < KP; ++k) { val[i][k] = -__builtin_inff(); stp[i][k] = 0; }
+    }
+    __device__ __forceinline__ void insert(int i, float x, int32_t step) {
+        if constexpr (KP == 1) {       // measured: two selects on one compare beat max + select
+            const bool c0 = x > val[i][0];
+            val[i][0] = sel(c0, x, val[i][0]);
+            stp[i][0] = sel(c0, step, stp[i][0]);
+            return;
+        }
+        bool c[KP];
+#pragma unroll
+        for (int k = 0; k < KP; ++k) c[k] = x > val[i][k];
+#pragma unroll
+        for (int k = KP - 1; k >= 1; --k) {
+            stp[i][k] = sel(c[k - 1], stp[i][k - 1], sel(c[k], step, stp[i][k]));
+            val[i][k] = __builtin_amdgcn_fmed3f(val[i][k - 1], val[i][k], x);
+        }
+        stp[i][0] = sel(c[0], step, stp[i][0]);
+        val[i][0] = __builtin_amdgcn_fmed3f(val[i][0], x, __builtin_inff());   // max, as one instruction
+    }
+    __device__ __forceinline__ bool valid(int i, int k) const { return val[i][k] != -__builtin_inff(); }
+    __device__ __forceinline__ uint32_t bits(int i, int k) const { return __float_as_uint(val[i][k]); }
+};
 
 template <int KP, int KS>   // KS = D / 16: matrix instructions per tile
 __global__ void __launch_bounds__(256) mips_stage1_kernel(MipsParams p) {
@@ -71,51 +109,76 @@ __global__ void __launch_bounds__(256) mips_stage1_kernel(MipsParams p) {
         qf[s] = __builtin_bit_cast(bf16x8, w);
     }
 
-    Lists<0, KP, 16> L;
+    ScoreLists<KP> L;
     L.init();
 
     // ---- walk ------------------------------------------------------------------------------------
     // the tile of step j is 32*D*2 contiguous bytes; thread t moves the 16-byte pieces t + 256u
+    // Software pipeline: the matrix instructions of step j+1 are issued before the list updates
+    // of step j, so the matrix core and the LDS work under the vector ALU's shadow.
     u32x4 pre[NLD];
     const char* src = (const char*)p.database + ((size_t)j0 * p.B + b0) * (size_t)(D * 2) + tid * 16;
     const size_t step_bytes = (size_t)p.B * (D * 2);
-    if (j0 < j1) {
+    auto fetch = [&]() {
 #pragma unroll
         for (int u = 0; u < NLD; ++u) pre[u] = *(const u32x4*)(src + u * 4096);
-    }
-    int buf = 0;
-    for (int j = j0; j < j1; ++j) {
+        src += step_bytes;
+    };
+    auto stage = [&](int b) {
 #pragma unroll
         for (int u = 0; u < NLD; ++u) {
             const int c = tid + 256 * u;
-            *(u32x4*)(tile[buf] + (c / (2 * KS)) * kRowBytes + (c % (2 * KS)) * 16) = pre[u];
+            *(u32x4*)(tile[b] + (c / (2 * KS)) * kRowBytes + (c % (2 * KS)) * 16) = pre[u];
         }
-        __syncthreads();
-        src += step_bytes;
-        if (j + 1 < j1) {
-#pragma unroll
-            for (int u = 0; u < NLD; ++u) pre[u] = *(const u32x4*)(src + u * 4096);
-        }
-
+    };
+    auto scores_of = [&](int b) {
         floatx16 acc;
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
-        const char* rowp = tile[buf] + col * kRowBytes + half * 16;
+        const char* rowp = tile[b] + col * kRowBytes + half * 16;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             const bf16x8 a = __builtin_bit_cast(bf16x8, *(const u32x4*)(rowp + s * 32));
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[s], acc, 0, 0, 0);
         }
+        return acc;
+    };
+    floatx16 acc;
+    if (j0 < j1) {
+        fetch();
+        stage(0);
+        __syncthreads();
+        if (j0 + 1 < j1) fetch();
+        acc = scores_of(0);
+    }
+    int buf = 0;
+    for (int j = j0; j + 1 < j1; ++j) {
+        float x[16];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const float x = acc[i];
-            if constexpr (KP > 2) {
-                if (__builtin_amdgcn_ballot_w64(!(x <= L.val[i][KP - 1])) != 0) L.insert(i, x, j);
-            } else {
-                L.insert(i, x, j);
+        for (int i = 0; i < 16; ++i) x[i] = acc[i];
+        stage(buf ^ 1);          // last read two steps ago, before every wave's previous barrier
+        __syncthreads();
+        if (j + 2 < j1) fetch();
+        acc = scores_of(buf ^ 1);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) L.insert(i, x[i], j);
+        // Issue order for the region after the barrier: LDS reads, then each matrix instruction
+        // followed by its share of the list updates, so that the matrix core works under the
+        // vector ALU (left to itself the scheduler puts all matrix instructions first and the
+        // wavefront waits for the chain).
+        if constexpr (KP >= 3) {
+            __builtin_amdgcn_sched_group_barrier(0x100, KS, 0);           // LDS reads
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        // one matrix instruction
+                __builtin_amdgcn_sched_group_barrier(0x002, (16 * (4 * KP)) / KS, 0);   // vector ALU
             }
         }
         buf ^= 1;
+    }
+    if (j0 < j1) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) L.insert(i, acc[i], j1 - 1);
     }
 
     // ---- partial lists out, as keys --------------------------------------------------------------

@@ -264,6 +264,25 @@ __device__ __forceinline__ void lds_select_digit(const uint64_t* keys, int n, ui
     hist_find_digit(hist, ctl, need, digit, above, count);
 }
 
+// Decode and write the first K keys of a sorted LDS array; every thread of the workgroup.
+template <typename DT>
+__device__ __forceinline__ void wg_write_topk(const uint64_t* keys, int K, const void* rowp,
+                                              void* out_vals, int32_t* out_idx, int64_t out_base) {
+    for (int i = threadIdx.x; i < K; i += blockDim.x) {
+        const uint64_t key = keys[i];
+        const uint32_t idx = key_index(key);
+        uint32_t bits = key_value_bits(key);
+        if (bits == 0 && key != 0) bits = elem<DT>::load_bits(rowp, idx);   // which zero it was
+        elem<DT>::store_bits(out_vals, out_base + i, bits);
+        out_idx[out_base + i] = (int32_t)idx;
+    }
+}
+
+// One wavefront sorts up to kWaveSortMaxKeys keys in registers; beyond kWgSortMinKeys keys a
+// workgroup of at least kWgSortMinThreads threads is faster sorting them in LDS together.
+constexpr int kWgSortMinKeys = 512;
+constexpr int kWgSortMinThreads = 256;
+
 // Top-K (descending) of the n keys in LDS `keys` (n a power of two, key 0 = empty, at least K
 // real keys), written decoded to out_*[out_base + 0..K).  Called by every thread of the
 // workgroup; `scratch` is kSelectScratchBytes of LDS (unused when n <= 256).
@@ -275,6 +294,11 @@ __device__ __forceinline__ void wg_topk_from_lds(uint64_t* keys, int n, int K, v
     const int tid = threadIdx.x, T = blockDim.x;
     // few keys, or most of them wanted: sort them all
     if (n <= 256 || (n <= kWaveSortMaxKeys && 4 * K > n)) {
+        if (n > kWgSortMinKeys && T >= kWgSortMinThreads) {
+            lds_bitonic_sort_desc(keys, n, n);
+            wg_write_topk<DT>(keys, K, rowp, out_vals, out_idx, out_base);
+            return;
+        }
         if (tid < kWave) wave_sort_dispatch<DT>(keys, n, K, rowp, out_vals, out_idx, out_base);
         return;
     }
@@ -312,20 +336,22 @@ __device__ __forceinline__ void wg_topk_from_lds(uint64_t* keys, int n, int K, v
             }
             __syncthreads();
             const int total = min((int)ctl[3], kWaveSortMaxKeys);
+            if (total > kWgSortMinKeys && T >= kWgSortMinThreads) {
+                // many keys and many idle wavefronts: sort in LDS with all of them
+                const int padded = next_pow2(total);
+                for (int i = total + tid; i < padded; i += T) buf[i] = 0;
+                __syncthreads();
+                lds_bitonic_sort_desc(buf, padded, padded);
+                wg_write_topk<DT>(buf, K, rowp, out_vals, out_idx, out_base);
+                return;
+            }
             if (tid < kWave) wave_sort_dispatch<DT>(buf, total, K, rowp, out_vals, out_idx, out_base);
             return;
         }
     }
     // fallback: order everything
     lds_bitonic_sort_desc(keys, n, n);
-    for (int i = tid; i < K; i += T) {
-        const uint64_t key = keys[i];
-        const uint32_t idx = key_index(key);
-        uint32_t bits = key_value_bits(key);
-        if (bits == 0 && key != 0) bits = elem<DT>::load_bits(rowp, idx);
-        elem<DT>::store_bits(out_vals, out_base + i, bits);
-        out_idx[out_base + i] = (int32_t)idx;
-    }
+    wg_write_topk<DT>(keys, K, rowp, out_vals, out_idx, out_base);
 }
 
 }  // namespace atk
