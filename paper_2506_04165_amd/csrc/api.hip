@@ -317,6 +317,46 @@ static int run_exact(const void* values, const int32_t* payload, int dtype, int6
 
 using namespace atk;
 
+// ---- matmul-fused path (Section 7.3): plan ---------------------------------------------------------
+namespace {
+
+struct MipsPlan {
+    int status = ATK_OK;
+    int KP = 0, nslab = 0, nqt = 0, nseg = 1, seg_steps = 0, Cpad = 0;
+    size_t workspace = 0;
+};
+
+constexpr int kMipsTargetWorkgroups = 512;   // 2 wavefronts per SIMD on 256 CUs
+constexpr int kMipsMinSegmentSteps = 64;     // shorter walks only refill lists
+
+MipsPlan make_mips_plan(int dtype, int64_t Q, int64_t N, int64_t D, int K, int Kprime, int B) {
+    MipsPlan pl;
+    if (Q < 0 || N <= 0 || N > 0x7fffffffLL || D <= 0) { pl.status = ATK_INVALID_ARG; return pl; }
+    if ((pl.status = validate_method(N, K, Kprime, B))) return pl;
+    if (dtype != ATK_BF16 || (D != 64 && D != 128 && D != 256) || B % kMipsSlab || Kprime > 4 ||
+        (int64_t)B * Kprime > 16384 || Q > 0x7fffffffLL / 2) {
+        pl.status = ATK_UNSUPPORTED;
+        return pl;
+    }
+    pl.KP = Kprime <= 2 ? Kprime : 4;
+    pl.nslab = B / kMipsSlab;
+    pl.nqt = (int)((Q + kMipsQueryTile - 1) / kMipsQueryTile);
+    const int nsteps = (int)(N / B);
+    const int64_t pairs = (int64_t)pl.nslab * (pl.nqt > 0 ? pl.nqt : 1);
+    int nseg = (int)((kMipsTargetWorkgroups + pairs - 1) / pairs);
+    nseg = std::min(nseg, std::max(1, nsteps / kMipsMinSegmentSteps));
+    nseg = std::max(1, std::min(nseg, 16));
+    const int forced = env_int("ATK_MIPS_SEGMENTS", 0);          // developer knob
+    if (forced >= 1 && forced <= 64 && forced <= nsteps) nseg = forced;
+    pl.seg_steps = (nsteps + nseg - 1) / nseg;
+    pl.nseg = (nsteps + pl.seg_steps - 1) / pl.seg_steps;
+    pl.Cpad = (int)pow2_ceil((int64_t)B * Kprime);
+    pl.workspace = (size_t)Q * pl.nseg * Kprime * B * 8;
+    return pl;
+}
+
+}  // namespace
+
 extern "C" {
 
 int atk_approx_topk(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride,
@@ -438,46 +478,7 @@ size_t atk_workspace_bytes(int op, int dtype, int64_t rows, int64_t N, int K, in
     return pl.workspace;
 }
 
-// ---- matmul-fused path (Section 7.3) ---------------------------------------------------------
-namespace {
-
-struct MipsPlan {
-    int status = ATK_OK;
-    int KP = 0, nslab = 0, nqt = 0, nseg = 1, seg_steps = 0, Cpad = 0;
-    size_t workspace = 0;
-};
-
-constexpr int kMipsTargetWorkgroups = 512;   // 2 wavefronts per SIMD on 256 CUs
-constexpr int kMipsMinSegmentSteps = 64;     // shorter walks only refill lists
-
-MipsPlan make_mips_plan(int dtype, int64_t Q, int64_t N, int64_t D, int K, int Kprime, int B) {
-    MipsPlan pl;
-    if (Q < 0 || N <= 0 || N > 0x7fffffffLL || D <= 0) { pl.status = ATK_INVALID_ARG; return pl; }
-    if ((pl.status = validate_method(N, K, Kprime, B))) return pl;
-    if (dtype != ATK_BF16 || (D != 64 && D != 128 && D != 256) || B % kMipsSlab || Kprime > 4 ||
-        (int64_t)B * Kprime > 16384 || Q > 0x7fffffffLL / 2) {
-        pl.status = ATK_UNSUPPORTED;
-        return pl;
-    }
-    pl.KP = Kprime <= 2 ? Kprime : 4;
-    pl.nslab = B / kMipsSlab;
-    pl.nqt = (int)((Q + kMipsQueryTile - 1) / kMipsQueryTile);
-    const int nsteps = (int)(N / B);
-    const int64_t pairs = (int64_t)pl.nslab * (pl.nqt > 0 ? pl.nqt : 1);
-    int nseg = (int)((kMipsTargetWorkgroups + pairs - 1) / pairs);
-    nseg = std::min(nseg, std::max(1, nsteps / kMipsMinSegmentSteps));
-    nseg = std::max(1, std::min(nseg, 16));
-    const int forced = env_int("ATK_MIPS_SEGMENTS", 0);          // developer knob
-    if (forced >= 1 && forced <= 64 && forced <= nsteps) nseg = forced;
-    pl.seg_steps = (nsteps + nseg - 1) / nseg;
-    pl.nseg = (nsteps + pl.seg_steps - 1) / pl.seg_steps;
-    pl.Cpad = (int)pow2_ceil((int64_t)B * Kprime);
-    pl.workspace = (size_t)Q * pl.nseg * Kprime * B * 8;
-    return pl;
-}
-
-}  // namespace
-
+// ---- matmul-fused path (Section 7.3): entry points ---------------------------------------------
 size_t atk_mips_workspace_bytes(int dtype, int64_t Q, int64_t N, int64_t D, int K, int Kprime, int B) {
     MipsPlan pl = make_mips_plan(dtype, Q, N, D, K, Kprime, B);
     return pl.status ? SIZE_MAX : pl.workspace;

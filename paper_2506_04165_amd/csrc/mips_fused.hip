@@ -1,222 +1,17 @@
-// Matmul-fused stage 1 of the approximate Top-K (Section 7.3; appendix "Matmul-fused
-// implementation"; Section 6.1 Steps 1-2 on scores that exist only in registers).
-//
-// Decomposition (ours; the paper's kernel walks a 3-D grid sequentially and keeps the lists in
-// on-chip memory, which does not carry over):
-//   * a workgroup of 4 wavefronts owns a slab of 32 buckets and a tile of 128 queries, and
-//     walks the elements of those buckets: step j covers the database vectors j*B + b0 + [0,32),
-//     32 contiguous vectors, so a given accumulator register sees the same (query, bucket)
-//     pair at every step and its K'-list lives in registers with static indexing, exactly as
-//     in the streaming kernel;
-//   * the 32 x D database tile goes through LDS (double buffered, one barrier per step) and is
-//     the row operand of v_mfma_f32_32x32x16_bf16; the query fragments are the column operand
-//     and stay in registers for the whole walk.  Each wavefront computes a 32 (buckets) x 32
-//     (queries) tile of binary32 scores per step: D/16 matrix instructions;
-//   * every score then updates its list (Algorithm 1 restated, branch-free; see ScoreLists).
-//     Skipping the update when no lane of the wavefront beats its list's tail was measured and
-//     is slower: one lane in 64 nearly always does, and the branches serialise the updates;
-//   * when there are too few (slab, tile) pairs to fill the chip the walk is cut into
-//     segments run by different workgroups; the per-bucket merge of the partial lists and
-//     Steps 3-4 are the finishing launch shared with the split streaming path;
-//   * the block index is decoded so that the workgroups sharing a database tile (same slab and
-//     segment, different queries) run on the same XCD and find the tile in its L2.
-//
-// Scores are binary32 sums formed by the matrix instruction; accumulation order inside the
-// instruction is the hardware's.  A zero score is +0.0 (the accumulator starts at +0.0).
-#include "mips_fused.h"
-#include "approx_kernel.h"
+// Matmul-fused stage 1 (Section 7.3): instantiations with short lists (K' <= 2) and the
+// dispatcher.  This file is compiled with matrix results kept in ordinary VGPRs (see the build
+// script): with short lists there are registers to spare and the move per score it saves shows.
+#include "mips_fused_kernel.h"
 
 namespace atk {
-namespace {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte move
-
-// The K' greatest scores each accumulator register has seen, greatest first, with the step at
-// which each arrived.  Scores are finite, so the empty entry is -inf and the values need no
-// compare-and-select: entry k becomes the median of (entry k-1, entry k, score), the head the
-// maximum (Algorithm 1's shift, as a clamp).  Only the steps follow the compare results.  A
-// strict compare keeps the earlier (lower-index) element ahead on ties.  Written without
-// branches on purpose: the 16 updates of a step are independent and interleave.
-template <int KP>
-struct ScoreLists {
-    float val[16][KP];
-    int32_t stp[16][KP];
-    __device__ __forceinline__ void init() {
-#pragma unroll
-        for (int i = 0; i < 16; ++i)
-#pragma unroll
-            for (int k = 0; k < KP; ++k) { val[i][k] = -__builtin_inff(); stp[i][k] = 0; }
-    }
-    __device__ __forceinline__ void insert(int i, float x, int32_t step) {
-        if constexpr (KP == 1) {       // measured: two selects on one compare beat max + select
-            const bool c0 = x > val[i][0];
-            val[i][0] = sel(c0, x, val[i][0]);
-            stp[i][0] = sel(c0, step, stp[i][0]);
-            return;
-        }
-        bool c[KP];
-#pragma unroll
-        for (int k = 0; k < KP; ++k) c[k] = x > val[i][k];
-#pragma unroll
-        for (int k = KP - 1; k >= 1; --k) {
-            stp[i][k] = sel(c[k - 1], stp[i][k - 1], sel(c[k], step, stp[i][k]));
-            val[i][k] = __builtin_amdgcn_fmed3f(val[i][k - 1], val[i][k], x);
-        }
-        stp[i][0] = sel(c[0], step, stp[i][0]);
-        val[i][0] = __builtin_amdgcn_fmed3f(val[i][0], x, __builtin_inff());   // max, as one instruction
-    }
-    __device__ __forceinline__ bool valid(int i, int k) const { return val[i][k] != -__builtin_inff(); }
-    __device__ __forceinline__ uint32_t bits(int i, int k) const { return __float_as_uint(val[i][k]); }
-};
-
-template <int KP, int KS>   // KS = D / 16: matrix instructions per tile
-__global__ void __launch_bounds__(256) mips_stage1_kernel(MipsParams p) {
-    constexpr int D = KS * 16;
-    constexpr int kRowBytes = D * 2 + 16;             // padded: rows 16 apart share no LDS bank
-    constexpr int kTileBytes = kMipsSlab * kRowBytes;
-    constexpr int NLD = KS / 4;                       // 16-byte loads per thread and step
-    __shared__ __attribute__((aligned(16))) char tile[2][kTileBytes];
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int half = lane >> 5, col = lane & 31;
-
-    // ---- block -> (slab, segment, query tile) ---------------------------------------------------
-    const int ngroups = p.nslab * p.nseg;             // (slab, segment) pairs: one database walk each
-    int group, qt;
-    if ((ngroups & 7) == 0) {
-        // consecutive block ids go round the 8 XCDs: keep the nqt workgroups of a walk on one
-        const int xcd = blockIdx.x & 7, y = blockIdx.x >> 3;
-        group = (y / p.nqt) * 8 + xcd;
-        qt = y % p.nqt;
-    } else {
-        group = blockIdx.x / p.nqt;
-        qt = blockIdx.x % p.nqt;
-    }
-    const int slab = group % p.nslab, seg = group / p.nslab;
-    const int b0 = slab * kMipsSlab;
-    const int j0 = seg * p.seg_steps;
-    const int j1 = min(p.nsteps, j0 + p.seg_steps);
-
-    // ---- query fragments: lane (col, half) holds query col, dims (2s + half)*8 .. +8 of step s ---
-    const int q = qt * kMipsQueryTile + wave * 32 + col;
-    bf16x8 qf[KS];
-#pragma unroll
-    for (int s = 0; s < KS; ++s) {
-        u32x4 w = {0, 0, 0, 0};
-        if (q < p.Q) w = *(const u32x4*)(p.queries + (size_t)q * D + (2 * s + half) * 8);
-        qf[s] = __builtin_bit_cast(bf16x8, w);
-    }
-
-    ScoreLists<KP> L;
-    L.init();
-
-    // ---- walk ------------------------------------------------------------------------------------
-    // the tile of step j is 32*D*2 contiguous bytes; thread t moves the 16-byte pieces t + 256u
-    // Software pipeline: the matrix instructions of step j+1 are issued before the list updates
-    // of step j, so the matrix core and the LDS work under the vector ALU's shadow.
-    u32x4 pre[NLD];
-    const char* src = (const char*)p.database + ((size_t)j0 * p.B + b0) * (size_t)(D * 2) + tid * 16;
-    const size_t step_bytes = (size_t)p.B * (D * 2);
-    auto fetch = [&]() {
-#pragma unroll
-        for (int u = 0; u < NLD; ++u) pre[u] = *(const u32x4*)(src + u * 4096);
-        src += step_bytes;
-    };
-    auto stage = [&](int b) {
-#pragma unroll
-        for (int u = 0; u < NLD; ++u) {
-            const int c = tid + 256 * u;
-            *(u32x4*)(tile[b] + (c / (2 * KS)) * kRowBytes + (c % (2 * KS)) * 16) = pre[u];
-        }
-    };
-    auto scores_of = [&](int b) {
-        floatx16 acc;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
-        const char* rowp = tile[b] + col * kRowBytes + half * 16;
-#pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            const bf16x8 a = __builtin_bit_cast(bf16x8, *(const u32x4*)(rowp + s * 32));
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[s], acc, 0, 0, 0);
-        }
-        return acc;
-    };
-    floatx16 acc;
-    if (j0 < j1) {
-        fetch();
-        stage(0);
-        __syncthreads();
-        if (j0 + 1 < j1) fetch();
-        acc = scores_of(0);
-    }
-    int buf = 0;
-    for (int j = j0; j + 1 < j1; ++j) {
-        float x[16];
-#pragma unroll
-        for (int i = 0; i < 16; ++i) x[i] = acc[i];
-        stage(buf ^ 1);          // last read two steps ago, before every wave's previous barrier
-        __syncthreads();
-        if (j + 2 < j1) fetch();
-        acc = scores_of(buf ^ 1);
-#pragma unroll
-        for (int i = 0; i < 16; ++i) L.insert(i, x[i], j);
-        // Issue order for the region after the barrier: LDS reads, then each matrix instruction
-        // followed by its share of the list updates, so that the matrix core works under the
-        // vector ALU (left to itself the scheduler puts all matrix instructions first and the
-        // wavefront waits for the chain).
-        if constexpr (KP >= 3) {
-            __builtin_amdgcn_sched_group_barrier(0x100, KS, 0);           // LDS reads
-#pragma unroll
-            for (int s = 0; s < KS; ++s) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        // one matrix instruction
-                __builtin_amdgcn_sched_group_barrier(0x002, (16 * (4 * KP)) / KS, 0);   // vector ALU
-            }
-        }
-        buf ^= 1;
-    }
-    if (j0 < j1) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) L.insert(i, acc[i], j1 - 1);
-    }
-
-    // ---- partial lists out, as keys --------------------------------------------------------------
-    // accumulator i of lane (col, half) is the score of bucket row 8*(i/4) + 4*half + i%4
-    if (q < p.Q) {
-        uint64_t* out = p.part_keys + ((size_t)q * p.nseg + seg) * p.Kprime * p.B;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int b = b0 + 8 * (i >> 2) + 4 * half + (i & 3);
-#pragma unroll
-            for (int k = 0; k < KP; ++k)
-                if (k < p.Kprime) {
-                    const uint32_t n = (uint32_t)L.stp[i][k] * (uint32_t)p.B + (uint32_t)b;
-                    out[(size_t)k * p.B + b] = L.valid(i, k) ? make_key(L.bits(i, k), n) : 0;
-                }
-        }
-    }
-}
-
-template <int KP>
-hipError_t launch_for(const MipsParams& p, hipStream_t stream) {
-    const dim3 grid((unsigned)(p.nslab * p.nseg * p.nqt)), block(256);
-    switch (p.D) {
-        case 64:  hipLaunchKernelGGL((mips_stage1_kernel<KP, 4>), grid, block, 0, stream, p); break;
-        case 128: hipLaunchKernelGGL((mips_stage1_kernel<KP, 8>), grid, block, 0, stream, p); break;
-        case 256: hipLaunchKernelGGL((mips_stage1_kernel<KP, 16>), grid, block, 0, stream, p); break;
-        default: return hipErrorInvalidValue;
-    }
-    return hipGetLastError();
-}
-
-}  // namespace
+hipError_t launch_mips_stage1_long(const MipsParams& p, hipStream_t stream);   // mips_fused_long.hip
 
 hipError_t launch_mips_stage1(const MipsParams& p, int KP, hipStream_t stream) {
     switch (KP) {
         case 1: return launch_for<1>(p, stream);
         case 2: return launch_for<2>(p, stream);
-        case 4: return launch_for<4>(p, stream);
+        case 4: return launch_mips_stage1_long(p, stream);
         default: return hipErrorInvalidValue;
     }
 }

@@ -1,0 +1,12 @@
+// Matmul-fused stage 1 (Section 7.3): the instantiation with lists of four.  Compiled with the
+// default register classes: at this register pressure the accumulator-register form of the
+// matrix instruction measured faster.
+#include "mips_fused_kernel.h"
+
+namespace atk {
+
+hipError_t launch_mips_stage1_long(const MipsParams& p, hipStream_t stream) {
+    return launch_for<4>(p, stream);
+}
+
+}  // namespace atk
