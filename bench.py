@@ -145,6 +145,64 @@ def bench_workload(name, steps, warmup, with_cpu_baseline, only_params=None):
     return results, exact, cpu
 
 
+# Vector-ALU peak for compares and selects: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-operations
+# per second (packed fp32 forms are compiled out, so one lane-operation per lane and cycle).
+VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+MIPS_SHAPE = dict(Q=1024, N=1 << 20, D=128, K=1024)       # Section 7.3 / Table 2
+MIPS_PARAMS = [(1024, 4), (4096, 2)]                       # both reach 99 % expected recall
+
+
+def bench_mips_fused(steps, warmup):
+    """The matmul-fused entry point at the paper's MIPS shape, and the same job unfused (a
+    library GEMM that writes the score matrix, then atk_approx_topk on it)."""
+    import torch
+    from paper_2506_04165_amd import binding as atk, workloads
+    Q, N, D, K = (MIPS_SHAPE[k] for k in ("Q", "N", "D", "K"))
+    dev = "cuda:0"
+    q, d = workloads.mips_vectors(Q, N, seed=1, device=dev, dim=D)
+    ov = torch.empty((Q, K), dtype=torch.float32, device=dev)
+    oi = torch.empty((Q, K), dtype=torch.int32, device=dev)
+    out = []
+    scores = torch.empty((Q, N), dtype=torch.float32, device=dev)
+    dT = d.float().t().contiguous()
+    qf = q.float()
+    for B, Kp in MIPS_PARAMS:
+        ws = torch.empty(atk.mips_workspace_bytes(Q, N, D, K, Kp, B), dtype=torch.uint8, device=dev)
+        t = time_steps(lambda i: atk.mips_approx_topk(q, d, K, Kp, B, out=(ov, oi), workspace=ws),
+                       1, steps, warmup)
+        _, plan = atk.mips_describe_plan(Q, N, D, K, Kp, B)
+        # unfused on the same inputs: fp32 GEMM of the same bf16 values, scores through HBM
+        ws2 = torch.empty(max(1, atk.workspace_bytes(atk.OP_APPROX_TOPK, torch.float32, Q, N, K, Kp, B)),
+                          dtype=torch.uint8, device=dev)
+        uv = torch.empty((Q, K), dtype=torch.float32, device=dev)
+        ui = torch.empty((Q, K), dtype=torch.int32, device=dev)
+
+        def unfused(_):
+            torch.matmul(qf, dT, out=scores)
+            atk.approx_topk(scores, K, Kp, B, out=(uv, ui), workspace=ws2)
+        tu = time_steps(unfused, 1, max(3, steps // 10), max(2, warmup // 10))
+        same = (torch.sort(ui.long(), 1).values == torch.sort(oi.long(), 1).values).float().mean().item()
+        ops = (5 * Kp - 2) * Q * N                       # Section 6.3: 5K'-2 operations per element
+        ms = t["kernel_ms_avg"]
+        out.append({
+            "B": B, "Kprime": Kp, "plan": plan, "ms_per_call": ms, "ms_per_call_min": t["kernel_ms_min"],
+            "queries_per_s": Q / ms * 1e3, "scores_per_s": Q * N / ms * 1e3,
+            "mfma_tflops": 2.0 * Q * N * D / ms / 1e9,
+            "expected_recall_random_placement": atk.expected_recall(N, B, K, Kp),
+            "roofline": {"bound": "alu", "achieved": ops / ms / 1e9, "peak": VALU_PEAK_TOPS,
+                         "unit": "T lane-ops/s", "frac": ops / ms / 1e9 / VALU_PEAK_TOPS, "traffic": None,
+                         "note": "both launches of the call (stage 1 with the matrix product, then the "
+                                 "merge and stage 2); algorithmic work = (5K'-2) list operations per score"},
+            "unfused_ms_per_call": tu["kernel_ms_avg"],
+            "speedup_vs_unfused": tu["kernel_ms_avg"] / ms,
+            "index_agreement_with_unfused": same,
+        })
+    return {"workload": f"mips: {Q} queries x {N} database vectors, D={D} bf16, K={K} "
+                        "(unit-norm Gaussian vectors standing in for the paper's MIPS set)",
+            "configs": out,
+            "paper_tpu_v5e_ms": {"K'=4 fused total": 10, "K'=4 unfused total": 22}}
+
+
 def cpu_baseline(name, xd, B, Kp):
     """The CPU oracle, as it stands, on a bounded sample of rows of the same workload."""
     from oracle import oracle
@@ -179,6 +237,9 @@ def main():
     ap.add_argument("--params", default=None, help="with --workload: only this 'B,Kprime' setting")
     ap.add_argument("--headline-only", action="store_true", help="skip the other configurations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-mips", action="store_true", help="skip the matmul-fused section")
+    ap.add_argument("--mips-only", action="store_true",
+                    help="run only the matmul-fused section and print it (for profiling that kernel)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy a few times (reference kernel of known "
                          "size for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE) and exit")
@@ -203,6 +264,10 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"calibration": "plain copy", "launches": 3, "bytes_read_per_launch": nbytes,
                           "bytes_written_per_launch": nbytes}))
+        return
+
+    if args.mips_only:
+        print(json.dumps({"mips_fused": bench_mips_fused(max(10, args.steps // 5), max(5, args.warmup // 10))}))
         return
 
     head_name, head_B, head_Kp = HEADLINE
@@ -254,6 +319,8 @@ def main():
         "per_config": per_config,
         "paper_context": PAPER_CONTEXT,
     }
+    if not (args.no_mips or args.workload or args.headline_only):
+        line["mips_fused"] = bench_mips_fused(max(10, args.steps // 5), max(5, args.warmup // 10))
     print(json.dumps(line))
 
 

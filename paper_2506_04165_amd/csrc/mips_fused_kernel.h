@@ -78,7 +78,13 @@ __global__ void __launch_bounds__(256) mips_stage1_kernel(MipsParams p) {
     constexpr int kRowBytes = D * 2 + 16;             // padded: rows 16 apart share no LDS bank
     constexpr int kTileBytes = kMipsSlab * kRowBytes;
     constexpr int NLD = KS / 4;                       // 16-byte loads per thread and step
-    __shared__ __attribute__((aligned(16))) char tile[2][kTileBytes];
+    // after the walk the same memory stages the keys for coalesced stores: 32 x (256+16) bytes
+    // per wavefront
+    constexpr int kStageRowBytes = kMipsSlab * 8 + 16;
+    constexpr int kStageBytes = 4 * 32 * kStageRowBytes;
+    constexpr int kLdsBytes = 2 * kTileBytes > kStageBytes ? 2 * kTileBytes : kStageBytes;
+    __shared__ __attribute__((aligned(16))) char lds_raw[kLdsBytes];
+    char (*tile)[kTileBytes] = reinterpret_cast<char (*)[kTileBytes]>(lds_raw);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, col = lane & 31;
@@ -183,18 +189,35 @@ __global__ void __launch_bounds__(256) mips_stage1_kernel(MipsParams p) {
     }
 
     // ---- partial lists out, as keys --------------------------------------------------------------
-    // accumulator i of lane (col, half) is the score of bucket row 8*(i/4) + 4*half + i%4
-    if (q < p.Q) {
-        uint64_t* out = p.part_keys + ((size_t)q * p.nseg + seg) * p.Kprime * p.B;
+    // accumulator i of lane (col, half) is the score of bucket row 8*(i/4) + 4*half + i%4.  A
+    // lane's keys of one list position are 32 bytes here, 32 bytes there; they are transposed
+    // through LDS so that every query's 32 buckets leave as one 256-byte run.
+    __syncthreads();                                   // every wavefront is done with the tiles
+    char* stage_w = lds_raw + wave * (32 * kStageRowBytes);
+    const int q_first = qt * kMipsQueryTile + wave * 32;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int b = b0 + 8 * (i >> 2) + 4 * half + (i & 3);
+    for (int k = 0; k < KP; ++k) {
+        if (k < p.Kprime) {
 #pragma unroll
-            for (int k = 0; k < KP; ++k)
-                if (k < p.Kprime) {
-                    const uint32_t n = (uint32_t)L.stp[i][k] * (uint32_t)p.B + (uint32_t)b;
-                    out[(size_t)k * p.B + b] = L.valid(i, k) ? make_key(L.bits(i, k), n) : 0;
+            for (int i = 0; i < 16; ++i) {
+                const int bl = 8 * (i >> 2) + 4 * half + (i & 3);
+                const uint32_t n = (uint32_t)L.stp[i][k] * (uint32_t)p.B + (uint32_t)(b0 + bl);
+                *(uint64_t*)(stage_w + col * kStageRowBytes + bl * 8) =
+                    L.valid(i, k) ? make_key(L.bits(i, k), n) : 0;
+            }
+            __syncthreads();
+            // 16 lanes x 16 bytes cover one query's row; a wavefront stores 4 rows at a time
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                const int ql = r * 4 + (lane >> 4), chunk = lane & 15;
+                const u32x4 v = *(const u32x4*)(stage_w + ql * kStageRowBytes + chunk * 16);
+                const int qq = q_first + ql;
+                if (qq < p.Q) {
+                    uint64_t* dst = p.part_keys + (((size_t)qq * p.nseg + seg) * p.Kprime + k) * p.B + b0;
+                    *(u32x4*)((char*)dst + chunk * 16) = v;
                 }
+            }
+            __syncthreads();
         }
     }
 }
