@@ -41,7 +41,10 @@
 extern "C" {
 #endif
 
-typedef enum atk_dtype { ATK_F32 = 0, ATK_BF16 = 1 } atk_dtype;
+/* Element types of `values`.  Floating types are compared after the exact widening to binary32
+ * (-0.0 equals +0.0, NaN excluded); signed and unsigned 32-bit integers are compared as such --
+ * the compute-type promotion of Section 6.3's listing.  Outputs carry the stored words. */
+typedef enum atk_dtype { ATK_F32 = 0, ATK_BF16 = 1, ATK_F16 = 2, ATK_I32 = 3, ATK_U32 = 4 } atk_dtype;
 
 typedef enum atk_status {
     ATK_OK = 0,

@@ -22,8 +22,9 @@
  * index decides); outputs carry the stored bits of the chosen element.
  * Precondition: no NaN in the input (checked, returns -2).
  *
- * bf16 inputs are widened to binary32 before comparing (exact and order
- * preserving; the promotion rule of Section 6.3's listing).
+ * bf16 and fp16 inputs are widened to binary32 before comparing (exact and
+ * order preserving), 32-bit integers are compared as integers: the promotion
+ * rule of Section 6.3's listing.
  *
  * The exact Top-K (the K greatest of all N elements in the same order) is the
  * B = 1, K' = K case of the definition and is also provided on its own, written
@@ -41,25 +42,55 @@
 #endif
 
 typedef struct {
-    float value;   /* numeric value used for comparisons */
+    double value;  /* numeric value used for comparisons */
     int32_t index; /* position n inside the row */
 } element_t;
 
-enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+/*
+ * Element types.  Section 6.3's listing promotes floating inputs of at most 32
+ * bits to binary32, signed integers to int32 and unsigned ones to uint32 before
+ * comparing.  Every value of those three compute types is exactly a binary64
+ * number, so one comparison in double stands for all of them.
+ */
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F16 = 2, ORACLE_I32 = 3, ORACLE_U32 = 4 };
 
-static float widen(const void *row, int dtype, int64_t n)
+/* IEEE binary16 -> binary32, written out field by field (exact). */
+static float half_to_float(uint16_t h)
 {
-    if (dtype == ORACLE_F32) {
+    int sign = h >> 15, exponent = (h >> 10) & 31, fraction = h & 1023;
+    double magnitude;
+    if (exponent == 31)
+        magnitude = fraction ? NAN : INFINITY;
+    else if (exponent == 0)
+        magnitude = ldexp((double)fraction, -24);            /* subnormal: fraction * 2^-24 */
+    else
+        magnitude = ldexp(1.0 + fraction / 1024.0, exponent - 15);
+    return (float)(sign ? -magnitude : magnitude);
+}
+
+static double widen(const void *row, int dtype, int64_t n)
+{
+    switch (dtype) {
+    case ORACLE_F32:
         return ((const float *)row)[n];
-    } else {
+    case ORACLE_BF16: {
         uint32_t bits = (uint32_t)((const uint16_t *)row)[n] << 16;
         float f;
         memcpy(&f, &bits, sizeof f);
         return f;
     }
+    case ORACLE_F16:
+        return half_to_float(((const uint16_t *)row)[n]);
+    case ORACLE_I32:
+        return ((const int32_t *)row)[n];
+    default:
+        return ((const uint32_t *)row)[n];
+    }
 }
 
-static size_t elem_size(int dtype) { return dtype == ORACLE_F32 ? 4 : 2; }
+static int known_dtype(int dtype) { return dtype >= ORACLE_F32 && dtype <= ORACLE_U32; }
+
+static size_t elem_size(int dtype) { return (dtype == ORACLE_BF16 || dtype == ORACLE_F16) ? 2 : 4; }
 
 /* qsort comparator: negative when a is "greater" (comes first). */
 static int greater_first(const void *pa, const void *pb)
@@ -103,7 +134,7 @@ int atk_oracle_num_threads(void)
 static int check_args(const void *values, int dtype, int64_t rows, int64_t N,
                       int64_t row_stride, int64_t K, int64_t Kp, int64_t B)
 {
-    if (!values || (dtype != ORACLE_F32 && dtype != ORACLE_BF16)) return -1;
+    if (!values || !known_dtype(dtype)) return -1;
     if (rows < 0 || N <= 0 || row_stride < N || N > 2147483647LL) return -1;
     if (B < 1 || N % B != 0) return -1;
     if (Kp < 1 || Kp > K || Kp > N / B) return -1;
@@ -194,7 +225,7 @@ int atk_oracle_approx_topk(const void *values, int dtype, int64_t rows, int64_t 
 int atk_oracle_topk(const void *values, int dtype, int64_t rows, int64_t N,
                     int64_t row_stride, int64_t K, void *out_vals, int32_t *out_idx)
 {
-    if (!values || (dtype != ORACLE_F32 && dtype != ORACLE_BF16)) return -1;
+    if (!values || !known_dtype(dtype)) return -1;
     if (rows < 0 || N <= 0 || row_stride < N || N > 2147483647LL) return -1;
     if (K < 1 || K > N) return -1;
     int status = 0;

@@ -30,8 +30,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "atk_oracle.c")
 _LIB = os.path.join(_HERE, "libatk_oracle.so")
 
-F32 = 0
-BF16 = 1
+F32, BF16, F16, I32, U32 = 0, 1, 2, 3, 4
 
 
 def build(force: bool = False) -> str:
@@ -73,16 +72,14 @@ def num_threads() -> int:
 
 
 def _prep(values: np.ndarray):
+    """float32, float16, int32 and uint32 arrays as they are; bf16 travels as uint16 bit patterns."""
     if values.ndim != 2:
         raise ValueError("values must be [rows, N]")
-    if values.dtype == np.float32:
-        dtype = F32
-    elif values.dtype == np.uint16:
-        dtype = BF16
-    else:
-        raise TypeError("values must be float32, or uint16 holding bf16 bits")
-    values = np.ascontiguousarray(values)
-    return values, dtype
+    codes = {np.dtype(np.float32): F32, np.dtype(np.uint16): BF16, np.dtype(np.float16): F16,
+             np.dtype(np.int32): I32, np.dtype(np.uint32): U32}
+    if values.dtype not in codes:
+        raise TypeError("values must be float32, float16, int32, uint32, or uint16 holding bf16 bits")
+    return np.ascontiguousarray(values), codes[values.dtype]
 
 
 def _raise(rc: int, what: str):

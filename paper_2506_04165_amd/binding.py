@@ -17,7 +17,9 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 # ATK_LIB_PATH lets a developer point the binding at an experimental build of the same library
 LIB_PATH = os.environ.get("ATK_LIB_PATH") or os.path.join(_PKG, "libatk.so")
 
-F32, BF16 = 0, 1
+F32, BF16, F16, I32, U32 = 0, 1, 2, 3, 4
+_CODES = {torch.float32: F32, torch.bfloat16: BF16, torch.float16: F16, torch.int32: I32,
+          torch.uint32: U32}
 OK, INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP_ERROR = range(5)
 OP_APPROX_TOPK, OP_TOPK, OP_STAGE1 = 0, 1, 2
 SIZE_MAX = ctypes.c_size_t(-1).value
@@ -97,7 +99,13 @@ def _dtype_code(t: torch.Tensor) -> int:
         return F32
     if t.dtype == torch.bfloat16:
         return BF16
-    raise TypeError(f"unsupported dtype {t.dtype}: float32 or bfloat16")
+    if t.dtype == torch.float16:
+        return F16
+    if t.dtype == torch.int32:
+        return I32
+    if t.dtype == torch.uint32:
+        return U32
+    raise TypeError(f"unsupported dtype {t.dtype}: float32, bfloat16, float16, int32 or uint32")
 
 
 def _check_input(values: torch.Tensor):
@@ -117,12 +125,12 @@ def _stream_ptr(device) -> int:
 
 
 def workspace_bytes(op: int, dtype: torch.dtype, rows: int, N: int, K: int, Kprime: int, B: int) -> int:
-    code = F32 if dtype == torch.float32 else BF16
+    code = _CODES[dtype]
     return int(lib.atk_workspace_bytes(op, code, rows, N, K, Kprime, B))
 
 
 def describe_plan(dtype: torch.dtype, rows: int, N: int, K: int, Kprime: int, B: int):
-    code = F32 if dtype == torch.float32 else BF16
+    code = _CODES[dtype]
     buf = ctypes.create_string_buffer(512)
     st = lib.atk_describe_plan(code, rows, N, K, Kprime, B, buf, 512)
     return st, buf.value.decode()

@@ -33,6 +33,12 @@ SOURCES = [
     "approx_inst_bf16_unaligned.hip",
     "approx_inst_bf16_packed.hip",
     "approx_inst_batched.hip",
+    "approx_inst_i32_small.hip",
+    "approx_inst_i32_wide.hip",
+    "approx_inst_i32_unaligned.hip",
+    "approx_inst_u32_small.hip",
+    "approx_inst_u32_wide.hip",
+    "approx_inst_u32_unaligned.hip",
     "recall.cpp",
     "select_params.cpp",
 ]

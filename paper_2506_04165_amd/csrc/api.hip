@@ -62,7 +62,19 @@ static int pow2_ceil(int64_t x) { int p = 1; while (p < x) p <<= 1; return p; }
 static int pow2_floor(int64_t x) { int p = 1; while ((int64_t)p * 2 <= x) p <<= 1; return p; }
 static int ilog2(int x) { int l = 0; while ((1 << l) < x) ++l; return l; }
 static bool is_pow2(int64_t x) { return x > 0 && (x & (x - 1)) == 0; }
-static int elem_size(int dtype) { return dtype == ATK_F32 ? 4 : 2; }
+static int elem_size(int dtype) { return (dtype == ATK_BF16 || dtype == ATK_F16) ? 2 : 4; }
+
+// The element type the kernels are compiled for, or -1.  fp16 runs on the bf16 kernels: both are
+// sign-magnitude formats, so ordering the 16-bit patterns (or those patterns widened by 16 zero
+// bits and compared as binary32) orders the values, -0.0 and +0.0 coincide in both, and results
+// are reported as the stored 16-bit patterns; with NaN excluded no reinterpreted fp16 is a NaN.
+static int kernel_dtype(int dtype) {
+    switch (dtype) {
+        case ATK_F32: case ATK_BF16: case ATK_I32: case ATK_U32: return dtype;
+        case ATK_F16: return ATK_BF16;
+        default: return -1;
+    }
+}
 
 static int env_int(const char* name, int fallback) {
     const char* s = std::getenv(name);
@@ -72,7 +84,7 @@ static int env_int(const char* name, int fallback) {
 // ---- validation (host only; every error can be provoked without a GPU) ----------------------
 static int validate_common(const void* values, int dtype, int64_t rows, int64_t N,
                            int64_t row_stride) {
-    if (dtype != ATK_F32 && dtype != ATK_BF16) return ATK_UNSUPPORTED;
+    if (kernel_dtype(dtype) < 0) return ATK_UNSUPPORTED;
     if (rows < 0 || rows > 0x7fffffff || N <= 0 || N > 0x7fffffffLL || row_stride < N)
         return ATK_INVALID_ARG;
     if (rows > 0 && !values) return ATK_INVALID_ARG;
@@ -364,6 +376,7 @@ int atk_approx_topk(const void* values, int dtype, int64_t rows, int64_t N, int6
                     void* workspace, size_t workspace_bytes, void* stream) {
     int rc = validate_common(values, dtype, rows, N, row_stride);
     if (rc) return rc;
+    dtype = kernel_dtype(dtype);       // fp16 -> the bf16 kernels
     rc = validate_method(N, K, Kprime, B);
     if (rc) return rc;
     if (rows > 0 && (!out_vals || !out_idx)) return ATK_INVALID_ARG;
@@ -417,9 +430,9 @@ int atk_approx_topk_recall(const void* values, int dtype, int64_t rows, int64_t 
                            int64_t row_stride, int K, double recall_target, void* out_vals,
                            int32_t* out_idx, void* workspace, size_t workspace_bytes,
                            void* stream, int* Kprime_used, int* B_used) {
-    if (dtype != ATK_F32 && dtype != ATK_BF16) return ATK_UNSUPPORTED;
+    if (kernel_dtype(dtype) < 0) return ATK_UNSUPPORTED;
     int kp = 0, b = 0;
-    int rc = atk_select_params(N, K, recall_target, dtype == ATK_BF16 ? 8 : 4, 64, &kp, &b, nullptr);
+    int rc = atk_select_params(N, K, recall_target, elem_size(dtype) == 2 ? 8 : 4, 64, &kp, &b, nullptr);
     if (rc) return rc;
     if (Kprime_used) *Kprime_used = kp;
     if (B_used) *B_used = b;
@@ -436,6 +449,7 @@ int atk_topk(const void* values, int dtype, int64_t rows, int64_t N, int64_t row
     (void)workspace; (void)workspace_bytes;
     int rc = validate_common(values, dtype, rows, N, row_stride);
     if (rc) return rc;
+    dtype = kernel_dtype(dtype);       // fp16 -> the bf16 kernels
     if (K < 1 || (int64_t)K > N) return ATK_INVALID_ARG;
     if (rows > 0 && (!out_vals || !out_idx)) return ATK_INVALID_ARG;
     if ((uintptr_t)out_vals % elem_size(dtype) || (uintptr_t)out_idx % 4) return ATK_INVALID_ARG;
@@ -450,6 +464,7 @@ int atk_approx_topk_stage1(const void* values, int dtype, int64_t rows, int64_t 
                            int32_t* surv_idx, void* stream) {
     int rc = validate_common(values, dtype, rows, N, row_stride);
     if (rc) return rc;
+    dtype = kernel_dtype(dtype);       // fp16 -> the bf16 kernels
     // stage 1 has no K of its own: any K in [K', B*K'] makes the same survivors
     rc = validate_method(N, Kprime, Kprime, B);
     if (rc) return rc;
@@ -466,7 +481,8 @@ int atk_approx_topk_stage1(const void* values, int dtype, int64_t rows, int64_t 
 }
 
 size_t atk_workspace_bytes(int op, int dtype, int64_t rows, int64_t N, int K, int Kprime, int B) {
-    if (dtype != ATK_F32 && dtype != ATK_BF16) return SIZE_MAX;
+    dtype = kernel_dtype(dtype);
+    if (dtype < 0) return SIZE_MAX;
     if (rows < 0 || N <= 0 || N > 0x7fffffffLL) return SIZE_MAX;
     if (op == ATK_OP_TOPK) return (K < 1 || K > N) ? SIZE_MAX : 0;
     if (op == ATK_OP_STAGE1) return validate_method(N, Kprime, Kprime, B) ? SIZE_MAX : 0;
@@ -533,7 +549,8 @@ int atk_describe_plan(int dtype, int64_t rows, int64_t N, int K, int Kprime, int
                       size_t buflen) {
     if (!buf || buflen == 0) return ATK_INVALID_ARG;
     buf[0] = 0;
-    if (dtype != ATK_F32 && dtype != ATK_BF16) return ATK_UNSUPPORTED;
+    dtype = kernel_dtype(dtype);
+    if (dtype < 0) return ATK_UNSUPPORTED;
     if (rows < 0 || N <= 0 || N > 0x7fffffffLL) return ATK_INVALID_ARG;
     int rc = validate_method(N, K, Kprime, B);
     if (rc) return rc;

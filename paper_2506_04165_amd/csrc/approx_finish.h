@@ -16,9 +16,10 @@ struct FinishParams {
     int32_t* out_idx;
 };
 
-// dtype value for keys whose values are binary32 scores with no stored array behind them
+// dtype: 0 fp32, 1 bf16 (and fp16, same order of bit patterns), 3 int32, 4 uint32, or this
+// value for keys whose values are binary32 scores with no stored array behind them
 // (`values` is not read; out_vals is float)
-constexpr int kFinishScores = 2;
+constexpr int kFinishScores = 100;
 
 // KP: compiled list length (>= Kprime), one of 1,2,3,4,6,8,16,32
 hipError_t launch_finish(const FinishParams& p, int dtype, int KP, hipStream_t stream);

@@ -68,8 +68,13 @@ hipError_t launch_finish(const FinishParams& p, int dtype, int KP, hipStream_t s
     while (threads < p.B && threads < 512) threads <<= 1;
     if (threads < 256 && p.Cpad >= 1024) threads = 256;     // the sort wants more lanes than buckets
     if (dtype == kFinishScores) return launch_for<score_t>(p, KP, threads, stream);
-    return dtype == 0 ? launch_for<float>(p, KP, threads, stream)
-                      : launch_for<bf16_t>(p, KP, threads, stream);
+    switch (dtype) {
+        case 0: return launch_for<float>(p, KP, threads, stream);
+        case 1: return launch_for<bf16_t>(p, KP, threads, stream);
+        case 3: return launch_for<i32_t>(p, KP, threads, stream);
+        case 4: return launch_for<u32_t>(p, KP, threads, stream);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace atk

@@ -5,7 +5,9 @@
 #pragma once
 
 // X(DTYPE_TAG, C++ type, KP, V, R, REP)   REP: 0 value+step lists, 1 packed 32-bit keys,
-//                                          2 sorted batches of 64-bit keys
+//                                          2 sorted batches of 64-bit keys, 3 insertion lists of
+//                                          64-bit keys (integer inputs)
+// DTYPE_TAG: 0 fp32, 1 bf16 (fp16 runs on the bf16 kernels), 3 int32, 4 uint32
 #define ATK_INSTANCES_NL1(X, TAG, T, V, R, P) \
     X(TAG, T, 1, V, R, P) X(TAG, T, 2, V, R, P) X(TAG, T, 3, V, R, P) X(TAG, T, 4, V, R, P) \
     X(TAG, T, 6, V, R, P) X(TAG, T, 8, V, R, P) X(TAG, T, 16, V, R, P) X(TAG, T, 32, V, R, P)
@@ -31,6 +33,17 @@
     ATK_INSTANCES_NL4(X, 1, bf16_t, 4, 1, 0) ATK_INSTANCES_NL8(X, 1, bf16_t, 8, 1, 0) \
     ATK_INSTANCES_NL16(X, 1, bf16_t, 8, 2, 0)
 
+#define ATK_INSTANCES_I32_SMALL(X) \
+    ATK_INSTANCES_NL1(X, 3, i32_t, 1, 1, 3) ATK_INSTANCES_NL2(X, 3, i32_t, 2, 1, 3)
+#define ATK_INSTANCES_I32_WIDE(X) \
+    ATK_INSTANCES_NL4(X, 3, i32_t, 4, 1, 3) ATK_INSTANCES_NL8(X, 3, i32_t, 4, 2, 3) \
+    ATK_INSTANCES_NL16(X, 3, i32_t, 4, 4, 3)
+#define ATK_INSTANCES_U32_SMALL(X) \
+    ATK_INSTANCES_NL1(X, 4, u32_t, 1, 1, 3) ATK_INSTANCES_NL2(X, 4, u32_t, 2, 1, 3)
+#define ATK_INSTANCES_U32_WIDE(X) \
+    ATK_INSTANCES_NL4(X, 4, u32_t, 4, 1, 3) ATK_INSTANCES_NL8(X, 4, u32_t, 4, 2, 3) \
+    ATK_INSTANCES_NL16(X, 4, u32_t, 4, 4, 3)
+
 // single-element loads with several loads per step: for rows whose base address, stride or
 // bucket count rule out vector loads
 #define ATK_INSTANCES_F32_UNALIGNED(X) \
@@ -39,6 +52,13 @@
 #define ATK_INSTANCES_BF16_UNALIGNED(X) \
     ATK_INSTANCES_NL2(X, 1, bf16_t, 1, 2, 0) ATK_INSTANCES_NL4(X, 1, bf16_t, 1, 4, 0) \
     ATK_INSTANCES_NL8(X, 1, bf16_t, 1, 8, 0) ATK_INSTANCES_NL16(X, 1, bf16_t, 1, 16, 0)
+
+#define ATK_INSTANCES_I32_UNALIGNED(X) \
+    ATK_INSTANCES_NL2(X, 3, i32_t, 1, 2, 3) ATK_INSTANCES_NL4(X, 3, i32_t, 1, 4, 3) \
+    ATK_INSTANCES_NL8(X, 3, i32_t, 1, 8, 3) ATK_INSTANCES_NL16(X, 3, i32_t, 1, 16, 3)
+#define ATK_INSTANCES_U32_UNALIGNED(X) \
+    ATK_INSTANCES_NL2(X, 4, u32_t, 1, 2, 3) ATK_INSTANCES_NL4(X, 4, u32_t, 1, 4, 3) \
+    ATK_INSTANCES_NL8(X, 4, u32_t, 1, 8, 3) ATK_INSTANCES_NL16(X, 4, u32_t, 1, 16, 3)
 
 // bf16 rows of at most 65536 elements: lists of packed 32-bit keys
 #define ATK_PACKED_NL1(X, V, R) \
@@ -61,9 +81,13 @@
 // large K', at most 256 buckets: sorted batches of 64-bit keys, one list per lane
 #define ATK_INSTANCES_BATCHED(X) \
     X(0, float, 8, 1, 1, 2) X(0, float, 16, 1, 1, 2) X(0, float, 32, 1, 1, 2) \
-    X(1, bf16_t, 8, 1, 1, 2) X(1, bf16_t, 16, 1, 1, 2) X(1, bf16_t, 32, 1, 1, 2)
+    X(1, bf16_t, 8, 1, 1, 2) X(1, bf16_t, 16, 1, 1, 2) X(1, bf16_t, 32, 1, 1, 2) \
+    X(3, i32_t, 8, 1, 1, 2) X(3, i32_t, 16, 1, 1, 2) X(3, i32_t, 32, 1, 1, 2) \
+    X(4, u32_t, 8, 1, 1, 2) X(4, u32_t, 16, 1, 1, 2) X(4, u32_t, 32, 1, 1, 2)
 
 #define ATK_ALL_INSTANCES(X) \
     ATK_INSTANCES_F32_SMALL(X) ATK_INSTANCES_F32_WIDE(X) ATK_INSTANCES_F32_UNALIGNED(X) \
     ATK_INSTANCES_BF16_SMALL(X) ATK_INSTANCES_BF16_WIDE(X) ATK_INSTANCES_BF16_UNALIGNED(X) \
-    ATK_INSTANCES_BF16_PACKED(X) ATK_INSTANCES_BATCHED(X)
+    ATK_INSTANCES_BF16_PACKED(X) ATK_INSTANCES_BATCHED(X) \
+    ATK_INSTANCES_I32_SMALL(X) ATK_INSTANCES_I32_WIDE(X) ATK_INSTANCES_I32_UNALIGNED(X) \
+    ATK_INSTANCES_U32_SMALL(X) ATK_INSTANCES_U32_WIDE(X) ATK_INSTANCES_U32_UNALIGNED(X)

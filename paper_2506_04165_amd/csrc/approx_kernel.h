@@ -84,6 +84,7 @@ __device__ __forceinline__ uint32_t med3_u32(uint32_t a, uint32_t b, uint32_t c)
 template <int KP, int NL>
 struct Lists<0, KP, NL> {
     static constexpr bool exact_bits = true;     // entries keep the stored bit pattern
+    static constexpr bool holds_ordered = false; // bits() is the stored pattern itself
     float val[NL][KP];
     int32_t stp[NL][KP];
     __device__ __forceinline__ void init() {
@@ -118,6 +119,7 @@ struct Lists<0, KP, NL> {
 template <int KP, int NL>
 struct Lists<1, KP, NL> {
     static constexpr bool exact_bits = false;    // -0.0 is stored as +0.0
+    static constexpr bool holds_ordered = false;
     uint32_t key[NL][KP];
     __device__ __forceinline__ void init() {
 #pragma unroll
@@ -178,6 +180,7 @@ template <int KP, int NL>
 struct Lists<2, KP, NL> {
     static_assert(NL == 1, "sorted batches keep one list per lane");
     static constexpr bool exact_bits = false;    // -0.0 is stored as +0.0
+    static constexpr bool holds_ordered = true;
     uint64_t key[KP];                            // descending, 0 = empty
     __device__ __forceinline__ void init() {
 #pragma unroll
@@ -191,10 +194,44 @@ struct Lists<2, KP, NL> {
         reg_bitonic_merge_desc<KP>(key);
     }
     __device__ __forceinline__ bool valid(int, int k) const { return key[k] != 0; }
-    __device__ __forceinline__ uint32_t bits(int, int k) const { return key_value_bits(key[k]); }
+    // ordered image of the value (holds_ordered): the kernel maps it back for its element type
+    __device__ __forceinline__ uint32_t bits(int, int k) const { return (uint32_t)(key[k] >> 32); }
     // the low word of a key is ~step; e: offset of the slot inside a step
     __device__ __forceinline__ uint32_t index(int, int k, uint32_t S, uint32_t e) const {
         return (~(uint32_t)key[k]) * S + e;
+    }
+};
+
+//  * 64-bit keys with insertion (integer inputs): an entry is (ordered value << 32 | ~step), so
+//    "greater key" is the total order inside a list and an entry is never 0; the update is
+//    Algorithm 1 on keys: K' 64-bit compares, then every entry takes its upper neighbour, the
+//    new key or itself.  Float inputs do not use it: their value+step lists compare in one
+//    32-bit instruction.
+template <int KP, int NL>
+struct Lists<3, KP, NL> {
+    static constexpr bool exact_bits = true;
+    static constexpr bool holds_ordered = true;
+    uint64_t key[NL][KP];                        // descending, 0 = empty
+    __device__ __forceinline__ void init() {
+#pragma unroll
+        for (int l = 0; l < NL; ++l)
+#pragma unroll
+            for (int k = 0; k < KP; ++k) key[l][k] = 0;
+    }
+    __device__ __forceinline__ void insert(int l, uint32_t ordered, int32_t step) {
+        const uint64_t x = ((uint64_t)ordered << 32) | (uint32_t)(~(uint32_t)step);
+        bool c[KP];
+#pragma unroll
+        for (int k = 0; k < KP; ++k) c[k] = x > key[l][k];
+#pragma unroll
+        for (int k = KP - 1; k >= 1; --k)
+            key[l][k] = sel(c[k - 1], key[l][k - 1], sel(c[k], x, key[l][k]));
+        key[l][0] = sel(c[0], x, key[l][0]);
+    }
+    __device__ __forceinline__ bool valid(int l, int k) const { return key[l][k] != 0; }
+    __device__ __forceinline__ uint32_t bits(int l, int k) const { return (uint32_t)(key[l][k] >> 32); }
+    __device__ __forceinline__ uint32_t index(int l, int k, uint32_t S, uint32_t e) const {
+        return (~(uint32_t)key[l][k]) * S + e;
     }
 };
 
@@ -210,11 +247,21 @@ struct ApproxKernel {
     using vec_t = typename VL::vec_t;
     static_assert(!PACKED || elem<DT>::size == 2, "packed keys are for 16-bit inputs");
 
+    // Stored bit pattern of a list entry (lists of keys hold the ordered image instead).
+    __device__ static __forceinline__ uint32_t stored_bits(const Lists<REP, KP, NL>& L, int l, int k) {
+        if constexpr (Lists<REP, KP, NL>::holds_ordered) return elem<DT>::from_ordered(L.bits(l, k));
+        else return L.bits(l, k);
+    }
+
     // Feed the V elements of one load into their lists.
     __device__ static __forceinline__ void consume(Lists<REP, KP, NL>& L, const vec_t& x, int r,
                                                    int step) {
         if constexpr (BATCHED) {
             (void)L; (void)x; (void)r; (void)step;       // batches are fed by the streaming loop
+        } else if constexpr (REP == 3) {
+#pragma unroll
+            for (int v = 0; v < V; ++v)
+                L.insert(r * V + v, elem<DT>::ordered(VL::bits(x, v)), step);
         } else if constexpr (!PACKED) {
 #pragma unroll
             for (int v = 0; v < V; ++v)
@@ -297,7 +344,7 @@ struct ApproxKernel {
                 uint64_t batch[KP];
 #pragma unroll
                 for (int u = 0; u < KP; ++u) {
-                    const uint64_t key = ((uint64_t)ordered_from_bits(VL::bits(buf[u], 0)) << 32) |
+                    const uint64_t key = ((uint64_t)elem<DT>::ordered(VL::bits(buf[u], 0)) << 32) |
                                          (uint32_t)(~(uint32_t)(s + u));
                     batch[u] = u < nb ? key : 0;
                 }
@@ -384,13 +431,13 @@ struct ApproxKernel {
                         if (!live || k >= p.Kprime) continue;
                         const int l = r * V + v;
                         const uint32_t n = L.index(l, k, (uint32_t)p.S, (uint32_t)bucket);
-                        uint32_t b = L.bits(l, k);
+                        uint32_t b = stored_bits(L, l, k);
                         if (p.mode == 0) {
-                            cand[bucket * p.Kprime + k] = make_key(b, n);
+                            cand[bucket * p.Kprime + k] = make_key<DT>(b, n);
                         } else if (p.mode == 2) {
                             // a segment shorter than K' steps leaves empty entries
                             const int64_t o = (((int64_t)row * p.nseg + blockIdx.y) * p.Kprime + k) * p.B + bucket;
-                            p.part_keys[o] = L.valid(l, k) ? make_key(b, n) : 0;
+                            p.part_keys[o] = L.valid(l, k) ? make_key<DT>(b, n) : 0;
                         } else {
                             if (!Lists<REP, KP, NL>::exact_bits && b == 0)
                                 b = elem<DT>::load_bits(rowp, n);       // which zero it was
@@ -420,7 +467,7 @@ struct ApproxKernel {
                     for (int k = 0; k < KP; ++k) {
                         const uint32_t n = L.index(v, k, (uint32_t)p.S, (uint32_t)e);
                         if (L.valid(v, k))
-                            part[(size_t)bucket * p.seg + owner * KP + k] = make_key(L.bits(v, k), n);
+                            part[(size_t)bucket * p.seg + owner * KP + k] = make_key<DT>(stored_bits(L, v, k), n);
                     }
                 }
             }
@@ -433,7 +480,7 @@ struct ApproxKernel {
                     cand[i] = key;
                 } else if (row_ok) {
                     const uint32_t n = key_index(key);
-                    uint32_t b = key_value_bits(key);
+                    uint32_t b = key_value_bits<DT>(key);
                     if (b == 0 && key != 0) b = elem<DT>::load_bits(rowp, n);   // which zero it was
                     const int64_t o = ((int64_t)row * p.Kprime + k) * p.B + bucket;
                     elem<DT>::store_bits(p.surv_vals, o, b);
@@ -462,7 +509,7 @@ struct ApproxKernel {
             for (int i = t; i < p.K; i += p.G) {
                 const uint64_t key = cand[i];
                 const uint32_t n = key_index(key);
-                uint32_t b = key_value_bits(key);
+                uint32_t b = key_value_bits<DT>(key);
                 if (b == 0 && key != 0) b = elem<DT>::load_bits(rowp, n);       // which zero it was
                 elem<DT>::store_bits(p.out_vals, (int64_t)row * p.K + i, b);
                 p.out_idx[(int64_t)row * p.K + i] = (int32_t)n;

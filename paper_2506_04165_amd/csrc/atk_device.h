@@ -23,18 +23,15 @@ __device__ __forceinline__ uint32_t ordered_from_bits(uint32_t b) {
 __device__ __forceinline__ uint32_t bits_from_ordered(uint32_t o) {
     return (o >= 0x80000000u) ? (o - 0x80000000u) : (0u - o);   // a zero decodes as +0.0
 }
-__device__ __forceinline__ uint64_t make_key(uint32_t value_bits, uint32_t index) {
-    return ((uint64_t)ordered_from_bits(value_bits) << 32) | (uint32_t)(~index);
-}
 __device__ __forceinline__ uint32_t key_index(uint64_t key) { return ~(uint32_t)key; }
-__device__ __forceinline__ uint32_t key_value_bits(uint64_t key) {
-    return bits_from_ordered((uint32_t)(key >> 32));
-}
 
 // ---- element access ---------------------------------------------------------------------
 template <typename DT> struct elem;
 template <> struct elem<float> {
     static constexpr int size = 4;
+    // order-preserving image of the element's binary32 pattern, and back
+    __device__ static uint32_t ordered(uint32_t bits) { return ordered_from_bits(bits); }
+    __device__ static uint32_t from_ordered(uint32_t o) { return bits_from_ordered(o); }
     __device__ static uint32_t load_bits(const void* base, int64_t i) {
         return ((const uint32_t*)base)[i];
     }
@@ -44,6 +41,9 @@ template <> struct elem<float> {
 };
 template <> struct elem<bf16_t> {
     static constexpr int size = 2;
+    // order-preserving image of the element's binary32 pattern, and back
+    __device__ static uint32_t ordered(uint32_t bits) { return ordered_from_bits(bits); }
+    __device__ static uint32_t from_ordered(uint32_t o) { return bits_from_ordered(o); }
     __device__ static uint32_t load_bits(const void* base, int64_t i) {
         return (uint32_t)((const uint16_t*)base)[i] << 16;
     }
@@ -57,11 +57,45 @@ template <> struct elem<bf16_t> {
 struct score_t {};
 template <> struct elem<score_t> {
     static constexpr int size = 4;
+    // order-preserving image of the element's binary32 pattern, and back
+    __device__ static uint32_t ordered(uint32_t bits) { return ordered_from_bits(bits); }
+    __device__ static uint32_t from_ordered(uint32_t o) { return bits_from_ordered(o); }
     __device__ static uint32_t load_bits(const void*, int64_t) { return 0; }
     __device__ static void store_bits(void* base, int64_t i, uint32_t b) {
         ((uint32_t*)base)[i] = b;
     }
 };
+
+// 32-bit integers (the compute types signed and unsigned inputs are promoted to in Section 6.3's
+// listing).  "bits" is the stored word; the ordered image flips the sign bit of signed values.
+// Every word is a legitimate value, so nothing in the value half marks "empty": keys stay
+// distinct from 0 through their index half.
+struct i32_t {};
+struct u32_t {};
+template <> struct elem<i32_t> {
+    static constexpr int size = 4;
+    __device__ static uint32_t ordered(uint32_t bits) { return bits ^ 0x80000000u; }
+    __device__ static uint32_t from_ordered(uint32_t o) { return o ^ 0x80000000u; }
+    __device__ static uint32_t load_bits(const void* base, int64_t i) { return ((const uint32_t*)base)[i]; }
+    __device__ static void store_bits(void* base, int64_t i, uint32_t b) { ((uint32_t*)base)[i] = b; }
+};
+template <> struct elem<u32_t> {
+    static constexpr int size = 4;
+    __device__ static uint32_t ordered(uint32_t bits) { return bits; }
+    __device__ static uint32_t from_ordered(uint32_t o) { return o; }
+    __device__ static uint32_t load_bits(const void* base, int64_t i) { return ((const uint32_t*)base)[i]; }
+    __device__ static void store_bits(void* base, int64_t i, uint32_t b) { ((uint32_t*)base)[i] = b; }
+};
+
+// key of an element: ordered image of its value in the high word, ~index in the low word
+template <typename DT>
+__device__ __forceinline__ uint64_t make_key(uint32_t value_bits, uint32_t index) {
+    return ((uint64_t)elem<DT>::ordered(value_bits) << 32) | (uint32_t)(~index);
+}
+template <typename DT>
+__device__ __forceinline__ uint32_t key_value_bits(uint64_t key) {
+    return elem<DT>::from_ordered((uint32_t)(key >> 32));
+}
 
 // A load of V consecutive elements as one memory instruction (2, 4, 8 or 16 bytes).
 template <int BYTES> struct vec_bytes;

@@ -203,7 +203,7 @@ __global__ void __launch_bounds__(256) mips_stage1_kernel(MipsParams p) {
                 const int bl = 8 * (i >> 2) + 4 * half + (i & 3);
                 const uint32_t n = (uint32_t)L.stp[i][k] * (uint32_t)p.B + (uint32_t)(b0 + bl);
                 *(uint64_t*)(stage_w + col * kStageRowBytes + bl * 8) =
-                    L.valid(i, k) ? make_key(L.bits(i, k), n) : 0;
+                    L.valid(i, k) ? make_key<score_t>(L.bits(i, k), n) : 0;
             }
             __syncthreads();
             // 16 lanes x 16 bytes cover one query's row; a wavefront stores 4 rows at a time

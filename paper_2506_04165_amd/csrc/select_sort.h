@@ -128,7 +128,7 @@ __device__ __forceinline__ void wave_write_topk(const uint64_t (&k)[R], int K, c
         const int e = lane * R + j;
         if (e < K) {
             const uint32_t n = key_index(k[j]);
-            uint32_t bits = key_value_bits(k[j]);
+            uint32_t bits = key_value_bits<DT>(k[j]);
             if (bits == 0 && k[j] != 0) bits = elem<DT>::load_bits(rowp, n);   // which zero it was
             elem<DT>::store_bits(out_vals, out_base + e, bits);
             out_idx[out_base + e] = (int32_t)n;
@@ -271,7 +271,7 @@ __device__ __forceinline__ void wg_write_topk(const uint64_t* keys, int K, const
     for (int i = threadIdx.x; i < K; i += blockDim.x) {
         const uint64_t key = keys[i];
         const uint32_t idx = key_index(key);
-        uint32_t bits = key_value_bits(key);
+        uint32_t bits = key_value_bits<DT>(key);
         if (bits == 0 && key != 0) bits = elem<DT>::load_bits(rowp, idx);   // which zero it was
         elem<DT>::store_bits(out_vals, out_base + i, bits);
         out_idx[out_base + i] = (int32_t)idx;

@@ -105,7 +105,7 @@ __global__ void __launch_bounds__(1024) topk_exact_kernel(TopkParams p) {
         for (int base = 0; base < N; base += chunk) {
             const int end = min(N, base + chunk);
             for_each_element<DT, VEC>(rowp, base, end, [&](uint32_t b, int) {
-                const uint32_t d = ordered_from_bits(b) >> 21;
+                const uint32_t d = elem<DT>::ordered(b) >> 21;
                 if (d >= dmin) atomicAdd(&hist[d], 1u);
             });
             // (only once at least K keys have been counted: the walk needs K of them)
@@ -129,7 +129,7 @@ __global__ void __launch_bounds__(1024) topk_exact_kernel(TopkParams p) {
             for (int i = tid; i < kSelectBins; i += T) hist[i] = 0;
             __syncthreads();
             for_each_element<DT, VEC>(rowp, 0, N, [&](uint32_t b, int n) {
-                const uint64_t key = make_key(b, index_of(n));
+                const uint64_t key = make_key<DT>(b, index_of(n));
                 if ((key & mask) == prefix) atomicAdd(&hist[(uint32_t)(key >> shift) & dmask], 1u);
             });
             hist_find_digit(hist, ctl, need, digit, above, count);
@@ -145,7 +145,7 @@ __global__ void __launch_bounds__(1024) topk_exact_kernel(TopkParams p) {
     __syncthreads();
     for_each_element<DT, VEC>(rowp, 0, N, [&](uint32_t b, int n) {
         // cheap reject on the value word before the full key is built
-        const uint32_t ord = ordered_from_bits(b);
+        const uint32_t ord = elem<DT>::ordered(b);
         if (ord >= (uint32_t)(prefix >> 32)) {
             const uint64_t key = ((uint64_t)ord << 32) | (uint32_t)(~index_of(n));
             if ((key & mask) >= prefix) {
@@ -168,7 +168,7 @@ __global__ void __launch_bounds__(1024) topk_exact_kernel(TopkParams p) {
     for (int i = tid; i < p.K; i += T) {
         const uint64_t key = lds64[i];
         const uint32_t idx = key_index(key);
-        uint32_t b = key_value_bits(key);
+        uint32_t b = key_value_bits<DT>(key);
         if (b == 0 && key != 0) {
             // rare: look the survivor up by its index to tell -0.0 from +0.0
             for (int n = 0; n < N; ++n)
@@ -194,7 +194,13 @@ hipError_t launch_for(const TopkParams& p, int threads, hipStream_t stream) {
 }  // namespace
 
 hipError_t launch_topk_exact(const TopkParams& p, int dtype, int threads, hipStream_t stream) {
-    return dtype == 0 ? launch_for<float>(p, threads, stream) : launch_for<bf16_t>(p, threads, stream);
+    switch (dtype) {
+        case 0: return launch_for<float>(p, threads, stream);
+        case 1: return launch_for<bf16_t>(p, threads, stream);
+        case 3: return launch_for<i32_t>(p, threads, stream);
+        case 4: return launch_for<u32_t>(p, threads, stream);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace atk

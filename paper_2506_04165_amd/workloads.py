@@ -162,9 +162,11 @@ def make(name: str, seed: int = 1, device="cpu", rows: int | None = None):
 
 
 def to_numpy_bits(x: torch.Tensor):
-    """Host NumPy view for the oracle: float32 as is, bf16 as uint16 bit patterns."""
+    """Host NumPy view for the oracle: bf16 as uint16 bit patterns, everything else as is."""
     import numpy as np
     x = x.detach().cpu().contiguous()
     if x.dtype == torch.bfloat16:
         return x.view(torch.int16).numpy().view(np.uint16)
+    if x.dtype == torch.uint32:
+        return x.view(torch.int32).numpy().view(np.uint32)
     return x.numpy()
