@@ -267,6 +267,24 @@ static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, in
         if (ws_cap > ws_avail) ws_cap = ws_avail;
         if ((size_t)want > ws_cap / per_seg) want = (int)(ws_cap / per_seg);
         if (in_bytes < kMinSplitBytes) want = 1;
+        // Fewer segments than would fill the chip can still be faster: the finishing launch
+        // merges nseg*K' keys per bucket, sixteen loads at a time, and few rows make it pure
+        // latency.  Rough per-row model in microseconds (constants measured on 8 x 262144 rows):
+        // a workgroup streams ~45 GB/s on its own, the second launch and the round trip through
+        // memory cost ~6, every batch of sixteen keys per bucket pass ~3.
+        if (want > 1) {
+            const double row_bytes = (double)N * es;
+            auto cost = [&](int n) {
+                const double stream = row_bytes / n / 45e3;
+                if (n == 1) return stream;
+                const int batches = ((n * Kp + 15) / 16) * ((B + 511) / 512);
+                return stream + 6.0 + 3.0 * batches;
+            };
+            int best = 1;
+            for (int n = 2; n <= want; n = (n * 2 <= want || n == want) ? n * 2 : want)
+                if (cost(n) < cost(best)) best = n;
+            want = best;
+        }
         const int forced = env_int("ATK_SEGMENTS", 0);
         if (forced > 0 && (size_t)forced * per_seg <= ws_avail) want = forced;
         if (want > pl.nsteps) want = pl.nsteps;

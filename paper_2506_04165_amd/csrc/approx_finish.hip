@@ -21,13 +21,22 @@ __global__ void __launch_bounds__(1024) approx_finish_kernel(FinishParams p) {
     const int C = p.B * p.Kprime;
     for (int i = C + tid; i < p.Cpad; i += T) cand[i] = 0;
     const uint64_t* part = p.part_keys + (size_t)row * p.nseg * p.Kprime * p.B;
+    // The nseg*K' keys of a bucket lie B apart: key j of bucket b is part[j*B + b].  They are
+    // fetched sixteen at a time before any is used, so that their latencies overlap (one row
+    // can be all the work there is).
+    const int per_bucket = p.nseg * p.Kprime;
     for (int b = tid; b < p.B; b += T) {
         uint64_t top[KP];
 #pragma unroll
         for (int j = 0; j < KP; ++j) top[j] = 0;
-        for (int q = 0; q < p.nseg; ++q) {
-            for (int k = 0; k < p.Kprime; ++k) {
-                const uint64_t key = part[((size_t)q * p.Kprime + k) * p.B + b];
+        for (int j0 = 0; j0 < per_bucket; j0 += 16) {
+            uint64_t in[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u)
+                in[u] = (j0 + u < per_bucket) ? part[(size_t)(j0 + u) * p.B + b] : 0;
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const uint64_t key = in[u];
                 bool c[KP];
 #pragma unroll
                 for (int j = 0; j < KP; ++j) c[j] = key > top[j];

@@ -83,7 +83,7 @@ __device__ __forceinline__ uint32_t med3_u32(uint32_t a, uint32_t b, uint32_t c)
 
 template <int KP, int NL>
 struct Lists<0, KP, NL> {
-    static constexpr bool exact_bits = true;     // entries keep the stored bit pattern
+    static constexpr bool exact_bits = false;    // a zero entry may carry the other zero's sign
     static constexpr bool holds_ordered = false; // bits() is the stored pattern itself
     float val[NL][KP];
     int32_t stp[NL][KP];
@@ -107,6 +107,23 @@ struct Lists<0, KP, NL> {
         }
         val[l][0] = sel(c[0], x, val[l][0]);
         stp[l][0] = sel(c[0], step, stp[l][0]);
+    }
+    // The same update once no entry is empty any more (K' elements have gone through the list):
+    // the values need no compare-and-select, entry k becomes the median of (entry k-1, entry k,
+    // element) -- the shift of Algorithm 1 as a clamp; only the steps follow the compares.
+    // 4K'-1 lane operations.  The median may return either zero when +0.0 meets -0.0, which is
+    // why a zero is re-read from the row when it is reported (exact_bits is false).
+    __device__ __forceinline__ void insert_full(int l, float x, int32_t step) {
+        bool c[KP];
+#pragma unroll
+        for (int k = 0; k < KP; ++k) c[k] = x > val[l][k];
+#pragma unroll
+        for (int k = KP - 1; k >= 1; --k) {
+            stp[l][k] = sel(c[k - 1], stp[l][k - 1], sel(c[k], step, stp[l][k]));
+            val[l][k] = __builtin_amdgcn_fmed3f(val[l][k - 1], val[l][k], x);
+        }
+        stp[l][0] = sel(c[0], step, stp[l][0]);
+        val[l][0] = sel(c[0], x, val[l][0]);
     }
     __device__ __forceinline__ bool valid(int l, int k) const { return val[l][k] == val[l][k]; }
     __device__ __forceinline__ uint32_t bits(int l, int k) const { return __float_as_uint(val[l][k]); }
@@ -254,6 +271,9 @@ struct ApproxKernel {
     }
 
     // Feed the V elements of one load into their lists.
+    // FULL: every list has already taken K' elements (value+step lists then use the shorter
+    // update).
+    template <bool FULL = false>
     __device__ static __forceinline__ void consume(Lists<REP, KP, NL>& L, const vec_t& x, int r,
                                                    int step) {
         if constexpr (BATCHED) {
@@ -264,8 +284,10 @@ struct ApproxKernel {
                 L.insert(r * V + v, elem<DT>::ordered(VL::bits(x, v)), step);
         } else if constexpr (!PACKED) {
 #pragma unroll
-            for (int v = 0; v < V; ++v)
-                L.insert(r * V + v, __uint_as_float(VL::bits(x, v)), step);
+            for (int v = 0; v < V; ++v) {
+                if constexpr (FULL && KP > 1) L.insert_full(r * V + v, __uint_as_float(VL::bits(x, v)), step);
+                else L.insert(r * V + v, __uint_as_float(VL::bits(x, v)), step);
+            }
         } else {
             // Low half of every key of this step: 0xFFFF - step.  All elements of one list share
             // the slot, so the step alone orders them; the position is rebuilt from it later.
@@ -351,6 +373,19 @@ struct ApproxKernel {
                 L.merge(batch);
             }
         } else {
+        // every slot takes one element per step: after KP steps no list entry is empty
+        constexpr bool TWO_PHASE = REP == 0 && KP > 1;
+        if constexpr (TWO_PHASE) {
+            const int fill_end = min(s_end, s + KP);
+            for (; s < fill_end; ++s) {
+                const buffer_rsrc rs = make_rsrc(wg_base + (size_t)s * step_bytes);
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    vec_t x = VL::load(rs, lane_off[r], 0);
+                    consume<false>(L, x, r, s);
+                }
+            }
+        }
         for (; s + U <= s_end; s += U) {
             const buffer_rsrc rs = make_rsrc(wg_base + (size_t)s * step_bytes);
             vec_t buf[U][R];
@@ -363,14 +398,14 @@ struct ApproxKernel {
             for (int u = 0; u < U; ++u)
 #pragma unroll
                 for (int r = 0; r < R; ++r)
-                    consume(L, buf[u][r], r, s + u);
+                    consume<TWO_PHASE>(L, buf[u][r], r, s + u);
         }
         for (; s < s_end; ++s) {
             const buffer_rsrc rs = make_rsrc(wg_base + (size_t)s * step_bytes);
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 vec_t x = VL::load(rs, lane_off[r], 0);
-                consume(L, x, r, s);
+                consume<TWO_PHASE>(L, x, r, s);
             }
         }
         }
@@ -439,7 +474,7 @@ struct ApproxKernel {
                             const int64_t o = (((int64_t)row * p.nseg + blockIdx.y) * p.Kprime + k) * p.B + bucket;
                             p.part_keys[o] = L.valid(l, k) ? make_key<DT>(b, n) : 0;
                         } else {
-                            if (!Lists<REP, KP, NL>::exact_bits && b == 0)
+                            if (!Lists<REP, KP, NL>::exact_bits && (b << 1) == 0)   // either zero
                                 b = elem<DT>::load_bits(rowp, n);       // which zero it was
                             const int64_t o = ((int64_t)row * p.Kprime + k) * p.B + bucket;
                             elem<DT>::store_bits(p.surv_vals, o, b);

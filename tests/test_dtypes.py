@@ -151,7 +151,9 @@ def test_integer_rows_every_route(atk, rows, N, K, Kp, B, route, unsigned):
 
 @pytest.mark.gpu
 @pytest.mark.parametrize("rows,N,K,Kp,B,route", ROUTES)
-def test_half_rows_every_route(atk, rows, N, K, Kp, B, route):
+def test_half_rows_every_route(atk, rows, N, K, Kp, B, route, monkeypatch):
+    if route == "split":     # rows this short are not split by themselves: ask for it
+        monkeypatch.setenv("ATK_SEGMENTS", "4")
     for kind in ("patterns", "gauss"):
         check(atk, half_rows(rows, N, seed=32, kind=kind), K, Kp, B, route)
 
