@@ -18,9 +18,11 @@
  *     `stream` (a hipStream_t passed as void*, NULL = the default stream) and the call returns;
  *   - `values` is row-major [rows, N] with `row_stride` elements between consecutive rows
  *     (row_stride >= N); outputs are dense row-major;
- *   - dtype: ATK_F32 = IEEE binary32, ATK_BF16 = bfloat16 (compared after exact widening to
- *     binary32, Section 6.3); output values have the input dtype and are the stored bits of the
- *     selected elements; indices are int32 positions inside the row;
+ *   - dtype: ATK_F32 = IEEE binary32; ATK_BF16 = bfloat16 and ATK_F16 = IEEE binary16 (compared
+ *     after exact widening to binary32); ATK_I32 / ATK_U32 = 32-bit integers compared as such
+ *     (the compute-type promotion of Section 6.3's listing); output values have the input
+ *     dtype and are the stored bits of the selected elements; indices are int32 positions
+ *     inside the row;
  *   - the return value is an atk_status; arguments are validated on the host before anything
  *     is launched, so every error below can be provoked without a GPU;
  *   - rows == 0 is legal and does nothing.
@@ -29,7 +31,8 @@
  * production): ATK_LANES_PER_ROW=<power of two <= 1024> lanes that share one row,
  * ATK_SEGMENTS=<n> force n row segments on the split route, ATK_NO_PACKED=1 / ATK_NO_SUBWAVE=1
  * switch the packed-key / several-rows-per-wavefront variants off, ATK_BATCH_MIN_KP=<k> list
- * length from which sorted batches are used.  Results never depend on them.
+ * length from which sorted batches are used, ATK_MIPS_SEGMENTS=<n> segments of the database walk
+ * in atk_mips_approx_topk.  Results never depend on them.
  */
 #ifndef ATK_H_
 #define ATK_H_
@@ -72,8 +75,8 @@ typedef enum atk_op { ATK_OP_APPROX_TOPK = 0, ATK_OP_TOPK = 1, ATK_OP_STAGE1 = 2
  *              NULL when that is 0 (it is 0 whenever stage 2 runs fused in the stage-1 launch,
  *              i.e. when the B*K' survivors of a row fit in LDS; otherwise survivors go through
  *              this buffer and a second launch finishes)
- * ATK_UNSUPPORTED: K' > 32 unless K' == K (then the exact kernel runs); B*K' > 32768;
- * K > 2048 on the exact and unfused routes.
+ * ATK_UNSUPPORTED: K' > 32 unless K' == K (then the exact kernel runs); more than 16384 list
+ * entries per row in the stage-1 launch; K > 2048 on the exact and unfused routes.
  */
 int atk_approx_topk(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride,
                     int K, int Kprime, int B, void* out_vals, int32_t* out_idx,
