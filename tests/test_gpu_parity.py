@@ -391,3 +391,38 @@ def test_full_size_sampled_rows_and_properties(atk, name):
     ov, oi = oracle.topk(xh, w.K)
     assert np.array_equal(gi.cpu().numpy()[sel], oi), name
     assert np.array_equal(bits(gv)[sel], host_bits(ov)), name
+
+
+def test_hip_graph_capture_and_replay(atk):
+    # The library enqueues on the caller's stream, allocates nothing and never synchronises, so a
+    # call can be captured into a HIP graph.  Every replay (with eager work and synchronisation
+    # in between, and new contents in the captured input buffer) must equal the eager result.
+    cases = [
+        ("fused", lambda x, out, ws: atk.approx_topk(x, 128, 4, 1024, out=out, workspace=ws), (32, 65536)),
+        ("split", lambda x, out, ws: atk.approx_topk(x, 1024, 4, 1024, out=out, workspace=ws), (8, 262144)),
+    ]
+    for name, call, (rows, N) in cases:
+        K = 128 if name == "fused" else 1024
+        static_in = workloads.gaussian(rows, N, seed=70).to(DEV)
+        ws = torch.empty(64 << 20, dtype=torch.uint8, device=DEV)
+        out = (torch.empty((rows, K), device=DEV), torch.empty((rows, K), dtype=torch.int32, device=DEV))
+        ref = (torch.empty_like(out[0]), torch.empty_like(out[1]))
+        call(static_in, out, ws)                       # eager once before capturing
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        with torch.cuda.graph(graph, stream=side):
+            call(static_in, out, ws)
+        for replay in range(4):
+            fresh = workloads.gaussian(rows, N, seed=71 + replay).to(DEV)
+            static_in.copy_(fresh)
+            out[0].zero_(); out[1].zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            call(fresh, ref, ws)                       # eager, same input
+            torch.cuda.synchronize()
+            assert torch.equal(out[1], ref[1]) and torch.equal(out[0], ref[0]), (name, replay)
+        # and one replay against the oracle
+        ov, oi = oracle.approx_topk(static_in.cpu().numpy()[:2], K, 4, 1024)
+        assert np.array_equal(out[1].cpu().numpy()[:2], oi)
