@@ -370,7 +370,8 @@ MipsPlan make_mips_plan(int dtype, int64_t Q, int64_t N, int64_t D, int K, int K
     }
     pl.KP = Kprime <= 2 ? Kprime : 4;
     pl.nslab = B / kMipsSlab;
-    pl.nqt = (int)((Q + kMipsQueryTile - 1) / kMipsQueryTile);
+    const int qtile = kMipsQueryTile * mips_subtiles(pl.KP, (int)D);
+    pl.nqt = (int)((Q + qtile - 1) / qtile);
     const int nsteps = (int)(N / B);
     const int64_t pairs = (int64_t)pl.nslab * (pl.nqt > 0 ? pl.nqt : 1);
     int nseg = (int)((kMipsTargetWorkgroups + pairs - 1) / pairs);

@@ -7,6 +7,7 @@
 //   * Steps 3-4: the B*K' merged keys go to LDS; radix selection thins them out, one wavefront
 //     sorts what is left in registers and writes the first K.
 #include "approx_finish.h"
+#include <type_traits>
 #include "atk_device.h"
 #include "select_sort.h"
 
@@ -21,33 +22,56 @@ __global__ void __launch_bounds__(1024) approx_finish_kernel(FinishParams p) {
     const int C = p.B * p.Kprime;
     for (int i = C + tid; i < p.Cpad; i += T) cand[i] = 0;
     const uint64_t* part = p.part_keys + (size_t)row * p.nseg * p.Kprime * p.B;
-    // The nseg*K' keys of a bucket lie B apart: key j of bucket b is part[j*B + b].  They are
-    // fetched sixteen at a time before any is used, so that their latencies overlap (one row
-    // can be all the work there is).
+    // The nseg*K' keys of a bucket lie B apart: key j of bucket b is part[j*B + b].  Sixteen
+    // loads are issued before any key is used, so that their latencies overlap (one row can be
+    // all the work there is): sixteen keys of one bucket, or four keys of four buckets when a
+    // bucket has few.
     const int per_bucket = p.nseg * p.Kprime;
-    for (int b = tid; b < p.B; b += T) {
-        uint64_t top[KP];
+    auto merge_tile = [&](auto nb_tag) {
+        constexpr int NB = decltype(nb_tag)::value, NK = 16 / NB;
+        for (int b0 = tid; b0 < p.B; b0 += T * NB) {
+            uint64_t top[NB][KP];
 #pragma unroll
-        for (int j = 0; j < KP; ++j) top[j] = 0;
-        for (int j0 = 0; j0 < per_bucket; j0 += 16) {
-            uint64_t in[16];
+            for (int v = 0; v < NB; ++v)
 #pragma unroll
-            for (int u = 0; u < 16; ++u)
-                in[u] = (j0 + u < per_bucket) ? part[(size_t)(j0 + u) * p.B + b] : 0;
+                for (int j = 0; j < KP; ++j) top[v][j] = 0;
+            for (int j0 = 0; j0 < per_bucket; j0 += NK) {
+                uint64_t in[NB][NK];
 #pragma unroll
-            for (int u = 0; u < 16; ++u) {
-                const uint64_t key = in[u];
-                bool c[KP];
+                for (int v = 0; v < NB; ++v)
 #pragma unroll
-                for (int j = 0; j < KP; ++j) c[j] = key > top[j];
+                    for (int u = 0; u < NK; ++u) {
+                        const int b = b0 + v * T;
+                        in[v][u] = (b < p.B && j0 + u < per_bucket) ? part[(size_t)(j0 + u) * p.B + b] : 0;
+                    }
 #pragma unroll
-                for (int j = KP - 1; j >= 1; --j) top[j] = c[j - 1] ? top[j - 1] : (c[j] ? key : top[j]);
-                top[0] = c[0] ? key : top[0];
+                for (int v = 0; v < NB; ++v)
+#pragma unroll
+                    for (int u = 0; u < NK; ++u) {
+                        const uint64_t key = in[v][u];
+                        bool c[KP];
+#pragma unroll
+                        for (int j = 0; j < KP; ++j) c[j] = key > top[v][j];
+#pragma unroll
+                        for (int j = KP - 1; j >= 1; --j)
+                            top[v][j] = c[j - 1] ? top[v][j - 1] : (c[j] ? key : top[v][j]);
+                        top[v][0] = c[0] ? key : top[v][0];
+                    }
+            }
+#pragma unroll
+            for (int v = 0; v < NB; ++v) {
+                const int b = b0 + v * T;
+#pragma unroll
+                for (int j = 0; j < KP; ++j)
+                    if (b < p.B && j < p.Kprime) cand[b * p.Kprime + j] = top[v][j];
             }
         }
-#pragma unroll
-        for (int j = 0; j < KP; ++j)
-            if (j < p.Kprime) cand[b * p.Kprime + j] = top[j];
+    };
+    if constexpr (KP <= 4) {
+        if (per_bucket <= 4) merge_tile(std::integral_constant<int, 4>{});
+        else merge_tile(std::integral_constant<int, 1>{});
+    } else {
+        merge_tile(std::integral_constant<int, 1>{});
     }
     __syncthreads();
     const char* rowp = (const char*)p.values + (size_t)row * p.row_stride * elem<DT>::size;

@@ -15,12 +15,16 @@ struct MipsParams {
     int nseg;                   // parts the element range of every bucket is cut into
     int seg_steps;              // steps per part (the last one may be shorter)
     int nslab;                  // B / 32: bucket slabs
-    int nqt;                    // ceil(Q / 128): query tiles
+    int nqt;                    // query tiles: ceil(Q / (128 * sub-tiles per wavefront))
     uint64_t* part_keys;        // [Q, nseg, K', B] keys, 0 = empty entry
 };
 
 constexpr int kMipsSlab = 32;        // buckets per workgroup
-constexpr int kMipsQueryTile = 128;  // queries per workgroup (4 wavefronts x 32)
+constexpr int kMipsQueryTile = 128;  // queries per workgroup and sub-tile (4 wavefronts x 32)
+
+// 32-query sub-tiles a wavefront computes per step for lists of length KP and dimension D
+// (p.nqt must be ceil(Q / (kMipsQueryTile * this))): two while the registers allow it
+constexpr int mips_subtiles(int KP, int D) { return (KP == 1 && D <= 128) ? 2 : 1; }
 
 // KP: compiled list length (1, 2 or 4, >= Kprime); D one of 64, 128, 256.
 hipError_t launch_mips_stage1(const MipsParams& p, int KP, hipStream_t stream);

@@ -72,7 +72,10 @@ struct ScoreLists {
     __device__ __forceinline__ uint32_t bits(int i, int k) const { return __float_as_uint(val[i][k]); }
 };
 
-template <int KP, int KS>   // KS = D / 16: matrix instructions per tile
+// KS = D / 16: matrix instructions per score tile; MQ: 32-query sub-tiles per wavefront.  With
+// MQ = 2 every database fragment read from LDS feeds two matrix instructions (half the LDS
+// traffic per score) at the price of twice the lists: only short lists leave room for that.
+template <int KP, int KS, int MQ>
 __global__ void __launch_bounds__(256) mips_stage1_kernel(MipsParams p) {
     constexpr int D = KS * 16;
     constexpr int kRowBytes = D * 2 + 16;             // padded: rows 16 apart share no LDS bank
@@ -107,17 +110,22 @@ __global__ void __launch_bounds__(256) mips_stage1_kernel(MipsParams p) {
     const int j1 = min(p.nsteps, j0 + p.seg_steps);
 
     // ---- query fragments: lane (col, half) holds query col, dims (2s + half)*8 .. +8 of step s ---
-    const int q = qt * kMipsQueryTile + wave * 32 + col;
-    bf16x8 qf[KS];
+    const int q_first = (qt * 4 + wave) * (32 * MQ);          // first query of this wavefront
+    bf16x8 qf[MQ][KS];
 #pragma unroll
-    for (int s = 0; s < KS; ++s) {
-        u32x4 w = {0, 0, 0, 0};
-        if (q < p.Q) w = *(const u32x4*)(p.queries + (size_t)q * D + (2 * s + half) * 8);
-        qf[s] = __builtin_bit_cast(bf16x8, w);
+    for (int m = 0; m < MQ; ++m) {
+        const int q = q_first + m * 32 + col;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            u32x4 w = {0, 0, 0, 0};
+            if (q < p.Q) w = *(const u32x4*)(p.queries + (size_t)q * D + (2 * s + half) * 8);
+            qf[m][s] = __builtin_bit_cast(bf16x8, w);
+        }
     }
 
-    ScoreLists<KP> L;
-    L.init();
+    ScoreLists<KP> L[MQ];
+#pragma unroll
+    for (int m = 0; m < MQ; ++m) L[m].init();
 
     // ---- walk ------------------------------------------------------------------------------------
     // the tile of step j is 32*D*2 contiguous bytes; thread t moves the 16-byte pieces t + 256u
@@ -138,37 +146,43 @@ __global__ void __launch_bounds__(256) mips_stage1_kernel(MipsParams p) {
             *(u32x4*)(tile[b] + (c / (2 * KS)) * kRowBytes + (c % (2 * KS)) * 16) = pre[u];
         }
     };
+    floatx16 acc[MQ];
     auto scores_of = [&](int b) {
-        floatx16 acc;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
+        for (int m = 0; m < MQ; ++m)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[m][i] = 0.0f;
         const char* rowp = tile[b] + col * kRowBytes + half * 16;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             const bf16x8 a = __builtin_bit_cast(bf16x8, *(const u32x4*)(rowp + s * 32));
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[s], acc, 0, 0, 0);
+#pragma unroll
+            for (int m = 0; m < MQ; ++m)
+                acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[m][s], acc[m], 0, 0, 0);
         }
-        return acc;
     };
-    floatx16 acc;
     if (j0 < j1) {
         fetch();
         stage(0);
         __syncthreads();
         if (j0 + 1 < j1) fetch();
-        acc = scores_of(0);
+        scores_of(0);
     }
     int buf = 0;
     for (int j = j0; j + 1 < j1; ++j) {
-        float x[16];
+        float x[MQ][16];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) x[i] = acc[i];
+        for (int m = 0; m < MQ; ++m)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) x[m][i] = acc[m][i];
         stage(buf ^ 1);          // last read two steps ago, before every wave's previous barrier
         __syncthreads();
         if (j + 2 < j1) fetch();
-        acc = scores_of(buf ^ 1);
+        scores_of(buf ^ 1);
 #pragma unroll
-        for (int i = 0; i < 16; ++i) L.insert(i, x[i], j);
+        for (int m = 0; m < MQ; ++m)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) L[m].insert(i, x[m][i], j);
         // Issue order for the region after the barrier: LDS reads, then each matrix instruction
         // followed by its share of the list updates, so that the matrix core works under the
         // vector ALU (left to itself the scheduler puts all matrix instructions first and the
@@ -176,7 +190,7 @@ __global__ void __launch_bounds__(256) mips_stage1_kernel(MipsParams p) {
         if constexpr (KP >= 3) {
             __builtin_amdgcn_sched_group_barrier(0x100, KS, 0);           // LDS reads
 #pragma unroll
-            for (int s = 0; s < KS; ++s) {
+            for (int s = 0; s < KS * MQ; ++s) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        // one matrix instruction
                 __builtin_amdgcn_sched_group_barrier(0x002, (16 * (4 * KP)) / KS, 0);   // vector ALU
             }
@@ -185,7 +199,9 @@ __global__ void __launch_bounds__(256) mips_stage1_kernel(MipsParams p) {
     }
     if (j0 < j1) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) L.insert(i, acc[i], j1 - 1);
+        for (int m = 0; m < MQ; ++m)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) L[m].insert(i, acc[m][i], j1 - 1);
     }
 
     // ---- partial lists out, as keys --------------------------------------------------------------
@@ -194,30 +210,32 @@ __global__ void __launch_bounds__(256) mips_stage1_kernel(MipsParams p) {
     // through LDS so that every query's 32 buckets leave as one 256-byte run.
     __syncthreads();                                   // every wavefront is done with the tiles
     char* stage_w = lds_raw + wave * (32 * kStageRowBytes);
-    const int q_first = qt * kMipsQueryTile + wave * 32;
 #pragma unroll
-    for (int k = 0; k < KP; ++k) {
-        if (k < p.Kprime) {
+    for (int m = 0; m < MQ; ++m) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int bl = 8 * (i >> 2) + 4 * half + (i & 3);
-                const uint32_t n = (uint32_t)L.stp[i][k] * (uint32_t)p.B + (uint32_t)(b0 + bl);
-                *(uint64_t*)(stage_w + col * kStageRowBytes + bl * 8) =
-                    L.valid(i, k) ? make_key<score_t>(L.bits(i, k), n) : 0;
-            }
-            __syncthreads();
-            // 16 lanes x 16 bytes cover one query's row; a wavefront stores 4 rows at a time
+        for (int k = 0; k < KP; ++k) {
+            if (k < p.Kprime) {
 #pragma unroll
-            for (int r = 0; r < 8; ++r) {
-                const int ql = r * 4 + (lane >> 4), chunk = lane & 15;
-                const u32x4 v = *(const u32x4*)(stage_w + ql * kStageRowBytes + chunk * 16);
-                const int qq = q_first + ql;
-                if (qq < p.Q) {
-                    uint64_t* dst = p.part_keys + (((size_t)qq * p.nseg + seg) * p.Kprime + k) * p.B + b0;
-                    *(u32x4*)((char*)dst + chunk * 16) = v;
+                for (int i = 0; i < 16; ++i) {
+                    const int bl = 8 * (i >> 2) + 4 * half + (i & 3);
+                    const uint32_t n = (uint32_t)L[m].stp[i][k] * (uint32_t)p.B + (uint32_t)(b0 + bl);
+                    *(uint64_t*)(stage_w + col * kStageRowBytes + bl * 8) =
+                        L[m].valid(i, k) ? make_key<score_t>(L[m].bits(i, k), n) : 0;
                 }
+                __syncthreads();
+                // 16 lanes x 16 bytes cover one query's row; a wavefront stores 4 rows at a time
+#pragma unroll
+                for (int r = 0; r < 8; ++r) {
+                    const int ql = r * 4 + (lane >> 4), chunk = lane & 15;
+                    const u32x4 v = *(const u32x4*)(stage_w + ql * kStageRowBytes + chunk * 16);
+                    const int qq = q_first + m * 32 + ql;
+                    if (qq < p.Q) {
+                        uint64_t* dst = p.part_keys + (((size_t)qq * p.nseg + seg) * p.Kprime + k) * p.B + b0;
+                        *(u32x4*)((char*)dst + chunk * 16) = v;
+                    }
+                }
+                __syncthreads();
             }
-            __syncthreads();
         }
     }
 }
@@ -226,9 +244,9 @@ template <int KP>
 hipError_t launch_for(const MipsParams& p, hipStream_t stream) {
     const dim3 grid((unsigned)(p.nslab * p.nseg * p.nqt)), block(256);
     switch (p.D) {
-        case 64:  hipLaunchKernelGGL((mips_stage1_kernel<KP, 4>), grid, block, 0, stream, p); break;
-        case 128: hipLaunchKernelGGL((mips_stage1_kernel<KP, 8>), grid, block, 0, stream, p); break;
-        case 256: hipLaunchKernelGGL((mips_stage1_kernel<KP, 16>), grid, block, 0, stream, p); break;
+        case 64:  hipLaunchKernelGGL((mips_stage1_kernel<KP, 4, mips_subtiles(KP, 64)>), grid, block, 0, stream, p); break;
+        case 128: hipLaunchKernelGGL((mips_stage1_kernel<KP, 8, mips_subtiles(KP, 128)>), grid, block, 0, stream, p); break;
+        case 256: hipLaunchKernelGGL((mips_stage1_kernel<KP, 16, mips_subtiles(KP, 256)>), grid, block, 0, stream, p); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
