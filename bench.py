@@ -132,6 +132,10 @@ def bench_workload(name, steps, warmup, with_cpu_baseline, only_params=None):
             "expected_recall_random_placement": atk.expected_recall(w.N, B, w.K, Kp),
             "speedup_vs_exact": ex["kernel_ms_avg"] / t["kernel_ms_avg"],
             "traffic_bytes": MEASURED_TRAFFIC_BYTES.get((name, B, Kp)),
+            # the other roof: Section 6.3 counts 5K'-2 list operations per element; against the
+            # vector ALU's 39.3 T lane-ops/s this says which settings are ALU-bound by construction
+            "alu_ops_per_element_section_6_3": 5 * Kp - 2,
+            "alu_frac_of_peak_at_that_count": (5 * Kp - 2) * w.rows * w.N / sec / 1e12 / (256 * 4 * 16 * 2.4e-3),
             "plan": plan, "input_copies_rotated": copies,
         })
 
