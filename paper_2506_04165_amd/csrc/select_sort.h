@@ -214,9 +214,17 @@ __device__ __forceinline__ void hist_find_digit(const uint32_t* hist, uint32_t* 
     // suffix sums over bins: thread t owns bins [t*bpt, (t+1)*bpt)
     const int bpt = (kSelectBins + T - 1) / T;
     uint32_t mine = 0;
-    for (int i = 0; i < bpt; ++i) {
-        const int bin = tid * bpt + i;
-        if (bin < kSelectBins) mine += hist[bin];
+    if ((bpt & 3) == 0) {                     // 16-byte loads (kSelectBins and T are powers of two)
+        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+        for (int i = 0; i < bpt; i += 4) {
+            const u32x4 h = *(const u32x4*)(hist + tid * bpt + i);
+            mine += h.x + h.y + h.z + h.w;
+        }
+    } else {
+        for (int i = 0; i < bpt; ++i) {
+            const int bin = tid * bpt + i;
+            if (bin < kSelectBins) mine += hist[bin];
+        }
     }
     const int lane = tid & (kWave - 1), wave = tid >> 6;
     uint32_t suf = mine;                               // inclusive suffix sum inside the wave
@@ -247,6 +255,21 @@ __device__ __forceinline__ void hist_find_digit(const uint32_t* hist, uint32_t* 
     __syncthreads();
 }
 
+// Visit the n keys of an LDS array, every thread of the workgroup taking keys tid, tid+T, ...;
+// four loads are issued before the first key is used so that their latencies overlap.
+template <typename F>
+__device__ __forceinline__ void for_each_lds_key(const uint64_t* keys, int n, F&& f) {
+    const int tid = threadIdx.x, T = blockDim.x;
+    for (int base = tid; base < n; base += 4 * T) {
+        uint64_t k[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) k[u] = (base + u * T < n) ? keys[base + u * T] : 0;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (base + u * T < n) f(k[u]);
+    }
+}
+
 // Histogram pass of the radix selection over keys in LDS: the `bits`-wide digit at `shift` of
 // the keys matching (prefix, mask) is counted, then hist_find_digit answers.
 __device__ __forceinline__ void lds_select_digit(const uint64_t* keys, int n, uint64_t prefix,
@@ -257,10 +280,9 @@ __device__ __forceinline__ void lds_select_digit(const uint64_t* keys, int n, ui
     const uint32_t dmask = (1u << bits) - 1u;
     for (int i = tid; i < kSelectBins; i += T) hist[i] = 0;
     __syncthreads();
-    for (int i = tid; i < n; i += T) {
-        const uint64_t key = keys[i];
+    for_each_lds_key(keys, n, [&](uint64_t key) {
         if (key != 0 && (key & mask) == prefix) atomicAdd(&hist[(uint32_t)(key >> shift) & dmask], 1u);
-    }
+    });
     hist_find_digit(hist, ctl, need, digit, above, count);
 }
 
@@ -285,7 +307,8 @@ constexpr int kWgSortMinThreads = 256;
 
 // Top-K (descending) of the n keys in LDS `keys` (n a power of two, key 0 = empty, at least K
 // real keys), written decoded to out_*[out_base + 0..K).  Called by every thread of the
-// workgroup; `scratch` is kSelectScratchBytes of LDS (unused when n <= 256).
+// workgroup; `scratch` is kSelectScratchBytes of LDS (unused when n <= 256): a buffer of
+// kWaveSortMaxKeys keys, which the histogram aliases, then 32 control words.
 // The keys array is used as working storage.
 template <typename DT>
 __device__ __forceinline__ void wg_topk_from_lds(uint64_t* keys, int n, int K, void* scratch,
@@ -306,34 +329,61 @@ __device__ __forceinline__ void wg_topk_from_lds(uint64_t* keys, int n, int K, v
         uint64_t* buf = (uint64_t*)scratch;
         uint32_t* hist = (uint32_t*)scratch;                          // aliases buf
         uint32_t* ctl = (uint32_t*)((char*)scratch + kWaveSortMaxKeys * 8);
-        uint64_t prefix = 0, mask = 0;
+        // The keys are the survivors of a first selection and sit in a narrow band of values:
+        // digits taken from fixed bit positions would put most of them into one bin, pass after
+        // pass.  So the band is measured first (greatest and least value present); the bits all
+        // keys share become the prefix and the first digit starts at the highest bit that varies.
+        const int lane = tid & (kWave - 1);
+        if (tid == 0) { ctl[20] = 0u; ctl[21] = 0xffffffffu; }
+        __syncthreads();
+        uint32_t vhi = 0u, vlo = 0xffffffffu;
+        for_each_lds_key(keys, n, [&](uint64_t key) {
+            if (key != 0) {
+                const uint32_t v = (uint32_t)(key >> 32);
+                vhi = max(vhi, v);
+                vlo = min(vlo, v);
+            }
+        });
+        for (int o = kWave / 2; o >= 1; o >>= 1) {
+            vhi = max(vhi, (uint32_t)__shfl_xor((int)vhi, o, kWave));
+            vlo = min(vlo, (uint32_t)__shfl_xor((int)vlo, o, kWave));
+        }
+        if (lane == 0) { atomicMax(&ctl[20], vhi); atomicMin(&ctl[21], vlo); }
+        __syncthreads();
+        vhi = ctl[20]; vlo = ctl[21];
+        const uint32_t differ = vhi ^ vlo;
+        const int varying = differ ? 32 - __clz((int)differ) : 0;       // low value bits that vary
+        uint64_t prefix = varying >= 32 ? 0ull : (uint64_t)((vhi >> varying) << varying) << 32;
+        uint64_t mask = varying >= 32 ? 0ull : ~0ull << (32 + varying);
         int need = K, certain = 0;
         bool fits = false;
-        // value bits first (11, 11, 10), then -- only when ties leave too many candidates --
-        // the index bits, so that the lowest indices win
-        const int shifts[6] = {53, 42, 32, 21, 10, 0}, widths[6] = {11, 11, 10, 11, 11, 10};
-        for (int d = 0; d < 6 && !fits; ++d) {
+        // value bits first, eleven at a time down to the index half, then -- only when ties leave
+        // too many candidates -- the index bits, so that the lowest indices win
+        int top = 32 + varying;                                          // bits below `top` are open
+        for (int pass = 0; top > 0 && !fits; ++pass) {
+            const int width = top > 32 ? min(11, top - 32) : min(11, top);
+            const int shift = top - width;
             uint32_t digit, above, count;
-            lds_select_digit(keys, n, prefix, mask, shifts[d], widths[d], need, hist, ctl, digit, above, count);
+            lds_select_digit(keys, n, prefix, mask, shift, width, need, hist, ctl, digit, above, count);
             certain += (int)above;
             need -= (int)above;
-            prefix |= (uint64_t)digit << shifts[d];
-            mask |= (uint64_t)((1u << widths[d]) - 1u) << shifts[d];
-            // stop when members + candidates fit one wave sort; prefer a sort of at most 2K keys
+            prefix |= (uint64_t)digit << shift;
+            mask |= (uint64_t)((1u << width) - 1u) << shift;
+            top = shift;
+            // stop when members + candidates fit one sort; prefer a sort of at most 2K keys
             fits = certain + (int)count <= kWaveSortMaxKeys &&
-                   (certain + (int)count <= 2 * K + 64 || d >= 2);
+                   (certain + (int)count <= 2 * K + 64 || pass >= 2);
         }
         if (fits) {
             if (tid == 0) ctl[3] = 0;
             __syncthreads();
             // certain members and candidates -> buf (the histogram is dead by now)
-            for (int i = tid; i < n; i += T) {
-                const uint64_t key = keys[i];
+            for_each_lds_key(keys, n, [&](uint64_t key) {
                 if (key != 0 && (key & mask) >= prefix) {
                     const uint32_t slot = atomicAdd(&ctl[3], 1u);
                     if (slot < (uint32_t)kWaveSortMaxKeys) buf[slot] = key;
                 }
-            }
+            });
             __syncthreads();
             const int total = min((int)ctl[3], kWaveSortMaxKeys);
             if (total > kWgSortMinKeys && T >= kWgSortMinThreads) {
