@@ -305,6 +305,55 @@ __device__ __forceinline__ void wg_write_topk(const uint64_t* keys, int K, const
 constexpr int kWgSortMinKeys = 512;
 constexpr int kWgSortMinThreads = 256;
 
+// Sort n keys in LDS (n a power of two >= 1024) far enough that keys[0..K) hold the K greatest in
+// order.  Every wavefront sorts runs of 512 keys in registers; the runs are then merged pairwise
+// by the bitonic network in its same-direction form (run a against the mirror image of run b,
+// then half-cleaners), and once a merged run would exceed `cap` keys (the power of two >= K,
+// at least 512) only its first `cap` positions are kept and cleaned.  Compared with running the
+// whole network in LDS this needs 10 barrier-separated stages per merge level instead of 55.
+// Every thread of the workgroup.
+__device__ __forceinline__ void wg_sort_merge_topk(uint64_t* keys, int n, int K) {
+    const int tid = threadIdx.x, T = blockDim.x;
+    const int lane = tid & (kWave - 1), wave = tid >> 6, nwaves = T >> 6;
+    constexpr int kRun = 512;
+    for (int c = wave; c < n / kRun; c += nwaves) {
+        uint64_t k[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) k[j] = keys[c * kRun + lane * 8 + j];
+        WaveSort<8, uint64_t>::sort(k);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) keys[c * kRun + lane * 8 + j] = k[j];
+    }
+    __syncthreads();
+    int cap = kRun;
+    while (cap < K) cap <<= 1;
+    for (int L = kRun; L < n; L <<= 1) {                 // blocks of 2L: runs at +0 and +L
+        const int m = L < cap ? L : cap;                 // sorted keys at the start of each run
+        const int nblocks = n / (2 * L);
+        // mirror step: key i of the first run against key m-1-i of the second; the greater
+        // stays in the first run, the smaller goes to the second (unused once runs are cut)
+        for (int q = tid; q < nblocks * m; q += T) {
+            const int blk = q / m, i = q - blk * m;
+            const int a = blk * 2 * L + i, b = blk * 2 * L + L + (m - 1 - i);
+            const uint64_t x = keys[a], y = keys[b];
+            if (x < y) { keys[a] = y; keys[b] = x; }
+        }
+        __syncthreads();
+        // half-cleaners inside what is kept: both runs while 2m <= cap, else the first run only
+        const int kept = 2 * m <= cap ? 2 * m : m;       // keys kept per block, from its start
+        for (int j = m >> 1; j >= 1; j >>= 1) {
+            for (int q = tid; q < nblocks * (kept >> 1); q += T) {
+                const int blk = q / (kept >> 1), i = q - blk * (kept >> 1);
+                const int lo = blk * 2 * L + (((i & ~(j - 1)) << 1) | (i & (j - 1)));
+                const int hi = lo | j;
+                const uint64_t x = keys[lo], y = keys[hi];
+                if (x < y) { keys[lo] = y; keys[hi] = x; }
+            }
+            __syncthreads();
+        }
+    }
+}
+
 // Top-K (descending) of the n keys in LDS `keys` (n a power of two, key 0 = empty, at least K
 // real keys), written decoded to out_*[out_base + 0..K).  Called by every thread of the
 // workgroup; `scratch` is kSelectScratchBytes of LDS (unused when n <= 256): a buffer of
@@ -318,7 +367,7 @@ __device__ __forceinline__ void wg_topk_from_lds(uint64_t* keys, int n, int K, v
     // few keys, or most of them wanted: sort them all
     if (n <= 256 || (n <= kWaveSortMaxKeys && 4 * K > n)) {
         if (n > kWgSortMinKeys && T >= kWgSortMinThreads) {
-            lds_bitonic_sort_desc(keys, n, n);
+            wg_sort_merge_topk(keys, n, K);
             wg_write_topk<DT>(keys, K, rowp, out_vals, out_idx, out_base);
             return;
         }
@@ -391,7 +440,7 @@ __device__ __forceinline__ void wg_topk_from_lds(uint64_t* keys, int n, int K, v
                 const int padded = next_pow2(total);
                 for (int i = total + tid; i < padded; i += T) buf[i] = 0;
                 __syncthreads();
-                lds_bitonic_sort_desc(buf, padded, padded);
+                wg_sort_merge_topk(buf, padded, K);
                 wg_write_topk<DT>(buf, K, rowp, out_vals, out_idx, out_base);
                 return;
             }
