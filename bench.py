@@ -39,16 +39,16 @@ PAPER_CONTEXT = {
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by a plain
 # copy of known size (profiles/approx_topk_<workload>_B<B>_Kp<K'>.md), keyed by (workload, B, K').
 MEASURED_TRAFFIC_BYTES = {
-    ("c4_mips", 1024, 4): 1074671077,
-    ("c4_mips", 4096, 1): 1074609591,
-    ("c2_ffn", 128, 4): 498396657,
-    ("c2_ffn", 1024, 1): 498533234,
-    ("c2_ffn", 64, 8): 498340134,
-    ("c3_vocab", 512, 4): 525722503,
-    ("c3_vocab", 512, 2): 525462350,
-    ("c5_adversarial", 256, 8): 272766639,
-    ("c5_adversarial", 256, 1): 272414825,
-    ("c5_adversarial", 256, 32): 271576547,
+    ("c4_mips", 1024, 4): 1074750024,
+    ("c4_mips", 4096, 1): 1074697801,
+    ("c2_ffn", 128, 4): 498399271,
+    ("c2_ffn", 1024, 1): 498535043,
+    ("c2_ffn", 64, 8): 498340244,
+    ("c3_vocab", 512, 4): 525578888,
+    ("c3_vocab", 512, 2): 525411644,
+    ("c5_adversarial", 256, 8): 272427269,
+    ("c5_adversarial", 256, 1): 272402495,
+    ("c5_adversarial", 256, 32): 271618327,
 }
 
 
