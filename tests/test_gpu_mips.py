@@ -40,6 +40,9 @@ def run_both(atk, Q, N, D, K, Kp, B, seed, kind):
     (8, 131072, 128, 300, 4, 128),      # few pairs: the walk is cut into segments
     (16, 4096, 128, 128, 4, 32),        # K = B*K': stage 2 is a pure sort
     (1, 2048, 64, 32, 1, 32),           # single query
+    (5, 128, 64, 100, 4, 32),           # every bucket holds exactly K' vectors: all survive
+    (3, 64, 64, 64, 1, 64),             # one vector per bucket, K = N: a sort of all scores
+    (7, 4096, 128, 4, 4, 32),           # K' = K
 ])
 def test_integer_vectors_bit_exact(atk, Q, N, D, K, Kp, B):
     q, d, gv, gi = run_both(atk, Q, N, D, K, Kp, B, seed=11, kind="integer")
