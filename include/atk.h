@@ -170,6 +170,17 @@ int atk_mips_approx_topk(const void* queries, const void* database, int dtype, i
                          int64_t D, int K, int Kprime, int B, float* out_vals, int32_t* out_idx,
                          void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Fusion-aware parameter choice for atk_mips_approx_topk (named as open work in the paper's
+ * conclusion): in the fused kernel every score pays about 5K'-2 vector operations (Section 6.3)
+ * whatever B is, so the choice is the smallest K' <= 4 for which some legal B (a multiple of 32
+ * dividing N, K <= B*K' <= 16384, K' <= N/B) reaches recall_target by Theorem 1, and for that K'
+ * the smallest such B.  ATK_UNSUPPORTED when no legal configuration reaches the target.
+ * Host only.  expected_recall_out may be NULL.
+ */
+int atk_mips_select_params(int64_t N, int K, double recall_target, int* Kprime_out, int* B_out,
+                           double* expected_recall_out);
+
 /* Workspace bytes atk_mips_approx_topk needs; SIZE_MAX on illegal or unsupported arguments.
  * Host only. */
 size_t atk_mips_workspace_bytes(int dtype, int64_t Q, int64_t N, int64_t D, int K, int Kprime, int B);

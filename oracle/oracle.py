@@ -220,6 +220,22 @@ def select_parameters(N: int, K: int, recall_target: float, allowed_kprime=(1, 2
     return None if best is None else (best[1], best[2])
 
 
+def mips_select_parameters(N: int, K: int, recall_target: float):
+    """Fusion-aware rule for the matmul-fused kernel (the paper's conclusion names fusion-aware
+    selection as open work): every score costs about 5K'-2 list operations whatever B is
+    (Section 6.3), so take the smallest K' <= 4 for which a legal B reaches the target by
+    Theorem 1, then the smallest such B.  Legal: B divides N, B a multiple of 32,
+    K <= B*K' <= 16384, K' <= N/B.  Plain enumeration, exact arithmetic.  Returns (K', B) or None.
+    """
+    for kp in range(1, min(4, K) + 1):
+        for B in range(32, 16384 // kp + 1, 32):
+            if N % B or B * kp < K or kp > N // B:
+                continue
+            if expected_recall(N, B, K, kp) >= recall_target:
+                return kp, B
+    return None
+
+
 def expected_recall_mc(N: int, B: int, K: int, Kprime: int, num_trials: int,
                        rng: np.random.Generator):
     """Monte-Carlo estimate of the same expectation (Section 6.2; appendix on parameter selection).

@@ -27,7 +27,7 @@ SIZE_MAX = ctypes.c_size_t(-1).value
 EXPORTS = [
     "atk_approx_topk", "atk_topk", "atk_approx_topk_stage1", "atk_workspace_bytes",
     "atk_expected_recall", "atk_select_params", "atk_approx_topk_recall", "atk_describe_plan", "atk_valu_probe",
-    "atk_mips_approx_topk", "atk_mips_workspace_bytes", "atk_mips_describe_plan", "atk_status_string", "atk_last_hip_error",
+    "atk_mips_approx_topk", "atk_mips_workspace_bytes", "atk_mips_describe_plan", "atk_mips_select_params", "atk_status_string", "atk_last_hip_error",
     "atk_version",
 ]
 
@@ -72,6 +72,8 @@ def _load() -> ctypes.CDLL:
     lib.atk_mips_workspace_bytes.restype = sz
     lib.atk_mips_describe_plan.argtypes = [ci, i64, i64, i64, ci, ci, ci, ctypes.c_char_p, sz]
     lib.atk_mips_describe_plan.restype = ci
+    lib.atk_mips_select_params.argtypes = [i64, ci, ctypes.c_double, ip, ip, dp]
+    lib.atk_mips_select_params.restype = ci
     lib.atk_status_string.argtypes = [ci]
     lib.atk_status_string.restype = ctypes.c_char_p
     lib.atk_last_hip_error.restype = ctypes.c_char_p
@@ -220,6 +222,16 @@ def mips_describe_plan(Q: int, N: int, D: int, K: int, Kprime: int, B: int):
     buf = ctypes.create_string_buffer(512)
     st = lib.atk_mips_describe_plan(BF16, Q, N, D, K, Kprime, B, buf, 512)
     return st, buf.value.decode()
+
+
+def mips_select_params(N: int, K: int, recall_target: float):
+    """Fusion-aware (K', B) for the fused entry: smallest K', then smallest B.  Returns
+    (K', B, expected recall); raises AtkError when no legal setting reaches the target."""
+    kp, b, r = ctypes.c_int(0), ctypes.c_int(0), ctypes.c_double(0.0)
+    st = lib.atk_mips_select_params(N, K, recall_target, ctypes.byref(kp), ctypes.byref(b), ctypes.byref(r))
+    if st != OK:
+        raise AtkError(st, "atk_mips_select_params")
+    return kp.value, b.value, r.value
 
 
 def mips_approx_topk(queries: torch.Tensor, database: torch.Tensor, K: int, Kprime: int, B: int,

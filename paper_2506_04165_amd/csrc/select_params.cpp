@@ -62,3 +62,38 @@ extern "C" int atk_select_params(int64_t N, int K, double recall_target, int max
     if (expected_recall_out) *expected_recall_out = best_recall;
     return ATK_OK;
 }
+
+// Fusion-aware choice for atk_mips_approx_topk (the paper's conclusion leaves "fusion-aware
+// parameter selection" open).  In the fused kernel the list update is what costs: every score
+// pays about 5K'-2 vector operations whatever B is, and the survivors are small next to the
+// matrix product.  So the rule is the reverse of the unfused one: the smallest K' for which some
+// legal B reaches the target, and for that K' the smallest such B.  Legal here: B divides N, B a
+// multiple of 32 (a slab of the kernel), K' <= min(4, N/B), K <= B*K' <= 16384.
+// Returns ATK_UNSUPPORTED when no legal configuration reaches the target.
+extern "C" int atk_mips_select_params(int64_t N, int K, double recall_target, int* Kprime_out,
+                                      int* B_out, double* expected_recall_out) {
+    if (N <= 0 || N > 0x7fffffffLL || K < 1 || K > N || !Kprime_out || !B_out) return ATK_INVALID_ARG;
+    if (!(recall_target > 0.0) || recall_target > 1.0) return ATK_INVALID_ARG;
+    std::vector<int64_t> buckets;
+    for (int64_t d = 1; d * d <= N; ++d) {
+        if (N % d) continue;
+        if (d % 32 == 0) buckets.push_back(d);
+        const int64_t e = N / d;
+        if (e != d && e % 32 == 0) buckets.push_back(e);
+    }
+    std::sort(buckets.begin(), buckets.end());
+    for (int kp = 1; kp <= 4 && kp <= K; ++kp) {
+        for (int64_t B : buckets) {
+            if (B * kp > 16384) break;
+            if (B * kp < K) continue;
+            if (kp > N / B) break;
+            const double r = atk_expected_recall(N, B, K, kp);
+            if (r >= recall_target) {
+                *Kprime_out = kp; *B_out = (int)B;
+                if (expected_recall_out) *expected_recall_out = r;
+                return ATK_OK;
+            }
+        }
+    }
+    return ATK_UNSUPPORTED;
+}

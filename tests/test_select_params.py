@@ -1,6 +1,8 @@
 """Recall-target parameter selection (Section 6.3 last paragraph; appendix "Algorithm Parameter
 Selection"): the library's closed-form sweep against the oracle's exhaustive enumeration in
 exact arithmetic, and against the configurations the paper names."""
+import ctypes
+
 import pytest
 import torch
 
@@ -78,3 +80,31 @@ def test_recall_target_entry_point_runs_the_selected_configuration():
         # the realised recall on random data is close to the target's expectation
         _, ei = oracle.topk(xh, K)
         assert oracle.index_recall(oi, ei).mean() >= target - 0.03
+
+
+@pytest.mark.parametrize("N,K,target", [(1 << 20, 1024, 0.99), (1 << 20, 1024, 0.95), (1 << 20, 128, 0.99),
+                                        (65536, 64, 0.9), (262144, 1024, 0.99), (98304, 300, 0.97),
+                                        (4096, 32, 0.999)])
+def test_fusion_aware_choice_matches_plain_enumeration(N, K, target):
+    ref = oracle.mips_select_parameters(N, K, target)
+    if ref is None:
+        with pytest.raises(atk.AtkError):
+            atk.mips_select_params(N, K, target)
+        return
+    kp, b, r = atk.mips_select_params(N, K, target)
+    assert (kp, b) == ref
+    assert r == pytest.approx(oracle.expected_recall(N, b, K, kp), abs=1e-9) and r >= target
+    # what the rule promises: no smaller K' has any legal B that reaches the target
+    for smaller in range(1, kp):
+        legal = [B for B in range(32, 16384 // smaller + 1, 32)
+                 if N % B == 0 and B * smaller >= K and smaller <= N // B]
+        assert all(atk.expected_recall(N, B, K, smaller) < target for B in legal)
+
+
+def test_fusion_aware_choice_rejects_bad_arguments():
+    kp, b, r = ctypes.c_int(), ctypes.c_int(), ctypes.c_double()
+    f = atk.lib.atk_mips_select_params
+    assert f(0, 1, 0.9, ctypes.byref(kp), ctypes.byref(b), None) == atk.INVALID_ARG
+    assert f(4096, 32, 1.5, ctypes.byref(kp), ctypes.byref(b), None) == atk.INVALID_ARG
+    assert f(4096, 32, 0.9, None, ctypes.byref(b), None) == atk.INVALID_ARG
+    assert f(1 << 20, 1024, 0.999999, ctypes.byref(kp), ctypes.byref(b), ctypes.byref(r)) == atk.UNSUPPORTED
