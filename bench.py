@@ -110,6 +110,9 @@ def bench_workload(name, steps, warmup, with_cpu_baseline, only_params=None):
     exact = {"kernel_ms_avg": ex["kernel_ms_avg"], "rows_per_s": w.rows / (ex["kernel_ms_avg"] * 1e-3),
              "achieved_gbps": alg / (ex["kernel_ms_avg"] * 1e-3) / 1e9,
              "frac_of_peak": alg / (ex["kernel_ms_avg"] * 1e-3) / 1e9 / HBM_PEAK_GBPS, "steps": exact_steps}
+    # context for the comparison system itself: the library exact Top-K on the same input
+    lib = time_steps(lambda i: torch.topk(xs[i], w.K, dim=1), copies, 5, 2)
+    exact["torch_topk_ms_avg"] = lib["kernel_ms_avg"]
 
     results = []
     for B, Kp in w.params:
