@@ -368,7 +368,7 @@ MipsPlan make_mips_plan(int dtype, int64_t Q, int64_t N, int64_t D, int K, int K
         pl.status = ATK_UNSUPPORTED;
         return pl;
     }
-    pl.KP = Kprime <= 2 ? Kprime : 4;
+    pl.KP = Kprime;
     pl.nslab = B / kMipsSlab;
     const int qtile = kMipsQueryTile * mips_subtiles(pl.KP, (int)D);
     pl.nqt = (int)((Q + qtile - 1) / qtile);

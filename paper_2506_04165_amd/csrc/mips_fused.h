@@ -26,7 +26,7 @@ constexpr int kMipsQueryTile = 128;  // queries per workgroup and sub-tile (4 wa
 // (p.nqt must be ceil(Q / (kMipsQueryTile * this))): two while the registers allow it
 constexpr int mips_subtiles(int KP, int D) { return (KP == 1 && D <= 128) ? 2 : 1; }
 
-// KP: compiled list length (1, 2 or 4, >= Kprime); D one of 64, 128, 256.
+// KP: compiled list length (1 to 4, = Kprime); D one of 64, 128, 256.
 hipError_t launch_mips_stage1(const MipsParams& p, int KP, hipStream_t stream);
 
 }  // namespace atk

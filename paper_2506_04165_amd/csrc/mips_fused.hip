@@ -5,13 +5,13 @@
 
 namespace atk {
 
-hipError_t launch_mips_stage1_long(const MipsParams& p, hipStream_t stream);   // mips_fused_long.hip
+hipError_t launch_mips_stage1_long(const MipsParams& p, int KP, hipStream_t stream);   // mips_fused_long.hip
 
 hipError_t launch_mips_stage1(const MipsParams& p, int KP, hipStream_t stream) {
     switch (KP) {
         case 1: return launch_for<1>(p, stream);
         case 2: return launch_for<2>(p, stream);
-        case 4: return launch_mips_stage1_long(p, stream);
+        case 3: case 4: return launch_mips_stage1_long(p, KP, stream);
         default: return hipErrorInvalidValue;
     }
 }
