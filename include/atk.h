@@ -150,10 +150,10 @@ int atk_describe_plan(int dtype, int64_t rows, int64_t N, int K, int Kprime, int
  * formed on the matrix cores with binary32 accumulation and consumed by the K'-list update of
  * Section 6.1 Steps 1-2 (bucket of score n = n mod B) without ever being stored; Steps 3-4 follow
  * in a second launch.  Same order and tie rule as atk_approx_topk on the score row.
- *   queries    device, [Q, D] bf16, vectors contiguous, 16-byte aligned
- *   database   device, [N, D] bf16, vectors contiguous, 16-byte aligned (vector-major, not the
+ *   queries    device, [Q, D] bf16 or fp16, vectors contiguous, 16-byte aligned
+ *   database   device, [N, D] same type, vectors contiguous, 16-byte aligned (vector-major, not the
  *              [D, N] operand of the paper's listing)
- *   dtype      ATK_BF16 (others: ATK_UNSUPPORTED);  D one of 64, 128, 256;  B a multiple of 32
+ *   dtype      ATK_BF16 or ATK_F16 (others: ATK_UNSUPPORTED);  D one of 64, 128, 256;  B a multiple of 32
  *              dividing N;  1 <= K' <= min(K, N/B, 4);  K <= B*K' <= 16384
  *   out_vals   device, [Q, K] binary32 scores, greatest first; a zero score is +0.0
  *   out_idx    device, [Q, K] int32 database positions

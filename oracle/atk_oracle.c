@@ -254,32 +254,26 @@ int atk_oracle_topk(const void *values, int dtype, int64_t rows, int64_t N,
  * implementation"): the rows whose Top-K is wanted are never given, they are
  * the products of Q query vectors with N database vectors,
  *     score[r][n] = sum over d of queries[r][d] * database[n][d].
- * Inputs are bf16 bit patterns, vectors contiguous ([Q, D] and [N, D]).  A
- * product of two bf16 numbers is exact in binary64 and a binary64 sum of D of
+ * Inputs are bf16 or fp16 bit patterns, vectors contiguous ([Q, D] and [N, D]).
+ * A product of two such numbers is exact in binary64 and a binary64 sum of D of
  * them carries a relative error near 1e-16, so the score kept here, that sum
  * rounded once to binary32, is the correctly rounded inner product.  (A
  * binary32 accumulator, which is what the paper's kernel and matrix hardware
  * use, differs from it by rounding that depends on the summation order.)
  */
-static double bf16_as_double(uint16_t h)
-{
-    uint32_t bits = (uint32_t)h << 16;
-    float f;
-    memcpy(&f, &bits, sizeof f);
-    return (double)f;
-}
-
-/* scores: [Q, N] binary32. */
-int atk_oracle_mips_scores(const uint16_t *queries, const uint16_t *database,
+/* scores: [Q, N] binary32.  dtype: ORACLE_BF16 or ORACLE_F16 (products of two binary16
+ * numbers are exact in binary64 as well). */
+int atk_oracle_mips_scores(const uint16_t *queries, const uint16_t *database, int dtype,
                            int64_t Q, int64_t N, int64_t D, float *scores)
 {
     if (!queries || !database || !scores || Q < 0 || N <= 0 || D <= 0) return -1;
+    if (dtype != ORACLE_BF16 && dtype != ORACLE_F16) return -1;
 #pragma omp parallel for schedule(static)
     for (int64_t r = 0; r < Q; ++r) {
         for (int64_t n = 0; n < N; ++n) {
             double acc = 0.0;
             for (int64_t d = 0; d < D; ++d)
-                acc += bf16_as_double(queries[r * D + d]) * bf16_as_double(database[n * D + d]);
+                acc += widen(queries, dtype, r * D + d) * widen(database, dtype, n * D + d);
             scores[r * N + n] = (float)acc;
         }
     }
@@ -290,7 +284,7 @@ int atk_oracle_mips_scores(const uint16_t *queries, const uint16_t *database,
  * Steps 1-4 of Section 6.1 applied to every row of the score matrix.
  * out_vals: [Q, K] binary32 scores; out_idx: [Q, K] database positions.
  */
-int atk_oracle_mips_approx_topk(const uint16_t *queries, const uint16_t *database,
+int atk_oracle_mips_approx_topk(const uint16_t *queries, const uint16_t *database, int dtype,
                                 int64_t Q, int64_t N, int64_t D,
                                 int64_t K, int64_t Kp, int64_t B,
                                 float *out_vals, int32_t *out_idx)
@@ -301,7 +295,7 @@ int atk_oracle_mips_approx_topk(const uint16_t *queries, const uint16_t *databas
     for (int64_t r = 0; r < Q; ++r) {
         float *row = (float *)malloc(sizeof(float) * (size_t)N);
         if (!row) { set_status(&status, -3); continue; }
-        int rc = atk_oracle_mips_scores(queries + r * D, database, 1, N, D, row);
+        int rc = atk_oracle_mips_scores(queries + r * D, database, dtype, 1, N, D, row);
         if (!rc)
             rc = atk_oracle_approx_topk(row, ORACLE_F32, 1, N, N, K, Kp, B,
                                         out_vals + r * K, out_idx + r * K);

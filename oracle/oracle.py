@@ -58,9 +58,9 @@ def _load():
         lib.atk_oracle_topk.argtypes = [vp, ci, i64, i64, i64, i64, vp, vp]
         lib.atk_oracle_topk.restype = ci
         lib.atk_oracle_num_threads.restype = ci
-        lib.atk_oracle_mips_scores.argtypes = [vp, vp, i64, i64, i64, vp]
+        lib.atk_oracle_mips_scores.argtypes = [vp, vp, ci, i64, i64, i64, vp]
         lib.atk_oracle_mips_scores.restype = ci
-        lib.atk_oracle_mips_approx_topk.argtypes = [vp, vp, i64, i64, i64, i64, i64, i64, vp, vp]
+        lib.atk_oracle_mips_approx_topk.argtypes = [vp, vp, ci, i64, i64, i64, i64, i64, i64, vp, vp]
         lib.atk_oracle_mips_approx_topk.restype = ci
         _lib = lib
     return _lib
@@ -129,18 +129,19 @@ def stage1(values: np.ndarray, Kprime: int, B: int):
 def _prep_vectors(queries: np.ndarray, database: np.ndarray):
     if queries.ndim != 2 or database.ndim != 2 or queries.shape[1] != database.shape[1]:
         raise ValueError("queries must be [Q, D] and database [N, D]")
-    if queries.dtype != np.uint16 or database.dtype != np.uint16:
-        raise TypeError("vectors are bf16 bit patterns held in uint16 arrays")
-    return np.ascontiguousarray(queries), np.ascontiguousarray(database)
+    if queries.dtype != database.dtype or queries.dtype not in (np.dtype(np.uint16), np.dtype(np.float16)):
+        raise TypeError("vectors are float16 arrays, or bf16 bit patterns held in uint16 arrays")
+    code = BF16 if queries.dtype == np.dtype(np.uint16) else F16
+    return np.ascontiguousarray(queries), np.ascontiguousarray(database), code
 
 
 def mips_scores(queries: np.ndarray, database: np.ndarray) -> np.ndarray:
     """Section 7.3: the [Q, N] inner products of bf16 vectors, each correctly rounded to float32."""
-    queries, database = _prep_vectors(queries, database)
+    queries, database, code = _prep_vectors(queries, database)
     Q, D = queries.shape
     N = database.shape[0]
     scores = np.empty((Q, N), dtype=np.float32)
-    rc = _load().atk_oracle_mips_scores(queries.ctypes.data, database.ctypes.data, Q, N, D,
+    rc = _load().atk_oracle_mips_scores(queries.ctypes.data, database.ctypes.data, code, Q, N, D,
                                         scores.ctypes.data)
     _raise(rc, "oracle mips_scores")
     return scores
@@ -149,12 +150,12 @@ def mips_scores(queries: np.ndarray, database: np.ndarray) -> np.ndarray:
 def mips_approx_topk(queries: np.ndarray, database: np.ndarray, K: int, Kprime: int, B: int):
     """Section 7.3: Steps 1-4 of Section 6.1 on every row of the score matrix, which is never
     stored as a whole.  Returns (scores[Q,K] float32, idx[Q,K] int32)."""
-    queries, database = _prep_vectors(queries, database)
+    queries, database, code = _prep_vectors(queries, database)
     Q, D = queries.shape
     N = database.shape[0]
     out_vals = np.empty((Q, K), dtype=np.float32)
     out_idx = np.empty((Q, K), dtype=np.int32)
-    rc = _load().atk_oracle_mips_approx_topk(queries.ctypes.data, database.ctypes.data, Q, N, D,
+    rc = _load().atk_oracle_mips_approx_topk(queries.ctypes.data, database.ctypes.data, code, Q, N, D,
                                              K, Kprime, B, out_vals.ctypes.data,
                                              out_idx.ctypes.data)
     _raise(rc, "oracle mips_approx_topk")

@@ -241,10 +241,11 @@ def mips_approx_topk(queries: torch.Tensor, database: torch.Tensor, K: int, Kpri
     for t in (queries, database):
         if not t.is_cuda:
             raise ValueError("vectors must live on the GPU")
-        if t.dim() != 2 or t.dtype != torch.bfloat16 or not t.is_contiguous():
-            raise ValueError("vectors must be contiguous bf16 [count, D] tensors")
-    if queries.shape[1] != database.shape[1]:
-        raise ValueError("queries and database differ in D")
+        if t.dim() != 2 or t.dtype not in (torch.bfloat16, torch.float16) or not t.is_contiguous():
+            raise ValueError("vectors must be contiguous bf16 or fp16 [count, D] tensors")
+    if queries.shape[1] != database.shape[1] or queries.dtype != database.dtype:
+        raise ValueError("queries and database differ in D or in type")
+    code = _CODES[queries.dtype]
     Q, D = queries.shape
     N = database.shape[0]
     if out is None:
@@ -252,13 +253,13 @@ def mips_approx_topk(queries: torch.Tensor, database: torch.Tensor, K: int, Kpri
         out_idx = torch.empty((Q, K), dtype=torch.int32, device=queries.device)
     else:
         out_vals, out_idx = out
-    need = lib.atk_mips_workspace_bytes(BF16, Q, N, D, K, Kprime, B)
+    need = lib.atk_mips_workspace_bytes(code, Q, N, D, K, Kprime, B)
     ws_ptr, ws_bytes = None, 0
     if need != SIZE_MAX and need > 0:
         if workspace is None or workspace.numel() * workspace.element_size() < need:
             workspace = torch.empty(need, dtype=torch.uint8, device=queries.device)
         ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
-    st = lib.atk_mips_approx_topk(queries.data_ptr(), database.data_ptr(), BF16, Q, N, D, K, Kprime,
+    st = lib.atk_mips_approx_topk(queries.data_ptr(), database.data_ptr(), code, Q, N, D, K, Kprime,
                                   B, out_vals.data_ptr(), out_idx.data_ptr(), ws_ptr, ws_bytes,
                                   _stream_ptr(queries.device))
     if st != OK:

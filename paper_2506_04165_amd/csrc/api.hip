@@ -363,7 +363,7 @@ MipsPlan make_mips_plan(int dtype, int64_t Q, int64_t N, int64_t D, int K, int K
     MipsPlan pl;
     if (Q < 0 || N <= 0 || N > 0x7fffffffLL || D <= 0) { pl.status = ATK_INVALID_ARG; return pl; }
     if ((pl.status = validate_method(N, K, Kprime, B))) return pl;
-    if (dtype != ATK_BF16 || (D != 64 && D != 128 && D != 256) || B % kMipsSlab || Kprime > 4 ||
+    if ((dtype != ATK_BF16 && dtype != ATK_F16) || (D != 64 && D != 128 && D != 256) || B % kMipsSlab || Kprime > 4 ||
         (int64_t)B * Kprime > 16384 || Q > 0x7fffffffLL / 2) {
         pl.status = ATK_UNSUPPORTED;
         return pl;
@@ -535,6 +535,7 @@ int atk_mips_approx_topk(const void* queries, const void* database, int dtype, i
 
     MipsParams p{};
     p.queries = (const uint16_t*)queries; p.database = (const uint16_t*)database;
+    p.f16 = dtype == ATK_F16;
     p.Q = (int)Q; p.N = (int)N; p.D = (int)D; p.Kprime = Kprime; p.B = B;
     p.nsteps = (int)(N / B); p.nseg = pl.nseg; p.seg_steps = pl.seg_steps;
     p.nslab = pl.nslab; p.nqt = pl.nqt;

@@ -8,8 +8,9 @@
 namespace atk {
 
 struct MipsParams {
-    const uint16_t* queries;    // [Q, D] bf16, vectors contiguous
-    const uint16_t* database;   // [N, D] bf16, vectors contiguous
+    const uint16_t* queries;    // [Q, D] bf16 or fp16, vectors contiguous
+    const uint16_t* database;   // [N, D] same type, vectors contiguous
+    int f16;                    // 1: the vectors are IEEE binary16, 0: bfloat16
     int Q, N, D, Kprime, B;
     int nsteps;                 // N / B: elements per bucket
     int nseg;                   // parts the element range of every bucket is cut into

@@ -31,6 +31,7 @@ namespace atk {
 namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 f16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte move
 
@@ -75,7 +76,8 @@ struct ScoreLists {
 // KS = D / 16: matrix instructions per score tile; MQ: 32-query sub-tiles per wavefront.  With
 // MQ = 2 every database fragment read from LDS feeds two matrix instructions (half the LDS
 // traffic per score) at the price of twice the lists: only short lists leave room for that.
-template <int KP, int KS, int MQ>
+// F16: the vectors are IEEE binary16 instead of bfloat16 (same layout, the other matrix instruction).
+template <int KP, int KS, int MQ, bool F16>
 __global__ void __launch_bounds__(256) mips_stage1_kernel(MipsParams p) {
     constexpr int D = KS * 16;
     constexpr int kRowBytes = D * 2 + 16;             // padded: rows 16 apart share no LDS bank
@@ -111,7 +113,7 @@ __global__ void __launch_bounds__(256) mips_stage1_kernel(MipsParams p) {
 
     // ---- query fragments: lane (col, half) holds query col, dims (2s + half)*8 .. +8 of step s ---
     const int q_first = (qt * 4 + wave) * (32 * MQ);          // first query of this wavefront
-    bf16x8 qf[MQ][KS];
+    u32x4 qf[MQ][KS];
 #pragma unroll
     for (int m = 0; m < MQ; ++m) {
         const int q = q_first + m * 32 + col;
@@ -119,7 +121,7 @@ __global__ void __launch_bounds__(256) mips_stage1_kernel(MipsParams p) {
         for (int s = 0; s < KS; ++s) {
             u32x4 w = {0, 0, 0, 0};
             if (q < p.Q) w = *(const u32x4*)(p.queries + (size_t)q * D + (2 * s + half) * 8);
-            qf[m][s] = __builtin_bit_cast(bf16x8, w);
+            qf[m][s] = w;
         }
     }
 
@@ -155,10 +157,16 @@ __global__ void __launch_bounds__(256) mips_stage1_kernel(MipsParams p) {
         const char* rowp = tile[b] + col * kRowBytes + half * 16;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            const bf16x8 a = __builtin_bit_cast(bf16x8, *(const u32x4*)(rowp + s * 32));
+            const u32x4 a = *(const u32x4*)(rowp + s * 32);
 #pragma unroll
-            for (int m = 0; m < MQ; ++m)
-                acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[m][s], acc[m], 0, 0, 0);
+            for (int m = 0; m < MQ; ++m) {
+                if constexpr (F16)
+                    acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                        __builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, qf[m][s]), acc[m], 0, 0, 0);
+                else
+                    acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        __builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, qf[m][s]), acc[m], 0, 0, 0);
+            }
         }
     };
     if (j0 < j1) {
@@ -240,16 +248,20 @@ __global__ void __launch_bounds__(256) mips_stage1_kernel(MipsParams p) {
     }
 }
 
-template <int KP>
-hipError_t launch_for(const MipsParams& p, hipStream_t stream) {
+template <int KP, bool F16>
+hipError_t launch_for_type(const MipsParams& p, hipStream_t stream) {
     const dim3 grid((unsigned)(p.nslab * p.nseg * p.nqt)), block(256);
     switch (p.D) {
-        case 64:  hipLaunchKernelGGL((mips_stage1_kernel<KP, 4, mips_subtiles(KP, 64)>), grid, block, 0, stream, p); break;
-        case 128: hipLaunchKernelGGL((mips_stage1_kernel<KP, 8, mips_subtiles(KP, 128)>), grid, block, 0, stream, p); break;
-        case 256: hipLaunchKernelGGL((mips_stage1_kernel<KP, 16, mips_subtiles(KP, 256)>), grid, block, 0, stream, p); break;
+        case 64:  hipLaunchKernelGGL((mips_stage1_kernel<KP, 4, mips_subtiles(KP, 64), F16>), grid, block, 0, stream, p); break;
+        case 128: hipLaunchKernelGGL((mips_stage1_kernel<KP, 8, mips_subtiles(KP, 128), F16>), grid, block, 0, stream, p); break;
+        case 256: hipLaunchKernelGGL((mips_stage1_kernel<KP, 16, mips_subtiles(KP, 256), F16>), grid, block, 0, stream, p); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
+}
+template <int KP>
+hipError_t launch_for(const MipsParams& p, hipStream_t stream) {
+    return p.f16 ? launch_for_type<KP, true>(p, stream) : launch_for_type<KP, false>(p, stream);
 }
 
 }  // namespace

@@ -84,7 +84,8 @@ def mips_scores(rows: int, N: int, seed: int, device="cpu", dim: int = 128):
     return (q @ d.t()).contiguous()
 
 
-def mips_vectors(Q: int, N: int, seed: int, device="cpu", dim: int = 128, kind: str = "unit"):
+def mips_vectors(Q: int, N: int, seed: int, device="cpu", dim: int = 128, kind: str = "unit",
+                 dtype=torch.bfloat16):
     """Query and database vectors for the matmul-fused entry point, as bf16 tensors [Q, dim] and
     [N, dim] (Section 7.3: one million 128-dimensional vectors, 1024 queries).
 
@@ -104,7 +105,7 @@ def mips_vectors(Q: int, N: int, seed: int, device="cpu", dim: int = 128, kind: 
         d = torch.randint(-2, 3, (N, dim), generator=g, device=device).to(torch.float32)
     else:
         raise ValueError(kind)
-    return q.to(torch.bfloat16).contiguous(), d.to(torch.bfloat16).contiguous()
+    return q.to(dtype).contiguous(), d.to(dtype).contiguous()
 
 
 def adversarial_sorted(rows: int, N: int, seed: int, device="cpu", K: int = 256, B: int = 256,

@@ -172,5 +172,7 @@ def test_mips_validation_and_plan():
     assert call(ws=None, ws_bytes=0) == atk.WORKSPACE_TOO_SMALL
     assert call(ws_bytes=need - 1) == atk.WORKSPACE_TOO_SMALL
     assert atk.mips_workspace_bytes(4, 4096, 96, 64, 2, 64) == atk.SIZE_MAX
+    assert atk.lib.atk_mips_workspace_bytes(2, 4, 4096, 128, 64, 2, 64) == need       # fp16 vectors
+    assert atk.lib.atk_mips_workspace_bytes(3, 4, 4096, 128, 64, 2, 64) == atk.SIZE_MAX   # integers
     st, text = atk.mips_describe_plan(1024, 1 << 20, 128, 1024, 4, 1024)
     assert st == atk.OK and text.startswith("mfma32x32x16") and "workspace=67108864" in text

@@ -23,8 +23,8 @@ def atk():
     return binding
 
 
-def run_both(atk, Q, N, D, K, Kp, B, seed, kind):
-    q, d = workloads.mips_vectors(Q, N, seed=seed, dim=D, kind=kind)
+def run_both(atk, Q, N, D, K, Kp, B, seed, kind, dtype=torch.bfloat16):
+    q, d = workloads.mips_vectors(Q, N, seed=seed, dim=D, kind=kind, dtype=dtype)
     print(f"mips case Q={Q} N={N} D={D} K={K} K'={Kp} B={B} kind={kind} seed={seed}", flush=True)
     gv, gi = atk.mips_approx_topk(q.to(DEV), d.to(DEV), K, Kp, B)
     torch.cuda.synchronize()
@@ -49,6 +49,20 @@ def test_integer_vectors_bit_exact(atk, Q, N, D, K, Kp, B):
     ov, oi = oracle.mips_approx_topk(workloads.to_numpy_bits(q), workloads.to_numpy_bits(d), K, Kp, B)
     assert (gi == oi).all()
     assert (gv.view(np.uint32) == ov.view(np.uint32)).all()
+
+
+@pytest.mark.parametrize("Q,N,D,K,Kp,B", [(100, 8192, 128, 100, 2, 64), (33, 32768, 64, 96, 3, 32),
+                                        (64, 65536, 256, 256, 4, 256), (130, 16384, 128, 128, 1, 128)])
+def test_fp16_vectors(atk, Q, N, D, K, Kp, B):
+    q, d, gv, gi = run_both(atk, Q, N, D, K, Kp, B, seed=21, kind="integer", dtype=torch.float16)
+    ov, oi = oracle.mips_approx_topk(q.numpy(), d.numpy(), K, Kp, B)
+    assert (gi == oi).all() and (gv.view(np.uint32) == ov.view(np.uint32)).all()
+    q, d, gv, gi = run_both(atk, Q, N, D, K, Kp, B, seed=22, kind="unit", dtype=torch.float16)
+    scores = oracle.mips_scores(q.numpy(), d.numpy())
+    ov, oi = oracle.mips_approx_topk(q.numpy(), d.numpy(), K, Kp, B)
+    tol = (D + 1) * 2.0 ** -24
+    moved = sum(explain_differences(scores[r], gv[r], gi[r], ov[r], oi[r], K, Kp, B, tol) for r in range(Q))
+    assert moved <= 0.01 * Q * K, moved
 
 
 def test_segments_are_used_when_pairs_are_few(atk):

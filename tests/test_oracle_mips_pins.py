@@ -23,6 +23,17 @@ def test_scores_match_library_matmul_in_float64():
     assert np.abs(s.astype(np.float64) - ref).max() <= 2.0 ** -24 * np.abs(ref).max() * 1.01
 
 
+def test_fp16_vectors_match_library_matmul_in_float64():
+    import torch
+    q, d = workloads.mips_vectors(5, 200, seed=7, dim=64, dtype=torch.float16)
+    s = oracle.mips_scores(q.numpy(), d.numpy())
+    ref = q.double().numpy() @ d.double().numpy().T
+    assert (s == ref.astype(np.float32)).mean() > 0.999
+    assert np.abs(s.astype(np.float64) - ref).max() <= 2.0 ** -24 * np.abs(ref).max() * 1.01
+    qi, di = workloads.mips_vectors(5, 200, seed=8, dim=64, kind="integer", dtype=torch.float16)
+    assert (oracle.mips_scores(qi.numpy(), di.numpy()) == qi.long().numpy() @ di.long().numpy().T).all()
+
+
 def test_integer_vectors_give_exact_integer_scores():
     q, d = workloads.mips_vectors(5, 257, seed=4, dim=64, kind="integer")
     s = oracle.mips_scores(bits(q), bits(d))
