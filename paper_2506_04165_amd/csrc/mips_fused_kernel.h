@@ -33,6 +33,20 @@ namespace {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 f16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+
+// operand fragment type and matrix instruction for the two 16-bit vector types
+template <bool F16> struct MipsFrag {
+    using type = bf16x8;
+    __device__ static __forceinline__ floatx16 mfma(type a, type b, floatx16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    }
+};
+template <> struct MipsFrag<true> {
+    using type = f16x8;
+    __device__ static __forceinline__ floatx16 mfma(type a, type b, floatx16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+    }
+};
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte move
 
 // The K' greatest scores each accumulator register has seen, greatest first, with the step at
@@ -113,7 +127,8 @@ __global__ void __launch_bounds__(256) mips_stage1_kernel(MipsParams p) {
 
     // ---- query fragments: lane (col, half) holds query col, dims (2s + half)*8 .. +8 of step s ---
     const int q_first = (qt * 4 + wave) * (32 * MQ);          // first query of this wavefront
-    u32x4 qf[MQ][KS];
+    using frag_t = typename MipsFrag<F16>::type;
+    frag_t qf[MQ][KS];
 #pragma unroll
     for (int m = 0; m < MQ; ++m) {
         const int q = q_first + m * 32 + col;
@@ -121,7 +136,7 @@ __global__ void __launch_bounds__(256) mips_stage1_kernel(MipsParams p) {
         for (int s = 0; s < KS; ++s) {
             u32x4 w = {0, 0, 0, 0};
             if (q < p.Q) w = *(const u32x4*)(p.queries + (size_t)q * D + (2 * s + half) * 8);
-            qf[m][s] = w;
+            qf[m][s] = __builtin_bit_cast(frag_t, w);
         }
     }
 
@@ -157,16 +172,9 @@ __global__ void __launch_bounds__(256) mips_stage1_kernel(MipsParams p) {
         const char* rowp = tile[b] + col * kRowBytes + half * 16;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            const u32x4 a = *(const u32x4*)(rowp + s * 32);
+            const frag_t a = __builtin_bit_cast(frag_t, *(const u32x4*)(rowp + s * 32));
 #pragma unroll
-            for (int m = 0; m < MQ; ++m) {
-                if constexpr (F16)
-                    acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
-                        __builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, qf[m][s]), acc[m], 0, 0, 0);
-                else
-                    acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        __builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, qf[m][s]), acc[m], 0, 0, 0);
-            }
+            for (int m = 0; m < MQ; ++m) acc[m] = MipsFrag<F16>::mfma(a, qf[m][s], acc[m]);
         }
     };
     if (j0 < j1) {
