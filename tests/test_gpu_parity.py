@@ -426,3 +426,24 @@ def test_hip_graph_capture_and_replay(atk):
         # and one replay against the oracle
         ov, oi = oracle.approx_topk(static_in.cpu().numpy()[:2], K, 4, 1024)
         assert np.array_equal(out[1].cpu().numpy()[:2], oi)
+
+
+def test_random_bit_patterns_through_every_stage2(atk):
+    # values drawn uniformly from the non-NaN binary32 patterns: both signs, infinities,
+    # subnormals, the whole exponent range -- the band of keys stage 2 sees is as wide as it gets
+    rng = np.random.default_rng(77)
+    def patterns(rows, N):
+        mag = rng.integers(0, 0x7F800001, (rows, N), dtype=np.int64).astype(np.uint32)
+        sign = (rng.integers(0, 2, (rows, N), dtype=np.int64) << 31).astype(np.uint32)
+        return torch.from_numpy((mag | sign).view(np.float32))
+    x = patterns(8, 262144)
+    check_approx(atk, x, 1024, 4, 1024)          # split route, finish kernel
+    check_approx(atk, x, 1024, 2, 4096)          # fused, one row per workgroup
+    check_exact(atk, x, 2048)
+    y = patterns(64, 16384)
+    for B, Kp, K in [(64, 8, 300), (256, 4, 1000), (1024, 1, 512), (16, 2, 20)]:
+        check_approx(atk, y, K, Kp, B)
+    # a narrow band that straddles a power of two (patterns differ in a high bit, values barely)
+    z = (2.0 + (torch.from_numpy(rng.integers(-2000, 2000, (8, 262144))).float() * 2.0 ** -22)).contiguous()
+    check_approx(atk, z, 1024, 4, 1024)
+    check_exact(atk, z, 1500)
