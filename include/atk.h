@@ -181,6 +181,16 @@ int atk_mips_approx_topk(const void* queries, const void* database, int dtype, i
 int atk_mips_select_params(int64_t N, int K, double recall_target, int* Kprime_out, int* B_out,
                            double* expected_recall_out);
 
+/*
+ * atk_mips_approx_topk with K' and B chosen by atk_mips_select_params(N, K, recall_target); the
+ * values used are reported through Kprime_used / B_used (may be NULL).  Size the workspace with
+ * atk_mips_workspace_bytes for the values atk_mips_select_params returns.
+ */
+int atk_mips_approx_topk_recall(const void* queries, const void* database, int dtype, int64_t Q,
+                                int64_t N, int64_t D, int K, double recall_target, float* out_vals,
+                                int32_t* out_idx, void* workspace, size_t workspace_bytes,
+                                void* stream, int* Kprime_used, int* B_used);
+
 /* Workspace bytes atk_mips_approx_topk needs; SIZE_MAX on illegal or unsupported arguments.
  * Host only. */
 size_t atk_mips_workspace_bytes(int dtype, int64_t Q, int64_t N, int64_t D, int K, int Kprime, int B);

@@ -27,7 +27,7 @@ SIZE_MAX = ctypes.c_size_t(-1).value
 EXPORTS = [
     "atk_approx_topk", "atk_topk", "atk_approx_topk_stage1", "atk_workspace_bytes",
     "atk_expected_recall", "atk_select_params", "atk_approx_topk_recall", "atk_describe_plan", "atk_valu_probe",
-    "atk_mips_approx_topk", "atk_mips_workspace_bytes", "atk_mips_describe_plan", "atk_mips_select_params", "atk_status_string", "atk_last_hip_error",
+    "atk_mips_approx_topk", "atk_mips_workspace_bytes", "atk_mips_describe_plan", "atk_mips_select_params", "atk_mips_approx_topk_recall", "atk_status_string", "atk_last_hip_error",
     "atk_version",
 ]
 
@@ -72,6 +72,8 @@ def _load() -> ctypes.CDLL:
     lib.atk_mips_workspace_bytes.restype = sz
     lib.atk_mips_describe_plan.argtypes = [ci, i64, i64, i64, ci, ci, ci, ctypes.c_char_p, sz]
     lib.atk_mips_describe_plan.restype = ci
+    lib.atk_mips_approx_topk_recall.argtypes = [vp, vp, ci, i64, i64, i64, ci, ctypes.c_double, vp, vp, vp, sz, vp, ip, ip]
+    lib.atk_mips_approx_topk_recall.restype = ci
     lib.atk_mips_select_params.argtypes = [i64, ci, ctypes.c_double, ip, ip, dp]
     lib.atk_mips_select_params.restype = ci
     lib.atk_status_string.argtypes = [ci]
@@ -265,6 +267,24 @@ def mips_approx_topk(queries: torch.Tensor, database: torch.Tensor, K: int, Kpri
     if st != OK:
         raise AtkError(st, "atk_mips_approx_topk")
     return out_vals, out_idx
+
+
+def mips_approx_topk_recall(queries: torch.Tensor, database: torch.Tensor, K: int, recall_target: float):
+    """Fused entry with fusion-aware parameters for a recall target.  Returns (scores, idx, K', B)."""
+    kp, b, _ = mips_select_params(database.shape[0], K, recall_target)
+    Q, D = queries.shape
+    ws = torch.empty(max(1, mips_workspace_bytes(Q, database.shape[0], D, K, kp, b)), dtype=torch.uint8,
+                     device=queries.device)
+    out_vals = torch.empty((Q, K), dtype=torch.float32, device=queries.device)
+    out_idx = torch.empty((Q, K), dtype=torch.int32, device=queries.device)
+    kp_used, b_used = ctypes.c_int(0), ctypes.c_int(0)
+    st = lib.atk_mips_approx_topk_recall(queries.data_ptr(), database.data_ptr(), _CODES[queries.dtype], Q,
+                                         database.shape[0], D, K, recall_target, out_vals.data_ptr(),
+                                         out_idx.data_ptr(), ws.data_ptr(), ws.numel(),
+                                         _stream_ptr(queries.device), ctypes.byref(kp_used), ctypes.byref(b_used))
+    if st != OK:
+        raise AtkError(st, "atk_mips_approx_topk_recall")
+    return out_vals, out_idx, kp_used.value, b_used.value
 
 
 def valu_probe(kind: int, x: torch.Tensor, y, ops: int, out=None):

@@ -551,6 +551,19 @@ int atk_mips_approx_topk(const void* queries, const void* database, int dtype, i
     return e == hipSuccess ? ATK_OK : hip_fail(e);
 }
 
+int atk_mips_approx_topk_recall(const void* queries, const void* database, int dtype, int64_t Q,
+                                int64_t N, int64_t D, int K, double recall_target, float* out_vals,
+                                int32_t* out_idx, void* workspace, size_t workspace_bytes,
+                                void* stream, int* Kprime_used, int* B_used) {
+    int kp = 0, b = 0;
+    int rc = atk_mips_select_params(N, K, recall_target, &kp, &b, nullptr);
+    if (rc) return rc;
+    if (Kprime_used) *Kprime_used = kp;
+    if (B_used) *B_used = b;
+    return atk_mips_approx_topk(queries, database, dtype, Q, N, D, K, kp, b, out_vals, out_idx,
+                                workspace, workspace_bytes, stream);
+}
+
 int atk_mips_describe_plan(int dtype, int64_t Q, int64_t N, int64_t D, int K, int Kprime, int B,
                            char* buf, size_t buflen) {
     if (!buf || buflen == 0) return ATK_INVALID_ARG;

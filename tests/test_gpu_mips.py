@@ -139,6 +139,15 @@ def test_full_size_integer_sampled_bit_exact(atk):
         assert (gi[r] == oi[0]).all() and (gv[r] == ov[0]).all()
 
 
+def test_recall_front_end(atk):
+    q, d = workloads.mips_vectors(40, 65536, seed=31, dim=128, kind="integer")
+    gv, gi, kp, b = atk.mips_approx_topk_recall(q.to(DEV), d.to(DEV), 256, 0.97)
+    torch.cuda.synchronize()
+    assert (kp, b) == oracle.mips_select_parameters(65536, 256, 0.97)
+    ov, oi = oracle.mips_approx_topk(workloads.to_numpy_bits(q), workloads.to_numpy_bits(d), 256, kp, b)
+    assert (gi.cpu().numpy() == oi).all() and (gv.cpu().numpy() == ov).all()
+
+
 def test_errors(atk):
     q, d = workloads.mips_vectors(4, 4096, seed=1, dim=128)
     q, d = q.to(DEV), d.to(DEV)
