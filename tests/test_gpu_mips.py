@@ -139,6 +139,26 @@ def test_full_size_integer_sampled_bit_exact(atk):
         assert (gi[r] == oi[0]).all() and (gv[r] == ov[0]).all()
 
 
+def test_seeded_random_shapes_integer_vectors(atk):
+    # shapes the list above does not name: any B that is a multiple of 32, every K', every
+    # supported D and both vector types, ragged query tiles, short and long walks
+    rng = np.random.default_rng(77)
+    for case in range(24):
+        D = int(rng.choice([64, 128, 256]))
+        B = 32 * int(rng.integers(1, 40))
+        steps = int(rng.integers(1, max(1, min(400, 200000 // B)) + 1))
+        N = B * steps
+        Kp = int(rng.integers(1, min(4, steps) + 1))
+        K = int(rng.integers(Kp, min(B * Kp, N, 2048) + 1))
+        Q = int(rng.integers(1, 300))
+        dtype = torch.bfloat16 if rng.random() < 0.6 else torch.float16
+        q, d, gv, gi = run_both(atk, Q, N, D, K, Kp, B, seed=1000 + case, kind="integer", dtype=dtype)
+        qh = workloads.to_numpy_bits(q) if dtype == torch.bfloat16 else q.numpy()
+        dh = workloads.to_numpy_bits(d) if dtype == torch.bfloat16 else d.numpy()
+        ov, oi = oracle.mips_approx_topk(qh, dh, K, Kp, B)
+        assert (gi == oi).all() and (gv.view(np.uint32) == ov.view(np.uint32)).all(), case
+
+
 def test_recall_front_end(atk):
     q, d = workloads.mips_vectors(40, 65536, seed=31, dim=128, kind="integer")
     gv, gi, kp, b = atk.mips_approx_topk_recall(q.to(DEV), d.to(DEV), 256, 0.97)

@@ -447,3 +447,62 @@ def test_random_bit_patterns_through_every_stage2(atk):
     z = (2.0 + (torch.from_numpy(rng.integers(-2000, 2000, (8, 262144))).float() * 2.0 ** -22)).contiguous()
     check_approx(atk, z, 1024, 4, 1024)
     check_exact(atk, z, 1500)
+
+
+def test_seeded_random_shapes_all_element_types(atk):
+    # shapes no hand-written case lists: bucket counts of every kind (tiny, powers of two,
+    # multiples of 32, arbitrary), list lengths up to 32, every element type, inputs with dense
+    # ties or in descending order; approximate and exact kernels against the oracle, bit for bit
+    rng = np.random.default_rng(2024)
+    dtypes = [torch.float32, torch.bfloat16, torch.float16, torch.int32, torch.uint32]
+
+    def raw(t):
+        t = t.detach().cpu().contiguous()
+        return (t.view(torch.int16).numpy().view(np.uint16) if t.element_size() == 2
+                else t.view(torch.int32).numpy().view(np.uint32))
+
+    def oracle_raw(a):
+        return a.view(np.uint16) if a.dtype.itemsize == 2 else a.view(np.uint32)
+
+    ran = 0
+    for case in range(90):
+        dt = dtypes[int(rng.integers(5))]
+        kind = int(rng.integers(4))
+        B = (int(rng.integers(1, 65)) if kind == 0 else int(2 ** rng.integers(0, 13)) if kind == 1
+             else int(rng.integers(1, 40)) * 32 if kind == 2 else int(rng.integers(65, 5000)))
+        steps = int(rng.integers(1, max(1, min(300, 150000 // B)) + 1))
+        N = B * steps
+        Kp = int(rng.integers(1, min(steps, 32) + 1))
+        if rng.random() < 0.5:
+            Kp = min(Kp, 4)
+        K = int(rng.integers(Kp, min(B * Kp, N, 2048) + 1))
+        rows = int(rng.integers(1, 40))
+        style = int(rng.integers(3))
+        g = torch.Generator().manual_seed(int(rng.integers(1 << 30)))
+        if dt in (torch.int32, torch.uint32):
+            lo, hi = (-(1 << 31), 1 << 31) if style == 0 else (-50, 50)
+            x = torch.randint(lo, hi, (rows, N), generator=g, dtype=torch.int64)
+            x = (x & 0xffffffff).to(torch.uint32) if dt == torch.uint32 else x.to(torch.int32)
+        else:
+            x = torch.randn(rows, N, generator=g)
+            if style == 1:
+                x = torch.round(x * 4) / 4
+            elif style == 2:
+                x = torch.sort(x, dim=1, descending=True).values
+            x = x.to(dt)
+        status, _ = atk.describe_plan(dt, rows, N, K, Kp, B)
+        if status == atk.UNSUPPORTED:      # more than 16384 list entries per row: documented limit
+            assert B * Kp > 8192
+            continue
+        print(f"case {case}: {dt} rows={rows} N={N} B={B} K'={Kp} K={K} style={style}", flush=True)
+        xh, xd = workloads.to_numpy_bits(x), x.to(DEV)
+        gv, gi = atk.approx_topk(xd, K, Kp, B)
+        torch.cuda.synchronize()
+        ov, oi = oracle.approx_topk(xh, K, Kp, B)
+        assert np.array_equal(gi.cpu().numpy(), oi) and np.array_equal(raw(gv), oracle_raw(ov)), case
+        ev, ei = atk.topk(xd, K)
+        torch.cuda.synchronize()
+        ov, oi = oracle.topk(xh, K)
+        assert np.array_equal(ei.cpu().numpy(), oi) and np.array_equal(raw(ev), oracle_raw(ov)), case
+        ran += 1
+    assert ran >= 70
