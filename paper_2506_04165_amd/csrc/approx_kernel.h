@@ -73,14 +73,6 @@ __device__ __forceinline__ T sel(bool c, T a, T b) { return c ? a : b; }
 //    -- K' lane operations -- and no index needs tracking.  Key 0 is the empty entry.
 template <int REP, int KP, int NL> struct Lists;
 
-// median of three unsigned words.  Written as the instruction itself: the equivalent min/max
-// expression sends the optimizer into exponential work on chains of list updates.
-__device__ __forceinline__ uint32_t med3_u32(uint32_t a, uint32_t b, uint32_t c) {
-    uint32_t d;
-    asm("v_med3_u32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
-    return d;
-}
-
 template <int KP, int NL>
 struct Lists<0, KP, NL> {
     static constexpr bool exact_bits = false;    // a zero entry may carry the other zero's sign
@@ -429,7 +421,9 @@ struct ApproxKernel {
                             const uint32_t key = (L.key[r * V + v][k] & 0xffff0000u) | (0xffffu - n);
                             cand32[(off[r] + v) * p.Kprime + k] = row_ok ? key : 0;
                         }
-            __syncthreads();
+            // a row's keys are written and sorted by the same wavefront unless several share it
+            if (p.G > kWave) __syncthreads();
+            else __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             if (p.G >= kWave) {
                 if (t < kWave && row_ok)
                     wave_sort32_dispatch<DT>(cand32, p.Cpad, p.K, rowp, p.out_vals, p.out_idx,
@@ -441,7 +435,7 @@ struct ApproxKernel {
                     const int gl = (tid >> 6) * per_wave + j;
                     const int rw = blockIdx.x * p.rows_per_wg + gl;
                     if (rw < p.rows)
-                        wave_sort32_dispatch<DT>((const uint32_t*)lds + (size_t)gl * p.Cpad, p.Cpad, p.K,
+                        wave_sort32_dispatch<DT>((uint32_t*)lds + (size_t)gl * p.Cpad, p.Cpad, p.K,
                                                  (const char*)p.values + (size_t)rw * p.row_stride * ES,
                                                  p.out_vals, p.out_idx, (int64_t)rw * p.K);
                 }

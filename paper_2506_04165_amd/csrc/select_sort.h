@@ -40,6 +40,14 @@ __device__ __forceinline__ KeyT lane_xor_key(KeyT x, int m) {
     else return ((uint64_t)lane_xor((uint32_t)(x >> 32), m) << 32) | lane_xor((uint32_t)x, m);
 }
 
+// median of three unsigned words.  Written as the instruction itself: the equivalent min/max
+// expression sends the optimizer into exponential work on chains of list updates.
+__device__ __forceinline__ uint32_t med3_u32(uint32_t a, uint32_t b, uint32_t c) {
+    uint32_t d;
+    asm("v_med3_u32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+    return d;
+}
+
 // Bitonic sorting network in the form whose comparators all point the same way: level kk first
 // compares every element e with its mirror image e ^ (kk-1) inside the block, then with
 // e ^ (kk/4), ..., e ^ 1; the lower index always keeps the greater key.
@@ -55,12 +63,11 @@ struct WaveSort {
         else { const bool sw = a < b; hi = sw ? b : a; lo = sw ? a : b; }
     }
     // The greater (want_max) or the smaller of a and b; want_max differs from lane to lane.  The
-    // 32-bit form merges max and min through a lane mask (one v_bfi) so that no branch on
-    // want_max can be formed around a run of these.
+    // 32-bit form is one median of three: with the greatest word as third operand the median
+    // of (a, b, .) is max(a, b), with zero it is min(a, b).
     __device__ static __forceinline__ KeyT pick(KeyT a, KeyT b, bool want_max) {
         if constexpr (sizeof(KeyT) == 4) {
-            const uint32_t m = want_max ? 0xffffffffu : 0u;
-            return (m & max(a, b)) | (~m & min(a, b));
+            return med3_u32(a, b, want_max ? 0xffffffffu : 0u);
         } else {
             const bool take_b = (b > a) == want_max;
             return take_b ? b : a;
@@ -118,28 +125,49 @@ struct WaveSort {
     __device__ static void sort(KeyT (&k)[R]) { levels<1>(k, __lane_id()); }
 };
 
-// Decode and write the first K of the sorted keys of one wavefront (rank e = lane*R + j).
+// A pointer known to point into LDS.  The sorting tails are not inlined and receive generic
+// pointers; through this type their accesses are LDS instructions rather than flat ones.
+template <typename T> using lds_ptr = __attribute__((address_space(3))) T*;
+
+// Position in a staging array of LDS for the key of rank e, chosen so that neither a wavefront
+// writing its registers (lane l, register j holds rank l*R + j) nor one reading ranks lane,
+// lane + 64, ... meets bank conflicts beyond the width of the access: the position inside each
+// aligned group of R is xor-ed with higher rank bits.  WORDS = 32-bit words per key.
+template <int R, int WORDS>
+__device__ __forceinline__ int staged_rank(int e) {
+    return e ^ ((e >> (WORDS == 2 ? 5 : 6)) & (R - 1));
+}
+
+// Decode and write the first K of the sorted keys of one wavefront (lane l, register j holds
+// rank l*R + j).  The keys pass through `stage` (LDS; only the ranks below K rounded up to a
+// multiple of R are touched) so that consecutive lanes write consecutive outputs.
 template <typename DT, int R>
 __device__ __forceinline__ void wave_write_topk(const uint64_t (&k)[R], int K, const void* rowp,
-                                                void* out_vals, int32_t* out_idx, int64_t out_base) {
+                                                void* out_vals, int32_t* out_idx, int64_t out_base,
+                                                uint64_t* stage_generic) {
+    lds_ptr<uint64_t> stage = (lds_ptr<uint64_t>)stage_generic;
     const int lane = __lane_id();
+    if (lane * R < K) {
 #pragma unroll
-    for (int j = 0; j < R; ++j) {
-        const int e = lane * R + j;
-        if (e < K) {
-            const uint32_t n = key_index(k[j]);
-            uint32_t bits = key_value_bits<DT>(k[j]);
-            if (bits == 0 && k[j] != 0) bits = elem<DT>::load_bits(rowp, n);   // which zero it was
-            elem<DT>::store_bits(out_vals, out_base + e, bits);
-            out_idx[out_base + e] = (int32_t)n;
-        }
+        for (int j = 0; j < R; ++j) stage[staged_rank<R, 2>(lane * R + j)] = k[j];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    for (int e = lane; e < K; e += kWave) {
+        const uint64_t key = stage[staged_rank<R, 2>(e)];
+        const uint32_t n = key_index(key);
+        uint32_t bits = key_value_bits<DT>(key);
+        if (bits == 0 && key != 0) bits = elem<DT>::load_bits(rowp, n);   // which zero it was
+        elem<DT>::store_bits(out_vals, out_base + e, bits);
+        out_idx[out_base + e] = (int32_t)n;
     }
 }
 
-// One wavefront sorts `n` (<= 64*R) keys read from LDS and writes the first K.
+// One wavefront sorts `n` (<= 64*R) keys read from LDS and writes the first K; the array (room
+// for K rounded up to a multiple of R keys) is reused as staging.
 template <typename DT, int R>
-__device__ __forceinline__ void wave_sort_from_lds(const uint64_t* keys, int n, int K, const void* rowp,
+__device__ __forceinline__ void wave_sort_from_lds(uint64_t* keys_generic, int n, int K, const void* rowp,
                                                    void* out_vals, int32_t* out_idx, int64_t out_base) {
+    lds_ptr<uint64_t> keys = (lds_ptr<uint64_t>)keys_generic;
     const int lane = __lane_id();
     uint64_t k[R];
 #pragma unroll
@@ -148,13 +176,13 @@ __device__ __forceinline__ void wave_sort_from_lds(const uint64_t* keys, int n, 
         k[j] = i < n ? keys[i] : 0;
     }
     WaveSort<R>::sort(k);
-    wave_write_topk<DT, R>(k, K, rowp, out_vals, out_idx, out_base);
+    wave_write_topk<DT, R>(k, K, rowp, out_vals, out_idx, out_base, keys_generic);
 }
 
 // Not inlined on purpose: the sorting networks are long, and every streaming kernel variant
 // that finishes in LDS shares this one copy per translation unit.
 template <typename DT>
-__device__ __noinline__ void wave_sort_dispatch(const uint64_t* keys, int n, int K, const void* rowp,
+__device__ __noinline__ void wave_sort_dispatch(uint64_t* keys, int n, int K, const void* rowp,
                                                    void* out_vals, int32_t* out_idx, int64_t out_base) {
     if (n <= 64)       wave_sort_from_lds<DT, 1>(keys, n, K, rowp, out_vals, out_idx, out_base);
     else if (n <= 128) wave_sort_from_lds<DT, 2>(keys, n, K, rowp, out_vals, out_idx, out_base);
@@ -166,8 +194,9 @@ __device__ __noinline__ void wave_sort_dispatch(const uint64_t* keys, int n, int
 // ---- packed 32-bit keys (bf16 rows of at most 65536 elements) ---------------------------------
 // key = ordered 16-bit value << 16 | (0xFFFF - index); 0 = empty.
 template <typename DT, int R>
-__device__ __forceinline__ void wave_sort32_from_lds(const uint32_t* keys, int n, int K, const void* rowp,
+__device__ __forceinline__ void wave_sort32_from_lds(uint32_t* keys_generic, int n, int K, const void* rowp,
                                                      void* out_vals, int32_t* out_idx, int64_t out_base) {
+    lds_ptr<uint32_t> keys = (lds_ptr<uint32_t>)keys_generic;
     const int lane = __lane_id();
     uint32_t k[R];
 #pragma unroll
@@ -176,21 +205,24 @@ __device__ __forceinline__ void wave_sort32_from_lds(const uint32_t* keys, int n
         k[j] = i < n ? keys[i] : 0;
     }
     WaveSort<R, uint32_t>::sort(k);
+    // through LDS (the key array itself) so that consecutive lanes write consecutive outputs
+    if (lane * R < K) {
 #pragma unroll
-    for (int j = 0; j < R; ++j) {
-        const int e = lane * R + j;
-        if (e < K) {
-            const uint32_t idx = 0xffffu - (k[j] & 0xffffu);
-            uint32_t bits = bits_from_ordered(k[j] & 0xffff0000u);
-            if (bits == 0 && k[j] != 0) bits = elem<DT>::load_bits(rowp, idx);   // which zero it was
-            elem<DT>::store_bits(out_vals, out_base + e, bits);
-            out_idx[out_base + e] = (int32_t)idx;
-        }
+        for (int j = 0; j < R; ++j) keys[staged_rank<R, 1>(lane * R + j)] = k[j];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    for (int e = lane; e < K; e += kWave) {
+        const uint32_t key = keys[staged_rank<R, 1>(e)];
+        const uint32_t idx = 0xffffu - (key & 0xffffu);
+        uint32_t bits = bits_from_ordered(key & 0xffff0000u);
+        if (bits == 0 && key != 0) bits = elem<DT>::load_bits(rowp, idx);   // which zero it was
+        elem<DT>::store_bits(out_vals, out_base + e, bits);
+        out_idx[out_base + e] = (int32_t)idx;
     }
 }
 
 template <typename DT>
-__device__ __noinline__ void wave_sort32_dispatch(const uint32_t* keys, int n, int K, const void* rowp,
+__device__ __noinline__ void wave_sort32_dispatch(uint32_t* keys, int n, int K, const void* rowp,
                                                   void* out_vals, int32_t* out_idx, int64_t out_base) {
     if (n <= 64)       wave_sort32_from_lds<DT, 1>(keys, n, K, rowp, out_vals, out_idx, out_base);
     else if (n <= 128) wave_sort32_from_lds<DT, 2>(keys, n, K, rowp, out_vals, out_idx, out_base);
