@@ -39,16 +39,16 @@ PAPER_CONTEXT = {
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by a plain
 # copy of known size (profiles/approx_topk_<workload>_B<B>_Kp<K'>.md), keyed by (workload, B, K').
 MEASURED_TRAFFIC_BYTES = {
-    ("c4_mips", 1024, 4): 1074750024,
-    ("c4_mips", 4096, 1): 1074697801,
-    ("c2_ffn", 128, 4): 498399271,
-    ("c2_ffn", 1024, 1): 498535043,
-    ("c2_ffn", 64, 8): 498340244,
-    ("c3_vocab", 512, 4): 525578888,
-    ("c3_vocab", 512, 2): 525411644,
-    ("c5_adversarial", 256, 8): 272427269,
-    ("c5_adversarial", 256, 1): 272402495,
-    ("c5_adversarial", 256, 32): 271618327,
+    ("c4_mips", 1024, 4): 1075838686,
+    ("c4_mips", 4096, 1): 1075797023,
+    ("c2_ffn", 128, 4): 498350425,
+    ("c2_ffn", 1024, 1): 498436239,
+    ("c2_ffn", 64, 8): 498299558,
+    ("c3_vocab", 512, 4): 528174531,
+    ("c3_vocab", 512, 2): 527631394,
+    ("c5_adversarial", 256, 8): 276454595,
+    ("c5_adversarial", 256, 1): 278560406,
+    ("c5_adversarial", 256, 32): 271606638,
 }
 
 

@@ -550,7 +550,7 @@ struct ApproxKernel {
 // The sorted-batch representation holds two K'-lists of 64-bit keys per lane and is only
 // launched with at most 256 lanes per workgroup, which lets it use the larger register budget.
 template <typename DT, int KP, int V, int R, int REP>
-__global__ void __launch_bounds__(REP == 2 ? 256 : 1024) approx_topk_kernel(ApproxParams p) {
+__global__ void __launch_bounds__(REP == 2 ? 256 : 1024, REP == 1 ? 6 : 1) approx_topk_kernel(ApproxParams p) {
     extern __shared__ uint64_t atk_lds[];
     ApproxKernel<DT, KP, V, R, REP>::run(p, atk_lds);
 }
