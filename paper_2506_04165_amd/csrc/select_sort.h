@@ -341,8 +341,8 @@ constexpr int kWgSortMinThreads = 256;
 // order.  Every wavefront sorts runs of 512 keys in registers; the runs are then merged pairwise
 // by the bitonic network in its same-direction form (run a against the mirror image of run b,
 // then half-cleaners), and once a merged run would exceed `cap` keys (the power of two >= K,
-// at least 512) only its first `cap` positions are kept and cleaned.  Compared with running the
-// whole network in LDS this needs 10 barrier-separated stages per merge level instead of 55.
+// at least 512) only its first `cap` positions are kept and cleaned.  A merge level costs one
+// barrier-separated LDS stage per distance of 512 and more, plus one pass through registers.
 // Every thread of the workgroup.
 __device__ __forceinline__ void wg_sort_merge_topk(uint64_t* keys, int n, int K) {
     const int tid = threadIdx.x, T = blockDim.x;
@@ -371,9 +371,10 @@ __device__ __forceinline__ void wg_sort_merge_topk(uint64_t* keys, int n, int K)
             if (x < y) { keys[a] = y; keys[b] = x; }
         }
         __syncthreads();
-        // half-cleaners inside what is kept: both runs while 2m <= cap, else the first run only
+        // half-cleaners inside what is kept: both runs while 2m <= cap, else the first run only.
+        // Distances of kRun and more go through LDS ...
         const int kept = 2 * m <= cap ? 2 * m : m;       // keys kept per block, from its start
-        for (int j = m >> 1; j >= 1; j >>= 1) {
+        for (int j = m >> 1; j >= kRun; j >>= 1) {
             for (int q = tid; q < nblocks * (kept >> 1); q += T) {
                 const int blk = q / (kept >> 1), i = q - blk * (kept >> 1);
                 const int lo = blk * 2 * L + (((i & ~(j - 1)) << 1) | (i & (j - 1)));
@@ -383,6 +384,20 @@ __device__ __forceinline__ void wg_sort_merge_topk(uint64_t* keys, int n, int K)
             }
             __syncthreads();
         }
+        // ... the shorter ones stay inside aligned pieces of kRun keys: a wavefront takes a piece
+        // into registers and runs all of them there
+        const int pieces = kept / kRun;
+        for (int c = wave; c < nblocks * pieces; c += nwaves) {
+            const int blk = c / pieces;
+            uint64_t* piece = keys + (size_t)blk * 2 * L + (size_t)(c - blk * pieces) * kRun;
+            uint64_t k[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) k[j] = piece[lane * 8 + j];
+            WaveSort<8, uint64_t>::template steps_down<8>(k, lane);      // distances 256 ... 1
+#pragma unroll
+            for (int j = 0; j < 8; ++j) piece[lane * 8 + j] = k[j];
+        }
+        __syncthreads();
     }
 }
 
@@ -404,6 +419,14 @@ __device__ __forceinline__ void wg_topk_from_lds(uint64_t* keys, int n, int K, v
             return;
         }
         if (tid < kWave) wave_sort_dispatch<DT>(keys, n, K, rowp, out_vals, out_idx, out_base);
+        return;
+    }
+    // twice that many keys with an eighth or more of them wanted: sorting them all (four runs,
+    // two merge levels) is still cheaper than the selection passes (measured; from 4096 keys on,
+    // or for a smaller share, the selection wins)
+    if (T >= kWgSortMinThreads && n == 2 * kWaveSortMaxKeys && 8 * K >= n) {
+        wg_sort_merge_topk(keys, n, K);
+        wg_write_topk<DT>(keys, K, rowp, out_vals, out_idx, out_base);
         return;
     }
     if (K <= kWaveSortMaxKeys) {
