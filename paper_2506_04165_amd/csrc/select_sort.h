@@ -334,27 +334,32 @@ __device__ __forceinline__ void wg_write_topk(const uint64_t* keys, int K, const
 
 // One wavefront sorts up to kWaveSortMaxKeys keys in registers; beyond kWgSortMinKeys keys a
 // workgroup of at least kWgSortMinThreads threads is faster sorting them in LDS together.
-constexpr int kWgSortMinKeys = 512;
+constexpr int kWgSortMinKeys = 256;
 constexpr int kWgSortMinThreads = 256;
+constexpr int kSideSortKeys = 256;      // a boundary bin of at most this many keys is sorted, not split
 
-// Sort n keys in LDS (n a power of two >= 1024) far enough that keys[0..K) hold the K greatest in
-// order.  Every wavefront sorts runs of 512 keys in registers; the runs are then merged pairwise
-// by the bitonic network in its same-direction form (run a against the mirror image of run b,
-// then half-cleaners), and once a merged run would exceed `cap` keys (the power of two >= K,
-// at least 512) only its first `cap` positions are kept and cleaned.  A merge level costs one
-// barrier-separated LDS stage per distance of 512 and more, plus one pass through registers.
-// Every thread of the workgroup.
-__device__ __forceinline__ void wg_sort_merge_topk(uint64_t* keys, int n, int K) {
+// Sort n keys in LDS (n a power of two >= 128 R) far enough that keys[0..K) hold the K greatest
+// in order.  Every wavefront sorts runs of 64 R keys in registers; the runs are then merged
+// pairwise by the bitonic network in its same-direction form (run a against the mirror image of
+// run b, then half-cleaners), and once a merged run would exceed `cap` keys (the power of two
+// >= K, at least one run) only its first `cap` positions are kept and cleaned.  A merge level
+// costs one barrier-separated LDS stage per distance of a run length and more, plus one pass
+// through registers for the shorter distances.  A lone wavefront needs about 5 us for 512 keys
+// (the network is one long dependency chain), so short runs on many wavefronts win: R is chosen
+// by the caller to give every wavefront a run.  Every thread of the workgroup.
+template <int R>
+__device__ __forceinline__ void wg_sort_merge_runs(uint64_t* keys, int n, int K) {
+    using WS = WaveSort<R, uint64_t>;
     const int tid = threadIdx.x, T = blockDim.x;
     const int lane = tid & (kWave - 1), wave = tid >> 6, nwaves = T >> 6;
-    constexpr int kRun = 512;
+    constexpr int kRun = kWave * R;
     for (int c = wave; c < n / kRun; c += nwaves) {
-        uint64_t k[8];
+        uint64_t k[R];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) k[j] = keys[c * kRun + lane * 8 + j];
-        WaveSort<8, uint64_t>::sort(k);
+        for (int j = 0; j < R; ++j) k[j] = keys[c * kRun + lane * R + j];
+        WS::sort(k);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) keys[c * kRun + lane * 8 + j] = k[j];
+        for (int j = 0; j < R; ++j) keys[c * kRun + lane * R + j] = k[j];
     }
     __syncthreads();
     int cap = kRun;
@@ -372,7 +377,7 @@ __device__ __forceinline__ void wg_sort_merge_topk(uint64_t* keys, int n, int K)
         }
         __syncthreads();
         // half-cleaners inside what is kept: both runs while 2m <= cap, else the first run only.
-        // Distances of kRun and more go through LDS ...
+        // Distances of a run length and more go through LDS ...
         const int kept = 2 * m <= cap ? 2 * m : m;       // keys kept per block, from its start
         for (int j = m >> 1; j >= kRun; j >>= 1) {
             for (int q = tid; q < nblocks * (kept >> 1); q += T) {
@@ -384,21 +389,29 @@ __device__ __forceinline__ void wg_sort_merge_topk(uint64_t* keys, int n, int K)
             }
             __syncthreads();
         }
-        // ... the shorter ones stay inside aligned pieces of kRun keys: a wavefront takes a piece
-        // into registers and runs all of them there
+        // ... the shorter ones stay inside aligned pieces of one run length: a wavefront takes a
+        // piece into registers and runs all of them there
         const int pieces = kept / kRun;
         for (int c = wave; c < nblocks * pieces; c += nwaves) {
             const int blk = c / pieces;
             uint64_t* piece = keys + (size_t)blk * 2 * L + (size_t)(c - blk * pieces) * kRun;
-            uint64_t k[8];
+            uint64_t k[R];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) k[j] = piece[lane * 8 + j];
-            WaveSort<8, uint64_t>::template steps_down<8>(k, lane);      // distances 256 ... 1
+            for (int j = 0; j < R; ++j) k[j] = piece[lane * R + j];
+            WS::template steps_down<WS::LOGN - 1>(k, lane);      // distances kRun/2 ... 1
 #pragma unroll
-            for (int j = 0; j < 8; ++j) piece[lane * 8 + j] = k[j];
+            for (int j = 0; j < R; ++j) piece[lane * R + j] = k[j];
         }
         __syncthreads();
     }
+}
+
+// n a power of two >= 256.
+__device__ __forceinline__ void wg_sort_merge_topk(uint64_t* keys, int n, int K) {
+    const int per_wave = n / (int)(blockDim.x >> 6);      // keys per wavefront if all take part
+    if (per_wave <= 128)      wg_sort_merge_runs<2>(keys, n, K);
+    else if (per_wave <= 256) wg_sort_merge_runs<4>(keys, n, K);
+    else                      wg_sort_merge_runs<8>(keys, n, K);
 }
 
 // Top-K (descending) of the n keys in LDS `keys` (n a power of two, key 0 = empty, at least K
@@ -477,6 +490,37 @@ __device__ __forceinline__ void wg_topk_from_lds(uint64_t* keys, int n, int K, v
             // stop when members + candidates fit one sort; prefer a sort of at most 2K keys
             fits = certain + (int)count <= kWaveSortMaxKeys &&
                    (certain + (int)count <= 2 * K + 64 || pass >= 2);
+            if (!fits && (int)count <= kSideSortKeys) {
+                // The bin that holds the K-th key is small: rather than take more digits, sort
+                // its keys in one wavefront and read the K-th key off; what remains is "every
+                // key at or above it", exactly K of them.
+                if (tid == 0) ctl[3] = 0;
+                __syncthreads();
+                for_each_lds_key(keys, n, [&](uint64_t key) {
+                    if (key != 0 && (key & mask) == prefix) {
+                        const uint32_t slot = atomicAdd(&ctl[3], 1u);
+                        if (slot < (uint32_t)kSideSortKeys) buf[slot] = key;
+                    }
+                });
+                __syncthreads();
+                if (tid < kWave) {
+                    constexpr int RS = kSideSortKeys / kWave;
+                    uint64_t k[RS];
+#pragma unroll
+                    for (int j = 0; j < RS; ++j) {
+                        const int i = j * kWave + lane;
+                        k[j] = i < (int)count ? buf[i] : 0;
+                    }
+                    WaveSort<RS>::sort(k);
+#pragma unroll
+                    for (int j = 0; j < RS; ++j) buf[lane * RS + j] = k[j];
+                }
+                __syncthreads();
+                prefix = buf[need - 1];
+                mask = ~0ull;
+                fits = true;
+                __syncthreads();          // buf is filled again below
+            }
         }
         if (fits) {
             if (tid == 0) ctl[3] = 0;
