@@ -29,7 +29,8 @@
  *
  * Developer knobs (environment, read at every call; for experiments and tests, not for
  * production): ATK_LANES_PER_ROW=<power of two <= 1024> lanes that share one row,
- * ATK_SEGMENTS=<n> force n row segments on the split route, ATK_NO_PACKED=1 / ATK_NO_SUBWAVE=1
+ * ATK_SEGMENTS=<n> force n row segments on the split route, ATK_SLAB=0/2 never / whenever
+ * possible give workgroups slabs of 32 buckets (few-row route), ATK_NO_PACKED=1 / ATK_NO_SUBWAVE=1
  * switch the packed-key / several-rows-per-wavefront variants off, ATK_BATCH_MIN_KP=<k> list
  * length from which sorted batches are used, ATK_MIPS_SEGMENTS=<n> segments of the database walk
  * in atk_mips_approx_topk.  Results never depend on them.
@@ -73,8 +74,10 @@ typedef enum atk_op { ATK_OP_APPROX_TOPK = 0, ATK_OP_TOPK = 1, ATK_OP_STAGE1 = 2
  *   out_idx    [rows, K] device, int32
  *   workspace  device scratch of at least atk_workspace_bytes(ATK_OP_APPROX_TOPK, ...) bytes, or
  *              NULL when that is 0 (it is 0 whenever stage 2 runs fused in the stage-1 launch,
- *              i.e. when the B*K' survivors of a row fit in LDS; otherwise survivors go through
- *              this buffer and a second launch finishes)
+ *              i.e. when the B*K' survivors of a row fit in LDS and the rows are enough to fill
+ *              the chip; otherwise survivors, or per-bucket keys of rows that several
+ *              workgroups share, go through this buffer and a second launch finishes.  A
+ *              buffer that is too small for the shared-row routes only switches them off)
  * ATK_UNSUPPORTED: K' > 32 unless K' == K (then the exact kernel runs); more than 16384 list
  * entries per row in the stage-1 launch; K > 2048 on the exact and unfused routes.
  */

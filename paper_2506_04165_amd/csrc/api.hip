@@ -55,6 +55,9 @@ constexpr int64_t kTargetWaves = 2048;   // 256 CUs x 4 SIMDs x 2 waves: below t
 constexpr int kMinSegmentSteps = 8;      // do not cut a row into pieces shorter than this
 constexpr int kMaxSegments = 64;
 constexpr size_t kMinSplitBytes = 4u << 20;
+constexpr int kSlabBuckets = 32;         // buckets per workgroup on the slab route
+constexpr size_t kSlabMinRowBytes = 128u << 10;
+constexpr size_t kSlabMaxBytes = 128u << 20;
 
 static thread_local std::string g_last_hip_error;
 
@@ -112,6 +115,7 @@ struct Plan {
     size_t lds = 0;
     size_t workspace = 0;       // bytes the plan needs (0: none)
     int nseg = 1, seg_steps = 0;  // > 1: rows are cut into segments, finished by a second launch
+    int slab_w = 0;             // > 0: workgroups take slabs of this many buckets (see below)
 };
 
 static int list_len_for(int Kp) {
@@ -250,6 +254,43 @@ static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, in
         if (K > kExactMaxK) { pl.status = ATK_UNSUPPORTED; return pl; }
     }
     if (stage1_only && pl.lds > kLdsBudget) { pl.status = ATK_UNSUPPORTED; return pl; }
+
+    // Very few rows: give every workgroup a slab of 32 buckets of one row over all steps, with m
+    // lanes per bucket taking every m-th step.  A lane then reads 128-byte runs (32 four-byte
+    // elements) that lie B elements apart, which costs bandwidth but puts rows * B / 32
+    // workgroups on the chip, and unlike segments along the row it leaves nothing to merge:
+    // the workgroup ends with the final K' keys of its buckets and the second launch is stage 2
+    // alone.
+    if (pl.fused && owners == 1 && G >= 64 && rows > 0 && B % kSlabBuckets == 0 &&
+        pl.var->rep != 2 && env_int("ATK_SLAB", 1) != 0) {
+        const int64_t steps = N / B;
+        int m = 8;
+        while (m > 1 && (steps % m != 0 || steps / m < 4 || m * KP > 64)) m >>= 1;
+        const Variant* v = find_variant(dtype, KP, 1, false, [](int V) { return V == 1; });
+        const size_t in_bytes = (size_t)rows * N * es;
+        const size_t ws = (size_t)rows * Kp * B * 8;
+        // measured against the other routes on 1..128 rows of 2^16..2^20 elements: a gain of
+        // 10-45 % while the launch has at most 1024 workgroups and B >= 1024, a loss beyond
+        const bool few = rows * (B / kSlabBuckets) <= 1024 && B >= 1024 && !pl.var->packed() &&
+                         (size_t)N * es >= kSlabMinRowBytes && in_bytes <= kSlabMaxBytes;
+        if (m > 1 && v && v->V == 1 && v->R == 1 && ws <= ws_avail &&
+            (env_int("ATK_SLAB", 1) == 2 || few)) {
+            pl.var = v;
+            pl.slab_w = kSlabBuckets;
+            pl.G = kSlabBuckets * m;
+            pl.owners = m;
+            pl.S = m * B;
+            pl.nsteps = (int)(N / pl.S);
+            pl.seg = pow2_ceil((int64_t)m * KP);
+            pl.rows_per_wg = 1;
+            pl.block = pl.G;
+            pl.grid = (int)rows;
+            pl.aux_offset = 0;
+            pl.lds = (size_t)kSlabBuckets * pl.seg * 8;
+            pl.workspace = ws;
+            return pl;
+        }
+    }
 
     // Too few rows to fill the chip: cut every row into segments streamed by separate
     // workgroups (aim: at least 2 waves on each of the 1024 SIMDs), merged by a finishing launch.
@@ -413,6 +454,20 @@ int atk_approx_topk(const void* values, int dtype, int64_t rows, int64_t N, int6
         return run_exact(values, nullptr, dtype, rows, N, row_stride, K, out_vals, out_idx, st);
 
     ApproxParams p = params_from(pl, values, rows, N, row_stride, K, Kprime, B);
+    if (pl.slab_w > 0) {
+        // slab path: the final K' keys of every bucket through the workspace, then stage 2
+        p.mode = 3;
+        p.slab_w = pl.slab_w;
+        p.part_keys = (uint64_t*)workspace;
+        hipError_t e = pl.var->fn(p, pl.grid, pl.block, pl.lds, st);
+        if (e != hipSuccess) return hip_fail(e);
+        FinishParams f{};
+        f.part_keys = (const uint64_t*)workspace; f.values = values; f.row_stride = row_stride;
+        f.rows = (int)rows; f.K = K; f.Kprime = Kprime; f.B = B; f.nseg = 1; f.Cpad = pl.Cpad;
+        f.out_vals = out_vals; f.out_idx = out_idx;
+        e = launch_finish(f, dtype, pl.var->KP, st);
+        return e == hipSuccess ? ATK_OK : hip_fail(e);
+    }
     if (pl.nseg > 1) {
         // split path: partial lists of every (row, segment) through the workspace
         p.mode = 2;
@@ -596,9 +651,10 @@ int atk_describe_plan(int dtype, int64_t rows, int64_t N, int K, int Kprime, int
     std::snprintf(buf, buflen,
                   "%s%s KP=%d V=%d R=%d lanes_per_row=%d rows_per_wg=%d block=%d grid=%dx%d step=%d "
                   "steps=%d owners=%d seg=%d cand=%d tail=%d lds=%zu workspace=%zu",
-                  pl.nseg > 1 ? "split" : (pl.fused ? "fused" : "unfused"),
+                  pl.slab_w > 0 ? "slab" : pl.nseg > 1 ? "split" : (pl.fused ? "fused" : "unfused"),
                   pl.var->packed() ? " packed" : "", pl.var->KP, pl.var->V,
-                  pl.var->R, pl.G, pl.rows_per_wg, pl.block, pl.grid, pl.nseg, pl.S, pl.nsteps,
+                  pl.var->R, pl.G, pl.rows_per_wg, pl.block, pl.grid,
+                  pl.slab_w > 0 ? B / pl.slab_w : pl.nseg, pl.S, pl.nsteps,
                   pl.owners, pl.seg, pl.Cpad, pl.tail, pl.lds, pl.workspace);
     return ATK_OK;
 }

@@ -97,8 +97,11 @@ hipError_t launch_for(const FinishParams& p, int KP, int threads, hipStream_t st
 }  // namespace
 
 hipError_t launch_finish(const FinishParams& p, int dtype, int KP, hipStream_t stream) {
-    int threads = 64;      // up to 512: beyond that the 16-wavefront barriers cost more than they buy
-    while (threads < p.B && threads < 512) threads <<= 1;
+    // up to 512 threads: beyond that the 16-wavefront barriers cost more than they buy, unless
+    // the rows are so few that most of the chip idles and a row's latency is all that counts
+    const int max_threads = p.rows <= 64 ? 1024 : 512;
+    int threads = 64;
+    while (threads < p.B && threads < max_threads) threads <<= 1;
     if (threads < 256 && p.Cpad >= 1024) threads = 256;     // the sort wants more lanes than buckets
     if (dtype == kFinishScores) return launch_for<score_t>(p, KP, threads, stream);
     switch (dtype) {

@@ -39,14 +39,17 @@ struct ApproxParams {
     int Cpad;             // power of two >= B*K', LDS keys per row for stage 2
     int aux_offset;       // LDS keys before the auxiliary region (partial lists / select scratch)
     int mode;             // 0: stage 2 fused, write out_*; 1: write survivors to surv_*;
-                          // 2: this workgroup covers one segment of its row, write partial keys
+                          // 2: this workgroup covers one segment of its row, write partial keys;
+                          // 3: this workgroup covers slab_w buckets of its row over all steps
+                          //    (owners lanes per bucket), write their final K' keys
     int tail;             // mode 0, how stage 2 runs: 0 generic LDS sort of every row of the
                           // workgroup; 1 at most 1024 candidates per row, sorted in registers by
                           // the first wavefront of the row's group; 2 one row per workgroup,
                           // radix selection + wave sort
     int nseg;             // mode 2: segments per row (gridDim.y)
     int seg_steps;        // mode 2: steps per segment (the last one may be shorter)
-    uint64_t* part_keys;  // mode 2: [rows, nseg, K', B] keys, 0 = empty entry
+    int slab_w;           // mode 3: buckets per workgroup, a power of two (gridDim.y = B / slab_w)
+    uint64_t* part_keys;  // mode 2: [rows, nseg, K', B] keys, 0 = empty entry; mode 3: [rows, K', B]
     void* out_vals;
     int32_t* out_idx;
     void* surv_vals;
@@ -326,6 +329,11 @@ struct ApproxKernel {
             slot_ok[r] = o < p.S;
             off[r] = slot_ok[r] ? o : 0;    // idle slots re-read offset 0; their lists are dropped
         }
+        if (p.mode == 3) {
+            // a slab of buckets: lane t is owner t / slab_w of bucket first + t % slab_w, and a
+            // step spans `owners` consecutive bucket rounds of the row
+            off[0] = (t / p.slab_w) * p.B + (int)blockIdx.y * p.slab_w + (t & (p.slab_w - 1));
+        }
 
         // ---- stage 1: stream the row (or this workgroup's segment of it) once ------------------
         // A load address is (uniform base of the step, in a buffer descriptor) + (per-lane
@@ -483,15 +491,17 @@ struct ApproxKernel {
         } else {
             // m owners per bucket: partial lists -> [bucket][owner*KP + k], sort each bucket's
             // segment, keep its first K'.  Partial lists may be short: NaN entries become key 0.
-            uint64_t* part = lds + p.aux_offset + (size_t)g * p.B * p.seg;
-            for (int i = t; i < p.B * p.seg; i += p.G) part[i] = 0;
-            for (int i = C + t; i < p.Cpad; i += p.G) cand[i] = 0;
+            const int nb = p.mode == 3 ? p.slab_w : p.B;             // buckets of this workgroup
+            const int b_first = p.mode == 3 ? (int)blockIdx.y * p.slab_w : 0;
+            uint64_t* part = lds + p.aux_offset + (size_t)g * nb * p.seg;
+            for (int i = t; i < nb * p.seg; i += p.G) part[i] = 0;
+            if (p.mode != 3) { for (int i = C + t; i < p.Cpad; i += p.G) cand[i] = 0; }
             __syncthreads();
             if (row_ok) {
 #pragma unroll
                 for (int v = 0; v < V; ++v) {           // R == 1 in this mode
                     const int e = off[0] + v;
-                    const int bucket = e % p.B, owner = e / p.B;
+                    const int bucket = e % p.B - b_first, owner = e / p.B;
 #pragma unroll
                     for (int k = 0; k < KP; ++k) {
                         const uint32_t n = L.index(v, k, (uint32_t)p.S, (uint32_t)e);
@@ -501,7 +511,17 @@ struct ApproxKernel {
                 }
             }
             __syncthreads();
-            lds_bitonic_sort_desc(lds + p.aux_offset, p.rows_per_wg * p.B * p.seg, p.seg);
+            lds_bitonic_sort_desc(lds + p.aux_offset, p.rows_per_wg * nb * p.seg, p.seg);
+            if (p.mode == 3) {
+                // the slab's final lists, laid out like one segment's partial keys
+                if (row_ok)
+                    for (int i = t; i < nb * p.Kprime; i += p.G) {
+                        const int k = i / nb, lb = i - k * nb;
+                        p.part_keys[((int64_t)row * p.Kprime + k) * p.B + b_first + lb] =
+                            part[(size_t)lb * p.seg + k];
+                    }
+                return;
+            }
             for (int i = t; i < C; i += p.G) {
                 const int bucket = i / p.Kprime, k = i - bucket * p.Kprime;
                 const uint64_t key = part[(size_t)bucket * p.seg + k];
@@ -566,7 +586,7 @@ hipError_t launch_approx(const ApproxParams& p, int grid, int block, size_t lds_
                                                    size_t lds_bytes, hipStream_t stream) {      \
         allow_large_lds((const void*)approx_topk_kernel<DT, KP, V, R, REP>, lds_bytes);         \
         hipLaunchKernelGGL((approx_topk_kernel<DT, KP, V, R, REP>),                             \
-                           dim3(grid, p.mode == 2 ? p.nseg : 1), dim3(block),                   \
+                           dim3(grid, p.mode == 2 ? p.nseg : (p.mode == 3 ? p.B / p.slab_w : 1)), dim3(block),                   \
                            lds_bytes, stream, p);                                               \
         return hipGetLastError();                                                               \
     }

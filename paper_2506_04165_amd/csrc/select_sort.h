@@ -348,8 +348,9 @@ constexpr int kSideSortKeys = 256;      // a boundary bin of at most this many k
 // (the network is one long dependency chain), so short runs on many wavefronts win: R is chosen
 // by the caller to give every wavefront a run.  Every thread of the workgroup.
 template <int R>
-__device__ __forceinline__ void wg_sort_merge_runs(uint64_t* keys, int n, int K) {
+__device__ __forceinline__ void wg_sort_merge_runs(uint64_t* keys_generic, int n, int K) {
     using WS = WaveSort<R, uint64_t>;
+    const lds_ptr<uint64_t> keys = (lds_ptr<uint64_t>)keys_generic;
     const int tid = threadIdx.x, T = blockDim.x;
     const int lane = tid & (kWave - 1), wave = tid >> 6, nwaves = T >> 6;
     constexpr int kRun = kWave * R;
@@ -394,7 +395,7 @@ __device__ __forceinline__ void wg_sort_merge_runs(uint64_t* keys, int n, int K)
         const int pieces = kept / kRun;
         for (int c = wave; c < nblocks * pieces; c += nwaves) {
             const int blk = c / pieces;
-            uint64_t* piece = keys + (size_t)blk * 2 * L + (size_t)(c - blk * pieces) * kRun;
+            const lds_ptr<uint64_t> piece = keys + blk * 2 * L + (c - blk * pieces) * kRun;
             uint64_t k[R];
 #pragma unroll
             for (int j = 0; j < R; ++j) k[j] = piece[lane * R + j];
@@ -406,8 +407,9 @@ __device__ __forceinline__ void wg_sort_merge_runs(uint64_t* keys, int n, int K)
     }
 }
 
-// n a power of two >= 256.
-__device__ __forceinline__ void wg_sort_merge_topk(uint64_t* keys, int n, int K) {
+// n a power of two >= 256.  Not inlined: three sorting networks that every kernel variant with a
+// stage 2 would otherwise carry a copy of.
+__device__ __noinline__ void wg_sort_merge_topk(uint64_t* keys, int n, int K) {
     const int per_wave = n / (int)(blockDim.x >> 6);      // keys per wavefront if all take part
     if (per_wave <= 128)      wg_sort_merge_runs<2>(keys, n, K);
     else if (per_wave <= 256) wg_sort_merge_runs<4>(keys, n, K);

@@ -111,15 +111,27 @@ def test_plans_for_benchmark_configs_are_fused_single_launch():
             assert "workspace=0" in text
 
 
-def test_few_long_rows_are_split_over_workgroups():
+def test_few_long_rows_are_spread_over_workgroups(monkeypatch):
     # 8 rows of 262144 (the shape of the paper's Table 1) cannot fill 256 CUs one row per
-    # workgroup: rows are cut into segments and the plan asks for a workspace for the partial lists
+    # workgroup.  Such rows are given out in slabs of 32 buckets; the plan asks for a workspace
+    # for the B*K' keys of every row
+    st, text = atk.describe_plan(torch.float32, 8, 262144, 1024, 4, 1024)
+    assert st == atk.OK and text.startswith("slab"), text
+    need = atk.workspace_bytes(atk.OP_APPROX_TOPK, torch.float32, 8, 262144, 1024, 4, 1024)
+    assert re.search(r"grid=8x(\d+)", text).group(1) == "32" and need == 8 * 4 * 1024 * 8
+    # with that route switched off, rows are cut into segments along their length instead
+    monkeypatch.setenv("ATK_SLAB", "0")
     st, text = atk.describe_plan(torch.float32, 8, 262144, 1024, 4, 1024)
     assert st == atk.OK and text.startswith("split"), text
     need = atk.workspace_bytes(atk.OP_APPROX_TOPK, torch.float32, 8, 262144, 1024, 4, 1024)
     nseg = int(re.search(r"grid=\d+x(\d+)", text).group(1))
     assert nseg > 1 and need == 8 * nseg * 4 * 1024 * 8
-    # the split is an optimisation: without a workspace the call is still legal (validation only
+    monkeypatch.delenv("ATK_SLAB")
+    # many rows, short rows or few buckets keep the single fused launch
+    for rows, N, B in [(256, 262144, 1024), (8, 16384, 1024), (8, 262144, 256)]:
+        st, text = atk.describe_plan(torch.float32, rows, N, 64, 4, B)
+        assert st == atk.OK and not text.startswith("slab"), text
+    # both are optimisations: without a workspace the call is still legal (validation only
     # here: rows=0 launches nothing)
     assert call_approx(rows=0, N=262144, K=1024, Kp=4, B=1024, values=None, out_vals=None,
                        out_idx=None) == atk.OK

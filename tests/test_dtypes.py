@@ -2,7 +2,7 @@
 
 CPU part: the oracle's handling of the new element types is pinned against NumPy's own
 conversions and sorts.  GPU part: the HIP path against the oracle, bit for bit, over every
-launch route (fused, shared buckets, split, unfused, exact, batched lists, stage 1 only)."""
+launch route (fused, shared buckets, slab, split, unfused, exact, batched lists, stage 1 only)."""
 import numpy as np
 import pytest
 import torch
@@ -134,6 +134,7 @@ ROUTES = [
     (9, 8192, 40, 6, 16, "fused"),             # several lanes share a bucket
     (5, 4100, 10, 3, 4, "fused"),              # B = 4, N not a multiple of anything large
     (3, 3600, 64, 3, 900, "fused"),            # B not a power of two
+    (8, 262144, 1024, 4, 1024, "slab"),
     (8, 262144, 1024, 4, 1024, "split"),
     (4, 131072, 128, 16, 2048, "unfused"),
     (6, 65536, 256, 32, 256, "fused"),         # long lists: sorted batches
@@ -144,7 +145,9 @@ ROUTES = [
 @pytest.mark.gpu
 @pytest.mark.parametrize("rows,N,K,Kp,B,route", ROUTES)
 @pytest.mark.parametrize("unsigned", [False, True])
-def test_integer_rows_every_route(atk, rows, N, K, Kp, B, route, unsigned):
+def test_integer_rows_every_route(atk, rows, N, K, Kp, B, route, unsigned, monkeypatch):
+    if route == "split":     # the default for so few rows is the slab route
+        monkeypatch.setenv("ATK_SLAB", "0")
     for kind in ("full", "ties", "floor"):
         check(atk, int_rows(rows, N, seed=31, kind=kind, unsigned=unsigned), K, Kp, B, route)
 
@@ -153,6 +156,7 @@ def test_integer_rows_every_route(atk, rows, N, K, Kp, B, route, unsigned):
 @pytest.mark.parametrize("rows,N,K,Kp,B,route", ROUTES)
 def test_half_rows_every_route(atk, rows, N, K, Kp, B, route, monkeypatch):
     if route == "split":     # rows this short are not split by themselves: ask for it
+        monkeypatch.setenv("ATK_SLAB", "0")
         monkeypatch.setenv("ATK_SEGMENTS", "4")
     for kind in ("patterns", "gauss"):
         check(atk, half_rows(rows, N, seed=32, kind=kind), K, Kp, B, route)

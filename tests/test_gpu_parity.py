@@ -243,9 +243,15 @@ def test_zero_rows(atk):
     assert v.shape == (0, 8)
 
 
-def test_largest_fused_candidate_set(atk):
-    # B*K' = 16384 candidates per row: the most the fused kernel keeps in LDS (128 KB of keys)
+def test_largest_fused_candidate_set(atk, monkeypatch):
+    # B*K' = 16384 candidates per row: the most the fused kernel keeps in LDS (128 KB of keys).
+    # With so few rows the default route is the slab one (same candidates, in the finishing
+    # launch's LDS): first that, then the single fused launch
     N, B, Kp, K = 32768, 2048, 8, 2000
+    st, text = atk.describe_plan(torch.float32, 3, N, K, Kp, B)
+    assert st == atk.OK and text.startswith("slab") and "cand=16384" in text, text
+    check_approx(atk, workloads.gaussian(3, N, seed=17), K, Kp, B)
+    monkeypatch.setenv("ATK_SLAB", "0")
     st, text = atk.describe_plan(torch.float32, 3, N, K, Kp, B)
     assert st == atk.OK and text.startswith("fused") and "cand=16384" in text, text
     check_approx(atk, workloads.gaussian(3, N, seed=17), K, Kp, B)
@@ -266,8 +272,49 @@ def test_unfused_path_through_workspace(atk):
     check_approx(atk, xb, K, Kp, B)
 
 
+def test_slab_path_very_few_rows(atk, monkeypatch):
+    # the shape of the paper's Table 1 and its neighbours: every workgroup takes 32 buckets of a
+    # row over all steps, several lanes per bucket; stage 2 runs in a second launch
+    for dtype in (torch.float32, torch.bfloat16, torch.int32):
+        for rows, N in [(8, 262144), (1, 65536), (3, 1048576)]:
+            if dtype == torch.int32:
+                g = torch.Generator().manual_seed(18)
+                x = torch.randint(-1000, 1000, (rows, N), generator=g, dtype=torch.int32)   # dense ties
+            else:
+                x = workloads.gaussian(rows, N, seed=17, dtype=dtype)
+            for B, Kp in [(1024, 4), (4096, 2), (8192, 1), (1024, 6), (1024, 16)]:
+                st, text = atk.describe_plan(dtype, rows, N, 1024, Kp, B)
+                assert st == atk.OK
+                # chosen while the launch stays within 1024 workgroups
+                assert text.startswith("slab") == (rows * (B // 32) <= 1024), text
+                check_approx(atk, x, 1024, Kp, B)
+    z = workloads.heavy_ties(8, 262144, seed=16, symbols=3)
+    check_approx(atk, z, 1024, 4, 1024)
+    # asked for where the planner would not choose it: few buckets, bucket counts that are only
+    # a multiple of 32, rows that one lane per bucket would cover in a handful of steps
+    monkeypatch.setenv("ATK_SLAB", "2")
+    for rows, N, B, Kp, K in [(5, 16384, 64, 4, 200), (2, 96 * 64, 96, 3, 100), (9, 32768, 512, 2, 64),
+                              (4, 8192, 256, 8, 256), (3, 160 * 24, 160, 2, 300)]:
+        st, text = atk.describe_plan(torch.float32, rows, N, K, Kp, B)
+        assert st == atk.OK and text.startswith("slab"), text
+        check_approx(atk, workloads.gaussian(rows, N, seed=19), K, Kp, B)
+        check_approx(atk, workloads.heavy_ties(rows, N, seed=20, symbols=5), K, Kp, B)
+    monkeypatch.delenv("ATK_SLAB")
+    # a workspace that is too small: the call falls back to a route that needs none
+    zd = z.to(DEV)
+    small = torch.empty(1024, dtype=torch.uint8, device=DEV)
+    v1, i1 = atk.approx_topk(zd, 1024, 4, 1024)
+    out = (torch.empty_like(v1), torch.empty_like(i1))
+    st = atk.lib.atk_approx_topk(zd.data_ptr(), 0, 8, 262144, 262144, 1024, 4, 1024,
+                                 out[0].data_ptr(), out[1].data_ptr(), small.data_ptr(), 1024, None)
+    torch.cuda.synchronize()
+    assert st == atk.OK and torch.equal(out[1], i1) and torch.equal(out[0], v1)
+
+
 def test_split_path_few_long_rows(atk, monkeypatch):
-    # the shape of the paper's Table 1: 8 rows x 262144, K=1024; rows are cut into segments
+    # the same shape with rows cut into segments along their length (the route for rows that
+    # are few but not very few)
+    monkeypatch.setenv("ATK_SLAB", "0")
     for dtype in (torch.float32, torch.bfloat16):
         x = workloads.gaussian(8, 262144, seed=15, dtype=dtype)
         if dtype == torch.bfloat16:     # half the bytes: the planner would not split by itself
@@ -393,16 +440,20 @@ def test_full_size_sampled_rows_and_properties(atk, name):
     assert np.array_equal(bits(gv)[sel], host_bits(ov)), name
 
 
-def test_hip_graph_capture_and_replay(atk):
+def test_hip_graph_capture_and_replay(atk, monkeypatch):
     # The library enqueues on the caller's stream, allocates nothing and never synchronises, so a
     # call can be captured into a HIP graph.  Every replay (with eager work and synchronisation
     # in between, and new contents in the captured input buffer) must equal the eager result.
     cases = [
-        ("fused", lambda x, out, ws: atk.approx_topk(x, 128, 4, 1024, out=out, workspace=ws), (32, 65536)),
+        ("fused", lambda x, out, ws: atk.approx_topk(x, 128, 4, 1024, out=out, workspace=ws), (64, 65536)),
+        ("slab", lambda x, out, ws: atk.approx_topk(x, 1024, 4, 1024, out=out, workspace=ws), (8, 262144)),
         ("split", lambda x, out, ws: atk.approx_topk(x, 1024, 4, 1024, out=out, workspace=ws), (8, 262144)),
     ]
     for name, call, (rows, N) in cases:
         K = 128 if name == "fused" else 1024
+        if name == "split":
+            monkeypatch.setenv("ATK_SLAB", "0")
+        assert atk.describe_plan(torch.float32, rows, N, K, 4, 1024)[1].startswith(name)
         static_in = workloads.gaussian(rows, N, seed=70).to(DEV)
         ws = torch.empty(64 << 20, dtype=torch.uint8, device=DEV)
         out = (torch.empty((rows, K), device=DEV), torch.empty((rows, K), dtype=torch.int32, device=DEV))
@@ -437,7 +488,7 @@ def test_random_bit_patterns_through_every_stage2(atk):
         sign = (rng.integers(0, 2, (rows, N), dtype=np.int64) << 31).astype(np.uint32)
         return torch.from_numpy((mag | sign).view(np.float32))
     x = patterns(8, 262144)
-    check_approx(atk, x, 1024, 4, 1024)          # split route, finish kernel
+    check_approx(atk, x, 1024, 4, 1024)          # slab route, finish kernel
     check_approx(atk, x, 1024, 2, 4096)          # fused, one row per workgroup
     check_exact(atk, x, 2048)
     y = patterns(64, 16384)
