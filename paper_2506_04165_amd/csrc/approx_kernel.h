@@ -376,14 +376,23 @@ struct ApproxKernel {
         // every slot takes one element per step: after KP steps no list entry is empty
         constexpr bool TWO_PHASE = REP == 0 && KP > 1;
         if constexpr (TWO_PHASE) {
-            const int fill_end = min(s_end, s + KP);
-            for (; s < fill_end; ++s) {
+            // the first KP steps (fewer on a short walk), loaded together like any other batch
+            const int nfill = min(KP, s_end - s);                  // uniform
+            if (nfill > 0) {
                 const buffer_rsrc rs = make_rsrc(wg_base + (size_t)s * step_bytes);
+                vec_t buf[KP][R];
 #pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    vec_t x = VL::load(rs, lane_off[r], 0);
-                    consume<false>(L, x, r, s);
-                }
+                for (int u = 0; u < KP; ++u)
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+                        buf[u][r] = VL::load(rs, lane_off[r], (uint32_t)(u < nfill ? u : 0) * step_bytes);
+#pragma unroll
+                for (int u = 0; u < KP; ++u)
+                    if (u < nfill) {
+#pragma unroll
+                        for (int r = 0; r < R; ++r) consume<false>(L, buf[u][r], r, s + u);
+                    }
+                s += nfill;
             }
         }
         for (; s + U <= s_end; s += U) {
@@ -400,13 +409,24 @@ struct ApproxKernel {
                 for (int r = 0; r < R; ++r)
                     consume<TWO_PHASE>(L, buf[u][r], r, s + u);
         }
-        for (; s < s_end; ++s) {
+        if (s < s_end) {
+            // the last, short batch: loads of the steps that do not exist repeat the first one
+            // and are not consumed (a step-by-step tail would pay a memory latency per step)
+            const int nlast = s_end - s;                           // uniform, 1 .. U-1
             const buffer_rsrc rs = make_rsrc(wg_base + (size_t)s * step_bytes);
+            vec_t buf[U][R];
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
-                vec_t x = VL::load(rs, lane_off[r], 0);
-                consume<TWO_PHASE>(L, x, r, s);
-            }
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+                    buf[u][r] = VL::load(rs, lane_off[r], (uint32_t)(u < nlast ? u : 0) * step_bytes);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (u < nlast) {
+#pragma unroll
+                    for (int r = 0; r < R; ++r) consume<TWO_PHASE>(L, buf[u][r], r, s + u);
+                }
+            s = s_end;
         }
         }
 
