@@ -380,12 +380,14 @@ struct ApproxKernel {
             const int nfill = min(KP, s_end - s);                  // uniform
             if (nfill > 0) {
                 const buffer_rsrc rs = make_rsrc(wg_base + (size_t)s * step_bytes);
-                vec_t buf[KP][R];
+                vec_t buf[KP][R] = {};
 #pragma unroll
                 for (int u = 0; u < KP; ++u)
+                    if (u < nfill) {
 #pragma unroll
-                    for (int r = 0; r < R; ++r)
-                        buf[u][r] = VL::load(rs, lane_off[r], (uint32_t)(u < nfill ? u : 0) * step_bytes);
+                        for (int r = 0; r < R; ++r)
+                            buf[u][r] = VL::load(rs, lane_off[r], (uint32_t)u * step_bytes);
+                    }
 #pragma unroll
                 for (int u = 0; u < KP; ++u)
                     if (u < nfill) {
@@ -410,16 +412,18 @@ struct ApproxKernel {
                     consume<TWO_PHASE>(L, buf[u][r], r, s + u);
         }
         if (s < s_end) {
-            // the last, short batch: loads of the steps that do not exist repeat the first one
-            // and are not consumed (a step-by-step tail would pay a memory latency per step)
-            const int nlast = s_end - s;                           // uniform, 1 .. U-1
+            // the last, short batch: its loads are issued together as well (a step-by-step tail
+            // would pay a memory latency per step); the count is uniform, so the tests are scalar
+            const int nlast = s_end - s;                           // 1 .. U-1
             const buffer_rsrc rs = make_rsrc(wg_base + (size_t)s * step_bytes);
-            vec_t buf[U][R];
+            vec_t buf[U][R] = {};
 #pragma unroll
             for (int u = 0; u < U; ++u)
+                if (u < nlast) {
 #pragma unroll
-                for (int r = 0; r < R; ++r)
-                    buf[u][r] = VL::load(rs, lane_off[r], (uint32_t)(u < nlast ? u : 0) * step_bytes);
+                    for (int r = 0; r < R; ++r)
+                        buf[u][r] = VL::load(rs, lane_off[r], (uint32_t)u * step_bytes);
+                }
 #pragma unroll
             for (int u = 0; u < U; ++u)
                 if (u < nlast) {
