@@ -52,7 +52,7 @@ typedef enum atk_dtype { ATK_F32 = 0, ATK_BF16 = 1, ATK_F16 = 2, ATK_I32 = 3, AT
 
 typedef enum atk_status {
     ATK_OK = 0,
-    /* null pointer, rows < 0, N <= 0, N >= 2^31, row_stride < N, B < 1, B does not divide N
+    /* null pointer, rows < 0, N <= 0, N > 2^31 - 65536 (ATK_MAX_N), row_stride < N, B < 1, B does not divide N
      * (Section 6.3 requires equal buckets), K' < 1, K' > K (abstract: 1 <= K' <= K), K' > N/B,
      * K > B*K', K > N, K < 1, misaligned pointer */
     ATK_INVALID_ARG = 1,
@@ -62,6 +62,9 @@ typedef enum atk_status {
     /* a HIP call failed; atk_last_hip_error() holds its text */
     ATK_HIP_ERROR = 4
 } atk_status;
+
+/* Longest supported row, in elements. */
+#define ATK_MAX_N 2147418112LL
 
 typedef enum atk_op { ATK_OP_APPROX_TOPK = 0, ATK_OP_TOPK = 1, ATK_OP_STAGE1 = 2 } atk_op;
 

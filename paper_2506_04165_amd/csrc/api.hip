@@ -48,6 +48,9 @@ static const Variant* find_variant(int dtype, int KP, int NL, bool packed_ok, Pr
 constexpr int kMaxListLen = 32;          // longest K'-list kept in registers
 constexpr int kMaxEntriesPerLane = 32;   // V*R*KP
 constexpr int kMaxLanes = 1024;
+// Longest row.  Kernel loops step 32-bit element counters by up to a chunk (32768) past the end
+// before they test them, so the last 65536 values of the int range stay out.
+constexpr int64_t kMaxN = 0x7fffffffLL - 0xffff;
 constexpr size_t kLdsBudget = 144 * 1024; // dynamic LDS per workgroup (the CU has 160 KB)
 constexpr int kExactCap = 4096;          // exact kernel: LDS key buffer
 constexpr int kExactMaxK = 2048;
@@ -88,7 +91,7 @@ static int env_int(const char* name, int fallback) {
 static int validate_common(const void* values, int dtype, int64_t rows, int64_t N,
                            int64_t row_stride) {
     if (kernel_dtype(dtype) < 0) return ATK_UNSUPPORTED;
-    if (rows < 0 || rows > 0x7fffffff || N <= 0 || N > 0x7fffffffLL || row_stride < N)
+    if (rows < 0 || rows > 0x7fffffff || N <= 0 || N > kMaxN || row_stride < N)
         return ATK_INVALID_ARG;
     if (rows > 0 && !values) return ATK_INVALID_ARG;
     if ((uintptr_t)values % elem_size(dtype)) return ATK_INVALID_ARG;
@@ -402,7 +405,7 @@ constexpr int kMipsMinSegmentSteps = 64;     // shorter walks only refill lists
 
 MipsPlan make_mips_plan(int dtype, int64_t Q, int64_t N, int64_t D, int K, int Kprime, int B) {
     MipsPlan pl;
-    if (Q < 0 || N <= 0 || N > 0x7fffffffLL || D <= 0) { pl.status = ATK_INVALID_ARG; return pl; }
+    if (Q < 0 || N <= 0 || N > kMaxN || D <= 0) { pl.status = ATK_INVALID_ARG; return pl; }
     if ((pl.status = validate_method(N, K, Kprime, B))) return pl;
     if ((dtype != ATK_BF16 && dtype != ATK_F16) || (D != 64 && D != 128 && D != 256) || B % kMipsSlab || Kprime > 4 ||
         (int64_t)B * Kprime > 16384 || Q > 0x7fffffffLL / 2) {
@@ -557,7 +560,7 @@ int atk_approx_topk_stage1(const void* values, int dtype, int64_t rows, int64_t 
 size_t atk_workspace_bytes(int op, int dtype, int64_t rows, int64_t N, int K, int Kprime, int B) {
     dtype = kernel_dtype(dtype);
     if (dtype < 0) return SIZE_MAX;
-    if (rows < 0 || N <= 0 || N > 0x7fffffffLL) return SIZE_MAX;
+    if (rows < 0 || N <= 0 || N > kMaxN) return SIZE_MAX;
     if (op == ATK_OP_TOPK) return (K < 1 || K > N) ? SIZE_MAX : 0;
     if (op == ATK_OP_STAGE1) return validate_method(N, Kprime, Kprime, B) ? SIZE_MAX : 0;
     if (op != ATK_OP_APPROX_TOPK) return SIZE_MAX;
@@ -639,7 +642,7 @@ int atk_describe_plan(int dtype, int64_t rows, int64_t N, int K, int Kprime, int
     buf[0] = 0;
     dtype = kernel_dtype(dtype);
     if (dtype < 0) return ATK_UNSUPPORTED;
-    if (rows < 0 || N <= 0 || N > 0x7fffffffLL) return ATK_INVALID_ARG;
+    if (rows < 0 || N <= 0 || N > kMaxN) return ATK_INVALID_ARG;
     int rc = validate_method(N, K, Kprime, B);
     if (rc) return rc;
     Plan pl = make_plan(nullptr, dtype, rows, N, N, K, Kprime, B, false);

@@ -20,7 +20,7 @@
 extern "C" int atk_select_params(int64_t N, int K, double recall_target, int max_kprime,
                                  int bucket_multiple, int* Kprime_out, int* B_out,
                                  double* expected_recall_out) {
-    if (N <= 0 || N > 0x7fffffffLL || K < 1 || K > N || !Kprime_out || !B_out) return ATK_INVALID_ARG;
+    if (N <= 0 || N > 0x7fffffffLL - 0xffff || K < 1 || K > N || !Kprime_out || !B_out) return ATK_INVALID_ARG;
     if (!(recall_target > 0.0) || recall_target > 1.0 || max_kprime < 1 || bucket_multiple < 1)
         return ATK_INVALID_ARG;
 
@@ -72,7 +72,7 @@ extern "C" int atk_select_params(int64_t N, int K, double recall_target, int max
 // Returns ATK_UNSUPPORTED when no legal configuration reaches the target.
 extern "C" int atk_mips_select_params(int64_t N, int K, double recall_target, int* Kprime_out,
                                       int* B_out, double* expected_recall_out) {
-    if (N <= 0 || N > 0x7fffffffLL || K < 1 || K > N || !Kprime_out || !B_out) return ATK_INVALID_ARG;
+    if (N <= 0 || N > 0x7fffffffLL - 0xffff || K < 1 || K > N || !Kprime_out || !B_out) return ATK_INVALID_ARG;
     if (!(recall_target > 0.0) || recall_target > 1.0) return ATK_INVALID_ARG;
     std::vector<int64_t> buckets;
     for (int64_t d = 1; d * d <= N; ++d) {

@@ -113,7 +113,7 @@ __global__ void __launch_bounds__(1024) topk_exact_kernel(TopkParams p) {
                 uint32_t digit, above, count;
                 hist_find_digit(hist, ctl, p.K, digit, above, count);
                 dmin = digit;                    // K keys at or above this digit exist already
-                next_update *= 2;
+                next_update = next_update <= 0x3fffffff ? next_update * 2 : 0x7fffffff;
             }
         }
         uint32_t digit, above, count;

@@ -48,7 +48,7 @@ def call_approx(values=FAKE, dtype=0, rows=4, N=4096, stride=None, K=32, Kp=4, B
 
 @pytest.mark.parametrize("kw", [
     dict(values=None), dict(out_vals=None), dict(out_idx=None),
-    dict(rows=-1), dict(N=0), dict(N=2**31), dict(stride=100),
+    dict(rows=-1), dict(N=0), dict(N=2**31), dict(N=2**31 - 65536 + 64), dict(stride=100),
     dict(B=0), dict(B=63),                 # B must divide N
     dict(Kp=0), dict(Kp=33),               # 1 <= K' <= K
     dict(B=1024, Kp=5, K=32),              # K' > N/B
@@ -59,6 +59,14 @@ def call_approx(values=FAKE, dtype=0, rows=4, N=4096, stride=None, K=32, Kp=4, B
 ])
 def test_invalid_arguments(kw):
     assert call_approx(**kw) == atk.INVALID_ARG
+
+
+def test_longest_row_is_accepted():
+    # 2^31 - 65536 elements (ATK_MAX_N); rows=0 validates and launches nothing
+    assert call_approx(rows=0, N=2**31 - 65536, K=32, Kp=4, B=64, values=None, out_vals=None,
+                       out_idx=None) == atk.OK
+    st, text = atk.describe_plan(torch.float32, 1, 2**31 - 65536, 64, 1, 8192)
+    assert st == atk.OK, text
 
 
 def test_unsupported_arguments():

@@ -339,6 +339,51 @@ def test_split_path_few_long_rows(atk, monkeypatch):
     assert st == atk.OK and torch.equal(out[1], i1) and torch.equal(out[0], v1)
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_longest_row(atk, dtype):
+    # one row of the greatest supported length, 2^31 - 65536 elements.  The oracle is not run
+    # on 8 GB: the row is a background of negative values with 300 distinct positive values
+    # planted at seeded positions (first and last elements, bucket edges, the far end), so the
+    # expected output follows from the planted set alone: per bucket its K' greatest planted
+    # values survive, the K greatest survivors come out in order; the exact Top-K returns the K
+    # greatest planted values.
+    N, B, Kp, K = 2 ** 31 - 65536, 8192, 1, 64
+    x = torch.empty(N, dtype=dtype, device=DEV)
+    chunk = 1 << 26
+    for start in range(0, N, chunk):
+        n = torch.arange(start, min(N, start + chunk), device=DEV, dtype=torch.int64)
+        x[start:start + n.numel()] = (-1.0 - (n % 977).to(torch.float32) * 1e-3).to(dtype)
+        del n
+    rng = np.random.default_rng(5)
+    pos = np.unique(np.concatenate([[0, 1, B - 1, B, N - 1, N - B, N - B - 1, 2 ** 30, 2 ** 30 - 1],
+                                    rng.integers(0, N, 291), rng.integers(N - 100000, N, 20)]))
+    order = rng.permutation(len(pos))
+    if dtype == torch.float32:
+        vals = (1.0 + order * 0.01).astype(np.float32)
+    else:       # distinct bf16 values: consecutive bit patterns from 1.0 up
+        vals = ((0x3F80 + order).astype(np.uint32) << 16).view(np.float32)
+    x[torch.from_numpy(pos).to(DEV)] = torch.from_numpy(vals).to(DEV).to(dtype)
+    # expected survivors: the greatest planted value of every bucket that holds one
+    best = {}
+    for p_, v in zip(pos.tolist(), vals.tolist()):
+        b = p_ % B
+        if b not in best or v > best[b][0]:
+            best[b] = (v, p_)
+    surv = sorted(best.values(), key=lambda t: -t[0])[:K]
+    xd = x.view(1, N)
+    print("longest row: approximate", flush=True)
+    gv, gi = atk.approx_topk(xd, K, Kp, B)
+    torch.cuda.synchronize()
+    assert gi.cpu().numpy()[0].tolist() == [p_ for _, p_ in surv]
+    assert gv.float().cpu().numpy()[0].tolist() == [v for v, _ in surv]
+    print("longest row: exact", flush=True)
+    ev, ei = atk.topk(xd, K)
+    torch.cuda.synchronize()
+    top = sorted(zip(vals.tolist(), pos.tolist()), key=lambda t: -t[0])[:K]
+    assert ei.cpu().numpy()[0].tolist() == [p_ for _, p_ in top]
+    assert ev.float().cpu().numpy()[0].tolist() == [v for v, _ in top]
+
+
 def test_exact_topk_sizes(atk):
     for N, K in [(1, 1), (63, 63), (64, 1), (1000, 1000), (5000, 2048), (100000, 7), (300000, 1500)]:
         x = workloads.gaussian(3, N, seed=400 + N % 97)
