@@ -339,6 +339,16 @@ def test_split_path_few_long_rows(atk, monkeypatch):
     assert st == atk.OK and torch.equal(out[1], i1) and torch.equal(out[0], v1)
 
 
+@pytest.mark.parametrize("rows,N,B,Kp,K", [(300001, 32, 4, 2, 7), (1000003, 8, 8, 1, 3), (65537, 1, 1, 1, 1)])
+def test_very_many_tiny_rows(atk, rows, N, B, Kp, K):
+    # the other extreme: rows far shorter than a wavefront, in a number that is not a multiple of
+    # anything (many rows per workgroup, a ragged last workgroup)
+    x = workloads.gaussian(rows, N, seed=21)
+    check_approx(atk, x, K, Kp, B)
+    check_exact(atk, x, K)
+    check_approx(atk, workloads.gaussian(rows, N, seed=22, dtype=torch.bfloat16), K, Kp, B)
+
+
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_longest_row(atk, dtype):
     # one row of the greatest supported length, 2^31 - 65536 elements.  The oracle is not run
