@@ -535,6 +535,16 @@ struct ApproxKernel {
                 }
             }
             __syncthreads();
+            if (p.mode == 3 && p.seg <= 16 * p.owners) {
+                // each wavefront holds the lists of 64 / owners buckets, seg / owners keys per
+                // lane: sorted in registers, the final K' keys go straight to memory
+                const int wave = tid >> 6, per_lane = p.seg / p.owners, per_wave = kWave / p.owners;
+                if (row_ok)
+                    wave_merge_bucket_lists_dispatch(
+                        part + (size_t)wave * kWave * per_lane, per_lane, 31 - __clz(p.owners), p.Kprime,
+                        p.part_keys + (int64_t)row * p.Kprime * p.B + b_first + wave * per_wave, p.B);
+                return;
+            }
             lds_bitonic_sort_desc(lds + p.aux_offset, p.rows_per_wg * nb * p.seg, p.seg);
             if (p.mode == 3) {
                 // the slab's final lists, laid out like one segment's partial keys

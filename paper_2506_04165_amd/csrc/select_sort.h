@@ -99,8 +99,9 @@ struct WaveSort {
     // rather than loops: every distance must be a compile-time constant (register indices, DPP
     // patterns), whatever the unroller decides.
     template <int LK>
-    __device__ static __forceinline__ void levels(KeyT (&k)[R], int lane) {
+    __device__ static __forceinline__ void levels(KeyT (&k)[R], int lane, int last_level = LOGN) {
         if constexpr (LK <= LOGN) {
+            if (LK > last_level) return;       // uniform; folds away when the default is used
             constexpr int KK = 1 << LK;
             if constexpr (KK <= R) {
 #pragma unroll
@@ -116,13 +117,15 @@ struct WaveSort {
                 for (int j = 0; j < R; ++j) k[j] = pick(k[j], recv[j], lower);
             }
             steps_down<LK - 2>(k, lane);
-            levels<LK + 1>(k, lane);
+            levels<LK + 1>(k, lane, last_level);
         }
     }
 
     // Element e = lane*R + j lives in k[j] of `lane`.  After the call e is the rank: k[j] of
     // lane l is the (l*R + j)-th greatest key.
     __device__ static void sort(KeyT (&k)[R]) { levels<1>(k, __lane_id()); }
+    // The first log_len levels only: every aligned block of 2^log_len elements ends up sorted.
+    __device__ static void sort_blocks(KeyT (&k)[R], int log_len) { levels<1>(k, __lane_id(), log_len); }
 };
 
 // A pointer known to point into LDS.  The sorting tails are not inlined and receive generic
@@ -229,6 +232,38 @@ __device__ __noinline__ void wave_sort32_dispatch(uint32_t* keys, int n, int K, 
     else if (n <= 256) wave_sort32_from_lds<DT, 4>(keys, n, K, rowp, out_vals, out_idx, out_base);
     else if (n <= 512) wave_sort32_from_lds<DT, 8>(keys, n, K, rowp, out_vals, out_idx, out_base);
     else               wave_sort32_from_lds<DT, 16>(keys, n, K, rowp, out_vals, out_idx, out_base);
+}
+
+// Slab route of the streaming kernel: the 64*R keys at `keys` (LDS) are the partial lists of
+// 64/m buckets, m*R consecutive keys per bucket (m lanes' worth).  One wavefront sorts every
+// bucket's keys in registers and the first lane of each bucket writes its K' greatest to
+// out[j*B + bucket] (j < K').  No barrier inside: each wavefront works on its own buckets.
+template <int R>
+__device__ __forceinline__ void wave_merge_bucket_lists(const uint64_t* keys_generic, int log_m,
+                                                        int Kprime, uint64_t* out, int B) {
+    const lds_ptr<const uint64_t> keys = (lds_ptr<const uint64_t>)keys_generic;
+    const int lane = __lane_id();
+    uint64_t k[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) k[j] = keys[lane * R + j];
+    WaveSort<R>::sort_blocks(k, WaveSort<R>::LOGR + log_m);
+    if ((lane & ((1 << log_m) - 1)) == 0) {
+#pragma unroll
+        for (int j = 0; j < R; ++j)
+            if (j < Kprime) out[(size_t)j * B + (lane >> log_m)] = k[j];
+    }
+}
+// (not inlined: five sorting networks that every streaming kernel variant would carry)
+__device__ __noinline__ bool wave_merge_bucket_lists_dispatch(const uint64_t* keys, int R, int log_m,
+                                                              int Kprime, uint64_t* out, int B) {
+    switch (R) {
+        case 1:  wave_merge_bucket_lists<1>(keys, log_m, Kprime, out, B); return true;
+        case 2:  wave_merge_bucket_lists<2>(keys, log_m, Kprime, out, B); return true;
+        case 4:  wave_merge_bucket_lists<4>(keys, log_m, Kprime, out, B); return true;
+        case 8:  wave_merge_bucket_lists<8>(keys, log_m, Kprime, out, B); return true;
+        case 16: wave_merge_bucket_lists<16>(keys, log_m, Kprime, out, B); return true;
+        default: return false;
+    }
 }
 
 // Walk a finished histogram from the top bin down.  On return (all threads):
