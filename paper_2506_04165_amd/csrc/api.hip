@@ -60,7 +60,7 @@ constexpr int kMaxSegments = 64;
 constexpr size_t kMinSplitBytes = 4u << 20;
 constexpr int kSlabBuckets = 32;         // buckets per workgroup on the slab route
 constexpr size_t kSlabMinRowBytes = 128u << 10;
-constexpr size_t kSlabMaxBytes = 128u << 20;
+constexpr size_t kSlabMaxBytes = 256u << 20;
 
 static thread_local std::string g_last_hip_error;
 
@@ -272,10 +272,12 @@ static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, in
         const Variant* v = find_variant(dtype, KP, 1, false, [](int V) { return V == 1; });
         const size_t in_bytes = (size_t)rows * N * es;
         const size_t ws = (size_t)rows * Kp * B * 8;
-        // measured against the other routes on 1..128 rows of 2^16..2^20 elements: a gain of
-        // 10-45 % while the launch has at most 1024 workgroups and B >= 1024, a loss beyond
-        const bool few = rows * (B / kSlabBuckets) <= 1024 && B >= 1024 && !pl.var->packed() &&
-                         (size_t)N * es >= kSlabMinRowBytes && in_bytes <= kSlabMaxBytes;
+        // measured against the other routes on 1..128 rows of 2^16..2^20 elements (GPU time with
+        // the queue kept full): a gain of 5-55 % inside these limits; beyond them the strided
+        // runs cost more than the extra workgroups bring
+        const bool few = rows <= 64 && rows * (B / kSlabBuckets) <= 2048 && B >= 256 &&
+                         !pl.var->packed() && (size_t)N * es >= kSlabMinRowBytes &&
+                         (size_t)(N / B) * es <= 4096 && in_bytes <= kSlabMaxBytes;
         if (m > 1 && v && v->V == 1 && v->R == 1 && ws <= ws_avail &&
             (env_int("ATK_SLAB", 1) == 2 || few)) {
             pl.var = v;

@@ -135,8 +135,8 @@ def test_few_long_rows_are_spread_over_workgroups(monkeypatch):
     nseg = int(re.search(r"grid=\d+x(\d+)", text).group(1))
     assert nseg > 1 and need == 8 * nseg * 4 * 1024 * 8
     monkeypatch.delenv("ATK_SLAB")
-    # many rows, short rows or few buckets keep the single fused launch
-    for rows, N, B in [(256, 262144, 1024), (8, 16384, 1024), (8, 262144, 256)]:
+    # many rows, short rows, few buckets or very long bucket walks go other ways
+    for rows, N, B in [(256, 262144, 1024), (8, 16384, 1024), (8, 262144, 64), (8, 1048576, 512)]:
         st, text = atk.describe_plan(torch.float32, rows, N, 64, 4, B)
         assert st == atk.OK and not text.startswith("slab"), text
     # both are optimisations: without a workspace the call is still legal (validation only
