@@ -442,13 +442,64 @@ __device__ __forceinline__ void wg_sort_merge_runs(uint64_t* keys_generic, int n
     }
 }
 
-// n a power of two >= 256.  Not inlined: three sorting networks that every kernel variant with a
+// The same result by ranking instead of merging, for at most one run per wavefront: after the
+// runs are sorted, the final position of a key is its position in its own run plus, for every
+// other run, the number of keys there that are greater (a binary search; neighbouring lanes
+// hold neighbouring keys and mostly read the same words).  Keys are distinct (the index is part
+// of them) except for the empty key 0, whose copies all get the same position behind every real
+// key: positions below the number of real keys are written exactly once, and K never exceeds
+// that number.  Three barriers in all, whatever the number of runs.
+template <int R>
+__device__ __forceinline__ void wg_sort_rank_runs(uint64_t* keys_generic, int n, int K) {
+    using WS = WaveSort<R, uint64_t>;
+    const lds_ptr<uint64_t> keys = (lds_ptr<uint64_t>)keys_generic;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1), wave = tid >> 6;
+    constexpr int kRun = kWave * R;
+    const int nruns = n / kRun;                          // <= wavefronts of the workgroup
+    uint64_t k[R];
+    if (wave < nruns) {
+#pragma unroll
+        for (int j = 0; j < R; ++j) k[j] = keys[wave * kRun + lane * R + j];
+        WS::sort(k);
+#pragma unroll
+        for (int j = 0; j < R; ++j) keys[wave * kRun + lane * R + j] = k[j];
+    }
+    __syncthreads();
+    int rank[R];
+    if (wave < nruns) {
+#pragma unroll
+        for (int j = 0; j < R; ++j) rank[j] = lane * R + j;
+        for (int r = 0; r < nruns; ++r) {
+            if (r == wave) continue;
+            const lds_ptr<uint64_t> run = keys + r * kRun;
+#pragma unroll
+            for (int j = 0; j < R; ++j) {
+                int pos = 0;                             // keys of `run` greater than k[j]
+#pragma unroll
+                for (int s = kRun / 2; s >= 1; s >>= 1)
+                    if (run[pos + s - 1] > k[j]) pos += s;
+                if (run[pos] > k[j]) pos += 1;
+                rank[j] += pos;
+            }
+        }
+    }
+    __syncthreads();
+    if (wave < nruns) {
+#pragma unroll
+        for (int j = 0; j < R; ++j)
+            if (rank[j] < K) keys[rank[j]] = k[j];
+    }
+    __syncthreads();
+}
+
+// n a power of two >= 256.  Not inlined: the sorting networks that every kernel variant with a
 // stage 2 would otherwise carry a copy of.
 __device__ __noinline__ void wg_sort_merge_topk(uint64_t* keys, int n, int K) {
     const int per_wave = n / (int)(blockDim.x >> 6);      // keys per wavefront if all take part
-    if (per_wave <= 128)      wg_sort_merge_runs<2>(keys, n, K);
-    else if (per_wave <= 256) wg_sort_merge_runs<4>(keys, n, K);
-    else                      wg_sort_merge_runs<8>(keys, n, K);
+    if (per_wave <= 128)      wg_sort_rank_runs<2>(keys, n, K);
+    else if (per_wave <= 256) wg_sort_rank_runs<4>(keys, n, K);
+    else                      wg_sort_merge_runs<8>(keys, n, K);   // (ranking 8 keys per lane: slower)
 }
 
 // Top-K (descending) of the n keys in LDS `keys` (n a power of two, key 0 = empty, at least K
