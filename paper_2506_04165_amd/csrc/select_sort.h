@@ -6,11 +6,11 @@
 //                    selects, those between lanes fetch the partner's key with a cross-lane
 //                    shuffle.  No LDS traffic, no barriers.
 //   wg_topk_from_lds workgroup-level Top-K of n keys in LDS.  Small inputs go straight to a
-//                    wave sort.  Larger ones are first cut down by radix selection (an LDS
-//                    histogram over the leading value bits finds the digit that holds the K-th
-//                    key; keys above it are certain members, keys inside it candidates) and only
-//                    the members and candidates are sorted.  A full LDS bitonic sort remains
-//                    as the fallback for inputs the selection cannot thin out (heavy ties).
+//                    wave sort.  Larger ones are first cut down by selection (an LDS histogram
+//                    over equal bins of the interval of keys present finds the bin that holds
+//                    the K-th key; keys above it are certain members, keys inside it candidates)
+//                    and only the members and candidates are sorted.  A full LDS bitonic sort
+//                    remains as the fallback.
 #pragma once
 #include "atk_device.h"
 
@@ -18,7 +18,8 @@ namespace atk {
 
 constexpr int kWaveSortMaxR = 16;                       // up to 1024 keys per wavefront
 constexpr int kWaveSortMaxKeys = kWave * kWaveSortMaxR;
-constexpr int kSelectBins = 2048;
+constexpr int kSelectBinBits = 11;
+constexpr int kSelectBins = 1 << kSelectBinBits;
 // LDS scratch wg_topk_from_lds needs next to the keys when n > 256:
 // a compaction buffer of kWaveSortMaxKeys keys (the histogram aliases it) + control words.
 constexpr int kSelectScratchBytes = kWaveSortMaxKeys * 8 + 128;
@@ -337,18 +338,17 @@ __device__ __forceinline__ void for_each_lds_key(const uint64_t* keys, int n, F&
     }
 }
 
-// Histogram pass of the radix selection over keys in LDS: the `bits`-wide digit at `shift` of
-// the keys matching (prefix, mask) is counted, then hist_find_digit answers.
-__device__ __forceinline__ void lds_select_digit(const uint64_t* keys, int n, uint64_t prefix,
-                                                 uint64_t mask, int shift, int bits, int need,
-                                                 uint32_t* hist, uint32_t* ctl,
-                                                 uint32_t& digit, uint32_t& above, uint32_t& count) {
+// Histogram pass of the selection over keys in LDS: the keys inside [klo, khi] are counted in
+// bins of 2^shift consecutive keys starting at klo (the caller picks shift so that the interval
+// spans at most kSelectBins bins), then hist_find_digit answers.
+__device__ __forceinline__ void lds_select_bin(const uint64_t* keys, int n, uint64_t klo, uint64_t khi,
+                                               int shift, int need, uint32_t* hist, uint32_t* ctl,
+                                               uint32_t& digit, uint32_t& above, uint32_t& count) {
     const int tid = threadIdx.x, T = blockDim.x;
-    const uint32_t dmask = (1u << bits) - 1u;
     for (int i = tid; i < kSelectBins; i += T) hist[i] = 0;
     __syncthreads();
     for_each_lds_key(keys, n, [&](uint64_t key) {
-        if (key != 0 && (key & mask) == prefix) atomicAdd(&hist[(uint32_t)(key >> shift) & dmask], 1u);
+        if (key >= klo && key <= khi) atomicAdd(&hist[(uint32_t)((key - klo) >> shift)], 1u);
     });
     hist_find_digit(hist, ctl, need, digit, above, count);
 }
@@ -536,8 +536,11 @@ __device__ __forceinline__ void wg_topk_from_lds(uint64_t* keys, int n, int K, v
         uint32_t* ctl = (uint32_t*)((char*)scratch + kWaveSortMaxKeys * 8);
         // The keys are the survivors of a first selection and sit in a narrow band of values:
         // digits taken from fixed bit positions would put most of them into one bin, pass after
-        // pass.  So the band is measured first (greatest and least value present); the bits all
-        // keys share become the prefix and the first digit starts at the highest bit that varies.
+        // pass (and a band that straddles a power of two shares no leading bits at all).  So the
+        // band is measured first (greatest and least value present) and every pass cuts the
+        // interval of keys that can still hold the K-th one into equal bins, 2048 at most: keys
+        // are compared as 64-bit integers, value word first, so the bins are intervals of values
+        // and, inside one value, of indices (ties resolve toward the lowest index).
         const int lane = tid & (kWave - 1);
         if (tid == 0) { ctl[20] = 0u; ctl[21] = 0xffffffffu; }
         __syncthreads();
@@ -556,36 +559,33 @@ __device__ __forceinline__ void wg_topk_from_lds(uint64_t* keys, int n, int K, v
         if (lane == 0) { atomicMax(&ctl[20], vhi); atomicMin(&ctl[21], vlo); }
         __syncthreads();
         vhi = ctl[20]; vlo = ctl[21];
-        const uint32_t differ = vhi ^ vlo;
-        const int varying = differ ? 32 - __clz((int)differ) : 0;       // low value bits that vary
-        uint64_t prefix = varying >= 32 ? 0ull : (uint64_t)((vhi >> varying) << varying) << 32;
-        uint64_t mask = varying >= 32 ? 0ull : ~0ull << (32 + varying);
+        // every real key lies in [klo, khi] (a real key is never 0: its low word is ~index)
+        uint64_t klo = ((uint64_t)vlo << 32) | 1ull, khi = ((uint64_t)vhi << 32) | 0xffffffffull;
         int need = K, certain = 0;
         bool fits = false;
-        // value bits first, eleven at a time down to the index half, then -- only when ties leave
-        // too many candidates -- the index bits, so that the lowest indices win
-        int top = 32 + varying;                                          // bits below `top` are open
-        for (int pass = 0; top > 0 && !fits; ++pass) {
-            const int width = top > 32 ? min(11, top - 32) : min(11, top);
-            const int shift = top - width;
+        for (int pass = 0; !fits; ++pass) {
+            const uint64_t span = khi - klo;
+            const int span_bits = span ? 64 - __clzll((long long)span) : 0;
+            const int shift = span_bits > kSelectBinBits ? span_bits - kSelectBinBits : 0;
             uint32_t digit, above, count;
-            lds_select_digit(keys, n, prefix, mask, shift, width, need, hist, ctl, digit, above, count);
+            lds_select_bin(keys, n, klo, khi, shift, need, hist, ctl, digit, above, count);
             certain += (int)above;
             need -= (int)above;
-            prefix |= (uint64_t)digit << shift;
-            mask |= (uint64_t)((1u << width) - 1u) << shift;
-            top = shift;
-            // stop when members + candidates fit one sort; prefer a sort of at most 2K keys
+            klo += (uint64_t)digit << shift;
+            const uint64_t bin_span = (1ull << shift) - 1ull;          // (klo + bin_span may wrap)
+            if (khi - klo > bin_span) khi = klo + bin_span;
+            // stop when members + candidates fit one sort; prefer a sort of at most 2K keys.
+            // With shift == 0 a bin is one key, so the loop ends there at the latest.
             fits = certain + (int)count <= kWaveSortMaxKeys &&
-                   (certain + (int)count <= 2 * K + 64 || pass >= 2);
+                   (certain + (int)count <= 2 * K + 64 || pass >= 2 || shift == 0);
             if (!fits && (int)count <= kSideSortKeys) {
-                // The bin that holds the K-th key is small: rather than take more digits, sort
-                // its keys in one wavefront and read the K-th key off; what remains is "every
-                // key at or above it", exactly K of them.
+                // The bin that holds the K-th key is small: rather than cut it again, sort its
+                // keys in one wavefront and read the K-th key off; what remains is "every key
+                // at or above it", exactly K of them.
                 if (tid == 0) ctl[3] = 0;
                 __syncthreads();
                 for_each_lds_key(keys, n, [&](uint64_t key) {
-                    if (key != 0 && (key & mask) == prefix) {
+                    if (key >= klo && key <= khi) {
                         const uint32_t slot = atomicAdd(&ctl[3], 1u);
                         if (slot < (uint32_t)kSideSortKeys) buf[slot] = key;
                     }
@@ -599,23 +599,29 @@ __device__ __forceinline__ void wg_topk_from_lds(uint64_t* keys, int n, int K, v
                         const int i = j * kWave + lane;
                         k[j] = i < (int)count ? buf[i] : 0;
                     }
-                    WaveSort<RS>::sort(k);
+                    if (count <= (uint32_t)kWave) {      // usually: a handful of keys
+                        uint64_t one[1] = {k[0]};
+                        WaveSort<1>::sort(one);
+                        buf[lane] = one[0];
+                    } else {
+                        WaveSort<RS>::sort(k);
 #pragma unroll
-                    for (int j = 0; j < RS; ++j) buf[lane * RS + j] = k[j];
+                        for (int j = 0; j < RS; ++j) buf[lane * RS + j] = k[j];
+                    }
                 }
                 __syncthreads();
-                prefix = buf[need - 1];
-                mask = ~0ull;
+                klo = buf[need - 1];
                 fits = true;
                 __syncthreads();          // buf is filled again below
             }
+            if (shift == 0 && !fits) break;              // cannot happen (see above); ends the loop
         }
         if (fits) {
             if (tid == 0) ctl[3] = 0;
             __syncthreads();
             // certain members and candidates -> buf (the histogram is dead by now)
             for_each_lds_key(keys, n, [&](uint64_t key) {
-                if (key != 0 && (key & mask) >= prefix) {
+                if (key >= klo) {
                     const uint32_t slot = atomicAdd(&ctl[3], 1u);
                     if (slot < (uint32_t)kWaveSortMaxKeys) buf[slot] = key;
                 }
