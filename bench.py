@@ -304,6 +304,8 @@ def main():
     ap.add_argument("--headline-only", action="store_true", help="skip the other configurations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mips", action="store_true", help="skip the matmul-fused section")
+    ap.add_argument("--table1-only", action="store_true",
+                    help="run only the Table 1 shape (8 x 262144, K=1024) and print it (for profiling)")
     ap.add_argument("--mips-only", action="store_true",
                     help="run only the matmul-fused section and print it (for profiling that kernel)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -332,6 +334,9 @@ def main():
                           "bytes_written_per_launch": nbytes}))
         return
 
+    if args.table1_only:
+        print(json.dumps({"table1_shape": bench_table1_shape()}))
+        return
     if args.mips_only:
         print(json.dumps({"mips_fused": bench_mips_fused(max(10, args.steps // 5), max(5, args.warmup // 10))}))
         return
