@@ -62,6 +62,44 @@ def test_kprime1_identity_and_bound(N, B, K):
     assert oracle.recall_lower_bound_k1(N, B, K) <= 1.0
 
 
+# Hand-evaluated points of 1 - (K/2)(1/B - 1/N) (last line of the proof of Theorem 1), written as
+# exact binary fractions so that a dropped 1/2, a flipped sign of 1/N or swapped B and N fails:
+#   (4096, 64, 32):      1 - 16 (64/4096 - 1/4096)        = 1 - 1008/4096     = 0.75390625
+#   (262144, 8192, 1024): 1 - 512 (32/262144 - 1/262144)  = 1 - 15872/262144  = 0.939453125
+#   (1024, 4, 2):        1 - 1 (256/1024 - 1/1024)        = 1 - 255/1024      = 0.7509765625
+#   (65536, 256, 256):   1 - 128 (256/65536 - 1/65536)    = 1 - 32640/65536   = 0.501953125
+@pytest.mark.parametrize("N,B,K,want", [(4096, 64, 32, 0.75390625), (262144, 8192, 1024, 0.939453125),
+                                        (1024, 4, 2, 0.7509765625), (65536, 256, 256, 0.501953125)])
+def test_kprime1_bound_at_hand_evaluated_points(N, B, K, want):
+    assert oracle.recall_lower_bound_k1(N, B, K) == pytest.approx(want, abs=1e-15)
+    # and the bound really lies below the exact value there
+    assert oracle.expected_recall(N, B, K, 1) >= want
+
+
+# Hand-evaluated points of B = K / (2 (1 - r + K/(2N))) (Theorem 1):
+#   N=4096, K=32, r=0.75390625:  1 - r = 1008/4096, K/2N = 16/4096, sum = 1024/4096 = 1/4, B = 32/(2/4)   = 64
+#   N=1024, K=2,  r=0.7509765625: 255/1024 + 1/1024 = 1/4,                                 B = 2/(2/4)    = 4
+#   N=262144, K=1024, r=0.939453125: 15872/262144 + 512/262144 = 1/16,                     B = 1024/(2/16) = 8192
+#   N=1000, K=100, r=0.9:  0.1 + 0.05 = 0.15,                                              B = 100/0.3    = 333.333...
+@pytest.mark.parametrize("N,K,r,want", [(4096, 32, 0.75390625, 64.0), (1024, 2, 0.7509765625, 4.0),
+                                        (262144, 1024, 0.939453125, 8192.0), (1000, 100, 0.9, 1000.0 / 3.0)])
+def test_bucket_formula_at_hand_evaluated_points(N, K, r, want):
+    assert oracle.buckets_for_recall_k1(N, K, r) == pytest.approx(want, rel=1e-13)
+
+
+@pytest.mark.parametrize("N,K,r", [(262144, 1024, 0.95), (262144, 1024, 0.99), (1048576, 128, 0.98),
+                                   (14336, 287, 0.9), (60, 7, 0.5)])
+def test_bucket_formula_inverts_the_bound(N, K, r):
+    # plugging the formula's B (a real number) back into the bound returns the target exactly:
+    # the two functions are inverse to each other in B <-> r
+    b = oracle.buckets_for_recall_k1(N, K, r)
+    assert 1.0 - (K / 2.0) * (1.0 / b - 1.0 / N) == pytest.approx(r, abs=1e-12)
+    # through the other function too (it takes B as a number)
+    assert oracle.recall_lower_bound_k1(N, b, K) == pytest.approx(r, abs=1e-12)
+    # r = 1 asks for one bucket per element: B = N
+    assert oracle.buckets_for_recall_k1(N, K, 1.0) == pytest.approx(N, rel=1e-13)
+
+
 @pytest.mark.parametrize("N,K,target", [(262144, 1024, 0.95), (262144, 1024, 0.99),
                                         (1048576, 128, 0.98)])
 def test_bucket_formula_meets_target(N, K, target):
