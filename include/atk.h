@@ -27,13 +27,8 @@
  *     is launched, so every error below can be provoked without a GPU;
  *   - rows == 0 is legal and does nothing.
  *
- * Developer knobs (environment, read at every call; for experiments and tests, not for
- * production): ATK_LANES_PER_ROW=<power of two <= 1024> lanes that share one row,
- * ATK_SEGMENTS=<n> force n row segments on the split route, ATK_SLAB=0/2 never / whenever
- * possible give workgroups slabs of 32 buckets (few-row route), ATK_NO_PACKED=1 / ATK_NO_SUBWAVE=1
- * switch the packed-key / several-rows-per-wavefront variants off, ATK_BATCH_MIN_KP=<k> list
- * length from which sorted batches are used, ATK_MIPS_SEGMENTS=<n> segments of the database walk
- * in atk_mips_approx_topk.  Results never depend on them.
+ * Developer options (launch geometry, for experiments and tests; results never depend on them):
+ * see atk_set_option.  No product call reads the environment.
  */
 #ifndef ATK_H_
 #define ATK_H_
@@ -81,8 +76,11 @@ typedef enum atk_op { ATK_OP_APPROX_TOPK = 0, ATK_OP_TOPK = 1, ATK_OP_STAGE1 = 2
  *              the chip; otherwise survivors, or per-bucket keys of rows that several
  *              workgroups share, go through this buffer and a second launch finishes.  A
  *              buffer that is too small for the shared-row routes only switches them off)
- * ATK_UNSUPPORTED: K' > 32 unless K' == K (then the exact kernel runs); more than 16384 list
- * entries per row in the stage-1 launch; K > 2048 on the exact and unfused routes.
+ *              More than 16384 survivors per row (any B): stage 1 writes them to the workspace,
+ *              rows cut along the bucket axis over several workgroups, and the exact kernel
+ *              selects among them (the unfused implementation of the paper's appendix).
+ * ATK_UNSUPPORTED: K' > 32 unless K' == K (then the exact kernel runs); K > 8192 on the exact and
+ * unfused routes; B > 2^24.
  */
 int atk_approx_topk(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride,
                     int K, int Kprime, int B, void* out_vals, int32_t* out_idx,
@@ -90,7 +88,7 @@ int atk_approx_topk(const void* values, int dtype, int64_t rows, int64_t N, int6
 
 /*
  * Exact Top-K of every row under the same total order (the comparison system of Section 7; also
- * what the method reduces to at K' = K or B = 1).  Arguments as above.  ATK_UNSUPPORTED: K > 2048.
+ * what the method reduces to at K' = K or B = 1).  Arguments as above.  ATK_UNSUPPORTED: K > 8192.
  */
 int atk_topk(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride, int K,
              void* out_vals, int32_t* out_idx, void* workspace, size_t workspace_bytes,
@@ -131,10 +129,20 @@ int atk_select_params(int64_t N, int K, double recall_target, int max_kprime, in
                       int* Kprime_out, int* B_out, double* expected_recall_out);
 
 /*
- * atk_approx_topk with K' and B chosen by atk_select_params(N, K, recall_target, ceiling for
- * the dtype, 64): the paper's approx_top_k(array, K, recall_target) interface.  The chosen
- * values are reported through Kprime_used / B_used (may be NULL).  Size the workspace with
- * atk_workspace_bytes for the values atk_select_params returns.
+ * The (K', B) that atk_approx_topk_recall uses for this problem: atk_select_params with this
+ * chip's ceilings (K' <= 4 for 32-bit elements, K' <= 8 for 16-bit ones, B a multiple of 64),
+ * restricted to configurations that atk_approx_topk runs for these arguments.  K' = K, B = 1
+ * means the exact Top-K (nothing approximate reaches the target); ATK_UNSUPPORTED if that is
+ * out of range too (K > 8192).  Host only.  expected_recall_out may be NULL.
+ */
+int atk_recall_params(int dtype, int64_t rows, int64_t N, int K, double recall_target, int* Kprime_out,
+                      int* B_out, double* expected_recall_out);
+
+/*
+ * atk_approx_topk with K' and B chosen by atk_recall_params: the paper's
+ * approx_top_k(array, K, recall_target) interface (Section 6.3).  The chosen values are reported
+ * through Kprime_used / B_used (may be NULL).  Size the workspace with atk_workspace_bytes for
+ * the values atk_recall_params returns.
  */
 int atk_approx_topk_recall(const void* values, int dtype, int64_t rows, int64_t N,
                            int64_t row_stride, int K, double recall_target, void* out_vals,
@@ -215,6 +223,25 @@ int atk_mips_describe_plan(int dtype, int64_t Q, int64_t N, int64_t D, int K, in
  */
 int atk_valu_probe(int kind, const void* x, const void* y, void* out, size_t n_words, int ops,
                    void* stream);
+
+/*
+ * Developer options: launch-geometry switches for experiments and tests.  Results never depend on
+ * them.  Process-wide; change them only while no call is in flight.  value < 0 restores the
+ * default.  Initial values may be given in the environment (read once, at the first call that
+ * plans a launch): ATK_LANES_PER_ROW, ATK_SEGMENTS, ATK_SLAB, ATK_NO_PACKED=1, ATK_NO_SUBWAVE=1,
+ * ATK_BATCH_MIN_KP, ATK_MIPS_SEGMENTS, ATK_UNFUSED.
+ *   "lanes_per_row"  0 = planner's choice, else a power of two <= 1024: lanes that share one row
+ *   "segments"       n > 0 forces n row segments on the split route
+ *   "slab"           0 never / 1 planner's choice / 2 whenever possible: slabs of 32 buckets per
+ *                    workgroup (few-row route)
+ *   "packed"         0 switches the packed-key variants (16-bit rows) off
+ *   "subwave"        0 switches the several-rows-per-wavefront variants off
+ *   "batch_min_kp"   list length from which sorted batches are used (default 16)
+ *   "mips_segments"  n > 0 forces n segments of the database walk in atk_mips_approx_topk
+ *   "unfused"        1 sends the survivors of every call through the workspace (two launches)
+ * Returns ATK_INVALID_ARG for an unknown name or an unusable value.  Host only.
+ */
+int atk_set_option(const char* name, int value);
 
 /* Static, human-readable name of a status code. */
 const char* atk_status_string(int status);

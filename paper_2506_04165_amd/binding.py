@@ -26,7 +26,7 @@ SIZE_MAX = ctypes.c_size_t(-1).value
 
 EXPORTS = [
     "atk_approx_topk", "atk_topk", "atk_approx_topk_stage1", "atk_workspace_bytes",
-    "atk_expected_recall", "atk_select_params", "atk_approx_topk_recall", "atk_describe_plan", "atk_valu_probe",
+    "atk_expected_recall", "atk_select_params", "atk_recall_params", "atk_set_option", "atk_approx_topk_recall", "atk_describe_plan", "atk_valu_probe",
     "atk_mips_approx_topk", "atk_mips_workspace_bytes", "atk_mips_describe_plan", "atk_mips_select_params", "atk_mips_approx_topk_recall", "atk_status_string", "atk_last_hip_error",
     "atk_version",
 ]
@@ -60,6 +60,10 @@ def _load() -> ctypes.CDLL:
     ip, dp = ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_double)
     lib.atk_select_params.argtypes = [i64, ci, ctypes.c_double, ci, ci, ip, ip, dp]
     lib.atk_select_params.restype = ci
+    lib.atk_recall_params.argtypes = [ci, i64, i64, ci, ctypes.c_double, ip, ip, dp]
+    lib.atk_recall_params.restype = ci
+    lib.atk_set_option.argtypes = [ctypes.c_char_p, ci]
+    lib.atk_set_option.restype = ci
     lib.atk_approx_topk_recall.argtypes = [vp, ci, i64, i64, i64, ci, ctypes.c_double, vp, vp, vp, sz, vp, ip, ip]
     lib.atk_approx_topk_recall.restype = ci
     lib.atk_valu_probe.argtypes = [ci, vp, vp, vp, sz, ci, vp]
@@ -154,11 +158,39 @@ def select_params(N: int, K: int, recall_target: float, max_kprime: int = 4, buc
     return kp.value, b.value, r.value
 
 
+def recall_params(dtype: torch.dtype, rows: int, N: int, K: int, recall_target: float):
+    """(K', B, expected recall) that approx_topk_recall uses for this problem."""
+    kp, b, r = ctypes.c_int(0), ctypes.c_int(0), ctypes.c_double(0.0)
+    st = lib.atk_recall_params(_CODES[dtype], rows, N, K, recall_target, ctypes.byref(kp), ctypes.byref(b),
+                               ctypes.byref(r))
+    if st != OK:
+        raise AtkError(st, "atk_recall_params")
+    return kp.value, b.value, r.value
+
+
+def set_option(name: str, value: int) -> None:
+    """Developer option of the library (launch geometry only); value < 0 restores the default."""
+    st = lib.atk_set_option(name.encode(), int(value))
+    if st != OK:
+        raise AtkError(st, f"atk_set_option({name!r}, {value})")
+
+
+def _check_out(out, rows: int, K: int, val_dtype: torch.dtype, device):
+    """A caller's (vals, idx) pair must be exactly what the library writes: dense [rows, K] of the
+    value type and of int32, on the input's device."""
+    out_vals, out_idx = out
+    for t, dt, what in ((out_vals, val_dtype, "out values"), (out_idx, torch.int32, "out indices")):
+        if not isinstance(t, torch.Tensor) or t.dtype != dt or tuple(t.shape) != (rows, K) \
+                or t.device != device or not t.is_contiguous():
+            raise ValueError(f"{what} must be a contiguous [{rows}, {K}] {dt} tensor on {device}")
+    return out_vals, out_idx
+
+
 def approx_topk_recall(values: torch.Tensor, K: int, recall_target: float, workspace=None):
     """approx_top_k(array, K, recall_target): returns (vals, idx, K' used, B used)."""
     rows, N, stride = _check_input(values)
     code = _dtype_code(values)
-    kp, b, _ = select_params(N, K, recall_target, 8 if code == BF16 else 4, 64)
+    kp, b, _ = recall_params(values.dtype, rows, N, K, recall_target)
     out_vals = torch.empty((rows, K), dtype=values.dtype, device=values.device)
     out_idx = torch.empty((rows, K), dtype=torch.int32, device=values.device)
     ws_ptr, ws_bytes = None, 0
@@ -185,7 +217,7 @@ def approx_topk(values: torch.Tensor, K: int, Kprime: int, B: int, out=None, wor
         out_vals = torch.empty((rows, K), dtype=values.dtype, device=values.device)
         out_idx = torch.empty((rows, K), dtype=torch.int32, device=values.device)
     else:
-        out_vals, out_idx = out
+        out_vals, out_idx = _check_out(out, rows, K, values.dtype, values.device)
     need = lib.atk_workspace_bytes(OP_APPROX_TOPK, code, rows, N, K, Kprime, B)
     ws_ptr, ws_bytes = None, 0
     if need != SIZE_MAX and need > 0:
@@ -208,7 +240,7 @@ def topk(values: torch.Tensor, K: int, out=None):
         out_vals = torch.empty((rows, K), dtype=values.dtype, device=values.device)
         out_idx = torch.empty((rows, K), dtype=torch.int32, device=values.device)
     else:
-        out_vals, out_idx = out
+        out_vals, out_idx = _check_out(out, rows, K, values.dtype, values.device)
     st = lib.atk_topk(values.data_ptr(), code, rows, N, stride, K, out_vals.data_ptr(),
                       out_idx.data_ptr(), None, 0, _stream_ptr(values.device))
     if st != OK:
@@ -254,7 +286,7 @@ def mips_approx_topk(queries: torch.Tensor, database: torch.Tensor, K: int, Kpri
         out_vals = torch.empty((Q, K), dtype=torch.float32, device=queries.device)
         out_idx = torch.empty((Q, K), dtype=torch.int32, device=queries.device)
     else:
-        out_vals, out_idx = out
+        out_vals, out_idx = _check_out(out, Q, K, torch.float32, queries.device)
     need = lib.atk_mips_workspace_bytes(code, Q, N, D, K, Kprime, B)
     ws_ptr, ws_bytes = None, 0
     if need != SIZE_MAX and need > 0:

@@ -12,6 +12,7 @@
 #include "mips_fused.h"
 #include "approx_kernel.h"
 #include "topk_exact.h"
+#include "select_params.h"
 
 namespace atk {
 
@@ -48,12 +49,16 @@ static const Variant* find_variant(int dtype, int KP, int NL, bool packed_ok, Pr
 constexpr int kMaxListLen = 32;          // longest K'-list kept in registers
 constexpr int kMaxEntriesPerLane = 32;   // V*R*KP
 constexpr int kMaxLanes = 1024;
+// Most buckets: a lane reaches the elements of up to 32 steps from one base address through
+// 32-bit byte offsets, a step being B elements.
+constexpr int kMaxBuckets = 1 << 24;
 // Longest row.  Kernel loops step 32-bit element counters by up to a chunk (32768) past the end
 // before they test them, so the last 65536 values of the int range stay out.
 constexpr int64_t kMaxN = 0x7fffffffLL - 0xffff;
 constexpr size_t kLdsBudget = 144 * 1024; // dynamic LDS per workgroup (the CU has 160 KB)
-constexpr int kExactCap = 4096;          // exact kernel: LDS key buffer
-constexpr int kExactMaxK = 2048;
+constexpr int kMaxFusedCandidates = 16384;  // keys of one row that stage 2 can hold in LDS
+constexpr int kExactCap = 16384;         // exact kernel: largest LDS key buffer
+constexpr int kExactMaxK = 8192;
 constexpr int64_t kTargetWaves = 2048;   // 256 CUs x 4 SIMDs x 2 waves: below this the chip idles
 constexpr int kMinSegmentSteps = 8;      // do not cut a row into pieces shorter than this
 constexpr int kMaxSegments = 64;
@@ -82,9 +87,45 @@ static int kernel_dtype(int dtype) {
     }
 }
 
-static int env_int(const char* name, int fallback) {
-    const char* s = std::getenv(name);
-    return (s && *s) ? std::atoi(s) : fallback;
+// ---- developer options ---------------------------------------------------------------------
+// Launch-geometry switches for experiments and tests; results never depend on them.  Initial
+// values come from the environment, read once when the first call needs them; afterwards only
+// atk_set_option changes them, so a product call reads no environment variable.
+struct Options {
+    int lanes_per_row = 0;    // 0: planner's choice, else a power of two <= 1024
+    int segments = 0;         // > 0: force this many row segments on the split route
+    int slab = 1;             // 0 never / 1 planner's choice / 2 whenever possible: slab route
+    int packed = 1;           // 0: no packed 32-bit keys for 16-bit rows
+    int subwave = 1;          // 0: no several-rows-per-wavefront variants
+    int batch_min_kp = 16;    // list length from which sorted batches are used
+    int mips_segments = 0;    // > 0: segments of the database walk of the fused inner-product entry
+    int unfused = 0;          // 1: survivors always go through the workspace (two launches)
+};
+static Options g_opt;
+static unsigned g_opt_generation = 1;      // bumped by every change: cached plans are keyed on it
+
+static void options_from_env_once() {
+    static const bool done = [] {
+        auto env = [](const char* name, int fallback) {
+            const char* s = std::getenv(name);
+            return (s && *s) ? std::atoi(s) : fallback;
+        };
+        Options o;
+        o.lanes_per_row = env("ATK_LANES_PER_ROW", o.lanes_per_row);
+        o.segments = env("ATK_SEGMENTS", o.segments);
+        o.slab = env("ATK_SLAB", o.slab);
+        o.packed = env("ATK_NO_PACKED", 0) ? 0 : 1;
+        o.subwave = env("ATK_NO_SUBWAVE", 0) ? 0 : 1;
+        o.batch_min_kp = env("ATK_BATCH_MIN_KP", o.batch_min_kp);
+        o.mips_segments = env("ATK_MIPS_SEGMENTS", o.mips_segments);
+        o.unfused = env("ATK_UNFUSED", o.unfused);
+        // an unusable value is ignored, it never turns a legal call into an error
+        if (o.lanes_per_row < 0 || o.lanes_per_row > kMaxLanes || (o.lanes_per_row & (o.lanes_per_row - 1)))
+            o.lanes_per_row = 0;
+        g_opt = o;
+        return true;
+    }();
+    (void)done;
 }
 
 // ---- validation (host only; every error can be provoked without a GPU) ----------------------
@@ -118,6 +159,7 @@ struct Plan {
     size_t lds = 0;
     size_t workspace = 0;       // bytes the plan needs (0: none)
     int nseg = 1, seg_steps = 0;  // > 1: rows are cut into segments, finished by a second launch
+    int chunk = 0, nchunk = 1;    // > 0: survivors to memory, a workgroup takes `chunk` buckets of a row
     int slab_w = 0;             // > 0: workgroups take slabs of this many buckets (see below)
 };
 
@@ -130,8 +172,8 @@ static int list_len_for(int Kp) {
 // Choose how lanes map to buckets.  `stage1_only` plans the survivor-writing launch.
 // `ws_avail` is the workspace the caller offers (SIZE_MAX when only asking what would be used):
 // splitting rows is an optimisation and is dropped when the workspace is too small for it.
-static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride,
-                      int K, int Kp, int B, bool stage1_only, size_t ws_avail = SIZE_MAX) {
+static Plan compute_plan(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride,
+                         int K, int Kp, int B, bool stage1_only, size_t ws_avail) {
     Plan pl;
     const int es = elem_size(dtype);
     const int KP = list_len_for(Kp);
@@ -140,6 +182,7 @@ static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, in
         pl.status = ATK_UNSUPPORTED;
         return pl;
     }
+    if (B > kMaxBuckets) { pl.status = ATK_UNSUPPORTED; return pl; }
     int maxNL = kMaxEntriesPerLane / KP;
     if (maxNL > 16) maxNL = 16;
     maxNL = pow2_floor(maxNL);
@@ -148,8 +191,7 @@ static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, in
     int Gd = pow2_floor(N / 224 > 0 ? N / 224 : 1);
     if (Gd < 64) Gd = 64;
     if (Gd > kMaxLanes) Gd = kMaxLanes;
-    Gd = env_int("ATK_LANES_PER_ROW", Gd);
-    if (!is_pow2(Gd) || Gd > kMaxLanes) { pl.status = ATK_INVALID_ARG; return pl; }
+    if (g_opt.lanes_per_row > 0) Gd = g_opt.lanes_per_row;
 
     auto aligned_for = [&](int V) {
         return B % V == 0 && row_stride % V == 0 && ((uintptr_t)values % (size_t)(V * es)) == 0;
@@ -167,6 +209,11 @@ static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, in
         if (G > B) { owners = G / B; NL = 1; }
         else G = 0;
     }
+    // Survivors that do not fit the fused kernel's LDS leave through memory (unfused route), and
+    // so does everything when only stage 1 was asked for.
+    const bool through_memory = !stage1_only && (pow2_ceil((int64_t)B * Kp) > kMaxFusedCandidates ||
+                                                 g_opt.unfused != 0);
+    bool chunked = false;
     if (G == 0) {
         owners = 1;
         G = B >= Gd ? Gd : pow2_ceil(B);
@@ -174,12 +221,27 @@ static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, in
         for (;;) {
             NL = pow2_ceil((B + G - 1) / G);
             if (NL <= maxNL) break;
-            if (G >= kMaxLanes) { pl.status = ATK_UNSUPPORTED; return pl; }
+            if (G >= kMaxLanes) {
+                // more buckets than one workgroup has list entries for: the row is cut along the
+                // bucket axis, every workgroup taking G*NL buckets of it over all steps
+                NL = maxNL;
+                chunked = true;
+                break;
+            }
             G <<= 1;
+        }
+        if (through_memory && G >= 64) {
+            // nothing is merged inside the workgroup on this route, so cutting a row along the
+            // bucket axis costs nothing: smaller workgroups until the chip is full
+            auto waves = [&] { return rows * (int64_t)((B + G * NL - 1) / (G * NL)) * (G / 64); };
+            while (waves() < kTargetWaves && (NL > 1 || G > 256)) {
+                if (NL > 1) NL >>= 1; else G >>= 1;
+            }
+            chunked = G * NL < B;
         }
         // Short lists: half the lanes with twice the lists each (wider loads, fewer waves per row)
         // measured 3-5 % faster as long as the chip stays full and a lane holds at most 8 entries.
-        if (env_int("ATK_LANES_PER_ROW", 0) == 0 && G >= 128 && NL * 2 * KP <= 8 && B % (NL * 2) == 0 &&
+        if (!chunked && g_opt.lanes_per_row == 0 && G >= 128 && NL * 2 * KP <= 8 && B % (NL * 2) == 0 &&
             rows * (int64_t)(G / 2 / 64) >= kTargetWaves &&
             find_variant(dtype, KP, NL * 2, false, aligned_for) != nullptr &&
             find_variant(dtype, KP, NL * 2, false, aligned_for)->V > 1) {
@@ -189,11 +251,11 @@ static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, in
     }
     // bf16 rows whose indices fit 16 bits: value and index share one 32-bit key
     // (such variants only exist for the plain fused route with at most 1024 candidates per row)
-    bool packed_ok = dtype == ATK_BF16 && N <= 65536 && !stage1_only && owners == 1 && G >= 64 &&
+    bool packed_ok = dtype == ATK_BF16 && N <= 65536 && !stage1_only && !through_memory && owners == 1 && G >= 64 &&
                      pow2_ceil((int64_t)B * Kp) <= kWaveSortMaxKeys &&
-                     env_int("ATK_NO_PACKED", 0) == 0;
+                     g_opt.packed != 0;
     if (packed_ok && G == 64 && NL == 1 && is_pow2(B) && rows >= 1024 &&
-        env_int("ATK_LANES_PER_ROW", 0) == 0 && env_int("ATK_NO_SUBWAVE", 0) == 0) {
+        g_opt.lanes_per_row == 0 && g_opt.subwave != 0) {
         // many short rows with only 64 buckets: rather than 2-byte loads from 64 lanes, a wavefront
         // works on several rows at once, each lane taking as many consecutive elements per load
         // as its registers allow (measured: a gain only in this case)
@@ -207,7 +269,7 @@ static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, in
     if (!pl.var) { pl.status = ATK_UNSUPPORTED; return pl; }
     // Long lists with few buckets: sorted batches of 64-bit keys, one bucket per lane, cost about a
     // third of the position-by-position update at K' = 32.
-    if (!pl.var->packed() && owners == 1 && KP >= env_int("ATK_BATCH_MIN_KP", 16) && B >= 64 && B <= 256) {
+    if (!pl.var->packed() && owners == 1 && KP >= g_opt.batch_min_kp && B >= 64 && B <= 256) {
         for (const Variant& v : kVariants)
             if (v.rep == 2 && v.dtype == dtype && v.KP == KP) {
                 pl.var = &v; G = pow2_ceil(B); NL = 1;
@@ -215,7 +277,7 @@ static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, in
             }
     }
     const int V = pl.var->V;
-    pl.G = G;
+    if (chunked && G * NL < B) { pl.chunk = G * NL; pl.nchunk = (B + pl.chunk - 1) / pl.chunk; }
     pl.owners = owners;
     pl.S = owners > 1 ? G * V : B;
     pl.nsteps = (int)(N / pl.S);
@@ -228,35 +290,42 @@ static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, in
     // LDS: [candidates of every row of the workgroup][auxiliary: partial lists of shared
     // buckets, later reused as scratch of the selection]
     const bool wave_tail = !stage1_only && G >= 64 && pl.Cpad <= kWaveSortMaxKeys;
+    const bool to_memory = stage1_only || through_memory;
     auto lds_for = [&](int r) {
         size_t cand = 0, aux = 0;
         if (owners > 1) { cand = (size_t)r * pl.Cpad; aux = (size_t)r * B * pl.seg; }
         else if (pl.var->packed()) cand = (size_t)r * pl.Cpad / 2 + 1;     // 32-bit keys
-        else if (!stage1_only) cand = (size_t)r * pl.Cpad;
-        if (!stage1_only && !pl.var->packed() && r == 1 && pl.Cpad > 256 &&
+        else if (!to_memory) cand = (size_t)r * pl.Cpad;
+        if (!to_memory && !pl.var->packed() && r == 1 && pl.Cpad > 256 &&
             aux * 8 < (size_t)kSelectScratchBytes)
             aux = (kSelectScratchBytes + 7) / 8;
         return (cand + aux) * 8;
     };
     while (rpw > 1 && lds_for(rpw) > kLdsBudget) rpw >>= 1;
-    // the kernel addresses a lane's row by a 32-bit byte offset from the workgroup's first row
+    // The kernel addresses a lane's row by a 32-bit byte offset from the workgroup's first row.
+    // Never launch less than a wavefront: when so few rows may share a workgroup that their
+    // lanes do not fill one, a row gets more lanes than it has buckets (the extra ones idle).
     while (rpw > 1 && (uint64_t)rpw * (uint64_t)row_stride * es >= (1ull << 31)) rpw >>= 1;
-    if (G * rpw < 64) rpw = 64 / G;          // never launch less than a wavefront
+    if (G * rpw < 64) {
+        if ((uint64_t)(64 / G) * (uint64_t)row_stride * es < (1ull << 31)) rpw = 64 / G;
+        else if (owners == 1) G = 64 / rpw;
+        else { pl.status = ATK_UNSUPPORTED; return pl; }   // shared buckets fix the lane count
+    }
+    pl.G = G;
     pl.rows_per_wg = rpw;
     pl.lds = lds_for(rpw);
     pl.aux_offset = (size_t)rpw * pl.Cpad;
     pl.tail = rpw == 1 ? 2 : (wave_tail ? 1 : 0);
     pl.block = G * rpw;
     pl.grid = (int)((rows + rpw - 1) / rpw);
-    pl.fused = !stage1_only && pl.lds <= kLdsBudget;
-    if (!stage1_only && !pl.fused) {
-        // survivors go through memory: values (input dtype) + int32 indices
+    pl.fused = !to_memory && pl.lds <= kLdsBudget;
+    if (pl.lds > kLdsBudget) { pl.status = ATK_UNSUPPORTED; return pl; }   // (cannot happen)
+    if (through_memory) {
+        // survivors go through memory: int32 indices, then values (input dtype); the exact
+        // kernel then selects among them
         pl.workspace = (size_t)rows * B * Kp * (es + 4);
-        pl.lds = owners > 1 ? lds_for(rpw) : 0;
-        if (pl.lds > kLdsBudget) { pl.status = ATK_UNSUPPORTED; return pl; }
         if (K > kExactMaxK) { pl.status = ATK_UNSUPPORTED; return pl; }
     }
-    if (stage1_only && pl.lds > kLdsBudget) { pl.status = ATK_UNSUPPORTED; return pl; }
 
     // Very few rows: give every workgroup a slab of 32 buckets of one row over all steps, with m
     // lanes per bucket taking every m-th step.  A lane then reads 128-byte runs (32 four-byte
@@ -265,7 +334,7 @@ static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, in
     // the workgroup ends with the final K' keys of its buckets and the second launch is stage 2
     // alone.
     if (pl.fused && owners == 1 && G >= 64 && rows > 0 && B % kSlabBuckets == 0 &&
-        pl.var->rep != 2 && env_int("ATK_SLAB", 1) != 0) {
+        pl.var->rep != 2 && g_opt.slab != 0) {
         const int64_t steps = N / B;
         int m = 8;
         while (m > 1 && (steps % m != 0 || steps / m < 4 || m * KP > 64)) m >>= 1;
@@ -279,7 +348,7 @@ static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, in
                          !pl.var->packed() && (size_t)N * es >= kSlabMinRowBytes &&
                          (size_t)(N / B) * es <= 4096 && in_bytes <= kSlabMaxBytes;
         if (m > 1 && v && v->V == 1 && v->R == 1 && ws <= ws_avail &&
-            (env_int("ATK_SLAB", 1) == 2 || few)) {
+            (g_opt.slab == 2 || few)) {
             pl.var = v;
             pl.slab_w = kSlabBuckets;
             pl.G = kSlabBuckets * m;
@@ -331,7 +400,7 @@ static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, in
                 if (cost(n) < cost(best)) best = n;
             want = best;
         }
-        const int forced = env_int("ATK_SEGMENTS", 0);
+        const int forced = g_opt.segments;
         if (forced > 0 && (size_t)forced * per_seg <= ws_avail) want = forced;
         if (want > pl.nsteps) want = pl.nsteps;
         if (want > 1) {
@@ -348,6 +417,35 @@ static Plan make_plan(const void* values, int dtype, int64_t rows, int64_t N, in
     return pl;
 }
 
+// The plan is a pure function of these arguments and the options, and callers in a loop repeat
+// them: the last few plans of a thread are kept.
+static const Plan& make_plan(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride,
+                             int K, int Kp, int B, bool stage1_only, size_t ws_avail = SIZE_MAX) {
+    options_from_env_once();
+    struct Key {
+        unsigned generation; int dtype, K, Kp, B, align; bool stage1_only;
+        int64_t rows, N, row_stride; size_t ws_avail;
+        bool operator==(const Key& o) const {
+            return generation == o.generation && dtype == o.dtype && K == o.K && Kp == o.Kp && B == o.B &&
+                   align == o.align && stage1_only == o.stage1_only && rows == o.rows && N == o.N &&
+                   row_stride == o.row_stride && ws_avail == o.ws_avail;
+        }
+    };
+    constexpr int kSlots = 8;
+    static thread_local Key keys[kSlots];
+    static thread_local Plan plans[kSlots];
+    static thread_local int used = 0, next = 0;
+    // only the alignment of the base address enters the plan (which vector loads are legal)
+    const Key key{g_opt_generation, dtype, K, Kp, B, (int)((uintptr_t)values & 15), stage1_only,
+                  rows, N, row_stride, ws_avail};
+    for (int i = 0; i < used; ++i)
+        if (keys[i] == key) return plans[i];
+    const int slot = used < kSlots ? used++ : (next = (next + 1) % kSlots);
+    keys[slot] = key;
+    plans[slot] = compute_plan(values, dtype, rows, N, row_stride, K, Kp, B, stage1_only, ws_avail);
+    return plans[slot];
+}
+
 static ApproxParams params_from(const Plan& pl, const void* values, int64_t rows, int64_t N,
                                 int64_t row_stride, int K, int Kp, int B) {
     ApproxParams p{};
@@ -358,6 +456,7 @@ static ApproxParams params_from(const Plan& pl, const void* values, int64_t rows
     p.rows_per_wg = pl.rows_per_wg;
     p.S = pl.S; p.nsteps = pl.nsteps; p.owners = pl.owners; p.seg = pl.seg; p.Cpad = pl.Cpad;
     p.aux_offset = (int)pl.aux_offset; p.tail = pl.tail;
+    p.chunk = pl.chunk;
     return p;
 }
 
@@ -373,16 +472,22 @@ static int exact_threads(int64_t N) {
     return t;
 }
 
+// `payload` non-null: `values` are survivors [rows, N] with their original positions in
+// `payload`, taken from the rows of `orig` (stride `orig_stride`), which is only read to tell
+// the two zeros apart.
 static int run_exact(const void* values, const int32_t* payload, int dtype, int64_t rows, int64_t N,
-                     int64_t row_stride, int K, void* out_vals, int32_t* out_idx, hipStream_t st) {
+                     int64_t row_stride, int K, void* out_vals, int32_t* out_idx, hipStream_t st,
+                     const void* orig = nullptr, int64_t orig_stride = 0) {
     if (K > kExactMaxK) return ATK_UNSUPPORTED;
     TopkParams tp{};
     tp.values = values; tp.payload = payload; tp.row_stride = row_stride;
+    tp.orig_values = orig; tp.orig_stride = orig_stride;
     tp.rows = (int)rows; tp.N = (int)N; tp.K = K;
-    // LDS key buffer: room for 4K keys (members + candidates of the threshold digit), within
-    // [1024, 4096]; a small buffer lets more rows share a CU
+    // LDS key buffer: room for 4K keys (members + candidates of the threshold digit) within
+    // [1024, 4096] -- a small buffer lets more rows share a CU -- and 2K keys for larger K
     tp.cap = pow2_ceil(4 * (int64_t)K);
     if (tp.cap < 1024) tp.cap = 1024;
+    if (tp.cap > 4096) tp.cap = K <= 2048 ? 4096 : pow2_ceil(2 * (int64_t)K);
     if (tp.cap > kExactCap) tp.cap = kExactCap;
     tp.out_vals = out_vals; tp.out_idx = out_idx;
     hipError_t e = launch_topk_exact(tp, dtype, exact_threads(N), st);
@@ -406,6 +511,7 @@ constexpr int kMipsTargetWorkgroups = 512;   // 2 wavefronts per SIMD on 256 CUs
 constexpr int kMipsMinSegmentSteps = 64;     // shorter walks only refill lists
 
 MipsPlan make_mips_plan(int dtype, int64_t Q, int64_t N, int64_t D, int K, int Kprime, int B) {
+    options_from_env_once();
     MipsPlan pl;
     if (Q < 0 || N <= 0 || N > kMaxN || D <= 0) { pl.status = ATK_INVALID_ARG; return pl; }
     if ((pl.status = validate_method(N, K, Kprime, B))) return pl;
@@ -423,7 +529,7 @@ MipsPlan make_mips_plan(int dtype, int64_t Q, int64_t N, int64_t D, int K, int K
     int nseg = (int)((kMipsTargetWorkgroups + pairs - 1) / pairs);
     nseg = std::min(nseg, std::max(1, nsteps / kMipsMinSegmentSteps));
     nseg = std::max(1, std::min(nseg, 16));
-    const int forced = env_int("ATK_MIPS_SEGMENTS", 0);          // developer knob
+    const int forced = g_opt.mips_segments;                      // developer option
     if (forced >= 1 && forced <= 64 && forced <= nsteps) nseg = forced;
     pl.seg_steps = (nsteps + nseg - 1) / nseg;
     pl.nseg = (nsteps + pl.seg_steps - 1) / pl.seg_steps;
@@ -446,8 +552,8 @@ int atk_approx_topk(const void* values, int dtype, int64_t rows, int64_t N, int6
     if (rc) return rc;
     if (rows > 0 && (!out_vals || !out_idx)) return ATK_INVALID_ARG;
     if ((uintptr_t)out_vals % elem_size(dtype) || (uintptr_t)out_idx % 4) return ATK_INVALID_ARG;
-    Plan pl = make_plan(values, dtype, rows, N, row_stride, K, Kprime, B, false,
-                        workspace ? workspace_bytes : 0);
+    const Plan& pl = make_plan(values, dtype, rows, N, row_stride, K, Kprime, B, false,
+                               workspace ? workspace_bytes : 0);
     if (pl.status) return pl.status;
     if (pl.route_exact && K > kExactMaxK) return ATK_UNSUPPORTED;
     if (pl.workspace > 0 && (!workspace || workspace_bytes < pl.workspace))
@@ -502,16 +608,35 @@ int atk_approx_topk(const void* values, int dtype, int64_t rows, int64_t N, int6
     p.surv_vals = surv_vals; p.surv_idx = surv_idx;
     hipError_t e = pl.var->fn(p, pl.grid, pl.block, pl.lds, st);
     if (e != hipSuccess) return hip_fail(e);
-    return run_exact(surv_vals, surv_idx, dtype, rows, C, C, K, out_vals, out_idx, st);
+    return run_exact(surv_vals, surv_idx, dtype, rows, C, C, K, out_vals, out_idx, st, values, row_stride);
+}
+
+int atk_recall_params(int dtype, int64_t rows, int64_t N, int K, double recall_target, int* Kprime_out,
+                      int* B_out, double* expected_recall_out) {
+    if (kernel_dtype(dtype) < 0) return ATK_UNSUPPORTED;
+    if (rows < 0) return ATK_INVALID_ARG;
+    struct Ctx { int dtype; int64_t rows, N; int K; } ctx{kernel_dtype(dtype), rows, N, K};
+    // only configurations that atk_approx_topk runs are candidates
+    auto runs = [](void* c, int kp, int64_t B) {
+        const Ctx& x = *(const Ctx*)c;
+        if (B > 0x7fffffff || validate_method(x.N, x.K, kp, (int)B)) return false;
+        return make_plan(nullptr, x.dtype, x.rows, x.N, x.N, x.K, kp, (int)B, false).status == ATK_OK;
+    };
+    // ceilings below which stage 1 stays memory-bound on this chip: K' <= 4 for 32-bit elements,
+    // K' <= 8 for 16-bit ones; buckets in multiples of a wavefront
+    int rc = select_params_impl(N, K, recall_target, elem_size(dtype) == 2 ? 8 : 4, 64, runs, &ctx,
+                                Kprime_out, B_out, expected_recall_out);
+    if (rc) return rc;
+    if (*Kprime_out == K && *B_out == 1 && K > kExactMaxK) return ATK_UNSUPPORTED;   // exact fallback
+    return ATK_OK;
 }
 
 int atk_approx_topk_recall(const void* values, int dtype, int64_t rows, int64_t N,
                            int64_t row_stride, int K, double recall_target, void* out_vals,
                            int32_t* out_idx, void* workspace, size_t workspace_bytes,
                            void* stream, int* Kprime_used, int* B_used) {
-    if (kernel_dtype(dtype) < 0) return ATK_UNSUPPORTED;
     int kp = 0, b = 0;
-    int rc = atk_select_params(N, K, recall_target, elem_size(dtype) == 2 ? 8 : 4, 64, &kp, &b, nullptr);
+    int rc = atk_recall_params(dtype, rows, N, K, recall_target, &kp, &b, nullptr);
     if (rc) return rc;
     if (Kprime_used) *Kprime_used = kp;
     if (B_used) *B_used = b;
@@ -549,7 +674,7 @@ int atk_approx_topk_stage1(const void* values, int dtype, int64_t rows, int64_t 
     if (rc) return rc;
     if (rows > 0 && (!surv_vals || !surv_idx)) return ATK_INVALID_ARG;
     if ((uintptr_t)surv_vals % elem_size(dtype) || (uintptr_t)surv_idx % 4) return ATK_INVALID_ARG;
-    Plan pl = make_plan(values, dtype, rows, N, row_stride, Kprime, Kprime, B, true);
+    const Plan& pl = make_plan(values, dtype, rows, N, row_stride, Kprime, Kprime, B, true);
     if (pl.status) return pl.status;
     if (rows == 0) return ATK_OK;
     ApproxParams p = params_from(pl, values, rows, N, row_stride, Kprime, Kprime, B);
@@ -568,7 +693,7 @@ size_t atk_workspace_bytes(int op, int dtype, int64_t rows, int64_t N, int K, in
     if (op != ATK_OP_APPROX_TOPK) return SIZE_MAX;
     if (validate_method(N, K, Kprime, B)) return SIZE_MAX;
     // alignment of the real buffers is not known here; assume the allocator's (>= 16 bytes)
-    Plan pl = make_plan(nullptr, dtype, rows, N, N, K, Kprime, B, false);
+    const Plan& pl = make_plan(nullptr, dtype, rows, N, N, K, Kprime, B, false);
     if (pl.status) return SIZE_MAX;
     return pl.workspace;
 }
@@ -647,7 +772,7 @@ int atk_describe_plan(int dtype, int64_t rows, int64_t N, int K, int Kprime, int
     if (rows < 0 || N <= 0 || N > kMaxN) return ATK_INVALID_ARG;
     int rc = validate_method(N, K, Kprime, B);
     if (rc) return rc;
-    Plan pl = make_plan(nullptr, dtype, rows, N, N, K, Kprime, B, false);
+    const Plan& pl = make_plan(nullptr, dtype, rows, N, N, K, Kprime, B, false);
     if (pl.status) return pl.status;
     if (pl.route_exact) {
         std::snprintf(buf, buflen, "exact(K'=K) threads=%d", exact_threads(N));
@@ -659,9 +784,31 @@ int atk_describe_plan(int dtype, int64_t rows, int64_t N, int K, int Kprime, int
                   pl.slab_w > 0 ? "slab" : pl.nseg > 1 ? "split" : (pl.fused ? "fused" : "unfused"),
                   pl.var->packed() ? " packed" : "", pl.var->KP, pl.var->V,
                   pl.var->R, pl.G, pl.rows_per_wg, pl.block, pl.grid,
-                  pl.slab_w > 0 ? B / pl.slab_w : pl.nseg, pl.S, pl.nsteps,
+                  pl.slab_w > 0 ? B / pl.slab_w : (pl.nseg > 1 ? pl.nseg : pl.nchunk), pl.S, pl.nsteps,
                   pl.owners, pl.seg, pl.Cpad, pl.tail, pl.lds, pl.workspace);
     return ATK_OK;
+}
+
+int atk_set_option(const char* name, int value) {
+    if (!name) return ATK_INVALID_ARG;
+    options_from_env_once();
+    const Options defaults;
+    struct Entry { const char* name; int Options::*field; };
+    static const Entry entries[] = {
+        {"lanes_per_row", &Options::lanes_per_row}, {"segments", &Options::segments},
+        {"slab", &Options::slab}, {"packed", &Options::packed}, {"subwave", &Options::subwave},
+        {"batch_min_kp", &Options::batch_min_kp}, {"mips_segments", &Options::mips_segments},
+        {"unfused", &Options::unfused},
+    };
+    for (const Entry& e : entries) {
+        if (std::strcmp(name, e.name) != 0) continue;
+        int v = value < 0 ? defaults.*(e.field) : value;
+        if (e.field == &Options::lanes_per_row && (v > kMaxLanes || (v & (v - 1)))) return ATK_INVALID_ARG;
+        g_opt.*(e.field) = v;
+        ++g_opt_generation;
+        return ATK_OK;
+    }
+    return ATK_INVALID_ARG;
 }
 
 const char* atk_status_string(int status) {

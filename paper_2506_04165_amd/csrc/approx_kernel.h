@@ -49,6 +49,9 @@ struct ApproxParams {
     int nseg;             // mode 2: segments per row (gridDim.y)
     int seg_steps;        // mode 2: steps per segment (the last one may be shorter)
     int slab_w;           // mode 3: buckets per workgroup, a power of two (gridDim.y = B / slab_w)
+    int chunk;            // mode 1, one owner per bucket: > 0 cuts the row along the bucket axis, a
+                          // workgroup taking buckets [blockIdx.y*chunk, +chunk) over all steps
+                          // (gridDim.y = ceil(B / chunk)); 0: the whole row
     uint64_t* part_keys;  // mode 2: [rows, nseg, K', B] keys, 0 = empty entry; mode 3: [rows, K', B]
     void* out_vals;
     int32_t* out_idx;
@@ -323,11 +326,13 @@ struct ApproxKernel {
 
         int off[R];
         bool slot_ok[R];
+        const int chunk_first = p.chunk > 0 ? (int)blockIdx.y * p.chunk : 0;
+        const int chunk_len = p.chunk > 0 ? min(p.chunk, p.S - chunk_first) : p.S;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int o = (r * p.G + t) * V;
-            slot_ok[r] = o < p.S;
-            off[r] = slot_ok[r] ? o : 0;    // idle slots re-read offset 0; their lists are dropped
+            slot_ok[r] = o < chunk_len;
+            off[r] = slot_ok[r] ? chunk_first + o : 0;    // idle slots re-read offset 0; their lists are dropped
         }
         if (p.mode == 3) {
             // a slab of buckets: lane t is owner t / slab_w of bucket first + t % slab_w, and a
@@ -620,7 +625,8 @@ hipError_t launch_approx(const ApproxParams& p, int grid, int block, size_t lds_
                                                    size_t lds_bytes, hipStream_t stream) {      \
         allow_large_lds((const void*)approx_topk_kernel<DT, KP, V, R, REP>, lds_bytes);         \
         hipLaunchKernelGGL((approx_topk_kernel<DT, KP, V, R, REP>),                             \
-                           dim3(grid, p.mode == 2 ? p.nseg : (p.mode == 3 ? p.B / p.slab_w : 1)), dim3(block),                   \
+                           dim3(grid, p.mode == 2 ? p.nseg : (p.mode == 3 ? p.B / p.slab_w :                \
+                                     (p.chunk > 0 ? (p.B + p.chunk - 1) / p.chunk : 1))), dim3(block), \
                            lds_bytes, stream, p);                                               \
         return hipGetLastError();                                                               \
     }

@@ -176,10 +176,26 @@ __device__ __forceinline__ void lds_bitonic_sort_desc(uint64_t* a, int total, in
     }
 }
 
-// Host: kernels that ask for more than 64 KB of dynamic LDS have to say so first.
+// Host: kernels that ask for more than 64 KB of dynamic LDS have to say so first.  The grant
+// holds per kernel and device, so it is asked for once and remembered (per calling thread).
 inline void allow_large_lds(const void* kernel, size_t lds_bytes) {
-    if (lds_bytes > 64 * 1024)
-        (void)hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    if (lds_bytes <= 64 * 1024) return;
+    struct Granted { const void* kernel; int device; size_t bytes; };
+    constexpr int kSlots = 64;
+    static thread_local Granted table[kSlots];
+    static thread_local int used = 0, victim = 0;
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    int slot = -1;
+    for (int i = 0; i < used; ++i)
+        if (table[i].kernel == kernel && table[i].device == dev) {
+            if (table[i].bytes >= lds_bytes) return;
+            slot = i;
+            break;
+        }
+    (void)hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    if (slot < 0) slot = used < kSlots ? used++ : (victim = (victim + 1) % kSlots);
+    table[slot] = {kernel, dev, lds_bytes};
 }
 
 __device__ __forceinline__ int next_pow2(int x) {

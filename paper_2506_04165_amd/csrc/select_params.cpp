@@ -16,10 +16,18 @@
 #include <vector>
 
 #include "../../include/atk.h"
+#include "select_params.h"
 
 extern "C" int atk_select_params(int64_t N, int K, double recall_target, int max_kprime,
                                  int bucket_multiple, int* Kprime_out, int* B_out,
                                  double* expected_recall_out) {
+    return atk::select_params_impl(N, K, recall_target, max_kprime, bucket_multiple, nullptr, nullptr,
+                                   Kprime_out, B_out, expected_recall_out);
+}
+
+int atk::select_params_impl(int64_t N, int K, double recall_target, int max_kprime, int bucket_multiple,
+                            RunsFn runs, void* ctx, int* Kprime_out, int* B_out,
+                            double* expected_recall_out) {
     if (N <= 0 || N > 0x7fffffffLL - 0xffff || K < 1 || K > N || !Kprime_out || !B_out) return ATK_INVALID_ARG;
     if (!(recall_target > 0.0) || recall_target > 1.0 || max_kprime < 1 || bucket_multiple < 1)
         return ATK_INVALID_ARG;
@@ -43,6 +51,7 @@ extern "C" int atk_select_params(int64_t N, int K, double recall_target, int max
             if (B * kp < K) continue;                 // stage 2 needs at least K survivors
             if (kp > N / B) break;                    // buckets only get shorter from here on
             if (best_elems >= 0 && B * kp >= best_elems) break;   // cannot improve any more
+            if (runs && !runs(ctx, kp, B)) continue;
             const double r = atk_expected_recall(N, B, K, kp);
             if (r >= recall_target) {
                 best_elems = B * kp; best_kp = kp; best_b = B; best_recall = r;

@@ -9,6 +9,8 @@ struct TopkParams {
     const void* values;       // [rows, row_stride] elements of the given dtype
     const int32_t* payload;   // optional [rows, row_stride] original indices (survivor mode)
     int64_t row_stride;
+    const void* orig_values;  // survivor mode: the rows the survivors were taken from ...
+    int64_t orig_stride;      // ... and their stride (read only to tell -0.0 from +0.0)
     int rows, N, K;
     int cap;                  // LDS key buffer capacity (power of two, >= 1024, > K)
     void* out_vals;

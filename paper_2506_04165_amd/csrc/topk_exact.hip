@@ -159,24 +159,10 @@ __global__ void __launch_bounds__(1024) topk_exact_kernel(TopkParams p) {
     const int n2 = next_pow2(total);
     for (int i = total + tid; i < n2; i += T) lds64[i] = 0;
     __syncthreads();
-    if (!PAYLOAD) {
-        wg_topk_from_lds<DT>(lds64, n2, p.K, scratch, rowp, p.out_vals, p.out_idx, (int64_t)row * p.K);
-        return;
-    }
-    // survivor mode: the key's index is the original position, the value sits at the survivor's slot
-    lds_bitonic_sort_desc(lds64, n2, n2);
-    for (int i = tid; i < p.K; i += T) {
-        const uint64_t key = lds64[i];
-        const uint32_t idx = key_index(key);
-        uint32_t b = key_value_bits<DT>(key);
-        if (b == 0 && key != 0) {
-            // rare: look the survivor up by its index to tell -0.0 from +0.0
-            for (int n = 0; n < N; ++n)
-                if ((uint32_t)payload[n] == idx) { b = elem<DT>::load_bits(rowp, n); break; }
-        }
-        elem<DT>::store_bits(p.out_vals, (int64_t)row * p.K + i, b);
-        p.out_idx[(int64_t)row * p.K + i] = (int32_t)idx;
-    }
+    // survivor mode: a key's index is the original position, so a zero's stored bits are re-read
+    // from the original row like everywhere else
+    const char* bits_row = PAYLOAD ? (const char*)p.orig_values + (size_t)row * p.orig_stride * elem<DT>::size : rowp;
+    wg_topk_from_lds<DT>(lds64, n2, p.K, scratch, bits_row, p.out_vals, p.out_idx, (int64_t)row * p.K);
 }
 
 template <typename DT>
@@ -185,9 +171,13 @@ hipError_t launch_for(const TopkParams& p, int threads, hipStream_t stream) {
     const dim3 grid(p.rows), block(threads);
     const bool vec = p.payload == nullptr && ((uintptr_t)p.values % 16 == 0) &&
                      ((p.row_stride * elem<DT>::size) % 16 == 0);
-    if (p.payload) hipLaunchKernelGGL((topk_exact_kernel<DT, true, false>), grid, block, lds, stream, p);
-    else if (vec)  hipLaunchKernelGGL((topk_exact_kernel<DT, false, true>), grid, block, lds, stream, p);
-    else           hipLaunchKernelGGL((topk_exact_kernel<DT, false, false>), grid, block, lds, stream, p);
+    auto launch = [&](auto kernel) {
+        allow_large_lds((const void*)kernel, lds);
+        hipLaunchKernelGGL(kernel, grid, block, lds, stream, p);
+    };
+    if (p.payload) launch(topk_exact_kernel<DT, true, false>);
+    else if (vec)  launch(topk_exact_kernel<DT, false, true>);
+    else           launch(topk_exact_kernel<DT, false, false>);
     return hipGetLastError();
 }
 

@@ -73,8 +73,40 @@ def test_unsupported_arguments():
     assert call_approx(dtype=7) == atk.UNSUPPORTED
     # K' beyond the register lists (and not the K'=K case)
     assert call_approx(N=65536, K=128, Kp=40, B=64) == atk.UNSUPPORTED
-    # more buckets than the widest mapping covers
-    assert call_approx(N=262144, K=1024, Kp=1, B=65536) == atk.UNSUPPORTED
+    # more survivors than LDS holds go through the workspace; K beyond the exact kernel's range
+    assert call_approx(N=262144, K=1024, Kp=1, B=65536) == atk.WORKSPACE_TOO_SMALL
+    assert call_approx(N=262144, K=9000, Kp=1, B=65536) == atk.UNSUPPORTED
+    assert call_approx(N=2 ** 26, K=100, Kp=1, B=2 ** 25) == atk.UNSUPPORTED      # B > 2^24
+
+
+def test_large_bucket_counts_run_unfused_in_bucket_chunks():
+    # Table 1's K'=1 rows with 32768 and 65536 buckets of 262144 elements, and neighbours: stage 1
+    # writes the survivors to the workspace with rows cut along the bucket axis
+    for rows, N, K, Kp, B in [(8, 262144, 1024, 1, 65536), (8, 262144, 1024, 1, 32768),
+                              (64, 1 << 20, 1024, 4, 16384), (2, 1 << 20, 5000, 4, 32768),
+                              (3, 3 * 50000, 100, 1, 50000), (1, 1 << 21, 8192, 1, 1 << 20)]:
+        st, text = atk.describe_plan(torch.float32, rows, N, K, Kp, B)
+        assert st == atk.OK and text.startswith("unfused"), (rows, N, K, Kp, B, text)
+        gy = int(re.search(r"grid=\d+x(\d+)", text).group(1))
+        lanes = int(re.search(r"lanes_per_row=(\d+)", text).group(1))
+        V, R = int(re.search(r" V=(\d+)", text).group(1)), int(re.search(r" R=(\d+)", text).group(1))
+        assert gy == -(-B // (lanes * V * R)) and gy > 1, text
+        assert atk.workspace_bytes(atk.OP_APPROX_TOPK, torch.float32, rows, N, K, Kp, B) == rows * B * Kp * 8
+    # stage 1 alone with as many buckets
+    assert atk.lib.atk_approx_topk_stage1(None, 0, 0, 1 << 21, 1 << 21, 2, 1 << 20, None, None, None) == atk.OK
+
+
+def test_rows_sharing_a_wavefront_stay_within_32_bit_offsets():
+    # few buckets that are not a power of two and very long rows: the rows of a workgroup are
+    # addressed by 32-bit byte offsets from its first row, so only so many may share it; the lanes
+    # of a wavefront that this leaves without a row idle rather than wrap around
+    for dtype, es in ((torch.float32, 4), (torch.bfloat16, 2)):
+        for rows, N, B in [(16, 3 * 2 ** 25, 3), (5, 3 * 2 ** 25, 3), (40, 5 * 2 ** 24, 5), (7, 2 ** 30 + 2 ** 29, 3)]:
+            st, text = atk.describe_plan(dtype, rows, N, 2, 2, B)
+            assert st == atk.OK, text
+            rpw = int(re.search(r"rows_per_wg=(\d+)", text).group(1))
+            lanes = int(re.search(r"lanes_per_row=(\d+)", text).group(1))
+            assert (rpw == 1 or rpw * N * es < 2 ** 31) and rpw * lanes >= 64, text
 
 
 def test_rows_zero_is_ok_without_gpu():
@@ -86,7 +118,7 @@ def test_rows_zero_is_ok_without_gpu():
 def test_topk_and_stage1_validation():
     assert atk.lib.atk_topk(FAKE, 0, 2, 128, 128, 0, FAKE, FAKE, None, 0, None) == atk.INVALID_ARG
     assert atk.lib.atk_topk(FAKE, 0, 2, 128, 128, 129, FAKE, FAKE, None, 0, None) == atk.INVALID_ARG
-    assert atk.lib.atk_topk(FAKE, 0, 2, 8192, 8192, 4096, FAKE, FAKE, None, 0, None) == atk.UNSUPPORTED
+    assert atk.lib.atk_topk(FAKE, 0, 2, 16384, 16384, 8193, FAKE, FAKE, None, 0, None) == atk.UNSUPPORTED
     assert atk.lib.atk_topk(None, 0, 2, 128, 128, 4, FAKE, FAKE, None, 0, None) == atk.INVALID_ARG
     st1 = atk.lib.atk_approx_topk_stage1
     assert st1(FAKE, 0, 2, 128, 128, 3, 64, FAKE, FAKE, None) == atk.INVALID_ARG   # K' > N/B
@@ -119,7 +151,7 @@ def test_plans_for_benchmark_configs_are_fused_single_launch():
             assert "workspace=0" in text
 
 
-def test_few_long_rows_are_spread_over_workgroups(monkeypatch):
+def test_few_long_rows_are_spread_over_workgroups(knobs):
     # 8 rows of 262144 (the shape of the paper's Table 1) cannot fill 256 CUs one row per
     # workgroup.  Such rows are given out in slabs of 32 buckets; the plan asks for a workspace
     # for the B*K' keys of every row
@@ -128,13 +160,13 @@ def test_few_long_rows_are_spread_over_workgroups(monkeypatch):
     need = atk.workspace_bytes(atk.OP_APPROX_TOPK, torch.float32, 8, 262144, 1024, 4, 1024)
     assert re.search(r"grid=8x(\d+)", text).group(1) == "32" and need == 8 * 4 * 1024 * 8
     # with that route switched off, rows are cut into segments along their length instead
-    monkeypatch.setenv("ATK_SLAB", "0")
+    knobs.set("slab", 0)
     st, text = atk.describe_plan(torch.float32, 8, 262144, 1024, 4, 1024)
     assert st == atk.OK and text.startswith("split"), text
     need = atk.workspace_bytes(atk.OP_APPROX_TOPK, torch.float32, 8, 262144, 1024, 4, 1024)
     nseg = int(re.search(r"grid=\d+x(\d+)", text).group(1))
     assert nseg > 1 and need == 8 * nseg * 4 * 1024 * 8
-    monkeypatch.delenv("ATK_SLAB")
+    knobs.set("slab", -1)
     # many rows, short rows, few buckets or very long bucket walks go other ways
     for rows, N, B in [(256, 262144, 1024), (8, 16384, 1024), (8, 262144, 64), (8, 1048576, 512)]:
         st, text = atk.describe_plan(torch.float32, rows, N, 64, 4, B)

@@ -145,19 +145,19 @@ ROUTES = [
 @pytest.mark.gpu
 @pytest.mark.parametrize("rows,N,K,Kp,B,route", ROUTES)
 @pytest.mark.parametrize("unsigned", [False, True])
-def test_integer_rows_every_route(atk, rows, N, K, Kp, B, route, unsigned, monkeypatch):
+def test_integer_rows_every_route(atk, rows, N, K, Kp, B, route, unsigned, knobs):
     if route == "split":     # the default for so few rows is the slab route
-        monkeypatch.setenv("ATK_SLAB", "0")
+        knobs.set("slab", 0)
     for kind in ("full", "ties", "floor"):
         check(atk, int_rows(rows, N, seed=31, kind=kind, unsigned=unsigned), K, Kp, B, route)
 
 
 @pytest.mark.gpu
 @pytest.mark.parametrize("rows,N,K,Kp,B,route", ROUTES)
-def test_half_rows_every_route(atk, rows, N, K, Kp, B, route, monkeypatch):
+def test_half_rows_every_route(atk, rows, N, K, Kp, B, route, knobs):
     if route == "split":     # rows this short are not split by themselves: ask for it
-        monkeypatch.setenv("ATK_SLAB", "0")
-        monkeypatch.setenv("ATK_SEGMENTS", "4")
+        knobs.set("slab", 0)
+        knobs.set("segments", 4)
     for kind in ("patterns", "gauss"):
         check(atk, half_rows(rows, N, seed=32, kind=kind), K, Kp, B, route)
 

@@ -101,17 +101,17 @@ def test_fused_route_guard_bands(atk):
     run_guarded_approx(atk, torch.randint(-99, 99, (65, 6000), generator=g, dtype=torch.int32), 77, 3, 125, "fused")
 
 
-def test_slab_and_split_routes_guard_bands_and_poisoned_workspace(atk, monkeypatch):
+def test_slab_and_split_routes_guard_bands_and_poisoned_workspace(atk, knobs):
     x = workloads.gaussian(8, 262144, seed=37)
     run_guarded_approx(atk, x, 1024, 4, 1024, "slab")
     run_guarded_approx(atk, x, 1024, 2, 4096, "slab")
     run_guarded_approx(atk, workloads.gaussian(3, 65536, seed=38, dtype=torch.bfloat16), 500, 6, 1024, "slab")
-    monkeypatch.setenv("ATK_SLAB", "0")
+    knobs.set("slab", 0)
     run_guarded_approx(atk, x, 1024, 4, 1024, "split")
     # a segment count that leaves the last segment short, and segments shorter than K' steps
-    monkeypatch.setenv("ATK_SEGMENTS", "7")
+    knobs.set("segments", 7)
     run_guarded_approx(atk, workloads.gaussian(5, 40 * 512, seed=39), 600, 8, 512, "split")
-    monkeypatch.setenv("ATK_SEGMENTS", "20")
+    knobs.set("segments", 20)
     run_guarded_approx(atk, workloads.heavy_ties(2, 40 * 256, seed=40, symbols=3), 256, 4, 256, "split")
 
 

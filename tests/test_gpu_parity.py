@@ -243,7 +243,7 @@ def test_zero_rows(atk):
     assert v.shape == (0, 8)
 
 
-def test_largest_fused_candidate_set(atk, monkeypatch):
+def test_largest_fused_candidate_set(atk, knobs):
     # B*K' = 16384 candidates per row: the most the fused kernel keeps in LDS (128 KB of keys).
     # With so few rows the default route is the slab one (same candidates, in the finishing
     # launch's LDS): first that, then the single fused launch
@@ -251,7 +251,7 @@ def test_largest_fused_candidate_set(atk, monkeypatch):
     st, text = atk.describe_plan(torch.float32, 3, N, K, Kp, B)
     assert st == atk.OK and text.startswith("slab") and "cand=16384" in text, text
     check_approx(atk, workloads.gaussian(3, N, seed=17), K, Kp, B)
-    monkeypatch.setenv("ATK_SLAB", "0")
+    knobs.set("slab", 0)
     st, text = atk.describe_plan(torch.float32, 3, N, K, Kp, B)
     assert st == atk.OK and text.startswith("fused") and "cand=16384" in text, text
     check_approx(atk, workloads.gaussian(3, N, seed=17), K, Kp, B)
@@ -270,9 +270,90 @@ def test_unfused_path_through_workspace(atk):
     check_approx(atk, x, K, Kp, B)
     xb = workloads.gaussian(4, N, seed=14, dtype=torch.bfloat16)
     check_approx(atk, xb, K, Kp, B)
+    # enough rows that a workgroup keeps a whole row (no cut along the bucket axis)
+    st, text = atk.describe_plan(torch.float32, 600, N, K, Kp, B)
+    assert st == atk.OK and text.startswith("unfused") and "x1 " in text, text
+    check_approx(atk, workloads.gaussian(600, N, seed=15), K, Kp, B, rows_to_check=[0, 1, 299, 598, 599])
 
 
-def test_slab_path_very_few_rows(atk, monkeypatch):
+@pytest.mark.parametrize("rows,N,K,Kp,B,dtype", [
+    (8, 262144, 1024, 1, 65536, torch.float32),      # Table 1's K'=1 rows with the most buckets
+    (8, 262144, 1024, 1, 32768, torch.float32),
+    (8, 262144, 1024, 2, 16384, torch.bfloat16),
+    (2, 1 << 20, 5000, 4, 32768, torch.float32),     # K beyond 2048
+    (3, 150000, 100, 1, 50000, torch.float32),       # bucket count that is no power of two: ragged last chunk
+    (3, 150000, 8192, 3, 50000, torch.int32),
+    (1, 1 << 21, 8192, 1, 1 << 20, torch.float32),   # a million buckets
+    (70, 1 << 18, 2000, 8, 4096, torch.uint32),
+])
+def test_large_bucket_counts_unfused_in_bucket_chunks(atk, rows, N, K, Kp, B, dtype):
+    st, text = atk.describe_plan(dtype, rows, N, K, Kp, B)
+    assert st == atk.OK and text.startswith("unfused"), text
+    if dtype in (torch.int32, torch.uint32):
+        g = torch.Generator().manual_seed(B)
+        x = torch.randint(-4000, 4000, (rows, N), generator=g, dtype=torch.int64)
+        x = (x & 0xffffffff).to(torch.uint32) if dtype == torch.uint32 else x.to(torch.int32)
+    else:
+        x = workloads.gaussian(rows, N, seed=B % 1000, dtype=dtype)
+    check_approx(atk, x, K, Kp, B)
+    check_stage1(atk, x, Kp, B)
+
+
+def test_forced_unfused_route_matches_on_every_list_representation(atk, knobs):
+    # the survivors of any call can be sent through the workspace: lanes sharing buckets, packed
+    # and batched lists, integers -- same bits as the oracle
+    knobs.set("unfused", 1)
+    for x, K, Kp, B in [(workloads.gaussian(37, 8192, seed=33), 40, 4, 16),
+                        (workloads.gaussian(300, 16384, seed=31), 128, 4, 1024),
+                        (workloads.gaussian(1031, 2048, seed=34, dtype=torch.bfloat16), 287, 4, 128),
+                        (workloads.gaussian(129, 65536, seed=35), 256, 32, 256),
+                        (workloads.heavy_ties(8, 262144, seed=16, symbols=3), 1024, 4, 1024),
+                        (workloads.gaussian(5, 900, seed=36), 40, 30, 3)]:
+        st, text = atk.describe_plan(x.dtype, x.shape[0], x.shape[1], K, Kp, B)
+        assert st == atk.OK and text.startswith("unfused"), text
+        check_approx(atk, x, K, Kp, B)
+
+
+@pytest.mark.parametrize("N,K", [(5000, 2049), (20000, 4096), (100000, 8192), (8192, 8192), (300000, 5000)])
+def test_exact_topk_large_k(atk, N, K):
+    check_exact(atk, workloads.gaussian(3, N, seed=N % 89), K)
+    check_exact(atk, workloads.heavy_ties(2, N, seed=N % 83, symbols=3).to(torch.bfloat16), K)
+
+
+def test_long_rows_sharing_a_wavefront(atk):
+    # three buckets and rows of 3 * 2^24 elements: the rows a workgroup may address from its first
+    # row by 32-bit offsets do not fill a wavefront.  Expected output from planted values (the
+    # oracle is not run on rows this long): a background of negative values and, per row, distinct
+    # positive values at seeded positions; per bucket the K' greatest planted values survive.
+    rows, B, Kp, K = 9, 3, 2, 5
+    N = 3 * 2 ** 24
+    x = torch.empty((rows, N), dtype=torch.float32, device=DEV)
+    n = torch.arange(N, device=DEV, dtype=torch.int64)
+    for r in range(rows):
+        x[r] = -1.0 - ((n + r) % 977).to(torch.float32) * 1e-3
+    del n
+    rng = np.random.default_rng(9)
+    expected = []
+    for r in range(rows):
+        pos = np.unique(np.concatenate([[0, 1, 2, N - 1, N - 2, N - 3], rng.integers(0, N, 30)]))
+        vals = (1.0 + rng.permutation(len(pos)) * 0.25 + r).astype(np.float32)
+        x[r, torch.from_numpy(pos).to(DEV)] = torch.from_numpy(vals).to(DEV)
+        surv = []
+        for b in range(B):
+            inb = sorted(((v, p_) for p_, v in zip(pos.tolist(), vals.tolist()) if p_ % B == b), key=lambda t: -t[0])
+            surv += inb[:Kp]
+        expected.append(sorted(surv, key=lambda t: -t[0])[:K])
+    st, text = atk.describe_plan(torch.float32, rows, N, K, Kp, B)
+    print(text, flush=True)
+    assert st == atk.OK and "rows_per_wg=8 " in text and "lanes_per_row=8 " in text, text
+    gv, gi = atk.approx_topk(x, K, Kp, B)
+    torch.cuda.synchronize()
+    for r in range(rows):
+        assert gi[r].cpu().tolist() == [p_ for _, p_ in expected[r]], r
+        assert gv[r].cpu().tolist() == [v for v, _ in expected[r]], r
+
+
+def test_slab_path_very_few_rows(atk, knobs):
     # the shape of the paper's Table 1 and its neighbours: every workgroup takes 32 buckets of a
     # row over all steps, several lanes per bucket; stage 2 runs in a second launch
     for dtype in (torch.float32, torch.bfloat16, torch.int32):
@@ -292,14 +373,14 @@ def test_slab_path_very_few_rows(atk, monkeypatch):
     check_approx(atk, z, 1024, 4, 1024)
     # asked for where the planner would not choose it: few buckets, bucket counts that are only
     # a multiple of 32, rows that one lane per bucket would cover in a handful of steps
-    monkeypatch.setenv("ATK_SLAB", "2")
+    knobs.set("slab", 2)
     for rows, N, B, Kp, K in [(5, 16384, 64, 4, 200), (2, 96 * 64, 96, 3, 100), (9, 32768, 512, 2, 64),
                               (4, 8192, 256, 8, 256), (3, 160 * 24, 160, 2, 300)]:
         st, text = atk.describe_plan(torch.float32, rows, N, K, Kp, B)
         assert st == atk.OK and text.startswith("slab"), text
         check_approx(atk, workloads.gaussian(rows, N, seed=19), K, Kp, B)
         check_approx(atk, workloads.heavy_ties(rows, N, seed=20, symbols=5), K, Kp, B)
-    monkeypatch.delenv("ATK_SLAB")
+    knobs.set("slab", -1)
     # a workspace that is too small: the call falls back to a route that needs none
     zd = z.to(DEV)
     small = torch.empty(1024, dtype=torch.uint8, device=DEV)
@@ -311,21 +392,21 @@ def test_slab_path_very_few_rows(atk, monkeypatch):
     assert st == atk.OK and torch.equal(out[1], i1) and torch.equal(out[0], v1)
 
 
-def test_split_path_few_long_rows(atk, monkeypatch):
+def test_split_path_few_long_rows(atk, knobs):
     # the same shape with rows cut into segments along their length (the route for rows that
     # are few but not very few)
-    monkeypatch.setenv("ATK_SLAB", "0")
+    knobs.set("slab", 0)
     for dtype in (torch.float32, torch.bfloat16):
         x = workloads.gaussian(8, 262144, seed=15, dtype=dtype)
         if dtype == torch.bfloat16:     # half the bytes: the planner would not split by itself
-            monkeypatch.setenv("ATK_SEGMENTS", "8")
+            knobs.set("segments", 8)
         for B, Kp in [(1024, 4), (8192, 1), (512, 6), (2048, 2), (256, 16)]:
             st, text = atk.describe_plan(dtype, 8, 262144, 1024, Kp, B)
             assert st == atk.OK
             if (B, Kp) == (1024, 4):
                 assert text.startswith("split"), text
             check_approx(atk, x, 1024, Kp, B)
-    monkeypatch.delenv("ATK_SEGMENTS")
+    knobs.set("segments", -1)
     # ties across segment boundaries, and a workspace that is too small (falls back to one launch)
     z = workloads.heavy_ties(8, 262144, seed=16, symbols=3)
     check_approx(atk, z, 1024, 4, 1024)
@@ -405,12 +486,12 @@ def test_exact_topk_sizes(atk):
     check_exact(atk, x, 2000)
 
 
-def test_results_do_not_depend_on_launch_geometry(atk, monkeypatch):
+def test_results_do_not_depend_on_launch_geometry(atk, knobs):
     # the same problem under different lanes-per-row choices must give identical bits
     x = workloads.gaussian(7, 32768, seed=21).to(DEV)
     ref = None
     for lanes in (64, 128, 256, 512, 1024):
-        monkeypatch.setenv("ATK_LANES_PER_ROW", str(lanes))
+        knobs.set("lanes_per_row", lanes)
         for (K, Kp, B) in [(64, 2, 512), (64, 4, 16)]:
             v, i = atk.approx_topk(x, K, Kp, B)
             torch.cuda.synchronize()
@@ -421,29 +502,29 @@ def test_results_do_not_depend_on_launch_geometry(atk, monkeypatch):
                 ref[key] = (v.clone(), i.clone())
             else:
                 assert torch.equal(ref[key][1], i) and torch.equal(ref[key][0], v), (lanes, key)
-    monkeypatch.delenv("ATK_LANES_PER_ROW")
+    knobs.set("lanes_per_row", -1)
 
 
-def test_results_do_not_depend_on_the_list_representation(atk, monkeypatch):
+def test_results_do_not_depend_on_the_list_representation(atk, knobs):
     # packed 32-bit keys vs value+step lists vs several rows per wavefront (bf16), and sorted
     # batches vs position-by-position updates (fp32, K'=16): identical bits
     xb = workloads.gaussian(1100, 4096, seed=22, dtype=torch.bfloat16).to(DEV)
     for (K, Kp, B) in [(200, 4, 128), (300, 8, 64), (64, 1, 1024)]:
         base = atk.approx_topk(xb, K, Kp, B)
-        for env in ({"ATK_NO_PACKED": "1"}, {"ATK_NO_SUBWAVE": "1"}, {"ATK_LANES_PER_ROW": "128"}):
+        for env in ({"packed": 0}, {"subwave": 0}, {"lanes_per_row": 128}):
             for k, v in env.items():
-                monkeypatch.setenv(k, v)
+                knobs.set(k, v)
             other = atk.approx_topk(xb, K, Kp, B)
             torch.cuda.synchronize()
             for k in env:
-                monkeypatch.delenv(k)
+                knobs.set(k, -1)
             assert torch.equal(base[1], other[1]) and torch.equal(base[0], other[0]), (K, Kp, B, env)
     xf = workloads.gaussian(64, 32768, seed=23).to(DEV)
     base = atk.approx_topk(xf, 500, 16, 128)
-    monkeypatch.setenv("ATK_BATCH_MIN_KP", "64")
+    knobs.set("batch_min_kp", 64)
     other = atk.approx_topk(xf, 500, 16, 128)
     torch.cuda.synchronize()
-    monkeypatch.delenv("ATK_BATCH_MIN_KP")
+    knobs.set("batch_min_kp", -1)
     assert torch.equal(base[1], other[1]) and torch.equal(base[0], other[0])
 
 
@@ -498,7 +579,7 @@ def test_full_size_every_row_against_the_oracle(atk, name):
     assert bad.size == 0, (name, "exact: rows that differ:", bad[:10].tolist(), "of", bad.size)
 
 
-def test_hip_graph_capture_and_replay(atk, monkeypatch):
+def test_hip_graph_capture_and_replay(atk, knobs):
     # The library enqueues on the caller's stream, allocates nothing and never synchronises, so a
     # call can be captured into a HIP graph.  Every replay (with eager work and synchronisation
     # in between, and new contents in the captured input buffer) must equal the eager result.
@@ -510,7 +591,7 @@ def test_hip_graph_capture_and_replay(atk, monkeypatch):
     for name, call, (rows, N) in cases:
         K = 128 if name == "fused" else 1024
         if name == "split":
-            monkeypatch.setenv("ATK_SLAB", "0")
+            knobs.set("slab", 0)
         assert atk.describe_plan(torch.float32, rows, N, K, 4, 1024)[1].startswith(name)
         static_in = workloads.gaussian(rows, N, seed=70).to(DEV)
         ws = torch.empty(64 << 20, dtype=torch.uint8, device=DEV)

@@ -62,24 +62,58 @@ def test_recall_target_entry_point_runs_the_selected_configuration():
     import numpy as np
     from paper_2506_04165_amd import workloads
     for dtype, N, K, target in [(torch.float32, 65536, 256, 0.95), (torch.bfloat16, 14336, 287, 0.95),
+                                (torch.float16, 14336, 287, 0.95), (torch.float32, 430080, 3360, 0.999),
                                 (torch.float32, 262144, 1024, 0.99), (torch.float32, 4096, 32, 1.0)]:
         x = workloads.gaussian(6, N, seed=77, dtype=dtype)
         xd = x.to("cuda:0")
         v, i, kp, B = atk.approx_topk_recall(xd, K, target)
         torch.cuda.synchronize()
-        want = atk.select_params(N, K, target, 8 if dtype == torch.bfloat16 else 4, 64)
-        assert (kp, B) == want[:2]
+        # the library's own choice, and the ceilings it documents (every configuration runs)
+        assert (kp, B) == atk.recall_params(dtype, 6, N, K, target)[:2]
+        assert (kp, B) == atk.select_params(N, K, target, 8 if x.element_size() == 2 else 4, 64)[:2]
         xh = workloads.to_numpy_bits(x)
         if (kp, B) == (K, 1):
             ov, oi = oracle.topk(xh, K)
         else:
             ov, oi = oracle.approx_topk(xh, K, kp, B)
         assert np.array_equal(i.cpu().numpy(), oi)
-        got = v.cpu().view(torch.int16).numpy().view(np.uint16) if dtype == torch.bfloat16 else v.cpu().numpy().view(np.uint32)
-        assert np.array_equal(got, ov if ov.dtype == np.uint16 else ov.view(np.uint32))
+        got = v.cpu().view(torch.int16).numpy().view(np.uint16) if x.element_size() == 2 else v.cpu().numpy().view(np.uint32)
+        assert np.array_equal(got, ov.view(np.uint16) if ov.dtype.itemsize == 2 else ov.view(np.uint32))
         # the realised recall on random data is close to the target's expectation
         _, ei = oracle.topk(xh, K)
         assert oracle.index_recall(oi, ei).mean() >= target - 0.03
+
+
+def test_recall_params_is_the_sweep_with_the_chips_ceilings_over_what_runs():
+    # 16-bit elements get the K' <= 8 ceiling whatever the format, 32-bit ones K' <= 4
+    for dtype, ceiling in [(torch.float32, 4), (torch.int32, 4), (torch.uint32, 4), (torch.bfloat16, 8),
+                           (torch.float16, 8)]:
+        for N, K, target in [(14336, 287, 0.95), (262144, 1024, 0.99), (65536, 256, 0.9), (430080, 3360, 0.999),
+                             (430080, 3360, 0.95), (4096, 32, 1.0), (1 << 20, 128, 0.9999)]:
+            got = atk.recall_params(dtype, 8, N, K, target)
+            assert got == atk.select_params(N, K, target, ceiling, 64), (dtype, N, K, target)
+            kp, b, r = got
+            if (kp, b) != (K, 1):
+                assert atk.describe_plan(dtype, 8, N, K, kp, b)[0] == atk.OK
+                assert r >= target and r == pytest.approx(oracle.expected_recall(N, b, K, kp), abs=1e-9)
+    # nothing approximate reaches the target and the exact kernel does not cover K either
+    kp, b = ctypes.c_int(), ctypes.c_int()
+    assert atk.lib.atk_recall_params(0, 8, 1 << 20, 9000, 1.0, ctypes.byref(kp), ctypes.byref(b), None) == atk.UNSUPPORTED
+    assert atk.lib.atk_recall_params(9, 8, 4096, 32, 0.9, ctypes.byref(kp), ctypes.byref(b), None) == atk.UNSUPPORTED
+    assert atk.lib.atk_recall_params(0, -1, 4096, 32, 0.9, ctypes.byref(kp), ctypes.byref(b), None) == atk.INVALID_ARG
+    assert atk.lib.atk_recall_params(0, 8, 4096, 32, 0.0, ctypes.byref(kp), ctypes.byref(b), None) == atk.INVALID_ARG
+
+
+def test_options_are_validated():
+    assert atk.lib.atk_set_option(b"no_such_option", 1) == atk.INVALID_ARG
+    assert atk.lib.atk_set_option(None, 1) == atk.INVALID_ARG
+    assert atk.lib.atk_set_option(b"lanes_per_row", 48) == atk.INVALID_ARG      # not a power of two
+    assert atk.lib.atk_set_option(b"lanes_per_row", 2048) == atk.INVALID_ARG
+    before = atk.describe_plan(torch.float32, 300, 65536, 64, 2, 512)
+    atk.set_option("lanes_per_row", 128)
+    assert "lanes_per_row=128" in atk.describe_plan(torch.float32, 300, 65536, 64, 2, 512)[1]
+    atk.set_option("lanes_per_row", -1)
+    assert atk.describe_plan(torch.float32, 300, 65536, 64, 2, 512) == before
 
 
 @pytest.mark.parametrize("N,K,target", [(1 << 20, 1024, 0.99), (1 << 20, 1024, 0.95), (1 << 20, 128, 0.99),
