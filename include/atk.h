@@ -225,6 +225,16 @@ int atk_valu_probe(int kind, const void* x, const void* y, void* out, size_t n_w
                    void* stream);
 
 /*
+ * Read-only streaming probe: the memory bandwidth this chip delivers to a kernel that only reads
+ * (the beta of Section 2.3's runtime model, measured rather than taken from the datasheet), as
+ * the ceiling the streaming kernels are compared with.  Reads `bytes` bytes at `data` (device,
+ * 16-byte aligned, a multiple of 16) once, with the loads the stage-1 kernel uses, and xors the
+ * exclusive-or of all 32-bit words into *checksum (device, one 32-bit word, which the caller
+ * sets to zero beforehand).  Asynchronous on `stream`.
+ */
+int atk_read_probe(const void* data, size_t bytes, void* checksum, void* stream);
+
+/*
  * Developer options: launch-geometry switches for experiments and tests.  Results never depend on
  * them.  Process-wide; change them only while no call is in flight.  value < 0 restores the
  * default.  Initial values may be given in the environment (read once, at the first call that

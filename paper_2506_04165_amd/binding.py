@@ -26,7 +26,7 @@ SIZE_MAX = ctypes.c_size_t(-1).value
 
 EXPORTS = [
     "atk_approx_topk", "atk_topk", "atk_approx_topk_stage1", "atk_workspace_bytes",
-    "atk_expected_recall", "atk_select_params", "atk_recall_params", "atk_set_option", "atk_approx_topk_recall", "atk_describe_plan", "atk_valu_probe",
+    "atk_expected_recall", "atk_select_params", "atk_recall_params", "atk_set_option", "atk_approx_topk_recall", "atk_describe_plan", "atk_valu_probe", "atk_read_probe",
     "atk_mips_approx_topk", "atk_mips_workspace_bytes", "atk_mips_describe_plan", "atk_mips_select_params", "atk_mips_approx_topk_recall", "atk_status_string", "atk_last_hip_error",
     "atk_version",
 ]
@@ -68,6 +68,8 @@ def _load() -> ctypes.CDLL:
     lib.atk_approx_topk_recall.restype = ci
     lib.atk_valu_probe.argtypes = [ci, vp, vp, vp, sz, ci, vp]
     lib.atk_valu_probe.restype = ci
+    lib.atk_read_probe.argtypes = [vp, sz, vp, vp]
+    lib.atk_read_probe.restype = ci
     lib.atk_describe_plan.argtypes = [ci, i64, i64, ci, ci, ci, ctypes.c_char_p, sz]
     lib.atk_describe_plan.restype = ci
     lib.atk_mips_approx_topk.argtypes = [vp, vp, ci, i64, i64, i64, ci, ci, ci, vp, vp, vp, sz, vp]
@@ -328,6 +330,20 @@ def valu_probe(kind: int, x: torch.Tensor, y, ops: int, out=None):
     if st != OK:
         raise AtkError(st, "atk_valu_probe")
     return out
+
+
+def read_probe(data: torch.Tensor, checksum: torch.Tensor | None = None):
+    """Stream `data` (contiguous, on the GPU) once, read only; returns the int32 tensor holding the
+    exclusive-or of all its 32-bit words (pass a zeroed one-element int32 tensor to reuse it)."""
+    if not data.is_cuda or not data.is_contiguous():
+        raise ValueError("data must be a contiguous GPU tensor")
+    if checksum is None:
+        checksum = torch.zeros(1, dtype=torch.int32, device=data.device)
+    st = lib.atk_read_probe(data.data_ptr(), data.numel() * data.element_size(), checksum.data_ptr(),
+                            _stream_ptr(data.device))
+    if st != OK:
+        raise AtkError(st, "atk_read_probe")
+    return checksum
 
 
 def approx_topk_stage1(values: torch.Tensor, Kprime: int, B: int):

@@ -25,6 +25,7 @@ SOURCES = [
     "mips_fused.hip",
     "mips_fused_long.hip",
     "valu_probe.hip",
+    "read_probe.hip",
     "approx_inst_f32_small.hip",
     "approx_inst_f32_wide.hip",
     "approx_inst_bf16_small.hip",

@@ -782,7 +782,7 @@ int atk_describe_plan(int dtype, int64_t rows, int64_t N, int K, int Kprime, int
                   "%s%s KP=%d V=%d R=%d lanes_per_row=%d rows_per_wg=%d block=%d grid=%dx%d step=%d "
                   "steps=%d owners=%d seg=%d cand=%d tail=%d lds=%zu workspace=%zu",
                   pl.slab_w > 0 ? "slab" : pl.nseg > 1 ? "split" : (pl.fused ? "fused" : "unfused"),
-                  pl.var->packed() ? " packed" : "", pl.var->KP, pl.var->V,
+                  pl.var->packed() ? " packed" : (pl.var->rep == 2 ? " batched" : ""), pl.var->KP, pl.var->V,
                   pl.var->R, pl.G, pl.rows_per_wg, pl.block, pl.grid,
                   pl.slab_w > 0 ? B / pl.slab_w : (pl.nseg > 1 ? pl.nseg : pl.nchunk), pl.S, pl.nsteps,
                   pl.owners, pl.seg, pl.Cpad, pl.tail, pl.lds, pl.workspace);

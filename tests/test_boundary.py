@@ -228,3 +228,4 @@ def test_mips_validation_and_plan():
     assert atk.lib.atk_mips_workspace_bytes(3, 4, 4096, 128, 64, 2, 64) == atk.SIZE_MAX   # integers
     st, text = atk.mips_describe_plan(1024, 1 << 20, 128, 1024, 4, 1024)
     assert st == atk.OK and text.startswith("mfma32x32x16") and "workspace=67108864" in text
+

@@ -33,3 +33,33 @@ def test_probe_rejects_bad_arguments():
     assert f(1, 0x1000, None, 0x1000, 16, -1, None) == atk.INVALID_ARG
     assert f(1, 0x1002, None, 0x1000, 16, 1, None) == atk.INVALID_ARG
     assert f(1, 0x1000, None, 0x1000, 0, 1, None) == atk.OK
+
+
+@pytest.mark.gpu
+def test_read_probe_folds_every_word_exactly_once():
+    # the bandwidth-ceiling probe: exclusive-or of all 32-bit words, so a word read twice or
+    # not at all shows
+    from paper_2506_04165_amd import binding as atk
+    rng = np.random.default_rng(4)
+    for n_vec in (1, 7, 1000, 8 * 512 * 3 + 5, 2048 * 4096 + 123, (64 << 20) // 16):
+        w = rng.integers(0, 2**32, size=n_vec * 4, dtype=np.uint32)
+        d = torch.from_numpy(w.view(np.int32)).to("cuda:0")
+        got = atk.read_probe(d)
+        torch.cuda.synchronize()
+        assert int(got.cpu().numpy().view(np.uint32)[0]) == int(np.bitwise_xor.reduce(w)), n_vec
+    # accumulates into the caller's word
+    acc = torch.full((1,), 0x5A5A, dtype=torch.int32, device="cuda:0")
+    atk.read_probe(torch.zeros(64, dtype=torch.int32, device="cuda:0"), acc)
+    torch.cuda.synchronize()
+    assert int(acc.item()) == 0x5A5A
+
+
+def test_read_probe_rejects_bad_arguments():
+    from paper_2506_04165_amd import binding as atk
+    f = atk.lib.atk_read_probe
+    assert f(0x1000, 64, None, None) == atk.INVALID_ARG
+    assert f(None, 64, 0x1000, None) == atk.INVALID_ARG
+    assert f(0x1004, 64, 0x1000, None) == atk.INVALID_ARG       # data not 16-byte aligned
+    assert f(0x1000, 60, 0x1000, None) == atk.INVALID_ARG       # not a multiple of 16
+    assert f(0x1000, 64, 0x1002, None) == atk.INVALID_ARG
+    assert f(None, 0, 0x1000, None) == atk.OK
