@@ -154,7 +154,7 @@ def bench_workload(name, steps, warmup, with_cpu_baseline, only_params=None):
     exact["torch_topk_ms_avg"] = lib["kernel_ms_avg"]
 
     # the measured ceiling: a kernel that only reads, over the same input copies, in the same run
-    chk = torch.zeros(1, dtype=torch.int32, device=dev)
+    chk = torch.zeros(atk.READ_PROBE_WORDS, dtype=torch.int32, device=dev)
     rd = time_steps(lambda i: atk.read_probe(xs[i], chk), copies, max(10, steps), warmup)
     ceiling_gbps = in_bytes / (rd["kernel_ms_median"] * 1e-3) / 1e9
     exact["measured_read_ceiling_gbps"] = ceiling_gbps

@@ -332,13 +332,20 @@ def valu_probe(kind: int, x: torch.Tensor, y, ops: int, out=None):
     return out
 
 
+READ_PROBE_WORDS = 1024
+
+
 def read_probe(data: torch.Tensor, checksum: torch.Tensor | None = None):
-    """Stream `data` (contiguous, on the GPU) once, read only; returns the int32 tensor holding the
-    exclusive-or of all its 32-bit words (pass a zeroed one-element int32 tensor to reuse it)."""
+    """Stream `data` (contiguous, on the GPU) once, read only.  Returns the int32 tensor of
+    READ_PROBE_WORDS words whose exclusive-or is that of all 32-bit words of `data` (pass a zeroed
+    one to reuse it)."""
     if not data.is_cuda or not data.is_contiguous():
         raise ValueError("data must be a contiguous GPU tensor")
     if checksum is None:
-        checksum = torch.zeros(1, dtype=torch.int32, device=data.device)
+        checksum = torch.zeros(READ_PROBE_WORDS, dtype=torch.int32, device=data.device)
+    elif checksum.dtype != torch.int32 or checksum.numel() != READ_PROBE_WORDS or not checksum.is_contiguous() \
+            or checksum.device != data.device:
+        raise ValueError(f"checksum must be a contiguous int32 tensor of {READ_PROBE_WORDS} words on {data.device}")
     st = lib.atk_read_probe(data.data_ptr(), data.numel() * data.element_size(), checksum.data_ptr(),
                             _stream_ptr(data.device))
     if st != OK:

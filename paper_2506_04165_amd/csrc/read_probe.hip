@@ -2,8 +2,9 @@
 // against (the beta of Section 2.3's runtime model, as this chip delivers it to a kernel that
 // does nothing but read).  It reads a buffer once with the same instruction the stage-1 kernel
 // streams rows with -- non-temporal 16-byte buffer loads, 32 dwords in flight per lane, every
-// workgroup walking a contiguous piece -- and folds the words into one checksum so that the
-// loads cannot be dropped and the result can be checked.
+// workgroup walking a contiguous piece -- and folds the words of every piece into a checksum word
+// of its own (no atomics: nothing but the loads takes time) so that the loads cannot be dropped
+// and the result can be checked.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -35,7 +36,14 @@ __global__ void __launch_bounds__(kThreads) read_probe_kernel(const char* data, 
         acc ^= v.x ^ v.y ^ v.z ^ v.w;
     }
     for (int o = atk::kWave / 2; o >= 1; o >>= 1) acc ^= (uint32_t)__shfl_xor((int)acc, o, atk::kWave);
-    if ((threadIdx.x & (atk::kWave - 1)) == 0 && acc != 0) atomicXor(out, acc);
+    __shared__ uint32_t wave_acc[kThreads / atk::kWave];
+    if ((threadIdx.x & (atk::kWave - 1)) == 0) wave_acc[threadIdx.x / atk::kWave] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t all = 0;
+        for (int w = 0; w < kThreads / atk::kWave; ++w) all ^= wave_acc[w];
+        out[blockIdx.x] ^= all;          // this workgroup's own word
+    }
 }
 
 }  // namespace
@@ -45,11 +53,11 @@ extern "C" int atk_read_probe(const void* data, size_t bytes, void* checksum, vo
     if (bytes == 0) return ATK_OK;
     if (!data || (uintptr_t)data % 16 || bytes % 16) return ATK_INVALID_ARG;
     const size_t n_vec = bytes / 16;
-    // 2048 workgroups (8 per CU) unless the pieces would exceed what a 32-bit offset reaches
-    size_t grid = 2048;
-    while ((n_vec + grid - 1) / grid * 16 >= ((size_t)1 << 31)) grid *= 2;
-    if (grid > n_vec) grid = n_vec;
+    // as many pieces as checksum words (4 workgroups per CU); a piece stays below what a 32-bit
+    // offset reaches
+    const size_t grid = ATK_READ_PROBE_WORDS;
     const size_t vec_per_wg = (n_vec + grid - 1) / grid;
+    if (vec_per_wg * 16 >= ((size_t)1 << 31)) return ATK_UNSUPPORTED;
     hipLaunchKernelGGL(read_probe_kernel, dim3((unsigned)grid), dim3(kThreads), 0, (hipStream_t)stream,
                        (const char*)data, n_vec, vec_per_wg, (uint32_t*)checksum);
     return hipGetLastError() == hipSuccess ? ATK_OK : ATK_HIP_ERROR;

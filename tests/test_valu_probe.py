@@ -46,12 +46,17 @@ def test_read_probe_folds_every_word_exactly_once():
         d = torch.from_numpy(w.view(np.int32)).to("cuda:0")
         got = atk.read_probe(d)
         torch.cuda.synchronize()
-        assert int(got.cpu().numpy().view(np.uint32)[0]) == int(np.bitwise_xor.reduce(w)), n_vec
-    # accumulates into the caller's word
-    acc = torch.full((1,), 0x5A5A, dtype=torch.int32, device="cuda:0")
+        g = got.cpu().numpy().view(np.uint32)
+        assert int(np.bitwise_xor.reduce(g)) == int(np.bitwise_xor.reduce(w)), n_vec
+        # piece i is words [i*p, (i+1)*p) with p = ceil(n_vec / words) vectors of four words
+        p = -(-n_vec // atk.READ_PROBE_WORDS) * 4
+        for i in (0, 1, atk.READ_PROBE_WORDS - 1):
+            assert int(g[i]) == int(np.bitwise_xor.reduce(w[i * p:(i + 1) * p], initial=np.uint32(0))), (n_vec, i)
+    # accumulates into the caller's words
+    acc = torch.full((atk.READ_PROBE_WORDS,), 0x5A5A, dtype=torch.int32, device="cuda:0")
     atk.read_probe(torch.zeros(64, dtype=torch.int32, device="cuda:0"), acc)
     torch.cuda.synchronize()
-    assert int(acc.item()) == 0x5A5A
+    assert bool((acc == 0x5A5A).all())
 
 
 def test_read_probe_rejects_bad_arguments():
