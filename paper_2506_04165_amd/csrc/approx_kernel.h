@@ -353,6 +353,11 @@ struct ApproxKernel {
         for (int r = 0; r < R; ++r)
             lane_off[r] = (uint32_t)(((size_t)(row_ok ? g : 0) * p.row_stride + off[r]) * ES);
 
+        // Wavefronts that stream outrank those that sort: a streaming wavefront needs few issue
+        // slots to turn its loads around, and every slot it waits for behind another wavefront's
+        // sorting network is memory bandwidth not asked for (measured on many short rows: 4-8 %).
+        // The sorted-batch lists sort while they stream and gain nothing from it.
+        if constexpr (!BATCHED) __builtin_amdgcn_s_setprio(1);
         int s = 0, s_end = p.nsteps;
         if (p.mode == 2) {
             s = blockIdx.y * p.seg_steps;
@@ -439,6 +444,7 @@ struct ApproxKernel {
         }
         }
 
+        if constexpr (!BATCHED) __builtin_amdgcn_s_setprio(0);
         const int C = p.B * p.Kprime;
         if constexpr (PACKED) {
             // packed variants only run fused, one owner per bucket, at most 1024 candidates per
@@ -608,8 +614,11 @@ struct ApproxKernel {
 
 // The sorted-batch representation holds two K'-lists of 64-bit keys per lane and is only
 // launched with at most 256 lanes per workgroup, which lets it use the larger register budget.
+#ifndef ATK_PACKED_WAVES
+#define ATK_PACKED_WAVES 6      // wavefronts per SIMD the packed variants are compiled for
+#endif
 template <typename DT, int KP, int V, int R, int REP>
-__global__ void __launch_bounds__(REP == 2 ? 256 : 1024, REP == 1 ? 6 : 1) approx_topk_kernel(ApproxParams p) {
+__global__ void __launch_bounds__(REP == 2 ? 256 : 1024, REP == 1 ? ATK_PACKED_WAVES : 1) approx_topk_kernel(ApproxParams p) {
     extern __shared__ uint64_t atk_lds[];
     ApproxKernel<DT, KP, V, R, REP>::run(p, atk_lds);
 }
