@@ -87,6 +87,24 @@ int atk_approx_topk(const void* values, int dtype, int64_t rows, int64_t N, int6
                     void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * atk_approx_topk for callers that cannot allocate device memory or hand over a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments
+ * minus the workspace, same results.  Where atk_approx_topk would use a workspace (few-row
+ * routes, survivors beyond LDS) this entry uses an array of ATK_NOALLOC_SCRATCH_BYTES that is part
+ * of the library's code object (each GPU the library runs on holds its copy until the process
+ * ends); it calls no allocating routine.  Problems whose survivors need more than that
+ * (rows * B * K' * (element size + 4) bytes when B*K' > 16384) are refused with
+ * ATK_WORKSPACE_TOO_SMALL; the few-row routes simply fall back to the single fused launch.
+ * Nothing in the array has to start at zero (every word read was written by the same call), so
+ * nothing is cleared.  All calls on one GPU share the array: calls that may overlap on one GPU
+ * (different streams, other host threads) race on it -- serialise them, or use atk_approx_topk
+ * with workspaces of their own.
+ */
+#define ATK_NOALLOC_SCRATCH_BYTES (16u << 20)
+int atk_approx_topk_noalloc(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride,
+                            int K, int Kprime, int B, void* out_vals, int32_t* out_idx, void* stream);
+
+/*
  * Exact Top-K of every row under the same total order (the comparison system of Section 7; also
  * what the method reduces to at K' = K or B = 1).  Arguments as above.  ATK_UNSUPPORTED: K > 8192.
  */

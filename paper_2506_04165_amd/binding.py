@@ -25,7 +25,7 @@ OP_APPROX_TOPK, OP_TOPK, OP_STAGE1 = 0, 1, 2
 SIZE_MAX = ctypes.c_size_t(-1).value
 
 EXPORTS = [
-    "atk_approx_topk", "atk_topk", "atk_approx_topk_stage1", "atk_workspace_bytes",
+    "atk_approx_topk", "atk_approx_topk_noalloc", "atk_topk", "atk_approx_topk_stage1", "atk_workspace_bytes",
     "atk_expected_recall", "atk_select_params", "atk_recall_params", "atk_set_option", "atk_approx_topk_recall", "atk_describe_plan", "atk_valu_probe", "atk_read_probe",
     "atk_mips_approx_topk", "atk_mips_workspace_bytes", "atk_mips_describe_plan", "atk_mips_select_params", "atk_mips_approx_topk_recall", "atk_status_string", "atk_last_hip_error",
     "atk_version",
@@ -49,6 +49,8 @@ def _load() -> ctypes.CDLL:
     i64, vp, ci, sz = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
     lib.atk_approx_topk.argtypes = [vp, ci, i64, i64, i64, ci, ci, ci, vp, vp, vp, sz, vp]
     lib.atk_approx_topk.restype = ci
+    lib.atk_approx_topk_noalloc.argtypes = [vp, ci, i64, i64, i64, ci, ci, ci, vp, vp, vp]
+    lib.atk_approx_topk_noalloc.restype = ci
     lib.atk_topk.argtypes = [vp, ci, i64, i64, i64, ci, vp, vp, vp, sz, vp]
     lib.atk_topk.restype = ci
     lib.atk_approx_topk_stage1.argtypes = [vp, ci, i64, i64, i64, ci, ci, vp, vp, vp]
@@ -231,6 +233,18 @@ def approx_topk(values: torch.Tensor, K: int, Kprime: int, B: int, out=None, wor
                              _stream_ptr(values.device))
     if st != OK:
         raise AtkError(st, "atk_approx_topk")
+    return out_vals, out_idx
+
+
+def approx_topk_noalloc(values: torch.Tensor, K: int, Kprime: int, B: int, out):
+    """atk_approx_topk_noalloc: the caller's `out` pair is required (this wrapper allocates nothing
+    either), the library's own scratch array stands in for the workspace."""
+    rows, N, stride = _check_input(values)
+    out_vals, out_idx = _check_out(out, rows, K, values.dtype, values.device)
+    st = lib.atk_approx_topk_noalloc(values.data_ptr(), _dtype_code(values), rows, N, stride, K, Kprime, B,
+                                     out_vals.data_ptr(), out_idx.data_ptr(), _stream_ptr(values.device))
+    if st != OK:
+        raise AtkError(st, "atk_approx_topk_noalloc")
     return out_vals, out_idx
 
 

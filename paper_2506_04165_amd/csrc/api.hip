@@ -4,6 +4,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <string>
 
 #include "../../include/atk.h"
@@ -68,6 +69,33 @@ constexpr size_t kSlabMinRowBytes = 128u << 10;
 constexpr size_t kSlabMaxBytes = 256u << 20;
 
 static thread_local std::string g_last_hip_error;
+
+// ---- library-owned scratch for the entry point that may not allocate ------------------------------
+// Device memory that exists from the moment the code object is loaded, one copy per GPU, held
+// until the process ends.  Host code never uses the array's name as an address: the address on
+// the current device is asked for once per device and kept.
+constexpr size_t kScratchBytes = ATK_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];          // per device; filled under g_scratch_mutex
+static std::mutex g_scratch_mutex;
+
+// Address of `scratch` on the current device (NULL and *err set when HIP refuses).
+static void* scratch_on_current_device(hipError_t* err) {
+    *err = hipSuccess;
+    int dev = 0;
+    if ((*err = hipGetDevice(&dev)) != hipSuccess) return nullptr;
+    if (dev < 0 || dev >= kMaxDevices) { *err = hipErrorInvalidDevice; return nullptr; }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        *err = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (*err != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
 
 static int pow2_ceil(int64_t x) { int p = 1; while (p < x) p <<= 1; return p; }
 static int pow2_floor(int64_t x) { int p = 1; while ((int64_t)p * 2 <= x) p <<= 1; return p; }
@@ -609,6 +637,28 @@ int atk_approx_topk(const void* values, int dtype, int64_t rows, int64_t N, int6
     hipError_t e = pl.var->fn(p, pl.grid, pl.block, pl.lds, st);
     if (e != hipSuccess) return hip_fail(e);
     return run_exact(surv_vals, surv_idx, dtype, rows, C, C, K, out_vals, out_idx, st, values, row_stride);
+}
+
+int atk_approx_topk_noalloc(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride,
+                            int K, int Kprime, int B, void* out_vals, int32_t* out_idx, void* stream) {
+    // what the call would need as a workspace, given that at most the scratch array is on offer
+    // (routes that only use a workspace to go faster fall back by themselves when it is too small)
+    int rc = validate_common(values, dtype, rows, N, row_stride);
+    if (rc) return rc;
+    rc = validate_method(N, K, Kprime, B);
+    if (rc) return rc;
+    const Plan& pl = make_plan(values, kernel_dtype(dtype), rows, N, row_stride, K, Kprime, B, false,
+                               kScratchBytes);
+    if (pl.status) return pl.status;
+    if (pl.workspace > kScratchBytes) return ATK_WORKSPACE_TOO_SMALL;   // survivors beyond the array
+    void* ws = nullptr;
+    if (pl.workspace > 0 && rows > 0) {
+        hipError_t e;
+        ws = scratch_on_current_device(&e);
+        if (!ws) return hip_fail(e);
+    }
+    return atk_approx_topk(values, dtype, rows, N, row_stride, K, Kprime, B, out_vals, out_idx,
+                           ws, ws ? kScratchBytes : 0, stream);
 }
 
 int atk_recall_params(int dtype, int64_t rows, int64_t N, int K, double recall_target, int* Kprime_out,

@@ -229,3 +229,12 @@ def test_mips_validation_and_plan():
     st, text = atk.mips_describe_plan(1024, 1 << 20, 128, 1024, 4, 1024)
     assert st == atk.OK and text.startswith("mfma32x32x16") and "workspace=67108864" in text
 
+
+def test_no_alloc_entry_validates_like_the_workspace_entry():
+    f = atk.lib.atk_approx_topk_noalloc
+    assert f(None, 0, 4, 4096, 4096, 32, 4, 64, FAKE, FAKE, None) == atk.INVALID_ARG
+    assert f(FAKE, 0, 4, 4096, 4096, 32, 4, 63, FAKE, FAKE, None) == atk.INVALID_ARG
+    assert f(FAKE, 7, 4, 4096, 4096, 32, 4, 64, FAKE, FAKE, None) == atk.UNSUPPORTED
+    assert f(None, 0, 0, 4096, 4096, 32, 4, 64, None, None, None) == atk.OK
+    # survivors that the library's own scratch array (16 MiB) cannot hold: refused before any launch
+    assert f(FAKE, 0, 80, 131072, 131072, 300, 16, 2048, FAKE, FAKE, None) == atk.WORKSPACE_TOO_SMALL
