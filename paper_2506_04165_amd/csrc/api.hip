@@ -60,6 +60,7 @@ constexpr size_t kLdsBudget = 144 * 1024; // dynamic LDS per workgroup (the CU h
 constexpr int kMaxFusedCandidates = 16384;  // keys of one row that stage 2 can hold in LDS
 constexpr int kExactCap = 16384;         // exact kernel: largest LDS key buffer
 constexpr int kExactMaxK = 8192;
+constexpr int64_t kOnepassMinN = 524288; // exact kernel: shortest row that is tried in one pass
 constexpr int64_t kTargetWaves = 2048;   // 256 CUs x 4 SIMDs x 2 waves: below this the chip idles
 constexpr int kMinSegmentSteps = 8;      // do not cut a row into pieces shorter than this
 constexpr int kMaxSegments = 64;
@@ -128,6 +129,8 @@ struct Options {
     int batch_min_kp = 16;    // list length from which sorted batches are used
     int mips_segments = 0;    // > 0: segments of the database walk of the fused inner-product entry
     int unfused = 0;          // 1: survivors always go through the workspace (two launches)
+    int onepass = 1;          // 0: the exact kernel always takes two passes over a row; 2: one pass
+                              // is tried on short rows too
 };
 static Options g_opt;
 static unsigned g_opt_generation = 1;      // bumped by every change: cached plans are keyed on it
@@ -147,6 +150,7 @@ static void options_from_env_once() {
         o.batch_min_kp = env("ATK_BATCH_MIN_KP", o.batch_min_kp);
         o.mips_segments = env("ATK_MIPS_SEGMENTS", o.mips_segments);
         o.unfused = env("ATK_UNFUSED", o.unfused);
+        o.onepass = env("ATK_ONEPASS", o.onepass);
         // an unusable value is ignored, it never turns a legal call into an error
         if (o.lanes_per_row < 0 || o.lanes_per_row > kMaxLanes || (o.lanes_per_row & (o.lanes_per_row - 1)))
             o.lanes_per_row = 0;
@@ -517,8 +521,22 @@ static int run_exact(const void* values, const int32_t* payload, int dtype, int6
     if (tp.cap < 1024) tp.cap = 1024;
     if (tp.cap > 4096) tp.cap = K <= 2048 ? 4096 : pow2_ceil(2 * (int64_t)K);
     if (tp.cap > kExactCap) tp.cap = kExactCap;
+    int threads = exact_threads(N);
+    // One pass with a rising threshold where it pays: rows long enough that a second pass costs
+    // more than the compactions of the buffer and the drained load pipeline at every look at
+    // the fill (measured: 1.6x faster on rows of 2^20 elements, even at 256000, slower from 65536
+    // down; option "onepass" = 2 forces it for tests).  The buffer must take a round of the whole workgroup (one
+    // vector load per lane) on top of what a compaction leaves, at most 1024 keys.
+    if (g_opt.onepass != 0 && K <= 1024 && (N >= kOnepassMinN || g_opt.onepass == 2) && threads >= 256) {
+        int t1 = threads;
+        if (elem_size(dtype) == 2 && !payload && t1 > 512) t1 = 512;     // eight elements per vector
+        const int round = t1 * (payload ? 1 : 16 / elem_size(dtype));
+        int cap1 = pow2_ceil(1024 + (int64_t)round);
+        if (cap1 < tp.cap) cap1 = tp.cap;
+        if (cap1 <= 8192 && cap1 <= 16 * t1) { tp.cap = cap1; tp.onepass = 1; threads = t1; }
+    }
     tp.out_vals = out_vals; tp.out_idx = out_idx;
-    hipError_t e = launch_topk_exact(tp, dtype, exact_threads(N), st);
+    hipError_t e = launch_topk_exact(tp, dtype, threads, st);
     return e == hipSuccess ? ATK_OK : hip_fail(e);
 }
 
@@ -848,7 +866,7 @@ int atk_set_option(const char* name, int value) {
         {"lanes_per_row", &Options::lanes_per_row}, {"segments", &Options::segments},
         {"slab", &Options::slab}, {"packed", &Options::packed}, {"subwave", &Options::subwave},
         {"batch_min_kp", &Options::batch_min_kp}, {"mips_segments", &Options::mips_segments},
-        {"unfused", &Options::unfused},
+        {"unfused", &Options::unfused}, {"onepass", &Options::onepass},
     };
     for (const Entry& e : entries) {
         if (std::strcmp(name, e.name) != 0) continue;

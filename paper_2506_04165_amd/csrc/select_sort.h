@@ -502,6 +502,102 @@ __device__ __noinline__ void wg_sort_merge_topk(uint64_t* keys, int n, int K) {
     else                      wg_sort_merge_runs<8>(keys, n, K);   // (ranking 8 keys per lane: slower)
 }
 
+// A key klo among the n keys in LDS `keys` (key 0 = empty; at least K real keys; K at most
+// kWaveSortMaxKeys) such that the keys >= klo number at least K and at most kWaveSortMaxKeys --
+// usually at most 2K + 64: the K greatest keys are among them and they fit one sort.  Returns 0
+// if no such key was found (cannot happen; callers fall back to sorting everything).  Called by
+// every thread of the workgroup, ends with a barrier; `scratch` as for wg_topk_from_lds (the
+// histogram and a buffer of kSideSortKeys keys alias its start).
+__device__ __noinline__ uint64_t wg_select_threshold(const uint64_t* keys, int n, int K, void* scratch) {
+    const int tid = threadIdx.x;
+    uint64_t* buf = (uint64_t*)scratch;
+    uint32_t* hist = (uint32_t*)scratch;                          // aliases buf
+    uint32_t* ctl = (uint32_t*)((char*)scratch + kWaveSortMaxKeys * 8);
+    // The keys are the survivors of a first selection and sit in a narrow band of values:
+    // digits taken from fixed bit positions would put most of them into one bin, pass after
+    // pass (and a band that straddles a power of two shares no leading bits at all).  So the
+    // band is measured first (greatest and least value present) and every pass cuts the
+    // interval of keys that can still hold the K-th one into equal bins, 2048 at most: keys
+    // are compared as 64-bit integers, value word first, so the bins are intervals of values
+    // and, inside one value, of indices (ties resolve toward the lowest index).
+    const int lane = tid & (kWave - 1);
+    if (tid == 0) { ctl[20] = 0u; ctl[21] = 0xffffffffu; }
+    __syncthreads();
+    uint32_t vhi = 0u, vlo = 0xffffffffu;
+    for_each_lds_key(keys, n, [&](uint64_t key) {
+        if (key != 0) {
+            const uint32_t v = (uint32_t)(key >> 32);
+            vhi = max(vhi, v);
+            vlo = min(vlo, v);
+        }
+    });
+    for (int o = kWave / 2; o >= 1; o >>= 1) {
+        vhi = max(vhi, (uint32_t)__shfl_xor((int)vhi, o, kWave));
+        vlo = min(vlo, (uint32_t)__shfl_xor((int)vlo, o, kWave));
+    }
+    if (lane == 0) { atomicMax(&ctl[20], vhi); atomicMin(&ctl[21], vlo); }
+    __syncthreads();
+    vhi = ctl[20]; vlo = ctl[21];
+    // every real key lies in [klo, khi] (a real key is never 0: its low word is ~index)
+    uint64_t klo = ((uint64_t)vlo << 32) | 1ull, khi = ((uint64_t)vhi << 32) | 0xffffffffull;
+    int need = K, certain = 0;
+    bool fits = false;
+    for (int pass = 0; !fits; ++pass) {
+        const uint64_t span = khi - klo;
+        const int span_bits = span ? 64 - __clzll((long long)span) : 0;
+        const int shift = span_bits > kSelectBinBits ? span_bits - kSelectBinBits : 0;
+        uint32_t digit, above, count;
+        lds_select_bin(keys, n, klo, khi, shift, need, hist, ctl, digit, above, count);
+        certain += (int)above;
+        need -= (int)above;
+        klo += (uint64_t)digit << shift;
+        const uint64_t bin_span = (1ull << shift) - 1ull;          // (klo + bin_span may wrap)
+        if (khi - klo > bin_span) khi = klo + bin_span;
+        // stop when members + candidates fit one sort; prefer a sort of at most 2K keys.
+        // With shift == 0 a bin is one key, so the loop ends there at the latest.
+        fits = certain + (int)count <= kWaveSortMaxKeys &&
+               (certain + (int)count <= 2 * K + 64 || pass >= 2 || shift == 0);
+        if (!fits && (int)count <= kSideSortKeys) {
+            // The bin that holds the K-th key is small: rather than cut it again, sort its
+            // keys in one wavefront and read the K-th key off; what remains is "every key
+            // at or above it", exactly K of them.
+            if (tid == 0) ctl[3] = 0;
+            __syncthreads();
+            for_each_lds_key(keys, n, [&](uint64_t key) {
+                if (key >= klo && key <= khi) {
+                    const uint32_t slot = atomicAdd(&ctl[3], 1u);
+                    if (slot < (uint32_t)kSideSortKeys) buf[slot] = key;
+                }
+            });
+            __syncthreads();
+            if (tid < kWave) {
+                constexpr int RS = kSideSortKeys / kWave;
+                uint64_t k[RS];
+#pragma unroll
+                for (int j = 0; j < RS; ++j) {
+                    const int i = j * kWave + lane;
+                    k[j] = i < (int)count ? buf[i] : 0;
+                }
+                if (count <= (uint32_t)kWave) {      // usually: a handful of keys
+                    uint64_t one[1] = {k[0]};
+                    WaveSort<1>::sort(one);
+                    buf[lane] = one[0];
+                } else {
+                    WaveSort<RS>::sort(k);
+#pragma unroll
+                    for (int j = 0; j < RS; ++j) buf[lane * RS + j] = k[j];
+                }
+            }
+            __syncthreads();
+            klo = buf[need - 1];
+            fits = true;
+            __syncthreads();          // buf is filled again by the caller
+        }
+        if (shift == 0 && !fits) return 0;           // cannot happen (see above); ends the loop
+    }
+    return klo;
+}
+
 // Top-K (descending) of the n keys in LDS `keys` (n a power of two, key 0 = empty, at least K
 // real keys), written decoded to out_*[out_base + 0..K).  Called by every thread of the
 // workgroup; `scratch` is kSelectScratchBytes of LDS (unused when n <= 256): a buffer of
@@ -532,91 +628,9 @@ __device__ __forceinline__ void wg_topk_from_lds(uint64_t* keys, int n, int K, v
     }
     if (K <= kWaveSortMaxKeys) {
         uint64_t* buf = (uint64_t*)scratch;
-        uint32_t* hist = (uint32_t*)scratch;                          // aliases buf
         uint32_t* ctl = (uint32_t*)((char*)scratch + kWaveSortMaxKeys * 8);
-        // The keys are the survivors of a first selection and sit in a narrow band of values:
-        // digits taken from fixed bit positions would put most of them into one bin, pass after
-        // pass (and a band that straddles a power of two shares no leading bits at all).  So the
-        // band is measured first (greatest and least value present) and every pass cuts the
-        // interval of keys that can still hold the K-th one into equal bins, 2048 at most: keys
-        // are compared as 64-bit integers, value word first, so the bins are intervals of values
-        // and, inside one value, of indices (ties resolve toward the lowest index).
-        const int lane = tid & (kWave - 1);
-        if (tid == 0) { ctl[20] = 0u; ctl[21] = 0xffffffffu; }
-        __syncthreads();
-        uint32_t vhi = 0u, vlo = 0xffffffffu;
-        for_each_lds_key(keys, n, [&](uint64_t key) {
-            if (key != 0) {
-                const uint32_t v = (uint32_t)(key >> 32);
-                vhi = max(vhi, v);
-                vlo = min(vlo, v);
-            }
-        });
-        for (int o = kWave / 2; o >= 1; o >>= 1) {
-            vhi = max(vhi, (uint32_t)__shfl_xor((int)vhi, o, kWave));
-            vlo = min(vlo, (uint32_t)__shfl_xor((int)vlo, o, kWave));
-        }
-        if (lane == 0) { atomicMax(&ctl[20], vhi); atomicMin(&ctl[21], vlo); }
-        __syncthreads();
-        vhi = ctl[20]; vlo = ctl[21];
-        // every real key lies in [klo, khi] (a real key is never 0: its low word is ~index)
-        uint64_t klo = ((uint64_t)vlo << 32) | 1ull, khi = ((uint64_t)vhi << 32) | 0xffffffffull;
-        int need = K, certain = 0;
-        bool fits = false;
-        for (int pass = 0; !fits; ++pass) {
-            const uint64_t span = khi - klo;
-            const int span_bits = span ? 64 - __clzll((long long)span) : 0;
-            const int shift = span_bits > kSelectBinBits ? span_bits - kSelectBinBits : 0;
-            uint32_t digit, above, count;
-            lds_select_bin(keys, n, klo, khi, shift, need, hist, ctl, digit, above, count);
-            certain += (int)above;
-            need -= (int)above;
-            klo += (uint64_t)digit << shift;
-            const uint64_t bin_span = (1ull << shift) - 1ull;          // (klo + bin_span may wrap)
-            if (khi - klo > bin_span) khi = klo + bin_span;
-            // stop when members + candidates fit one sort; prefer a sort of at most 2K keys.
-            // With shift == 0 a bin is one key, so the loop ends there at the latest.
-            fits = certain + (int)count <= kWaveSortMaxKeys &&
-                   (certain + (int)count <= 2 * K + 64 || pass >= 2 || shift == 0);
-            if (!fits && (int)count <= kSideSortKeys) {
-                // The bin that holds the K-th key is small: rather than cut it again, sort its
-                // keys in one wavefront and read the K-th key off; what remains is "every key
-                // at or above it", exactly K of them.
-                if (tid == 0) ctl[3] = 0;
-                __syncthreads();
-                for_each_lds_key(keys, n, [&](uint64_t key) {
-                    if (key >= klo && key <= khi) {
-                        const uint32_t slot = atomicAdd(&ctl[3], 1u);
-                        if (slot < (uint32_t)kSideSortKeys) buf[slot] = key;
-                    }
-                });
-                __syncthreads();
-                if (tid < kWave) {
-                    constexpr int RS = kSideSortKeys / kWave;
-                    uint64_t k[RS];
-#pragma unroll
-                    for (int j = 0; j < RS; ++j) {
-                        const int i = j * kWave + lane;
-                        k[j] = i < (int)count ? buf[i] : 0;
-                    }
-                    if (count <= (uint32_t)kWave) {      // usually: a handful of keys
-                        uint64_t one[1] = {k[0]};
-                        WaveSort<1>::sort(one);
-                        buf[lane] = one[0];
-                    } else {
-                        WaveSort<RS>::sort(k);
-#pragma unroll
-                        for (int j = 0; j < RS; ++j) buf[lane * RS + j] = k[j];
-                    }
-                }
-                __syncthreads();
-                klo = buf[need - 1];
-                fits = true;
-                __syncthreads();          // buf is filled again below
-            }
-            if (shift == 0 && !fits) break;              // cannot happen (see above); ends the loop
-        }
-        if (fits) {
+        const uint64_t klo = wg_select_threshold(keys, n, K, scratch);
+        if (klo != 0) {
             if (tid == 0) ctl[3] = 0;
             __syncthreads();
             // certain members and candidates -> buf (the histogram is dead by now)

@@ -13,6 +13,8 @@ struct TopkParams {
     int64_t orig_stride;      // ... and their stride (read only to tell -0.0 from +0.0)
     int rows, N, K;
     int cap;                  // LDS key buffer capacity (power of two, >= 1024, > K)
+    int onepass;              // try the single pass with a rising threshold first (needs K <= 1024,
+                              // cap >= 1024 + one round of the workgroup, cap <= 16 * threads)
     void* out_vals;
     int32_t* out_idx;
 };

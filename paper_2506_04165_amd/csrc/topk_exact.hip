@@ -16,7 +16,16 @@
 //      toward the lower index);
 //   4. a last pass gathers certain members and prefix matches into LDS, where the same
 //      selection-then-wave-sort as in the fused kernel's stage 2 picks and orders the K.
-// Two passes over the row for ordinary data: at most half of the HBM roofline by design.
+// Two passes over the row for ordinary data: at most half of the HBM roofline.
+//
+// Rows of ordinary data are first tried in ONE pass (`onepass` below): the row is streamed once,
+// keys above a rising threshold are collected in LDS, and whenever the buffer is half full a
+// selection finds a key with at least K keys at or above it, which becomes the new threshold and
+// everything below it is dropped.  For data in random order the keys that pass after the first
+// few thousand elements are few (about K ln(N / seen)), so the buffer is compacted a handful of
+// times per row.  Data that keeps beating the threshold (ascending order) would overflow the
+// buffer between two compactions: the attempt is then abandoned and the row done in two passes
+// as above, which does not depend on the order of the data.
 #include "atk_device.h"
 #include "select_sort.h"
 #include "topk_exact.h"
@@ -74,6 +83,100 @@ __device__ __forceinline__ void for_each_element(const char* rowp, int begin, in
     }
 }
 
+// One pass with a rising threshold.  On success the K greatest keys of the row are among the
+// `count` keys at the start of `buf` and true is returned; false (all threads alike) when the
+// buffer overflowed, with nothing written anywhere but LDS.
+//   buf      p.cap keys;  scratch: kSelectScratchBytes;  ctl: control words (3: fill, 5: overflow)
+// Until a threshold exists every element is kept, and the row is taken one round of the whole
+// workgroup (a 16-byte vector, or one element, per thread) at a time; after that in stretches
+// sized by how many keys are expected to pass.
+template <typename DT, bool PAYLOAD, bool VEC>
+__device__ __forceinline__ bool onepass(const TopkParams& p, const char* rowp, const int32_t* payload,
+                                        uint64_t* buf, void* scratch, uint32_t* ctl, int& count) {
+    const int tid = threadIdx.x, T = blockDim.x, lane = tid & (kWave - 1);
+    const int N = p.N, cap = p.cap;
+    constexpr int VE = VEC ? 16 / elem<DT>::size : 1;
+    constexpr int kMaxRounds = 64;
+    auto index_of = [&](int n) -> uint32_t { return PAYLOAD ? (uint32_t)payload[n] : (uint32_t)n; };
+    if (tid == 0) { ctl[3] = 0; ctl[5] = 0; }
+    __syncthreads();
+    uint64_t thr = 0;                       // keys at or below it cannot be among the K greatest
+    const int round = T * VE;               // elements one round of the workgroup covers
+    int fill = 0;
+    int seen_at_thr = 0;                    // elements seen when the threshold was last raised
+    for (int done = 0; done < N;) {
+        // How far to go before looking at the fill again.  Without a threshold every element is
+        // kept: one round.  With one, an element of data in random order passes with probability
+        // about K / seen_at_thr: go as far as is expected to fill half of the room that is left.
+        int64_t take = round;
+        if (seen_at_thr > 0) {
+            take = (int64_t)((cap - fill) / 2) * seen_at_thr / p.K / round * round;
+            if (take < round) take = round;
+            if (take > (int64_t)kMaxRounds * round) take = (int64_t)kMaxRounds * round;
+            if (take > 4 * (int64_t)done) take = 4 * (int64_t)done;   // data in ascending order shows early
+        }
+        const int end = (int)min((int64_t)N, (int64_t)done + take);
+        const uint32_t thr_hi = (uint32_t)(thr >> 32);
+        for_each_element<DT, VEC>(rowp, done, end, [&](uint32_t b, int n) {
+            const uint32_t ord = elem<DT>::ordered(b);
+            bool pass = ord >= thr_hi;                      // cheap reject on the value word
+            uint64_t key = 0;
+            if (pass) {
+                key = ((uint64_t)ord << 32) | (uint32_t)(~index_of(n));
+                pass = key > thr;
+            }
+            // one LDS atomic per wavefront: the lanes that keep their key take consecutive slots
+            const uint64_t m = __ballot(pass);
+            if (m != 0) {
+                const int leader = __ffsll((unsigned long long)m) - 1;
+                uint32_t base = 0;
+                if (lane == leader) base = atomicAdd(&ctl[3], (uint32_t)__popcll(m));
+                base = (uint32_t)__shfl((int)base, leader, kWave);
+                if (pass) {
+                    const uint32_t slot = base + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+                    if (slot < (uint32_t)cap) buf[slot] = key;
+                    else ctl[5] = 1;                        // no room: the attempt has failed
+                }
+            }
+        });
+        done = end;
+        __syncthreads();
+        const bool overflow = ctl[5] != 0;
+        fill = (int)ctl[3];
+        __syncthreads();                    // (ctl[3] is rewritten below)
+        if (overflow) return false;
+        // (the second condition keeps a round of the warm-up, in which every element may pass,
+        // from overflowing: a compaction leaves at most kWaveSortMaxKeys keys and the buffer has
+        // room for that many plus a round)
+        if (done < N && fill > p.K && (fill > cap / 2 || (seen_at_thr == 0 && fill + round > cap))) {
+            // new threshold: a key with at least K and at most kWaveSortMaxKeys keys at or above
+            // it; the keys below it leave the buffer (through registers: the buffer is compacted
+            // in place)
+            const uint64_t klo = wg_select_threshold(buf, fill, p.K, scratch);
+            if (klo == 0) return false;
+            constexpr int kMaxPerThread = 16;               // cap <= 16 * T is checked by the launcher
+            uint64_t mine[kMaxPerThread];
+#pragma unroll
+            for (int j = 0; j < kMaxPerThread; ++j) {
+                const int i = tid + j * T;
+                mine[j] = (i < fill) ? buf[i] : 0;
+            }
+            if (tid == 0) ctl[3] = 0;
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < kMaxPerThread; ++j)
+                if (mine[j] >= klo && mine[j] != 0) buf[atomicAdd(&ctl[3], 1u)] = mine[j];
+            __syncthreads();
+            fill = (int)ctl[3];
+            thr = klo - 1;                  // keys are distinct: "above klo - 1" is "at or above klo"
+            seen_at_thr = done;
+            __syncthreads();
+        }
+    }
+    count = fill;
+    return true;
+}
+
 template <typename DT, bool PAYLOAD, bool VEC>
 __global__ void __launch_bounds__(1024) topk_exact_kernel(TopkParams p) {
     extern __shared__ uint64_t lds64[];
@@ -88,6 +191,19 @@ __global__ void __launch_bounds__(1024) topk_exact_kernel(TopkParams p) {
     const int32_t* payload = PAYLOAD ? p.payload + (size_t)row * p.row_stride : nullptr;
     const int N = p.N;
     auto index_of = [&](int n) -> uint32_t { return PAYLOAD ? (uint32_t)payload[n] : (uint32_t)n; };
+
+    if (p.onepass) {
+        int count = 0;
+        if (onepass<DT, PAYLOAD, VEC>(p, rowp, payload, lds64, scratch, ctl, count)) {
+            const int n1 = next_pow2(count);
+            for (int i = count + tid; i < n1; i += T) lds64[i] = 0;
+            __syncthreads();
+            const char* bits_row1 = PAYLOAD ? (const char*)p.orig_values + (size_t)row * p.orig_stride * elem<DT>::size : rowp;
+            wg_topk_from_lds<DT>(lds64, n1, p.K, scratch, bits_row1, p.out_vals, p.out_idx, (int64_t)row * p.K);
+            return;
+        }
+        __syncthreads();
+    }
 
     uint64_t prefix = 0, mask = 0;
     int need = p.K;          // members still to be taken from the keys matching the prefix

@@ -320,6 +320,37 @@ def test_exact_topk_large_k(atk, N, K):
     check_exact(atk, workloads.heavy_ties(2, N, seed=N % 83, symbols=3).to(torch.bfloat16), K)
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.int32])
+def test_exact_one_pass_with_rising_threshold_and_its_fallback(atk, knobs, dtype):
+    # the exact kernel tries long rows in one pass (keys above a rising threshold collected in LDS,
+    # compacted when half full) and falls back to two passes when the buffer overflows; option
+    # "onepass" = 2 asks for the attempt on short rows as well.  Random order (the attempt
+    # succeeds), ascending order (every element beats the threshold: overflow, fallback),
+    # descending order (nothing passes after the first round), dense ties, one value everywhere.
+    knobs.set("onepass", 2)
+    rng = np.random.default_rng(11)
+    for N, K in [(8192, 1), (8192, 1024), (20000, 64), (65536 + 17, 300), (300000, 1000), (1 << 20, 128),
+                 (131072 + 8, 1024)]:
+        base = torch.randn(5, N, generator=torch.Generator().manual_seed(N + K))
+        rows = [base[0], torch.sort(base[1]).values, torch.sort(base[2], descending=True).values,
+                torch.round(base[3] * 2) / 2, torch.full((N,), 1.5)]
+        x = torch.stack(rows)
+        if dtype == torch.int32:
+            x = (x * 1000).to(torch.int32)
+        else:
+            x = x.to(dtype)
+        print(f"one pass: {dtype} N={N} K={K}", flush=True)
+        check_exact(atk, x, K)
+    # survivor mode (the unfused route's second launch reads values and positions from the workspace)
+    knobs.set("unfused", 1)
+    for rows, N, K, Kp, B in [(6, 65536, 500, 4, 4096), (3, 1 << 18, 1024, 2, 16384), (4, 32768, 100, 1, 8192)]:
+        x = workloads.gaussian(rows, N, seed=K)
+        x[1] = torch.sort(x[1]).values
+        x = x.to(dtype) if dtype != torch.int32 else (x * 1000).to(torch.int32)
+        assert atk.describe_plan(x.dtype, rows, N, K, Kp, B)[1].startswith("unfused")
+        check_approx(atk, x, K, Kp, B)
+
+
 def test_long_rows_sharing_a_wavefront(atk):
     # three buckets and rows of 3 * 2^24 elements: the rows a workgroup may address from its first
     # row by 32-bit offsets do not fill a wavefront.  Expected output from planted values (the
