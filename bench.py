@@ -227,7 +227,10 @@ def bench_table1_shape():
     out = (torch.empty((rows, K), device=dev), torch.empty((rows, K), dtype=torch.int32, device=dev))
     ballast = torch.randn(8192, 8192, device=dev)
     res = []
-    for B, Kp in [(1024, 4), (2048, 2), (4096, 2)]:
+    paper_us = {(1024, 4): 27, (2048, 2): 27, (4096, 2): 45, (8192, 1): 42, (16384, 1): 77, (65536, 1): 326}
+    for B, Kp in [(1024, 4), (2048, 2), (4096, 2), (8192, 1), (16384, 1), (65536, 1)]:
+        need = atk.workspace_bytes(atk.OP_APPROX_TOPK, torch.float32, rows, N, K, Kp, B)
+        assert need <= ws.numel()
         call = lambda: atk.approx_topk(x, K, Kp, B, out=out, workspace=ws)
         for _ in range(20):
             call()
@@ -242,7 +245,8 @@ def bench_table1_shape():
         torch.cuda.synchronize()
         res.append({"B": B, "Kprime": Kp, "us_per_call": start.elapsed_time(end) * 1e3 / calls,
                     "plan": atk.describe_plan(torch.float32, rows, N, K, Kp, B)[1],
-                    "paper_tpuv5e_us": {(1024, 4): 27, (2048, 2): 27, (4096, 2): 45}[(B, Kp)]})
+                    "expected_recall": atk.expected_recall(N, B, K, Kp),
+                    "paper_tpuv5e_us": paper_us[(B, Kp)]})
     ex = lambda: atk.topk(x, K, out=out)
     for _ in range(5):
         ex()
@@ -328,6 +332,36 @@ def bench_mips_fused(steps, warmup):
             "paper_tpu_v5e_ms": {"K'=4 fused total": 10, "K'=4 unfused total": 22}}
 
 
+def bench_unfused(steps, warmup):
+    """Survivors beyond LDS (B*K' > 16384): stage 1 writes them to the workspace, rows cut along
+    the bucket axis, and the exact kernel selects among them (the paper's unfused implementation:
+    a stage-1 kernel, then a separate stage 2).  64 rows x 2^20 fp32, K = 1024."""
+    import torch
+    from paper_2506_04165_amd import binding as atk, workloads
+    rows, N, K = 64, 1 << 20, 1024
+    dev = "cuda:0"
+    copies = 9
+    xs = [workloads.gaussian(rows, N, seed=40 + c, device=dev) for c in range(copies)]
+    out = (torch.empty((rows, K), device=dev), torch.empty((rows, K), dtype=torch.int32, device=dev))
+    alg = algorithmic_bytes(rows, N, K, 4)
+    res = []
+    for B, Kp in [(8192, 4), (16384, 2)]:
+        st, plan = atk.describe_plan(torch.float32, rows, N, K, Kp, B)
+        need = atk.workspace_bytes(atk.OP_APPROX_TOPK, torch.float32, rows, N, K, Kp, B)
+        ws = torch.empty(need, dtype=torch.uint8, device=dev)
+        t = time_steps(lambda i: atk.approx_topk(xs[i], K, Kp, B, out=out, workspace=ws), copies, steps, warmup)
+        sec = t["kernel_ms_median"] * 1e-3
+        survivors = rows * B * Kp * 8          # written by stage 1, read again by stage 2
+        res.append({"B": B, "Kprime": Kp, "plan": plan, "us_per_call_median": sec * 1e6,
+                    "us_per_call_min": t["kernel_ms_min"] * 1e3,
+                    "algorithmic_bytes": alg, "survivor_bytes_written_and_read": 2 * survivors,
+                    "achieved_gbps": alg / sec / 1e9, "frac_of_peak": alg / sec / 1e9 / HBM_PEAK_GBPS,
+                    "expected_recall": atk.expected_recall(N, B, K, Kp)})
+    ex = time_steps(lambda i: atk.topk(xs[i], K, out=out), copies, max(5, steps // 4), 2)
+    return {"workload": f"{rows} rows x N={N} f32 (i.i.d. N(0,1)), K={K}: B*K' = 32768 survivors per row",
+            "configs": res, "exact_topk_us": ex["kernel_ms_median"] * 1e3}
+
+
 def cpu_baseline(name, xd, B, Kp):
     """The CPU oracle, as it stands, on a bounded sample of rows of the same workload."""
     from oracle import oracle
@@ -365,6 +399,8 @@ def main():
     ap.add_argument("--no-mips", action="store_true", help="skip the matmul-fused section")
     ap.add_argument("--table1-only", action="store_true",
                     help="run only the Table 1 shape (8 x 262144, K=1024) and print it (for profiling)")
+    ap.add_argument("--unfused-only", action="store_true",
+                    help="run only the unfused-route section and print it (for profiling those kernels)")
     ap.add_argument("--mips-only", action="store_true",
                     help="run only the matmul-fused section and print it (for profiling that kernel)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -395,6 +431,9 @@ def main():
 
     if args.table1_only:
         print(json.dumps({"table1_shape": bench_table1_shape()}))
+        return
+    if args.unfused_only:
+        print(json.dumps({"unfused": bench_unfused(max(10, args.steps // 2), 5)}))
         return
     if args.mips_only:
         print(json.dumps({"mips_fused": bench_mips_fused(max(10, args.steps // 5), max(5, args.warmup // 10))}))
@@ -457,6 +496,7 @@ def main():
     if not (args.no_mips or args.workload or args.headline_only):
         line["mips_fused"] = bench_mips_fused(max(10, args.steps // 5), max(5, args.warmup // 10))
         line["table1_shape"] = bench_table1_shape()
+        line["unfused"] = bench_unfused(max(10, args.steps // 2), 5)
     print(json.dumps(line))
 
 

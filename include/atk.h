@@ -259,7 +259,7 @@ int atk_read_probe(const void* data, size_t bytes, void* checksum, void* stream)
  * them.  Process-wide; change them only while no call is in flight.  value < 0 restores the
  * default.  Initial values may be given in the environment (read once, at the first call that
  * plans a launch): ATK_LANES_PER_ROW, ATK_SEGMENTS, ATK_SLAB, ATK_NO_PACKED=1, ATK_NO_SUBWAVE=1,
- * ATK_BATCH_MIN_KP, ATK_MIPS_SEGMENTS, ATK_UNFUSED, ATK_ONEPASS.
+ * ATK_BATCH_MIN_KP, ATK_MIPS_SEGMENTS, ATK_UNFUSED, ATK_CHUNKED, ATK_ONEPASS.
  *   "lanes_per_row"  0 = planner's choice, else a power of two <= 1024: lanes that share one row
  *   "segments"       n > 0 forces n row segments on the split route
  *   "slab"           0 never / 1 planner's choice / 2 whenever possible: slabs of 32 buckets per
@@ -269,6 +269,8 @@ int atk_read_probe(const void* data, size_t bytes, void* checksum, void* stream)
  *   "batch_min_kp"   list length from which sorted batches are used (default 16)
  *   "mips_segments"  n > 0 forces n segments of the database walk in atk_mips_approx_topk
  *   "unfused"        1 sends the survivors of every call through the workspace (two launches)
+ *   "chunked"        1: when survivors go through the workspace, every bucket chunk's workgroup runs
+ *                    stage 2 on its own survivors and passes on only its K greatest
  *   "onepass"        exact kernel: 0 always two passes over a row, 1 (default) one pass with a rising
  *                    threshold on long rows, 2 on every row it can handle
  * Returns ATK_INVALID_ARG for an unknown name or an unusable value.  Host only.

@@ -129,6 +129,9 @@ struct Options {
     int batch_min_kp = 16;    // list length from which sorted batches are used
     int mips_segments = 0;    // > 0: segments of the database walk of the fused inner-product entry
     int unfused = 0;          // 1: survivors always go through the workspace (two launches)
+    int chunked = 0;          // 1: survivors beyond LDS: every bucket chunk's workgroup runs stage 2 on its
+                              // own survivors and passes on its K greatest (smaller workspace; measured
+                              // no faster than passing all survivors on, slower when rows are few)
     int onepass = 1;          // 0: the exact kernel always takes two passes over a row; 2: one pass
                               // is tried on short rows too
 };
@@ -151,6 +154,7 @@ static void options_from_env_once() {
         o.mips_segments = env("ATK_MIPS_SEGMENTS", o.mips_segments);
         o.unfused = env("ATK_UNFUSED", o.unfused);
         o.onepass = env("ATK_ONEPASS", o.onepass);
+        o.chunked = env("ATK_CHUNKED", o.chunked);
         // an unusable value is ignored, it never turns a legal call into an error
         if (o.lanes_per_row < 0 || o.lanes_per_row > kMaxLanes || (o.lanes_per_row & (o.lanes_per_row - 1)))
             o.lanes_per_row = 0;
@@ -191,7 +195,9 @@ struct Plan {
     size_t lds = 0;
     size_t workspace = 0;       // bytes the plan needs (0: none)
     int nseg = 1, seg_steps = 0;  // > 1: rows are cut into segments, finished by a second launch
-    int chunk = 0, nchunk = 1;    // > 0: survivors to memory, a workgroup takes `chunk` buckets of a row
+    int chunk = 0, nchunk = 1;    // > 0: a workgroup takes `chunk` buckets of a row over all steps
+    int chunk_k = 0;              // > 0: ... and runs stage 2 on them itself, leaving its chunk_k greatest
+                                  // (of which the exact kernel picks the row's K); 0: all survivors leave
     int slab_w = 0;             // > 0: workgroups take slabs of this many buckets (see below)
 };
 
@@ -262,11 +268,18 @@ static Plan compute_plan(const void* values, int dtype, int64_t rows, int64_t N,
             }
             G <<= 1;
         }
-        if (through_memory && G >= 64) {
+        if ((through_memory || stage1_only) && G >= 64) {
             // nothing is merged inside the workgroup on this route, so cutting a row along the
             // bucket axis costs nothing: smaller workgroups until the chip is full
             auto waves = [&] { return rows * (int64_t)((B + G * NL - 1) / (G * NL)) * (G / 64); };
+            // chunks whose survivors fit LDS can run stage 2 themselves (see chunk_k below)
+            while (through_memory && g_opt.chunked != 0 && (NL > 1 || G > 256) &&
+                   pow2_ceil((int64_t)G * NL * Kp) > kMaxFusedCandidates) {
+                if (NL > 1) NL >>= 1; else G >>= 1;
+            }
             while (waves() < kTargetWaves && (NL > 1 || G > 256)) {
+                // (a chunk that runs its own stage 2 should hold a few times K survivors)
+                if (through_memory && g_opt.chunked != 0 && (int64_t)G * NL * Kp < 8 * (int64_t)K) break;
                 if (NL > 1) NL >>= 1; else G >>= 1;
             }
             chunked = G * NL < B;
@@ -286,6 +299,9 @@ static Plan compute_plan(const void* values, int dtype, int64_t rows, int64_t N,
     bool packed_ok = dtype == ATK_BF16 && N <= 65536 && !stage1_only && !through_memory && owners == 1 && G >= 64 &&
                      pow2_ceil((int64_t)B * Kp) <= kWaveSortMaxKeys &&
                      g_opt.packed != 0;
+    // sixteen packed lists in one lane: two wavefronts with eight lists per lane stream the row
+    // faster (measured on 16384 rows of 14336 with 1024 buckets: 95 -> 90 us)
+    if (packed_ok && G == 64 && NL * KP >= 16 && NL >= 2 && g_opt.lanes_per_row == 0) { G = 128; NL >>= 1; }
     if (packed_ok && G == 64 && NL == 1 && is_pow2(B) && rows >= 1024 &&
         g_opt.lanes_per_row == 0 && g_opt.subwave != 0) {
         // many short rows with only 64 buckets: rather than 2-byte loads from 64 lanes, a wavefront
@@ -310,11 +326,19 @@ static Plan compute_plan(const void* values, int dtype, int64_t rows, int64_t N,
     }
     const int V = pl.var->V;
     if (chunked && G * NL < B) { pl.chunk = G * NL; pl.nchunk = (B + pl.chunk - 1) / pl.chunk; }
+    // Survivors beyond LDS, option "chunked": when the chunks divide the row evenly and each holds
+    // at least 2K survivors that fit LDS, a chunk's workgroup runs stage 2 on its own survivors and only its K
+    // greatest leave (a row's K greatest are among its chunks' K greatest); the exact kernel then
+    // selects among nchunk*K instead of B*K'.
+    const bool chunk_fused = through_memory && g_opt.chunked != 0 && pl.chunk > 0 && G >= 256 && B % pl.chunk == 0 &&
+                             pow2_ceil((int64_t)pl.chunk * Kp) <= kMaxFusedCandidates &&
+                             (int64_t)pl.chunk * Kp >= 2 * (int64_t)K && !pl.var->packed() && pl.var->rep != 2;
+    if (chunk_fused) pl.chunk_k = K;
     pl.owners = owners;
     pl.S = owners > 1 ? G * V : B;
     pl.nsteps = (int)(N / pl.S);
     pl.seg = owners > 1 ? pow2_ceil((int64_t)owners * KP) : 0;
-    pl.Cpad = pow2_ceil((int64_t)B * Kp);
+    pl.Cpad = pow2_ceil((int64_t)(chunk_fused ? pl.chunk : B) * Kp);
 
     // rows per workgroup: fill 256 lanes when one row needs fewer
     int rpw = G >= 256 ? 1 : 256 / G;
@@ -322,7 +346,7 @@ static Plan compute_plan(const void* values, int dtype, int64_t rows, int64_t N,
     // LDS: [candidates of every row of the workgroup][auxiliary: partial lists of shared
     // buckets, later reused as scratch of the selection]
     const bool wave_tail = !stage1_only && G >= 64 && pl.Cpad <= kWaveSortMaxKeys;
-    const bool to_memory = stage1_only || through_memory;
+    const bool to_memory = stage1_only || (through_memory && !chunk_fused);
     auto lds_for = [&](int r) {
         size_t cand = 0, aux = 0;
         if (owners > 1) { cand = (size_t)r * pl.Cpad; aux = (size_t)r * B * pl.seg; }
@@ -353,10 +377,11 @@ static Plan compute_plan(const void* values, int dtype, int64_t rows, int64_t N,
     pl.fused = !to_memory && pl.lds <= kLdsBudget;
     if (pl.lds > kLdsBudget) { pl.status = ATK_UNSUPPORTED; return pl; }   // (cannot happen)
     if (through_memory) {
-        // survivors go through memory: int32 indices, then values (input dtype); the exact
-        // kernel then selects among them
-        pl.workspace = (size_t)rows * B * Kp * (es + 4);
+        // survivors (or every chunk's K greatest) go through memory: int32 indices, then values
+        // (input dtype); the exact kernel then selects among them
+        pl.workspace = (size_t)rows * (chunk_fused ? (size_t)pl.nchunk * K : (size_t)B * Kp) * (es + 4);
         if (K > kExactMaxK) { pl.status = ATK_UNSUPPORTED; return pl; }
+        pl.fused = false;
     }
 
     // Very few rows: give every workgroup a slab of 32 buckets of one row over all steps, with m
@@ -645,6 +670,18 @@ int atk_approx_topk(const void* values, int dtype, int64_t rows, int64_t N, int6
         hipError_t e = pl.var->fn(p, pl.grid, pl.block, pl.lds, st);
         return e == hipSuccess ? ATK_OK : hip_fail(e);
     }
+    if (pl.chunk_k > 0) {
+        // every bucket chunk's K greatest [rows, nchunk, K] through the workspace, then exact Top-K
+        const int64_t C = (int64_t)pl.nchunk * K;
+        char* ws = (char*)workspace;
+        int32_t* part_idx = (int32_t*)ws;
+        void* part_vals = ws + (size_t)rows * C * 4;
+        p.mode = 0;
+        p.out_vals = part_vals; p.out_idx = part_idx;
+        hipError_t e = pl.var->fn(p, pl.grid, pl.block, pl.lds, st);
+        if (e != hipSuccess) return hip_fail(e);
+        return run_exact(part_vals, part_idx, dtype, rows, C, C, K, out_vals, out_idx, st, values, row_stride);
+    }
     // unfused: survivors [rows, K', B] through the workspace, then exact Top-K over them
     const int64_t C = (int64_t)B * Kprime;
     char* ws = (char*)workspace;
@@ -849,7 +886,7 @@ int atk_describe_plan(int dtype, int64_t rows, int64_t N, int K, int Kprime, int
     std::snprintf(buf, buflen,
                   "%s%s KP=%d V=%d R=%d lanes_per_row=%d rows_per_wg=%d block=%d grid=%dx%d step=%d "
                   "steps=%d owners=%d seg=%d cand=%d tail=%d lds=%zu workspace=%zu",
-                  pl.slab_w > 0 ? "slab" : pl.nseg > 1 ? "split" : (pl.fused ? "fused" : "unfused"),
+                  pl.slab_w > 0 ? "slab" : pl.nseg > 1 ? "split" : (pl.fused ? "fused" : (pl.chunk_k > 0 ? "chunked" : "unfused")),
                   pl.var->packed() ? " packed" : (pl.var->rep == 2 ? " batched" : ""), pl.var->KP, pl.var->V,
                   pl.var->R, pl.G, pl.rows_per_wg, pl.block, pl.grid,
                   pl.slab_w > 0 ? B / pl.slab_w : (pl.nseg > 1 ? pl.nseg : pl.nchunk), pl.S, pl.nsteps,
@@ -866,7 +903,7 @@ int atk_set_option(const char* name, int value) {
         {"lanes_per_row", &Options::lanes_per_row}, {"segments", &Options::segments},
         {"slab", &Options::slab}, {"packed", &Options::packed}, {"subwave", &Options::subwave},
         {"batch_min_kp", &Options::batch_min_kp}, {"mips_segments", &Options::mips_segments},
-        {"unfused", &Options::unfused}, {"onepass", &Options::onepass},
+        {"unfused", &Options::unfused}, {"onepass", &Options::onepass}, {"chunked", &Options::chunked},
     };
     for (const Entry& e : entries) {
         if (std::strcmp(name, e.name) != 0) continue;

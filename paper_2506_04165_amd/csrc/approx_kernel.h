@@ -49,9 +49,12 @@ struct ApproxParams {
     int nseg;             // mode 2: segments per row (gridDim.y)
     int seg_steps;        // mode 2: steps per segment (the last one may be shorter)
     int slab_w;           // mode 3: buckets per workgroup, a power of two (gridDim.y = B / slab_w)
-    int chunk;            // mode 1, one owner per bucket: > 0 cuts the row along the bucket axis, a
-                          // workgroup taking buckets [blockIdx.y*chunk, +chunk) over all steps
-                          // (gridDim.y = ceil(B / chunk)); 0: the whole row
+    int chunk;            // modes 0 and 1, one owner per bucket: > 0 cuts the row along the bucket
+                          // axis, a workgroup taking buckets [blockIdx.y*chunk, +chunk) over all steps
+                          // (gridDim.y = ceil(B / chunk)); 0: the whole row.  In mode 0 (chunk must
+                          // divide B, one row per workgroup) stage 2 runs on the chunk's own
+                          // survivors and the K greatest of them go to out_*[(row*gridDim.y +
+                          // blockIdx.y)*K ...]: a row's result is among its chunks' results
     uint64_t* part_keys;  // mode 2: [rows, nseg, K', B] keys, 0 = empty entry; mode 3: [rows, K', B]
     void* out_vals;
     int32_t* out_idx;
@@ -445,7 +448,9 @@ struct ApproxKernel {
         }
 
         if constexpr (!BATCHED) __builtin_amdgcn_s_setprio(0);
-        const int C = p.B * p.Kprime;
+        const int C = (p.chunk > 0 ? chunk_len : p.B) * p.Kprime;   // candidates of this workgroup's row (part)
+        // where this workgroup's K results go (a chunk of a row has a result of its own)
+        const int64_t out_base = (p.chunk > 0 ? (int64_t)row * gridDim.y + blockIdx.y : (int64_t)row) * p.K;
         if constexpr (PACKED) {
             // packed variants only run fused, one owner per bucket, at most 1024 candidates per
             // row: the keys go to LDS as they are and the first wavefront of the row's group
@@ -505,7 +510,7 @@ struct ApproxKernel {
                         const uint32_t n = L.index(l, k, (uint32_t)p.S, (uint32_t)bucket);
                         uint32_t b = stored_bits(L, l, k);
                         if (p.mode == 0) {
-                            cand[bucket * p.Kprime + k] = make_key<DT>(b, n);
+                            cand[(bucket - chunk_first) * p.Kprime + k] = make_key<DT>(b, n);
                         } else if (p.mode == 2) {
                             // a segment shorter than K' steps leaves empty entries
                             const int64_t o = (((int64_t)row * p.nseg + blockIdx.y) * p.Kprime + k) * p.B + bucket;
@@ -589,13 +594,13 @@ struct ApproxKernel {
         if (p.tail == 1) {
             // few candidates: the first wavefront of every row's group sorts them in registers
             if (t < kWave && row_ok)
-                wave_sort_dispatch<DT>(cand, p.Cpad, p.K, rowp, p.out_vals, p.out_idx, (int64_t)row * p.K);
+                wave_sort_dispatch<DT>(cand, p.Cpad, p.K, rowp, p.out_vals, p.out_idx, out_base);
             return;
         }
         if (p.tail == 2) {
             // one row per workgroup: thin the candidates out by radix selection, wave-sort the rest
             wg_topk_from_lds<DT>(lds, p.Cpad, p.K, lds + p.aux_offset, rowp, p.out_vals, p.out_idx,
-                                 (int64_t)row * p.K);
+                                 out_base);
             return;
         }
         lds_bitonic_sort_desc(lds, p.rows_per_wg * p.Cpad, p.Cpad);
@@ -605,8 +610,8 @@ struct ApproxKernel {
                 const uint32_t n = key_index(key);
                 uint32_t b = key_value_bits<DT>(key);
                 if (b == 0 && key != 0) b = elem<DT>::load_bits(rowp, n);       // which zero it was
-                elem<DT>::store_bits(p.out_vals, (int64_t)row * p.K + i, b);
-                p.out_idx[(int64_t)row * p.K + i] = (int32_t)n;
+                elem<DT>::store_bits(p.out_vals, out_base + i, b);
+                p.out_idx[out_base + i] = (int32_t)n;
             }
         }
     }

@@ -79,19 +79,26 @@ def test_unsupported_arguments():
     assert call_approx(N=2 ** 26, K=100, Kp=1, B=2 ** 25) == atk.UNSUPPORTED      # B > 2^24
 
 
-def test_large_bucket_counts_run_unfused_in_bucket_chunks():
-    # Table 1's K'=1 rows with 32768 and 65536 buckets of 262144 elements, and neighbours: stage 1
-    # writes the survivors to the workspace with rows cut along the bucket axis
-    for rows, N, K, Kp, B in [(8, 262144, 1024, 1, 65536), (8, 262144, 1024, 1, 32768),
-                              (64, 1 << 20, 1024, 4, 16384), (2, 1 << 20, 5000, 4, 32768),
-                              (3, 3 * 50000, 100, 1, 50000), (1, 1 << 21, 8192, 1, 1 << 20)]:
-        st, text = atk.describe_plan(torch.float32, rows, N, K, Kp, B)
-        assert st == atk.OK and text.startswith("unfused"), (rows, N, K, Kp, B, text)
-        gy = int(re.search(r"grid=\d+x(\d+)", text).group(1))
-        lanes = int(re.search(r"lanes_per_row=(\d+)", text).group(1))
-        V, R = int(re.search(r" V=(\d+)", text).group(1)), int(re.search(r" R=(\d+)", text).group(1))
-        assert gy == -(-B // (lanes * V * R)) and gy > 1, text
-        assert atk.workspace_bytes(atk.OP_APPROX_TOPK, torch.float32, rows, N, K, Kp, B) == rows * B * Kp * 8
+def test_large_bucket_counts_run_in_bucket_chunks(knobs):
+    # Table 1's K'=1 rows with 32768 and 65536 buckets of 262144 elements, and neighbours: rows
+    # are cut along the bucket axis; a chunk's workgroup passes on all its survivors ("unfused")
+    # or, with option "chunked" and chunks that divide the buckets evenly, its K greatest
+    cases = [(8, 262144, 1024, 1, 65536), (8, 262144, 1024, 1, 32768), (64, 1 << 20, 1024, 4, 16384),
+             (2, 1 << 20, 5000, 4, 32768), (3, 3 * 50000, 100, 1, 50000), (1, 1 << 21, 8192, 1, 1 << 20)]
+    for chunked in (0, 1):
+        knobs.set("chunked", chunked)
+        for rows, N, K, Kp, B in cases:
+            st, text = atk.describe_plan(torch.float32, rows, N, K, Kp, B)
+            route = "chunked" if (chunked and B % 1024 == 0) else "unfused"
+            assert st == atk.OK and text.startswith(route), (rows, N, K, Kp, B, text)
+            gy = int(re.search(r"grid=\d+x(\d+)", text).group(1))
+            lanes = int(re.search(r"lanes_per_row=(\d+)", text).group(1))
+            V, R = int(re.search(r" V=(\d+)", text).group(1)), int(re.search(r" R=(\d+)", text).group(1))
+            assert gy == -(-B // (lanes * V * R)) and gy > 1, text
+            need = atk.workspace_bytes(atk.OP_APPROX_TOPK, torch.float32, rows, N, K, Kp, B)
+            assert need == (rows * B * Kp * 8 if route == "unfused" else rows * gy * K * 8)
+            if route == "chunked":      # a chunk's survivors fit LDS and are a few times K
+                assert 2 * K <= lanes * V * R * Kp <= 16384
     # stage 1 alone with as many buckets
     assert atk.lib.atk_approx_topk_stage1(None, 0, 0, 1 << 21, 1 << 21, 2, 1 << 20, None, None, None) == atk.OK
 
@@ -237,4 +244,4 @@ def test_no_alloc_entry_validates_like_the_workspace_entry():
     assert f(FAKE, 7, 4, 4096, 4096, 32, 4, 64, FAKE, FAKE, None) == atk.UNSUPPORTED
     assert f(None, 0, 0, 4096, 4096, 32, 4, 64, None, None, None) == atk.OK
     # survivors that the library's own scratch array (16 MiB) cannot hold: refused before any launch
-    assert f(FAKE, 0, 80, 131072, 131072, 300, 16, 2048, FAKE, FAKE, None) == atk.WORKSPACE_TOO_SMALL
+    assert f(FAKE, 0, 45, 150000, 150000, 100, 1, 50000, FAKE, FAKE, None) == atk.WORKSPACE_TOO_SMALL

@@ -2,7 +2,7 @@
 
 CPU part: the oracle's handling of the new element types is pinned against NumPy's own
 conversions and sorts.  GPU part: the HIP path against the oracle, bit for bit, over every
-launch route (fused, shared buckets, slab, split, unfused, exact, batched lists, stage 1 only)."""
+launch route (fused, shared buckets, slab, split, chunked, unfused, exact, batched lists, stage 1 only)."""
 import numpy as np
 import pytest
 import torch
@@ -136,7 +136,8 @@ ROUTES = [
     (3, 3600, 64, 3, 900, "fused"),            # B not a power of two
     (8, 262144, 1024, 4, 1024, "slab"),
     (8, 262144, 1024, 4, 1024, "split"),
-    (4, 131072, 128, 16, 2048, "unfused"),
+    (4, 131072, 128, 16, 2048, "chunked"),     # survivors beyond LDS: every chunk's K greatest through memory
+    (4, 131072, 128, 16, 2048, "unfused"),     # ... or all survivors
     (6, 65536, 256, 32, 256, "fused"),         # long lists: sorted batches
     (5, 8192, 40, 40, 8, "exact"),             # K' = K beyond the register lists
 ]
@@ -148,6 +149,8 @@ ROUTES = [
 def test_integer_rows_every_route(atk, rows, N, K, Kp, B, route, unsigned, knobs):
     if route == "split":     # the default for so few rows is the slab route
         knobs.set("slab", 0)
+    if route == "chunked":
+        knobs.set("chunked", 1)
     for kind in ("full", "ties", "floor"):
         check(atk, int_rows(rows, N, seed=31, kind=kind, unsigned=unsigned), K, Kp, B, route)
 
@@ -158,6 +161,8 @@ def test_half_rows_every_route(atk, rows, N, K, Kp, B, route, knobs):
     if route == "split":     # rows this short are not split by themselves: ask for it
         knobs.set("slab", 0)
         knobs.set("segments", 4)
+    if route == "chunked":
+        knobs.set("chunked", 1)
     for kind in ("patterns", "gauss"):
         check(atk, half_rows(rows, N, seed=32, kind=kind), K, Kp, B, route)
 

@@ -115,15 +115,20 @@ def test_slab_and_split_routes_guard_bands_and_poisoned_workspace(atk, knobs):
     run_guarded_approx(atk, workloads.heavy_ties(2, 40 * 256, seed=40, symbols=3), 256, 4, 256, "split")
 
 
-def test_unfused_route_guard_bands_and_poisoned_workspace(atk):
-    run_guarded_approx(atk, workloads.gaussian(4, 131072, seed=41), 300, 16, 2048, "unfused")
+@pytest.mark.parametrize("route", ["chunked", "unfused"])
+def test_workspace_routes_for_survivors_beyond_lds_guard_bands_and_poison(atk, knobs, route):
+    if route == "chunked":
+        knobs.set("chunked", 1)
+    run_guarded_approx(atk, workloads.gaussian(4, 131072, seed=41), 300, 16, 2048, route)
     # zeros of both signs among the survivors (their stored bits come from the row)
     z = workloads.heavy_ties(3, 131072, seed=42, symbols=3)
     z[z == z.max()] = 0.0
     z[:, ::7] = -0.0
-    run_guarded_approx(atk, z, 2048, 16, 2048, "unfused")
+    run_guarded_approx(atk, z, 2048, 16, 2048, route)
     g = torch.Generator().manual_seed(43)
-    run_guarded_approx(atk, torch.randint(-3, 3, (3, 98304), generator=g, dtype=torch.int32), 1000, 12, 2048, "unfused")
+    run_guarded_approx(atk, torch.randint(-3, 3, (3, 98304), generator=g, dtype=torch.int32), 1000, 12, 2048, route)
+    # a bucket count that chunks do not divide evenly: all survivors through the workspace either way
+    run_guarded_approx(atk, workloads.gaussian(3, 150000, seed=44), 100, 1, 50000, "unfused")
 
 
 def test_exact_and_stage1_guard_bands(atk):

@@ -259,21 +259,30 @@ def test_largest_fused_candidate_set(atk, knobs):
     check_approx(atk, workloads.gaussian(3, N, seed=19, dtype=torch.bfloat16), K, Kp, B)
 
 
-def test_unfused_path_through_workspace(atk):
-    # B*K' = 32768 survivors per row do not fit the fused kernel's LDS: two launches + workspace
+@pytest.mark.parametrize("route", ["chunked", "unfused"])
+def test_survivors_beyond_lds_go_through_the_workspace(atk, knobs, route):
+    # B*K' = 32768 survivors per row do not fit the fused kernel's LDS: two launches + workspace.
+    # By default all survivors are passed on ("unfused"); with option "chunked" every workgroup
+    # takes a chunk of the buckets, runs stage 2 on the chunk's own survivors and passes on its K
+    # greatest.
+    if route == "chunked":
+        knobs.set("chunked", 1)
     N, B, Kp, K = 131072, 2048, 16, 300
     st, text = atk.describe_plan(torch.float32, 4, N, K, Kp, B)
-    assert st == atk.OK and text.startswith("unfused")
+    assert st == atk.OK and text.startswith(route), text
     x = workloads.gaussian(4, N, seed=12)
     check_approx(atk, x, K, Kp, B)
     x = workloads.heavy_ties(3, N, seed=13, symbols=4)
     check_approx(atk, x, K, Kp, B)
     xb = workloads.gaussian(4, N, seed=14, dtype=torch.bfloat16)
     check_approx(atk, xb, K, Kp, B)
-    # enough rows that a workgroup keeps a whole row (no cut along the bucket axis)
+    # enough rows that the chip is full without cutting rows any finer than LDS asks for
     st, text = atk.describe_plan(torch.float32, 600, N, K, Kp, B)
-    assert st == atk.OK and text.startswith("unfused") and "x1 " in text, text
+    assert st == atk.OK and text.startswith(route) and ("x2 " if route == "chunked" else "x1 ") in text, text
     check_approx(atk, workloads.gaussian(600, N, seed=15), K, Kp, B, rows_to_check=[0, 1, 299, 598, 599])
+    # K close to what a chunk holds, ties across chunks
+    z = workloads.heavy_ties(3, N, seed=16, symbols=2)
+    check_approx(atk, z, 2048, Kp, B)
 
 
 @pytest.mark.parametrize("rows,N,K,Kp,B,dtype", [

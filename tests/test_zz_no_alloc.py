@@ -49,12 +49,15 @@ def both(atk, x, K, Kp, B, route):
     # (rows, N, K, K', B): the second call is the smaller problem and finds the first one's keys in the array
     ("slab", (8, 262144, 1024, 4, 1024), (3, 65536, 500, 2, 1024)),
     ("split", (8, 262144, 1024, 4, 1024), (6, 262144, 300, 4, 512)),
+    ("chunked", (6, 131072, 300, 16, 2048), (2, 65536, 2000, 1, 32768)),
     ("unfused", (6, 131072, 300, 16, 2048), (2, 65536, 2000, 1, 32768)),
     ("fused", (300, 16384, 128, 4, 1024), (7, 4096, 32, 4, 64)),
 ])
 def test_no_alloc_entry_matches_the_workspace_entry_on_two_calls_in_a_row(atk, knobs, route, first, second):
     if route == "split":
         knobs.set("slab", 0)
+    if route == "chunked":
+        knobs.set("chunked", 1)
     for call, (rows, N, K, Kp, B) in enumerate((first, second)):
         x = workloads.gaussian(rows, N, seed=90 + call)
         gv, gi = both(atk, x, K, Kp, B, route)
@@ -68,14 +71,15 @@ def test_no_alloc_entry_matches_the_workspace_entry_on_two_calls_in_a_row(atk, k
 
 
 def test_no_alloc_entry_refuses_what_the_array_cannot_hold(atk):
-    # 40 rows x 32768 survivors x 8 bytes = 10 MiB fits, 80 rows do not
-    x = workloads.gaussian(80, 131072, seed=94).to(DEV)
-    out_v = torch.empty((80, 300), device=DEV)
-    out_i = torch.empty((80, 300), dtype=torch.int32, device=DEV)
-    rc = atk.lib.atk_approx_topk_noalloc(x.data_ptr(), 0, 80, 131072, 131072, 300, 16, 2048, out_v.data_ptr(),
+    # 50000 buckets (chunks cannot divide them evenly, so all survivors go through the array):
+    # 40 rows x 50000 survivors x 8 bytes = 16.0 MB fit, 45 rows do not
+    x = workloads.gaussian(45, 150000, seed=94).to(DEV)
+    out_v = torch.empty((45, 100), device=DEV)
+    out_i = torch.empty((45, 100), dtype=torch.int32, device=DEV)
+    rc = atk.lib.atk_approx_topk_noalloc(x.data_ptr(), 0, 45, 150000, 150000, 100, 1, 50000, out_v.data_ptr(),
                                          out_i.data_ptr(), None)
     assert rc == atk.WORKSPACE_TOO_SMALL
-    gv, gi = atk.approx_topk_noalloc(x[:40], 300, 16, 2048, (out_v[:40], out_i[:40]))
-    rv, ri = atk.approx_topk(x[:40], 300, 16, 2048)
+    gv, gi = atk.approx_topk_noalloc(x[:40], 100, 1, 50000, (out_v[:40], out_i[:40]))
+    rv, ri = atk.approx_topk(x[:40], 100, 1, 50000)
     torch.cuda.synchronize()
     assert torch.equal(gi, ri) and torch.equal(gv, rv)
