@@ -39,16 +39,16 @@ PAPER_CONTEXT = {
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by a plain
 # copy of known size (profiles/approx_topk_<workload>_B<B>_Kp<K'>.md), keyed by (workload, B, K').
 MEASURED_TRAFFIC_BYTES = {
-    ("c4_mips", 1024, 4): 1075902162,
-    ("c4_mips", 4096, 1): 1075796020,
-    ("c2_ffn", 128, 4): 498365390,
-    ("c2_ffn", 1024, 1): 498462031,
-    ("c2_ffn", 64, 8): 498313943,
-    ("c3_vocab", 512, 4): 528051929,
-    ("c3_vocab", 512, 2): 527671539,
-    ("c5_adversarial", 256, 8): 271158719,
-    ("c5_adversarial", 256, 1): 278272946,
-    ("c5_adversarial", 256, 32): 271471574,
+    ("c4_mips", 1024, 4): 1076463707,
+    ("c4_mips", 4096, 1): 1076360290,
+    ("c2_ffn", 128, 4): 498397433,
+    ("c2_ffn", 1024, 1): 498726818,
+    ("c2_ffn", 64, 8): 498431695,
+    ("c3_vocab", 512, 4): 528284591,
+    ("c3_vocab", 512, 2): 528077955,
+    ("c5_adversarial", 256, 8): 271165198,
+    ("c5_adversarial", 256, 1): 277649443,
+    ("c5_adversarial", 256, 32): 272397426,
 }
 
 

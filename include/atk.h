@@ -246,12 +246,12 @@ int atk_valu_probe(int kind, const void* x, const void* y, void* out, size_t n_w
  * Read-only streaming probe: the memory bandwidth this chip delivers to a kernel that only reads
  * (the beta of Section 2.3's runtime model, measured rather than taken from the datasheet), as
  * the ceiling the streaming kernels are compared with.  Reads `bytes` bytes at `data` (device,
- * 16-byte aligned, a multiple of 16, below 2 TiB) once, with the loads the stage-1 kernel uses, in
+ * 16-byte aligned, a multiple of 16, below 512 GiB) once, with the loads the stage-1 kernel uses, in
  * ATK_READ_PROBE_WORDS contiguous pieces, and xors the exclusive-or of the 32-bit words of piece i
  * into checksum[i] (device, ATK_READ_PROBE_WORDS 32-bit words, which the caller sets to zero
  * beforehand; their exclusive-or is that of the whole buffer).  Asynchronous on `stream`.
  */
-#define ATK_READ_PROBE_WORDS 1024
+#define ATK_READ_PROBE_WORDS 256
 int atk_read_probe(const void* data, size_t bytes, void* checksum, void* stream);
 
 /*

@@ -346,7 +346,7 @@ def valu_probe(kind: int, x: torch.Tensor, y, ops: int, out=None):
     return out
 
 
-READ_PROBE_WORDS = 1024
+READ_PROBE_WORDS = 256
 
 
 def read_probe(data: torch.Tensor, checksum: torch.Tensor | None = None):

@@ -1,8 +1,9 @@
 // Read-only streaming probe: the measured bandwidth ceiling that the streaming kernels are held
 // against (the beta of Section 2.3's runtime model, as this chip delivers it to a kernel that
 // does nothing but read).  It reads a buffer once with the same instruction the stage-1 kernel
-// streams rows with -- non-temporal 16-byte buffer loads, 32 dwords in flight per lane, every
-// workgroup walking a contiguous piece -- and folds the words of every piece into a checksum word
+// streams rows with -- non-temporal 16-byte buffer loads, every workgroup walking a contiguous
+// piece; one workgroup of 512 threads per CU with four loads in flight per lane measured fastest of
+// the shapes tried, 6.5 TB/s on 256 MB and 7.1 TB/s on 1 GiB -- and folds the words of every piece into a checksum word
 // of its own (no atomics: nothing but the loads takes time) so that the loads cannot be dropped
 // and the result can be checked.
 #include <hip/hip_runtime.h>
@@ -14,7 +15,7 @@
 namespace {
 
 constexpr int kThreads = 512;
-constexpr int kInFlight = 8;                 // 16-byte loads issued before the first is used
+constexpr int kInFlight = 4;                 // 16-byte loads issued before the first is used
 
 __global__ void __launch_bounds__(kThreads) read_probe_kernel(const char* data, size_t n_vec,
                                                              size_t vec_per_wg, uint32_t* out) {
@@ -53,7 +54,7 @@ extern "C" int atk_read_probe(const void* data, size_t bytes, void* checksum, vo
     if (bytes == 0) return ATK_OK;
     if (!data || (uintptr_t)data % 16 || bytes % 16) return ATK_INVALID_ARG;
     const size_t n_vec = bytes / 16;
-    // as many pieces as checksum words (4 workgroups per CU); a piece stays below what a 32-bit
+    // as many pieces as checksum words (one workgroup per CU); a piece stays below what a 32-bit
     // offset reaches
     const size_t grid = ATK_READ_PROBE_WORDS;
     const size_t vec_per_wg = (n_vec + grid - 1) / grid;
