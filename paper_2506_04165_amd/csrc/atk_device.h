@@ -29,6 +29,10 @@ __device__ __forceinline__ uint32_t key_index(uint64_t key) { return ~(uint32_t)
 template <typename DT> struct elem;
 template <> struct elem<float> {
     static constexpr int size = 4;
+    // a >= b as values (stored patterns; -0.0 equals +0.0), and the pattern of the least value
+    // whose ordered image is at least `o` (images below that of -inf belong to no value)
+    __device__ static bool ge(uint32_t a, uint32_t b) { return __uint_as_float(a) >= __uint_as_float(b); }
+    __device__ static uint32_t floor_bits(uint32_t o) { return o < 0x00800000u ? 0xff800000u : bits_from_ordered(o); }
     // order-preserving image of the element's binary32 pattern, and back
     __device__ static uint32_t ordered(uint32_t bits) { return ordered_from_bits(bits); }
     __device__ static uint32_t from_ordered(uint32_t o) { return bits_from_ordered(o); }
@@ -41,6 +45,10 @@ template <> struct elem<float> {
 };
 template <> struct elem<bf16_t> {
     static constexpr int size = 2;
+    // a >= b as values (stored patterns; -0.0 equals +0.0), and the pattern of the least value
+    // whose ordered image is at least `o` (images below that of -inf belong to no value)
+    __device__ static bool ge(uint32_t a, uint32_t b) { return __uint_as_float(a) >= __uint_as_float(b); }
+    __device__ static uint32_t floor_bits(uint32_t o) { return o < 0x00800000u ? 0xff800000u : bits_from_ordered(o); }
     // order-preserving image of the element's binary32 pattern, and back
     __device__ static uint32_t ordered(uint32_t bits) { return ordered_from_bits(bits); }
     __device__ static uint32_t from_ordered(uint32_t o) { return bits_from_ordered(o); }
@@ -57,6 +65,10 @@ template <> struct elem<bf16_t> {
 struct score_t {};
 template <> struct elem<score_t> {
     static constexpr int size = 4;
+    // a >= b as values (stored patterns; -0.0 equals +0.0), and the pattern of the least value
+    // whose ordered image is at least `o` (images below that of -inf belong to no value)
+    __device__ static bool ge(uint32_t a, uint32_t b) { return __uint_as_float(a) >= __uint_as_float(b); }
+    __device__ static uint32_t floor_bits(uint32_t o) { return o < 0x00800000u ? 0xff800000u : bits_from_ordered(o); }
     // order-preserving image of the element's binary32 pattern, and back
     __device__ static uint32_t ordered(uint32_t bits) { return ordered_from_bits(bits); }
     __device__ static uint32_t from_ordered(uint32_t o) { return bits_from_ordered(o); }
@@ -74,6 +86,8 @@ struct i32_t {};
 struct u32_t {};
 template <> struct elem<i32_t> {
     static constexpr int size = 4;
+    __device__ static bool ge(uint32_t a, uint32_t b) { return (int32_t)a >= (int32_t)b; }
+    __device__ static uint32_t floor_bits(uint32_t o) { return o ^ 0x80000000u; }
     __device__ static uint32_t ordered(uint32_t bits) { return bits ^ 0x80000000u; }
     __device__ static uint32_t from_ordered(uint32_t o) { return o ^ 0x80000000u; }
     __device__ static uint32_t load_bits(const void* base, int64_t i) { return ((const uint32_t*)base)[i]; }
@@ -81,6 +95,8 @@ template <> struct elem<i32_t> {
 };
 template <> struct elem<u32_t> {
     static constexpr int size = 4;
+    __device__ static bool ge(uint32_t a, uint32_t b) { return a >= b; }
+    __device__ static uint32_t floor_bits(uint32_t o) { return o; }
     __device__ static uint32_t ordered(uint32_t bits) { return bits; }
     __device__ static uint32_t from_ordered(uint32_t o) { return o; }
     __device__ static uint32_t load_bits(const void* base, int64_t i) { return ((const uint32_t*)base)[i]; }

@@ -40,7 +40,7 @@ __device__ __constant__ int kDigitBits[kNumDigits] = {11, 11, 10, 11, 11, 10};
 
 // Calls fn(bits, n) for every element n of the row: 16-byte vector loads when the row allows
 // (no payload, base and stride 16-byte aligned), element loads otherwise.  All threads take part.
-template <typename DT, bool VEC, typename F>
+template <typename DT, bool VEC, int UN = 4, typename F>
 __device__ __forceinline__ void for_each_element(const char* rowp, int begin, int end, F&& fn) {
     const int tid = threadIdx.x, T = blockDim.x;
     constexpr int VE = 16 / elem<DT>::size;
@@ -48,7 +48,6 @@ __device__ __forceinline__ void for_each_element(const char* rowp, int begin, in
         // begin is a multiple of VE
         const int nvec = (end - begin) / VE;
         const uint4* vp = (const uint4*)(rowp + (size_t)begin * elem<DT>::size);
-        constexpr int UN = 4;
         int i = tid;
         for (; i + (UN - 1) * T < nvec; i += UN * T) {
             uint4 v[UN];
@@ -96,7 +95,8 @@ __device__ __forceinline__ bool onepass(const TopkParams& p, const char* rowp, c
     const int tid = threadIdx.x, T = blockDim.x, lane = tid & (kWave - 1);
     const int N = p.N, cap = p.cap;
     constexpr int VE = VEC ? 16 / elem<DT>::size : 1;
-    constexpr int kMaxRounds = 64;
+    constexpr int kMaxRounds = 1024;
+    constexpr int kInFlight = 4;            // vector loads a lane issues before it looks at the first (8 and 16: no faster)
     auto index_of = [&](int n) -> uint32_t { return PAYLOAD ? (uint32_t)payload[n] : (uint32_t)n; };
     if (tid == 0) { ctl[3] = 0; ctl[5] = 0; }
     __syncthreads();
@@ -116,13 +116,15 @@ __device__ __forceinline__ bool onepass(const TopkParams& p, const char* rowp, c
             if (take > 4 * (int64_t)done) take = 4 * (int64_t)done;   // data in ascending order shows early
         }
         const int end = (int)min((int64_t)N, (int64_t)done + take);
-        const uint32_t thr_hi = (uint32_t)(thr >> 32);
-        for_each_element<DT, VEC>(rowp, done, end, [&](uint32_t b, int n) {
-            const uint32_t ord = elem<DT>::ordered(b);
-            bool pass = ord >= thr_hi;                      // cheap reject on the value word
+        // cheap reject: one compare of the stored value with the threshold's value; only the few
+        // elements at or above it have their key built and compared
+        const uint32_t thr_bits = elem<DT>::floor_bits((uint32_t)(thr >> 32));
+        for_each_element<DT, VEC, kInFlight>(rowp, done, end, [&](uint32_t b, int n) {
+            bool pass = elem<DT>::ge(b, thr_bits);
+            if (__ballot(pass) == 0) return;
             uint64_t key = 0;
             if (pass) {
-                key = ((uint64_t)ord << 32) | (uint32_t)(~index_of(n));
+                key = make_key<DT>(b, index_of(n));
                 pass = key > thr;
             }
             // one LDS atomic per wavefront: the lanes that keep their key take consecutive slots
@@ -220,9 +222,10 @@ __global__ void __launch_bounds__(1024) topk_exact_kernel(TopkParams p) {
         int next_update = chunk;
         for (int base = 0; base < N; base += chunk) {
             const int end = min(N, base + chunk);
+            // (one compare of the stored value rejects what lies below the lower bound)
+            const uint32_t dmin_bits = elem<DT>::floor_bits(dmin << 21);
             for_each_element<DT, VEC>(rowp, base, end, [&](uint32_t b, int) {
-                const uint32_t d = elem<DT>::ordered(b) >> 21;
-                if (d >= dmin) atomicAdd(&hist[d], 1u);
+                if (elem<DT>::ge(b, dmin_bits)) atomicAdd(&hist[elem<DT>::ordered(b) >> 21], 1u);
             });
             // (only once at least K keys have been counted: the walk needs K of them)
             if (end >= next_update && end < N && end >= p.K) {
@@ -259,11 +262,11 @@ __global__ void __launch_bounds__(1024) topk_exact_kernel(TopkParams p) {
     // ---- gather certain members and prefix matches ----------------------------------------------
     if (tid == 0) ctl[3] = 0;
     __syncthreads();
+    const uint32_t prefix_bits = elem<DT>::floor_bits((uint32_t)(prefix >> 32));
     for_each_element<DT, VEC>(rowp, 0, N, [&](uint32_t b, int n) {
-        // cheap reject on the value word before the full key is built
-        const uint32_t ord = elem<DT>::ordered(b);
-        if (ord >= (uint32_t)(prefix >> 32)) {
-            const uint64_t key = ((uint64_t)ord << 32) | (uint32_t)(~index_of(n));
+        // cheap reject on the stored value before the key is built
+        if (elem<DT>::ge(b, prefix_bits)) {
+            const uint64_t key = make_key<DT>(b, index_of(n));
             if ((key & mask) >= prefix) {
                 const uint32_t slot = atomicAdd(&ctl[3], 1u);
                 if (slot < (uint32_t)p.cap) lds64[slot] = key;   // always true; keeps a slip memory safe
