@@ -62,6 +62,7 @@ constexpr int kExactCap = 16384;         // exact kernel: largest LDS key buffer
 constexpr int kExactMaxK = 8192;
 constexpr int64_t kOnepassMinN = 524288; // exact kernel: shortest row that is tried in one pass
 constexpr int64_t kTargetWaves = 2048;   // 256 CUs x 4 SIMDs x 2 waves: below this the chip idles
+constexpr int64_t kTargetWorkgroups = 256; // ... and with fewer workgroups than CUs some CUs have none
 constexpr int kMinSegmentSteps = 8;      // do not cut a row into pieces shorter than this
 constexpr int kMaxSegments = 64;
 constexpr size_t kMinSplitBytes = 4u << 20;
@@ -277,7 +278,8 @@ static Plan compute_plan(const void* values, int dtype, int64_t rows, int64_t N,
                    pow2_ceil((int64_t)G * NL * Kp) > kMaxFusedCandidates) {
                 if (NL > 1) NL >>= 1; else G >>= 1;
             }
-            while (waves() < kTargetWaves && (NL > 1 || G > 256)) {
+            auto workgroups = [&] { return rows * (int64_t)((B + G * NL - 1) / (G * NL)); };
+            while ((waves() < kTargetWaves || workgroups() < kTargetWorkgroups) && (NL > 1 || G > 256)) {
                 // (a chunk that runs its own stage 2 should hold a few times K survivors)
                 if (through_memory && g_opt.chunked != 0 && (int64_t)G * NL * Kp < 8 * (int64_t)K) break;
                 if (NL > 1) NL >>= 1; else G >>= 1;
@@ -689,6 +691,7 @@ int atk_approx_topk(const void* values, int dtype, int64_t rows, int64_t N, int6
     void* surv_vals = ws + (size_t)rows * C * 4;
     p.mode = 1;
     p.surv_vals = surv_vals; p.surv_idx = surv_idx;
+    p.surv_aligned = ((uintptr_t)surv_vals % 16 == 0 && (uintptr_t)surv_idx % 16 == 0) ? 1 : 0;
     hipError_t e = pl.var->fn(p, pl.grid, pl.block, pl.lds, st);
     if (e != hipSuccess) return hip_fail(e);
     return run_exact(surv_vals, surv_idx, dtype, rows, C, C, K, out_vals, out_idx, st, values, row_stride);
@@ -785,6 +788,7 @@ int atk_approx_topk_stage1(const void* values, int dtype, int64_t rows, int64_t 
     ApproxParams p = params_from(pl, values, rows, N, row_stride, Kprime, Kprime, B);
     p.mode = 1;
     p.surv_vals = surv_vals; p.surv_idx = surv_idx;
+    p.surv_aligned = ((uintptr_t)surv_vals % 16 == 0 && (uintptr_t)surv_idx % 16 == 0) ? 1 : 0;
     hipError_t e = pl.var->fn(p, pl.grid, pl.block, pl.lds, (hipStream_t)stream);
     return e == hipSuccess ? ATK_OK : hip_fail(e);
 }

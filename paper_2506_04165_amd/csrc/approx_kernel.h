@@ -60,6 +60,7 @@ struct ApproxParams {
     int32_t* out_idx;
     void* surv_vals;
     int32_t* surv_idx;
+    int surv_aligned;     // mode 1: both survivor arrays start at multiples of 16 bytes (vector stores allowed)
 };
 
 // Plain two-way select on values; written as a function of values so that it is emitted as a
@@ -500,6 +501,8 @@ struct ApproxKernel {
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const bool live = slot_ok[r] && row_ok;
+                uint32_t sv_vec[KP][4], si_vec[KP][4];      // mode 1 with 16-byte stores (folded away otherwise)
+                (void)sv_vec; (void)si_vec;
 #pragma unroll
                 for (int v = 0; v < V; ++v) {
                     const int bucket = off[r] + v;
@@ -519,8 +522,19 @@ struct ApproxKernel {
                             if (!Lists<REP, KP, NL>::exact_bits && (b << 1) == 0)   // either zero
                                 b = elem<DT>::load_bits(rowp, n);       // which zero it was
                             const int64_t o = ((int64_t)row * p.Kprime + k) * p.B + bucket;
-                            elem<DT>::store_bits(p.surv_vals, o, b);
-                            p.surv_idx[o] = (int32_t)n;
+                            if (V == 4 && elem<DT>::size == 4 && p.surv_aligned) {
+                                // the V buckets of a load are neighbours in plane k: one 16-byte store
+                                // each for values and indices (a lane's four 4-byte stores 16 bytes
+                                // apart from its neighbours' were measured to write 1.6x the bytes)
+                                sv_vec[k][v] = b; si_vec[k][v] = n;
+                                if (v == V - 1) {
+                                    *(uint4*)((uint32_t*)p.surv_vals + (o - (V - 1))) = make_uint4(sv_vec[k][0], sv_vec[k][1], sv_vec[k][2], sv_vec[k][3]);
+                                    *(uint4*)(p.surv_idx + (o - (V - 1))) = make_uint4(si_vec[k][0], si_vec[k][1], si_vec[k][2], si_vec[k][3]);
+                                }
+                            } else {
+                                elem<DT>::store_bits(p.surv_vals, o, b);
+                                p.surv_idx[o] = (int32_t)n;
+                            }
                         }
                     }
                 }

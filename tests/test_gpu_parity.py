@@ -738,3 +738,79 @@ def test_seeded_random_shapes_all_element_types(atk, seed, cases, max_n, min_ran
         assert np.array_equal(ei.cpu().numpy(), oi) and np.array_equal(raw(ev), oracle_raw(ov)), case
         ran += 1
     assert ran >= min_ran
+
+
+@pytest.mark.parametrize("seed,cases", [(3101, 50)])
+def test_seeded_random_shapes_many_buckets_large_k_and_options(atk, knobs, seed, cases):
+    # what the sweep above does not reach: bucket counts up to 2^18 (survivors through the
+    # workspace, rows cut along the bucket axis), K up to 8192, random developer options (chunked,
+    # unfused, one-pass exact, slab), and the entry that allocates nothing; approximate and exact
+    # kernels against the oracle, bit for bit
+    rng = np.random.default_rng(seed)
+    dtypes = [torch.float32, torch.bfloat16, torch.float16, torch.int32, torch.uint32]
+
+    def raw(t):
+        t = t.detach().cpu().contiguous()
+        return (t.view(torch.int16).numpy().view(np.uint16) if t.element_size() == 2
+                else t.view(torch.int32).numpy().view(np.uint32))
+
+    def oracle_raw(a):
+        return a.view(np.uint16) if a.dtype.itemsize == 2 else a.view(np.uint32)
+
+    for case in range(cases):
+        dt = dtypes[int(rng.integers(5))]
+        kind = int(rng.integers(3))
+        B = (int(2 ** rng.integers(10, 19)) if kind == 0 else int(rng.integers(1, 300)) * int(2 ** rng.integers(5, 11))
+             if kind == 1 else int(rng.integers(2000, 60000)))
+        steps = int(rng.integers(1, max(2, min(64, 2000000 // B)) + 1))
+        N = B * steps
+        Kp = int(rng.integers(1, min(steps, 32) + 1))
+        if rng.random() < 0.6:
+            Kp = min(Kp, 4)
+        K = int(rng.integers(Kp, min(B * Kp, N, 8192) + 1))
+        if rng.random() < 0.5:
+            K = min(K, 1024)
+        rows = int(rng.integers(1, 12 if N < 500000 else 4))
+        style = int(rng.integers(3))
+        opts = {}
+        if rng.random() < 0.3:
+            opts["chunked"] = 1
+        if rng.random() < 0.3:
+            opts["unfused"] = 1
+        if rng.random() < 0.4:
+            opts["onepass"] = 2
+        if rng.random() < 0.2:
+            opts["slab"] = int(rng.integers(0, 3))
+        for k, v in opts.items():
+            knobs.set(k, v)
+        g = torch.Generator().manual_seed(int(rng.integers(1 << 30)))
+        if dt in (torch.int32, torch.uint32):
+            lo, hi = (-(1 << 31), 1 << 31) if style == 0 else (-50, 50)
+            x = torch.randint(lo, hi, (rows, N), generator=g, dtype=torch.int64)
+            x = (x & 0xffffffff).to(torch.uint32) if dt == torch.uint32 else x.to(torch.int32)
+        else:
+            x = torch.randn(rows, N, generator=g)
+            if style == 1:
+                x = torch.round(x * 4) / 4
+            elif style == 2:
+                x = torch.sort(x, dim=1, descending=bool(rng.integers(2))).values
+            x = x.to(dt)
+        status, plan = atk.describe_plan(dt, rows, N, K, Kp, B)
+        assert status == atk.OK, plan
+        print(f"case {case}: {dt} rows={rows} N={N} B={B} K'={Kp} K={K} style={style} {opts} {plan.split()[0]}", flush=True)
+        xh, xd = workloads.to_numpy_bits(x), x.to(DEV)
+        gv, gi = atk.approx_topk(xd, K, Kp, B)
+        torch.cuda.synchronize()
+        ov, oi = oracle.approx_topk(xh, K, Kp, B)
+        assert np.array_equal(gi.cpu().numpy(), oi) and np.array_equal(raw(gv), oracle_raw(ov)), case
+        out = (torch.zeros_like(gv), torch.zeros_like(gi))
+        rc = atk.lib.atk_approx_topk_noalloc(xd.data_ptr(), atk._CODES[dt], rows, N, N, K, Kp, B,
+                                             out[0].data_ptr(), out[1].data_ptr(), None)
+        torch.cuda.synchronize()
+        assert rc == atk.WORKSPACE_TOO_SMALL or (rc == atk.OK and torch.equal(out[1], gi)), (case, rc)
+        ev, ei = atk.topk(xd, K)
+        torch.cuda.synchronize()
+        ov, oi = oracle.topk(xh, K)
+        assert np.array_equal(ei.cpu().numpy(), oi) and np.array_equal(raw(ev), oracle_raw(ov)), case
+        for k in opts:
+            knobs.set(k, -1)
