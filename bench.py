@@ -39,16 +39,16 @@ PAPER_CONTEXT = {
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by a plain
 # copy of known size (profiles/approx_topk_<workload>_B<B>_Kp<K'>.md), keyed by (workload, B, K').
 MEASURED_TRAFFIC_BYTES = {
-    ("c4_mips", 1024, 4): 1076463707,
-    ("c4_mips", 4096, 1): 1076360290,
-    ("c2_ffn", 128, 4): 498397433,
-    ("c2_ffn", 1024, 1): 498726818,
-    ("c2_ffn", 64, 8): 498431695,
-    ("c3_vocab", 512, 4): 528284591,
-    ("c3_vocab", 512, 2): 528077955,
-    ("c5_adversarial", 256, 8): 271165198,
-    ("c5_adversarial", 256, 1): 277649443,
-    ("c5_adversarial", 256, 32): 272397426,
+    ("c4_mips", 1024, 4): 1076464134,
+    ("c4_mips", 4096, 1): 1076397580,
+    ("c2_ffn", 128, 4): 498396060,
+    ("c2_ffn", 1024, 1): 498726578,
+    ("c2_ffn", 64, 8): 498432796,
+    ("c3_vocab", 512, 4): 528306441,
+    ("c3_vocab", 512, 2): 528078226,
+    ("c5_adversarial", 256, 8): 271165303,
+    ("c5_adversarial", 256, 1): 278122377,
+    ("c5_adversarial", 256, 32): 272396236,
 }
 
 
