@@ -522,14 +522,21 @@ struct ApproxKernel {
                             if (!Lists<REP, KP, NL>::exact_bits && (b << 1) == 0)   // either zero
                                 b = elem<DT>::load_bits(rowp, n);       // which zero it was
                             const int64_t o = ((int64_t)row * p.Kprime + k) * p.B + bucket;
-                            if (V == 4 && elem<DT>::size == 4 && p.surv_aligned) {
-                                // the V buckets of a load are neighbours in plane k: one 16-byte store
-                                // each for values and indices (a lane's four 4-byte stores 16 bytes
-                                // apart from its neighbours' were measured to write 1.6x the bytes)
+                            if ((V == 4 || V == 2) && elem<DT>::size == 4 && p.surv_aligned) {
+                                // the V buckets of a load are neighbours in plane k: one 16- or 8-byte
+                                // store each for values and indices (a lane's 4-byte stores, V elements
+                                // apart from its neighbours', were measured to write 1.6x the bytes)
                                 sv_vec[k][v] = b; si_vec[k][v] = n;
                                 if (v == V - 1) {
-                                    *(uint4*)((uint32_t*)p.surv_vals + (o - (V - 1))) = make_uint4(sv_vec[k][0], sv_vec[k][1], sv_vec[k][2], sv_vec[k][3]);
-                                    *(uint4*)(p.surv_idx + (o - (V - 1))) = make_uint4(si_vec[k][0], si_vec[k][1], si_vec[k][2], si_vec[k][3]);
+                                    uint32_t* dv = (uint32_t*)p.surv_vals + (o - (V - 1));
+                                    int32_t* di = p.surv_idx + (o - (V - 1));
+                                    if constexpr (V == 4) {
+                                        *(uint4*)dv = make_uint4(sv_vec[k][0], sv_vec[k][1], sv_vec[k][2], sv_vec[k][3]);
+                                        *(uint4*)di = make_uint4(si_vec[k][0], si_vec[k][1], si_vec[k][2], si_vec[k][3]);
+                                    } else {
+                                        *(uint2*)dv = make_uint2(sv_vec[k][0], sv_vec[k][1]);
+                                        *(uint2*)di = make_uint2(si_vec[k][0], si_vec[k][1]);
+                                    }
                                 }
                             } else {
                                 elem<DT>::store_bits(p.surv_vals, o, b);
