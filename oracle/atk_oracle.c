@@ -104,6 +104,24 @@ static int greater_first(const void *pa, const void *pb)
     return 0;
 }
 
+/*
+ * The mirrored problem, the K smallest ("min-K"): element a comes before element b when
+ * value(a) < value(b), or the values compare equal and index(a) < index(b).  Everything else
+ * in the definition stays as it is, with "greatest" read as "first in this order".
+ */
+static int smaller_first(const void *pa, const void *pb)
+{
+    const element_t *a = (const element_t *)pa;
+    const element_t *b = (const element_t *)pb;
+    if (a->value < b->value) return -1;
+    if (a->value > b->value) return 1;
+    if (a->index < b->index) return -1;
+    if (a->index > b->index) return 1;
+    return 0;
+}
+
+typedef int (*order_fn)(const void *, const void *);
+
 static void store_output(const void *row, int dtype, const element_t *e,
                          void *out_vals, int32_t *out_idx, int64_t pos)
 {
@@ -147,9 +165,9 @@ static int check_args(const void *values, int dtype, int64_t rows, int64_t N,
  * [rows, K', B] (Section 6.3): plane k holds, for every bucket, its k-th
  * greatest element.  surv_vals has the input dtype, surv_idx is int32.
  */
-int atk_oracle_stage1(const void *values, int dtype, int64_t rows, int64_t N,
-                      int64_t row_stride, int64_t Kp, int64_t B,
-                      void *surv_vals, int32_t *surv_idx)
+static int stage1_in_order(order_fn first, const void *values, int dtype, int64_t rows, int64_t N,
+                           int64_t row_stride, int64_t Kp, int64_t B,
+                           void *surv_vals, int32_t *surv_idx)
 {
     int rc = check_args(values, dtype, rows, N, row_stride, Kp, Kp, B);
     if (rc) return rc;
@@ -167,7 +185,7 @@ int atk_oracle_stage1(const void *values, int dtype, int64_t rows, int64_t N,
                 bucket[j].index = (int32_t)n;
                 if (isnan(bucket[j].value)) set_status(&status, -2);
             }
-            qsort(bucket, (size_t)per_bucket, sizeof(element_t), greater_first);
+            qsort(bucket, (size_t)per_bucket, sizeof(element_t), first);
             for (int64_t k = 0; k < Kp; ++k) {
                 int64_t pos = k * B + b;
                 store_output(row, dtype, &bucket[k],
@@ -180,8 +198,15 @@ int atk_oracle_stage1(const void *values, int dtype, int64_t rows, int64_t N,
     return status;
 }
 
+int atk_oracle_stage1(const void *values, int dtype, int64_t rows, int64_t N,
+                      int64_t row_stride, int64_t Kp, int64_t B,
+                      void *surv_vals, int32_t *surv_idx)
+{
+    return stage1_in_order(greater_first, values, dtype, rows, N, row_stride, Kp, B, surv_vals, surv_idx);
+}
+
 /* Steps 1-4. out_vals: [rows, K] in the input dtype; out_idx: [rows, K] int32. */
-int atk_oracle_approx_topk(const void *values, int dtype, int64_t rows, int64_t N,
+static int approx_in_order(order_fn first, const void *values, int dtype, int64_t rows, int64_t N,
                            int64_t row_stride, int64_t K, int64_t Kp, int64_t B,
                            void *out_vals, int32_t *out_idx)
 {
@@ -204,13 +229,13 @@ int atk_oracle_approx_topk(const void *values, int dtype, int64_t rows, int64_t 
                 bucket[j].index = (int32_t)n;
                 if (isnan(bucket[j].value)) set_status(&status, -2);
             }
-            /* Step 2: its K' greatest */
-            qsort(bucket, (size_t)per_bucket, sizeof(element_t), greater_first);
+            /* Step 2: its K' greatest (first in the order) */
+            qsort(bucket, (size_t)per_bucket, sizeof(element_t), first);
             /* Step 3: union */
             for (int64_t k = 0; k < Kp; ++k) selected[n_selected++] = bucket[k];
         }
         /* Step 4: sort the union, keep the first K */
-        qsort(selected, (size_t)n_selected, sizeof(element_t), greater_first);
+        qsort(selected, (size_t)n_selected, sizeof(element_t), first);
         for (int64_t k = 0; k < K; ++k)
             store_output(row, dtype, &selected[k],
                          (char *)out_vals + (size_t)r * K * elem_size(dtype),
@@ -221,9 +246,31 @@ int atk_oracle_approx_topk(const void *values, int dtype, int64_t rows, int64_t 
     return status;
 }
 
-/* Exact Top-K: the K greatest of all N elements of each row, greatest first. */
-int atk_oracle_topk(const void *values, int dtype, int64_t rows, int64_t N,
-                    int64_t row_stride, int64_t K, void *out_vals, int32_t *out_idx)
+int atk_oracle_approx_topk(const void *values, int dtype, int64_t rows, int64_t N,
+                           int64_t row_stride, int64_t K, int64_t Kp, int64_t B,
+                           void *out_vals, int32_t *out_idx)
+{
+    return approx_in_order(greater_first, values, dtype, rows, N, row_stride, K, Kp, B, out_vals, out_idx);
+}
+
+/* The same four steps for the K smallest. */
+int atk_oracle_approx_mink(const void *values, int dtype, int64_t rows, int64_t N,
+                           int64_t row_stride, int64_t K, int64_t Kp, int64_t B,
+                           void *out_vals, int32_t *out_idx)
+{
+    return approx_in_order(smaller_first, values, dtype, rows, N, row_stride, K, Kp, B, out_vals, out_idx);
+}
+
+int atk_oracle_stage1_min(const void *values, int dtype, int64_t rows, int64_t N,
+                          int64_t row_stride, int64_t Kp, int64_t B,
+                          void *surv_vals, int32_t *surv_idx)
+{
+    return stage1_in_order(smaller_first, values, dtype, rows, N, row_stride, Kp, B, surv_vals, surv_idx);
+}
+
+/* Exact Top-K: the K greatest (first in the order) of all N elements of each row, in order. */
+static int exact_in_order(order_fn first, const void *values, int dtype, int64_t rows, int64_t N,
+                          int64_t row_stride, int64_t K, void *out_vals, int32_t *out_idx)
 {
     if (!values || !known_dtype(dtype)) return -1;
     if (rows < 0 || N <= 0 || row_stride < N || N > 2147483647LL) return -1;
@@ -239,7 +286,7 @@ int atk_oracle_topk(const void *values, int dtype, int64_t rows, int64_t N,
             all[n].index = (int32_t)n;
             if (isnan(all[n].value)) set_status(&status, -2);
         }
-        qsort(all, (size_t)N, sizeof(element_t), greater_first);
+        qsort(all, (size_t)N, sizeof(element_t), first);
         for (int64_t k = 0; k < K; ++k)
             store_output(row, dtype, &all[k],
                          (char *)out_vals + (size_t)r * K * elem_size(dtype),
@@ -247,6 +294,19 @@ int atk_oracle_topk(const void *values, int dtype, int64_t rows, int64_t N,
         free(all);
     }
     return status;
+}
+
+int atk_oracle_topk(const void *values, int dtype, int64_t rows, int64_t N,
+                    int64_t row_stride, int64_t K, void *out_vals, int32_t *out_idx)
+{
+    return exact_in_order(greater_first, values, dtype, rows, N, row_stride, K, out_vals, out_idx);
+}
+
+/* Exact min-K: the K smallest of each row, smallest first. */
+int atk_oracle_mink(const void *values, int dtype, int64_t rows, int64_t N,
+                    int64_t row_stride, int64_t K, void *out_vals, int32_t *out_idx)
+{
+    return exact_in_order(smaller_first, values, dtype, rows, N, row_stride, K, out_vals, out_idx);
 }
 
 /*

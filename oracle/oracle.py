@@ -57,6 +57,12 @@ def _load():
         lib.atk_oracle_approx_topk.restype = ci
         lib.atk_oracle_topk.argtypes = [vp, ci, i64, i64, i64, i64, vp, vp]
         lib.atk_oracle_topk.restype = ci
+        lib.atk_oracle_approx_mink.argtypes = [vp, ci, i64, i64, i64, i64, i64, i64, vp, vp]
+        lib.atk_oracle_approx_mink.restype = ci
+        lib.atk_oracle_mink.argtypes = [vp, ci, i64, i64, i64, i64, vp, vp]
+        lib.atk_oracle_mink.restype = ci
+        lib.atk_oracle_stage1_min.argtypes = [vp, ci, i64, i64, i64, i64, i64, vp, vp]
+        lib.atk_oracle_stage1_min.restype = ci
         lib.atk_oracle_num_threads.restype = ci
         lib.atk_oracle_mips_scores.argtypes = [vp, vp, ci, i64, i64, i64, vp]
         lib.atk_oracle_mips_scores.restype = ci
@@ -90,38 +96,39 @@ def _raise(rc: int, what: str):
     raise ValueError(f"{what}: {msg}")
 
 
-def approx_topk(values: np.ndarray, K: int, Kprime: int, B: int):
-    """Section 6.1 Steps 1-4.  Returns (vals[rows,K] in the input dtype, idx[rows,K] int32)."""
+def approx_topk(values: np.ndarray, K: int, Kprime: int, B: int, smallest: bool = False):
+    """Section 6.1 Steps 1-4.  Returns (vals[rows,K] in the input dtype, idx[rows,K] int32).
+    smallest: the mirrored problem (the K smallest, smallest first, ties toward the lowest index)."""
     values, dtype = _prep(values)
     rows, N = values.shape
     out_vals = np.empty((rows, K), dtype=values.dtype)
     out_idx = np.empty((rows, K), dtype=np.int32)
-    rc = _load().atk_oracle_approx_topk(values.ctypes.data, dtype, rows, N, N, K, Kprime, B,
-                                        out_vals.ctypes.data, out_idx.ctypes.data)
+    fn = _load().atk_oracle_approx_mink if smallest else _load().atk_oracle_approx_topk
+    rc = fn(values.ctypes.data, dtype, rows, N, N, K, Kprime, B, out_vals.ctypes.data, out_idx.ctypes.data)
     _raise(rc, "oracle approx_topk")
     return out_vals, out_idx
 
 
-def topk(values: np.ndarray, K: int):
-    """Exact Top-K under the same total order.  Returns (vals[rows,K], idx[rows,K])."""
+def topk(values: np.ndarray, K: int, smallest: bool = False):
+    """Exact Top-K (or min-K) under the same total order.  Returns (vals[rows,K], idx[rows,K])."""
     values, dtype = _prep(values)
     rows, N = values.shape
     out_vals = np.empty((rows, K), dtype=values.dtype)
     out_idx = np.empty((rows, K), dtype=np.int32)
-    rc = _load().atk_oracle_topk(values.ctypes.data, dtype, rows, N, N, K,
-                                 out_vals.ctypes.data, out_idx.ctypes.data)
+    fn = _load().atk_oracle_mink if smallest else _load().atk_oracle_topk
+    rc = fn(values.ctypes.data, dtype, rows, N, N, K, out_vals.ctypes.data, out_idx.ctypes.data)
     _raise(rc, "oracle topk")
     return out_vals, out_idx
 
 
-def stage1(values: np.ndarray, Kprime: int, B: int):
+def stage1(values: np.ndarray, Kprime: int, B: int, smallest: bool = False):
     """Steps 1-2 only: survivors as (vals[rows,K',B], idx[rows,K',B]), Section 6.3 layout."""
     values, dtype = _prep(values)
     rows, N = values.shape
     sv = np.empty((rows, Kprime, B), dtype=values.dtype)
     si = np.empty((rows, Kprime, B), dtype=np.int32)
-    rc = _load().atk_oracle_stage1(values.ctypes.data, dtype, rows, N, N, Kprime, B,
-                                   sv.ctypes.data, si.ctypes.data)
+    fn = _load().atk_oracle_stage1_min if smallest else _load().atk_oracle_stage1
+    rc = fn(values.ctypes.data, dtype, rows, N, N, Kprime, B, sv.ctypes.data, si.ctypes.data)
     _raise(rc, "oracle stage1")
     return sv, si
 
