@@ -87,6 +87,21 @@ int atk_approx_topk(const void* values, int dtype, int64_t rows, int64_t N, int6
                     void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The mirrored problem, min-K: the K smallest elements of every row, smallest first, found by the
+ * same two stages (stage 1 keeps the K' smallest of every bucket; Section 6.1 with the order
+ * reversed).  Total order: element a precedes element b when value(a) < value(b), or the values
+ * compare equal and index(a) < index(b).  Arguments, workspace, routes, limits and status codes
+ * as atk_approx_topk / atk_topk (atk_workspace_bytes and atk_describe_plan answer for both).
+ * The kernels are the same: every loaded value passes through the order-reversing map of its
+ * type (sign flip for floating types, complement for integers) and results pass back through it.
+ */
+int atk_approx_mink(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride,
+                    int K, int Kprime, int B, void* out_vals, int32_t* out_idx,
+                    void* workspace, size_t workspace_bytes, void* stream);
+int atk_mink(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride, int K,
+             void* out_vals, int32_t* out_idx, void* stream);
+
+/*
  * atk_approx_topk for callers that cannot allocate device memory or hand over a workspace (code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments
  * minus the workspace, same results.  Where atk_approx_topk would use a workspace (few-row

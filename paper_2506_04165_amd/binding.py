@@ -25,7 +25,7 @@ OP_APPROX_TOPK, OP_TOPK, OP_STAGE1 = 0, 1, 2
 SIZE_MAX = ctypes.c_size_t(-1).value
 
 EXPORTS = [
-    "atk_approx_topk", "atk_approx_topk_noalloc", "atk_topk", "atk_approx_topk_stage1", "atk_workspace_bytes",
+    "atk_approx_topk", "atk_approx_mink", "atk_mink", "atk_approx_topk_noalloc", "atk_topk", "atk_approx_topk_stage1", "atk_workspace_bytes",
     "atk_expected_recall", "atk_select_params", "atk_recall_params", "atk_set_option", "atk_approx_topk_recall", "atk_describe_plan", "atk_valu_probe", "atk_read_probe",
     "atk_mips_approx_topk", "atk_mips_workspace_bytes", "atk_mips_describe_plan", "atk_mips_select_params", "atk_mips_approx_topk_recall", "atk_status_string", "atk_last_hip_error",
     "atk_version",
@@ -49,6 +49,10 @@ def _load() -> ctypes.CDLL:
     i64, vp, ci, sz = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
     lib.atk_approx_topk.argtypes = [vp, ci, i64, i64, i64, ci, ci, ci, vp, vp, vp, sz, vp]
     lib.atk_approx_topk.restype = ci
+    lib.atk_approx_mink.argtypes = [vp, ci, i64, i64, i64, ci, ci, ci, vp, vp, vp, sz, vp]
+    lib.atk_approx_mink.restype = ci
+    lib.atk_mink.argtypes = [vp, ci, i64, i64, i64, ci, vp, vp, vp]
+    lib.atk_mink.restype = ci
     lib.atk_approx_topk_noalloc.argtypes = [vp, ci, i64, i64, i64, ci, ci, ci, vp, vp, vp]
     lib.atk_approx_topk_noalloc.restype = ci
     lib.atk_topk.argtypes = [vp, ci, i64, i64, i64, ci, vp, vp, vp, sz, vp]
@@ -213,8 +217,10 @@ def approx_topk_recall(values: torch.Tensor, K: int, recall_target: float, works
     return out_vals, out_idx, kp_used.value, b_used.value
 
 
-def approx_topk(values: torch.Tensor, K: int, Kprime: int, B: int, out=None, workspace=None):
-    """Two-stage approximate Top-K of every row.  Returns (vals[rows,K], idx[rows,K] int32)."""
+def approx_topk(values: torch.Tensor, K: int, Kprime: int, B: int, out=None, workspace=None,
+                smallest: bool = False):
+    """Two-stage approximate Top-K of every row (smallest: min-K, the K smallest, smallest first).
+    Returns (vals[rows,K], idx[rows,K] int32)."""
     rows, N, stride = _check_input(values)
     code = _dtype_code(values)
     if out is None:
@@ -228,11 +234,11 @@ def approx_topk(values: torch.Tensor, K: int, Kprime: int, B: int, out=None, wor
         if workspace is None or workspace.numel() * workspace.element_size() < need:
             workspace = torch.empty(need, dtype=torch.uint8, device=values.device)
         ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
-    st = lib.atk_approx_topk(values.data_ptr(), code, rows, N, stride, K, Kprime, B,
-                             out_vals.data_ptr(), out_idx.data_ptr(), ws_ptr, ws_bytes,
-                             _stream_ptr(values.device))
+    entry = lib.atk_approx_mink if smallest else lib.atk_approx_topk
+    st = entry(values.data_ptr(), code, rows, N, stride, K, Kprime, B,
+               out_vals.data_ptr(), out_idx.data_ptr(), ws_ptr, ws_bytes, _stream_ptr(values.device))
     if st != OK:
-        raise AtkError(st, "atk_approx_topk")
+        raise AtkError(st, "atk_approx_mink" if smallest else "atk_approx_topk")
     return out_vals, out_idx
 
 
@@ -248,8 +254,8 @@ def approx_topk_noalloc(values: torch.Tensor, K: int, Kprime: int, B: int, out):
     return out_vals, out_idx
 
 
-def topk(values: torch.Tensor, K: int, out=None):
-    """Exact Top-K of every row under the library's total order."""
+def topk(values: torch.Tensor, K: int, out=None, smallest: bool = False):
+    """Exact Top-K (smallest: min-K) of every row under the library's total order."""
     rows, N, stride = _check_input(values)
     code = _dtype_code(values)
     if out is None:
@@ -257,10 +263,14 @@ def topk(values: torch.Tensor, K: int, out=None):
         out_idx = torch.empty((rows, K), dtype=torch.int32, device=values.device)
     else:
         out_vals, out_idx = _check_out(out, rows, K, values.dtype, values.device)
-    st = lib.atk_topk(values.data_ptr(), code, rows, N, stride, K, out_vals.data_ptr(),
-                      out_idx.data_ptr(), None, 0, _stream_ptr(values.device))
+    if smallest:
+        st = lib.atk_mink(values.data_ptr(), code, rows, N, stride, K, out_vals.data_ptr(),
+                          out_idx.data_ptr(), _stream_ptr(values.device))
+    else:
+        st = lib.atk_topk(values.data_ptr(), code, rows, N, stride, K, out_vals.data_ptr(),
+                          out_idx.data_ptr(), None, 0, _stream_ptr(values.device))
     if st != OK:
-        raise AtkError(st, "atk_topk")
+        raise AtkError(st, "atk_mink" if smallest else "atk_topk")
     return out_vals, out_idx
 
 

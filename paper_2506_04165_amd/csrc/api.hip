@@ -519,6 +519,13 @@ static ApproxParams params_from(const Plan& pl, const void* values, int64_t rows
     return p;
 }
 
+// The mask that reverses the order of an element type (kernel dtype), xor-ed onto its (widened)
+// bit pattern: the sign bit of a floating type, every bit of an integer.  0 for the K greatest.
+static uint32_t flip_mask(int dtype, bool smallest) {
+    if (!smallest) return 0;
+    return (dtype == ATK_I32 || dtype == ATK_U32) ? 0xffffffffu : 0x80000000u;
+}
+
 static int hip_fail(hipError_t e) {
     g_last_hip_error = hipGetErrorString(e);
     return ATK_HIP_ERROR;
@@ -536,9 +543,10 @@ static int exact_threads(int64_t N) {
 // the two zeros apart.
 static int run_exact(const void* values, const int32_t* payload, int dtype, int64_t rows, int64_t N,
                      int64_t row_stride, int K, void* out_vals, int32_t* out_idx, hipStream_t st,
-                     const void* orig = nullptr, int64_t orig_stride = 0) {
+                     const void* orig = nullptr, int64_t orig_stride = 0, uint32_t flip = 0) {
     if (K > kExactMaxK) return ATK_UNSUPPORTED;
     TopkParams tp{};
+    tp.flip = flip;
     tp.values = values; tp.payload = payload; tp.row_stride = row_stride;
     tp.orig_values = orig; tp.orig_stride = orig_stride;
     tp.rows = (int)rows; tp.N = (int)N; tp.K = K;
@@ -613,11 +621,11 @@ MipsPlan make_mips_plan(int dtype, int64_t Q, int64_t N, int64_t D, int K, int K
 
 }  // namespace
 
-extern "C" {
+namespace {
 
-int atk_approx_topk(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride,
-                    int K, int Kprime, int B, void* out_vals, int32_t* out_idx,
-                    void* workspace, size_t workspace_bytes, void* stream) {
+static int approx_impl(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride,
+                       int K, int Kprime, int B, void* out_vals, int32_t* out_idx,
+                       void* workspace, size_t workspace_bytes, void* stream, bool smallest) {
     int rc = validate_common(values, dtype, rows, N, row_stride);
     if (rc) return rc;
     dtype = kernel_dtype(dtype);       // fp16 -> the bf16 kernels
@@ -634,10 +642,12 @@ int atk_approx_topk(const void* values, int dtype, int64_t rows, int64_t N, int6
     if ((uintptr_t)workspace % 8) return ATK_INVALID_ARG;
     if (rows == 0) return ATK_OK;
     hipStream_t st = (hipStream_t)stream;
+    const uint32_t flip = flip_mask(dtype, smallest);
     if (pl.route_exact)
-        return run_exact(values, nullptr, dtype, rows, N, row_stride, K, out_vals, out_idx, st);
+        return run_exact(values, nullptr, dtype, rows, N, row_stride, K, out_vals, out_idx, st, nullptr, 0, flip);
 
     ApproxParams p = params_from(pl, values, rows, N, row_stride, K, Kprime, B);
+    p.flip = flip;
     if (pl.slab_w > 0) {
         // slab path: the final K' keys of every bucket through the workspace, then stage 2
         p.mode = 3;
@@ -648,6 +658,7 @@ int atk_approx_topk(const void* values, int dtype, int64_t rows, int64_t N, int6
         FinishParams f{};
         f.part_keys = (const uint64_t*)workspace; f.values = values; f.row_stride = row_stride;
         f.rows = (int)rows; f.K = K; f.Kprime = Kprime; f.B = B; f.nseg = 1; f.Cpad = pl.Cpad;
+        f.flip = flip;
         f.out_vals = out_vals; f.out_idx = out_idx;
         e = launch_finish(f, dtype, pl.var->KP, st);
         return e == hipSuccess ? ATK_OK : hip_fail(e);
@@ -662,6 +673,7 @@ int atk_approx_topk(const void* values, int dtype, int64_t rows, int64_t N, int6
         FinishParams f{};
         f.part_keys = (const uint64_t*)workspace; f.values = values; f.row_stride = row_stride;
         f.rows = (int)rows; f.K = K; f.Kprime = Kprime; f.B = B; f.nseg = pl.nseg; f.Cpad = pl.Cpad;
+        f.flip = flip;
         f.out_vals = out_vals; f.out_idx = out_idx;
         e = launch_finish(f, dtype, pl.var->KP, st);
         return e == hipSuccess ? ATK_OK : hip_fail(e);
@@ -682,7 +694,7 @@ int atk_approx_topk(const void* values, int dtype, int64_t rows, int64_t N, int6
         p.out_vals = part_vals; p.out_idx = part_idx;
         hipError_t e = pl.var->fn(p, pl.grid, pl.block, pl.lds, st);
         if (e != hipSuccess) return hip_fail(e);
-        return run_exact(part_vals, part_idx, dtype, rows, C, C, K, out_vals, out_idx, st, values, row_stride);
+        return run_exact(part_vals, part_idx, dtype, rows, C, C, K, out_vals, out_idx, st, values, row_stride, flip);
     }
     // unfused: survivors [rows, K', B] through the workspace, then exact Top-K over them
     const int64_t C = (int64_t)B * Kprime;
@@ -694,7 +706,25 @@ int atk_approx_topk(const void* values, int dtype, int64_t rows, int64_t N, int6
     p.surv_aligned = ((uintptr_t)surv_vals % 16 == 0 && (uintptr_t)surv_idx % 16 == 0) ? 1 : 0;
     hipError_t e = pl.var->fn(p, pl.grid, pl.block, pl.lds, st);
     if (e != hipSuccess) return hip_fail(e);
-    return run_exact(surv_vals, surv_idx, dtype, rows, C, C, K, out_vals, out_idx, st, values, row_stride);
+    return run_exact(surv_vals, surv_idx, dtype, rows, C, C, K, out_vals, out_idx, st, values, row_stride, flip);
+}
+
+}  // namespace
+
+extern "C" {
+
+int atk_approx_topk(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride,
+                    int K, int Kprime, int B, void* out_vals, int32_t* out_idx,
+                    void* workspace, size_t workspace_bytes, void* stream) {
+    return approx_impl(values, dtype, rows, N, row_stride, K, Kprime, B, out_vals, out_idx, workspace,
+                       workspace_bytes, stream, false);
+}
+
+int atk_approx_mink(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride,
+                    int K, int Kprime, int B, void* out_vals, int32_t* out_idx,
+                    void* workspace, size_t workspace_bytes, void* stream) {
+    return approx_impl(values, dtype, rows, N, row_stride, K, Kprime, B, out_vals, out_idx, workspace,
+                       workspace_bytes, stream, true);
 }
 
 int atk_approx_topk_noalloc(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride,
@@ -755,10 +785,8 @@ int atk_approx_topk_recall(const void* values, int dtype, int64_t rows, int64_t 
                            workspace, workspace_bytes, stream);
 }
 
-int atk_topk(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride, int K,
-             void* out_vals, int32_t* out_idx, void* workspace, size_t workspace_bytes,
-             void* stream) {
-    (void)workspace; (void)workspace_bytes;
+static int exact_impl(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride, int K,
+                      void* out_vals, int32_t* out_idx, void* stream, bool smallest) {
     int rc = validate_common(values, dtype, rows, N, row_stride);
     if (rc) return rc;
     dtype = kernel_dtype(dtype);       // fp16 -> the bf16 kernels
@@ -768,7 +796,19 @@ int atk_topk(const void* values, int dtype, int64_t rows, int64_t N, int64_t row
     if (K > kExactMaxK) return ATK_UNSUPPORTED;
     if (rows == 0) return ATK_OK;
     return run_exact(values, nullptr, dtype, rows, N, row_stride, K, out_vals, out_idx,
-                     (hipStream_t)stream);
+                     (hipStream_t)stream, nullptr, 0, flip_mask(dtype, smallest));
+}
+
+int atk_topk(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride, int K,
+             void* out_vals, int32_t* out_idx, void* workspace, size_t workspace_bytes,
+             void* stream) {
+    (void)workspace; (void)workspace_bytes;
+    return exact_impl(values, dtype, rows, N, row_stride, K, out_vals, out_idx, stream, false);
+}
+
+int atk_mink(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride, int K,
+             void* out_vals, int32_t* out_idx, void* stream) {
+    return exact_impl(values, dtype, rows, N, row_stride, K, out_vals, out_idx, stream, true);
 }
 
 int atk_approx_topk_stage1(const void* values, int dtype, int64_t rows, int64_t N,

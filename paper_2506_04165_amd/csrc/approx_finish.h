@@ -11,6 +11,7 @@ struct FinishParams {
     const void* values;          // the input, only read to tell -0.0 from +0.0
     int64_t row_stride;
     int rows, K, Kprime, B, nseg;
+    uint32_t flip;               // the order-reversing mask the keys were built under (0: Top-K), see ApproxParams
     int Cpad;                    // power of two >= B*K'
     void* out_vals;
     int32_t* out_idx;

@@ -76,7 +76,7 @@ __global__ void __launch_bounds__(1024) approx_finish_kernel(FinishParams p) {
     __syncthreads();
     const char* rowp = (const char*)p.values + (size_t)row * p.row_stride * elem<DT>::size;
     wg_topk_from_lds<DT>(cand, p.Cpad, p.K, cand + p.Cpad, rowp, p.out_vals, p.out_idx,
-                         (int64_t)row * p.K);
+                         (int64_t)row * p.K, p.flip);
 }
 
 template <typename DT>

@@ -60,6 +60,10 @@ struct ApproxParams {
     int32_t* out_idx;
     void* surv_vals;
     int32_t* surv_idx;
+    uint32_t flip;        // 0: the K greatest.  The K smallest (min-K): the mask that reverses the order
+                          // of the element type, xor-ed onto every loaded pattern -- the sign bit of
+                          // a floating type (0x80000000 on the widened pattern), all bits of an
+                          // integer -- and again onto every pattern that is written out
     int surv_aligned;     // mode 1: both survivor arrays start at multiples of 16 bytes (vector stores allowed)
 };
 
@@ -277,18 +281,18 @@ struct ApproxKernel {
     // update).
     template <bool FULL = false>
     __device__ static __forceinline__ void consume(Lists<REP, KP, NL>& L, const vec_t& x, int r,
-                                                   int step) {
+                                                   int step, uint32_t flip) {
         if constexpr (BATCHED) {
             (void)L; (void)x; (void)r; (void)step;       // batches are fed by the streaming loop
         } else if constexpr (REP == 3) {
 #pragma unroll
             for (int v = 0; v < V; ++v)
-                L.insert(r * V + v, elem<DT>::ordered(VL::bits(x, v)), step);
+                L.insert(r * V + v, elem<DT>::ordered(VL::bits(x, v) ^ flip), step);
         } else if constexpr (!PACKED) {
 #pragma unroll
             for (int v = 0; v < V; ++v) {
-                if constexpr (FULL && KP > 1) L.insert_full(r * V + v, __uint_as_float(VL::bits(x, v)), step);
-                else L.insert(r * V + v, __uint_as_float(VL::bits(x, v)), step);
+                if constexpr (FULL && KP > 1) L.insert_full(r * V + v, __uint_as_float(VL::bits(x, v) ^ flip), step);
+                else L.insert(r * V + v, __uint_as_float(VL::bits(x, v) ^ flip), step);
             }
         } else {
             // Low half of every key of this step: 0xFFFF - step.  All elements of one list share
@@ -296,7 +300,7 @@ struct ApproxKernel {
             uint32_t low;
             asm("v_mov_b32 %0, %1" : "=v"(low) : "s"(0xffffu - (uint32_t)step));
             if constexpr (sizeof(vec_t) == 2) {
-                L.insert(r * V, ordered_from_bits((uint32_t)x << 16) | low);
+                L.insert(r * V, ordered_from_bits(((uint32_t)x << 16) ^ flip) | low);
             } else {
                 typedef short short2_t __attribute__((ext_vector_type(2)));
                 typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
@@ -304,7 +308,7 @@ struct ApproxKernel {
                 for (int d = 0; d < V / 2; ++d) {
                     // two bf16 per dword: ordered 16-bit images of both with packed 16-bit ops
                     // (sign fill, flip, and +1 on negatives so that -0.0 lands on +0.0's image)
-                    const uint32_t w = ((const uint32_t*)&x)[d];
+                    const uint32_t w = ((const uint32_t*)&x)[d] ^ (flip | (flip >> 16));   // both halves
                     const uint32_t sg = __builtin_bit_cast(uint32_t, __builtin_bit_cast(short2_t, w) >> (short)15);
                     const uint32_t fl = w ^ (sg | 0x80008000u);
                     const uint32_t o = __builtin_bit_cast(
@@ -316,7 +320,11 @@ struct ApproxKernel {
         }
     }
 
+    // MINK: the mirrored problem; every loaded pattern passes through the order-reversing xor
+    // (the Top-K instantiation carries no trace of it).
+    template <bool MINK>
     __device__ static void run(const ApproxParams& p, uint64_t* lds) {
+        const uint32_t flip = MINK ? p.flip : 0u;
         const int tid = threadIdx.x;
         const int g = tid >> p.log2G;
         const int t = tid & (p.G - 1);
@@ -380,7 +388,7 @@ struct ApproxKernel {
                 uint64_t batch[KP];
 #pragma unroll
                 for (int u = 0; u < KP; ++u) {
-                    const uint64_t key = ((uint64_t)elem<DT>::ordered(VL::bits(buf[u], 0)) << 32) |
+                    const uint64_t key = ((uint64_t)elem<DT>::ordered(VL::bits(buf[u], 0) ^ flip) << 32) |
                                          (uint32_t)(~(uint32_t)(s + u));
                     batch[u] = u < nb ? key : 0;
                 }
@@ -406,7 +414,7 @@ struct ApproxKernel {
                 for (int u = 0; u < KP; ++u)
                     if (u < nfill) {
 #pragma unroll
-                        for (int r = 0; r < R; ++r) consume<false>(L, buf[u][r], r, s + u);
+                        for (int r = 0; r < R; ++r) consume<false>(L, buf[u][r], r, s + u, flip);
                     }
                 s += nfill;
             }
@@ -423,7 +431,7 @@ struct ApproxKernel {
             for (int u = 0; u < U; ++u)
 #pragma unroll
                 for (int r = 0; r < R; ++r)
-                    consume<TWO_PHASE>(L, buf[u][r], r, s + u);
+                    consume<TWO_PHASE>(L, buf[u][r], r, s + u, flip);
         }
         if (s < s_end) {
             // the last, short batch: its loads are issued together as well (a step-by-step tail
@@ -442,7 +450,7 @@ struct ApproxKernel {
             for (int u = 0; u < U; ++u)
                 if (u < nlast) {
 #pragma unroll
-                    for (int r = 0; r < R; ++r) consume<TWO_PHASE>(L, buf[u][r], r, s + u);
+                    for (int r = 0; r < R; ++r) consume<TWO_PHASE>(L, buf[u][r], r, s + u, flip);
                 }
             s = s_end;
         }
@@ -476,7 +484,7 @@ struct ApproxKernel {
             if (p.G >= kWave) {
                 if (t < kWave && row_ok)
                     wave_sort32_dispatch<DT>(cand32, p.Cpad, p.K, rowp, p.out_vals, p.out_idx,
-                                             (int64_t)row * p.K);
+                                             (int64_t)row * p.K, flip);
             } else {
                 // several rows per wavefront: it sorts them one after the other
                 const int per_wave = kWave / p.G;
@@ -486,7 +494,7 @@ struct ApproxKernel {
                     if (rw < p.rows)
                         wave_sort32_dispatch<DT>((uint32_t*)lds + (size_t)gl * p.Cpad, p.Cpad, p.K,
                                                  (const char*)p.values + (size_t)rw * p.row_stride * ES,
-                                                 p.out_vals, p.out_idx, (int64_t)rw * p.K);
+                                                 p.out_vals, p.out_idx, (int64_t)rw * p.K, flip);
                 }
             }
             return;
@@ -521,6 +529,8 @@ struct ApproxKernel {
                         } else {
                             if (!Lists<REP, KP, NL>::exact_bits && (b << 1) == 0)   // either zero
                                 b = elem<DT>::load_bits(rowp, n);       // which zero it was
+                            else
+                                b ^= flip;                            // the stored pattern
                             const int64_t o = ((int64_t)row * p.Kprime + k) * p.B + bucket;
                             if ((V == 4 || V == 2) && elem<DT>::size == 4 && p.surv_aligned) {
                                 // the V buckets of a load are neighbours in plane k: one 16- or 8-byte
@@ -600,8 +610,7 @@ struct ApproxKernel {
                     cand[i] = key;
                 } else if (row_ok) {
                     const uint32_t n = key_index(key);
-                    uint32_t b = key_value_bits<DT>(key);
-                    if (b == 0 && key != 0) b = elem<DT>::load_bits(rowp, n);   // which zero it was
+                    const uint32_t b = key_stored_bits<DT>(key, rowp, n, flip);
                     const int64_t o = ((int64_t)row * p.Kprime + k) * p.B + bucket;
                     elem<DT>::store_bits(p.surv_vals, o, b);
                     p.surv_idx[o] = (int32_t)n;
@@ -615,13 +624,13 @@ struct ApproxKernel {
         if (p.tail == 1) {
             // few candidates: the first wavefront of every row's group sorts them in registers
             if (t < kWave && row_ok)
-                wave_sort_dispatch<DT>(cand, p.Cpad, p.K, rowp, p.out_vals, p.out_idx, out_base);
+                wave_sort_dispatch<DT>(cand, p.Cpad, p.K, rowp, p.out_vals, p.out_idx, out_base, flip);
             return;
         }
         if (p.tail == 2) {
             // one row per workgroup: thin the candidates out by radix selection, wave-sort the rest
             wg_topk_from_lds<DT>(lds, p.Cpad, p.K, lds + p.aux_offset, rowp, p.out_vals, p.out_idx,
-                                 out_base);
+                                 out_base, flip);
             return;
         }
         lds_bitonic_sort_desc(lds, p.rows_per_wg * p.Cpad, p.Cpad);
@@ -629,9 +638,7 @@ struct ApproxKernel {
             for (int i = t; i < p.K; i += p.G) {
                 const uint64_t key = cand[i];
                 const uint32_t n = key_index(key);
-                uint32_t b = key_value_bits<DT>(key);
-                if (b == 0 && key != 0) b = elem<DT>::load_bits(rowp, n);       // which zero it was
-                elem<DT>::store_bits(p.out_vals, out_base + i, b);
+                elem<DT>::store_bits(p.out_vals, out_base + i, key_stored_bits<DT>(key, rowp, n, flip));
                 p.out_idx[out_base + i] = (int32_t)n;
             }
         }
@@ -643,10 +650,10 @@ struct ApproxKernel {
 #ifndef ATK_PACKED_WAVES
 #define ATK_PACKED_WAVES 6      // wavefronts per SIMD the packed variants are compiled for
 #endif
-template <typename DT, int KP, int V, int R, int REP>
+template <typename DT, int KP, int V, int R, int REP, bool MINK>
 __global__ void __launch_bounds__(REP == 2 ? 256 : 1024, REP == 1 ? ATK_PACKED_WAVES : 1) approx_topk_kernel(ApproxParams p) {
     extern __shared__ uint64_t atk_lds[];
-    ApproxKernel<DT, KP, V, R, REP>::run(p, atk_lds);
+    ApproxKernel<DT, KP, V, R, REP>::template run<MINK>(p, atk_lds);
 }
 
 // Host-side launcher, one explicit instantiation per supported (dtype, KP, V, R, REP).
@@ -658,11 +665,17 @@ hipError_t launch_approx(const ApproxParams& p, int grid, int block, size_t lds_
     template <>                                                                                 \
     hipError_t launch_approx<DT, KP, V, R, REP>(const ApproxParams& p, int grid, int block,     \
                                                    size_t lds_bytes, hipStream_t stream) {      \
-        allow_large_lds((const void*)approx_topk_kernel<DT, KP, V, R, REP>, lds_bytes);         \
-        hipLaunchKernelGGL((approx_topk_kernel<DT, KP, V, R, REP>),                             \
-                           dim3(grid, p.mode == 2 ? p.nseg : (p.mode == 3 ? p.B / p.slab_w :                \
-                                     (p.chunk > 0 ? (p.B + p.chunk - 1) / p.chunk : 1))), dim3(block), \
-                           lds_bytes, stream, p);                                               \
+        const dim3 g(grid, p.mode == 2 ? p.nseg : (p.mode == 3 ? p.B / p.slab_w :               \
+                           (p.chunk > 0 ? (p.B + p.chunk - 1) / p.chunk : 1)));                 \
+        if (p.flip == 0) {                                                                      \
+            allow_large_lds((const void*)approx_topk_kernel<DT, KP, V, R, REP, false>, lds_bytes); \
+            hipLaunchKernelGGL((approx_topk_kernel<DT, KP, V, R, REP, false>), g, dim3(block),  \
+                               lds_bytes, stream, p);                                           \
+        } else {                                                                                \
+            allow_large_lds((const void*)approx_topk_kernel<DT, KP, V, R, REP, true>, lds_bytes); \
+            hipLaunchKernelGGL((approx_topk_kernel<DT, KP, V, R, REP, true>), g, dim3(block),   \
+                               lds_bytes, stream, p);                                           \
+        }                                                                                       \
         return hipGetLastError();                                                               \
     }
 

@@ -133,6 +133,17 @@ struct WaveSort {
 // pointers; through this type their accesses are LDS instructions rather than flat ones.
 template <typename T> using lds_ptr = __attribute__((address_space(3))) T*;
 
+// Stored bit pattern of the element a key stands for.  Keys are built from values after the
+// order-reversing map of the min-K problem (`flip`: 0 for Top-K; xor-ed onto the pattern: the sign
+// bit of floating types, all bits of integers), so the pattern comes back through the same xor;
+// a zero is re-read from the row, where its sign is (rowp; not read for scores, whose zero is +0.0).
+template <typename DT>
+__device__ __forceinline__ uint32_t key_stored_bits(uint64_t key, const void* rowp, uint32_t index, uint32_t flip) {
+    const uint32_t bits = key_value_bits<DT>(key);
+    if (bits == 0 && key != 0) return elem<DT>::load_bits(rowp, index);
+    return bits ^ flip;
+}
+
 // Position in a staging array of LDS for the key of rank e, chosen so that neither a wavefront
 // writing its registers (lane l, register j holds rank l*R + j) nor one reading ranks lane,
 // lane + 64, ... meets bank conflicts beyond the width of the access: the position inside each
@@ -148,7 +159,7 @@ __device__ __forceinline__ int staged_rank(int e) {
 template <typename DT, int R>
 __device__ __forceinline__ void wave_write_topk(const uint64_t (&k)[R], int K, const void* rowp,
                                                 void* out_vals, int32_t* out_idx, int64_t out_base,
-                                                uint64_t* stage_generic) {
+                                                uint64_t* stage_generic, uint32_t flip = 0) {
     lds_ptr<uint64_t> stage = (lds_ptr<uint64_t>)stage_generic;
     const int lane = __lane_id();
     if (lane * R < K) {
@@ -159,9 +170,7 @@ __device__ __forceinline__ void wave_write_topk(const uint64_t (&k)[R], int K, c
     for (int e = lane; e < K; e += kWave) {
         const uint64_t key = stage[staged_rank<R, 2>(e)];
         const uint32_t n = key_index(key);
-        uint32_t bits = key_value_bits<DT>(key);
-        if (bits == 0 && key != 0) bits = elem<DT>::load_bits(rowp, n);   // which zero it was
-        elem<DT>::store_bits(out_vals, out_base + e, bits);
+        elem<DT>::store_bits(out_vals, out_base + e, key_stored_bits<DT>(key, rowp, n, flip));
         out_idx[out_base + e] = (int32_t)n;
     }
 }
@@ -170,7 +179,8 @@ __device__ __forceinline__ void wave_write_topk(const uint64_t (&k)[R], int K, c
 // for K rounded up to a multiple of R keys) is reused as staging.
 template <typename DT, int R>
 __device__ __forceinline__ void wave_sort_from_lds(uint64_t* keys_generic, int n, int K, const void* rowp,
-                                                   void* out_vals, int32_t* out_idx, int64_t out_base) {
+                                                   void* out_vals, int32_t* out_idx, int64_t out_base,
+                                                   uint32_t flip) {
     lds_ptr<uint64_t> keys = (lds_ptr<uint64_t>)keys_generic;
     const int lane = __lane_id();
     uint64_t k[R];
@@ -180,26 +190,28 @@ __device__ __forceinline__ void wave_sort_from_lds(uint64_t* keys_generic, int n
         k[j] = i < n ? keys[i] : 0;
     }
     WaveSort<R>::sort(k);
-    wave_write_topk<DT, R>(k, K, rowp, out_vals, out_idx, out_base, keys_generic);
+    wave_write_topk<DT, R>(k, K, rowp, out_vals, out_idx, out_base, keys_generic, flip);
 }
 
 // Not inlined on purpose: the sorting networks are long, and every streaming kernel variant
 // that finishes in LDS shares this one copy per translation unit.
 template <typename DT>
 __device__ __noinline__ void wave_sort_dispatch(uint64_t* keys, int n, int K, const void* rowp,
-                                                   void* out_vals, int32_t* out_idx, int64_t out_base) {
-    if (n <= 64)       wave_sort_from_lds<DT, 1>(keys, n, K, rowp, out_vals, out_idx, out_base);
-    else if (n <= 128) wave_sort_from_lds<DT, 2>(keys, n, K, rowp, out_vals, out_idx, out_base);
-    else if (n <= 256) wave_sort_from_lds<DT, 4>(keys, n, K, rowp, out_vals, out_idx, out_base);
-    else if (n <= 512) wave_sort_from_lds<DT, 8>(keys, n, K, rowp, out_vals, out_idx, out_base);
-    else               wave_sort_from_lds<DT, 16>(keys, n, K, rowp, out_vals, out_idx, out_base);
+                                                   void* out_vals, int32_t* out_idx, int64_t out_base,
+                                                   uint32_t flip = 0) {
+    if (n <= 64)       wave_sort_from_lds<DT, 1>(keys, n, K, rowp, out_vals, out_idx, out_base, flip);
+    else if (n <= 128) wave_sort_from_lds<DT, 2>(keys, n, K, rowp, out_vals, out_idx, out_base, flip);
+    else if (n <= 256) wave_sort_from_lds<DT, 4>(keys, n, K, rowp, out_vals, out_idx, out_base, flip);
+    else if (n <= 512) wave_sort_from_lds<DT, 8>(keys, n, K, rowp, out_vals, out_idx, out_base, flip);
+    else               wave_sort_from_lds<DT, 16>(keys, n, K, rowp, out_vals, out_idx, out_base, flip);
 }
 
 // ---- packed 32-bit keys (bf16 rows of at most 65536 elements) ---------------------------------
 // key = ordered 16-bit value << 16 | (0xFFFF - index); 0 = empty.
 template <typename DT, int R>
 __device__ __forceinline__ void wave_sort32_from_lds(uint32_t* keys_generic, int n, int K, const void* rowp,
-                                                     void* out_vals, int32_t* out_idx, int64_t out_base) {
+                                                     void* out_vals, int32_t* out_idx, int64_t out_base,
+                                                     uint32_t flip) {
     lds_ptr<uint32_t> keys = (lds_ptr<uint32_t>)keys_generic;
     const int lane = __lane_id();
     uint32_t k[R];
@@ -220,6 +232,7 @@ __device__ __forceinline__ void wave_sort32_from_lds(uint32_t* keys_generic, int
         const uint32_t idx = 0xffffu - (key & 0xffffu);
         uint32_t bits = bits_from_ordered(key & 0xffff0000u);
         if (bits == 0 && key != 0) bits = elem<DT>::load_bits(rowp, idx);   // which zero it was
+        else bits ^= flip;                                                  // (min-K: back through the sign flip)
         elem<DT>::store_bits(out_vals, out_base + e, bits);
         out_idx[out_base + e] = (int32_t)idx;
     }
@@ -227,12 +240,13 @@ __device__ __forceinline__ void wave_sort32_from_lds(uint32_t* keys_generic, int
 
 template <typename DT>
 __device__ __noinline__ void wave_sort32_dispatch(uint32_t* keys, int n, int K, const void* rowp,
-                                                  void* out_vals, int32_t* out_idx, int64_t out_base) {
-    if (n <= 64)       wave_sort32_from_lds<DT, 1>(keys, n, K, rowp, out_vals, out_idx, out_base);
-    else if (n <= 128) wave_sort32_from_lds<DT, 2>(keys, n, K, rowp, out_vals, out_idx, out_base);
-    else if (n <= 256) wave_sort32_from_lds<DT, 4>(keys, n, K, rowp, out_vals, out_idx, out_base);
-    else if (n <= 512) wave_sort32_from_lds<DT, 8>(keys, n, K, rowp, out_vals, out_idx, out_base);
-    else               wave_sort32_from_lds<DT, 16>(keys, n, K, rowp, out_vals, out_idx, out_base);
+                                                  void* out_vals, int32_t* out_idx, int64_t out_base,
+                                                  uint32_t flip = 0) {
+    if (n <= 64)       wave_sort32_from_lds<DT, 1>(keys, n, K, rowp, out_vals, out_idx, out_base, flip);
+    else if (n <= 128) wave_sort32_from_lds<DT, 2>(keys, n, K, rowp, out_vals, out_idx, out_base, flip);
+    else if (n <= 256) wave_sort32_from_lds<DT, 4>(keys, n, K, rowp, out_vals, out_idx, out_base, flip);
+    else if (n <= 512) wave_sort32_from_lds<DT, 8>(keys, n, K, rowp, out_vals, out_idx, out_base, flip);
+    else               wave_sort32_from_lds<DT, 16>(keys, n, K, rowp, out_vals, out_idx, out_base, flip);
 }
 
 // Slab route of the streaming kernel: the 64*R keys at `keys` (LDS) are the partial lists of
@@ -356,13 +370,12 @@ __device__ __forceinline__ void lds_select_bin(const uint64_t* keys, int n, uint
 // Decode and write the first K keys of a sorted LDS array; every thread of the workgroup.
 template <typename DT>
 __device__ __forceinline__ void wg_write_topk(const uint64_t* keys, int K, const void* rowp,
-                                              void* out_vals, int32_t* out_idx, int64_t out_base) {
+                                              void* out_vals, int32_t* out_idx, int64_t out_base,
+                                              uint32_t flip = 0) {
     for (int i = threadIdx.x; i < K; i += blockDim.x) {
         const uint64_t key = keys[i];
         const uint32_t idx = key_index(key);
-        uint32_t bits = key_value_bits<DT>(key);
-        if (bits == 0 && key != 0) bits = elem<DT>::load_bits(rowp, idx);   // which zero it was
-        elem<DT>::store_bits(out_vals, out_base + i, bits);
+        elem<DT>::store_bits(out_vals, out_base + i, key_stored_bits<DT>(key, rowp, idx, flip));
         out_idx[out_base + i] = (int32_t)idx;
     }
 }
@@ -606,16 +619,16 @@ __device__ __noinline__ uint64_t wg_select_threshold(const uint64_t* keys, int n
 template <typename DT>
 __device__ __forceinline__ void wg_topk_from_lds(uint64_t* keys, int n, int K, void* scratch,
                                                  const void* rowp, void* out_vals,
-                                                 int32_t* out_idx, int64_t out_base) {
+                                                 int32_t* out_idx, int64_t out_base, uint32_t flip = 0) {
     const int tid = threadIdx.x, T = blockDim.x;
     // few keys, or most of them wanted: sort them all
     if (n <= 256 || (n <= kWaveSortMaxKeys && 4 * K > n)) {
         if (n > kWgSortMinKeys && T >= kWgSortMinThreads) {
             wg_sort_merge_topk(keys, n, K);
-            wg_write_topk<DT>(keys, K, rowp, out_vals, out_idx, out_base);
+            wg_write_topk<DT>(keys, K, rowp, out_vals, out_idx, out_base, flip);
             return;
         }
-        if (tid < kWave) wave_sort_dispatch<DT>(keys, n, K, rowp, out_vals, out_idx, out_base);
+        if (tid < kWave) wave_sort_dispatch<DT>(keys, n, K, rowp, out_vals, out_idx, out_base, flip);
         return;
     }
     // twice that many keys with an eighth or more of them wanted: sorting them all (four runs,
@@ -623,7 +636,7 @@ __device__ __forceinline__ void wg_topk_from_lds(uint64_t* keys, int n, int K, v
     // or for a smaller share, the selection wins)
     if (T >= kWgSortMinThreads && n == 2 * kWaveSortMaxKeys && 8 * K >= n) {
         wg_sort_merge_topk(keys, n, K);
-        wg_write_topk<DT>(keys, K, rowp, out_vals, out_idx, out_base);
+        wg_write_topk<DT>(keys, K, rowp, out_vals, out_idx, out_base, flip);
         return;
     }
     if (K <= kWaveSortMaxKeys) {
@@ -648,16 +661,16 @@ __device__ __forceinline__ void wg_topk_from_lds(uint64_t* keys, int n, int K, v
                 for (int i = total + tid; i < padded; i += T) buf[i] = 0;
                 __syncthreads();
                 wg_sort_merge_topk(buf, padded, K);
-                wg_write_topk<DT>(buf, K, rowp, out_vals, out_idx, out_base);
+                wg_write_topk<DT>(buf, K, rowp, out_vals, out_idx, out_base, flip);
                 return;
             }
-            if (tid < kWave) wave_sort_dispatch<DT>(buf, total, K, rowp, out_vals, out_idx, out_base);
+            if (tid < kWave) wave_sort_dispatch<DT>(buf, total, K, rowp, out_vals, out_idx, out_base, flip);
             return;
         }
     }
     // fallback: order everything
     lds_bitonic_sort_desc(keys, n, n);
-    wg_write_topk<DT>(keys, K, rowp, out_vals, out_idx, out_base);
+    wg_write_topk<DT>(keys, K, rowp, out_vals, out_idx, out_base, flip);
 }
 
 }  // namespace atk

@@ -12,6 +12,8 @@ struct TopkParams {
     const void* orig_values;  // survivor mode: the rows the survivors were taken from ...
     int64_t orig_stride;      // ... and their stride (read only to tell -0.0 from +0.0)
     int rows, N, K;
+    uint32_t flip;            // 0: the K greatest; min-K: the order-reversing mask of the element type, xor-ed
+                              // onto every loaded pattern and again onto every pattern written out
     int cap;                  // LDS key buffer capacity (power of two, >= 1024, > K)
     int onepass;              // try the single pass with a rising threshold first (needs K <= 1024,
                               // cap >= 1024 + one round of the workgroup, cap <= 16 * threads)

@@ -89,11 +89,12 @@ __device__ __forceinline__ void for_each_element(const char* rowp, int begin, in
 // Until a threshold exists every element is kept, and the row is taken one round of the whole
 // workgroup (a 16-byte vector, or one element, per thread) at a time; after that in stretches
 // sized by how many keys are expected to pass.
-template <typename DT, bool PAYLOAD, bool VEC>
+template <typename DT, bool PAYLOAD, bool VEC, bool MINK>
 __device__ __forceinline__ bool onepass(const TopkParams& p, const char* rowp, const int32_t* payload,
                                         uint64_t* buf, void* scratch, uint32_t* ctl, int& count) {
     const int tid = threadIdx.x, T = blockDim.x, lane = tid & (kWave - 1);
     const int N = p.N, cap = p.cap;
+    const uint32_t flip = MINK ? p.flip : 0u;
     constexpr int VE = VEC ? 16 / elem<DT>::size : 1;
     constexpr int kMaxRounds = 1024;
     constexpr int kInFlight = 4;            // vector loads a lane issues before it looks at the first (8 and 16: no faster)
@@ -120,6 +121,7 @@ __device__ __forceinline__ bool onepass(const TopkParams& p, const char* rowp, c
         // elements at or above it have their key built and compared
         const uint32_t thr_bits = elem<DT>::floor_bits((uint32_t)(thr >> 32));
         for_each_element<DT, VEC, kInFlight>(rowp, done, end, [&](uint32_t b, int n) {
+            b ^= flip;
             bool pass = elem<DT>::ge(b, thr_bits);
             if (__ballot(pass) == 0) return;
             uint64_t key = 0;
@@ -179,8 +181,11 @@ __device__ __forceinline__ bool onepass(const TopkParams& p, const char* rowp, c
     return true;
 }
 
-template <typename DT, bool PAYLOAD, bool VEC>
+// MINK: the mirrored problem (the K smallest): every loaded pattern passes through the
+// order-reversing xor p.flip; the Top-K instantiation carries no trace of it.
+template <typename DT, bool PAYLOAD, bool VEC, bool MINK>
 __global__ void __launch_bounds__(1024) topk_exact_kernel(TopkParams p) {
+    const uint32_t flip = MINK ? p.flip : 0u;
     extern __shared__ uint64_t lds64[];
     // layout: [0, cap) key buffer (the histogram aliases its start), scratch of the final
     // selection, then 32 control words
@@ -196,12 +201,12 @@ __global__ void __launch_bounds__(1024) topk_exact_kernel(TopkParams p) {
 
     if (p.onepass) {
         int count = 0;
-        if (onepass<DT, PAYLOAD, VEC>(p, rowp, payload, lds64, scratch, ctl, count)) {
+        if (onepass<DT, PAYLOAD, VEC, MINK>(p, rowp, payload, lds64, scratch, ctl, count)) {
             const int n1 = next_pow2(count);
             for (int i = count + tid; i < n1; i += T) lds64[i] = 0;
             __syncthreads();
             const char* bits_row1 = PAYLOAD ? (const char*)p.orig_values + (size_t)row * p.orig_stride * elem<DT>::size : rowp;
-            wg_topk_from_lds<DT>(lds64, n1, p.K, scratch, bits_row1, p.out_vals, p.out_idx, (int64_t)row * p.K);
+            wg_topk_from_lds<DT>(lds64, n1, p.K, scratch, bits_row1, p.out_vals, p.out_idx, (int64_t)row * p.K, flip);
             return;
         }
         __syncthreads();
@@ -225,6 +230,7 @@ __global__ void __launch_bounds__(1024) topk_exact_kernel(TopkParams p) {
             // (one compare of the stored value rejects what lies below the lower bound)
             const uint32_t dmin_bits = elem<DT>::floor_bits(dmin << 21);
             for_each_element<DT, VEC>(rowp, base, end, [&](uint32_t b, int) {
+                b ^= flip;
                 if (elem<DT>::ge(b, dmin_bits)) atomicAdd(&hist[elem<DT>::ordered(b) >> 21], 1u);
             });
             // (only once at least K keys have been counted: the walk needs K of them)
@@ -248,7 +254,7 @@ __global__ void __launch_bounds__(1024) topk_exact_kernel(TopkParams p) {
             for (int i = tid; i < kSelectBins; i += T) hist[i] = 0;
             __syncthreads();
             for_each_element<DT, VEC>(rowp, 0, N, [&](uint32_t b, int n) {
-                const uint64_t key = make_key<DT>(b, index_of(n));
+                const uint64_t key = make_key<DT>(b ^ flip, index_of(n));
                 if ((key & mask) == prefix) atomicAdd(&hist[(uint32_t)(key >> shift) & dmask], 1u);
             });
             hist_find_digit(hist, ctl, need, digit, above, count);
@@ -265,6 +271,7 @@ __global__ void __launch_bounds__(1024) topk_exact_kernel(TopkParams p) {
     const uint32_t prefix_bits = elem<DT>::floor_bits((uint32_t)(prefix >> 32));
     for_each_element<DT, VEC>(rowp, 0, N, [&](uint32_t b, int n) {
         // cheap reject on the stored value before the key is built
+        b ^= flip;
         if (elem<DT>::ge(b, prefix_bits)) {
             const uint64_t key = make_key<DT>(b, index_of(n));
             if ((key & mask) >= prefix) {
@@ -281,7 +288,7 @@ __global__ void __launch_bounds__(1024) topk_exact_kernel(TopkParams p) {
     // survivor mode: a key's index is the original position, so a zero's stored bits are re-read
     // from the original row like everywhere else
     const char* bits_row = PAYLOAD ? (const char*)p.orig_values + (size_t)row * p.orig_stride * elem<DT>::size : rowp;
-    wg_topk_from_lds<DT>(lds64, n2, p.K, scratch, bits_row, p.out_vals, p.out_idx, (int64_t)row * p.K);
+    wg_topk_from_lds<DT>(lds64, n2, p.K, scratch, bits_row, p.out_vals, p.out_idx, (int64_t)row * p.K, flip);
 }
 
 template <typename DT>
@@ -294,9 +301,15 @@ hipError_t launch_for(const TopkParams& p, int threads, hipStream_t stream) {
         allow_large_lds((const void*)kernel, lds);
         hipLaunchKernelGGL(kernel, grid, block, lds, stream, p);
     };
-    if (p.payload) launch(topk_exact_kernel<DT, true, false>);
-    else if (vec)  launch(topk_exact_kernel<DT, false, true>);
-    else           launch(topk_exact_kernel<DT, false, false>);
+    if (p.flip == 0) {
+        if (p.payload) launch(topk_exact_kernel<DT, true, false, false>);
+        else if (vec)  launch(topk_exact_kernel<DT, false, true, false>);
+        else           launch(topk_exact_kernel<DT, false, false, false>);
+    } else {
+        if (p.payload) launch(topk_exact_kernel<DT, true, false, true>);
+        else if (vec)  launch(topk_exact_kernel<DT, false, true, true>);
+        else           launch(topk_exact_kernel<DT, false, false, true>);
+    }
     return hipGetLastError();
 }
 
