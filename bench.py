@@ -143,12 +143,19 @@ def bench_workload(name, steps, warmup, with_cpu_baseline, only_params=None):
 
     # exact Top-K on the same inputs (the comparison system)
     exact_steps = max(3, steps // 4)
-    ex = time_steps(lambda i: atk.topk(xs[i], w.K, out=(out_v, out_i)), copies, exact_steps,
+    need = atk.workspace_bytes(atk.OP_TOPK, w.dtype, w.rows, w.N, w.K, 0, 0)
+    ews = torch.empty(need, dtype=torch.uint8, device=dev) if need else False
+    ex = time_steps(lambda i: atk.topk(xs[i], w.K, out=(out_v, out_i), workspace=ews), copies, exact_steps,
                     max(1, warmup // 4))
+    # the radix-selection kernel by itself (what atk_topk runs without a workspace)
+    exr = time_steps(lambda i: atk.topk(xs[i], w.K, out=(out_v, out_i), workspace=False), copies, exact_steps,
+                     max(1, warmup // 4)) if need else ex
     ev, ei = atk.topk(xs[0], w.K)
     exact = {"kernel_ms_avg": ex["kernel_ms_avg"], "rows_per_s": w.rows / (ex["kernel_ms_avg"] * 1e-3),
              "achieved_gbps": alg / (ex["kernel_ms_avg"] * 1e-3) / 1e9,
-             "frac_of_peak": alg / (ex["kernel_ms_avg"] * 1e-3) / 1e9 / HBM_PEAK_GBPS, "steps": exact_steps}
+             "frac_of_peak": alg / (ex["kernel_ms_avg"] * 1e-3) / 1e9 / HBM_PEAK_GBPS, "steps": exact_steps,
+             "plan": atk.describe_topk_plan(w.dtype, w.rows, w.N, w.K)[1],
+             "radix_kernel_ms_avg": exr["kernel_ms_avg"]}
     # context for the comparison system itself: the library exact Top-K on the same input
     lib = time_steps(lambda i: torch.topk(xs[i], w.K, dim=1), copies, 5, 2)
     exact["torch_topk_ms_avg"] = lib["kernel_ms_avg"]

@@ -99,7 +99,7 @@ int atk_approx_mink(const void* values, int dtype, int64_t rows, int64_t N, int6
                     int K, int Kprime, int B, void* out_vals, int32_t* out_idx,
                     void* workspace, size_t workspace_bytes, void* stream);
 int atk_mink(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride, int K,
-             void* out_vals, int32_t* out_idx, void* stream);
+             void* out_vals, int32_t* out_idx, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * atk_approx_topk for callers that cannot allocate device memory or hand over a workspace (code
@@ -122,6 +122,14 @@ int atk_approx_topk_noalloc(const void* values, int dtype, int64_t rows, int64_t
 /*
  * Exact Top-K of every row under the same total order (the comparison system of Section 7; also
  * what the method reduces to at K' = K or B = 1).  Arguments as above.  ATK_UNSUPPORTED: K > 8192.
+ *
+ * workspace: optional device memory, 8-byte aligned.  With atk_workspace_bytes(ATK_OP_TOPK, ...)
+ * bytes (0 where it does not apply: short rows, K < 8, K > 1024) rows that are long against K are
+ * done by the two-stage kernels at a (B, K' = 4) chosen by the library, followed by a kernel that
+ * certifies each row exact (no bucket contributes K' elements to the result) or repairs it from
+ * the buckets in doubt: one pass over the input at the approximate method's speed, the result is
+ * the exact Top-K bit for bit.  Without it (null, or too small) a radix-selection kernel runs,
+ * which needs no workspace.  Workspace contents need not be initialised and are not preserved.
  */
 int atk_topk(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride, int K,
              void* out_vals, int32_t* out_idx, void* workspace, size_t workspace_bytes,
@@ -181,6 +189,13 @@ int atk_approx_topk_recall(const void* values, int dtype, int64_t rows, int64_t 
                            int64_t row_stride, int K, double recall_target, void* out_vals,
                            int32_t* out_idx, void* workspace, size_t workspace_bytes,
                            void* stream, int* Kprime_used, int* B_used);
+
+/*
+ * One-line description of how atk_topk / atk_mink run the given problem when handed the workspace
+ * atk_workspace_bytes(ATK_OP_TOPK, ...) asks for: "certified B=... K'=... workspace=..." or
+ * "radix threads=...".  Host only; for logs and tests.
+ */
+int atk_describe_topk_plan(int dtype, int64_t rows, int64_t N, int K, char* buf, size_t buflen);
 
 /*
  * Writes a one-line description of how atk_approx_topk would run the given problem (kernel

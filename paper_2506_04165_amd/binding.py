@@ -26,7 +26,7 @@ SIZE_MAX = ctypes.c_size_t(-1).value
 
 EXPORTS = [
     "atk_approx_topk", "atk_approx_mink", "atk_mink", "atk_approx_topk_noalloc", "atk_topk", "atk_approx_topk_stage1", "atk_workspace_bytes",
-    "atk_expected_recall", "atk_select_params", "atk_recall_params", "atk_set_option", "atk_approx_topk_recall", "atk_describe_plan", "atk_valu_probe", "atk_read_probe",
+    "atk_expected_recall", "atk_select_params", "atk_recall_params", "atk_set_option", "atk_approx_topk_recall", "atk_describe_plan", "atk_describe_topk_plan", "atk_valu_probe", "atk_read_probe",
     "atk_mips_approx_topk", "atk_mips_workspace_bytes", "atk_mips_describe_plan", "atk_mips_select_params", "atk_mips_approx_topk_recall", "atk_status_string", "atk_last_hip_error",
     "atk_version",
 ]
@@ -51,7 +51,7 @@ def _load() -> ctypes.CDLL:
     lib.atk_approx_topk.restype = ci
     lib.atk_approx_mink.argtypes = [vp, ci, i64, i64, i64, ci, ci, ci, vp, vp, vp, sz, vp]
     lib.atk_approx_mink.restype = ci
-    lib.atk_mink.argtypes = [vp, ci, i64, i64, i64, ci, vp, vp, vp]
+    lib.atk_mink.argtypes = [vp, ci, i64, i64, i64, ci, vp, vp, vp, sz, vp]
     lib.atk_mink.restype = ci
     lib.atk_approx_topk_noalloc.argtypes = [vp, ci, i64, i64, i64, ci, ci, ci, vp, vp, vp]
     lib.atk_approx_topk_noalloc.restype = ci
@@ -78,6 +78,8 @@ def _load() -> ctypes.CDLL:
     lib.atk_read_probe.restype = ci
     lib.atk_describe_plan.argtypes = [ci, i64, i64, ci, ci, ci, ctypes.c_char_p, sz]
     lib.atk_describe_plan.restype = ci
+    lib.atk_describe_topk_plan.argtypes = [ci, i64, i64, ci, ctypes.c_char_p, sz]
+    lib.atk_describe_topk_plan.restype = ci
     lib.atk_mips_approx_topk.argtypes = [vp, vp, ci, i64, i64, i64, ci, ci, ci, vp, vp, vp, sz, vp]
     lib.atk_mips_approx_topk.restype = ci
     lib.atk_mips_workspace_bytes.argtypes = [ci, i64, i64, i64, ci, ci, ci]
@@ -149,6 +151,12 @@ def describe_plan(dtype: torch.dtype, rows: int, N: int, K: int, Kprime: int, B:
     code = _CODES[dtype]
     buf = ctypes.create_string_buffer(512)
     st = lib.atk_describe_plan(code, rows, N, K, Kprime, B, buf, 512)
+    return st, buf.value.decode()
+
+
+def describe_topk_plan(dtype: torch.dtype, rows: int, N: int, K: int):
+    buf = ctypes.create_string_buffer(512)
+    st = lib.atk_describe_topk_plan(_CODES[dtype], rows, N, K, buf, 512)
     return st, buf.value.decode()
 
 
@@ -254,8 +262,10 @@ def approx_topk_noalloc(values: torch.Tensor, K: int, Kprime: int, B: int, out):
     return out_vals, out_idx
 
 
-def topk(values: torch.Tensor, K: int, out=None, smallest: bool = False):
-    """Exact Top-K (smallest: min-K) of every row under the library's total order."""
+def topk(values: torch.Tensor, K: int, out=None, smallest: bool = False, workspace=None):
+    """Exact Top-K (smallest: min-K) of every row under the library's total order.  workspace:
+    a uint8 device tensor of workspace_bytes(OP_TOPK, ...) bytes, allocated here when omitted;
+    False: none (the radix-selection kernel)."""
     rows, N, stride = _check_input(values)
     code = _dtype_code(values)
     if out is None:
@@ -263,12 +273,16 @@ def topk(values: torch.Tensor, K: int, out=None, smallest: bool = False):
         out_idx = torch.empty((rows, K), dtype=torch.int32, device=values.device)
     else:
         out_vals, out_idx = _check_out(out, rows, K, values.dtype, values.device)
-    if smallest:
-        st = lib.atk_mink(values.data_ptr(), code, rows, N, stride, K, out_vals.data_ptr(),
-                          out_idx.data_ptr(), _stream_ptr(values.device))
-    else:
-        st = lib.atk_topk(values.data_ptr(), code, rows, N, stride, K, out_vals.data_ptr(),
-                          out_idx.data_ptr(), None, 0, _stream_ptr(values.device))
+    ws_ptr, ws_bytes = None, 0
+    if workspace is None:
+        need = int(lib.atk_workspace_bytes(OP_TOPK, code, rows, N, K, 0, 0))
+        if need not in (0, SIZE_MAX):
+            workspace = torch.empty(need, dtype=torch.uint8, device=values.device)
+    if workspace is not None and workspace is not False:
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    entry = lib.atk_mink if smallest else lib.atk_topk
+    st = entry(values.data_ptr(), code, rows, N, stride, K, out_vals.data_ptr(), out_idx.data_ptr(),
+               ws_ptr, ws_bytes, _stream_ptr(values.device))
     if st != OK:
         raise AtkError(st, "atk_mink" if smallest else "atk_topk")
     return out_vals, out_idx

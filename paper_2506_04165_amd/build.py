@@ -21,6 +21,7 @@ ARCH = "gfx950"
 SOURCES = [
     "api.hip",
     "topk_exact.hip",
+    "certify.hip",
     "approx_finish.hip",
     "mips_fused.hip",
     "mips_fused_long.hip",

@@ -1,6 +1,7 @@
 // C ABI of libatk: argument validation, launch planning and dispatch (host code only).
 #include <hip/hip_runtime.h>
 
+#include <cmath>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -13,6 +14,7 @@
 #include "mips_fused.h"
 #include "approx_kernel.h"
 #include "topk_exact.h"
+#include "certify.h"
 #include "select_params.h"
 
 namespace atk {
@@ -135,6 +137,9 @@ struct Options {
                               // no faster than passing all survivors on, slower when rows are few)
     int onepass = 1;          // 0: the exact kernel always takes two passes over a row; 2: one pass
                               // is tried on short rows too
+    int certified = 1;        // 0: the exact entry points never go through the two-stage kernels + certificate
+    int reg_rows = 1;         // 0: the exact kernel never keeps a short row in registers
+    int exact_threads = 0;    // 0: planner's choice, else lanes of an exact-kernel workgroup (a power of two, 64..1024)
 };
 static Options g_opt;
 static unsigned g_opt_generation = 1;      // bumped by every change: cached plans are keyed on it
@@ -532,6 +537,7 @@ static int hip_fail(hipError_t e) {
 }
 
 static int exact_threads(int64_t N) {
+    if (g_opt.exact_threads) return g_opt.exact_threads;
     int t = pow2_ceil((N + 63) / 64);     // about 64 elements per lane, more lanes for long rows
     if (t < 64) t = 64;
     if (t > 1024) t = 1024;
@@ -543,10 +549,12 @@ static int exact_threads(int64_t N) {
 // the two zeros apart.
 static int run_exact(const void* values, const int32_t* payload, int dtype, int64_t rows, int64_t N,
                      int64_t row_stride, int K, void* out_vals, int32_t* out_idx, hipStream_t st,
-                     const void* orig = nullptr, int64_t orig_stride = 0, uint32_t flip = 0) {
+                     const void* orig = nullptr, int64_t orig_stride = 0, uint32_t flip = 0,
+                     const int32_t* row_mask = nullptr) {
     if (K > kExactMaxK) return ATK_UNSUPPORTED;
     TopkParams tp{};
     tp.flip = flip;
+    tp.row_mask = row_mask;
     tp.values = values; tp.payload = payload; tp.row_stride = row_stride;
     tp.orig_values = orig; tp.orig_stride = orig_stride;
     tp.rows = (int)rows; tp.N = (int)N; tp.K = K;
@@ -569,6 +577,14 @@ static int run_exact(const void* values, const int32_t* payload, int dtype, int6
         int cap1 = pow2_ceil(1024 + (int64_t)round);
         if (cap1 < tp.cap) cap1 = tp.cap;
         if (cap1 <= 8192 && cap1 <= 16 * t1) { tp.cap = cap1; tp.onepass = 1; threads = t1; }
+    }
+    // A short row goes into registers once (all of its loads in flight together) and every pass
+    // runs from there.
+    const int ve = 16 / elem_size(dtype);
+    if (g_opt.reg_rows != 0 && !payload && !tp.onepass && g_opt.exact_threads == 0 && N % ve == 0 &&
+        N <= (int64_t)kRegRowThreads * ve * kRegRowVectors && N * elem_size(dtype) >= 4096) {
+        tp.reg_row = 1;
+        threads = kRegRowThreads;
     }
     tp.out_vals = out_vals; tp.out_idx = out_idx;
     hipError_t e = launch_topk_exact(tp, dtype, threads, st);
@@ -623,6 +639,101 @@ MipsPlan make_mips_plan(int dtype, int64_t Q, int64_t N, int64_t D, int K, int K
 
 namespace {
 
+// ---- exact Top-K through the two-stage kernels plus a certificate ------------------------------
+// Where rows are long against K, the exact entry points run the approximate path at a (B, K')
+// for which a bucket rarely holds more than K' of the K greatest, then the certificate kernel
+// (certify.hip) proves the rows exact or repairs them from the few buckets in doubt, and the
+// radix-selection kernel takes whatever rows that kernel gave up on.
+struct CertPlan { int B = 0, Kprime = 0; };      // B == 0: not applicable
+
+// Expected number of buckets per row that hold at least kp of the K greatest elements, placement
+// at random: B * P[Binomial(K, 1/B) >= kp] (the balls-in-buckets model of Section 6.2).
+static double expected_full_buckets(int K, int B, int kp) {
+    const double q = 1.0 / B;
+    double term = std::pow(1.0 - q, K), below = 0.0;          // P[X = i], i = 0 ...
+    for (int i = 0; i < kp; ++i) {
+        below += term;
+        term *= (double)(K - i) / (i + 1) * q / (1.0 - q);
+    }
+    return B * std::fmax(0.0, 1.0 - below);
+}
+
+constexpr int kCertKprime = 4;              // the fast list length (one maximum and three medians per element)
+constexpr int kCertMinK = 8;                // below, K' = 4 would be K' >= K
+constexpr int kCertMinRowPerSurvivor = 16;  // N >= 16 B K': otherwise stage 2 costs more than a second pass
+constexpr int kCertMaxScan = 65536;         // elements a repairing workgroup reads again
+
+static CertPlan certified_params(int64_t N, int K) {
+    struct Slot { int64_t N; int K; unsigned gen; CertPlan cp; };
+    thread_local Slot last{0, 0, 0, {}};
+    options_from_env_once();
+    if (last.N == N && last.K == K && last.gen == g_opt_generation) return last.cp;
+    CertPlan cp;
+    if (g_opt.certified != 0 && K >= kCertMinK && K <= kWaveSortMaxKeys) {
+        // smallest B (fewest survivors) at which nearly every row is certified at once; failing
+        // that, the smallest at which a row needs about one bucket repaired.  Powers of two first
+        // (the fast kernels), then any divisor of N.
+        int chosen = 0;
+        for (int pass = 0; pass < 2 && !chosen; ++pass) {
+            int fallback = 0;
+            for (int64_t B = 64; B <= kCertifyMaxB; B = pass ? B + 1 : B << 1) {
+                if (B * kCertKprime * kCertMinRowPerSurvivor > N) break;
+                if (N % B || N / B <= kCertKprime || B * kCertKprime < K) continue;
+                const double e = expected_full_buckets(K, (int)B, kCertKprime);
+                if (e <= 0.05) { fallback = (int)B; break; }
+                if (e <= 1.5 && !fallback) fallback = (int)B;
+            }
+            chosen = fallback;
+        }
+        if (chosen) { cp.B = chosen; cp.Kprime = kCertKprime; }
+    }
+    last = {N, K, g_opt_generation, cp};
+    return cp;
+}
+
+static size_t certified_lists_bytes(int64_t rows) { return ((size_t)rows * 4 + 255) & ~(size_t)255; }
+
+static int approx_impl(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride,
+                       int K, int Kprime, int B, void* out_vals, int32_t* out_idx,
+                       void* workspace, size_t workspace_bytes, void* stream, bool smallest);
+
+// dtype: the kernel's (fp16 already mapped).  Arguments validated by the caller.  A workspace that
+// is absent or too small for the certified route only selects the radix-selection kernel.
+static int exact_dispatch(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride, int K,
+                          void* out_vals, int32_t* out_idx, void* workspace, size_t workspace_bytes,
+                          hipStream_t st, bool smallest) {
+    const uint32_t flip = flip_mask(dtype, smallest);
+    const CertPlan cp = certified_params(N, K);
+    const size_t lists = certified_lists_bytes(rows);
+    if (cp.B && workspace && (uintptr_t)workspace % 8 == 0 && workspace_bytes >= lists) {
+        const size_t rest = workspace_bytes - lists;
+        size_t need;
+        {
+            const Plan& pl = make_plan(values, dtype, rows, N, row_stride, K, cp.Kprime, cp.B, false, rest);
+            need = (pl.status == ATK_OK && !pl.route_exact) ? pl.workspace : SIZE_MAX;
+        }
+        if (need <= rest) {
+            int rc = approx_impl(values, dtype, rows, N, row_stride, K, cp.Kprime, cp.B, out_vals, out_idx,
+                                 (char*)workspace + lists, rest, (void*)st, smallest);
+            if (rc) return rc;
+            CertifyParams c{};
+            c.values = values; c.row_stride = row_stride;
+            c.rows = (int)rows; c.N = (int)N; c.K = K; c.Kprime = cp.Kprime; c.B = cp.B;
+            c.flip = flip;
+            c.cap = (int)pow2_ceil(2 * (int64_t)K);
+            if (c.cap < 1024) c.cap = 1024;
+            c.max_scan = kCertMaxScan;
+            c.out_vals = out_vals; c.out_idx = out_idx;
+            c.hard_rows = (int32_t*)workspace;
+            hipError_t e = launch_certify(c, dtype, st);
+            if (e != hipSuccess) return hip_fail(e);
+            return run_exact(values, nullptr, dtype, rows, N, row_stride, K, out_vals, out_idx, st,
+                             nullptr, 0, flip, c.hard_rows);
+        }
+    }
+    return run_exact(values, nullptr, dtype, rows, N, row_stride, K, out_vals, out_idx, st, nullptr, 0, flip);
+}
+
 static int approx_impl(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride,
                        int K, int Kprime, int B, void* out_vals, int32_t* out_idx,
                        void* workspace, size_t workspace_bytes, void* stream, bool smallest) {
@@ -644,7 +755,8 @@ static int approx_impl(const void* values, int dtype, int64_t rows, int64_t N, i
     hipStream_t st = (hipStream_t)stream;
     const uint32_t flip = flip_mask(dtype, smallest);
     if (pl.route_exact)
-        return run_exact(values, nullptr, dtype, rows, N, row_stride, K, out_vals, out_idx, st, nullptr, 0, flip);
+        return exact_dispatch(values, dtype, rows, N, row_stride, K, out_vals, out_idx, workspace,
+                              workspace_bytes, st, smallest);
 
     ApproxParams p = params_from(pl, values, rows, N, row_stride, K, Kprime, B);
     p.flip = flip;
@@ -786,7 +898,8 @@ int atk_approx_topk_recall(const void* values, int dtype, int64_t rows, int64_t 
 }
 
 static int exact_impl(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride, int K,
-                      void* out_vals, int32_t* out_idx, void* stream, bool smallest) {
+                      void* out_vals, int32_t* out_idx, void* workspace, size_t workspace_bytes,
+                      void* stream, bool smallest) {
     int rc = validate_common(values, dtype, rows, N, row_stride);
     if (rc) return rc;
     dtype = kernel_dtype(dtype);       // fp16 -> the bf16 kernels
@@ -795,20 +908,41 @@ static int exact_impl(const void* values, int dtype, int64_t rows, int64_t N, in
     if ((uintptr_t)out_vals % elem_size(dtype) || (uintptr_t)out_idx % 4) return ATK_INVALID_ARG;
     if (K > kExactMaxK) return ATK_UNSUPPORTED;
     if (rows == 0) return ATK_OK;
-    return run_exact(values, nullptr, dtype, rows, N, row_stride, K, out_vals, out_idx,
-                     (hipStream_t)stream, nullptr, 0, flip_mask(dtype, smallest));
+    return exact_dispatch(values, dtype, rows, N, row_stride, K, out_vals, out_idx, workspace,
+                          workspace_bytes, (hipStream_t)stream, smallest);
 }
 
 int atk_topk(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride, int K,
              void* out_vals, int32_t* out_idx, void* workspace, size_t workspace_bytes,
              void* stream) {
-    (void)workspace; (void)workspace_bytes;
-    return exact_impl(values, dtype, rows, N, row_stride, K, out_vals, out_idx, stream, false);
+    return exact_impl(values, dtype, rows, N, row_stride, K, out_vals, out_idx, workspace, workspace_bytes,
+                      stream, false);
 }
 
 int atk_mink(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride, int K,
-             void* out_vals, int32_t* out_idx, void* stream) {
-    return exact_impl(values, dtype, rows, N, row_stride, K, out_vals, out_idx, stream, true);
+             void* out_vals, int32_t* out_idx, void* workspace, size_t workspace_bytes, void* stream) {
+    return exact_impl(values, dtype, rows, N, row_stride, K, out_vals, out_idx, workspace, workspace_bytes,
+                      stream, true);
+}
+
+int atk_describe_topk_plan(int dtype, int64_t rows, int64_t N, int K, char* buf, size_t buflen) {
+    if (!buf || buflen == 0) return ATK_INVALID_ARG;
+    buf[0] = 0;
+    dtype = kernel_dtype(dtype);
+    if (dtype < 0 || rows < 0 || N <= 0 || N > kMaxN || K < 1 || K > N) return ATK_INVALID_ARG;
+    if (K > kExactMaxK) return ATK_UNSUPPORTED;
+    options_from_env_once();
+    const CertPlan cp = certified_params(N, K);
+    if (cp.B) {
+        const Plan& pl = make_plan(nullptr, dtype, rows, N, N, K, cp.Kprime, cp.B, false);
+        if (pl.status == ATK_OK && !pl.route_exact) {
+            std::snprintf(buf, buflen, "certified B=%d K'=%d workspace=%zu (else radix threads=%d)", cp.B, cp.Kprime,
+                          certified_lists_bytes(rows) + pl.workspace, exact_threads(N));
+            return ATK_OK;
+        }
+    }
+    std::snprintf(buf, buflen, "radix threads=%d", exact_threads(N));
+    return ATK_OK;
 }
 
 int atk_approx_topk_stage1(const void* values, int dtype, int64_t rows, int64_t N,
@@ -837,7 +971,14 @@ size_t atk_workspace_bytes(int op, int dtype, int64_t rows, int64_t N, int K, in
     dtype = kernel_dtype(dtype);
     if (dtype < 0) return SIZE_MAX;
     if (rows < 0 || N <= 0 || N > kMaxN) return SIZE_MAX;
-    if (op == ATK_OP_TOPK) return (K < 1 || K > N) ? SIZE_MAX : 0;
+    if (op == ATK_OP_TOPK) {
+        if (K < 1 || K > N) return SIZE_MAX;
+        options_from_env_once();
+        const CertPlan cp = certified_params(N, K);
+        if (!cp.B) return 0;
+        const Plan& pl = make_plan(nullptr, dtype, rows, N, N, K, cp.Kprime, cp.B, false);
+        return (pl.status == ATK_OK && !pl.route_exact) ? certified_lists_bytes(rows) + pl.workspace : 0;
+    }
     if (op == ATK_OP_STAGE1) return validate_method(N, Kprime, Kprime, B) ? SIZE_MAX : 0;
     if (op != ATK_OP_APPROX_TOPK) return SIZE_MAX;
     if (validate_method(N, K, Kprime, B)) return SIZE_MAX;
@@ -948,11 +1089,13 @@ int atk_set_option(const char* name, int value) {
         {"slab", &Options::slab}, {"packed", &Options::packed}, {"subwave", &Options::subwave},
         {"batch_min_kp", &Options::batch_min_kp}, {"mips_segments", &Options::mips_segments},
         {"unfused", &Options::unfused}, {"onepass", &Options::onepass}, {"chunked", &Options::chunked},
+        {"exact_threads", &Options::exact_threads}, {"certified", &Options::certified}, {"reg_rows", &Options::reg_rows},
     };
     for (const Entry& e : entries) {
         if (std::strcmp(name, e.name) != 0) continue;
         int v = value < 0 ? defaults.*(e.field) : value;
         if (e.field == &Options::lanes_per_row && (v > kMaxLanes || (v & (v - 1)))) return ATK_INVALID_ARG;
+        if (e.field == &Options::exact_threads && v != 0 && (v < 64 || v > 1024 || (v & (v - 1)))) return ATK_INVALID_ARG;
         g_opt.*(e.field) = v;
         ++g_opt_generation;
         return ATK_OK;

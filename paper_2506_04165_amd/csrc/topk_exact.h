@@ -5,6 +5,9 @@
 
 namespace atk {
 
+constexpr int kRegRowVectors = 8;     // 16-byte vectors of a short row a thread keeps in registers
+constexpr int kRegRowThreads = 256;   // ... in a workgroup of this many threads
+
 struct TopkParams {
     const void* values;       // [rows, row_stride] elements of the given dtype
     const int32_t* payload;   // optional [rows, row_stride] original indices (survivor mode)
@@ -17,6 +20,9 @@ struct TopkParams {
     int cap;                  // LDS key buffer capacity (power of two, >= 1024, > K)
     int onepass;              // try the single pass with a rising threshold first (needs K <= 1024,
                               // cap >= 1024 + one round of the workgroup, cap <= 16 * threads)
+    int reg_row;              // short aligned rows (N <= 256 threads x 8 vectors of 16 bytes, N a multiple of the
+                              // vector length, 256 threads, no payload): keep the row in registers
+    const int32_t* row_mask;  // optional [rows]: only rows with a non-zero entry are done, the others' outputs stay
     void* out_vals;
     int32_t* out_idx;
 };

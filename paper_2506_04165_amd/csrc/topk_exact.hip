@@ -183,8 +183,13 @@ __device__ __forceinline__ bool onepass(const TopkParams& p, const char* rowp, c
 
 // MINK: the mirrored problem (the K smallest): every loaded pattern passes through the
 // order-reversing xor p.flip; the Top-K instantiation carries no trace of it.
-template <typename DT, bool PAYLOAD, bool VEC, bool MINK>
-__global__ void __launch_bounds__(1024) topk_exact_kernel(TopkParams p) {
+// NV > 0: a short row (at most NV 16-byte vectors per thread of a 256-thread workgroup, N a
+// multiple of the vector length) is loaded into registers once, all loads in flight together, and
+// every pass below runs over the registers: one trip to memory instead of one per chunk and pass,
+// which is what a row of a few tens of kilobytes spends its time on.
+template <typename DT, bool PAYLOAD, bool VEC, bool MINK, int NV = 0>
+__global__ void __launch_bounds__(NV > 0 ? kRegRowThreads : 1024, NV > 0 ? 4 : 1) topk_exact_kernel(TopkParams p) {
+    static_assert(NV == 0 || (VEC && !PAYLOAD), "rows in registers: vector loads of the row itself");
     const uint32_t flip = MINK ? p.flip : 0u;
     extern __shared__ uint64_t lds64[];
     // layout: [0, cap) key buffer (the histogram aliases its start), scratch of the final
@@ -194,12 +199,46 @@ __global__ void __launch_bounds__(1024) topk_exact_kernel(TopkParams p) {
     uint32_t* ctl = (uint32_t*)((char*)scratch + kSelectScratchBytes);   // 3: fill  4..: wave sums
     const int tid = threadIdx.x, T = blockDim.x;
     const int row = blockIdx.x;
+    if (p.row_mask && p.row_mask[row] == 0) return;      // (uniform: the whole workgroup leaves)
     const char* rowp = (const char*)p.values + (size_t)row * p.row_stride * elem<DT>::size;
     const int32_t* payload = PAYLOAD ? p.payload + (size_t)row * p.row_stride : nullptr;
     const int N = p.N;
     auto index_of = [&](int n) -> uint32_t { return PAYLOAD ? (uint32_t)payload[n] : (uint32_t)n; };
 
-    if (p.onepass) {
+    constexpr int VE = 16 / elem<DT>::size;
+    uint4 regs[NV > 0 ? NV : 1];
+    if constexpr (NV > 0) {
+        const uint4* vp = (const uint4*)rowp;
+        const int nvec = N / VE;
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            const int i = u * T + tid;
+            regs[u] = i < nvec ? vp[i] : uint4{0u, 0u, 0u, 0u};
+        }
+    }
+    // fn(bits, n) for every element n in [begin, end) (begin a multiple of T * VE when NV > 0)
+    auto each = [&](int begin, int end, auto&& fn) {
+        if constexpr (NV > 0) {
+#pragma unroll
+            for (int u = 0; u < NV; ++u) {
+                const int first = (u * T + tid) * VE;            // this thread's elements of vector u
+                if (first >= begin && first < end) {
+                    const uint32_t* w = (const uint32_t*)&regs[u];
+#pragma unroll
+                    for (int e = 0; e < VE; ++e) {
+                        uint32_t b;
+                        if constexpr (elem<DT>::size == 4) b = w[e];
+                        else b = (e & 1) ? (w[e >> 1] & 0xffff0000u) : (w[e >> 1] << 16);
+                        fn(b, first + e);
+                    }
+                }
+            }
+        } else {
+            for_each_element<DT, VEC>(rowp, begin, end, fn);
+        }
+    };
+
+    if (NV == 0 && p.onepass) {
         int count = 0;
         if (onepass<DT, PAYLOAD, VEC, MINK>(p, rowp, payload, lds64, scratch, ctl, count)) {
             const int n1 = next_pow2(count);
@@ -220,16 +259,17 @@ __global__ void __launch_bounds__(1024) topk_exact_kernel(TopkParams p) {
     {
         for (int i = tid; i < kSelectBins; i += T) hist[i] = 0;
         __syncthreads();
-        constexpr int VE = 16 / elem<DT>::size;
         // vectors per lane and chunk: more in flight on long rows, early lower bound on short ones
-        const int chunk = T * VE * (N >= 131072 ? 8 : (N >= 32768 ? 4 : 1));
+        // (a row in registers is counted in one sweep: finding a lower bound costs more than the
+        // atomics it would save)
+        const int chunk = NV > 0 ? N : T * VE * (N >= 131072 ? 8 : (N >= 32768 ? 4 : 1));
         uint32_t dmin = 0;
         int next_update = chunk;
         for (int base = 0; base < N; base += chunk) {
             const int end = min(N, base + chunk);
             // (one compare of the stored value rejects what lies below the lower bound)
             const uint32_t dmin_bits = elem<DT>::floor_bits(dmin << 21);
-            for_each_element<DT, VEC>(rowp, base, end, [&](uint32_t b, int) {
+            each(base, end, [&](uint32_t b, int) {
                 b ^= flip;
                 if (elem<DT>::ge(b, dmin_bits)) atomicAdd(&hist[elem<DT>::ordered(b) >> 21], 1u);
             });
@@ -253,7 +293,7 @@ __global__ void __launch_bounds__(1024) topk_exact_kernel(TopkParams p) {
             const uint32_t dmask = (1u << kDigitBits[d]) - 1u;
             for (int i = tid; i < kSelectBins; i += T) hist[i] = 0;
             __syncthreads();
-            for_each_element<DT, VEC>(rowp, 0, N, [&](uint32_t b, int n) {
+            each(0, N, [&](uint32_t b, int n) {
                 const uint64_t key = make_key<DT>(b ^ flip, index_of(n));
                 if ((key & mask) == prefix) atomicAdd(&hist[(uint32_t)(key >> shift) & dmask], 1u);
             });
@@ -269,7 +309,55 @@ __global__ void __launch_bounds__(1024) topk_exact_kernel(TopkParams p) {
     if (tid == 0) ctl[3] = 0;
     __syncthreads();
     const uint32_t prefix_bits = elem<DT>::floor_bits((uint32_t)(prefix >> 32));
-    for_each_element<DT, VEC>(rowp, 0, N, [&](uint32_t b, int n) {
+    if constexpr (NV > 0) {
+        // from registers: count first, reserve the slots of a whole wavefront with one atomic, then
+        // store -- instead of one atomic round trip per element that qualifies
+        // With the leading digit alone as prefix -- the usual case -- one compare of the stored
+        // value decides: it holds exactly when the key's leading digit is at or above the prefix's.
+        const bool one_digit = mask == ((uint64_t)0x7ff << 53);
+        auto general = [&](uint32_t b, int n, uint64_t& key) {
+            if (!elem<DT>::ge(b, prefix_bits)) return false;
+            key = make_key<DT>(b, (uint32_t)n);
+            return (key & mask) >= prefix;
+        };
+        int mine = 0;
+        if (one_digit) {
+            each(0, N, [&](uint32_t b, int) { mine += elem<DT>::ge(b ^ flip, prefix_bits) ? 1 : 0; });
+        } else {
+            each(0, N, [&](uint32_t b, int n) {
+                uint64_t key;
+                if (general(b ^ flip, n, key)) ++mine;
+            });
+        }
+        const int lane = tid & (kWave - 1);
+        int incl = mine;
+        for (int o = 1; o < kWave; o <<= 1) {
+            const int other = __shfl_up(incl, o, kWave);
+            if (lane >= o) incl += other;
+        }
+        uint32_t base = 0;
+        if (lane == kWave - 1 && incl > 0) base = atomicAdd(&ctl[3], (uint32_t)incl);
+        base = (uint32_t)__shfl((int)base, kWave - 1, kWave);
+        uint32_t slot = base + (uint32_t)(incl - mine);
+        // (slot < cap always holds; the test keeps a slip memory safe)
+        if (one_digit) {
+            each(0, N, [&](uint32_t b, int n) {
+                if (elem<DT>::ge(b ^ flip, prefix_bits)) {
+                    if (slot < (uint32_t)p.cap) lds64[slot] = make_key<DT>(b ^ flip, (uint32_t)n);
+                    ++slot;
+                }
+            });
+        } else {
+            each(0, N, [&](uint32_t b, int n) {
+                uint64_t key;
+                if (general(b ^ flip, n, key)) {
+                    if (slot < (uint32_t)p.cap) lds64[slot] = key;
+                    ++slot;
+                }
+            });
+        }
+    } else
+    each(0, N, [&](uint32_t b, int n) {
         // cheap reject on the stored value before the key is built
         b ^= flip;
         if (elem<DT>::ge(b, prefix_bits)) {
@@ -301,14 +389,19 @@ hipError_t launch_for(const TopkParams& p, int threads, hipStream_t stream) {
         allow_large_lds((const void*)kernel, lds);
         hipLaunchKernelGGL(kernel, grid, block, lds, stream, p);
     };
+    constexpr int VE = 16 / elem<DT>::size;
+    const bool in_regs = vec && p.reg_row && threads == kRegRowThreads && p.N % VE == 0 &&
+                         p.N <= kRegRowThreads * VE * kRegRowVectors;
     if (p.flip == 0) {
-        if (p.payload) launch(topk_exact_kernel<DT, true, false, false>);
-        else if (vec)  launch(topk_exact_kernel<DT, false, true, false>);
-        else           launch(topk_exact_kernel<DT, false, false, false>);
+        if (p.payload)    launch(topk_exact_kernel<DT, true, false, false>);
+        else if (in_regs) launch(topk_exact_kernel<DT, false, true, false, kRegRowVectors>);
+        else if (vec)     launch(topk_exact_kernel<DT, false, true, false>);
+        else              launch(topk_exact_kernel<DT, false, false, false>);
     } else {
-        if (p.payload) launch(topk_exact_kernel<DT, true, false, true>);
-        else if (vec)  launch(topk_exact_kernel<DT, false, true, true>);
-        else           launch(topk_exact_kernel<DT, false, false, true>);
+        if (p.payload)    launch(topk_exact_kernel<DT, true, false, true>);
+        else if (in_regs) launch(topk_exact_kernel<DT, false, true, true, kRegRowVectors>);
+        else if (vec)     launch(topk_exact_kernel<DT, false, true, true>);
+        else              launch(topk_exact_kernel<DT, false, false, true>);
     }
     return hipGetLastError();
 }
