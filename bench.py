@@ -39,16 +39,16 @@ PAPER_CONTEXT = {
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by a plain
 # copy of known size (profiles/approx_topk_<workload>_B<B>_Kp<K'>.md), keyed by (workload, B, K').
 MEASURED_TRAFFIC_BYTES = {
-    ("c4_mips", 1024, 4): 1076464134,
-    ("c4_mips", 4096, 1): 1076397580,
-    ("c2_ffn", 128, 4): 498396060,
-    ("c2_ffn", 1024, 1): 498726578,
-    ("c2_ffn", 64, 8): 498432796,
-    ("c3_vocab", 512, 4): 528306441,
-    ("c3_vocab", 512, 2): 528078226,
-    ("c5_adversarial", 256, 8): 271165303,
-    ("c5_adversarial", 256, 1): 278122377,
-    ("c5_adversarial", 256, 32): 272396236,
+    ("c4_mips", 1024, 4): 1076602857,
+    ("c4_mips", 4096, 1): 1076454222,
+    ("c2_ffn", 128, 4): 498471710,
+    ("c2_ffn", 1024, 1): 498750710,
+    ("c2_ffn", 64, 8): 498481630,
+    ("c3_vocab", 512, 4): 528427726,
+    ("c3_vocab", 512, 2): 528294908,
+    ("c5_adversarial", 256, 8): 271144655,
+    ("c5_adversarial", 256, 1): 278910068,
+    ("c5_adversarial", 256, 32): 272451600,
 }
 
 
@@ -195,6 +195,7 @@ def bench_workload(name, steps, warmup, with_cpu_baseline, only_params=None):
             "recall_index": ir, "recall_value": vr,
             "expected_recall_random_placement": atk.expected_recall(w.N, B, w.K, Kp),
             "speedup_vs_exact": ex["kernel_ms_avg"] / t["kernel_ms_avg"],
+            "speedup_vs_radix_select_exact": exr["kernel_ms_avg"] / t["kernel_ms_avg"],
             "min_k_kernel_ms_median": tm["kernel_ms_median"],
             "traffic_bytes": MEASURED_TRAFFIC_BYTES.get((name, B, Kp)),
             # the other roof, the vector ALU (39.3 T lane-ops/s): by the operations the kernel
@@ -373,6 +374,38 @@ def bench_unfused(steps, warmup):
             "configs": res, "exact_topk_us": ex["kernel_ms_median"] * 1e3}
 
 
+def bench_exact(steps, warmup):
+    """The exact Top-K entry point on the benchmark workloads: the route the library picks when
+    handed a workspace (two-stage kernels + certificate where rows are long against K) and the
+    radix-selection kernel alone."""
+    import torch
+    from paper_2506_04165_amd import binding as atk, workloads
+    dev = "cuda:0"
+    out = {}
+    for name in ("c4_mips", "c3_vocab", "c5_adversarial", "c2_ffn"):
+        w = workloads.WORKLOADS[name]
+        esize = 4 if w.dtype == torch.float32 else 2
+        in_bytes = w.rows * w.N * esize
+        copies = max(2, -(-(2 << 30) // in_bytes) + 1)
+        xs = [workloads.make(name, seed=1 + c, device=dev) for c in range(copies)]
+        alg = algorithmic_bytes(w.rows, w.N, w.K, esize)
+        ov = torch.empty((w.rows, w.K), dtype=w.dtype, device=dev)
+        oi = torch.empty((w.rows, w.K), dtype=torch.int32, device=dev)
+        need = atk.workspace_bytes(atk.OP_TOPK, w.dtype, w.rows, w.N, w.K, 0, 0)
+        ws = torch.empty(need, dtype=torch.uint8, device=dev) if need else False
+        t = time_steps(lambda i: atk.topk(xs[i], w.K, out=(ov, oi), workspace=ws), copies, steps, warmup)
+        r = time_steps(lambda i: atk.topk(xs[i], w.K, out=(ov, oi), workspace=False), copies, steps, warmup) if need else t
+        sec = t["kernel_ms_median"] * 1e-3
+        out[name] = {"plan": atk.describe_topk_plan(w.dtype, w.rows, w.N, w.K)[1],
+                     "us_per_call_median": sec * 1e6, "us_per_call_min": t["kernel_ms_min"] * 1e3,
+                     "radix_alone_us_per_call_median": r["kernel_ms_median"] * 1e3,
+                     "algorithmic_bytes": alg, "achieved_gbps": alg / sec / 1e9,
+                     "frac_of_peak": alg / sec / 1e9 / HBM_PEAK_GBPS}
+        del xs
+        torch.cuda.empty_cache()
+    return out
+
+
 def cpu_baseline(name, xd, B, Kp):
     """The CPU oracle, as it stands, on a bounded sample of rows of the same workload."""
     from oracle import oracle
@@ -412,6 +445,8 @@ def main():
                     help="run only the Table 1 shape (8 x 262144, K=1024) and print it (for profiling)")
     ap.add_argument("--unfused-only", action="store_true",
                     help="run only the unfused-route section and print it (for profiling those kernels)")
+    ap.add_argument("--exact-only", action="store_true",
+                    help="run only the exact Top-K entry point on c2-c5 and print it (for profiling those kernels)")
     ap.add_argument("--mips-only", action="store_true",
                     help="run only the matmul-fused section and print it (for profiling that kernel)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -445,6 +480,9 @@ def main():
         return
     if args.unfused_only:
         print(json.dumps({"unfused": bench_unfused(max(10, args.steps // 2), 5)}))
+        return
+    if args.exact_only:
+        print(json.dumps({"exact_topk": bench_exact(max(10, args.steps // 5), 5)}))
         return
     if args.mips_only:
         print(json.dumps({"mips_fused": bench_mips_fused(max(10, args.steps // 5), max(5, args.warmup // 10))}))

@@ -176,3 +176,74 @@ def test_short_rows_kept_in_registers(atk, knobs):
     torch.cuda.synchronize()
     ov, oi = oracle.topk(np.ascontiguousarray(base[:, 3:].numpy()), 64)
     assert np.array_equal(gi.cpu().numpy(), oi) and np.array_equal(raw(gv), oracle_raw(ov))
+
+
+def _random_rows(rng, rows, N, dt, style, K):
+    if dt in (torch.int32, torch.uint32):
+        lo, hi = (-(1 << 31), (1 << 31)) if style % 2 == 0 else (-50, 50)
+        x = rng.integers(lo, hi, (rows, N)).astype(np.uint32).view(np.int32)
+        if style == 2:
+            x = np.sort(x, axis=1)
+        t = torch.from_numpy(x)
+        return t.view(torch.uint32) if dt == torch.uint32 else t
+    x = rng.standard_normal((rows, N)).astype(np.float32)
+    if style == 1:                                     # heavy ties
+        x = np.round(x * 4) / 4
+    elif style == 2:                                   # sorted, either way
+        x = np.sort(x, axis=1)[:, ::-1 if rng.integers(2) else 1].copy()
+    elif style == 3:                                   # extremes packed into a few residues of a random modulus
+        m = int(2 ** rng.integers(6, 12))
+        nb = int(rng.integers(1, 5))
+        cnt = min(N // m, (K + int(rng.integers(0, 900))) // nb + 1)
+        for r in range(rows):
+            if N // m == 0:
+                break
+            b0 = int(rng.integers(0, m - nb))
+            pos = (b0 + np.arange(nb)[None, :] + m * rng.choice(N // m, cnt, replace=False)[:, None]).ravel()
+            pos = pos[pos < N]
+            x[r, pos] = (10.0 + rng.random(len(pos))) * (1 if rng.integers(2) else -1)
+    return torch.from_numpy(x).to(dt)
+
+
+@pytest.mark.parametrize("seed,cases", [(4101, 60)])
+def test_seeded_random_shapes_exact_and_min_k(atk, knobs, seed, cases):
+    """Random row lengths (powers of two, odd multiples, arbitrary, short), K, element types, value
+    patterns and developer options through atk_topk / atk_mink, against the oracle bit for bit."""
+    rng = np.random.default_rng(seed)
+    dts = [torch.float32, torch.bfloat16, torch.float16, torch.int32, torch.uint32]
+    for c in range(cases):
+        dt = dts[int(rng.integers(5))]
+        kind = int(rng.integers(4))
+        if kind == 0:
+            N = int(2 ** rng.integers(10, 21))
+        elif kind == 1:
+            N = int(rng.integers(1, 64)) * int(2 ** rng.integers(6, 15))
+        elif kind == 2:
+            N = int(rng.integers(1000, 300000))
+        else:
+            N = int(rng.integers(1, 9)) * 2048
+        K = int(rng.integers(1, min(N, 1100) + 1))
+        if rng.random() < 0.5:
+            K = min(K, int(rng.integers(1, 300)))
+        rows = int(rng.integers(1, 40 if N < 100000 else 6))
+        style = int(rng.integers(4))
+        smallest = bool(rng.integers(2))
+        opts = {}
+        if rng.random() < 0.2:
+            opts["certified"] = 0
+        if rng.random() < 0.3:
+            opts["reg_rows"] = 0
+        if rng.random() < 0.3:
+            opts["onepass"] = 2
+        for k, v in opts.items():
+            knobs.set(k, v)
+        plan = atk.describe_topk_plan(dt, rows, N, K)[1]
+        print(f"case {c}: {dt} rows={rows} N={N} K={K} style={style} smallest={smallest} opts={opts} {plan[:28]}", flush=True)
+        x = _random_rows(rng, rows, N, dt, style, K)
+        xd = x.view(torch.int32).to(DEV).view(torch.uint32) if dt == torch.uint32 else x.to(DEV)
+        ev, ei = atk.topk(xd, K, smallest=smallest)
+        torch.cuda.synchronize()
+        ov, oi = oracle.topk(workloads.to_numpy_bits(x), K, smallest=smallest)
+        assert np.array_equal(ei.cpu().numpy(), oi) and np.array_equal(raw(ev), oracle_raw(ov)), f"case {c}"
+        for k in opts:
+            knobs.set(k, -1)
