@@ -316,8 +316,12 @@ __device__ __forceinline__ void hist_find_digit(const uint32_t* hist, uint32_t* 
     }
     if (lane == 0) ctl[4 + wave] = suf;
     __syncthreads();
-    uint32_t later = 0;                                // waves after mine
-    for (int w = wave + 1; w < (T + kWave - 1) / kWave; ++w) later += ctl[4 + w];
+    // waves after mine: lane l fetches the total of wave l (at most 16 of them), a reduction over
+    // the wavefront adds up the later ones -- one LDS round trip instead of one per wave
+    const int nwaves = (T + kWave - 1) / kWave;
+    uint32_t later = (lane < nwaves && lane > wave) ? ctl[4 + lane] : 0u;
+    for (int o = 8; o >= 1; o >>= 1) later += (uint32_t)__shfl_xor((int)later, o, kWave);
+    later = (uint32_t)__shfl((int)later, 0, kWave);
     const uint32_t incl = suf + later, excl = incl - mine;
     if (excl < (uint32_t)need && incl >= (uint32_t)need) {
         uint32_t run = excl;
@@ -506,8 +510,9 @@ __device__ __forceinline__ void wg_sort_rank_runs(uint64_t* keys_generic, int n,
     __syncthreads();
 }
 
-// n a power of two >= 256.  Not inlined: the sorting networks that every kernel variant with a
-// stage 2 would otherwise carry a copy of.
+// n >= 256: a multiple of 128 up to 128 keys per wavefront, of 256 up to 256 per wavefront, a
+// power of two beyond.  Not inlined: the sorting networks that every kernel variant with a stage 2
+// would otherwise carry a copy of.
 __device__ __noinline__ void wg_sort_merge_topk(uint64_t* keys, int n, int K) {
     const int per_wave = n / (int)(blockDim.x >> 6);      // keys per wavefront if all take part
     if (per_wave <= 128)      wg_sort_rank_runs<2>(keys, n, K);
@@ -657,7 +662,12 @@ __device__ __forceinline__ void wg_topk_from_lds(uint64_t* keys, int n, int K, v
             const int total = min((int)ctl[3], kWaveSortMaxKeys);
             if (total > kWgSortMinKeys && T >= kWgSortMinThreads) {
                 // many keys and many idle wavefronts: sort in LDS with all of them
-                const int padded = next_pow2(total);
+                // whole runs of the ranking sort (128 or 256 keys, one per wavefront); a power of two
+                // only where the merging sort takes over
+                const int nwaves = T >> 6;
+                int padded = (total + 127) & ~127;
+                if (padded > 128 * nwaves) padded = (total + 255) & ~255;
+                if (padded > 256 * nwaves) padded = next_pow2(total);
                 for (int i = total + tid; i < padded; i += T) buf[i] = 0;
                 __syncthreads();
                 wg_sort_merge_topk(buf, padded, K);
