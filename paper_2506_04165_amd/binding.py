@@ -202,6 +202,13 @@ def _check_out(out, rows: int, K: int, val_dtype: torch.dtype, device):
     return out_vals, out_idx
 
 
+def _workspace_ptr(workspace, device):
+    """(pointer, bytes) of a caller's workspace: a dense tensor on the input's device."""
+    if not isinstance(workspace, torch.Tensor) or workspace.device != device or not workspace.is_contiguous():
+        raise ValueError(f"workspace must be a contiguous tensor on {device}")
+    return workspace.data_ptr(), workspace.numel() * workspace.element_size()
+
+
 def approx_topk_recall(values: torch.Tensor, K: int, recall_target: float, workspace=None):
     """approx_top_k(array, K, recall_target): returns (vals, idx, K' used, B used)."""
     rows, N, stride = _check_input(values)
@@ -215,7 +222,7 @@ def approx_topk_recall(values: torch.Tensor, K: int, recall_target: float, works
         if need != SIZE_MAX and need > 0:
             if workspace is None or workspace.numel() * workspace.element_size() < need:
                 workspace = torch.empty(need, dtype=torch.uint8, device=values.device)
-            ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+            ws_ptr, ws_bytes = _workspace_ptr(workspace, values.device)
     kp_used, b_used = ctypes.c_int(0), ctypes.c_int(0)
     st = lib.atk_approx_topk_recall(values.data_ptr(), code, rows, N, stride, K, recall_target,
                                     out_vals.data_ptr(), out_idx.data_ptr(), ws_ptr, ws_bytes,
@@ -241,7 +248,7 @@ def approx_topk(values: torch.Tensor, K: int, Kprime: int, B: int, out=None, wor
     if need != SIZE_MAX and need > 0:
         if workspace is None or workspace.numel() * workspace.element_size() < need:
             workspace = torch.empty(need, dtype=torch.uint8, device=values.device)
-        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+        ws_ptr, ws_bytes = _workspace_ptr(workspace, values.device)
     entry = lib.atk_approx_mink if smallest else lib.atk_approx_topk
     st = entry(values.data_ptr(), code, rows, N, stride, K, Kprime, B,
                out_vals.data_ptr(), out_idx.data_ptr(), ws_ptr, ws_bytes, _stream_ptr(values.device))
@@ -279,7 +286,7 @@ def topk(values: torch.Tensor, K: int, out=None, smallest: bool = False, workspa
         if need not in (0, SIZE_MAX):
             workspace = torch.empty(need, dtype=torch.uint8, device=values.device)
     if workspace is not None and workspace is not False:
-        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+        ws_ptr, ws_bytes = _workspace_ptr(workspace, values.device)
     entry = lib.atk_mink if smallest else lib.atk_topk
     st = entry(values.data_ptr(), code, rows, N, stride, K, out_vals.data_ptr(), out_idx.data_ptr(),
                ws_ptr, ws_bytes, _stream_ptr(values.device))
@@ -332,7 +339,7 @@ def mips_approx_topk(queries: torch.Tensor, database: torch.Tensor, K: int, Kpri
     if need != SIZE_MAX and need > 0:
         if workspace is None or workspace.numel() * workspace.element_size() < need:
             workspace = torch.empty(need, dtype=torch.uint8, device=queries.device)
-        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+        ws_ptr, ws_bytes = _workspace_ptr(workspace, queries.device)
     st = lib.atk_mips_approx_topk(queries.data_ptr(), database.data_ptr(), code, Q, N, D, K, Kprime,
                                   B, out_vals.data_ptr(), out_idx.data_ptr(), ws_ptr, ws_bytes,
                                   _stream_ptr(queries.device))

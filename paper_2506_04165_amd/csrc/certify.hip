@@ -42,10 +42,21 @@ __global__ void __launch_bounds__(kCertifyThreads) certify_kernel(CertifyParams 
 
     if (tid == 0) p.hard_rows[row] = 0;
     if (per_bucket <= p.Kprime) return;          // every bucket was kept whole: nothing can be missing
+    // the result's indices are asked for first (K <= 1024: at most four per thread), the counters
+    // are cleared while they travel
+    constexpr int kPerThread = kWaveSortMaxKeys / kCertifyThreads;
+    uint32_t mine[kPerThread];
+#pragma unroll
+    for (int u = 0; u < kPerThread; ++u) {
+        const int i = tid + u * T;
+        mine[u] = i < K ? (uint32_t)p.out_idx[out_base + i] : 0xffffffffu;
+    }
     for (int b = tid; b < B; b += T) hist[b] = 0;
     if (tid == 0) { ctl[0] = 0; ctl[1] = 0; }
     __syncthreads();
-    for (int i = tid; i < K; i += T) atomicAdd(&hist[(uint32_t)p.out_idx[out_base + i] % (uint32_t)B], 1u);
+#pragma unroll
+    for (int u = 0; u < kPerThread; ++u)
+        if (mine[u] != 0xffffffffu) atomicAdd(&hist[mine[u] % (uint32_t)B], 1u);
     __syncthreads();
     for (int b = tid; b < B; b += T)
         if (hist[b] >= (uint32_t)p.Kprime) {
