@@ -617,6 +617,21 @@ def test_full_size_every_row_against_the_oracle(atk, name):
     gi_h, gv_h = gi.cpu().numpy(), bits(gv)
     bad = np.flatnonzero((gi_h != oi).any(axis=1) | (gv_h != host_bits(ov)).any(axis=1))
     assert bad.size == 0, (name, "exact: rows that differ:", bad[:10].tolist(), "of", bad.size)
+    # the radix-selection kernel by itself (no workspace), and the mirrored problem: approximate at
+    # the first setting, exact
+    print(f"{name}: exact without a workspace, min-K", flush=True)
+    rv, ri = atk.topk(xd, w.K, workspace=False)
+    torch.cuda.synchronize()
+    assert torch.equal(ri, gi) and np.array_equal(bits(rv), gv_h)
+    B, Kp = w.params[0]
+    for call, ref in ((lambda: atk.approx_topk(xd, w.K, Kp, B, smallest=True),
+                       lambda: oracle.approx_topk(xh, w.K, Kp, B, smallest=True)),
+                      (lambda: atk.topk(xd, w.K, smallest=True), lambda: oracle.topk(xh, w.K, smallest=True))):
+        mv, mi = call()
+        torch.cuda.synchronize()
+        ov, oi = ref()
+        bad = np.flatnonzero((mi.cpu().numpy() != oi).any(axis=1) | (bits(mv) != host_bits(ov)).any(axis=1))
+        assert bad.size == 0, (name, "min-K: rows that differ:", bad[:10].tolist(), "of", bad.size)
 
 
 def test_hip_graph_capture_and_replay(atk, knobs):
@@ -627,12 +642,17 @@ def test_hip_graph_capture_and_replay(atk, knobs):
         ("fused", lambda x, out, ws: atk.approx_topk(x, 128, 4, 1024, out=out, workspace=ws), (256, 65536)),
         ("slab", lambda x, out, ws: atk.approx_topk(x, 1024, 4, 1024, out=out, workspace=ws), (8, 262144)),
         ("split", lambda x, out, ws: atk.approx_topk(x, 1024, 4, 1024, out=out, workspace=ws), (8, 262144)),
+        # exact Top-K: two-stage kernels, certificate kernel, radix kernel over the flagged rows
+        ("certified", lambda x, out, ws: atk.topk(x, 128, out=out, workspace=ws), (40, 65536)),
     ]
     for name, call, (rows, N) in cases:
-        K = 128 if name == "fused" else 1024
+        K = 128 if name in ("fused", "certified") else 1024
         if name == "split":
             knobs.set("slab", 0)
-        assert atk.describe_plan(torch.float32, rows, N, K, 4, 1024)[1].startswith(name)
+        if name == "certified":
+            assert atk.describe_topk_plan(torch.float32, rows, N, K)[1].startswith(name)
+        else:
+            assert atk.describe_plan(torch.float32, rows, N, K, 4, 1024)[1].startswith(name)
         static_in = workloads.gaussian(rows, N, seed=70).to(DEV)
         ws = torch.empty(64 << 20, dtype=torch.uint8, device=DEV)
         out = (torch.empty((rows, K), device=DEV), torch.empty((rows, K), dtype=torch.int32, device=DEV))
@@ -654,7 +674,10 @@ def test_hip_graph_capture_and_replay(atk, knobs):
             torch.cuda.synchronize()
             assert torch.equal(out[1], ref[1]) and torch.equal(out[0], ref[0]), (name, replay)
         # and one replay against the oracle
-        ov, oi = oracle.approx_topk(static_in.cpu().numpy()[:2], K, 4, 1024)
+        if name == "certified":
+            ov, oi = oracle.topk(static_in.cpu().numpy()[:2], K)
+        else:
+            ov, oi = oracle.approx_topk(static_in.cpu().numpy()[:2], K, 4, 1024)
         assert np.array_equal(out[1].cpu().numpy()[:2], oi)
 
 
