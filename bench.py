@@ -557,7 +557,11 @@ def main():
         "recall_index": head["recall_index"],
         "recall_value": head["recall_value"],
         "expected_recall": head["expected_recall_random_placement"],
+        # atk_topk on the same input: where rows are long against K it runs the two-stage kernels and
+        # certifies or repairs the result (exact at the approximate path's speed + a few percent); the
+        # second ratio is against the radix-selection kernel alone, the classical exact Top-K
         "speedup_vs_exact_gpu_topk": head["speedup_vs_exact"],
+        "speedup_vs_radix_select_exact_gpu_topk": head["speedup_vs_radix_select_exact"],
         "exact_topk": exact_by_workload,
         "per_config": per_config,
         "paper_context": PAPER_CONTEXT,
