@@ -308,7 +308,8 @@ static Plan compute_plan(const void* values, int dtype, int64_t rows, int64_t N,
                      g_opt.packed != 0;
     // sixteen packed lists in one lane: two wavefronts with eight lists per lane stream the row
     // faster (measured on 16384 rows of 14336 with 1024 buckets: 95 -> 90 us)
-    if (packed_ok && G == 64 && NL * KP >= 16 && NL >= 2 && g_opt.lanes_per_row == 0) { G = 128; NL >>= 1; }
+    // (not when that leaves a lane two-byte loads: 128 buckets at K' = 8, 133 against 113 us)
+    if (packed_ok && G == 64 && NL * KP >= 16 && NL >= 4 && g_opt.lanes_per_row == 0) { G = 128; NL >>= 1; }
     if (packed_ok && G == 64 && NL == 1 && is_pow2(B) && rows >= 1024 &&
         g_opt.lanes_per_row == 0 && g_opt.subwave != 0) {
         // many short rows with only 64 buckets: rather than 2-byte loads from 64 lanes, a wavefront
@@ -663,11 +664,12 @@ constexpr int kCertMinK = 8;                // below, K' = 4 would be K' >= K
 constexpr int kCertMinRowPerSurvivor = 16;  // N >= 16 B K': otherwise stage 2 costs more than a second pass
 constexpr int kCertMaxScan = 65536;         // elements a repairing workgroup reads again
 
-static CertPlan certified_params(int64_t N, int K) {
-    struct Slot { int64_t N; int K; unsigned gen; CertPlan cp; };
-    thread_local Slot last{0, 0, 0, {}};
+static CertPlan certified_params(int dtype, int64_t N, int K) {
+    struct Slot { int64_t N; int K, es; unsigned gen; CertPlan cp; };
+    thread_local Slot last{0, 0, 0, 0, {}};
     options_from_env_once();
-    if (last.N == N && last.K == K && last.gen == g_opt_generation) return last.cp;
+    const int es = elem_size(dtype);
+    if (last.N == N && last.K == K && last.es == es && last.gen == g_opt_generation) return last.cp;
     CertPlan cp;
     if (g_opt.certified != 0 && K >= kCertMinK && K <= kWaveSortMaxKeys) {
         // smallest B (fewest survivors) at which nearly every row is certified at once; failing
@@ -686,8 +688,22 @@ static CertPlan certified_params(int64_t N, int K) {
             chosen = fallback;
         }
         if (chosen) { cp.B = chosen; cp.Kprime = kCertKprime; }
+        // Short rows of 16-bit elements: the packed-key kernels run stage 2 on up to 1024 survivors
+        // at streaming speed whatever the row length, so the rule above (rows long against the
+        // survivors) need not hold; K' = 8 then keeps buckets in doubt rare where K' = 4 cannot
+        // (c2: K = 287 of 14336 at (128, 8): 0.3 buckets per row).
+        if (!chosen && es == 2 && N <= 65536 && g_opt.packed != 0) {
+            double best = 1.5;
+            for (int kp = 4; kp <= 8; kp += 4)
+                for (int64_t B = kWaveSortMaxKeys / kp; B >= 16; B >>= 1) {
+                    if (N % B || N / B <= kp || B * kp < K) continue;
+                    const double e = expected_full_buckets(K, (int)B, kp);
+                    if (e <= best) { best = e; cp.B = (int)B; cp.Kprime = kp; }
+                    if (e <= 0.05) break;
+                }
+        }
     }
-    last = {N, K, g_opt_generation, cp};
+    last = {N, K, es, g_opt_generation, cp};
     return cp;
 }
 
@@ -703,7 +719,7 @@ static int exact_dispatch(const void* values, int dtype, int64_t rows, int64_t N
                           void* out_vals, int32_t* out_idx, void* workspace, size_t workspace_bytes,
                           hipStream_t st, bool smallest) {
     const uint32_t flip = flip_mask(dtype, smallest);
-    const CertPlan cp = certified_params(N, K);
+    const CertPlan cp = certified_params(dtype, N, K);
     const size_t lists = certified_lists_bytes(rows);
     if (cp.B && workspace && (uintptr_t)workspace % 8 == 0 && workspace_bytes >= lists) {
         const size_t rest = workspace_bytes - lists;
@@ -723,6 +739,7 @@ static int exact_dispatch(const void* values, int dtype, int64_t rows, int64_t N
             c.cap = (int)pow2_ceil(2 * (int64_t)K);
             if (c.cap < 1024) c.cap = 1024;
             c.max_scan = kCertMaxScan;
+            c.rows_per_wg = (rows >= 4096 && cp.B <= 1024) ? kCertifyRowsPerWg : 1;
             c.out_vals = out_vals; c.out_idx = out_idx;
             c.hard_rows = (int32_t*)workspace;
             hipError_t e = launch_certify(c, dtype, st);
@@ -932,7 +949,7 @@ int atk_describe_topk_plan(int dtype, int64_t rows, int64_t N, int K, char* buf,
     if (dtype < 0 || rows < 0 || N <= 0 || N > kMaxN || K < 1 || K > N) return ATK_INVALID_ARG;
     if (K > kExactMaxK) return ATK_UNSUPPORTED;
     options_from_env_once();
-    const CertPlan cp = certified_params(N, K);
+    const CertPlan cp = certified_params(dtype, N, K);
     if (cp.B) {
         const Plan& pl = make_plan(nullptr, dtype, rows, N, N, K, cp.Kprime, cp.B, false);
         if (pl.status == ATK_OK && !pl.route_exact) {
@@ -974,7 +991,7 @@ size_t atk_workspace_bytes(int op, int dtype, int64_t rows, int64_t N, int K, in
     if (op == ATK_OP_TOPK) {
         if (K < 1 || K > N) return SIZE_MAX;
         options_from_env_once();
-        const CertPlan cp = certified_params(N, K);
+        const CertPlan cp = certified_params(dtype, N, K);
         if (!cp.B) return 0;
         const Plan& pl = make_plan(nullptr, dtype, rows, N, N, K, cp.Kprime, cp.B, false);
         return (pl.status == ATK_OK && !pl.route_exact) ? certified_lists_bytes(rows) + pl.workspace : 0;

@@ -13,12 +13,15 @@ struct CertifyParams {
     uint32_t flip;            // order-reversing mask of the call (0: Top-K), see ApproxParams
     int cap;                  // LDS key buffer (keys): a power of two >= 2K, at least 1024
     int max_scan;             // most elements a workgroup re-reads from the row before it gives up
+    int rows_per_wg;          // 1, or kCertifyRowsPerWg (many short rows with few buckets: every wavefront
+                              // of a workgroup certifies four rows by itself)
     void* out_vals;           // [rows, K] in: the two-stage result; out: the exact one
     int32_t* out_idx;
     int32_t* hard_rows;       // [rows] out: 1 where the row has to be done by the exact kernel, else 0
 };
 
 constexpr int kCertifyMaxB = 4096;       // buckets the LDS counters hold
+constexpr int kCertifyRowsPerWg = 8;
 constexpr int kCertifyMaxFlagged = 128;  // buckets a workgroup repairs before it gives up
 
 size_t certify_lds_bytes(const CertifyParams& p);

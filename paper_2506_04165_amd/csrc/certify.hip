@@ -24,24 +24,152 @@ namespace atk {
 namespace {
 
 constexpr int kCertifyThreads = 256;
+constexpr int kCertifyWaves = kCertifyThreads / kWave;
+constexpr int kMaxExtras = 64;          // dropped elements merged into the sorted result in place; more: selection
 
+struct CertifyLds {
+    uint64_t* buf;        // [cap] the result's keys (sorted), then what a repair adds
+    uint64_t* bmin;       // [kCertifyMaxFlagged] least result key of every bucket in doubt
+    uint64_t* ext;        // [kMaxExtras + 1] dropped elements that belong to the union; last: the result's K-th key
+    void* scratch;        // of the selection
+    uint32_t* hist;       // [B] result elements per bucket (of the row the workgroup works on)
+    int* flagged;         // [kCertifyMaxFlagged] buckets with K' of them
+    uint32_t* ctl;        // 0: keys added by the repair  4: buckets in doubt  8: rows to redo
+};
+
+// The workgroup checks, and if need be repairs, one row: hist/flagged/nf are the row's counters,
+// the buckets in doubt and their number.  Every thread; ends with the row's exact result in place,
+// or the row marked hard.  Nearly always nothing was dropped that matters, so the check comes
+// first and is kept short: the elements of the buckets in doubt are asked for at once, beside the
+// result's indices; only the result's elements of those buckets have their values read (the least
+// of them bounds what the bucket can still contribute), and the result's keys are rebuilt in LDS
+// only when something has to be merged into them.
 template <typename DT>
-__global__ void __launch_bounds__(kCertifyThreads) certify_kernel(CertifyParams p) {
-    extern __shared__ uint64_t lds64[];
-    // layout: key buffer [cap], selection scratch, counters [B], flagged buckets, control words
-    uint64_t* buf = lds64;
-    void* scratch = lds64 + p.cap;
-    uint32_t* hist = (uint32_t*)((char*)scratch + kSelectScratchBytes);
-    int* flagged = (int*)(hist + p.B);
-    uint32_t* ctl = (uint32_t*)(flagged + kCertifyMaxFlagged);      // 0: flagged buckets  1: keys in buf
+__device__ void certify_repair(const CertifyParams& p, const CertifyLds& L, int row, uint32_t* hist,
+                               const int* flagged, int nf) {
     const int tid = threadIdx.x, T = blockDim.x;
-    const int row = blockIdx.x;
+    const int K = p.K, B = p.B, per_bucket = p.N / B;
+    const int64_t out_base = (int64_t)row * K;
+    if (nf > kCertifyMaxFlagged || (int64_t)nf * per_bucket > p.max_scan) {
+        if (tid == 0) p.hard_rows[row] = 1;
+        return;
+    }
+    const char* rowp = (const char*)p.values + (size_t)row * p.row_stride * elem<DT>::size;
+    const int total = nf * per_bucket;
+    constexpr int kRegs = 4;                     // elements (and result indices: K <= 1024) per thread in registers
+    auto element_of = [&](int e) -> uint32_t {   // position in the row of element e of the buckets in doubt
+        const int f = e / per_bucket, j = e - f * per_bucket;
+        return (uint32_t)j * (uint32_t)B + (uint32_t)flagged[f];
+    };
+    uint32_t ebits[kRegs], myidx[kRegs];
+#pragma unroll
+    for (int u = 0; u < kRegs; ++u) {
+        const int e = tid + u * T;
+        ebits[u] = e < total ? elem<DT>::load_bits(rowp, element_of(e)) : 0u;
+    }
+#pragma unroll
+    for (int u = 0; u < kRegs; ++u) {
+        const int i = tid + u * T;
+        myidx[u] = i < K ? (uint32_t)p.out_idx[out_base + i] : 0xffffffffu;
+    }
+    // the counters of the buckets in doubt now name their slot
+    for (int f = tid; f < nf; f += T) {
+        hist[flagged[f]] = 0x80000000u | (uint32_t)f;
+        L.bmin[f] = ~0ull;
+    }
+    if (tid == 0) L.ctl[0] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < kRegs; ++u) {
+        if (myidx[u] == 0xffffffffu) continue;
+        const int i = tid + u * T;
+        const uint32_t h = hist[myidx[u] % (uint32_t)B];
+        if ((h & 0x80000000u) || i == K - 1) {
+            const uint64_t key = make_key<DT>(elem<DT>::load_bits(p.out_vals, out_base + i) ^ p.flip, myidx[u]);
+            if (h & 0x80000000u) atomicMin((unsigned long long*)&L.bmin[h & 0x7fffffffu], (unsigned long long)key);
+            if (i == K - 1) L.ext[kMaxExtras] = key;        // the K-th key of the result
+        }
+    }
+    __syncthreads();
+    const uint64_t t_key = L.ext[kMaxExtras];
+    // elements of the buckets in doubt that stage 1 dropped (below the bucket's K' kept ones) and
+    // that beat the K-th key of the result: with them the union holds the true Top-K
+    auto scan = [&](auto&& take) {
+        auto consider = [&](int e, uint32_t b) {
+            const uint64_t key = make_key<DT>(b ^ p.flip, element_of(e));
+            if (key > t_key && key < L.bmin[e / per_bucket]) take(key);
+        };
+#pragma unroll
+        for (int u = 0; u < kRegs; ++u) {
+            const int e = tid + u * T;
+            if (e < total) consider(e, ebits[u]);
+        }
+        for (int e = tid + kRegs * T; e < total; e += T) consider(e, elem<DT>::load_bits(rowp, element_of(e)));
+    };
+    scan([&](uint64_t key) {
+        const uint32_t slot = atomicAdd(&L.ctl[0], 1u);
+        if (slot < (uint32_t)kMaxExtras) L.ext[slot] = key;
+    });
+    __syncthreads();
+    const int extras = (int)L.ctl[0];
+    if (extras == 0) return;                     // nothing was missing after all
+    if (K + extras > p.cap) {
+        if (tid == 0) p.hard_rows[row] = 1;
+        return;
+    }
+    // the result's keys (sorted) to LDS
+    for (int i = tid; i < K; i += T)
+        L.buf[i] = make_key<DT>(elem<DT>::load_bits(p.out_vals, out_base + i) ^ p.flip,
+                                (uint32_t)p.out_idx[out_base + i]);
+    __syncthreads();
+    if (extras <= kMaxExtras) {
+        // a few: every key's new rank is its old one plus the extras above it; an extra's rank is
+        // the number of result keys above it (binary search, the result is sorted) plus the extras
+        // above it.  Ranks below K are written; all reads of the old result are done.
+        for (int i = tid; i < K; i += T) {
+            const uint64_t key = L.buf[i];
+            int pos = i;
+            for (int j = 0; j < extras; ++j) pos += L.ext[j] > key ? 1 : 0;
+            if (pos < K && pos != i) {
+                const uint32_t idx = key_index(key);
+                elem<DT>::store_bits(p.out_vals, out_base + pos, key_stored_bits<DT>(key, rowp, idx, p.flip));
+                p.out_idx[out_base + pos] = (int32_t)idx;
+            }
+        }
+        for (int j = tid; j < extras; j += T) {
+            const uint64_t key = L.ext[j];
+            int lo = 0, hi = K;                  // number of result keys above key
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (L.buf[mid] > key) lo = mid + 1; else hi = mid;
+            }
+            int pos = lo;
+            for (int q = 0; q < extras; ++q) pos += L.ext[q] > key ? 1 : 0;
+            if (pos < K) {
+                const uint32_t idx = key_index(key);
+                elem<DT>::store_bits(p.out_vals, out_base + pos, key_stored_bits<DT>(key, rowp, idx, p.flip));
+                p.out_idx[out_base + pos] = (int32_t)idx;
+            }
+        }
+        return;
+    }
+    // many: the selection over result + extras
+    if (tid == 0) L.ctl[0] = 0;
+    __syncthreads();
+    scan([&](uint64_t key) { L.buf[K + atomicAdd(&L.ctl[0], 1u)] = key; });
+    const int fill = K + extras;
+    const int n2 = next_pow2(fill);
+    for (int i = fill + tid; i < n2; i += T) L.buf[i] = 0;
+    __syncthreads();
+    wg_topk_from_lds<DT>(L.buf, n2, K, L.scratch, rowp, p.out_vals, p.out_idx, out_base, p.flip);
+}
+
+// One row by the whole workgroup: count, then check and repair.  Every thread.
+template <typename DT>
+__device__ void certify_row_wg(const CertifyParams& p, const CertifyLds& L, int row) {
+    const int tid = threadIdx.x, T = blockDim.x;
     const int K = p.K, B = p.B;
     const int64_t out_base = (int64_t)row * K;
-    const int per_bucket = p.N / B;
-
-    if (tid == 0) p.hard_rows[row] = 0;
-    if (per_bucket <= p.Kprime) return;          // every bucket was kept whole: nothing can be missing
     // the result's indices are asked for first (K <= 1024: at most four per thread), the counters
     // are cleared while they travel
     constexpr int kPerThread = kWaveSortMaxKeys / kCertifyThreads;
@@ -51,77 +179,187 @@ __global__ void __launch_bounds__(kCertifyThreads) certify_kernel(CertifyParams 
         const int i = tid + u * T;
         mine[u] = i < K ? (uint32_t)p.out_idx[out_base + i] : 0xffffffffu;
     }
-    for (int b = tid; b < B; b += T) hist[b] = 0;
-    if (tid == 0) { ctl[0] = 0; ctl[1] = 0; }
+    for (int b = tid; b < B; b += T) L.hist[b] = 0;
+    if (tid == 0) L.ctl[4] = 0;
     __syncthreads();
 #pragma unroll
     for (int u = 0; u < kPerThread; ++u)
-        if (mine[u] != 0xffffffffu) atomicAdd(&hist[mine[u] % (uint32_t)B], 1u);
+        if (mine[u] != 0xffffffffu) atomicAdd(&L.hist[mine[u] % (uint32_t)B], 1u);
     __syncthreads();
     for (int b = tid; b < B; b += T)
-        if (hist[b] >= (uint32_t)p.Kprime) {
-            const uint32_t slot = atomicAdd(&ctl[0], 1u);
-            if (slot < (uint32_t)kCertifyMaxFlagged) flagged[slot] = b;
+        if (L.hist[b] >= (uint32_t)p.Kprime) {
+            const uint32_t slot = atomicAdd(&L.ctl[4], 1u);
+            if (slot < (uint32_t)kCertifyMaxFlagged) L.flagged[slot] = b;
         }
     __syncthreads();
-    const int nf = (int)ctl[0];
-    if (nf == 0) return;                         // certified
+    const int nf = (int)L.ctl[4];                // (the same for every thread)
+    if (nf > 0) certify_repair<DT>(p, L, row, L.hist, L.flagged, nf);
+}
 
-    // ---- repair ---------------------------------------------------------------------------------
-    if (nf > kCertifyMaxFlagged || (int64_t)nf * per_bucket > p.max_scan) {
-        if (tid == 0) p.hard_rows[row] = 1;
-        return;
-    }
-    const char* rowp = (const char*)p.values + (size_t)row * p.row_stride * elem<DT>::size;
-    const uint64_t t_key = make_key<DT>(elem<DT>::load_bits(p.out_vals, out_base + K - 1) ^ p.flip,
-                                        (uint32_t)p.out_idx[out_base + K - 1]);
-    // the result's elements of unflagged buckets ...
-    for (int i = tid; i < K; i += T) {
-        const uint32_t idx = (uint32_t)p.out_idx[out_base + i];
-        if (hist[idx % (uint32_t)B] < (uint32_t)p.Kprime) {
-            const uint32_t slot = atomicAdd(&ctl[1], 1u);       // (fewer than K <= cap / 2 of them)
-            buf[slot] = make_key<DT>(elem<DT>::load_bits(p.out_vals, out_base + i) ^ p.flip, idx);
+constexpr int kWaveCheckBuckets = 4;             // buckets in doubt a lone wavefront checks itself ...
+constexpr int kWaveCheckRegs = 4;                // ... if they hold at most this many elements per lane
+
+// One row by one wavefront, no barrier: count; if buckets are in doubt and few, check them (the
+// result's least key per such bucket, the K-th key, the buckets' elements against both).
+// Returns true when the row is certified, false when the workgroup has to look at it.
+//   hist: B counters of this wavefront;  small: 2 * kWaveCheckBuckets + 2 words of 64 bits
+template <typename DT>
+__device__ bool certify_row_wave(const CertifyParams& p, int row, uint32_t* hist, uint64_t* small) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int K = p.K, B = p.B, per_bucket = p.N / B;
+    const int64_t out_base = (int64_t)row * K;
+    uint32_t* count = (uint32_t*)&small[kWaveCheckBuckets + 1];          // buckets in doubt
+    int* flagged = (int*)&small[kWaveCheckBuckets + 2];                  // [2 * kWaveCheckBuckets]
+    for (int b = lane; b < B; b += kWave) hist[b] = 0;
+    if (lane == 0) *count = 0;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    // (the indices eight loads at a time: one memory latency per 512 of them, not per 64)
+    for (int i0 = 0; i0 < K; i0 += 8 * kWave) {
+        uint32_t idx[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = i0 + u * kWave + lane;
+            idx[u] = i < K ? (uint32_t)p.out_idx[out_base + i] : 0xffffffffu;
         }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (idx[u] != 0xffffffffu) atomicAdd(&hist[idx[u] % (uint32_t)B], 1u);
     }
-    // ... and every element of a flagged bucket at or above t (the result's own among them)
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    for (int b = lane; b < B; b += kWave)
+        if (hist[b] >= (uint32_t)p.Kprime) {
+            const uint32_t slot = atomicAdd(count, 1u);
+            if (slot < (uint32_t)kWaveCheckBuckets) flagged[slot] = b;
+        }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    const int nf = (int)*count;
+    if (nf == 0) return true;
     const int total = nf * per_bucket;
-    for (int e = tid; e < total; e += T) {
+    if (nf > kWaveCheckBuckets || total > kWaveCheckRegs * kWave) return false;
+    // the elements of the buckets in doubt, all loads at once
+    const char* rowp = (const char*)p.values + (size_t)row * p.row_stride * elem<DT>::size;
+    uint32_t ebits[kWaveCheckRegs];
+#pragma unroll
+    for (int u = 0; u < kWaveCheckRegs; ++u) {
+        const int e = lane + u * kWave;
         const int f = e / per_bucket, j = e - f * per_bucket;
-        const uint32_t n = (uint32_t)j * (uint32_t)B + (uint32_t)flagged[f];
-        const uint64_t key = make_key<DT>(elem<DT>::load_bits(rowp, n) ^ p.flip, n);
-        if (key >= t_key) {
-            const uint32_t slot = atomicAdd(&ctl[1], 1u);
-            if (slot < (uint32_t)p.cap) buf[slot] = key;
+        ebits[u] = e < total ? elem<DT>::load_bits(rowp, (uint32_t)j * (uint32_t)B + (uint32_t)flagged[f < nf ? f : 0]) : 0u;
+    }
+    if (lane < nf) {
+        hist[flagged[lane]] = 0x80000000u | (uint32_t)lane;
+        small[lane] = ~0ull;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    // least result key of every bucket in doubt, and the K-th key
+    for (int i0 = 0; i0 < K; i0 += 8 * kWave) {
+        uint32_t idx[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = i0 + u * kWave + lane;
+            idx[u] = i < K ? (uint32_t)p.out_idx[out_base + i] : 0xffffffffu;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            if (idx[u] == 0xffffffffu) continue;
+            const int i = i0 + u * kWave + lane;
+            const uint32_t h = hist[idx[u] % (uint32_t)B];
+            if ((h & 0x80000000u) || i == K - 1) {
+                const uint64_t key = make_key<DT>(elem<DT>::load_bits(p.out_vals, out_base + i) ^ p.flip, idx[u]);
+                if (h & 0x80000000u) atomicMin((unsigned long long*)&small[h & 0x7fffffffu], (unsigned long long)key);
+                if (i == K - 1) small[kWaveCheckBuckets] = key;
+            }
         }
     }
-    __syncthreads();
-    const int fill = (int)ctl[1];
-    if (fill > p.cap) {                          // more than the buffer takes: the output is untouched
-        if (tid == 0) p.hard_rows[row] = 1;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    const uint64_t t_key = small[kWaveCheckBuckets];
+    bool missing = false;
+#pragma unroll
+    for (int u = 0; u < kWaveCheckRegs; ++u) {
+        const int e = lane + u * kWave;
+        if (e < total) {
+            const int f = e / per_bucket, j = e - f * per_bucket;
+            const uint32_t n = (uint32_t)j * (uint32_t)B + (uint32_t)flagged[f];
+            const uint64_t key = make_key<DT>(ebits[u] ^ p.flip, n);
+            missing |= key > t_key && key < small[f];
+        }
+    }
+    return __ballot(missing) == 0;
+}
+
+constexpr int kRowsPerWave = 2;                  // rows a wavefront takes in the many-rows form
+static_assert(kCertifyWaves * kRowsPerWave == kCertifyRowsPerWg, "rows of a workgroup in the many-rows form");
+
+template <typename DT>
+__global__ void __launch_bounds__(kCertifyThreads, 4) certify_kernel(CertifyParams p) {   // four workgroups per CU
+    extern __shared__ uint64_t lds64[];
+    CertifyLds L;
+    L.buf = lds64;
+    L.bmin = L.buf + p.cap;
+    L.ext = L.bmin + kCertifyMaxFlagged;
+    L.scratch = L.ext + kMaxExtras + 1;
+    L.hist = (uint32_t*)((char*)L.scratch + kSelectScratchBytes);
+    L.flagged = (int*)(L.hist + p.B);
+    L.ctl = (uint32_t*)(L.flagged + kCertifyMaxFlagged);               // 16 words, then 32 rows to redo
+    const int tid = threadIdx.x;
+    const int per_bucket = p.N / p.B;
+    const int first_row = blockIdx.x * p.rows_per_wg;
+
+    if (tid == 0)                                // (the thread that may set them again below)
+        for (int r = 0; r < p.rows_per_wg; ++r)
+            if (first_row + r < p.rows) p.hard_rows[first_row + r] = 0;
+    if (per_bucket <= p.Kprime) return;          // every bucket was kept whole: nothing can be missing
+
+    if (p.rows_per_wg == 1) {
+        certify_row_wg<DT>(p, L, first_row);
         return;
     }
-    const int n2 = next_pow2(fill);              // fill >= K: the result's K elements are all in the union
-    for (int i = fill + tid; i < n2; i += T) buf[i] = 0;
+    // many short rows: every wavefront certifies kRowsPerWave rows by itself; what it cannot
+    // settle (many buckets in doubt, or a dropped element that belongs into the result) the
+    // workgroup takes afterwards
+    uint32_t* todo = L.ctl + 16;
+    uint64_t* wave_small = (uint64_t*)(((uintptr_t)(todo + kCertifyWaves * kRowsPerWave) + 7) & ~(uintptr_t)7);
+    uint32_t* wave_hist = (uint32_t*)(wave_small + kCertifyWaves * (2 * kWaveCheckBuckets + 2));
+    const int w = tid >> 6;
+    if (tid == 0) L.ctl[8] = 0;
     __syncthreads();
-    wg_topk_from_lds<DT>(buf, n2, K, scratch, rowp, p.out_vals, p.out_idx, out_base, p.flip);
+    for (int q = 0; q < kRowsPerWave; ++q) {
+        const int row = first_row + q * kCertifyWaves + w;
+        if (row >= p.rows) break;
+        const bool ok = certify_row_wave<DT>(p, row, wave_hist + (size_t)w * p.B,
+                                             wave_small + w * (2 * kWaveCheckBuckets + 2));
+        if (!ok && (tid & (kWave - 1)) == 0) todo[atomicAdd(&L.ctl[8], 1u)] = (uint32_t)row;
+    }
+    __syncthreads();
+    const int ntodo = (int)L.ctl[8];
+    for (int t = 0; t < ntodo; ++t) {
+        certify_row_wg<DT>(p, L, (int)todo[t]);
+        __syncthreads();
+    }
 }
 
 template <typename DT>
 hipError_t launch_for(const CertifyParams& p, hipStream_t stream) {
     const size_t lds = certify_lds_bytes(p);
     allow_large_lds((const void*)certify_kernel<DT>, lds);
-    hipLaunchKernelGGL(certify_kernel<DT>, dim3(p.rows), dim3(kCertifyThreads), lds, stream, p);
+    const int grid = (p.rows + p.rows_per_wg - 1) / p.rows_per_wg;
+    hipLaunchKernelGGL(certify_kernel<DT>, dim3(grid), dim3(kCertifyThreads), lds, stream, p);
     return hipGetLastError();
 }
 
 }  // namespace
 
 size_t certify_lds_bytes(const CertifyParams& p) {
-    return (size_t)p.cap * 8 + kSelectScratchBytes + (size_t)p.B * 4 + kCertifyMaxFlagged * 4 + 16 * 4;
+    size_t bytes = (size_t)p.cap * 8 + (kCertifyMaxFlagged + kMaxExtras + 1) * 8 + kSelectScratchBytes +
+                   (size_t)p.B * 4 + kCertifyMaxFlagged * 4 + 16 * 4;
+    if (p.rows_per_wg > 1)      // rows to redo, the wavefronts' small arrays and counters
+        bytes += kCertifyWaves * kRowsPerWave * 4 + 8 + kCertifyWaves * (2 * kWaveCheckBuckets + 2) * 8 +
+                 (size_t)kCertifyWaves * p.B * 4;
+    return bytes;
 }
 
 hipError_t launch_certify(const CertifyParams& p, int dtype, hipStream_t stream) {
-    if (p.B > kCertifyMaxB || p.K > kWaveSortMaxKeys || p.cap < 2 * p.K || (p.cap & (p.cap - 1)) || p.N % p.B)
+    if (p.B > kCertifyMaxB || p.K > kWaveSortMaxKeys || p.cap < 2 * p.K || (p.cap & (p.cap - 1)) || p.N % p.B ||
+        (p.rows_per_wg != 1 && p.rows_per_wg != kCertifyRowsPerWg))
         return hipErrorInvalidValue;
     switch (dtype) {
         case 0: return launch_for<float>(p, stream);

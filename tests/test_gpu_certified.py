@@ -247,3 +247,23 @@ def test_seeded_random_shapes_exact_and_min_k(atk, knobs, seed, cases):
         assert np.array_equal(ei.cpu().numpy(), oi) and np.array_equal(raw(ev), oracle_raw(ov)), f"case {c}"
         for k in opts:
             knobs.set(k, -1)
+
+
+def test_many_short_rows_certified_by_single_wavefronts(atk):
+    """4096 rows and more with at most 1024 buckets: every wavefront of the certificate kernel takes
+    rows by itself and hands the workgroup what it cannot settle (a ragged last workgroup, rows with
+    elements to merge in, rows with many buckets in doubt, rows given up on)."""
+    rows = 4100 + 3
+    x = workloads.gaussian(rows, 4096, seed=71)
+    x[100:140] = packed_into_buckets(40, 4096, 64, 64, 2, seed=72)        # 32 per bucket: merged by the workgroup
+    x[1000:1010] = packed_into_buckets(10, 4096, 64, 64, 16, seed=73)     # sixteen buckets in doubt
+    x[2000:2004] = 1.0                                                     # ties
+    x[4099:] = packed_into_buckets(4, 4096, 64, 64, 1, seed=74)           # the ragged tail
+    check(atk, x, 64)
+    check(atk, x, 64, smallest=True)
+    check(atk, x.to(torch.bfloat16), 64)
+    # the FFN shape at reduced row count: K' = 8 on the packed-key kernels
+    y = workloads.gaussian(4200, 14336, seed=75, dtype=torch.bfloat16)
+    assert "K'=8" in atk.describe_topk_plan(y.dtype, 4200, 14336, 287)[1]
+    check(atk, y, 287)
+    check(atk, y.to(torch.float16), 287, smallest=True)
