@@ -25,13 +25,10 @@ namespace {
 
 constexpr int kCertifyThreads = 256;
 constexpr int kCertifyWaves = kCertifyThreads / kWave;
-constexpr int kMaxExtras = 64;          // dropped elements merged into the sorted result in place; more: selection
 
 struct CertifyLds {
     uint64_t* buf;        // [cap] the result's keys (sorted), then what a repair adds
-    uint64_t* bmin;       // [kCertifyMaxFlagged] least result key of every bucket in doubt
-    uint64_t* ext;        // [kMaxExtras + 1] dropped elements that belong to the union; last: the result's K-th key
-    void* scratch;        // of the selection
+    uint64_t* bmin;       // [kCertifyMaxFlagged + 1] least result key of every bucket in doubt; last: the K-th key
     uint32_t* hist;       // [B] result elements per bucket (of the row the workgroup works on)
     int* flagged;         // [kCertifyMaxFlagged] buckets with K' of them
     uint32_t* ctl;        // 0: keys added by the repair  4: buckets in doubt  8: rows to redo
@@ -61,7 +58,7 @@ __device__ void certify_repair(const CertifyParams& p, const CertifyLds& L, int 
         const int f = e / per_bucket, j = e - f * per_bucket;
         return (uint32_t)j * (uint32_t)B + (uint32_t)flagged[f];
     };
-    uint32_t ebits[kRegs], myidx[kRegs];
+    uint32_t ebits[kRegs], myidx[kRegs], myval[kRegs];
 #pragma unroll
     for (int u = 0; u < kRegs; ++u) {
         const int e = tid + u * T;
@@ -71,6 +68,7 @@ __device__ void certify_repair(const CertifyParams& p, const CertifyLds& L, int 
     for (int u = 0; u < kRegs; ++u) {
         const int i = tid + u * T;
         myidx[u] = i < K ? (uint32_t)p.out_idx[out_base + i] : 0xffffffffu;
+        myval[u] = i < K ? elem<DT>::load_bits(p.out_vals, out_base + i) : 0u;   // (needed or not: no second wait)
     }
     // the counters of the buckets in doubt now name their slot
     for (int f = tid; f < nf; f += T) {
@@ -85,19 +83,24 @@ __device__ void certify_repair(const CertifyParams& p, const CertifyLds& L, int 
         const int i = tid + u * T;
         const uint32_t h = hist[myidx[u] % (uint32_t)B];
         if ((h & 0x80000000u) || i == K - 1) {
-            const uint64_t key = make_key<DT>(elem<DT>::load_bits(p.out_vals, out_base + i) ^ p.flip, myidx[u]);
+            const uint64_t key = make_key<DT>(myval[u] ^ p.flip, myidx[u]);
             if (h & 0x80000000u) atomicMin((unsigned long long*)&L.bmin[h & 0x7fffffffu], (unsigned long long)key);
-            if (i == K - 1) L.ext[kMaxExtras] = key;        // the K-th key of the result
+            if (i == K - 1) L.bmin[kCertifyMaxFlagged] = key;   // the K-th key of the result
         }
     }
     __syncthreads();
-    const uint64_t t_key = L.ext[kMaxExtras];
+    const uint64_t t_key = L.bmin[kCertifyMaxFlagged];
     // elements of the buckets in doubt that stage 1 dropped (below the bucket's K' kept ones) and
     // that beat the K-th key of the result: with them the union holds the true Top-K
-    auto scan = [&](auto&& take) {
+    const int room = p.cap - K;                  // extras the buffer takes behind the result's keys
+    uint64_t* ext = L.buf + K;
+    {
         auto consider = [&](int e, uint32_t b) {
             const uint64_t key = make_key<DT>(b ^ p.flip, element_of(e));
-            if (key > t_key && key < L.bmin[e / per_bucket]) take(key);
+            if (key > t_key && key < L.bmin[e / per_bucket]) {
+                const uint32_t slot = atomicAdd(&L.ctl[0], 1u);
+                if (slot < (uint32_t)room) ext[slot] = key;
+            }
         };
 #pragma unroll
         for (int u = 0; u < kRegs; ++u) {
@@ -105,63 +108,44 @@ __device__ void certify_repair(const CertifyParams& p, const CertifyLds& L, int 
             if (e < total) consider(e, ebits[u]);
         }
         for (int e = tid + kRegs * T; e < total; e += T) consider(e, elem<DT>::load_bits(rowp, element_of(e)));
-    };
-    scan([&](uint64_t key) {
-        const uint32_t slot = atomicAdd(&L.ctl[0], 1u);
-        if (slot < (uint32_t)kMaxExtras) L.ext[slot] = key;
-    });
+    }
     __syncthreads();
     const int extras = (int)L.ctl[0];
     if (extras == 0) return;                     // nothing was missing after all
-    if (K + extras > p.cap) {
+    if (extras > room) {
         if (tid == 0) p.hard_rows[row] = 1;
         return;
     }
-    // the result's keys (sorted) to LDS
-    for (int i = tid; i < K; i += T)
-        L.buf[i] = make_key<DT>(elem<DT>::load_bits(p.out_vals, out_base + i) ^ p.flip,
-                                (uint32_t)p.out_idx[out_base + i]);
+    // The result's keys to LDS: they are sorted, so nothing has to be sorted again.  Every key's
+    // new rank is its old one plus the extras above it; an extra's rank is the number of result
+    // keys above it (binary search) plus the extras above it.  Ranks below K are written; all
+    // reads of the old result are done by then.
+#pragma unroll
+    for (int u = 0; u < kRegs; ++u)
+        if (myidx[u] != 0xffffffffu) L.buf[tid + u * T] = make_key<DT>(myval[u] ^ p.flip, myidx[u]);
     __syncthreads();
-    if (extras <= kMaxExtras) {
-        // a few: every key's new rank is its old one plus the extras above it; an extra's rank is
-        // the number of result keys above it (binary search, the result is sorted) plus the extras
-        // above it.  Ranks below K are written; all reads of the old result are done.
-        for (int i = tid; i < K; i += T) {
-            const uint64_t key = L.buf[i];
-            int pos = i;
-            for (int j = 0; j < extras; ++j) pos += L.ext[j] > key ? 1 : 0;
-            if (pos < K && pos != i) {
-                const uint32_t idx = key_index(key);
-                elem<DT>::store_bits(p.out_vals, out_base + pos, key_stored_bits<DT>(key, rowp, idx, p.flip));
-                p.out_idx[out_base + pos] = (int32_t)idx;
-            }
-        }
-        for (int j = tid; j < extras; j += T) {
-            const uint64_t key = L.ext[j];
-            int lo = 0, hi = K;                  // number of result keys above key
-            while (lo < hi) {
-                const int mid = (lo + hi) >> 1;
-                if (L.buf[mid] > key) lo = mid + 1; else hi = mid;
-            }
-            int pos = lo;
-            for (int q = 0; q < extras; ++q) pos += L.ext[q] > key ? 1 : 0;
-            if (pos < K) {
-                const uint32_t idx = key_index(key);
-                elem<DT>::store_bits(p.out_vals, out_base + pos, key_stored_bits<DT>(key, rowp, idx, p.flip));
-                p.out_idx[out_base + pos] = (int32_t)idx;
-            }
-        }
-        return;
+    auto write = [&](int pos, uint64_t key) {
+        const uint32_t idx = key_index(key);
+        elem<DT>::store_bits(p.out_vals, out_base + pos, key_stored_bits<DT>(key, rowp, idx, p.flip));
+        p.out_idx[out_base + pos] = (int32_t)idx;
+    };
+    for (int i = tid; i < K; i += T) {
+        const uint64_t key = L.buf[i];
+        int pos = i;
+        for (int j = 0; j < extras; ++j) pos += ext[j] > key ? 1 : 0;
+        if (pos < K && pos != i) write(pos, key);
     }
-    // many: the selection over result + extras
-    if (tid == 0) L.ctl[0] = 0;
-    __syncthreads();
-    scan([&](uint64_t key) { L.buf[K + atomicAdd(&L.ctl[0], 1u)] = key; });
-    const int fill = K + extras;
-    const int n2 = next_pow2(fill);
-    for (int i = fill + tid; i < n2; i += T) L.buf[i] = 0;
-    __syncthreads();
-    wg_topk_from_lds<DT>(L.buf, n2, K, L.scratch, rowp, p.out_vals, p.out_idx, out_base, p.flip);
+    for (int j = tid; j < extras; j += T) {
+        const uint64_t key = ext[j];
+        int lo = 0, hi = K;                      // number of result keys above key
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (L.buf[mid] > key) lo = mid + 1; else hi = mid;
+        }
+        int pos = lo;
+        for (int q = 0; q < extras; ++q) pos += ext[q] > key ? 1 : 0;
+        if (pos < K) write(pos, key);
+    }
 }
 
 // One row by the whole workgroup: count, then check and repair.  Every thread.
@@ -251,12 +235,15 @@ __device__ bool certify_row_wave(const CertifyParams& p, int row, uint32_t* hist
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     // least result key of every bucket in doubt, and the K-th key
+    // (values asked for with the indices, needed or not: a load behind the test would wait for
+    // memory once per element of a bucket in doubt)
     for (int i0 = 0; i0 < K; i0 += 8 * kWave) {
-        uint32_t idx[8];
+        uint32_t idx[8], val[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const int i = i0 + u * kWave + lane;
             idx[u] = i < K ? (uint32_t)p.out_idx[out_base + i] : 0xffffffffu;
+            val[u] = i < K ? elem<DT>::load_bits(p.out_vals, out_base + i) : 0u;
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
@@ -264,7 +251,7 @@ __device__ bool certify_row_wave(const CertifyParams& p, int row, uint32_t* hist
             const int i = i0 + u * kWave + lane;
             const uint32_t h = hist[idx[u] % (uint32_t)B];
             if ((h & 0x80000000u) || i == K - 1) {
-                const uint64_t key = make_key<DT>(elem<DT>::load_bits(p.out_vals, out_base + i) ^ p.flip, idx[u]);
+                const uint64_t key = make_key<DT>(val[u] ^ p.flip, idx[u]);
                 if (h & 0x80000000u) atomicMin((unsigned long long*)&small[h & 0x7fffffffu], (unsigned long long)key);
                 if (i == K - 1) small[kWaveCheckBuckets] = key;
             }
@@ -290,14 +277,12 @@ constexpr int kRowsPerWave = 2;                  // rows a wavefront takes in th
 static_assert(kCertifyWaves * kRowsPerWave == kCertifyRowsPerWg, "rows of a workgroup in the many-rows form");
 
 template <typename DT>
-__global__ void __launch_bounds__(kCertifyThreads, 4) certify_kernel(CertifyParams p) {   // four workgroups per CU
+__global__ void __launch_bounds__(kCertifyThreads) certify_kernel(CertifyParams p) {
     extern __shared__ uint64_t lds64[];
     CertifyLds L;
     L.buf = lds64;
     L.bmin = L.buf + p.cap;
-    L.ext = L.bmin + kCertifyMaxFlagged;
-    L.scratch = L.ext + kMaxExtras + 1;
-    L.hist = (uint32_t*)((char*)L.scratch + kSelectScratchBytes);
+    L.hist = (uint32_t*)(L.bmin + kCertifyMaxFlagged + 1);
     L.flagged = (int*)(L.hist + p.B);
     L.ctl = (uint32_t*)(L.flagged + kCertifyMaxFlagged);               // 16 words, then 32 rows to redo
     const int tid = threadIdx.x;
@@ -349,7 +334,7 @@ hipError_t launch_for(const CertifyParams& p, hipStream_t stream) {
 }  // namespace
 
 size_t certify_lds_bytes(const CertifyParams& p) {
-    size_t bytes = (size_t)p.cap * 8 + (kCertifyMaxFlagged + kMaxExtras + 1) * 8 + kSelectScratchBytes +
+    size_t bytes = (size_t)p.cap * 8 + (kCertifyMaxFlagged + 1) * 8 +
                    (size_t)p.B * 4 + kCertifyMaxFlagged * 4 + 16 * 4;
     if (p.rows_per_wg > 1)      // rows to redo, the wavefronts' small arrays and counters
         bytes += kCertifyWaves * kRowsPerWave * 4 + 8 + kCertifyWaves * (2 * kWaveCheckBuckets + 2) * 8 +
