@@ -1002,6 +1002,8 @@ size_t atk_workspace_bytes(int op, int dtype, int64_t rows, int64_t N, int K, in
     // alignment of the real buffers is not known here; assume the allocator's (>= 16 bytes)
     const Plan& pl = make_plan(nullptr, dtype, rows, N, N, K, Kprime, B, false);
     if (pl.status) return SIZE_MAX;
+    // K' = K beyond the list lengths: the exact Top-K, which is faster with its own workspace
+    if (pl.route_exact) return atk_workspace_bytes(ATK_OP_TOPK, dtype, rows, N, K, 0, 0);
     return pl.workspace;
 }
 
