@@ -303,6 +303,11 @@ int atk_read_probe(const void* data, size_t bytes, void* checksum, void* stream)
  *                    stage 2 on its own survivors and passes on only its K greatest
  *   "onepass"        exact kernel: 0 always two passes over a row, 1 (default) one pass with a rising
  *                    threshold on long rows, 2 on every row it can handle
+ *   "certified"      0: atk_topk / atk_mink never go through the two-stage kernels and the
+ *                    certificate kernel, whatever workspace they are given
+ *   "reg_rows"       0: the radix-selection kernel never keeps a short row in registers
+ *   "exact_threads"  0 = planner's choice, else a power of two in [64, 1024]: lanes of a workgroup
+ *                    of the radix-selection kernel
  * Returns ATK_INVALID_ARG for an unknown name or an unusable value.  Host only.
  */
 int atk_set_option(const char* name, int value);
