@@ -267,3 +267,22 @@ def test_many_short_rows_certified_by_single_wavefronts(atk):
     assert "K'=8" in atk.describe_topk_plan(y.dtype, 4200, 14336, 287)[1]
     check(atk, y, 287)
     check(atk, y.to(torch.float16), 287, smallest=True)
+
+
+def test_strided_and_unaligned_rows_through_the_exact_route(atk):
+    """Views with a row stride beyond N and a base that is not 16-byte aligned: the two-stage
+    kernels take their single-element loads, the certificate kernel and the radix kernel read the
+    same rows through the same stride."""
+    for dt in (torch.float32, torch.bfloat16):
+        base = workloads.gaussian(37, 65536 + 5, seed=81, dtype=dt)
+        base[5:9, 3:65539] = packed_into_buckets(4, 65536, 64, 256, 2, seed=82).to(dt)      # rows that need a repair
+        base[20, 3:65539] = 1.0                                                         # ties
+        xd = base.to(DEV)[:, 3:65539]
+        assert xd.stride(0) == 65541 and xd.data_ptr() % 16 != 0
+        assert atk.describe_topk_plan(dt, 37, 65536, 64)[1].startswith("certified")
+        x = base[:, 3:65539].contiguous()
+        for smallest in (False, True):
+            gv, gi = atk.topk(xd, 64, smallest=smallest)
+            torch.cuda.synchronize()
+            ov, oi = oracle.topk(workloads.to_numpy_bits(x), 64, smallest=smallest)
+            assert np.array_equal(gi.cpu().numpy(), oi) and np.array_equal(raw(gv), oracle_raw(ov)), (dt, smallest)
