@@ -229,22 +229,18 @@ __device__ bool certify_row_wave(const CertifyParams& p, int row, uint32_t* hist
         const int f = e / per_bucket, j = e - f * per_bucket;
         ebits[u] = e < total ? elem<DT>::load_bits(rowp, (uint32_t)j * (uint32_t)B + (uint32_t)flagged[f < nf ? f : 0]) : 0u;
     }
-    if (lane < nf) {
-        hist[flagged[lane]] = 0x80000000u | (uint32_t)lane;
-        small[lane] = ~0ull;
-    }
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    // least result key of every bucket in doubt, and the K-th key
-    // (values asked for with the indices, needed or not: a load behind the test would wait for
-    // memory once per element of a bucket in doubt)
-    for (int i0 = 0; i0 < K; i0 += 8 * kWave) {
-        uint32_t idx[8], val[8];
+    // ... and with them the result's indices and values (needed or not: a load behind a test, or
+    // behind the fence below, would wait for memory a second time)
+    auto fetch = [&](int i0, uint32_t (&idx)[8], uint32_t (&val)[8]) {
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const int i = i0 + u * kWave + lane;
             idx[u] = i < K ? (uint32_t)p.out_idx[out_base + i] : 0xffffffffu;
             val[u] = i < K ? elem<DT>::load_bits(p.out_vals, out_base + i) : 0u;
         }
+    };
+    // least result key of every bucket in doubt, and the K-th key
+    auto note = [&](int i0, const uint32_t (&idx)[8], const uint32_t (&val)[8]) {
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             if (idx[u] == 0xffffffffu) continue;
@@ -256,6 +252,19 @@ __device__ bool certify_row_wave(const CertifyParams& p, int row, uint32_t* hist
                 if (i == K - 1) small[kWaveCheckBuckets] = key;
             }
         }
+    };
+    uint32_t idx0[8], val0[8];
+    fetch(0, idx0, val0);
+    if (lane < nf) {
+        hist[flagged[lane]] = 0x80000000u | (uint32_t)lane;
+        small[lane] = ~0ull;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    note(0, idx0, val0);
+    for (int i0 = 8 * kWave; i0 < K; i0 += 8 * kWave) {
+        uint32_t idx[8], val[8];
+        fetch(i0, idx, val);
+        note(i0, idx, val);
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     const uint64_t t_key = small[kWaveCheckBuckets];
