@@ -707,11 +707,13 @@ static CertPlan certified_params(int dtype, int64_t N, int K) {
     return cp;
 }
 
-static size_t certified_lists_bytes(int64_t rows) { return ((size_t)rows * 4 + 255) & ~(size_t)255; }
+// two words per row: rows left to the radix kernel, rows the two-stage launch left open
+static size_t certified_lists_bytes(int64_t rows) { return 2 * (((size_t)rows * 4 + 255) & ~(size_t)255); }
 
 static int approx_impl(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride,
                        int K, int Kprime, int B, void* out_vals, int32_t* out_idx,
-                       void* workspace, size_t workspace_bytes, void* stream, bool smallest);
+                       void* workspace, size_t workspace_bytes, void* stream, bool smallest,
+                       int32_t* cert_flags = nullptr);
 
 // dtype: the kernel's (fp16 already mapped).  Arguments validated by the caller.  A workspace that
 // is absent or too small for the certified route only selects the radix-selection kernel.
@@ -724,13 +726,16 @@ static int exact_dispatch(const void* values, int dtype, int64_t rows, int64_t N
     if (cp.B && workspace && (uintptr_t)workspace % 8 == 0 && workspace_bytes >= lists) {
         const size_t rest = workspace_bytes - lists;
         size_t need;
+        bool tail_certifies;        // the packed-key variants take the certificate in their own tail
         {
             const Plan& pl = make_plan(values, dtype, rows, N, row_stride, K, cp.Kprime, cp.B, false, rest);
             need = (pl.status == ATK_OK && !pl.route_exact) ? pl.workspace : SIZE_MAX;
+            tail_certifies = need != SIZE_MAX && pl.fused && pl.var->packed();
         }
         if (need <= rest) {
+            int32_t* open_rows = tail_certifies ? (int32_t*)((char*)workspace + lists / 2) : nullptr;
             int rc = approx_impl(values, dtype, rows, N, row_stride, K, cp.Kprime, cp.B, out_vals, out_idx,
-                                 (char*)workspace + lists, rest, (void*)st, smallest);
+                                 (char*)workspace + lists, rest, (void*)st, smallest, open_rows);
             if (rc) return rc;
             CertifyParams c{};
             c.values = values; c.row_stride = row_stride;
@@ -742,6 +747,7 @@ static int exact_dispatch(const void* values, int dtype, int64_t rows, int64_t N
             c.rows_per_wg = (rows >= 4096 && cp.B <= 1024) ? kCertifyRowsPerWg : 1;
             c.out_vals = out_vals; c.out_idx = out_idx;
             c.hard_rows = (int32_t*)workspace;
+            c.open_rows = open_rows;
             hipError_t e = launch_certify(c, dtype, st);
             if (e != hipSuccess) return hip_fail(e);
             return run_exact(values, nullptr, dtype, rows, N, row_stride, K, out_vals, out_idx, st,
@@ -753,7 +759,8 @@ static int exact_dispatch(const void* values, int dtype, int64_t rows, int64_t N
 
 static int approx_impl(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride,
                        int K, int Kprime, int B, void* out_vals, int32_t* out_idx,
-                       void* workspace, size_t workspace_bytes, void* stream, bool smallest) {
+                       void* workspace, size_t workspace_bytes, void* stream, bool smallest,
+                       int32_t* cert_flags) {
     int rc = validate_common(values, dtype, rows, N, row_stride);
     if (rc) return rc;
     dtype = kernel_dtype(dtype);       // fp16 -> the bf16 kernels
@@ -777,6 +784,7 @@ static int approx_impl(const void* values, int dtype, int64_t rows, int64_t N, i
 
     ApproxParams p = params_from(pl, values, rows, N, row_stride, K, Kprime, B);
     p.flip = flip;
+    p.cert_flags = cert_flags;      // (only the packed-key variants of the fused route look at it)
     if (pl.slab_w > 0) {
         // slab path: the final K' keys of every bucket through the workspace, then stage 2
         p.mode = 3;

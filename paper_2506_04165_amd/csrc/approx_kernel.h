@@ -60,6 +60,9 @@ struct ApproxParams {
     int32_t* out_idx;
     void* surv_vals;
     int32_t* surv_idx;
+    int32_t* cert_flags;  // optional [rows] (packed-key variants only): 0 where no bucket contributes K' of the
+                          // row's K results (the results are then the exact Top-K), 1 where one does or
+                          // the question stays open; see certify.hip
     uint32_t flip;        // 0: the K greatest.  The K smallest (min-K): the mask that reverses the order
                           // of the element type, xor-ed onto every loaded pattern -- the sign bit of
                           // a floating type (0x80000000 on the widened pattern), all bits of an
@@ -483,8 +486,14 @@ struct ApproxKernel {
             else __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             if (p.G >= kWave) {
                 if (t < kWave && row_ok)
-                    wave_sort32_dispatch<DT>(cand32, p.Cpad, p.K, rowp, p.out_vals, p.out_idx,
-                                             (int64_t)row * p.K, flip);
+                {
+                    if (p.cert_flags)
+                        wave_sort32_certify_dispatch<DT>(cand32, p.Cpad, p.K, rowp, p.out_vals, p.out_idx,
+                                                         (int64_t)row * p.K, flip, p.cert_flags + row, p.B, p.Kprime);
+                    else
+                        wave_sort32_dispatch<DT>(cand32, p.Cpad, p.K, rowp, p.out_vals, p.out_idx,
+                                                 (int64_t)row * p.K, flip);
+                }
             } else {
                 // several rows per wavefront: it sorts them one after the other
                 const int per_wave = kWave / p.G;
@@ -492,9 +501,16 @@ struct ApproxKernel {
                     const int gl = (tid >> 6) * per_wave + j;
                     const int rw = blockIdx.x * p.rows_per_wg + gl;
                     if (rw < p.rows)
-                        wave_sort32_dispatch<DT>((uint32_t*)lds + (size_t)gl * p.Cpad, p.Cpad, p.K,
-                                                 (const char*)p.values + (size_t)rw * p.row_stride * ES,
-                                                 p.out_vals, p.out_idx, (int64_t)rw * p.K, flip);
+                    {
+                        uint32_t* keys32 = (uint32_t*)lds + (size_t)gl * p.Cpad;
+                        const char* rowp_w = (const char*)p.values + (size_t)rw * p.row_stride * ES;
+                        if (p.cert_flags)
+                            wave_sort32_certify_dispatch<DT>(keys32, p.Cpad, p.K, rowp_w, p.out_vals, p.out_idx,
+                                                             (int64_t)rw * p.K, flip, p.cert_flags + rw, p.B, p.Kprime);
+                        else
+                            wave_sort32_dispatch<DT>(keys32, p.Cpad, p.K, rowp_w, p.out_vals, p.out_idx,
+                                                     (int64_t)rw * p.K, flip);
+                    }
                 }
             }
             return;

@@ -18,10 +18,12 @@ struct CertifyParams {
     void* out_vals;           // [rows, K] in: the two-stage result; out: the exact one
     int32_t* out_idx;
     int32_t* hard_rows;       // [rows] out: 1 where the row has to be done by the exact kernel, else 0
+    const int32_t* open_rows; // optional [rows]: 0 where the two-stage launch has already certified the row
+                              // (ApproxParams::cert_flags), which is then not looked at
 };
 
 constexpr int kCertifyMaxB = 4096;       // buckets the LDS counters hold
-constexpr int kCertifyRowsPerWg = 8;
+constexpr int kCertifyRowsPerWg = 4;
 constexpr int kCertifyMaxFlagged = 128;  // buckets a workgroup repairs before it gives up
 
 size_t certify_lds_bytes(const CertifyParams& p);

@@ -62,13 +62,17 @@ __device__ void certify_repair(const CertifyParams& p, const CertifyLds& L, int 
 #pragma unroll
     for (int u = 0; u < kRegs; ++u) {
         const int e = tid + u * T;
-        ebits[u] = e < total ? elem<DT>::load_bits(rowp, element_of(e)) : 0u;
+        ebits[u] = elem<DT>::load_bits(rowp, element_of(min(e, total - 1)));      // (clamped, not branched: see below)
     }
 #pragma unroll
     for (int u = 0; u < kRegs; ++u) {
         const int i = tid + u * T;
-        myidx[u] = i < K ? (uint32_t)p.out_idx[out_base + i] : 0xffffffffu;
-        myval[u] = i < K ? elem<DT>::load_bits(p.out_vals, out_base + i) : 0u;   // (needed or not: no second wait)
+        // Loads at a clamped position with the result masked afterwards, never a load under a
+        // test: the compiler ends every such test with a wait, one memory latency per load.
+        const int ic = min(i, K - 1);
+        myidx[u] = (uint32_t)p.out_idx[out_base + ic];
+        myval[u] = elem<DT>::load_bits(p.out_vals, out_base + ic);   // (needed or not: no second wait)
+        if (i >= K) myidx[u] = 0xffffffffu;
     }
     // the counters of the buckets in doubt now name their slot
     for (int f = tid; f < nf; f += T) {
@@ -161,7 +165,8 @@ __device__ void certify_row_wg(const CertifyParams& p, const CertifyLds& L, int 
 #pragma unroll
     for (int u = 0; u < kPerThread; ++u) {
         const int i = tid + u * T;
-        mine[u] = i < K ? (uint32_t)p.out_idx[out_base + i] : 0xffffffffu;
+        mine[u] = (uint32_t)p.out_idx[out_base + min(i, K - 1)];     // (clamped, masked below: no load under a test)
+        if (i >= K) mine[u] = 0xffffffffu;
     }
     for (int b = tid; b < B; b += T) L.hist[b] = 0;
     if (tid == 0) L.ctl[4] = 0;
@@ -203,7 +208,8 @@ __device__ bool certify_row_wave(const CertifyParams& p, int row, uint32_t* hist
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const int i = i0 + u * kWave + lane;
-            idx[u] = i < K ? (uint32_t)p.out_idx[out_base + i] : 0xffffffffu;
+            idx[u] = (uint32_t)p.out_idx[out_base + min(i, K - 1)];  // (clamped, masked: no load under a test)
+            if (i >= K) idx[u] = 0xffffffffu;
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u)
@@ -225,9 +231,9 @@ __device__ bool certify_row_wave(const CertifyParams& p, int row, uint32_t* hist
     uint32_t ebits[kWaveCheckRegs];
 #pragma unroll
     for (int u = 0; u < kWaveCheckRegs; ++u) {
-        const int e = lane + u * kWave;
+        const int e = min(lane + u * kWave, total - 1);       // (clamped: no load under a test)
         const int f = e / per_bucket, j = e - f * per_bucket;
-        ebits[u] = e < total ? elem<DT>::load_bits(rowp, (uint32_t)j * (uint32_t)B + (uint32_t)flagged[f < nf ? f : 0]) : 0u;
+        ebits[u] = elem<DT>::load_bits(rowp, (uint32_t)j * (uint32_t)B + (uint32_t)flagged[f]);
     }
     // ... and with them the result's indices and values (needed or not: a load behind a test, or
     // behind the fence below, would wait for memory a second time)
@@ -235,8 +241,10 @@ __device__ bool certify_row_wave(const CertifyParams& p, int row, uint32_t* hist
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const int i = i0 + u * kWave + lane;
-            idx[u] = i < K ? (uint32_t)p.out_idx[out_base + i] : 0xffffffffu;
-            val[u] = i < K ? elem<DT>::load_bits(p.out_vals, out_base + i) : 0u;
+            const int ic = min(i, K - 1);                    // (clamped, masked: no load under a test)
+            idx[u] = (uint32_t)p.out_idx[out_base + ic];
+            val[u] = elem<DT>::load_bits(p.out_vals, out_base + ic);
+            if (i >= K) idx[u] = 0xffffffffu;
         }
     };
     // least result key of every bucket in doubt, and the K-th key
@@ -282,11 +290,11 @@ __device__ bool certify_row_wave(const CertifyParams& p, int row, uint32_t* hist
     return __ballot(missing) == 0;
 }
 
-constexpr int kRowsPerWave = 2;                  // rows a wavefront takes in the many-rows form
+constexpr int kRowsPerWave = 1;                  // rows a wavefront takes in the many-rows form
 static_assert(kCertifyWaves * kRowsPerWave == kCertifyRowsPerWg, "rows of a workgroup in the many-rows form");
 
 template <typename DT>
-__global__ void __launch_bounds__(kCertifyThreads) certify_kernel(CertifyParams p) {
+__global__ void __launch_bounds__(kCertifyThreads, 8) certify_kernel(CertifyParams p) {
     extern __shared__ uint64_t lds64[];
     CertifyLds L;
     L.buf = lds64;
@@ -304,6 +312,7 @@ __global__ void __launch_bounds__(kCertifyThreads) certify_kernel(CertifyParams 
     if (per_bucket <= p.Kprime) return;          // every bucket was kept whole: nothing can be missing
 
     if (p.rows_per_wg == 1) {
+        if (p.open_rows && p.open_rows[first_row] == 0) return;
         certify_row_wg<DT>(p, L, first_row);
         return;
     }
@@ -319,6 +328,7 @@ __global__ void __launch_bounds__(kCertifyThreads) certify_kernel(CertifyParams 
     for (int q = 0; q < kRowsPerWave; ++q) {
         const int row = first_row + q * kCertifyWaves + w;
         if (row >= p.rows) break;
+        if (p.open_rows && p.open_rows[row] == 0) continue;
         const bool ok = certify_row_wave<DT>(p, row, wave_hist + (size_t)w * p.B,
                                              wave_small + w * (2 * kWaveCheckBuckets + 2));
         if (!ok && (tid & (kWave - 1)) == 0) todo[atomicAdd(&L.ctl[8], 1u)] = (uint32_t)row;

@@ -208,10 +208,13 @@ __device__ __noinline__ void wave_sort_dispatch(uint64_t* keys, int n, int K, co
 
 // ---- packed 32-bit keys (bf16 rows of at most 65536 elements) ---------------------------------
 // key = ordered 16-bit value << 16 | (0xFFFF - index); 0 = empty.
-template <typename DT, int R>
+// cert_flag (optional): where to note whether some bucket (index mod cert_B) contributes cert_Kp or
+// more of the K results -- the exactness certificate of the two-stage method, taken here while the
+// sorted keys sit in registers: 0 = no bucket does, the K results are the exact Top-K of the row.
+template <typename DT, int R, bool CERT>
 __device__ __forceinline__ void wave_sort32_from_lds(uint32_t* keys_generic, int n, int K, const void* rowp,
                                                      void* out_vals, int32_t* out_idx, int64_t out_base,
-                                                     uint32_t flip) {
+                                                     uint32_t flip, int32_t* cert_flag, int cert_B, int cert_Kp) {
     lds_ptr<uint32_t> keys = (lds_ptr<uint32_t>)keys_generic;
     const int lane = __lane_id();
     uint32_t k[R];
@@ -221,6 +224,29 @@ __device__ __forceinline__ void wave_sort32_from_lds(uint32_t* keys_generic, int
         k[j] = i < n ? keys[i] : 0;
     }
     WaveSort<R, uint32_t>::sort(k);
+    if constexpr (CERT) {
+        // counters at the end of the key array, behind what the staging below uses (the keys are
+        // in registers by now); no room: the question stays open
+        bool doubt = true;
+        if ((K + R - 1) / R * R + cert_B <= n) {
+            lds_ptr<uint32_t> count = keys + (n - cert_B);
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            for (int b = lane; b < cert_B; b += kWave) count[b] = 0;
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            const bool pow2 = (cert_B & (cert_B - 1)) == 0;
+            bool full = false;
+#pragma unroll
+            for (int j = 0; j < R; ++j)
+                if (lane * R + j < K && k[j] != 0) {
+                    const uint32_t idx = 0xffffu - (k[j] & 0xffffu);
+                    const uint32_t b = pow2 ? (idx & (uint32_t)(cert_B - 1)) : idx % (uint32_t)cert_B;
+                    full |= atomicAdd((uint32_t*)&count[b], 1u) + 1u >= (uint32_t)cert_Kp;
+                }
+            doubt = __ballot(full) != 0;
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        }
+        if (lane == 0) *cert_flag = doubt ? 1 : 0;
+    }
     // through LDS (the key array itself) so that consecutive lanes write consecutive outputs
     if (lane * R < K) {
 #pragma unroll
@@ -242,11 +268,24 @@ template <typename DT>
 __device__ __noinline__ void wave_sort32_dispatch(uint32_t* keys, int n, int K, const void* rowp,
                                                   void* out_vals, int32_t* out_idx, int64_t out_base,
                                                   uint32_t flip = 0) {
-    if (n <= 64)       wave_sort32_from_lds<DT, 1>(keys, n, K, rowp, out_vals, out_idx, out_base, flip);
-    else if (n <= 128) wave_sort32_from_lds<DT, 2>(keys, n, K, rowp, out_vals, out_idx, out_base, flip);
-    else if (n <= 256) wave_sort32_from_lds<DT, 4>(keys, n, K, rowp, out_vals, out_idx, out_base, flip);
-    else if (n <= 512) wave_sort32_from_lds<DT, 8>(keys, n, K, rowp, out_vals, out_idx, out_base, flip);
-    else               wave_sort32_from_lds<DT, 16>(keys, n, K, rowp, out_vals, out_idx, out_base, flip);
+    if (n <= 64)       wave_sort32_from_lds<DT, 1, false>(keys, n, K, rowp, out_vals, out_idx, out_base, flip, nullptr, 0, 0);
+    else if (n <= 128) wave_sort32_from_lds<DT, 2, false>(keys, n, K, rowp, out_vals, out_idx, out_base, flip, nullptr, 0, 0);
+    else if (n <= 256) wave_sort32_from_lds<DT, 4, false>(keys, n, K, rowp, out_vals, out_idx, out_base, flip, nullptr, 0, 0);
+    else if (n <= 512) wave_sort32_from_lds<DT, 8, false>(keys, n, K, rowp, out_vals, out_idx, out_base, flip, nullptr, 0, 0);
+    else               wave_sort32_from_lds<DT, 16, false>(keys, n, K, rowp, out_vals, out_idx, out_base, flip, nullptr, 0, 0);
+}
+
+// The same, taking the exactness certificate on the way (see wave_sort32_from_lds): a copy of its
+// own, so that the plain form carries nothing of it.
+template <typename DT>
+__device__ __noinline__ void wave_sort32_certify_dispatch(uint32_t* keys, int n, int K, const void* rowp,
+                                                          void* out_vals, int32_t* out_idx, int64_t out_base,
+                                                          uint32_t flip, int32_t* cert_flag, int cert_B, int cert_Kp) {
+    if (n <= 64)       wave_sort32_from_lds<DT, 1, true>(keys, n, K, rowp, out_vals, out_idx, out_base, flip, cert_flag, cert_B, cert_Kp);
+    else if (n <= 128) wave_sort32_from_lds<DT, 2, true>(keys, n, K, rowp, out_vals, out_idx, out_base, flip, cert_flag, cert_B, cert_Kp);
+    else if (n <= 256) wave_sort32_from_lds<DT, 4, true>(keys, n, K, rowp, out_vals, out_idx, out_base, flip, cert_flag, cert_B, cert_Kp);
+    else if (n <= 512) wave_sort32_from_lds<DT, 8, true>(keys, n, K, rowp, out_vals, out_idx, out_base, flip, cert_flag, cert_B, cert_Kp);
+    else               wave_sort32_from_lds<DT, 16, true>(keys, n, K, rowp, out_vals, out_idx, out_base, flip, cert_flag, cert_B, cert_Kp);
 }
 
 // Slab route of the streaming kernel: the 64*R keys at `keys` (LDS) are the partial lists of

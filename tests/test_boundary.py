@@ -138,12 +138,12 @@ def test_workspace_query_and_too_small():
     # fused cases need no workspace
     assert atk.workspace_bytes(atk.OP_APPROX_TOPK, f32, 256, 1048576, 128, 4, 1024) == 0
     # the exact entry: the flag words of the certified route where it applies, else nothing
-    assert atk.workspace_bytes(atk.OP_TOPK, f32, 4, 4096, 32, 0, 0) == 256
+    assert atk.workspace_bytes(atk.OP_TOPK, f32, 4, 4096, 32, 0, 0) == 512
     assert atk.describe_topk_plan(f32, 4, 4096, 32)[1].startswith("certified B=64 K'=4")
     assert atk.workspace_bytes(atk.OP_TOPK, f32, 16384, 14336, 287, 0, 0) == 0               # short rows
     assert atk.describe_topk_plan(f32, 16384, 14336, 287) == (atk.OK, "radix threads=256")
     # ... unless of 16-bit elements: the packed-key kernels, K' = 8
-    assert atk.workspace_bytes(atk.OP_TOPK, torch.bfloat16, 16384, 14336, 287, 0, 0) == 16384 * 4
+    assert atk.workspace_bytes(atk.OP_TOPK, torch.bfloat16, 16384, 14336, 287, 0, 0) == 2 * 16384 * 4
     assert atk.describe_topk_plan(torch.bfloat16, 16384, 14336, 287)[1].startswith("certified B=128 K'=8")
     # K' = K beyond the list lengths is the exact Top-K: the same workspace
     assert atk.workspace_bytes(atk.OP_APPROX_TOPK, f32, 4, 65536, 64, 64, 8) == \
