@@ -234,14 +234,16 @@ __device__ __forceinline__ void wave_sort32_from_lds(uint32_t* keys_generic, int
             for (int b = lane; b < cert_B; b += kWave) count[b] = 0;
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             const bool pow2 = (cert_B & (cert_B - 1)) == 0;
-            bool full = false;
 #pragma unroll
             for (int j = 0; j < R; ++j)
                 if (lane * R + j < K && k[j] != 0) {
                     const uint32_t idx = 0xffffu - (k[j] & 0xffffu);
                     const uint32_t b = pow2 ? (idx & (uint32_t)(cert_B - 1)) : idx % (uint32_t)cert_B;
-                    full |= atomicAdd((uint32_t*)&count[b], 1u) + 1u >= (uint32_t)cert_Kp;
+                    atomicAdd((uint32_t*)&count[b], 1u);         // (result unused: nothing to wait for)
                 }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            bool full = false;
+            for (int b = lane; b < cert_B; b += kWave) full |= count[b] >= (uint32_t)cert_Kp;
             doubt = __ballot(full) != 0;
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         }
