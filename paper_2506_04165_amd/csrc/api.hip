@@ -127,6 +127,10 @@ struct Options {
     int lanes_per_row = 0;    // 0: planner's choice, else a power of two <= 1024
     int segments = 0;         // > 0: force this many row segments on the split route
     int slab = 1;             // 0 never / 1 planner's choice / 2 whenever possible: slab route
+    int rank_finish = 1;      // 0: stage 2 of the slab route is never spread over several workgroups per row
+    int slab_owners = 0;      // 0: planner's choice (8), else a power of two: most lanes that share a bucket on the slab route
+    int slab_width = 0;       // 0: planner's choice, else buckets per workgroup on the slab route with the
+                              // ranking finish (a power of two >= 32)
     int packed = 1;           // 0: no packed 32-bit keys for 16-bit rows
     int subwave = 1;          // 0: no several-rows-per-wavefront variants
     int batch_min_kp = 16;    // list length from which sorted batches are used
@@ -154,6 +158,10 @@ static void options_from_env_once() {
         o.lanes_per_row = env("ATK_LANES_PER_ROW", o.lanes_per_row);
         o.segments = env("ATK_SEGMENTS", o.segments);
         o.slab = env("ATK_SLAB", o.slab);
+        o.rank_finish = env("ATK_RANK_FINISH", o.rank_finish);
+        o.slab_width = env("ATK_SLAB_WIDTH", o.slab_width);
+        o.slab_owners = env("ATK_SLAB_OWNERS", o.slab_owners);
+        if (o.slab_owners < 0 || o.slab_owners > 32 || (o.slab_owners & (o.slab_owners - 1))) o.slab_owners = 0;
         o.packed = env("ATK_NO_PACKED", 0) ? 0 : 1;
         o.subwave = env("ATK_NO_SUBWAVE", 0) ? 0 : 1;
         o.batch_min_kp = env("ATK_BATCH_MIN_KP", o.batch_min_kp);
@@ -205,6 +213,8 @@ struct Plan {
     int chunk_k = 0;              // > 0: ... and runs stage 2 on them itself, leaving its chunk_k greatest
                                   // (of which the exact kernel picks the row's K); 0: all survivors leave
     int slab_w = 0;             // > 0: workgroups take slabs of this many buckets (see below)
+    int run_len = 0;            // slab route, > 0: a slab's final keys leave as one sorted run of this length and
+    int rank_runs_per_wg = 0;   // stage 2 is the ranking finish, a workgroup placing the keys of this many runs
 };
 
 static int list_len_for(int Kp) {
@@ -401,8 +411,8 @@ static Plan compute_plan(const void* values, int dtype, int64_t rows, int64_t N,
     if (pl.fused && owners == 1 && G >= 64 && rows > 0 && B % kSlabBuckets == 0 &&
         pl.var->rep != 2 && g_opt.slab != 0) {
         const int64_t steps = N / B;
-        int m = 8;
-        while (m > 1 && (steps % m != 0 || steps / m < 4 || m * KP > 64)) m >>= 1;
+        int m = g_opt.slab_owners > 0 ? g_opt.slab_owners : 8;
+        while (m > 1 && (steps % m != 0 || steps / m < 4 || m * KP > 64 || m * kSlabBuckets > kMaxLanes)) m >>= 1;
         const Variant* v = find_variant(dtype, KP, 1, false, [](int V) { return V == 1; });
         const size_t in_bytes = (size_t)rows * N * es;
         const size_t ws = (size_t)rows * Kp * B * 8;
@@ -415,18 +425,57 @@ static Plan compute_plan(const void* values, int dtype, int64_t rows, int64_t N,
         if (m > 1 && v && v->V == 1 && v->R == 1 && ws <= ws_avail &&
             (g_opt.slab == 2 || few)) {
             pl.var = v;
-            pl.slab_w = kSlabBuckets;
-            pl.G = kSlabBuckets * m;
-            pl.owners = m;
-            pl.S = m * B;
-            pl.nsteps = (int)(N / pl.S);
-            pl.seg = pow2_ceil((int64_t)m * KP);
             pl.rows_per_wg = 1;
-            pl.block = pl.G;
             pl.grid = (int)rows;
             pl.aux_offset = 0;
-            pl.lds = (size_t)kSlabBuckets * pl.seg * 8;
+            auto shape = [&](int slab_w, int owners_) {
+                pl.slab_w = slab_w;
+                pl.G = pl.block = slab_w * owners_;
+                pl.owners = owners_;
+                pl.S = owners_ * B;
+                pl.nsteps = (int)(N / pl.S);
+                pl.seg = pow2_ceil((int64_t)owners_ * KP);
+                pl.lds = (size_t)slab_w * pl.seg * 8;
+            };
+            shape(kSlabBuckets, m);
             pl.workspace = ws;
+            // Stage 2 spread over several workgroups per row: every slab's keys leave as a sorted
+            // run and the second launch places each key by counting the keys above it, which
+            // costs in proportion to the count of runs.  Slabs are therefore widened until a run
+            // has 128 keys, and 256 while there are more than 32 runs (K' = 2: 64 or 128 buckets,
+            // K' = 1: 128), with fewer lanes per bucket so that the workgroup keeps 256 lanes.
+            // Measured on 8 x 262144, K = 1024 (GPU time per call): 15.5 against 22.9 us at
+            // (1024, 4), 13.8 / 20.7 at (2048, 2), 16.2 / 23.0 at (4096, 2), 16.2 / 25.1 at
+            // (8192, 1), 23.0 / 36.1 at (512, 8).  The gain shrinks as rows are added (there are
+            // then enough single-workgroup finishes to fill the chip) and is gone where a
+            // workgroup would have to place the keys of more than two runs (1 to 64 rows of
+            // 2^16 to 2^20 elements, K = 64 to 1024: 64 rows at (1024, 4) 42.6 against 28.8 us).
+            const int kp2 = (int)pow2_ceil(Kp);
+            int slab_w = kSlabBuckets;
+            if (g_opt.slab_width >= kSlabBuckets && B % g_opt.slab_width == 0) {
+                slab_w = g_opt.slab_width;
+            } else {
+                while ((slab_w * kp2 < 128 || (slab_w * kp2 < 256 && B / slab_w > 32)) &&
+                       slab_w < 128 && B % (2 * slab_w) == 0)
+                    slab_w *= 2;
+            }
+            int mr = m;
+            while (mr > 2 && slab_w * mr > (g_opt.slab_owners > 0 ? kMaxLanes : 256)) mr >>= 1;
+            const int run_len = slab_w * kp2;
+            const int64_t nruns = B / slab_w;
+            const size_t ws_runs = (size_t)rows * nruns * run_len * 8;
+            if (g_opt.rank_finish != 0 && run_len <= 256 && slab_w * mr <= kMaxLanes &&
+                pow2_ceil((int64_t)mr * KP) <= 16 * mr &&
+                nruns * run_len <= kRankMaxKeys && rows * nruns <= 1024 && ws_runs <= ws_avail) {
+                shape(slab_w, mr);
+                pl.run_len = run_len;
+                pl.rank_runs_per_wg = 1;
+                while (pl.rank_runs_per_wg < nruns &&
+                       rows * ((nruns + pl.rank_runs_per_wg - 1) / pl.rank_runs_per_wg) > 512)
+                    pl.rank_runs_per_wg <<= 1;
+                pl.lds += (size_t)run_len * 8;
+                pl.workspace = ws_runs;
+            }
             return pl;
         }
     }
@@ -790,8 +839,21 @@ static int approx_impl(const void* values, int dtype, int64_t rows, int64_t N, i
         p.mode = 3;
         p.slab_w = pl.slab_w;
         p.part_keys = (uint64_t*)workspace;
+        p.run_len = pl.run_len;
         hipError_t e = pl.var->fn(p, pl.grid, pl.block, pl.lds, st);
         if (e != hipSuccess) return hip_fail(e);
+        if (pl.run_len > 0) {
+            RankFinishParams r{};
+            r.runs = (const uint64_t*)workspace; r.values = values; r.row_stride = row_stride;
+            r.rows = (int)rows; r.K = K; r.nruns = B / pl.slab_w;
+            r.log_run = 0;
+            while ((1 << r.log_run) < pl.run_len) ++r.log_run;
+            r.runs_per_wg = pl.rank_runs_per_wg;
+            r.flip = flip;
+            r.out_vals = out_vals; r.out_idx = out_idx;
+            e = launch_rank_finish(r, dtype, st);
+            return e == hipSuccess ? ATK_OK : hip_fail(e);
+        }
         FinishParams f{};
         f.part_keys = (const uint64_t*)workspace; f.values = values; f.row_stride = row_stride;
         f.rows = (int)rows; f.K = K; f.Kprime = Kprime; f.B = B; f.nseg = 1; f.Cpad = pl.Cpad;
@@ -1103,6 +1165,13 @@ int atk_describe_plan(int dtype, int64_t rows, int64_t N, int K, int Kprime, int
                   pl.var->R, pl.G, pl.rows_per_wg, pl.block, pl.grid,
                   pl.slab_w > 0 ? B / pl.slab_w : (pl.nseg > 1 ? pl.nseg : pl.nchunk), pl.S, pl.nsteps,
                   pl.owners, pl.seg, pl.Cpad, pl.tail, pl.lds, pl.workspace);
+    if (pl.run_len > 0) {
+        // second launch: workgroups per row x keys each of them places
+        const size_t n = std::strlen(buf);
+        const int nruns = B / pl.slab_w;
+        std::snprintf(buf + n, buflen - n, " rank_finish=%dx%d",
+                      (nruns + pl.rank_runs_per_wg - 1) / pl.rank_runs_per_wg, pl.rank_runs_per_wg * pl.run_len);
+    }
     return ATK_OK;
 }
 
@@ -1113,7 +1182,7 @@ int atk_set_option(const char* name, int value) {
     struct Entry { const char* name; int Options::*field; };
     static const Entry entries[] = {
         {"lanes_per_row", &Options::lanes_per_row}, {"segments", &Options::segments},
-        {"slab", &Options::slab}, {"packed", &Options::packed}, {"subwave", &Options::subwave},
+        {"slab", &Options::slab}, {"rank_finish", &Options::rank_finish}, {"slab_width", &Options::slab_width}, {"slab_owners", &Options::slab_owners}, {"packed", &Options::packed}, {"subwave", &Options::subwave},
         {"batch_min_kp", &Options::batch_min_kp}, {"mips_segments", &Options::mips_segments},
         {"unfused", &Options::unfused}, {"onepass", &Options::onepass}, {"chunked", &Options::chunked},
         {"exact_threads", &Options::exact_threads}, {"certified", &Options::certified}, {"reg_rows", &Options::reg_rows},
@@ -1122,6 +1191,8 @@ int atk_set_option(const char* name, int value) {
         if (std::strcmp(name, e.name) != 0) continue;
         int v = value < 0 ? defaults.*(e.field) : value;
         if (e.field == &Options::lanes_per_row && (v > kMaxLanes || (v & (v - 1)))) return ATK_INVALID_ARG;
+        if (e.field == &Options::slab_owners && (v > 32 || (v & (v - 1)))) return ATK_INVALID_ARG;
+        if (e.field == &Options::slab_width && v != 0 && (v < 32 || v > 1024 || (v & (v - 1)))) return ATK_INVALID_ARG;
         if (e.field == &Options::exact_threads && v != 0 && (v < 64 || v > 1024 || (v & (v - 1)))) return ATK_INVALID_ARG;
         g_opt.*(e.field) = v;
         ++g_opt_generation;

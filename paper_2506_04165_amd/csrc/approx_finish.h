@@ -25,4 +25,18 @@ constexpr int kFinishScores = 100;
 // KP: compiled list length (>= Kprime), one of 1,2,3,4,6,8,16,32
 hipError_t launch_finish(const FinishParams& p, int dtype, int KP, hipStream_t stream);
 
+// Stage 2 by ranking (slab route): see rank_finish_kernel.
+struct RankFinishParams {
+    const uint64_t* runs;        // [rows, nruns, 1 << log_run] keys, every run sorted (greatest first), zeros last
+    const void* values;          // the input, only read to tell -0.0 from +0.0
+    int64_t row_stride;
+    int rows, K, nruns, log_run;
+    int runs_per_wg;             // runs whose keys one workgroup ranks (grid: ceil(nruns / runs_per_wg) x rows)
+    uint32_t flip;
+    void* out_vals;
+    int32_t* out_idx;
+};
+constexpr int kRankMaxKeys = 8192;     // keys of a row (nruns << log_run) that the kernel holds in LDS
+hipError_t launch_rank_finish(const RankFinishParams& p, int dtype, hipStream_t stream);
+
 }  // namespace atk

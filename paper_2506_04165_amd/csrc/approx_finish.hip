@@ -79,6 +79,136 @@ __global__ void __launch_bounds__(1024) approx_finish_kernel(FinishParams p) {
                          (int64_t)row * p.K, p.flip);
 }
 
+// Stage 2 by ranking, spread over several workgroups per row (few rows: the streaming launch
+// left the survivors of every row as sorted runs of equal length, one per slab of buckets).
+// Keys are distinct, so the place of a key in the result is the number of keys above it: its
+// place in its own run plus, per other run, the count of greater keys there (a binary search).
+// Every workgroup copies all runs of its row to LDS, ranks the keys of its own runs and writes
+// those whose rank is below K to that place of the output; nothing is sorted or selected.
+// Keys that cannot reach the result are left out first: with q = ceil(K / runs), the least of
+// the runs' q-th keys has at least K keys at or above it, so it bounds the K-th key from below.
+constexpr int kRankThreads = 256;
+
+__device__ __forceinline__ int count_greater(const lds_ptr<const uint64_t> run, int log_len, uint64_t x) {
+    int pos = 0;
+    for (int s = 1 << (log_len - 1); s >= 1; s >>= 1) pos += run[pos + s - 1] > x ? s : 0;
+    return pos + (run[pos] > x ? 1 : 0);
+}
+
+template <typename DT>
+__global__ void __launch_bounds__(kRankThreads) rank_finish_kernel(RankFinishParams p) {
+    extern __shared__ uint64_t rk_lds[];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+    const int row = blockIdx.y;
+    const int L = 1 << p.log_run, C = p.nruns << p.log_run;
+    lds_ptr<uint64_t> keys = (lds_ptr<uint64_t>)rk_lds;
+    lds_ptr<uint32_t> rank = (lds_ptr<uint32_t>)(rk_lds + C);           // one word per key of mine
+    lds_ptr<uint64_t> red = (lds_ptr<uint64_t>)(rk_lds + C) + ((p.runs_per_wg << p.log_run) + 1) / 2;
+    {
+        // eight 16-byte loads per thread are asked for before the first is stored (positions
+        // clamped instead of tested: a load under a test ends in a wait of its own)
+        typedef uint64_t u64x2 __attribute__((ext_vector_type(2)));
+        const u64x2* src = (const u64x2*)(p.runs + (size_t)row * C);
+        lds_ptr<u64x2> dst = (lds_ptr<u64x2>)rk_lds;
+        const int nvec = C / 2;
+        for (int base = tid; base < nvec; base += 8 * kRankThreads) {
+            u64x2 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = src[min(base + u * kRankThreads, nvec - 1)];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (base + u * kRankThreads < nvec) dst[base + u * kRankThreads] = v[u];
+        }
+    }
+    const int first = (int)blockIdx.x * p.runs_per_wg;
+    const int mine = min(p.runs_per_wg, p.nruns - first) << p.log_run;  // keys of this workgroup
+    for (int i = tid; i < mine; i += kRankThreads) rank[i] = 0;
+    __syncthreads();
+    // lower bound of the K-th key
+    uint64_t bound = 0;
+    const int q = (p.K + p.nruns - 1) / p.nruns;
+    if (q <= L) {
+        uint64_t least = ~0ull;
+        for (int r = tid; r < p.nruns; r += kRankThreads) least = min(least, keys[(r << p.log_run) + q - 1]);
+        for (int o = 32; o >= 1; o >>= 1) {
+            const uint64_t other = ((uint64_t)__shfl_xor((unsigned)(least >> 32), o, kWave) << 32) |
+                                   __shfl_xor((unsigned)least, o, kWave);
+            least = min(least, other);
+        }
+        if (lane == 0) red[wave] = least;
+        __syncthreads();
+        bound = min(min(red[0], red[1]), min(red[2], red[3]));
+    }
+    // Work items: (key of mine, part of the runs).  Keys at or above the bound are the first
+    // ones of each run; a run's count of them comes from the same binary search.
+    // Consecutive threads take consecutive keys of a run: their searches in another run visit
+    // mostly the same or neighbouring words.  Few keys: several threads share a key, each
+    // taking every parts-th run, and add their counts up in LDS.
+    int slots = 1;                      // power of two >= the greatest count of such keys over my runs
+    if (bound == 0) {
+        slots = L;
+    } else {
+        lds_ptr<uint32_t> most_word = (lds_ptr<uint32_t>)(red + 4);
+        if (tid == 0) *most_word = 1;
+        __syncthreads();
+        if (tid < (mine >> p.log_run))
+            atomicMax((uint32_t*)most_word,
+                      (uint32_t)count_greater(keys + ((first + tid) << p.log_run), p.log_run, bound - 1));
+        __syncthreads();
+        const int most = (int)*most_word;
+        while (slots < most) slots <<= 1;
+    }
+    const int myruns = mine >> p.log_run;
+    const int items = slots * myruns;                     // (run of mine, position < slots)
+    const int parts = items >= kRankThreads ? 1 : kRankThreads / items;      // threads sharing a key
+    const int part = items >= kRankThreads ? 0 : tid / items;
+    for (int it = tid - part * items; it < items && part < parts; it += kRankThreads) {
+        const int r = it / slots, pos = it - r * slots;
+        const uint64_t x = keys[((first + r) << p.log_run) + pos];
+        if (x == 0 || x < bound) continue;
+        int above = 0;
+        int o = part;
+        for (; o + 3 * parts < p.nruns; o += 4 * parts) {
+            // four searches side by side: their loads overlap
+            int p0 = 0, p1 = 0, p2 = 0, p3 = 0;
+            const lds_ptr<const uint64_t> r0 = keys + (o << p.log_run), r1 = keys + ((o + parts) << p.log_run),
+                                          r2 = keys + ((o + 2 * parts) << p.log_run), r3 = keys + ((o + 3 * parts) << p.log_run);
+            for (int s = L >> 1; s >= 1; s >>= 1) {
+                const uint64_t a0 = r0[p0 + s - 1], a1 = r1[p1 + s - 1], a2 = r2[p2 + s - 1], a3 = r3[p3 + s - 1];
+                p0 += a0 > x ? s : 0; p1 += a1 > x ? s : 0; p2 += a2 > x ? s : 0; p3 += a3 > x ? s : 0;
+            }
+            const uint64_t a0 = r0[p0], a1 = r1[p1], a2 = r2[p2], a3 = r3[p3];
+            above += p0 + p1 + p2 + p3 + (a0 > x ? 1 : 0) + (a1 > x ? 1 : 0) + (a2 > x ? 1 : 0) + (a3 > x ? 1 : 0);
+        }
+        for (; o < p.nruns; o += parts) above += count_greater(keys + (o << p.log_run), p.log_run, x);
+        if (parts == 1) rank[(r << p.log_run) + pos] = (uint32_t)above;
+        else atomicAdd((uint32_t*)&rank[(r << p.log_run) + pos], (uint32_t)above);
+    }
+    __syncthreads();
+    const char* rowp = (const char*)p.values + (size_t)row * p.row_stride * elem<DT>::size;
+    for (int it = tid; it < items; it += kRankThreads) {
+        const int r = it / slots, pos = it - r * slots;
+        const uint64_t key = keys[((first + r) << p.log_run) + pos];
+        const uint32_t place = rank[(r << p.log_run) + pos];
+        if (key != 0 && key >= bound && place < (uint32_t)p.K) {
+            const uint32_t n = key_index(key);
+            const int64_t o = (int64_t)row * p.K + place;
+            elem<DT>::store_bits(p.out_vals, o, key_stored_bits<DT>(key, rowp, n, p.flip));
+            p.out_idx[o] = (int32_t)n;
+        }
+    }
+}
+
+template <typename DT>
+hipError_t launch_rank_for(const RankFinishParams& p, hipStream_t stream) {
+    const size_t C = (size_t)p.nruns << p.log_run, mine = (size_t)p.runs_per_wg << p.log_run;
+    const size_t lds = C * 8 + ((mine + 1) / 2) * 8 + 64;
+    const dim3 grid((p.nruns + p.runs_per_wg - 1) / p.runs_per_wg, p.rows), block(kRankThreads);
+    allow_large_lds((const void*)rank_finish_kernel<DT>, lds);
+    hipLaunchKernelGGL((rank_finish_kernel<DT>), grid, block, lds, stream, p);
+    return hipGetLastError();
+}
+
 template <typename DT>
 hipError_t launch_for(const FinishParams& p, int KP, int threads, hipStream_t stream) {
     const size_t lds = (size_t)p.Cpad * 8 + (p.Cpad > 256 ? kSelectScratchBytes : 0);
@@ -109,6 +239,16 @@ hipError_t launch_finish(const FinishParams& p, int dtype, int KP, hipStream_t s
         case 1: return launch_for<bf16_t>(p, KP, threads, stream);
         case 3: return launch_for<i32_t>(p, KP, threads, stream);
         case 4: return launch_for<u32_t>(p, KP, threads, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_rank_finish(const RankFinishParams& p, int dtype, hipStream_t stream) {
+    switch (dtype) {
+        case 0: return launch_rank_for<float>(p, stream);
+        case 1: return launch_rank_for<bf16_t>(p, stream);
+        case 3: return launch_rank_for<i32_t>(p, stream);
+        case 4: return launch_rank_for<u32_t>(p, stream);
         default: return hipErrorInvalidValue;
     }
 }

@@ -49,6 +49,9 @@ struct ApproxParams {
     int nseg;             // mode 2: segments per row (gridDim.y)
     int seg_steps;        // mode 2: steps per segment (the last one may be shorter)
     int slab_w;           // mode 3: buckets per workgroup, a power of two (gridDim.y = B / slab_w)
+    int run_len;          // mode 3: > 0 (slab_w times a power of two >= K', at most 256; one row per
+                          // workgroup): the workgroup's slab_w*K' final keys leave as one sorted,
+                          // zero-padded run, part_keys being [rows, B / slab_w, run_len]
     int chunk;            // modes 0 and 1, one owner per bucket: > 0 cuts the row along the bucket
                           // axis, a workgroup taking buckets [blockIdx.y*chunk, +chunk) over all steps
                           // (gridDim.y = ceil(B / chunk)); 0: the whole row.  In mode 0 (chunk must
@@ -581,7 +584,7 @@ struct ApproxKernel {
             const int nb = p.mode == 3 ? p.slab_w : p.B;             // buckets of this workgroup
             const int b_first = p.mode == 3 ? (int)blockIdx.y * p.slab_w : 0;
             uint64_t* part = lds + p.aux_offset + (size_t)g * nb * p.seg;
-            for (int i = t; i < nb * p.seg; i += p.G) part[i] = 0;
+            for (int i = t; i < nb * p.seg + (p.mode == 3 ? p.run_len : 0); i += p.G) part[i] = 0;   // (and the run behind)
             if (p.mode != 3) { for (int i = C + t; i < p.Cpad; i += p.G) cand[i] = 0; }
             __syncthreads();
             if (row_ok) {
@@ -602,6 +605,19 @@ struct ApproxKernel {
                 // each wavefront holds the lists of 64 / owners buckets, seg / owners keys per
                 // lane: sorted in registers, the final K' keys go straight to memory
                 const int wave = tid >> 6, per_lane = p.seg / p.owners, per_wave = kWave / p.owners;
+                if (p.run_len > 0) {
+                    // ranking finish: the workgroup's final keys leave as one sorted run.  They
+                    // are gathered behind the partial lists ([j][bucket], entries K' <= j <
+                    // run_len / slab_w stay zero as cleared above) and the first wavefront sorts them.
+                    uint64_t* run = lds + p.aux_offset + (size_t)nb * p.seg;
+                    wave_merge_bucket_lists_dispatch(part + (size_t)wave * kWave * per_lane, per_lane,
+                                                     31 - __clz(p.owners), p.Kprime, run + wave * per_wave, nb);
+                    __syncthreads();
+                    if (wave == 0)
+                        wave_sort_run_dispatch(run, p.run_len, p.part_keys +
+                            ((int64_t)row * (p.B / p.slab_w) + blockIdx.y) * p.run_len);
+                    return;
+                }
                 if (row_ok)
                     wave_merge_bucket_lists_dispatch(
                         part + (size_t)wave * kWave * per_lane, per_lane, 31 - __clz(p.owners), p.Kprime,

@@ -322,6 +322,27 @@ __device__ __noinline__ bool wave_merge_bucket_lists_dispatch(const uint64_t* ke
     }
 }
 
+// Slab route with the ranking finish: one wavefront sorts the n (<= 256) keys at `keys` (LDS: the
+// final lists of a workgroup's buckets, zeros where a list is padded) and writes them to
+// out[0, n) in rank order, the greatest first.
+template <int R>
+__device__ __forceinline__ void wave_sort_run(const uint64_t* keys_generic, int n, uint64_t* out) {
+    const lds_ptr<const uint64_t> keys = (lds_ptr<const uint64_t>)keys_generic;
+    const int lane = __lane_id();
+    uint64_t k[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) k[j] = lane * R + j < n ? keys[lane * R + j] : 0;
+    WaveSort<R>::sort(k);
+#pragma unroll
+    for (int j = 0; j < R; ++j)
+        if (lane * R + j < n) out[lane * R + j] = k[j];
+}
+__device__ __noinline__ void wave_sort_run_dispatch(const uint64_t* keys, int n, uint64_t* out) {
+    if (n <= 64)       wave_sort_run<1>(keys, n, out);
+    else if (n <= 128) wave_sort_run<2>(keys, n, out);
+    else               wave_sort_run<4>(keys, n, out);
+}
+
 // Walk a finished histogram from the top bin down.  On return (all threads):
 //   digit   the bin in which the running count reaches `need`,
 //   above   the total of the bins above it,

@@ -407,10 +407,27 @@ def test_slab_path_very_few_rows(atk, knobs):
                 st, text = atk.describe_plan(dtype, rows, N, 1024, Kp, B)
                 assert st == atk.OK
                 # chosen while the launch stays within 2048 workgroups
-                assert text.startswith("slab") == (rows * (B // 32) <= 2048), text
+                slab = rows * (B // 32) <= 2048
+                assert text.startswith("slab") == slab, text
+                # stage 2 spread over several workgroups per row (every key placed by its rank
+                # among the sorted runs the slabs leave) up to 8192 keys per row and lists of 8
+                assert ("rank_finish" in text) == (slab and Kp <= 8), text
                 check_approx(atk, x, 1024, Kp, B)
+                if "rank_finish" in text:
+                    # ... and in one workgroup per row
+                    knobs.set("rank_finish", 0)
+                    st, text = atk.describe_plan(dtype, rows, N, 1024, Kp, B)
+                    assert text.startswith("slab") and "rank_finish" not in text, text
+                    check_approx(atk, x, 1024, Kp, B)
+                    knobs.set("rank_finish", -1)
     z = workloads.heavy_ties(8, 262144, seed=16, symbols=3)
     check_approx(atk, z, 1024, 4, 1024)
+    # K from one key to every survivor
+    zd = z.to(DEV)
+    y = workloads.gaussian(8, 262144, seed=21)
+    for K in (4, 33, 2048, 4096):
+        check_approx(atk, y, K, 4, 1024)
+    check_approx(atk, y, 1, 1, 8192)
     # asked for where the planner would not choose it: few buckets, bucket counts that are only
     # a multiple of 32, rows that one lane per bucket would cover in a handful of steps
     knobs.set("slab", 2)
@@ -422,7 +439,6 @@ def test_slab_path_very_few_rows(atk, knobs):
         check_approx(atk, workloads.heavy_ties(rows, N, seed=20, symbols=5), K, Kp, B)
     knobs.set("slab", -1)
     # a workspace that is too small: the call falls back to a route that needs none
-    zd = z.to(DEV)
     small = torch.empty(1024, dtype=torch.uint8, device=DEV)
     v1, i1 = atk.approx_topk(zd, 1024, 4, 1024)
     out = (torch.empty_like(v1), torch.empty_like(i1))
