@@ -419,62 +419,62 @@ static Plan compute_plan(const void* values, int dtype, int64_t rows, int64_t N,
         // measured against the other routes on 1..128 rows of 2^16..2^20 elements (GPU time with
         // the queue kept full): a gain of 5-55 % inside these limits; beyond them the strided
         // runs cost more than the extra workgroups bring
-        const bool few = rows <= 64 && rows * (B / kSlabBuckets) <= 2048 && B >= 256 &&
+        // Stage 2 spread over several workgroups per row: every slab's keys leave as a sorted
+        // run and the second launch places each key by counting the keys above it, which
+        // costs in proportion to the count of runs.  Slabs are therefore widened until a run
+        // has 128 keys, and 256 while there are more than 32 runs (K' = 2: 64 or 128 buckets,
+        // K' = 1: 128), with fewer lanes per bucket so that the workgroup keeps 256 lanes.
+        // Measured on 8 x 262144, K = 1024 (GPU time per call): 15.4 against 22.9 us at
+        // (1024, 4), 13.7 / 20.7 at (2048, 2), 15.0 / 23.0 at (4096, 2), 14.5 / 25.1 at
+        // (8192, 1), 23.0 / 36.1 at (512, 8), 22.2 / 31.3 at (8192, 2).  The gain shrinks as
+        // rows are added (there are then enough single-workgroup finishes to fill the chip)
+        // and is gone where a workgroup would have to place the keys of more than two runs
+        // (1 to 64 rows of 2^16 to 2^20 elements, K = 64 to 1024: 64 rows at (1024, 4) 42.6
+        // against 28.8 us).
+        const int kp2 = (int)pow2_ceil(Kp);
+        int slab_w = kSlabBuckets;
+        if (g_opt.slab_width >= kSlabBuckets && B % g_opt.slab_width == 0) {
+            slab_w = g_opt.slab_width;
+        } else {
+            while ((slab_w * kp2 < 128 || (slab_w * kp2 < 256 && B / slab_w > 32)) &&
+                   slab_w < 128 && B % (2 * slab_w) == 0)
+                slab_w *= 2;
+        }
+        int mr = m;
+        while (mr > 2 && slab_w * mr > (g_opt.slab_owners > 0 ? kMaxLanes : 256)) mr >>= 1;
+        const int run_len = slab_w * kp2;
+        const int64_t nruns = B / slab_w;
+        const size_t ws_runs = (size_t)rows * nruns * run_len * 8;
+        const bool ranked = g_opt.rank_finish != 0 && run_len <= 256 && slab_w * mr <= kMaxLanes &&
+                            pow2_ceil((int64_t)mr * KP) <= 16 * mr && nruns * run_len <= kRankMaxKeys &&
+                            rows * nruns <= 1024 && ws_runs <= ws_avail;
+        const bool few = rows <= 64 && (ranked || rows * (B / kSlabBuckets) <= 2048) && B >= 256 &&
                          !pl.var->packed() && (size_t)N * es >= kSlabMinRowBytes &&
                          (size_t)(N / B) * es <= 4096 && in_bytes <= kSlabMaxBytes;
-        if (m > 1 && v && v->V == 1 && v->R == 1 && ws <= ws_avail &&
+        if (m > 1 && v && v->V == 1 && v->R == 1 && (ws <= ws_avail || ranked) &&
             (g_opt.slab == 2 || few)) {
             pl.var = v;
             pl.rows_per_wg = 1;
             pl.grid = (int)rows;
             pl.aux_offset = 0;
-            auto shape = [&](int slab_w, int owners_) {
-                pl.slab_w = slab_w;
-                pl.G = pl.block = slab_w * owners_;
+            auto shape = [&](int slab_width, int owners_) {
+                pl.slab_w = slab_width;
+                pl.G = pl.block = slab_width * owners_;
                 pl.owners = owners_;
                 pl.S = owners_ * B;
                 pl.nsteps = (int)(N / pl.S);
                 pl.seg = pow2_ceil((int64_t)owners_ * KP);
-                pl.lds = (size_t)slab_w * pl.seg * 8;
+                pl.lds = (size_t)slab_width * pl.seg * 8;
             };
-            shape(kSlabBuckets, m);
-            pl.workspace = ws;
-            // Stage 2 spread over several workgroups per row: every slab's keys leave as a sorted
-            // run and the second launch places each key by counting the keys above it, which
-            // costs in proportion to the count of runs.  Slabs are therefore widened until a run
-            // has 128 keys, and 256 while there are more than 32 runs (K' = 2: 64 or 128 buckets,
-            // K' = 1: 128), with fewer lanes per bucket so that the workgroup keeps 256 lanes.
-            // Measured on 8 x 262144, K = 1024 (GPU time per call): 15.5 against 22.9 us at
-            // (1024, 4), 13.8 / 20.7 at (2048, 2), 16.2 / 23.0 at (4096, 2), 16.2 / 25.1 at
-            // (8192, 1), 23.0 / 36.1 at (512, 8).  The gain shrinks as rows are added (there are
-            // then enough single-workgroup finishes to fill the chip) and is gone where a
-            // workgroup would have to place the keys of more than two runs (1 to 64 rows of
-            // 2^16 to 2^20 elements, K = 64 to 1024: 64 rows at (1024, 4) 42.6 against 28.8 us).
-            const int kp2 = (int)pow2_ceil(Kp);
-            int slab_w = kSlabBuckets;
-            if (g_opt.slab_width >= kSlabBuckets && B % g_opt.slab_width == 0) {
-                slab_w = g_opt.slab_width;
-            } else {
-                while ((slab_w * kp2 < 128 || (slab_w * kp2 < 256 && B / slab_w > 32)) &&
-                       slab_w < 128 && B % (2 * slab_w) == 0)
-                    slab_w *= 2;
-            }
-            int mr = m;
-            while (mr > 2 && slab_w * mr > (g_opt.slab_owners > 0 ? kMaxLanes : 256)) mr >>= 1;
-            const int run_len = slab_w * kp2;
-            const int64_t nruns = B / slab_w;
-            const size_t ws_runs = (size_t)rows * nruns * run_len * 8;
-            if (g_opt.rank_finish != 0 && run_len <= 256 && slab_w * mr <= kMaxLanes &&
-                pow2_ceil((int64_t)mr * KP) <= 16 * mr &&
-                nruns * run_len <= kRankMaxKeys && rows * nruns <= 1024 && ws_runs <= ws_avail) {
+            if (ranked) {
                 shape(slab_w, mr);
                 pl.run_len = run_len;
-                pl.rank_runs_per_wg = 1;
-                while (pl.rank_runs_per_wg < nruns &&
-                       rows * ((nruns + pl.rank_runs_per_wg - 1) / pl.rank_runs_per_wg) > 512)
-                    pl.rank_runs_per_wg <<= 1;
+                pl.rank_runs_per_wg = rows * nruns <= 512 ? 1 : 2;
                 pl.lds += (size_t)run_len * 8;
                 pl.workspace = ws_runs;
+            } else {
+                shape(kSlabBuckets, m);
+                pl.workspace = ws;
             }
             return pl;
         }
@@ -849,6 +849,12 @@ static int approx_impl(const void* values, int dtype, int64_t rows, int64_t N, i
             r.log_run = 0;
             while ((1 << r.log_run) < pl.run_len) ++r.log_run;
             r.runs_per_wg = pl.rank_runs_per_wg;
+            // heads of three times the share of K that falls to a run (the runs are near-random
+            // samples of the survivors: a run's count of keys above the bound stays below that)
+            const int q = (K + r.nruns - 1) / r.nruns;
+            r.log_head = 5;
+            while ((1 << r.log_head) < 3 * q && r.log_head < r.log_run) ++r.log_head;
+            if (q > pl.run_len || r.log_head > r.log_run) r.log_head = r.log_run;
             r.flip = flip;
             r.out_vals = out_vals; r.out_idx = out_idx;
             e = launch_rank_finish(r, dtype, st);

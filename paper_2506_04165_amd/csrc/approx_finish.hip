@@ -104,27 +104,39 @@ __global__ void __launch_bounds__(kRankThreads) rank_finish_kernel(RankFinishPar
     lds_ptr<uint64_t> keys = (lds_ptr<uint64_t>)rk_lds;
     lds_ptr<uint32_t> rank = (lds_ptr<uint32_t>)(rk_lds + C);           // one word per key of mine
     lds_ptr<uint64_t> red = (lds_ptr<uint64_t>)(rk_lds + C) + ((p.runs_per_wg << p.log_run) + 1) / 2;
-    {
-        // eight 16-byte loads per thread are asked for before the first is stored (positions
-        // clamped instead of tested: a load under a test ends in a wait of its own)
+    lds_ptr<uint32_t> most_word = (lds_ptr<uint32_t>)(red + 4), open_word = most_word + 1;
+    // Copy of keys [from, to) of every run (from, to: multiples of two), LDS laid out like memory.
+    // Eight 16-byte loads per thread are asked for before the first is stored (positions clamped
+    // instead of tested: a load under a test ends in a wait of its own).
+    auto fetch = [&](int from, int log_count) {
         typedef uint64_t u64x2 __attribute__((ext_vector_type(2)));
         const u64x2* src = (const u64x2*)(p.runs + (size_t)row * C);
         lds_ptr<u64x2> dst = (lds_ptr<u64x2>)rk_lds;
-        const int nvec = C / 2;
+        const int per_run = 1 << (log_count - 1), nvec = p.nruns << (log_count - 1);
         for (int base = tid; base < nvec; base += 8 * kRankThreads) {
             u64x2 v[8];
+            int at[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = src[min(base + u * kRankThreads, nvec - 1)];
+            for (int u = 0; u < 8; ++u) {
+                const int i = min(base + u * kRankThreads, nvec - 1);
+                at[u] = ((i >> (log_count - 1)) << (p.log_run - 1)) + (from >> 1) + (i & (per_run - 1));
+                v[u] = src[at[u]];
+            }
 #pragma unroll
             for (int u = 0; u < 8; ++u)
-                if (base + u * kRankThreads < nvec) dst[base + u * kRankThreads] = v[u];
+                if (base + u * kRankThreads < nvec) dst[at[u]] = v[u];
         }
-    }
+    };
+    // The head of every run first: the keys that can reach the result are the first ones of
+    // their runs, and with K well below the count of keys the heads hold them all.
+    const int H = 1 << p.log_head;
+    fetch(0, p.log_head);
     const int first = (int)blockIdx.x * p.runs_per_wg;
-    const int mine = min(p.runs_per_wg, p.nruns - first) << p.log_run;  // keys of this workgroup
-    for (int i = tid; i < mine; i += kRankThreads) rank[i] = 0;
+    const int myruns = min(p.runs_per_wg, p.nruns - first);
+    for (int i = tid; i < (myruns << p.log_run); i += kRankThreads) rank[i] = 0;
+    if (tid == 0) { *most_word = 1; *open_word = 0; }
     __syncthreads();
-    // lower bound of the K-th key
+    // lower bound of the K-th key (q <= H by the host's choice of H, or q > L)
     uint64_t bound = 0;
     const int q = (p.K + p.nruns - 1) / p.nruns;
     if (q <= L) {
@@ -139,6 +151,20 @@ __global__ void __launch_bounds__(kRankThreads) rank_finish_kernel(RankFinishPar
         __syncthreads();
         bound = min(min(red[0], red[1]), min(red[2], red[3]));
     }
+    // Does some run have keys at or above the bound beyond its head?  Then (rarely: the bound is
+    // loose, or the keys are far from evenly spread over the runs) the rest is fetched as well.
+    int log_len = p.log_head;                    // length of the run prefixes that are searched
+    if (H < L) {
+        bool open = false;
+        for (int r = tid; r < p.nruns; r += kRankThreads) open |= bound == 0 || keys[(r << p.log_run) + H - 1] >= bound;
+        if (open) *open_word = 1;
+        __syncthreads();
+        if (*open_word) {
+            for (int from = H; from < L; from += H) fetch(from, p.log_head);
+            log_len = p.log_run;
+            __syncthreads();
+        }
+    }
     // Work items: (key of mine, part of the runs).  Keys at or above the bound are the first
     // ones of each run; a run's count of them comes from the same binary search.
     // Consecutive threads take consecutive keys of a run: their searches in another run visit
@@ -148,17 +174,14 @@ __global__ void __launch_bounds__(kRankThreads) rank_finish_kernel(RankFinishPar
     if (bound == 0) {
         slots = L;
     } else {
-        lds_ptr<uint32_t> most_word = (lds_ptr<uint32_t>)(red + 4);
-        if (tid == 0) *most_word = 1;
-        __syncthreads();
-        if (tid < (mine >> p.log_run))
+        if (tid < myruns)
             atomicMax((uint32_t*)most_word,
-                      (uint32_t)count_greater(keys + ((first + tid) << p.log_run), p.log_run, bound - 1));
+                      (uint32_t)count_greater(keys + ((first + tid) << p.log_run), log_len, bound - 1));
         __syncthreads();
         const int most = (int)*most_word;
         while (slots < most) slots <<= 1;
     }
-    const int myruns = mine >> p.log_run;
+    const int Ls = 1 << log_len;
     const int items = slots * myruns;                     // (run of mine, position < slots)
     const int parts = items >= kRankThreads ? 1 : kRankThreads / items;      // threads sharing a key
     const int part = items >= kRankThreads ? 0 : tid / items;
@@ -173,14 +196,14 @@ __global__ void __launch_bounds__(kRankThreads) rank_finish_kernel(RankFinishPar
             int p0 = 0, p1 = 0, p2 = 0, p3 = 0;
             const lds_ptr<const uint64_t> r0 = keys + (o << p.log_run), r1 = keys + ((o + parts) << p.log_run),
                                           r2 = keys + ((o + 2 * parts) << p.log_run), r3 = keys + ((o + 3 * parts) << p.log_run);
-            for (int s = L >> 1; s >= 1; s >>= 1) {
+            for (int s = Ls >> 1; s >= 1; s >>= 1) {
                 const uint64_t a0 = r0[p0 + s - 1], a1 = r1[p1 + s - 1], a2 = r2[p2 + s - 1], a3 = r3[p3 + s - 1];
                 p0 += a0 > x ? s : 0; p1 += a1 > x ? s : 0; p2 += a2 > x ? s : 0; p3 += a3 > x ? s : 0;
             }
             const uint64_t a0 = r0[p0], a1 = r1[p1], a2 = r2[p2], a3 = r3[p3];
             above += p0 + p1 + p2 + p3 + (a0 > x ? 1 : 0) + (a1 > x ? 1 : 0) + (a2 > x ? 1 : 0) + (a3 > x ? 1 : 0);
         }
-        for (; o < p.nruns; o += parts) above += count_greater(keys + (o << p.log_run), p.log_run, x);
+        for (; o < p.nruns; o += parts) above += count_greater(keys + (o << p.log_run), log_len, x);
         if (parts == 1) rank[(r << p.log_run) + pos] = (uint32_t)above;
         else atomicAdd((uint32_t*)&rank[(r << p.log_run) + pos], (uint32_t)above);
     }

@@ -403,21 +403,27 @@ def test_slab_path_very_few_rows(atk, knobs):
                 x = torch.randint(-1000, 1000, (rows, N), generator=g, dtype=torch.int32)   # dense ties
             else:
                 x = workloads.gaussian(rows, N, seed=17, dtype=dtype)
-            for B, Kp in [(1024, 4), (4096, 2), (8192, 1), (1024, 6), (1024, 16)]:
+            for B, Kp in [(1024, 4), (4096, 2), (8192, 1), (1024, 6), (1024, 16), (16384, 1)]:
                 st, text = atk.describe_plan(dtype, rows, N, 1024, Kp, B)
                 assert st == atk.OK
-                # chosen while the launch stays within 2048 workgroups
-                slab = rows * (B // 32) <= 2048
+                # chosen while the launch stays within 2048 workgroups (slabs of 32 buckets; short
+                # lists are given wider slabs), rows of 16-bit elements: from 128 KB on
+                # and buckets of at least eight elements (two lanes per bucket, four steps each)
+                slab = N // B >= 8 and (rows * (B // 32) <= 2048 or
+                                        (Kp == 1 and rows * (B // 128) <= 1024 and N * x.element_size() >= 131072))
                 assert text.startswith("slab") == slab, text
                 # stage 2 spread over several workgroups per row (every key placed by its rank
                 # among the sorted runs the slabs leave) up to 8192 keys per row and lists of 8
                 assert ("rank_finish" in text) == (slab and Kp <= 8), text
+                if "rank_finish" not in text and not text.startswith("slab"):
+                    continue            # (checked by the tests of those routes)
                 check_approx(atk, x, 1024, Kp, B)
                 if "rank_finish" in text:
                     # ... and in one workgroup per row
                     knobs.set("rank_finish", 0)
                     st, text = atk.describe_plan(dtype, rows, N, 1024, Kp, B)
-                    assert text.startswith("slab") and "rank_finish" not in text, text
+                    assert text.startswith("slab") == (rows * (B // 32) <= 2048 and N // B >= 8), text
+                    assert "rank_finish" not in text, text
                     check_approx(atk, x, 1024, Kp, B)
                     knobs.set("rank_finish", -1)
     z = workloads.heavy_ties(8, 262144, seed=16, symbols=3)
@@ -428,6 +434,18 @@ def test_slab_path_very_few_rows(atk, knobs):
     for K in (4, 33, 2048, 4096):
         check_approx(atk, y, K, 4, 1024)
     check_approx(atk, y, 1, 1, 8192)
+    # the greatest values all in the buckets of one slab (and of two): that slab's sorted run
+    # holds the whole result, far beyond the head of the run that the placing launch fetches first
+    for B, Kp, width in [(1024, 4, 32), (4096, 2, 128), (8192, 1, 128), (8192, 2, 128)]:
+        w = workloads.gaussian(4, 262144, seed=22)
+        n = torch.arange(262144)
+        for r, b0 in enumerate((0, width, B - width, 5 * width)):
+            inside = (n % B >= b0) & (n % B < b0 + width)
+            if r == 3:
+                inside |= (n % B >= B - 2 * width) & (n % B < B - width)
+            w[r, inside] += 100.0
+        check_approx(atk, w, 1024, Kp, B)
+        check_approx(atk, w, 200, Kp, B)
     # asked for where the planner would not choose it: few buckets, bucket counts that are only
     # a multiple of 32, rows that one lane per bucket would cover in a handful of steps
     knobs.set("slab", 2)
