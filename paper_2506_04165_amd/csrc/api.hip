@@ -103,6 +103,7 @@ static void* scratch_on_current_device(hipError_t* err) {
 
 static int pow2_ceil(int64_t x) { int p = 1; while (p < x) p <<= 1; return p; }
 static int pow2_floor(int64_t x) { int p = 1; while ((int64_t)p * 2 <= x) p <<= 1; return p; }
+static int log2_of(int64_t pow2) { int l = 0; while (((int64_t)1 << l) < pow2) ++l; return l; }
 static int ilog2(int x) { int l = 0; while ((1 << l) < x) ++l; return l; }
 static bool is_pow2(int64_t x) { return x > 0 && (x & (x - 1)) == 0; }
 static int elem_size(int dtype) { return (dtype == ATK_BF16 || dtype == ATK_F16) ? 2 : 4; }
@@ -216,6 +217,19 @@ struct Plan {
     int run_len = 0;            // slab route, > 0: a slab's final keys leave as one sorted run of this length and
     int rank_runs_per_wg = 0;   // stage 2 is the ranking finish, a workgroup placing the keys of this many runs
 };
+
+// Ranking finish: how much of every sorted run is held in LDS, as a power of two.  With q =
+// ceil(K / runs) the bound on the K-th key is the least of the runs' q-th keys; a run (a
+// near-random sample of the survivors) then has about q + 3 sqrt(q) + 3 keys above the bound,
+// and four standard deviations more cover the run that has the most.
+static int rank_log_head(int K, int64_t nruns, int log_run) {
+    const int64_t q = (K + nruns - 1) / nruns;
+    if (q > ((int64_t)1 << log_run)) return log_run;
+    const double mu = (double)q + 3.0 * std::sqrt((double)q) + 3.0, need = mu + 4.0 * std::sqrt(mu);
+    int lh = 5;
+    while (lh < log_run && (((int64_t)1 << lh) < need || ((int64_t)1 << lh) < q)) ++lh;
+    return lh;
+}
 
 static int list_len_for(int Kp) {
     static const int lens[] = {1, 2, 3, 4, 6, 8, 16, 32};
@@ -446,7 +460,7 @@ static Plan compute_plan(const void* values, int dtype, int64_t rows, int64_t N,
         const int64_t nruns = B / slab_w;
         const size_t ws_runs = (size_t)rows * nruns * run_len * 8;
         const bool ranked = g_opt.rank_finish != 0 && run_len <= 256 && slab_w * mr <= kMaxLanes &&
-                            pow2_ceil((int64_t)mr * KP) <= 16 * mr && nruns * run_len <= kRankMaxKeys &&
+                            pow2_ceil((int64_t)mr * KP) <= 16 * mr && (nruns << rank_log_head(K, nruns, log2_of(run_len))) <= kRankMaxHeadKeys &&
                             rows * nruns <= 1024 && ws_runs <= ws_avail;
         const bool few = rows <= 64 && (ranked || rows * (B / kSlabBuckets) <= 2048) && B >= 256 &&
                          !pl.var->packed() && (size_t)N * es >= kSlabMinRowBytes &&
@@ -846,15 +860,9 @@ static int approx_impl(const void* values, int dtype, int64_t rows, int64_t N, i
             RankFinishParams r{};
             r.runs = (const uint64_t*)workspace; r.values = values; r.row_stride = row_stride;
             r.rows = (int)rows; r.K = K; r.nruns = B / pl.slab_w;
-            r.log_run = 0;
-            while ((1 << r.log_run) < pl.run_len) ++r.log_run;
+            r.log_run = log2_of(pl.run_len);
             r.runs_per_wg = pl.rank_runs_per_wg;
-            // heads of three times the share of K that falls to a run (the runs are near-random
-            // samples of the survivors: a run's count of keys above the bound stays below that)
-            const int q = (K + r.nruns - 1) / r.nruns;
-            r.log_head = 5;
-            while ((1 << r.log_head) < 3 * q && r.log_head < r.log_run) ++r.log_head;
-            if (q > pl.run_len || r.log_head > r.log_run) r.log_head = r.log_run;
+            r.log_head = rank_log_head(K, r.nruns, r.log_run);
             r.flip = flip;
             r.out_vals = out_vals; r.out_idx = out_idx;
             e = launch_rank_finish(r, dtype, st);

@@ -31,15 +31,14 @@ struct RankFinishParams {
     const void* values;          // the input, only read to tell -0.0 from +0.0
     int64_t row_stride;
     int rows, K, nruns, log_run;
-    int log_head;                // the first 1 << log_head keys of every run are fetched at once, the rest only
-                                 // when needed; 2 <= 1 << log_head <= run length, and >= ceil(K / nruns) when
-                                 // that is at most the run length
+    int log_head;                // the first H = 1 << log_head keys of every run are held in LDS; H <= run length,
+                                 // H >= ceil(K / nruns) when that is at most the run length, H >= 2
     int runs_per_wg;             // runs whose keys one workgroup ranks (grid: ceil(nruns / runs_per_wg) x rows)
     uint32_t flip;
     void* out_vals;
     int32_t* out_idx;
 };
-constexpr int kRankMaxKeys = 16384;    // keys of a row (nruns << log_run) that the kernel holds in LDS
+constexpr int kRankMaxHeadKeys = 12288;  // keys of a row's run heads (nruns << log_head) that the kernel holds in LDS
 hipError_t launch_rank_finish(const RankFinishParams& p, int dtype, hipStream_t stream);
 
 }  // namespace atk

@@ -80,16 +80,21 @@ __global__ void __launch_bounds__(1024) approx_finish_kernel(FinishParams p) {
 }
 
 // Stage 2 by ranking, spread over several workgroups per row (few rows: the streaming launch
-// left the survivors of every row as sorted runs of equal length, one per slab of buckets).
-// Keys are distinct, so the place of a key in the result is the number of keys above it: its
-// place in its own run plus, per other run, the count of greater keys there (a binary search).
-// Every workgroup copies all runs of its row to LDS, ranks the keys of its own runs and writes
-// those whose rank is below K to that place of the output; nothing is sorted or selected.
-// Keys that cannot reach the result are left out first: with q = ceil(K / runs), the least of
-// the runs' q-th keys has at least K keys at or above it, so it bounds the K-th key from below.
+// left the survivors of every row as sorted runs of equal length).  Keys are distinct, so the
+// place of a key in the result is the number of keys above it: its place in its own run plus,
+// per other run, the count of greater keys there (a binary search).  Every workgroup ranks the
+// keys of its own runs and writes those whose rank is below K to that place of the output;
+// nothing is sorted or selected.
+// Only the head of every run (its first H keys) is copied to LDS.  With q = ceil(K / runs), the
+// least of the runs' q-th keys has at least K keys at or above it, so it bounds the K-th key
+// from below; keys under the bound are left out, and when every run's H-th key is under it
+// (H is chosen for that: the runs are near-random samples of the survivors) the heads hold all
+// that matters.  Otherwise -- the bound is loose because the greatest keys sit in few runs --
+// the same searches run on the whole runs in memory: slow, correct, rare.
 constexpr int kRankThreads = 256;
 
-__device__ __forceinline__ int count_greater(const lds_ptr<const uint64_t> run, int log_len, uint64_t x) {
+template <typename Ptr>
+__device__ __forceinline__ int count_greater(Ptr run, int log_len, uint64_t x) {
     int pos = 0;
     for (int s = 1 << (log_len - 1); s >= 1; s >>= 1) pos += run[pos + s - 1] > x ? s : 0;
     return pos + (run[pos] > x ? 1 : 0);
@@ -100,48 +105,43 @@ __global__ void __launch_bounds__(kRankThreads) rank_finish_kernel(RankFinishPar
     extern __shared__ uint64_t rk_lds[];
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
     const int row = blockIdx.y;
-    const int L = 1 << p.log_run, C = p.nruns << p.log_run;
-    lds_ptr<uint64_t> keys = (lds_ptr<uint64_t>)rk_lds;
-    lds_ptr<uint32_t> rank = (lds_ptr<uint32_t>)(rk_lds + C);           // one word per key of mine
-    lds_ptr<uint64_t> red = (lds_ptr<uint64_t>)(rk_lds + C) + ((p.runs_per_wg << p.log_run) + 1) / 2;
+    const int L = 1 << p.log_run, H = 1 << p.log_head;
+    const uint64_t* runs = p.runs + ((size_t)row * p.nruns << p.log_run);
+    lds_ptr<uint64_t> heads = (lds_ptr<uint64_t>)rk_lds;                 // [nruns][H]
+    lds_ptr<uint32_t> rank = (lds_ptr<uint32_t>)(rk_lds + ((size_t)p.nruns << p.log_head));   // [my runs][L]
+    lds_ptr<uint64_t> red = (lds_ptr<uint64_t>)(rk_lds + ((size_t)p.nruns << p.log_head)) +
+                            ((p.runs_per_wg << p.log_run) + 1) / 2;
     lds_ptr<uint32_t> most_word = (lds_ptr<uint32_t>)(red + 4), open_word = most_word + 1;
-    // Copy of keys [from, to) of every run (from, to: multiples of two), LDS laid out like memory.
-    // Eight 16-byte loads per thread are asked for before the first is stored (positions clamped
-    // instead of tested: a load under a test ends in a wait of its own).
-    auto fetch = [&](int from, int log_count) {
+    {
+        // eight 16-byte loads per thread are asked for before the first is stored (positions
+        // clamped instead of tested: a load under a test ends in a wait of its own)
         typedef uint64_t u64x2 __attribute__((ext_vector_type(2)));
-        const u64x2* src = (const u64x2*)(p.runs + (size_t)row * C);
+        const u64x2* src = (const u64x2*)runs;
         lds_ptr<u64x2> dst = (lds_ptr<u64x2>)rk_lds;
-        const int per_run = 1 << (log_count - 1), nvec = p.nruns << (log_count - 1);
+        const int nvec = p.nruns << (p.log_head - 1);
         for (int base = tid; base < nvec; base += 8 * kRankThreads) {
             u64x2 v[8];
-            int at[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const int i = min(base + u * kRankThreads, nvec - 1);
-                at[u] = ((i >> (log_count - 1)) << (p.log_run - 1)) + (from >> 1) + (i & (per_run - 1));
-                v[u] = src[at[u]];
+                v[u] = src[((i >> (p.log_head - 1)) << (p.log_run - 1)) + (i & ((H >> 1) - 1))];
             }
 #pragma unroll
             for (int u = 0; u < 8; ++u)
-                if (base + u * kRankThreads < nvec) dst[at[u]] = v[u];
+                if (base + u * kRankThreads < nvec) dst[base + u * kRankThreads] = v[u];
         }
-    };
-    // The head of every run first: the keys that can reach the result are the first ones of
-    // their runs, and with K well below the count of keys the heads hold them all.
-    const int H = 1 << p.log_head;
-    fetch(0, p.log_head);
+    }
     const int first = (int)blockIdx.x * p.runs_per_wg;
     const int myruns = min(p.runs_per_wg, p.nruns - first);
     for (int i = tid; i < (myruns << p.log_run); i += kRankThreads) rank[i] = 0;
     if (tid == 0) { *most_word = 1; *open_word = 0; }
     __syncthreads();
-    // lower bound of the K-th key (q <= H by the host's choice of H, or q > L)
+    // lower bound of the K-th key (q <= H by the host's choice of H, or q > L = H)
     uint64_t bound = 0;
     const int q = (p.K + p.nruns - 1) / p.nruns;
-    if (q <= L) {
+    if (q <= H) {
         uint64_t least = ~0ull;
-        for (int r = tid; r < p.nruns; r += kRankThreads) least = min(least, keys[(r << p.log_run) + q - 1]);
+        for (int r = tid; r < p.nruns; r += kRankThreads) least = min(least, heads[(r << p.log_head) + q - 1]);
         for (int o = 32; o >= 1; o >>= 1) {
             const uint64_t other = ((uint64_t)__shfl_xor((unsigned)(least >> 32), o, kWave) << 32) |
                                    __shfl_xor((unsigned)least, o, kWave);
@@ -151,81 +151,83 @@ __global__ void __launch_bounds__(kRankThreads) rank_finish_kernel(RankFinishPar
         __syncthreads();
         bound = min(min(red[0], red[1]), min(red[2], red[3]));
     }
-    // Does some run have keys at or above the bound beyond its head?  Then (rarely: the bound is
-    // loose, or the keys are far from evenly spread over the runs) the rest is fetched as well.
-    int log_len = p.log_head;                    // length of the run prefixes that are searched
+    bool whole_runs = false;               // some run has keys at or above the bound beyond its head
     if (H < L) {
         bool open = false;
-        for (int r = tid; r < p.nruns; r += kRankThreads) open |= bound == 0 || keys[(r << p.log_run) + H - 1] >= bound;
+        for (int r = tid; r < p.nruns; r += kRankThreads)
+            open |= bound == 0 || heads[(r << p.log_head) + H - 1] >= bound;
         if (open) *open_word = 1;
         __syncthreads();
-        if (*open_word) {
-            for (int from = H; from < L; from += H) fetch(from, p.log_head);
-            log_len = p.log_run;
-            __syncthreads();
-        }
+        whole_runs = *open_word != 0;
     }
-    // Work items: (key of mine, part of the runs).  Keys at or above the bound are the first
-    // ones of each run; a run's count of them comes from the same binary search.
-    // Consecutive threads take consecutive keys of a run: their searches in another run visit
-    // mostly the same or neighbouring words.  Few keys: several threads share a key, each
-    // taking every parts-th run, and add their counts up in LDS.
-    int slots = 1;                      // power of two >= the greatest count of such keys over my runs
-    if (bound == 0) {
-        slots = L;
-    } else {
+    const char* rowp = (const char*)p.values + (size_t)row * p.row_stride * elem<DT>::size;
+
+    // Work items: (run of mine, position < slots).  Consecutive threads take consecutive keys of
+    // a run: their searches in another run visit mostly the same or neighbouring words.  Few
+    // items: several threads share a key, each taking every parts-th run, and add their counts
+    // up in LDS.  run_at(r): the keys of run r that are searched, 1 << log_len of them.
+    auto place_keys = [&](auto run_at, int log_len, int slots) {
+        const int Ls = 1 << log_len;
+        const int items = slots * myruns;
+        const int parts = items >= kRankThreads ? 1 : kRankThreads / items;
+        const int part = items >= kRankThreads ? 0 : tid / items;
+        for (int it = tid - part * items; it < items && part < parts; it += kRankThreads) {
+            const int r = it / slots, pos = it - r * slots;
+            const uint64_t x = run_at(first + r)[pos];
+            if (x == 0 || x < bound) continue;
+            int above = 0;
+            int o = part;
+            for (; o + 3 * parts < p.nruns; o += 4 * parts) {
+                // four searches side by side: their loads overlap
+                int p0 = 0, p1 = 0, p2 = 0, p3 = 0;
+                const auto r0 = run_at(o), r1 = run_at(o + parts), r2 = run_at(o + 2 * parts), r3 = run_at(o + 3 * parts);
+                for (int s = Ls >> 1; s >= 1; s >>= 1) {
+                    const uint64_t a0 = r0[p0 + s - 1], a1 = r1[p1 + s - 1], a2 = r2[p2 + s - 1], a3 = r3[p3 + s - 1];
+                    p0 += a0 > x ? s : 0; p1 += a1 > x ? s : 0; p2 += a2 > x ? s : 0; p3 += a3 > x ? s : 0;
+                }
+                const uint64_t a0 = r0[p0], a1 = r1[p1], a2 = r2[p2], a3 = r3[p3];
+                above += p0 + p1 + p2 + p3 + (a0 > x ? 1 : 0) + (a1 > x ? 1 : 0) + (a2 > x ? 1 : 0) + (a3 > x ? 1 : 0);
+            }
+            for (; o < p.nruns; o += parts) above += count_greater(run_at(o), log_len, x);
+            if (parts == 1) rank[(r << p.log_run) + pos] = (uint32_t)above;
+            else atomicAdd((uint32_t*)&rank[(r << p.log_run) + pos], (uint32_t)above);
+        }
+        __syncthreads();
+        for (int it = tid; it < items; it += kRankThreads) {
+            const int r = it / slots, pos = it - r * slots;
+            const uint64_t key = run_at(first + r)[pos];
+            const uint32_t place = rank[(r << p.log_run) + pos];
+            if (key != 0 && key >= bound && place < (uint32_t)p.K) {
+                const uint32_t n = key_index(key);
+                const int64_t o = (int64_t)row * p.K + place;
+                elem<DT>::store_bits(p.out_vals, o, key_stored_bits<DT>(key, rowp, n, p.flip));
+                p.out_idx[o] = (int32_t)n;
+            }
+        }
+    };
+    if (whole_runs) {
+        place_keys([&](int r) { return runs + ((size_t)r << p.log_run); }, p.log_run, L);
+        return;
+    }
+    // the keys at or above the bound are the first ones of each run; slots: a power of two >= the
+    // greatest count of them over my runs
+    int slots = H;
+    if (bound != 0) {
         if (tid < myruns)
             atomicMax((uint32_t*)most_word,
-                      (uint32_t)count_greater(keys + ((first + tid) << p.log_run), log_len, bound - 1));
+                      (uint32_t)count_greater(heads + ((first + tid) << p.log_head), p.log_head, bound - 1));
         __syncthreads();
         const int most = (int)*most_word;
+        slots = 1;
         while (slots < most) slots <<= 1;
     }
-    const int Ls = 1 << log_len;
-    const int items = slots * myruns;                     // (run of mine, position < slots)
-    const int parts = items >= kRankThreads ? 1 : kRankThreads / items;      // threads sharing a key
-    const int part = items >= kRankThreads ? 0 : tid / items;
-    for (int it = tid - part * items; it < items && part < parts; it += kRankThreads) {
-        const int r = it / slots, pos = it - r * slots;
-        const uint64_t x = keys[((first + r) << p.log_run) + pos];
-        if (x == 0 || x < bound) continue;
-        int above = 0;
-        int o = part;
-        for (; o + 3 * parts < p.nruns; o += 4 * parts) {
-            // four searches side by side: their loads overlap
-            int p0 = 0, p1 = 0, p2 = 0, p3 = 0;
-            const lds_ptr<const uint64_t> r0 = keys + (o << p.log_run), r1 = keys + ((o + parts) << p.log_run),
-                                          r2 = keys + ((o + 2 * parts) << p.log_run), r3 = keys + ((o + 3 * parts) << p.log_run);
-            for (int s = Ls >> 1; s >= 1; s >>= 1) {
-                const uint64_t a0 = r0[p0 + s - 1], a1 = r1[p1 + s - 1], a2 = r2[p2 + s - 1], a3 = r3[p3 + s - 1];
-                p0 += a0 > x ? s : 0; p1 += a1 > x ? s : 0; p2 += a2 > x ? s : 0; p3 += a3 > x ? s : 0;
-            }
-            const uint64_t a0 = r0[p0], a1 = r1[p1], a2 = r2[p2], a3 = r3[p3];
-            above += p0 + p1 + p2 + p3 + (a0 > x ? 1 : 0) + (a1 > x ? 1 : 0) + (a2 > x ? 1 : 0) + (a3 > x ? 1 : 0);
-        }
-        for (; o < p.nruns; o += parts) above += count_greater(keys + (o << p.log_run), log_len, x);
-        if (parts == 1) rank[(r << p.log_run) + pos] = (uint32_t)above;
-        else atomicAdd((uint32_t*)&rank[(r << p.log_run) + pos], (uint32_t)above);
-    }
-    __syncthreads();
-    const char* rowp = (const char*)p.values + (size_t)row * p.row_stride * elem<DT>::size;
-    for (int it = tid; it < items; it += kRankThreads) {
-        const int r = it / slots, pos = it - r * slots;
-        const uint64_t key = keys[((first + r) << p.log_run) + pos];
-        const uint32_t place = rank[(r << p.log_run) + pos];
-        if (key != 0 && key >= bound && place < (uint32_t)p.K) {
-            const uint32_t n = key_index(key);
-            const int64_t o = (int64_t)row * p.K + place;
-            elem<DT>::store_bits(p.out_vals, o, key_stored_bits<DT>(key, rowp, n, p.flip));
-            p.out_idx[o] = (int32_t)n;
-        }
-    }
+    place_keys([&](int r) { return (lds_ptr<const uint64_t>)(heads + (r << p.log_head)); }, p.log_head, slots);
 }
 
 template <typename DT>
 hipError_t launch_rank_for(const RankFinishParams& p, hipStream_t stream) {
-    const size_t C = (size_t)p.nruns << p.log_run, mine = (size_t)p.runs_per_wg << p.log_run;
-    const size_t lds = C * 8 + ((mine + 1) / 2) * 8 + 64;
+    const size_t heads = (size_t)p.nruns << p.log_head, mine = (size_t)p.runs_per_wg << p.log_run;
+    const size_t lds = heads * 8 + ((mine + 1) / 2) * 8 + 64;
     const dim3 grid((p.nruns + p.runs_per_wg - 1) / p.runs_per_wg, p.rows), block(kRankThreads);
     allow_large_lds((const void*)rank_finish_kernel<DT>, lds);
     hipLaunchKernelGGL((rank_finish_kernel<DT>), grid, block, lds, stream, p);
