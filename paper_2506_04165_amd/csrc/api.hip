@@ -129,6 +129,7 @@ struct Options {
     int segments = 0;         // > 0: force this many row segments on the split route
     int slab = 1;             // 0 never / 1 planner's choice / 2 whenever possible: slab route
     int rank_finish = 1;      // 0: stage 2 of the slab route is never spread over several workgroups per row
+    int rank_wgs = 2048;      // most workgroups of the ranking finish when survivors go through memory
     int slab_owners = 0;      // 0: planner's choice (8), else a power of two: most lanes that share a bucket on the slab route
     int slab_width = 0;       // 0: planner's choice, else buckets per workgroup on the slab route with the
                               // ranking finish (a power of two >= 32)
@@ -161,6 +162,7 @@ static void options_from_env_once() {
         o.slab = env("ATK_SLAB", o.slab);
         o.rank_finish = env("ATK_RANK_FINISH", o.rank_finish);
         o.slab_width = env("ATK_SLAB_WIDTH", o.slab_width);
+        o.rank_wgs = env("ATK_RANK_WGS", o.rank_wgs);
         o.slab_owners = env("ATK_SLAB_OWNERS", o.slab_owners);
         if (o.slab_owners < 0 || o.slab_owners > 32 || (o.slab_owners & (o.slab_owners - 1))) o.slab_owners = 0;
         o.packed = env("ATK_NO_PACKED", 0) ? 0 : 1;
@@ -412,8 +414,30 @@ static Plan compute_plan(const void* values, int dtype, int64_t rows, int64_t N,
         // survivors (or every chunk's K greatest) go through memory: int32 indices, then values
         // (input dtype); the exact kernel then selects among them
         pl.workspace = (size_t)rows * (chunk_fused ? (size_t)pl.nchunk * K : (size_t)B * Kp) * (es + 4);
-        if (K > kExactMaxK) { pl.status = ATK_UNSUPPORTED; return pl; }
         pl.fused = false;
+        // ... or, stage 2 by ranking: every wavefront's survivors leave as one sorted run of keys
+        // and the second launch places each key by counting the keys above it, many workgroups
+        // per row (64 x 2^20, K = 1024: 62 against 96 us at (8192, 4), 80 / 130 at (16384, 2)).
+        // What it costs grows with the count of runs, 64 to 1024 keys long.
+        const int per_lane = pow2_ceil((int64_t)NL * Kp);
+        const int64_t nruns = (int64_t)pl.nchunk * (G / 64);
+        if (!chunk_fused && g_opt.rank_finish != 0 && owners == 1 && G >= 64 && pl.var->rep != 2 &&
+            per_lane <= 16 && rows > 0) {
+            const int run_len = 64 * per_lane, log_head = rank_log_head(K, nruns, log2_of(run_len));
+            int per_wg = 1;
+            while (per_wg < nruns && rows * ((nruns + per_wg - 1) / per_wg) > g_opt.rank_wgs) per_wg <<= 1;
+            // LDS reads per thread of a placing workgroup, half of every head being in play
+            const int64_t reads = (int64_t)per_wg * ((int64_t)1 << log_head) / 2 * nruns * (log_head + 1) / 256;
+            const size_t ws_runs = (size_t)rows * nruns * run_len * 8;
+            if ((nruns << log_head) <= kRankMaxHeadKeys && reads <= 1024 && ws_runs <= ws_avail &&
+                (size_t)pl.block * per_lane * 8 <= kLdsBudget) {
+                pl.run_len = run_len;
+                pl.rank_runs_per_wg = per_wg;
+                pl.lds = (size_t)pl.block * per_lane * 8;
+                pl.workspace = ws_runs;
+            }
+        }
+        if (pl.run_len == 0 && K > kExactMaxK) { pl.status = ATK_UNSUPPORTED; return pl; }
     }
 
     // Very few rows: give every workgroup a slab of 32 buckets of one row over all steps, with m
@@ -909,6 +933,24 @@ static int approx_impl(const void* values, int dtype, int64_t rows, int64_t N, i
         if (e != hipSuccess) return hip_fail(e);
         return run_exact(part_vals, part_idx, dtype, rows, C, C, K, out_vals, out_idx, st, values, row_stride, flip);
     }
+    if (pl.run_len > 0) {
+        // unfused, stage 2 by ranking: sorted runs of keys through the workspace
+        p.mode = 4;
+        p.run_len = pl.run_len;
+        p.part_keys = (uint64_t*)workspace;
+        hipError_t e = pl.var->fn(p, pl.grid, pl.block, pl.lds, st);
+        if (e != hipSuccess) return hip_fail(e);
+        RankFinishParams r{};
+        r.runs = (const uint64_t*)workspace; r.values = values; r.row_stride = row_stride;
+        r.rows = (int)rows; r.K = K; r.nruns = pl.nchunk * (pl.G / 64);
+        r.log_run = log2_of(pl.run_len);
+        r.log_head = rank_log_head(K, r.nruns, r.log_run);
+        r.runs_per_wg = pl.rank_runs_per_wg;
+        r.flip = flip;
+        r.out_vals = out_vals; r.out_idx = out_idx;
+        e = launch_rank_finish(r, dtype, st);
+        return e == hipSuccess ? ATK_OK : hip_fail(e);
+    }
     // unfused: survivors [rows, K', B] through the workspace, then exact Top-K over them
     const int64_t C = (int64_t)B * Kprime;
     char* ws = (char*)workspace;
@@ -1182,7 +1224,7 @@ int atk_describe_plan(int dtype, int64_t rows, int64_t N, int K, int Kprime, int
     if (pl.run_len > 0) {
         // second launch: workgroups per row x keys each of them places
         const size_t n = std::strlen(buf);
-        const int nruns = B / pl.slab_w;
+        const int nruns = pl.slab_w > 0 ? B / pl.slab_w : pl.nchunk * (pl.G / 64);
         std::snprintf(buf + n, buflen - n, " rank_finish=%dx%d",
                       (nruns + pl.rank_runs_per_wg - 1) / pl.rank_runs_per_wg, pl.rank_runs_per_wg * pl.run_len);
     }
@@ -1196,7 +1238,7 @@ int atk_set_option(const char* name, int value) {
     struct Entry { const char* name; int Options::*field; };
     static const Entry entries[] = {
         {"lanes_per_row", &Options::lanes_per_row}, {"segments", &Options::segments},
-        {"slab", &Options::slab}, {"rank_finish", &Options::rank_finish}, {"slab_width", &Options::slab_width}, {"slab_owners", &Options::slab_owners}, {"packed", &Options::packed}, {"subwave", &Options::subwave},
+        {"slab", &Options::slab}, {"rank_finish", &Options::rank_finish}, {"slab_width", &Options::slab_width}, {"rank_wgs", &Options::rank_wgs}, {"slab_owners", &Options::slab_owners}, {"packed", &Options::packed}, {"subwave", &Options::subwave},
         {"batch_min_kp", &Options::batch_min_kp}, {"mips_segments", &Options::mips_segments},
         {"unfused", &Options::unfused}, {"onepass", &Options::onepass}, {"chunked", &Options::chunked},
         {"exact_threads", &Options::exact_threads}, {"certified", &Options::certified}, {"reg_rows", &Options::reg_rows},

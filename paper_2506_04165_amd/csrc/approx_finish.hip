@@ -111,7 +111,7 @@ __global__ void __launch_bounds__(kRankThreads) rank_finish_kernel(RankFinishPar
     lds_ptr<uint32_t> rank = (lds_ptr<uint32_t>)(rk_lds + ((size_t)p.nruns << p.log_head));   // [my runs][L]
     lds_ptr<uint64_t> red = (lds_ptr<uint64_t>)(rk_lds + ((size_t)p.nruns << p.log_head)) +
                             ((p.runs_per_wg << p.log_run) + 1) / 2;
-    lds_ptr<uint32_t> most_word = (lds_ptr<uint32_t>)(red + 4), open_word = most_word + 1;
+    lds_ptr<uint32_t> open_word = (lds_ptr<uint32_t>)(red + 4);
     {
         // eight 16-byte loads per thread are asked for before the first is stored (positions
         // clamped instead of tested: a load under a test ends in a wait of its own)
@@ -134,7 +134,7 @@ __global__ void __launch_bounds__(kRankThreads) rank_finish_kernel(RankFinishPar
     const int first = (int)blockIdx.x * p.runs_per_wg;
     const int myruns = min(p.runs_per_wg, p.nruns - first);
     for (int i = tid; i < (myruns << p.log_run); i += kRankThreads) rank[i] = 0;
-    if (tid == 0) { *most_word = 1; *open_word = 0; }
+    if (tid == 0) *open_word = 0;
     __syncthreads();
     // lower bound of the K-th key (q <= H by the host's choice of H, or q > L = H)
     uint64_t bound = 0;
@@ -162,19 +162,30 @@ __global__ void __launch_bounds__(kRankThreads) rank_finish_kernel(RankFinishPar
     }
     const char* rowp = (const char*)p.values + (size_t)row * p.row_stride * elem<DT>::size;
 
-    // Work items: (run of mine, position < slots).  Consecutive threads take consecutive keys of
-    // a run: their searches in another run visit mostly the same or neighbouring words.  Few
+    // Work items: the keys of my runs at or above the bound, cnt[r] at the head of run r (a binary
+    // search per run), numbered run after run.  Consecutive threads take consecutive keys of a
+    // run: their searches in another run visit mostly the same or neighbouring words.  Few
     // items: several threads share a key, each taking every parts-th run, and add their counts
     // up in LDS.  run_at(r): the keys of run r that are searched, 1 << log_len of them.
-    auto place_keys = [&](auto run_at, int log_len, int slots) {
+    lds_ptr<uint32_t> cnt = open_word + 1;                  // [my runs], then their total
+    auto place_keys = [&](auto run_at, int log_len) {
         const int Ls = 1 << log_len;
-        const int items = slots * myruns;
-        const int parts = items >= kRankThreads ? 1 : kRankThreads / items;
-        const int part = items >= kRankThreads ? 0 : tid / items;
+        if (tid < myruns)
+            cnt[tid] = bound == 0 ? (uint32_t)Ls : (uint32_t)count_greater(run_at(first + tid), log_len, bound - 1);
+        __syncthreads();
+        int items = 0;
+        for (int r = 0; r < myruns; ++r) items += (int)cnt[r];
+        const int parts = items >= kRankThreads ? 1 : kRankThreads / max(items, 1);
+        const int part = items >= kRankThreads ? 0 : tid / max(items, 1);
+        auto locate = [&](int it, int& r, int& pos) {       // item -> (run of mine, position)
+            r = 0; pos = it;
+            while (pos >= (int)cnt[r]) { pos -= (int)cnt[r]; ++r; }
+        };
         for (int it = tid - part * items; it < items && part < parts; it += kRankThreads) {
-            const int r = it / slots, pos = it - r * slots;
+            int r, pos;
+            locate(it, r, pos);
             const uint64_t x = run_at(first + r)[pos];
-            if (x == 0 || x < bound) continue;
+            if (x == 0) continue;
             int above = 0;
             int o = part;
             for (; o + 3 * parts < p.nruns; o += 4 * parts) {
@@ -194,10 +205,11 @@ __global__ void __launch_bounds__(kRankThreads) rank_finish_kernel(RankFinishPar
         }
         __syncthreads();
         for (int it = tid; it < items; it += kRankThreads) {
-            const int r = it / slots, pos = it - r * slots;
+            int r, pos;
+            locate(it, r, pos);
             const uint64_t key = run_at(first + r)[pos];
             const uint32_t place = rank[(r << p.log_run) + pos];
-            if (key != 0 && key >= bound && place < (uint32_t)p.K) {
+            if (key != 0 && place < (uint32_t)p.K) {
                 const uint32_t n = key_index(key);
                 const int64_t o = (int64_t)row * p.K + place;
                 elem<DT>::store_bits(p.out_vals, o, key_stored_bits<DT>(key, rowp, n, p.flip));
@@ -205,29 +217,16 @@ __global__ void __launch_bounds__(kRankThreads) rank_finish_kernel(RankFinishPar
             }
         }
     };
-    if (whole_runs) {
-        place_keys([&](int r) { return runs + ((size_t)r << p.log_run); }, p.log_run, L);
-        return;
-    }
-    // the keys at or above the bound are the first ones of each run; slots: a power of two >= the
-    // greatest count of them over my runs
-    int slots = H;
-    if (bound != 0) {
-        if (tid < myruns)
-            atomicMax((uint32_t*)most_word,
-                      (uint32_t)count_greater(heads + ((first + tid) << p.log_head), p.log_head, bound - 1));
-        __syncthreads();
-        const int most = (int)*most_word;
-        slots = 1;
-        while (slots < most) slots <<= 1;
-    }
-    place_keys([&](int r) { return (lds_ptr<const uint64_t>)(heads + (r << p.log_head)); }, p.log_head, slots);
+    if (whole_runs)
+        place_keys([&](int r) { return runs + ((size_t)r << p.log_run); }, p.log_run);
+    else
+        place_keys([&](int r) { return (lds_ptr<const uint64_t>)(heads + (r << p.log_head)); }, p.log_head);
 }
 
 template <typename DT>
 hipError_t launch_rank_for(const RankFinishParams& p, hipStream_t stream) {
     const size_t heads = (size_t)p.nruns << p.log_head, mine = (size_t)p.runs_per_wg << p.log_run;
-    const size_t lds = heads * 8 + ((mine + 1) / 2) * 8 + 64;
+    const size_t lds = heads * 8 + ((mine + 1) / 2) * 8 + 64 + ((size_t)p.runs_per_wg * 4 + 7) / 8 * 8;
     const dim3 grid((p.nruns + p.runs_per_wg - 1) / p.runs_per_wg, p.rows), block(kRankThreads);
     allow_large_lds((const void*)rank_finish_kernel<DT>, lds);
     hipLaunchKernelGGL((rank_finish_kernel<DT>), grid, block, lds, stream, p);

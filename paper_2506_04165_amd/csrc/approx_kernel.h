@@ -42,6 +42,9 @@ struct ApproxParams {
                           // 2: this workgroup covers one segment of its row, write partial keys;
                           // 3: this workgroup covers slab_w buckets of its row over all steps
                           //    (owners lanes per bucket), write their final K' keys
+                          // 4: like 1 (one owner per bucket, G >= 64), but the survivors of every
+                          //    wavefront leave as one sorted run of run_len keys, part_keys being
+                          //    [rows, gridDim.y * G / 64, run_len]
     int tail;             // mode 0, how stage 2 runs: 0 generic LDS sort of every row of the
                           // workgroup; 1 at most 1024 candidates per row, sorted in registers by
                           // the first wavefront of the row's group; 2 one row per workgroup,
@@ -521,6 +524,31 @@ struct ApproxKernel {
 
         // ---- survivors -> LDS keys (or straight to memory for one-owner mode 1) ---------------
         uint64_t* cand = lds + (size_t)g * p.Cpad;                    // per-row stage-2 segment
+        if (p.mode == 4) {
+            // survivors through memory, ranking finish: the survivors of every wavefront leave as
+            // one sorted run (its lanes' final list entries, a power of two per lane, zeros where
+            // there are none), staged in the wavefront's own piece of LDS
+            const int lane = tid & (kWave - 1), per_lane = p.run_len / kWave;
+            uint64_t* stage = lds + (size_t)(tid >> 6) * p.run_len;
+            for (int sl = NL * p.Kprime; sl < per_lane; ++sl) stage[sl * kWave + lane] = 0;
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int v = 0; v < V; ++v)
+#pragma unroll
+                    for (int k = 0; k < KP; ++k) {
+                        if (k >= p.Kprime) continue;
+                        const int l = r * V + v;
+                        const uint32_t n = L.index(l, k, (uint32_t)p.S, (uint32_t)(off[r] + v));
+                        stage[(l * p.Kprime + k) * kWave + lane] =
+                            slot_ok[r] && row_ok ? make_key<DT>(stored_bits(L, l, k), n) : 0;
+                    }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            if (row_ok)
+                wave_sort_run_dispatch(stage, p.run_len, p.part_keys +
+                    (((int64_t)row * gridDim.y + blockIdx.y) * (p.G >> 6) + (t >> 6)) * p.run_len);
+            return;
+        }
         if (p.owners == 1) {
             if (p.mode == 0) {
                 for (int i = C + t; i < p.Cpad; i += p.G) cand[i] = 0;

@@ -322,16 +322,16 @@ __device__ __noinline__ bool wave_merge_bucket_lists_dispatch(const uint64_t* ke
     }
 }
 
-// Slab route with the ranking finish: one wavefront sorts the n (<= 256) keys at `keys` (LDS: the
-// final lists of a workgroup's buckets, zeros where a list is padded) and writes them to
-// out[0, n) in rank order, the greatest first.
+// Routes with the ranking finish: one wavefront sorts the n = 64*R keys at `keys` (LDS: final
+// list entries, zeros where there are none) and writes them to out[0, n) in rank order, the
+// greatest first.  (n = 32: the upper half of the wavefront holds zeros.)
 template <int R>
 __device__ __forceinline__ void wave_sort_run(const uint64_t* keys_generic, int n, uint64_t* out) {
     const lds_ptr<const uint64_t> keys = (lds_ptr<const uint64_t>)keys_generic;
     const int lane = __lane_id();
     uint64_t k[R];
 #pragma unroll
-    for (int j = 0; j < R; ++j) k[j] = lane * R + j < n ? keys[lane * R + j] : 0;
+    for (int j = 0; j < R; ++j) k[j] = j * kWave + lane < n ? keys[j * kWave + lane] : 0;   // (any assignment will do)
     WaveSort<R>::sort(k);
 #pragma unroll
     for (int j = 0; j < R; ++j)
@@ -340,7 +340,9 @@ __device__ __forceinline__ void wave_sort_run(const uint64_t* keys_generic, int 
 __device__ __noinline__ void wave_sort_run_dispatch(const uint64_t* keys, int n, uint64_t* out) {
     if (n <= 64)       wave_sort_run<1>(keys, n, out);
     else if (n <= 128) wave_sort_run<2>(keys, n, out);
-    else               wave_sort_run<4>(keys, n, out);
+    else if (n <= 256) wave_sort_run<4>(keys, n, out);
+    else if (n <= 512) wave_sort_run<8>(keys, n, out);
+    else               wave_sort_run<16>(keys, n, out);
 }
 
 // Walk a finished histogram from the top bin down.  On return (all threads):

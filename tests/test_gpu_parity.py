@@ -308,6 +308,48 @@ def test_large_bucket_counts_unfused_in_bucket_chunks(atk, rows, N, K, Kp, B, dt
     check_stage1(atk, x, Kp, B)
 
 
+def test_unfused_route_with_the_ranking_finish(atk, knobs):
+    # survivors beyond LDS whose lanes hold 8 or 16 list entries: every wavefront's survivors
+    # leave as one sorted run of 512 or 1024 keys and the second launch places every key by
+    # counting the keys above it (many workgroups per row); without the option the survivors
+    # leave as values and positions and the exact kernel selects among them
+    cases = [(workloads.gaussian(6, 1 << 20, seed=51), 1024, 4, 8192),
+             (workloads.gaussian(5, 262144, seed=52, dtype=torch.bfloat16), 1024, 2, 16384),
+             (workloads.gaussian(4, 131072, seed=53), 128, 16, 2048),
+             (workloads.gaussian(3, 3 << 17, seed=54), 500, 3, 8192),            # three entries per list: padded runs
+             (workloads.heavy_ties(7, 65536, seed=55, symbols=5), 2000, 4, 8192),
+             (workloads.gaussian(70, 65536, seed=57), 64, 4, 8192)]
+    g = torch.Generator().manual_seed(58)
+    cases.append((torch.randint(-3000, 3000, (5, 262144), generator=g, dtype=torch.int32), 1024, 4, 8192))
+    # the greatest values all in buckets that one wavefront owns: its run holds the whole result
+    w = workloads.gaussian(4, 1 << 20, seed=59)
+    n = torch.arange(1 << 20)
+    for r, b0 in enumerate((0, 128, 8192 - 128, 4096)):
+        w[r, (n % 8192 >= b0) & (n % 8192 < b0 + 128)] += 100.0
+    cases.append((w, 1024, 4, 8192))
+    for x, K, Kp, B in cases:
+        st, text = atk.describe_plan(x.dtype, x.shape[0], x.shape[1], K, Kp, B)
+        assert st == atk.OK and text.startswith("unfused") and "rank_finish" in text, text
+        check_approx(atk, x, K, Kp, B)
+        knobs.set("rank_finish", 0)
+        st, text = atk.describe_plan(x.dtype, x.shape[0], x.shape[1], K, Kp, B)
+        assert st == atk.OK and text.startswith("unfused") and "rank_finish" not in text, text
+        check_approx(atk, x, K, Kp, B)
+        knobs.set("rank_finish", -1)
+    # K so large that the heads of the runs would not fit LDS: the exact kernel selects
+    for x, K, Kp, B in [(workloads.heavy_ties(7, 65536, seed=55, symbols=5), 3360, 4, 8192),
+                        (workloads.gaussian(2, 1 << 20, seed=56), 8192, 8, 4096)]:
+        st, text = atk.describe_plan(x.dtype, x.shape[0], x.shape[1], K, Kp, B)
+        assert st == atk.OK and text.startswith("unfused") and "rank_finish" not in text, text
+        check_approx(atk, x, K, Kp, B)
+    # the K smallest
+    x = cases[0][0].to(DEV)
+    gv, gi = atk.approx_topk(x, 1024, 4, 8192, smallest=True)
+    torch.cuda.synchronize()
+    ov, oi = oracle.approx_topk(workloads.to_numpy_bits(cases[0][0]), 1024, 4, 8192, smallest=True)
+    assert np.array_equal(gi.cpu().numpy(), oi) and np.array_equal(bits(gv), host_bits(ov))
+
+
 def test_forced_unfused_route_matches_on_every_list_representation(atk, knobs):
     # the survivors of any call can be sent through the workspace: lanes sharing buckets, packed
     # and batched lists, integers -- same bits as the oracle
