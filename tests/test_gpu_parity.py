@@ -839,12 +839,13 @@ def test_seeded_random_shapes_all_element_types(atk, seed, cases, max_n, min_ran
     assert ran >= min_ran
 
 
-@pytest.mark.parametrize("seed,cases", [(3101, 50)])
-def test_seeded_random_shapes_many_buckets_large_k_and_options(atk, knobs, seed, cases):
+@pytest.mark.parametrize("seed,cases,finish_options", [(3101, 50, False), (4202, 50, True)])
+def test_seeded_random_shapes_many_buckets_large_k_and_options(atk, knobs, seed, cases, finish_options):
     # what the sweep above does not reach: bucket counts up to 2^18 (survivors through the
     # workspace, rows cut along the bucket axis), K up to 8192, random developer options (chunked,
-    # unfused, one-pass exact, slab), and the entry that allocates nothing; approximate and exact
-    # kernels against the oracle, bit for bit
+    # unfused, one-pass exact, slab; finish_options: also the ranking finish switched off, slab
+    # widths, lanes per bucket and workgroup counts other than the planner's), and the entry that
+    # allocates nothing; approximate and exact kernels against the oracle, bit for bit
     rng = np.random.default_rng(seed)
     dtypes = [torch.float32, torch.bfloat16, torch.float16, torch.int32, torch.uint32]
 
@@ -880,6 +881,17 @@ def test_seeded_random_shapes_many_buckets_large_k_and_options(atk, knobs, seed,
             opts["onepass"] = 2
         if rng.random() < 0.2:
             opts["slab"] = int(rng.integers(0, 3))
+        if finish_options:
+            if rng.random() < 0.5:
+                opts["slab"] = 2
+            if rng.random() < 0.25:
+                opts["rank_finish"] = 0
+            if rng.random() < 0.3:
+                opts["slab_width"] = int(2 ** rng.integers(5, 9))
+            if rng.random() < 0.3:
+                opts["slab_owners"] = int(2 ** rng.integers(1, 5))
+            if rng.random() < 0.3:
+                opts["rank_wgs"] = int(2 ** rng.integers(4, 13))
         for k, v in opts.items():
             knobs.set(k, v)
         g = torch.Generator().manual_seed(int(rng.integers(1 << 30)))
@@ -896,7 +908,8 @@ def test_seeded_random_shapes_many_buckets_large_k_and_options(atk, knobs, seed,
             x = x.to(dt)
         status, plan = atk.describe_plan(dt, rows, N, K, Kp, B)
         assert status == atk.OK, plan
-        print(f"case {case}: {dt} rows={rows} N={N} B={B} K'={Kp} K={K} style={style} {opts} {plan.split()[0]}", flush=True)
+        print(f"case {case}: {dt} rows={rows} N={N} B={B} K'={Kp} K={K} style={style} {opts} {plan.split()[0]}"
+              f"{' ranked' if 'rank_finish' in plan else ''}", flush=True)
         xh, xd = workloads.to_numpy_bits(x), x.to(DEV)
         gv, gi = atk.approx_topk(xd, K, Kp, B)
         torch.cuda.synchronize()
