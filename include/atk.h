@@ -288,7 +288,8 @@ int atk_read_probe(const void* data, size_t bytes, void* checksum, void* stream)
  * Developer options: launch-geometry switches for experiments and tests.  Results never depend on
  * them.  Process-wide; change them only while no call is in flight.  value < 0 restores the
  * default.  Initial values may be given in the environment (read once, at the first call that
- * plans a launch): ATK_LANES_PER_ROW, ATK_SEGMENTS, ATK_SLAB, ATK_RANK_FINISH, ATK_SLAB_WIDTH, ATK_NO_PACKED=1, ATK_NO_SUBWAVE=1,
+ * plans a launch): ATK_LANES_PER_ROW, ATK_SEGMENTS, ATK_SLAB, ATK_RANK_FINISH, ATK_SLAB_WIDTH,
+ * ATK_SLAB_OWNERS, ATK_RANK_WGS, ATK_DEFER, ATK_NO_PACKED=1, ATK_NO_SUBWAVE=1,
  * ATK_BATCH_MIN_KP, ATK_MIPS_SEGMENTS, ATK_UNFUSED, ATK_CHUNKED, ATK_ONEPASS.
  *   "lanes_per_row"  0 = planner's choice, else a power of two <= 1024: lanes that share one row
  *   "segments"       n > 0 forces n row segments on the split route
@@ -299,6 +300,12 @@ int atk_read_probe(const void* data, size_t bytes, void* checksum, void* stream)
  *                    survivors above it, where the planner finds that applicable)
  *   "slab_width"     0 = planner's choice, else a power of two >= 32: buckets per workgroup on the
  *                    few-row route when stage 2 is spread over several workgroups
+ *   "rank_wgs"       most workgroups of that second launch when survivors go through the workspace
+ *   "defer"          value+step lists: 0 every element updates its list at once, 1 (default) elements
+ *                    that beat a list's least entry are set aside and inserted later where the
+ *                    planner finds that it pays (long buckets), 2 wherever the lists allow it
+ *   "slab_owners"    0 = planner's choice, else a power of two <= 32: most lanes that share a bucket
+ *                    on the few-row route
  *   "packed"         0 switches the packed-key variants (16-bit rows) off
  *   "subwave"        0 switches the several-rows-per-wavefront variants off
  *   "batch_min_kp"   list length from which sorted batches are used (default 16)

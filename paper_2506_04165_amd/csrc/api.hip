@@ -40,7 +40,7 @@ template <typename Pred>
 static const Variant* find_variant(int dtype, int KP, int NL, bool packed_ok, Pred vector_ok) {
     const Variant* best = nullptr;
     for (const Variant& v : kVariants) {
-        if (v.dtype != dtype || v.KP != KP || v.V * v.R != NL || !vector_ok(v.V) || v.rep == 2) continue;
+        if (v.dtype != dtype || v.KP != KP || v.V * v.R != NL || !vector_ok(v.V) || v.rep == 2 || v.rep == 4) continue;
         if (v.packed() && !packed_ok) continue;
         if (!best || (v.packed() && !best->packed()) || (v.packed() == best->packed() && v.V > best->V))
             best = &v;
@@ -129,6 +129,7 @@ struct Options {
     int segments = 0;         // > 0: force this many row segments on the split route
     int slab = 1;             // 0 never / 1 planner's choice / 2 whenever possible: slab route
     int rank_finish = 1;      // 0: stage 2 of the slab route is never spread over several workgroups per row
+    int defer = 1;            // 0: list updates always insert at once; 2: elements are set aside whenever the lists allow it
     int rank_wgs = 2048;      // most workgroups of the ranking finish when survivors go through memory
     int slab_owners = 0;      // 0: planner's choice (8), else a power of two: most lanes that share a bucket on the slab route
     int slab_width = 0;       // 0: planner's choice, else buckets per workgroup on the slab route with the
@@ -163,6 +164,7 @@ static void options_from_env_once() {
         o.rank_finish = env("ATK_RANK_FINISH", o.rank_finish);
         o.slab_width = env("ATK_SLAB_WIDTH", o.slab_width);
         o.rank_wgs = env("ATK_RANK_WGS", o.rank_wgs);
+        o.defer = env("ATK_DEFER", o.defer);
         o.slab_owners = env("ATK_SLAB_OWNERS", o.slab_owners);
         if (o.slab_owners < 0 || o.slab_owners > 32 || (o.slab_owners & (o.slab_owners - 1))) o.slab_owners = 0;
         o.packed = env("ATK_NO_PACKED", 0) ? 0 : 1;
@@ -216,6 +218,7 @@ struct Plan {
     int chunk_k = 0;              // > 0: ... and runs stage 2 on them itself, leaving its chunk_k greatest
                                   // (of which the exact kernel picks the row's K); 0: all survivors leave
     int slab_w = 0;             // > 0: workgroups take slabs of this many buckets (see below)
+    int defer_from = 0x7fffffff; // variants with deferred insertion: the step from which elements may be set aside
     int run_len = 0;            // slab route, > 0: a slab's final keys leave as one sorted run of this length and
     int rank_runs_per_wg = 0;   // stage 2 is the ranking finish, a workgroup placing the keys of this many runs
 };
@@ -594,8 +597,27 @@ static const Plan& make_plan(const void* values, int dtype, int64_t rows, int64_
         if (keys[i] == key) return plans[i];
     const int slot = used < kSlots ? used++ : (next = (next + 1) % kSlots);
     keys[slot] = key;
-    plans[slot] = compute_plan(values, dtype, rows, N, row_stride, K, Kp, B, stage1_only, ws_avail);
-    return plans[slot];
+    Plan& pl = plans[slot];
+    pl = compute_plan(values, dtype, rows, N, row_stride, K, Kp, B, stage1_only, ws_avail);
+    // Value+step lists, long buckets: the variant that sets an element aside when it beats its
+    // list's least entry and inserts it later (wavefront-uniform branch, rarely taken) instead of
+    // updating the list with every element.  Measured: lists of 8 entries from 128 steps a row
+    // on (1024 x 65536, 256 buckets: 81 -> 75 us), shorter lists from 768 steps (256 x 2^20,
+    // 1024 buckets, K' = 4: 170 -> 166 us; at 500 steps and fewer, or with one list per lane --
+    // one branch per element then -- 1-4 % slower).  Option "defer": 0 never, 2 wherever such a
+    // variant exists.
+    if (pl.status == ATK_OK && !pl.route_exact && pl.var && pl.var->rep == 0 && g_opt.defer != 0) {
+        const int steps = pl.nseg > 1 ? pl.seg_steps : pl.nsteps;
+        const bool pays = pl.var->KP >= 8 ? steps >= 128 : (steps >= 768 && pl.var->V * pl.var->R >= 2);
+        if (pays || g_opt.defer == 2)
+            for (const Variant& v : kVariants)
+                if (v.rep == 4 && v.dtype == pl.var->dtype && v.KP == pl.var->KP && v.V == pl.var->V && v.R == pl.var->R) {
+                    pl.var = &v;
+                    pl.defer_from = 8 * v.KP;
+                    break;
+                }
+    }
+    return pl;
 }
 
 static ApproxParams params_from(const Plan& pl, const void* values, int64_t rows, int64_t N,
@@ -609,6 +631,7 @@ static ApproxParams params_from(const Plan& pl, const void* values, int64_t rows
     p.S = pl.S; p.nsteps = pl.nsteps; p.owners = pl.owners; p.seg = pl.seg; p.Cpad = pl.Cpad;
     p.aux_offset = (int)pl.aux_offset; p.tail = pl.tail;
     p.chunk = pl.chunk;
+    p.defer_from = pl.defer_from;
     return p;
 }
 
@@ -1217,7 +1240,7 @@ int atk_describe_plan(int dtype, int64_t rows, int64_t N, int K, int Kprime, int
                   "%s%s KP=%d V=%d R=%d lanes_per_row=%d rows_per_wg=%d block=%d grid=%dx%d step=%d "
                   "steps=%d owners=%d seg=%d cand=%d tail=%d lds=%zu workspace=%zu",
                   pl.slab_w > 0 ? "slab" : pl.nseg > 1 ? "split" : (pl.fused ? "fused" : (pl.chunk_k > 0 ? "chunked" : "unfused")),
-                  pl.var->packed() ? " packed" : (pl.var->rep == 2 ? " batched" : ""), pl.var->KP, pl.var->V,
+                  pl.var->packed() ? " packed" : (pl.var->rep == 2 ? " batched" : (pl.var->rep == 4 ? " deferred" : "")), pl.var->KP, pl.var->V,
                   pl.var->R, pl.G, pl.rows_per_wg, pl.block, pl.grid,
                   pl.slab_w > 0 ? B / pl.slab_w : (pl.nseg > 1 ? pl.nseg : pl.nchunk), pl.S, pl.nsteps,
                   pl.owners, pl.seg, pl.Cpad, pl.tail, pl.lds, pl.workspace);
@@ -1238,7 +1261,7 @@ int atk_set_option(const char* name, int value) {
     struct Entry { const char* name; int Options::*field; };
     static const Entry entries[] = {
         {"lanes_per_row", &Options::lanes_per_row}, {"segments", &Options::segments},
-        {"slab", &Options::slab}, {"rank_finish", &Options::rank_finish}, {"slab_width", &Options::slab_width}, {"rank_wgs", &Options::rank_wgs}, {"slab_owners", &Options::slab_owners}, {"packed", &Options::packed}, {"subwave", &Options::subwave},
+        {"slab", &Options::slab}, {"rank_finish", &Options::rank_finish}, {"slab_width", &Options::slab_width}, {"rank_wgs", &Options::rank_wgs}, {"defer", &Options::defer}, {"slab_owners", &Options::slab_owners}, {"packed", &Options::packed}, {"subwave", &Options::subwave},
         {"batch_min_kp", &Options::batch_min_kp}, {"mips_segments", &Options::mips_segments},
         {"unfused", &Options::unfused}, {"onepass", &Options::onepass}, {"chunked", &Options::chunked},
         {"exact_threads", &Options::exact_threads}, {"certified", &Options::certified}, {"reg_rows", &Options::reg_rows},

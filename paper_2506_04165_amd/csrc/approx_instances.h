@@ -6,7 +6,8 @@
 
 // X(DTYPE_TAG, C++ type, KP, V, R, REP)   REP: 0 value+step lists, 1 packed 32-bit keys,
 //                                          2 sorted batches of 64-bit keys, 3 insertion lists of
-//                                          64-bit keys (integer inputs)
+//                                          64-bit keys (integer inputs), 4 value+step lists
+//                                          with deferred insertion
 // DTYPE_TAG: 0 fp32, 1 bf16 (fp16 runs on the bf16 kernels), 3 int32, 4 uint32
 #define ATK_INSTANCES_NL1(X, TAG, T, V, R, P) \
     X(TAG, T, 1, V, R, P) X(TAG, T, 2, V, R, P) X(TAG, T, 3, V, R, P) X(TAG, T, 4, V, R, P) \
@@ -78,6 +79,18 @@
     ATK_PACKED_NL1(X, 1, 1) ATK_PACKED_NL2(X, 2, 1) ATK_PACKED_NL4(X, 4, 1) \
     ATK_PACKED_NL8(X, 8, 1) ATK_PACKED_NL16(X, 8, 2)
 
+// value+step lists with deferred insertion (REP 4), for long buckets: lists of 2 to 8 entries,
+// aligned vector loads
+#define ATK_DEFER_NL1(X, TAG, T, V, R) \
+    X(TAG, T, 2, V, R, 4) X(TAG, T, 3, V, R, 4) X(TAG, T, 4, V, R, 4) X(TAG, T, 6, V, R, 4) X(TAG, T, 8, V, R, 4)
+#define ATK_DEFER_NL8(X, TAG, T, V, R) X(TAG, T, 2, V, R, 4) X(TAG, T, 3, V, R, 4) X(TAG, T, 4, V, R, 4)
+#define ATK_INSTANCES_F32_DEFER(X) \
+    ATK_DEFER_NL1(X, 0, float, 1, 1) ATK_DEFER_NL1(X, 0, float, 2, 1) ATK_DEFER_NL1(X, 0, float, 4, 1) \
+    ATK_DEFER_NL8(X, 0, float, 4, 2) X(0, float, 2, 4, 4, 4)
+#define ATK_INSTANCES_BF16_DEFER(X) \
+    ATK_DEFER_NL1(X, 1, bf16_t, 1, 1) ATK_DEFER_NL1(X, 1, bf16_t, 2, 1) ATK_DEFER_NL1(X, 1, bf16_t, 4, 1) \
+    ATK_DEFER_NL8(X, 1, bf16_t, 8, 1) X(1, bf16_t, 2, 8, 2, 4)
+
 // large K', at most 256 buckets: sorted batches of 64-bit keys, one list per lane
 #define ATK_INSTANCES_BATCHED(X) \
     X(0, float, 8, 1, 1, 2) X(0, float, 16, 1, 1, 2) X(0, float, 32, 1, 1, 2) \
@@ -89,5 +102,6 @@
     ATK_INSTANCES_F32_SMALL(X) ATK_INSTANCES_F32_WIDE(X) ATK_INSTANCES_F32_UNALIGNED(X) \
     ATK_INSTANCES_BF16_SMALL(X) ATK_INSTANCES_BF16_WIDE(X) ATK_INSTANCES_BF16_UNALIGNED(X) \
     ATK_INSTANCES_BF16_PACKED(X) ATK_INSTANCES_BATCHED(X) \
+    ATK_INSTANCES_F32_DEFER(X) ATK_INSTANCES_BF16_DEFER(X) \
     ATK_INSTANCES_I32_SMALL(X) ATK_INSTANCES_I32_WIDE(X) ATK_INSTANCES_I32_UNALIGNED(X) \
     ATK_INSTANCES_U32_SMALL(X) ATK_INSTANCES_U32_WIDE(X) ATK_INSTANCES_U32_UNALIGNED(X)

@@ -74,6 +74,8 @@ struct ApproxParams {
                           // a floating type (0x80000000 on the widened pattern), all bits of an
                           // integer -- and again onto every pattern that is written out
     int surv_aligned;     // mode 1: both survivor arrays start at multiples of 16 bytes (vector stores allowed)
+    int defer_from;       // value+step lists: the step from which elements may be set aside instead of
+                          // inserted at once (variants with deferred insertion, see Lists<4>)
 };
 
 // Plain two-way select on values; written as a function of values so that it is emitted as a
@@ -145,6 +147,35 @@ struct Lists<0, KP, NL> {
     // e: offset of the slot inside a step, S: elements per step
     __device__ __forceinline__ uint32_t index(int l, int k, uint32_t S, uint32_t e) const {
         return (uint32_t)stp[l][k] * S + e;
+    }
+};
+
+//  * value + step with deferred insertion: the same lists, see below.
+template <int KP, int NL>
+struct Lists<4, KP, NL> : Lists<0, KP, NL> {
+    using Lists<0, KP, NL>::val;
+    using Lists<0, KP, NL>::insert_full;
+    // Deferred insertion (full lists only).  Once a list has seen many elements, few of the
+    // following ones beat its least entry.  Such an element is only set aside (one compare, two
+    // selects); it enters the list when another element of the same list, in any lane of the
+    // wavefront, wants the place where it waits -- a wavefront-uniform branch that is rarely
+    // taken -- or at the end.  Elements wait at most one per list, and nothing overtakes a
+    // waiting element inside its list, so the list ends up exactly as with immediate insertion.
+    float pend_v[NL];
+    int32_t pend_s[NL];          // < 0: nothing waits
+    __device__ __forceinline__ void pend_init() {
+#pragma unroll
+        for (int l = 0; l < NL; ++l) { pend_v[l] = 0.0f; pend_s[l] = -1; }
+    }
+    __device__ __forceinline__ bool beats_least(int l, float x) const { return x > val[l][KP - 1]; }
+    __device__ __forceinline__ void set_aside(int l, bool hit, float x, int32_t step) {
+        pend_v[l] = sel(hit, x, pend_v[l]);
+        pend_s[l] = sel(hit, step, pend_s[l]);
+    }
+    __device__ __forceinline__ void flush(int l) {
+        // lanes where nothing waits insert -inf, which changes nothing
+        insert_full(l, sel(pend_s[l] >= 0, pend_v[l], -__builtin_inff()), pend_s[l]);
+        pend_s[l] = -1;
     }
 };
 
@@ -405,7 +436,7 @@ struct ApproxKernel {
             }
         } else {
         // every slot takes one element per step: after KP steps no list entry is empty
-        constexpr bool TWO_PHASE = REP == 0 && KP > 1;
+        constexpr bool TWO_PHASE = (REP == 0 || REP == 4) && KP > 1;
         if constexpr (TWO_PHASE) {
             // the first KP steps (fewer on a short walk), loaded together like any other batch
             const int nfill = min(KP, s_end - s);                  // uniform
@@ -428,6 +459,23 @@ struct ApproxKernel {
                 s += nfill;
             }
         }
+        // The variants with deferred insertion set elements aside instead of inserting them
+        // (see Lists<4>) while that pays: a batch of U steps runs in that form, and when more
+        // than a quarter of its list updates had to insert after all (ascending data: every
+        // element beats its list) the following batches insert at once, 1, 2, 4, ... of them
+        // before the next attempt.
+        constexpr bool DEFER = REP == 4;
+        static_assert(!DEFER || KP > 1, "deferred insertion is for lists of two entries or more");
+        uint64_t waiting[NL] = {};          // per list: the lanes where an element waits (uniform)
+        int direct_batches = 0, backoff = 1;
+        if constexpr (DEFER) L.pend_init();
+        auto flush_all = [&]() {
+            if constexpr (DEFER) {
+#pragma unroll
+                for (int l = 0; l < NL; ++l)
+                    if (waiting[l] != 0) { L.flush(l); waiting[l] = 0; }
+            }
+        };
         for (; s + U <= s_end; s += U) {
             const buffer_rsrc rs = make_rsrc(wg_base + (size_t)s * step_bytes);
             vec_t buf[U][R];
@@ -436,12 +484,51 @@ struct ApproxKernel {
 #pragma unroll
                 for (int r = 0; r < R; ++r)
                     buf[u][r] = VL::load(rs, lane_off[r], (uint32_t)u * step_bytes);
+            if constexpr (DEFER) {
+                if (direct_batches == 0 && s >= p.defer_from) {
+                    int inserted = 0;
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        // one branch per step: when an element of any list wants a place where
+                        // another one waits, everything that waits enters its list first
+                        float x[NL];
+                        bool hit[NL];
+                        uint64_t hits[NL], clash = 0;
+#pragma unroll
+                        for (int r = 0; r < R; ++r)
+#pragma unroll
+                            for (int v = 0; v < V; ++v) {
+                                const int l = r * V + v;
+                                x[l] = __uint_as_float(VL::bits(buf[u][r], v) ^ flip);
+                                hit[l] = L.beats_least(l, x[l]);
+                                hits[l] = __ballot(hit[l]);
+                                clash |= hits[l] & waiting[l];
+                            }
+                        if (clash != 0) { flush_all(); ++inserted; }
+#pragma unroll
+                        for (int l = 0; l < NL; ++l) {
+                            L.set_aside(l, hit[l], x[l], s + u);
+                            waiting[l] |= hits[l];
+                        }
+                    }
+                    if (inserted * 4 > U) {
+                        flush_all();
+                        direct_batches = backoff;
+                        backoff = min(backoff * 2, 64);
+                    } else {
+                        backoff = 1;
+                    }
+                    continue;
+                }
+                if (direct_batches > 0) --direct_batches;
+            }
 #pragma unroll
             for (int u = 0; u < U; ++u)
 #pragma unroll
                 for (int r = 0; r < R; ++r)
                     consume<TWO_PHASE>(L, buf[u][r], r, s + u, flip);
         }
+        flush_all();
         if (s < s_end) {
             // the last, short batch: its loads are issued together as well (a step-by-step tail
             // would pay a memory latency per step); the count is uniform, so the tests are scalar

@@ -308,6 +308,48 @@ def test_large_bucket_counts_unfused_in_bucket_chunks(atk, rows, N, K, Kp, B, dt
     check_stage1(atk, x, Kp, B)
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_elements_set_aside_and_inserted_later(atk, knobs, dtype):
+    # value+step lists may keep an element that beats a list's least entry aside and insert it
+    # when another element of the same list turns up in any lane of the wavefront, or at the end
+    # (option "defer": 2 wherever the lists allow it, 0 never).  Same bits as the oracle on
+    # random order, ascending order (every element beats its list: the kernel goes back to
+    # inserting at once, batch by batch), descending order (nothing ever beats a full list),
+    # dense ties, infinities, and one value everywhere; every list length; rows of a few steps
+    # up to a thousand
+    for rows, N, B, K in [(5, 65536, 256, 200), (6, 1 << 18, 1024, 128), (5, 9 * 640, 640, 64), (7, 40 * 96, 96, 50)]:
+        base = torch.randn(rows, N, generator=torch.Generator().manual_seed(N + B))
+        x = base.clone()
+        x[1] = torch.sort(base[1]).values
+        x[2] = torch.sort(base[2], descending=True).values
+        x[3] = torch.round(base[3] * 2) / 2
+        x[4] = 1.5
+        if rows > 5:
+            x[5, ::7] = float("inf")
+            x[5, 3::11] = float("-inf")
+        x = x.to(dtype)
+        for Kp in (2, 3, 4, 6, 8):
+            if Kp * B < K or Kp > N // B:
+                continue
+            for defer in (2, 0):
+                knobs.set("defer", defer)
+                # (16-bit rows: the packed-key lists have no such form; they are switched off)
+                knobs.set("packed", 0)
+                print(f"defer={defer} {dtype} rows={rows} N={N} B={B} K'={Kp}", flush=True)
+                check_approx(atk, x, K, Kp, B)
+                check_stage1(atk, x, Kp, B)
+            knobs.set("defer", -1)
+    # the split route (segments of a row) and the mirrored problem
+    knobs.set("defer", 2)
+    y = workloads.gaussian(3, 1 << 20, seed=77)
+    y[1] = torch.sort(y[1]).values
+    check_approx(atk, y, 128, 4, 512)
+    gv, gi = atk.approx_topk(y.to(DEV), 128, 4, 512, smallest=True)
+    torch.cuda.synchronize()
+    ov, oi = oracle.approx_topk(workloads.to_numpy_bits(y), 128, 4, 512, smallest=True)
+    assert np.array_equal(gi.cpu().numpy(), oi) and np.array_equal(bits(gv), host_bits(ov))
+
+
 def test_unfused_route_with_the_ranking_finish(atk, knobs):
     # survivors beyond LDS whose lanes hold 8 or 16 list entries: every wavefront's survivors
     # leave as one sorted run of 512 or 1024 keys and the second launch places every key by
@@ -892,6 +934,8 @@ def test_seeded_random_shapes_many_buckets_large_k_and_options(atk, knobs, seed,
                 opts["slab_owners"] = int(2 ** rng.integers(1, 5))
             if rng.random() < 0.3:
                 opts["rank_wgs"] = int(2 ** rng.integers(4, 13))
+            if rng.random() < 0.5:
+                opts["defer"] = int(rng.choice([0, 2]))
         for k, v in opts.items():
             knobs.set(k, v)
         g = torch.Generator().manual_seed(int(rng.integers(1 << 30)))
