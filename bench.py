@@ -39,16 +39,16 @@ PAPER_CONTEXT = {
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by a plain
 # copy of known size (profiles/approx_topk_<workload>_B<B>_Kp<K'>.md), keyed by (workload, B, K').
 MEASURED_TRAFFIC_BYTES = {
-    ("c4_mips", 1024, 4): 1076606134,
-    ("c4_mips", 4096, 1): 1076466724,
-    ("c2_ffn", 128, 4): 498468205,
-    ("c2_ffn", 1024, 1): 498749163,
-    ("c2_ffn", 64, 8): 498480344,
-    ("c3_vocab", 512, 4): 528454966,
-    ("c3_vocab", 512, 2): 528280928,
-    ("c5_adversarial", 256, 8): 271130371,
-    ("c5_adversarial", 256, 1): 278474040,
-    ("c5_adversarial", 256, 32): 272492517,
+    ("c4_mips", 1024, 4): 1076706527,
+    ("c4_mips", 4096, 1): 1076507712,
+    ("c2_ffn", 128, 4): 498472284,
+    ("c2_ffn", 1024, 1): 498758244,
+    ("c2_ffn", 64, 8): 498460330,
+    ("c3_vocab", 512, 4): 528439926,
+    ("c3_vocab", 512, 2): 528316553,
+    ("c5_adversarial", 256, 8): 271409796,
+    ("c5_adversarial", 256, 1): 278177195,
+    ("c5_adversarial", 256, 32): 272520448,
 }
 
 
@@ -220,6 +220,10 @@ def bench_workload(name, steps, warmup, with_cpu_baseline, only_params=None):
             "alu_ops_per_element_executed": ops_exec,
             "alu_frac_of_peak_executed": ops_exec * w.rows * w.N / sec / valu_peak,
             "alu_ops_per_element_section_6_3": 5 * Kp - 2,
+            **({"alu_note": "variant with deferred insertion: three operations per element (one compare, "
+                            "two selects) plus 4K'+1 per insertion actually made, which depends on the "
+                            "data; the executed figure is the count of the immediate-insertion form, "
+                            "an upper bound"} if " deferred" in plan else {}),
             "bound": "alu" if ops_exec * w.rows * w.N / valu_peak > alg / (HBM_PEAK_GBPS * 1e9) else "hbm",
             "plan": plan, "input_copies_rotated": copies, "steady_state_calls": t["steady_state_calls"],
         })
