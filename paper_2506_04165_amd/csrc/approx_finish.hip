@@ -168,7 +168,11 @@ __global__ void __launch_bounds__(kRankThreads) rank_finish_kernel(RankFinishPar
     // items: several threads share a key, each taking every parts-th run, and add their counts
     // up in LDS.  run_at(r): the keys of run r that are searched, 1 << log_len of them.
     lds_ptr<uint32_t> cnt = open_word + 1;                  // [my runs], then their total
-    auto place_keys = [&](auto run_at, int log_len) {
+    // len_tag: the logarithm of the searched length as a compile-time constant (the search loops are
+    // then unrolled and their offsets are immediates), or 0 for the run-time value log_any.
+    auto place_keys = [&](auto run_at, auto len_tag, int log_any) {
+        constexpr int CL = decltype(len_tag)::value;
+        const int log_len = CL > 0 ? CL : log_any;
         const int Ls = 1 << log_len;
         if (tid < myruns)
             cnt[tid] = bound == 0 ? (uint32_t)Ls : (uint32_t)count_greater(run_at(first + tid), log_len, bound - 1);
@@ -192,9 +196,15 @@ __global__ void __launch_bounds__(kRankThreads) rank_finish_kernel(RankFinishPar
                 // four searches side by side: their loads overlap
                 int p0 = 0, p1 = 0, p2 = 0, p3 = 0;
                 const auto r0 = run_at(o), r1 = run_at(o + parts), r2 = run_at(o + 2 * parts), r3 = run_at(o + 3 * parts);
-                for (int s = Ls >> 1; s >= 1; s >>= 1) {
+                auto probe = [&](int s) {
                     const uint64_t a0 = r0[p0 + s - 1], a1 = r1[p1 + s - 1], a2 = r2[p2 + s - 1], a3 = r3[p3 + s - 1];
                     p0 += a0 > x ? s : 0; p1 += a1 > x ? s : 0; p2 += a2 > x ? s : 0; p3 += a3 > x ? s : 0;
+                };
+                if constexpr (CL > 0) {
+#pragma unroll
+                    for (int s = 1 << (CL - 1); s >= 1; s >>= 1) probe(s);
+                } else {
+                    for (int s = Ls >> 1; s >= 1; s >>= 1) probe(s);
                 }
                 const uint64_t a0 = r0[p0], a1 = r1[p1], a2 = r2[p2], a3 = r3[p3];
                 above += p0 + p1 + p2 + p3 + (a0 > x ? 1 : 0) + (a1 > x ? 1 : 0) + (a2 > x ? 1 : 0) + (a3 > x ? 1 : 0);
@@ -217,10 +227,18 @@ __global__ void __launch_bounds__(kRankThreads) rank_finish_kernel(RankFinishPar
             }
         }
     };
-    if (whole_runs)
-        place_keys([&](int r) { return runs + ((size_t)r << p.log_run); }, p.log_run);
-    else
-        place_keys([&](int r) { return (lds_ptr<const uint64_t>)(heads + (r << p.log_head)); }, p.log_head);
+    if (whole_runs) {
+        place_keys([&](int r) { return runs + ((size_t)r << p.log_run); }, std::integral_constant<int, 0>{}, p.log_run);
+        return;
+    }
+    auto head_at = [&](int r) { return (lds_ptr<const uint64_t>)(heads + (r << p.log_head)); };
+    switch (p.log_head) {
+        case 5: place_keys(head_at, std::integral_constant<int, 5>{}, 5); break;
+        case 6: place_keys(head_at, std::integral_constant<int, 6>{}, 6); break;
+        case 7: place_keys(head_at, std::integral_constant<int, 7>{}, 7); break;
+        case 8: place_keys(head_at, std::integral_constant<int, 8>{}, 8); break;
+        default: place_keys(head_at, std::integral_constant<int, 0>{}, p.log_head); break;
+    }
 }
 
 template <typename DT>
