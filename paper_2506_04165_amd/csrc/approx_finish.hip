@@ -167,7 +167,7 @@ __global__ void __launch_bounds__(kRankThreads) rank_finish_kernel(RankFinishPar
     // run: their searches in another run visit mostly the same or neighbouring words.  Few
     // items: several threads share a key, each taking every parts-th run, and add their counts
     // up in LDS.  run_at(r): the keys of run r that are searched, 1 << log_len of them.
-    lds_ptr<uint32_t> cnt = open_word + 1;                  // [my runs], then their total
+    lds_ptr<uint32_t> cnt = open_word + 1;                  // [my runs]
     // len_tag: the logarithm of the searched length as a compile-time constant (the search loops are
     // then unrolled and their offsets are immediates), or 0 for the run-time value log_any.
     auto place_keys = [&](auto run_at, auto len_tag, int log_any) {

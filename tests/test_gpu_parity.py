@@ -350,6 +350,30 @@ def test_elements_set_aside_and_inserted_later(atk, knobs, dtype):
     assert np.array_equal(gi.cpu().numpy(), oi) and np.array_equal(bits(gv), host_bits(ov))
 
 
+def test_ranking_finish_signed_zeros_and_row_strides(atk):
+    # rows whose greatest values are zeros of both signs (equal in the order: the lowest index
+    # first, each reported with its own sign, which the second launch reads back from the row),
+    # as views with a row stride and a base that is not 16-byte aligned; few-row and unfused routes
+    for rows, N, K, Kp, B, route in [(5, 262144, 1024, 4, 1024, "slab"), (6, 1 << 19, 1024, 4, 8192, "unfused")]:
+        g = torch.Generator().manual_seed(N + B)
+        z = -torch.abs(torch.round(torch.randn(rows, N, generator=g) * 0.7))       # zeros are -0.0
+        flip = (z == 0) & (torch.rand(rows, N, generator=g) < 0.5)
+        z[flip] = 0.0                                                              # ... half of them +0.0
+        z[rows - 1, ::5] = float("-inf")
+        big = torch.full((rows, N + 72), 7.0)
+        for off in (0, 4, 3):
+            big[:, off:off + N] = z
+            view = big.to(DEV)[:, off:off + N]
+            st, text = atk.describe_plan(torch.float32, rows, N, K, Kp, B)
+            assert st == atk.OK and text.startswith(route) and "rank_finish" in text, text
+            gv, gi = atk.approx_topk(view, K, Kp, B)
+            torch.cuda.synchronize()
+            ov, oi = oracle.approx_topk(workloads.to_numpy_bits(z), K, Kp, B)
+            assert np.array_equal(gi.cpu().numpy(), oi), (route, off)
+            assert np.array_equal(bits(gv), host_bits(ov)), (route, off)
+            assert (bits(gv) == 0x80000000).any() and (bits(gv) == 0).any()
+
+
 def test_unfused_route_with_the_ranking_finish(atk, knobs):
     # survivors beyond LDS whose lanes hold 8 or 16 list entries: every wavefront's survivors
     # leave as one sorted run of 512 or 1024 keys and the second launch places every key by
