@@ -1,6 +1,7 @@
 // C ABI of libatk: argument validation, launch planning and dispatch (host code only).
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
@@ -66,7 +67,7 @@ constexpr int64_t kOnepassMinN = 524288; // exact kernel: shortest row that is t
 constexpr int64_t kTargetWaves = 2048;   // 256 CUs x 4 SIMDs x 2 waves: below this the chip idles
 constexpr int64_t kTargetWorkgroups = 256; // ... and with fewer workgroups than CUs some CUs have none
 constexpr int kMinSegmentSteps = 8;      // do not cut a row into pieces shorter than this
-constexpr int kMaxSegments = 64;
+constexpr int kMaxSegments = 128;
 constexpr size_t kMinSplitBytes = 4u << 20;
 constexpr int kSlabBuckets = 32;         // buckets per workgroup on the slab route
 constexpr size_t kSlabMinRowBytes = 128u << 10;
@@ -264,6 +265,13 @@ static Plan compute_plan(const void* values, int dtype, int64_t rows, int64_t N,
     int Gd = pow2_floor(N / 224 > 0 ? N / 224 : 1);
     if (Gd < 64) Gd = 64;
     if (Gd > kMaxLanes) Gd = kMaxLanes;
+    // short rows with many survivors: stage 2 (a selection among B*K' keys by the row's lanes) then
+    // weighs more than the stream, and wants a lane per eight keys (16384 x 4096, 1024 buckets,
+    // K' = 4, bf16: 590 us with 128 lanes a row, 430 us with 512; 2048 x 32768 fp32: 140 -> 93 us)
+    if (pow2_ceil((int64_t)B * Kp) > kWaveSortMaxKeys && pow2_ceil((int64_t)B * Kp) <= kMaxFusedCandidates) {
+        const int for_stage2 = pow2_ceil((int64_t)B * Kp) / 8 > kMaxLanes ? kMaxLanes : pow2_ceil((int64_t)B * Kp) / 8;
+        if (Gd < for_stage2) Gd = for_stage2;
+    }
     if (g_opt.lanes_per_row > 0) Gd = g_opt.lanes_per_row;
 
     auto aligned_for = [&](int V) {
@@ -384,6 +392,10 @@ static Plan compute_plan(const void* values, int dtype, int64_t rows, int64_t N,
     // buckets, later reused as scratch of the selection]
     const bool wave_tail = !stage1_only && G >= 64 && pl.Cpad <= kWaveSortMaxKeys;
     const bool to_memory = stage1_only || (through_memory && !chunk_fused);
+    // More candidates than one wavefront sorts: one row per workgroup, so that stage 2 is the
+    // selection (rows sharing a workgroup would fall back to a full LDS sort of all their
+    // candidates: 16384 x 4096 with 1024 buckets, K' = 4: 2500 us against 120 us)
+    if (!to_memory && G >= 64 && pl.Cpad > kWaveSortMaxKeys) rpw = 1;
     auto lds_for = [&](int r) {
         size_t cand = 0, aux = 0;
         if (owners > 1) { cand = (size_t)r * pl.Cpad; aux = (size_t)r * B * pl.seg; }
@@ -526,6 +538,8 @@ static Plan compute_plan(const void* values, int dtype, int64_t rows, int64_t N,
     if (pl.fused && owners == 1 && G >= 64 && rows > 0 && !pl.var->packed()) {
         const int64_t waves = (int64_t)pl.grid * (pl.block / 64);
         int want = (int)((kTargetWaves + waves - 1) / waves);
+        // (... and a workgroup on every CU: 128 rows of 1024 lanes are 2048 waves on half the chip)
+        if (pl.grid * 2 <= kTargetWorkgroups && want < kTargetWorkgroups / pl.grid) want = (int)(kTargetWorkgroups / pl.grid);
         const int max_by_len = pl.nsteps / kMinSegmentSteps;
         if (want > max_by_len) want = max_by_len;
         if (want > kMaxSegments) want = kMaxSegments;
@@ -541,14 +555,29 @@ static Plan compute_plan(const void* values, int dtype, int64_t rows, int64_t N,
         // merges nseg*K' keys per bucket, sixteen loads at a time, and few rows make it pure
         // latency.  Rough per-row model in microseconds (constants measured on 8 x 262144 rows):
         // a workgroup streams ~45 GB/s on its own, the second launch and the round trip through
-        // memory cost ~6, every batch of sixteen keys per bucket pass ~3.
+        // memory cost ~6, every batch of sixteen keys per bucket pass ~3 (~1 from 8 rows on, more
+        // when a row's batch is more than a latency's worth of bytes).
+        // The stream itself is the slower of two things: a row's own rate (its lanes' loads in
+        // flight: a row of fewer than 256 lanes streams in proportion to its lanes) and the chip's
+        // (every wavefront keeps 64 x U x R x V elements in flight for about 1.5 us; about 5 TB/s
+        // once there are enough of them, and about 28 GB/s per CU that has a workgroup).  Measured: 8 x 2^24 with 64 buckets 484 -> 180 us (32 ->
+        // 128 segments), 32 x 2^22 253 -> 118 us, 12 x 2^20 119 -> 47 us.
         if (want > 1) {
             const double row_bytes = (double)N * es;
+            const double lanes_share = G >= 256 ? 1.0 : G / 256.0;
+            const int dw = (pl.var->V * es + 3) / 4;
+            int inflight = 32 / (pl.var->R * dw);
+            inflight = inflight < 1 ? 1 : (inflight > 16 ? 16 : inflight);
+            const double wave_rate = 64.0 * inflight * pl.var->R * pl.var->V * es / 1.5;      // bytes per us
+            // one batch of a row: a memory latency, or its B x 16 keys at what one workgroup reads
+            const double per_batch = std::max(rows >= 8 ? 1.0 : 3.0, B * 128.0 / 30e3);
             auto cost = [&](int n) {
-                const double stream = row_bytes / n / 45e3;
+                const double busy_cus = std::min<double>(256.0, (double)pl.grid * n);
+                const double chip = std::min({5e6, (double)waves * n * wave_rate, busy_cus * 28e3});
+                const double own = row_bytes / n / (45e3 * lanes_share);
+                const double stream = std::max(own, (double)in_bytes / chip);
                 if (n == 1) return stream;
-                const int batches = ((n * Kp + 15) / 16) * ((B + 511) / 512);
-                return stream + 6.0 + 3.0 * batches;
+                return stream + 6.0 + per_batch * ((n * Kp + 15) / 16);
             };
             int best = 1;
             for (int n = 2; n <= want; n = (n * 2 <= want || n == want) ? n * 2 : want)

@@ -96,7 +96,9 @@ def test_fused_route_guard_bands(atk):
     run_guarded_approx(atk, workloads.gaussian(301, 4096, seed=32), 100, 2, 512, "fused")
     run_guarded_approx(atk, workloads.gaussian(37, 8192, seed=33), 40, 4, 16, "fused")
     run_guarded_approx(atk, workloads.gaussian(1031, 2048, seed=34, dtype=torch.bfloat16), 287, 4, 128, "fused packed")
-    run_guarded_approx(atk, workloads.gaussian(129, 65536, seed=35), 256, 32, 256, "fused")
+    run_guarded_approx(atk, workloads.gaussian(260, 65536, seed=35), 256, 32, 256, "fused")
+    # (half as many rows leave CUs idle: every row is cut in two)
+    run_guarded_approx(atk, workloads.gaussian(129, 65536, seed=35), 256, 32, 256, "split batched")
     g = torch.Generator().manual_seed(36)
     run_guarded_approx(atk, torch.randint(-99, 99, (65, 6000), generator=g, dtype=torch.int32), 77, 3, 125, "fused")
 
