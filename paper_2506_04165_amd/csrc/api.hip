@@ -803,13 +803,31 @@ constexpr int kCertMinK = 8;                // below, K' = 4 would be K' >= K
 constexpr int kCertMinRowPerSurvivor = 16;  // N >= 16 B K': otherwise stage 2 costs more than a second pass
 constexpr int kCertMaxScan = 65536;         // elements a repairing workgroup reads again
 
-static CertPlan certified_params(int dtype, int64_t N, int K) {
-    struct Slot { int64_t N; int K, es; unsigned gen; CertPlan cp; };
-    thread_local Slot last{0, 0, 0, 0, {}};
+static CertPlan certified_params(int dtype, int64_t rows, int64_t N, int K) {
+    struct Slot { int64_t rows, N; int K, es; unsigned gen; CertPlan cp; };
+    thread_local Slot last{0, 0, 0, 0, 0, {}};
     options_from_env_once();
     const int es = elem_size(dtype);
-    if (last.N == N && last.K == K && last.es == es && last.gen == g_opt_generation) return last.cp;
+    if (last.rows == rows && last.N == N && last.K == K && last.es == es && last.gen == g_opt_generation) return last.cp;
     CertPlan cp;
+    if (g_opt.certified != 0 && K < kCertMinK && (K <= 4 || rows <= 64)) {
+        // Very small K: lists of K' = K entries keep the whole Top-K by construction (Section 1: the
+        // method is exact there), so the two-stage kernels give the exact result with nothing to
+        // certify.  Survivors (B x K, K rounded up to a power of two) at
+        // most a sixteenth of the row, between 256 and 4096, and at most 1024 where that keeps
+        // 16-bit rows on the packed-key kernels.  Lists of more than four entries only where the
+        // rows are too few for the radix kernel to fill the chip (it takes a workgroup per row).
+        // Measured against the radix kernel: 8 x 2^23 fp32, K = 1: 69 against 447 us; 1 x 2^24: 65 /
+        // 708; 16384 x 4096: 69 / 113; 50000 x 1024 bf16: 28 / 369.
+        int64_t survivors = N / 16 < 256 ? 256 : (N / 16 > 4096 ? 4096 : N / 16);
+        if (es == 2 && N <= 65536 && survivors > kWaveSortMaxKeys) survivors = kWaveSortMaxKeys;
+        const int64_t most = survivors / pow2_ceil(K);
+        auto fits = [&](int64_t B) { return N % B == 0 && N / B >= 16 && N / B >= K; };
+        for (int64_t B = pow2_floor(most); B >= 64 && B * 4 >= most && !cp.B; B >>= 1)     // a power of two near the budget,
+            if (fits(B)) { cp.B = (int)B; cp.Kprime = K; }
+        for (int64_t B = most; B >= 64 && !cp.B; --B)                                        // else the greatest divisor of N
+            if (fits(B)) { cp.B = (int)B; cp.Kprime = K; }
+    }
     if (g_opt.certified != 0 && K >= kCertMinK && K <= kWaveSortMaxKeys) {
         // smallest B (fewest survivors) at which nearly every row is certified at once; failing
         // that, the smallest at which a row needs about one bucket repaired.  Powers of two first
@@ -842,7 +860,7 @@ static CertPlan certified_params(int dtype, int64_t N, int K) {
                 }
         }
     }
-    last = {N, K, es, g_opt_generation, cp};
+    last = {rows, N, K, es, g_opt_generation, cp};
     return cp;
 }
 
@@ -860,7 +878,10 @@ static int exact_dispatch(const void* values, int dtype, int64_t rows, int64_t N
                           void* out_vals, int32_t* out_idx, void* workspace, size_t workspace_bytes,
                           hipStream_t st, bool smallest) {
     const uint32_t flip = flip_mask(dtype, smallest);
-    const CertPlan cp = certified_params(dtype, N, K);
+    const CertPlan cp = certified_params(dtype, rows, N, K);
+    if (cp.B && cp.Kprime >= K)          // exact by construction: the two-stage call is the whole job
+        return approx_impl(values, dtype, rows, N, row_stride, K, cp.Kprime, cp.B, out_vals, out_idx,
+                           (uintptr_t)workspace % 8 == 0 ? workspace : nullptr, workspace_bytes, (void*)st, smallest);
     const size_t lists = certified_lists_bytes(rows);
     if (cp.B && workspace && (uintptr_t)workspace % 8 == 0 && workspace_bytes >= lists) {
         const size_t rest = workspace_bytes - lists;
@@ -1127,9 +1148,13 @@ int atk_describe_topk_plan(int dtype, int64_t rows, int64_t N, int K, char* buf,
     if (dtype < 0 || rows < 0 || N <= 0 || N > kMaxN || K < 1 || K > N) return ATK_INVALID_ARG;
     if (K > kExactMaxK) return ATK_UNSUPPORTED;
     options_from_env_once();
-    const CertPlan cp = certified_params(dtype, N, K);
+    const CertPlan cp = certified_params(dtype, rows, N, K);
     if (cp.B) {
         const Plan& pl = make_plan(nullptr, dtype, rows, N, N, K, cp.Kprime, cp.B, false);
+        if (pl.status == ATK_OK && !pl.route_exact && cp.Kprime >= K) {
+            std::snprintf(buf, buflen, "two-stage B=%d K'=K=%d workspace=%zu", cp.B, cp.Kprime, pl.workspace);
+            return ATK_OK;
+        }
         if (pl.status == ATK_OK && !pl.route_exact) {
             std::snprintf(buf, buflen, "certified B=%d K'=%d workspace=%zu (else radix threads=%d)", cp.B, cp.Kprime,
                           certified_lists_bytes(rows) + pl.workspace, exact_threads(N));
@@ -1169,10 +1194,11 @@ size_t atk_workspace_bytes(int op, int dtype, int64_t rows, int64_t N, int K, in
     if (op == ATK_OP_TOPK) {
         if (K < 1 || K > N) return SIZE_MAX;
         options_from_env_once();
-        const CertPlan cp = certified_params(dtype, N, K);
+        const CertPlan cp = certified_params(dtype, rows, N, K);
         if (!cp.B) return 0;
         const Plan& pl = make_plan(nullptr, dtype, rows, N, N, K, cp.Kprime, cp.B, false);
-        return (pl.status == ATK_OK && !pl.route_exact) ? certified_lists_bytes(rows) + pl.workspace : 0;
+        if (pl.status != ATK_OK || pl.route_exact) return 0;
+        return cp.Kprime >= K ? pl.workspace : certified_lists_bytes(rows) + pl.workspace;
     }
     if (op == ATK_OP_STAGE1) return validate_method(N, Kprime, Kprime, B) ? SIZE_MAX : 0;
     if (op != ATK_OP_APPROX_TOPK) return SIZE_MAX;

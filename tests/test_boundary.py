@@ -148,7 +148,15 @@ def test_workspace_query_and_too_small():
     # K' = K beyond the list lengths is the exact Top-K: the same workspace
     assert atk.workspace_bytes(atk.OP_APPROX_TOPK, f32, 4, 65536, 64, 64, 8) == \
         atk.workspace_bytes(atk.OP_TOPK, f32, 4, 65536, 64, 0, 0) > 0
-    assert atk.workspace_bytes(atk.OP_TOPK, f32, 4, 65536, 4, 0, 0) == 0                     # K < 8
+    # K < 8: the two-stage kernels with K' = K, exact by construction; the workspace is what that call
+    # takes (few rows: the slab route); rows too short for it stay with the radix kernel
+    assert atk.describe_topk_plan(f32, 4, 65536, 4)[1].startswith("two-stage B=1024 K'=K=4")
+    assert atk.workspace_bytes(atk.OP_TOPK, f32, 4, 65536, 4, 0, 0) == \
+        atk.workspace_bytes(atk.OP_APPROX_TOPK, f32, 4, 65536, 4, 4, 1024) > 0
+    assert atk.describe_topk_plan(f32, 100000, 512, 1) == (atk.OK, "radix threads=64")
+    assert atk.describe_topk_plan(f32, 300, 65536, 7) == (atk.OK, "radix threads=1024")       # many rows: lists of up to 4
+    assert atk.describe_topk_plan(f32, 30, 65536, 7)[1].startswith("two-stage B=512 K'=K=7")
+    assert atk.describe_topk_plan(f32, 2000, 30000, 1)[1].startswith("two-stage B=1875 K'=K=1")   # no power of two fits
     assert atk.workspace_bytes(atk.OP_TOPK, f32, 4, 1 << 20, 2048, 0, 0) == 0                # K > 1024
     # survivors beyond LDS go through memory: rows * B*K' * (4 + 4) bytes
     need = atk.workspace_bytes(atk.OP_APPROX_TOPK, f32, 8, 131072, 128, 16, 2048)

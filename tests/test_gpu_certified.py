@@ -286,3 +286,35 @@ def test_strided_and_unaligned_rows_through_the_exact_route(atk):
             torch.cuda.synchronize()
             ov, oi = oracle.topk(workloads.to_numpy_bits(x), 64, smallest=smallest)
             assert np.array_equal(gi.cpu().numpy(), oi) and np.array_equal(raw(gv), oracle_raw(ov)), (dt, smallest)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16, torch.int32, torch.uint32])
+def test_very_small_k_through_lists_of_k_entries(atk, knobs, dtype):
+    # K below 8: the two-stage kernels with K' = K keep the whole Top-K by construction, so they are
+    # the exact route (few long rows: the routes that cut rows; many short ones: several rows per
+    # workgroup; bucket counts that are no power of two); lists of 5 to 7 entries only when the
+    # rows are few.  Dense ties, both zeros, infinities, the K smallest, no workspace, option off.
+    for rows, N, Ks in [(3, 1 << 20, (1, 2, 4, 7)), (50, 65536, (1, 3, 4, 6)), (3000, 4096, (1, 2, 4)),
+                        (700, 30000, (1, 4)), (9, 15015 * 16, (2, 5))]:
+        g = torch.Generator().manual_seed(N + rows)
+        if dtype in (torch.int32, torch.uint32):
+            x = torch.randint(-40, 40, (rows, N), generator=g, dtype=torch.int64)
+            x = (x & 0xffffffff).to(torch.uint32) if dtype == torch.uint32 else x.to(torch.int32)
+        else:
+            x = torch.round(torch.randn(rows, N, generator=g) * 3) / 3
+            x[0, 5::7] = 0.0
+            x[0, 6::7] = -0.0
+            x[rows - 1, ::1001] = float("inf")
+            x[rows - 1, 1::1003] = float("-inf")
+            x = x.to(dtype)
+        for K in Ks:
+            check(atk, x, K, expect="two-stage")
+            check(atk, x, K, smallest=True, expect="two-stage")
+    # rows too short for it, and lists of more than four entries with many rows: the radix kernel
+    x = workloads.gaussian(400, 512, seed=5).to(dtype) if dtype not in (torch.int32, torch.uint32) else \
+        torch.randint(0, 1000, (400, 512), dtype=torch.int32).to(dtype)
+    check(atk, x, 1, expect="radix")
+    if dtype == torch.float32:
+        check(atk, workloads.gaussian(300, 65536, seed=6), 7, expect="radix")
+        knobs.set("certified", 0)
+        check(atk, workloads.gaussian(5, 1 << 18, seed=7), 2, expect="radix")
