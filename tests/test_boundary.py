@@ -153,7 +153,8 @@ def test_workspace_query_and_too_small():
     assert atk.describe_topk_plan(f32, 4, 65536, 4)[1].startswith("two-stage B=1024 K'=K=4")
     assert atk.workspace_bytes(atk.OP_TOPK, f32, 4, 65536, 4, 0, 0) == \
         atk.workspace_bytes(atk.OP_APPROX_TOPK, f32, 4, 65536, 4, 4, 1024) > 0
-    assert atk.describe_topk_plan(f32, 100000, 512, 1) == (atk.OK, "radix threads=64")
+    assert atk.describe_topk_plan(f32, 100000, 512, 1)[1].startswith("two-stage B=64 K'=K=1")   # short rows: 64 buckets
+    assert atk.describe_topk_plan(f32, 100000, 480, 1) == (atk.OK, "radix threads=64")           # ... when they divide
     assert atk.describe_topk_plan(f32, 300, 65536, 7) == (atk.OK, "radix threads=1024")       # many rows: lists of up to 4
     assert atk.describe_topk_plan(f32, 30, 65536, 7)[1].startswith("two-stage B=512 K'=K=7")
     assert atk.describe_topk_plan(f32, 2000, 30000, 1)[1].startswith("two-stage B=1875 K'=K=1")   # no power of two fits

@@ -311,9 +311,15 @@ def test_very_small_k_through_lists_of_k_entries(atk, knobs, dtype):
             check(atk, x, K, expect="two-stage")
             check(atk, x, K, smallest=True, expect="two-stage")
     # rows too short for it, and lists of more than four entries with many rows: the radix kernel
-    x = workloads.gaussian(400, 512, seed=5).to(dtype) if dtype not in (torch.int32, torch.uint32) else \
-        torch.randint(0, 1000, (400, 512), dtype=torch.int32).to(dtype)
+    x = workloads.gaussian(400, 480, seed=5).to(dtype) if dtype not in (torch.int32, torch.uint32) else \
+        torch.randint(0, 1000, (400, 480), dtype=torch.int32).to(dtype)
     check(atk, x, 1, expect="radix")
+    # short rows that 64 buckets divide: several rows per workgroup
+    y = workloads.gaussian(5000, 512, seed=8).to(dtype) if dtype not in (torch.int32, torch.uint32) else \
+        torch.randint(0, 50, (5000, 512), dtype=torch.int32).to(dtype)
+    for K in (1, 4):
+        check(atk, y, K, expect="two-stage B=64")
+    check(atk, y[:, :128].contiguous(), 2, smallest=True, expect="two-stage B=64")
     if dtype == torch.float32:
         check(atk, workloads.gaussian(300, 65536, seed=6), 7, expect="radix")
         knobs.set("certified", 0)
