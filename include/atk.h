@@ -170,11 +170,16 @@ int atk_select_params(int64_t N, int K, double recall_target, int max_kprime, in
                       int* Kprime_out, int* B_out, double* expected_recall_out);
 
 /*
- * The (K', B) that atk_approx_topk_recall uses for this problem: atk_select_params with this
- * chip's ceilings (K' <= 4 for 32-bit elements, K' <= 8 for 16-bit ones, B a multiple of 64),
- * restricted to configurations that atk_approx_topk runs for these arguments.  K' = K, B = 1
- * means the exact Top-K (nothing approximate reaches the target); ATK_UNSUPPORTED if that is
- * out of range too (K > 8192).  Host only.  expected_recall_out may be NULL.
+ * The (K', B) that atk_approx_topk_recall uses for this problem, among the configurations that
+ * atk_approx_topk runs for these arguments with K' <= 4 (32-bit elements) or K' <= 8 (16-bit
+ * ones) and B a multiple of 64 whose expected recall (Theorem 1) reaches the target: the shortest
+ * lists for which some B keeps the survivors B*K' within a sixteenth of the row (between 512 and
+ * 4096; 1024 for 16-bit rows of at most 65536 elements), with the smallest sufficient power of
+ * two as B, doubled up to 1024 while the budget allows (else the smallest sufficient divisor of N) -- on this chip the list length is what
+ * stage 1 pays for; when nothing fits that budget, atk_select_params' choice (the fewest
+ * survivors, Section 6.3) under the same ceilings.  K' = K, B = 1 means the exact Top-K (nothing
+ * approximate reaches the target); ATK_UNSUPPORTED if that is out of range too (K > 8192).
+ * Host only; the last answer is cached per thread.  expected_recall_out may be NULL.
  */
 int atk_recall_params(int dtype, int64_t rows, int64_t N, int K, double recall_target, int* Kprime_out,
                       int* B_out, double* expected_recall_out);

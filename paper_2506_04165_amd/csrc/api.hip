@@ -1084,19 +1084,66 @@ int atk_recall_params(int dtype, int64_t rows, int64_t N, int K, double recall_t
                       int* B_out, double* expected_recall_out) {
     if (kernel_dtype(dtype) < 0) return ATK_UNSUPPORTED;
     if (rows < 0) return ATK_INVALID_ARG;
-    struct Ctx { int dtype; int64_t rows, N; int K; } ctx{kernel_dtype(dtype), rows, N, K};
-    // only configurations that atk_approx_topk runs are candidates
-    auto runs = [](void* c, int kp, int64_t B) {
-        const Ctx& x = *(const Ctx*)c;
-        if (B > 0x7fffffff || validate_method(x.N, x.K, kp, (int)B)) return false;
-        return make_plan(nullptr, x.dtype, x.rows, x.N, x.N, x.K, kp, (int)B, false).status == ATK_OK;
-    };
-    // ceilings below which stage 1 stays memory-bound on this chip: K' <= 4 for 32-bit elements,
-    // K' <= 8 for 16-bit ones; buckets in multiples of a wavefront
-    int rc = select_params_impl(N, K, recall_target, elem_size(dtype) == 2 ? 8 : 4, 64, runs, &ctx,
-                                Kprime_out, B_out, expected_recall_out);
-    if (rc) return rc;
-    if (*Kprime_out == K && *B_out == 1 && K > kExactMaxK) return ATK_UNSUPPORTED;   // exact fallback
+    if (N <= 0 || N > kMaxN || K < 1 || K > N || !Kprime_out || !B_out) return ATK_INVALID_ARG;
+    if (!(recall_target > 0.0) || recall_target > 1.0) return ATK_INVALID_ARG;
+    options_from_env_once();
+    // the answer is a pure function of the arguments and the options, and callers in a loop
+    // repeat them (the sweep evaluates Theorem 1 a few hundred times): the last one is kept
+    struct Slot { int dtype; int64_t rows, N; int K; double target; unsigned gen; int rc, kp, b; double r; };
+    thread_local Slot last{-1, 0, 0, 0, 0.0, 0, 0, 0, 0, 0.0};
+    const int kd = kernel_dtype(dtype);
+    if (!(last.dtype == kd && last.rows == rows && last.N == N && last.K == K && last.target == recall_target &&
+          last.gen == g_opt_generation)) {
+        struct Ctx { int dtype; int64_t rows, N; int K; } ctx{kd, rows, N, K};
+        // only configurations that atk_approx_topk runs are candidates
+        auto runs = [](void* c, int kp, int64_t B) {
+            const Ctx& x = *(const Ctx*)c;
+            if (B > 0x7fffffff || validate_method(x.N, x.K, kp, (int)B)) return false;
+            return make_plan(nullptr, x.dtype, x.rows, x.N, x.N, x.K, kp, (int)B, false).status == ATK_OK;
+        };
+        // ceilings below which stage 1 stays memory-bound on this chip: K' <= 4 for 32-bit elements,
+        // K' <= 8 for 16-bit ones; buckets in multiples of a wavefront
+        const int ceiling = elem_size(kd) == 2 ? 8 : 4;
+        int kp = 0, b = 0;
+        double r = 0.0;
+        // On this chip the list length is what stage 1 pays for, and stage 2 is cheap while the
+        // survivors are few against the row: the shortest lists for which some B within a
+        // survivor budget reaches the target -- a sixteenth of the row, between 512 and 4096,
+        // at most 1024 where that keeps 16-bit rows on the packed-key kernels -- and for that K'
+        // the smallest sufficient power of two (doubled up to 1024 within the budget), else the
+        // smallest sufficient divisor.  Measured
+        // against the fewest-survivors rule: 256 x 2^20, K = 128, target 0.95: (1, 2048) 163 us
+        // against (4, 64) 188 us; 4096 x 32768 bf16, K = 100: (1, 1024) 48 us against (4, 64) 102 us.
+        int64_t budget = N / 16 < 512 ? 512 : (N / 16 > 4096 ? 4096 : N / 16);
+        if (elem_size(kd) == 2 && N <= 65536 && budget > kWaveSortMaxKeys) budget = kWaveSortMaxKeys;
+        for (int k = 1; k <= ceiling && k <= K && !kp; ++k) {
+            int64_t first = 0, first_pow2 = 0;
+            for (int64_t B = 64; B * k <= budget && B <= N / k; B += 64) {
+                if (N % B || B * k < K || !runs(&ctx, k, B)) continue;
+                if (first && (B & (B - 1))) continue;                  // after the first: powers of two only
+                const double e = atk_expected_recall(N, B, K, k);
+                if (e < recall_target) continue;
+                if (!first) first = B;
+                if ((B & (B - 1)) == 0) { first_pow2 = B; break; }
+            }
+            int64_t pick = first_pow2 ? first_pow2 : first;
+            // (a power of two below 1024 leaves a lane single-element loads: doubled while the budget
+            // allows -- 256 x 2^20, K = 128, target 0.99: (2, 1024) 162 us against (2, 512) 182 us)
+            while (first_pow2 && pick < 1024 && 2 * pick * k <= budget && N % (2 * pick) == 0 &&
+                   N / (2 * pick) >= k && runs(&ctx, k, 2 * pick))
+                pick *= 2;
+            if (pick) { kp = k; b = (int)pick; r = atk_expected_recall(N, pick, K, k); }
+        }
+        int rc = ATK_OK;
+        if (!kp)        // nothing within the budget: the fewest survivors (Section 6.3's rule)
+            rc = select_params_impl(N, K, recall_target, ceiling, 64, runs, &ctx, &kp, &b, &r);
+        if (!rc && kp == K && b == 1 && K > kExactMaxK) rc = ATK_UNSUPPORTED;   // exact fallback out of range
+        last = {kd, rows, N, K, recall_target, g_opt_generation, rc, kp, b, r};
+    }
+    if (last.rc) return last.rc;
+    *Kprime_out = last.kp;
+    *B_out = last.b;
+    if (expected_recall_out) *expected_recall_out = last.r;
     return ATK_OK;
 }
 
