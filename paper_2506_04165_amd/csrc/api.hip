@@ -1303,9 +1303,16 @@ int atk_mips_approx_topk_recall(const void* queries, const void* database, int d
                                 int64_t N, int64_t D, int K, double recall_target, float* out_vals,
                                 int32_t* out_idx, void* workspace, size_t workspace_bytes,
                                 void* stream, int* Kprime_used, int* B_used) {
-    int kp = 0, b = 0;
-    int rc = atk_mips_select_params(N, K, recall_target, &kp, &b, nullptr);
-    if (rc) return rc;
+    // (the sweep costs a few hundred microseconds of host time: the last answer is kept)
+    struct Slot { int64_t N; int K; double target; int rc, kp, b; };
+    thread_local Slot last{0, 0, 0.0, 0, 0, 0};
+    if (!(last.N == N && last.K == K && last.target == recall_target && N > 0)) {
+        int kp0 = 0, b0 = 0;
+        const int rc0 = atk_mips_select_params(N, K, recall_target, &kp0, &b0, nullptr);
+        last = {N, K, recall_target, rc0, kp0, b0};
+    }
+    if (last.rc) return last.rc;
+    const int kp = last.kp, b = last.b;
     if (Kprime_used) *Kprime_used = kp;
     if (B_used) *B_used = b;
     return atk_mips_approx_topk(queries, database, dtype, Q, N, D, K, kp, b, out_vals, out_idx,
