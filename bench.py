@@ -39,16 +39,16 @@ PAPER_CONTEXT = {
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by a plain
 # copy of known size (profiles/approx_topk_<workload>_B<B>_Kp<K'>.md), keyed by (workload, B, K').
 MEASURED_TRAFFIC_BYTES = {
-    ("c4_mips", 1024, 4): 1076706527,
-    ("c4_mips", 4096, 1): 1076507712,
-    ("c2_ffn", 128, 4): 498472284,
-    ("c2_ffn", 1024, 1): 498758244,
-    ("c2_ffn", 64, 8): 498460330,
-    ("c3_vocab", 512, 4): 528439926,
-    ("c3_vocab", 512, 2): 528316553,
-    ("c5_adversarial", 256, 8): 271409796,
-    ("c5_adversarial", 256, 1): 278177195,
-    ("c5_adversarial", 256, 32): 272520448,
+    ("c4_mips", 1024, 4): 1076698920,
+    ("c4_mips", 4096, 1): 1076517540,
+    ("c2_ffn", 128, 4): 498472164,
+    ("c2_ffn", 1024, 1): 498756221,
+    ("c2_ffn", 64, 8): 498461493,
+    ("c3_vocab", 512, 4): 528411933,
+    ("c3_vocab", 512, 2): 528323407,
+    ("c5_adversarial", 256, 8): 271377613,
+    ("c5_adversarial", 256, 1): 278876889,
+    ("c5_adversarial", 256, 32): 272485584,
 }
 
 
