@@ -266,3 +266,35 @@ def test_no_alloc_entry_validates_like_the_workspace_entry():
     assert f(None, 0, 0, 4096, 4096, 32, 4, 64, None, None, None) == atk.OK
     # survivors that the library's own scratch array (16 MiB) cannot hold: refused before any launch
     assert f(FAKE, 0, 45, 150000, 150000, 100, 1, 50000, FAKE, FAKE, None) == atk.WORKSPACE_TOO_SMALL
+
+
+def test_planner_choices_found_by_the_sweep_for_cliffs():
+    # shapes outside the benchmark set on which a plausible plan was several times slower than
+    # the one now taken (measured on the GPU; here the plan itself is pinned)
+    f32 = torch.float32
+
+    def plan(*a):
+        st, text = atk.describe_plan(f32, *a)
+        assert st == atk.OK
+        return text
+
+    # more survivors than a wavefront sorts: one row per workgroup and a lane per eight survivors
+    # (rows sharing a workgroup would end in a full LDS sort of all their candidates)
+    t = plan(16384, 4096, 64, 4, 1024)
+    assert "lanes_per_row=512 rows_per_wg=1 " in t and "tail=2" in t, t
+    t = plan(8192, 8192, 1024, 32, 64)
+    assert t.startswith("fused batched") and "rows_per_wg=1 " in t and "tail=2" in t, t
+    # few long rows with few buckets: as many segments as fill the chip (a row of 64 lanes streams
+    # a quarter of what 256 lanes do), up to 128
+    assert "grid=2x128 " in plan(8, 1 << 24, 64, 4, 64)
+    assert "grid=3x64 " in plan(12, 1 << 20, 64, 4, 64)
+    # 128 rows of 1024 lanes are 2048 wavefronts on half of the CUs: cut in two
+    assert plan(128, 1 << 20, 128, 4, 1024).startswith("split") and "grid=128x2 " in plan(128, 1 << 20, 128, 4, 1024)
+    assert plan(200, 1 << 19, 128, 4, 1024).startswith("fused")
+    # long buckets: the variants with deferred insertion
+    assert plan(256, 1 << 20, 128, 4, 1024).startswith("fused deferred")
+    assert plan(1024, 65536, 256, 8, 256).startswith("fused deferred")
+    assert plan(512, 256000, 64, 4, 512).startswith("fused KP=4")            # 500 steps: not worth it
+    # few rows: stage 2 by ranking on the slab route and on survivors beyond LDS
+    assert "rank_finish=32x128" in plan(8, 262144, 1024, 4, 1024)
+    assert "rank_finish=32x1024" in plan(64, 1 << 20, 1024, 4, 8192) and plan(64, 1 << 20, 1024, 4, 8192).startswith("unfused")
