@@ -631,13 +631,17 @@ static const Plan& make_plan(const void* values, int dtype, int64_t rows, int64_
     // Value+step lists, long buckets: the variant that sets an element aside when it beats its
     // list's least entry and inserts it later (wavefront-uniform branch, rarely taken) instead of
     // updating the list with every element.  Measured: lists of 8 entries from 128 steps a row
-    // on (1024 x 65536, 256 buckets: 81 -> 75 us), shorter lists from 768 steps (256 x 2^20,
-    // 1024 buckets, K' = 4: 170 -> 166 us; at 500 steps and fewer, or with one list per lane --
-    // one branch per element then -- 1-4 % slower).  Option "defer": 0 never, 2 wherever such a
-    // variant exists.
+    // on (1024 x 65536, 256 buckets: 81 -> 75 us; 512 x 262144: 160 -> 126 us), lists of 3 and 4
+    // from 768 steps (256 x 2^20, 1024 buckets, K' = 4: 170 -> 166 us; at 500 steps and fewer, or
+    // with one list per lane -- one branch per element then -- 1-4 % slower), from 256 steps for
+    // 16-bit rows, which reach the vector ALU's limit at half the operations per element (4096 x
+    // 131072 bf16, 256 buckets, K' = 4: 304 -> 241 us); never lists of 2 (bf16: 99 -> 118 us).
+    // Option "defer": 0 never, 2 wherever such a variant exists.
     if (pl.status == ATK_OK && !pl.route_exact && pl.var && pl.var->rep == 0 && g_opt.defer != 0) {
         const int steps = pl.nseg > 1 ? pl.seg_steps : pl.nsteps;
-        const bool pays = pl.var->KP >= 8 ? steps >= 128 : (steps >= 768 && pl.var->V * pl.var->R >= 2);
+        const int lists = pl.var->V * pl.var->R, kp = pl.var->KP;
+        const bool pays = kp >= 6 ? steps >= 128
+                                  : (kp >= 3 && lists >= 2 && steps >= (elem_size(pl.var->dtype) == 2 ? 256 : 768));
         if (pays || g_opt.defer == 2)
             for (const Variant& v : kVariants)
                 if (v.rep == 4 && v.dtype == pl.var->dtype && v.KP == pl.var->KP && v.V == pl.var->V && v.R == pl.var->R) {

@@ -295,6 +295,9 @@ def test_planner_choices_found_by_the_sweep_for_cliffs():
     assert plan(256, 1 << 20, 128, 4, 1024).startswith("fused deferred")
     assert plan(1024, 65536, 256, 8, 256).startswith("fused deferred")
     assert plan(512, 256000, 64, 4, 512).startswith("fused KP=4")            # 500 steps: not worth it
+    assert plan(256, 1 << 20, 128, 2, 1024).startswith("fused KP=2")          # nor are lists of two
+    st, text = atk.describe_plan(torch.bfloat16, 4096, 131072, 256, 4, 256)   # 16-bit rows: from 256 steps
+    assert st == atk.OK and text.startswith("fused deferred"), text
     # few rows: stage 2 by ranking on the slab route and on survivors beyond LDS
     assert "rank_finish=32x128" in plan(8, 262144, 1024, 4, 1024)
     assert "rank_finish=32x1024" in plan(64, 1 << 20, 1024, 4, 8192) and plan(64, 1 << 20, 1024, 4, 8192).startswith("unfused")
