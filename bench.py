@@ -116,7 +116,7 @@ def executed_ops_per_element(plan, Kp):
     (the compiled code's count, against Section 6.3's 5K'-2 for the select-only form)."""
     import re
     kp = int(re.search(r"KP=(\d+)", plan).group(1))       # compiled list length (>= K')
-    if " packed" in plan:
+    if " packed" in plan or " lists32" in plan:
         return kp + 3.0           # ordered images of two bf16 by three packed ops, one max, KP-1 medians
     if " batched" in plan:
         # sorted batches of 64-bit keys: per batch of KP elements a bitonic sort (log2(KP)(log2(KP)+1)/2

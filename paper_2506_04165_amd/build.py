@@ -37,6 +37,7 @@ SOURCES = [
     "approx_inst_batched.hip",
     "approx_inst_f32_defer.hip",
     "approx_inst_bf16_defer.hip",
+    "approx_inst_bf16_long.hip",
     "approx_inst_i32_small.hip",
     "approx_inst_i32_wide.hip",
     "approx_inst_i32_unaligned.hip",

@@ -41,7 +41,7 @@ template <typename Pred>
 static const Variant* find_variant(int dtype, int KP, int NL, bool packed_ok, Pred vector_ok) {
     const Variant* best = nullptr;
     for (const Variant& v : kVariants) {
-        if (v.dtype != dtype || v.KP != KP || v.V * v.R != NL || !vector_ok(v.V) || v.rep == 2 || v.rep == 4) continue;
+        if (v.dtype != dtype || v.KP != KP || v.V * v.R != NL || !vector_ok(v.V) || v.rep == 2 || v.rep == 4 || v.rep == 5) continue;
         if (v.packed() && !packed_ok) continue;
         if (!best || (v.packed() && !best->packed()) || (v.packed() == best->packed() && v.V > best->V))
             best = &v;
@@ -637,6 +637,18 @@ static const Plan& make_plan(const void* values, int dtype, int64_t rows, int64_
     // 16-bit rows, which reach the vector ALU's limit at half the operations per element (4096 x
     // 131072 bf16, 256 buckets, K' = 4: 304 -> 241 us); never lists of 2 (bf16: 99 -> 118 us).
     // Option "defer": 0 never, 2 wherever such a variant exists.
+    // 16-bit rows on the value+step lists (too long for keys that hold the position, or off the plain
+    // fused route): the variant whose lists hold packed keys of value and step -- K'+3 operations
+    // per element instead of 4K'-1 -- and which builds the general keys from them afterwards.
+    // The step must fit 16 bits.  (4096 x 131072 bf16, 256 buckets, K' = 4: 241 -> 150 us.)
+    if (pl.status == ATK_OK && !pl.route_exact && pl.var && pl.var->rep == 0 && elem_size(pl.var->dtype) == 2 &&
+        pl.nsteps <= 65535 && g_opt.packed != 0) {
+        for (const Variant& v : kVariants)
+            if (v.rep == 5 && v.dtype == pl.var->dtype && v.KP == pl.var->KP && v.V == pl.var->V && v.R == pl.var->R) {
+                pl.var = &v;
+                break;
+            }
+    }
     if (pl.status == ATK_OK && !pl.route_exact && pl.var && pl.var->rep == 0 && g_opt.defer != 0) {
         const int steps = pl.nseg > 1 ? pl.seg_steps : pl.nsteps;
         const int lists = pl.var->V * pl.var->R, kp = pl.var->KP;
@@ -1356,7 +1368,7 @@ int atk_describe_plan(int dtype, int64_t rows, int64_t N, int K, int Kprime, int
                   "%s%s KP=%d V=%d R=%d lanes_per_row=%d rows_per_wg=%d block=%d grid=%dx%d step=%d "
                   "steps=%d owners=%d seg=%d cand=%d tail=%d lds=%zu workspace=%zu",
                   pl.slab_w > 0 ? "slab" : pl.nseg > 1 ? "split" : (pl.fused ? "fused" : (pl.chunk_k > 0 ? "chunked" : "unfused")),
-                  pl.var->packed() ? " packed" : (pl.var->rep == 2 ? " batched" : (pl.var->rep == 4 ? " deferred" : "")), pl.var->KP, pl.var->V,
+                  pl.var->packed() ? " packed" : (pl.var->rep == 2 ? " batched" : (pl.var->rep == 4 ? " deferred" : (pl.var->rep == 5 ? " lists32" : ""))), pl.var->KP, pl.var->V,
                   pl.var->R, pl.G, pl.rows_per_wg, pl.block, pl.grid,
                   pl.slab_w > 0 ? B / pl.slab_w : (pl.nseg > 1 ? pl.nseg : pl.nchunk), pl.S, pl.nsteps,
                   pl.owners, pl.seg, pl.Cpad, pl.tail, pl.lds, pl.workspace);

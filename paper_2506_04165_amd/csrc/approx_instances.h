@@ -7,7 +7,8 @@
 // X(DTYPE_TAG, C++ type, KP, V, R, REP)   REP: 0 value+step lists, 1 packed 32-bit keys,
 //                                          2 sorted batches of 64-bit keys, 3 insertion lists of
 //                                          64-bit keys (integer inputs), 4 value+step lists
-//                                          with deferred insertion
+//                                          with deferred insertion, 5 packed keys in the lists and
+//                                          64-bit keys from there on (16-bit rows of any length)
 // DTYPE_TAG: 0 fp32, 1 bf16 (fp16 runs on the bf16 kernels), 3 int32, 4 uint32
 #define ATK_INSTANCES_NL1(X, TAG, T, V, R, P) \
     X(TAG, T, 1, V, R, P) X(TAG, T, 2, V, R, P) X(TAG, T, 3, V, R, P) X(TAG, T, 4, V, R, P) \
@@ -91,6 +92,16 @@
     ATK_DEFER_NL1(X, 1, bf16_t, 1, 1) ATK_DEFER_NL1(X, 1, bf16_t, 2, 1) ATK_DEFER_NL1(X, 1, bf16_t, 4, 1) \
     ATK_DEFER_NL8(X, 1, bf16_t, 8, 1) X(1, bf16_t, 2, 8, 2, 4)
 
+// 16-bit rows of any length (at most 65535 steps): lists of packed 32-bit keys, 64-bit keys from
+// the lists on (REP 5); lists of up to 8 entries
+#define ATK_LONG16_NL(X, V, R) \
+    X(1, bf16_t, 1, V, R, 5) X(1, bf16_t, 2, V, R, 5) X(1, bf16_t, 3, V, R, 5) X(1, bf16_t, 4, V, R, 5)
+#define ATK_INSTANCES_BF16_LONG(X) \
+    ATK_LONG16_NL(X, 1, 1) X(1, bf16_t, 6, 1, 1, 5) X(1, bf16_t, 8, 1, 1, 5) \
+    ATK_LONG16_NL(X, 2, 1) X(1, bf16_t, 6, 2, 1, 5) X(1, bf16_t, 8, 2, 1, 5) \
+    ATK_LONG16_NL(X, 4, 1) X(1, bf16_t, 6, 4, 1, 5) X(1, bf16_t, 8, 4, 1, 5) \
+    ATK_LONG16_NL(X, 8, 1) X(1, bf16_t, 1, 8, 2, 5) X(1, bf16_t, 2, 8, 2, 5)
+
 // large K', at most 256 buckets: sorted batches of 64-bit keys, one list per lane
 #define ATK_INSTANCES_BATCHED(X) \
     X(0, float, 8, 1, 1, 2) X(0, float, 16, 1, 1, 2) X(0, float, 32, 1, 1, 2) \
@@ -102,6 +113,6 @@
     ATK_INSTANCES_F32_SMALL(X) ATK_INSTANCES_F32_WIDE(X) ATK_INSTANCES_F32_UNALIGNED(X) \
     ATK_INSTANCES_BF16_SMALL(X) ATK_INSTANCES_BF16_WIDE(X) ATK_INSTANCES_BF16_UNALIGNED(X) \
     ATK_INSTANCES_BF16_PACKED(X) ATK_INSTANCES_BATCHED(X) \
-    ATK_INSTANCES_F32_DEFER(X) ATK_INSTANCES_BF16_DEFER(X) \
+    ATK_INSTANCES_F32_DEFER(X) ATK_INSTANCES_BF16_DEFER(X) ATK_INSTANCES_BF16_LONG(X) \
     ATK_INSTANCES_I32_SMALL(X) ATK_INSTANCES_I32_WIDE(X) ATK_INSTANCES_I32_UNALIGNED(X) \
     ATK_INSTANCES_U32_SMALL(X) ATK_INSTANCES_U32_WIDE(X) ATK_INSTANCES_U32_UNALIGNED(X)

@@ -206,6 +206,13 @@ struct Lists<1, KP, NL> {
     }
 };
 
+//  * packed 32-bit keys in the lists, 64-bit keys from there on (16-bit rows of any length
+//    with at most 65535 steps): stage 1 as above -- the step fits the low half whatever the
+//    row's length -- and what leaves the lists is turned into the general (value, position)
+//    keys, so every route and stage 2 of the value+step lists apply unchanged.
+template <int KP, int NL>
+struct Lists<5, KP, NL> : Lists<1, KP, NL> {};
+
 //  * sorted batches of 64-bit keys (large K', one list per lane): K' consecutive elements of the
 //    slot are turned into keys (ordered value << 32 | ~step), sorted in registers by a bitonic
 //    network, and merged with the running list (element-wise max against the reversed batch
@@ -300,7 +307,8 @@ struct Lists<3, KP, NL> {
 
 template <typename DT, int KP, int V, int R, int REP = 0>
 struct ApproxKernel {
-    static constexpr bool PACKED = REP == 1;
+    static constexpr bool PACKED = REP == 1;             // packed lists and the 32-bit stage 2
+    static constexpr bool PACKED_LISTS = REP == 1 || REP == 5;
     static constexpr bool BATCHED = REP == 2;
     static constexpr int NL = V * R;
     static constexpr int DW = (V * elem<DT>::size + 3) / 4;           // dwords per load
@@ -308,7 +316,7 @@ struct ApproxKernel {
     static constexpr int U = U_ < 1 ? 1 : (U_ > 16 ? 16 : U_);        // at most 16 steps
     using VL = vec_load<DT, V>;
     using vec_t = typename VL::vec_t;
-    static_assert(!PACKED || elem<DT>::size == 2, "packed keys are for 16-bit inputs");
+    static_assert(!PACKED_LISTS || elem<DT>::size == 2, "packed keys are for 16-bit inputs");
 
     // Stored bit pattern of a list entry (lists of keys hold the ordered image instead).
     __device__ static __forceinline__ uint32_t stored_bits(const Lists<REP, KP, NL>& L, int l, int k) {
@@ -328,7 +336,7 @@ struct ApproxKernel {
 #pragma unroll
             for (int v = 0; v < V; ++v)
                 L.insert(r * V + v, elem<DT>::ordered(VL::bits(x, v) ^ flip), step);
-        } else if constexpr (!PACKED) {
+        } else if constexpr (!PACKED_LISTS) {
 #pragma unroll
             for (int v = 0; v < V; ++v) {
                 if constexpr (FULL && KP > 1) L.insert_full(r * V + v, __uint_as_float(VL::bits(x, v) ^ flip), step);

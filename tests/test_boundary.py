@@ -296,8 +296,18 @@ def test_planner_choices_found_by_the_sweep_for_cliffs():
     assert plan(1024, 65536, 256, 8, 256).startswith("fused deferred")
     assert plan(512, 256000, 64, 4, 512).startswith("fused KP=4")            # 500 steps: not worth it
     assert plan(256, 1 << 20, 128, 2, 1024).startswith("fused KP=2")          # nor are lists of two
-    st, text = atk.describe_plan(torch.bfloat16, 4096, 131072, 256, 4, 256)   # 16-bit rows: from 256 steps
-    assert st == atk.OK and text.startswith("fused deferred"), text
+    # 16-bit rows too long for keys that hold the position: packed keys of value and step in the
+    # lists, the general keys from there on; without them, deferred insertion from 256 steps
+    st, text = atk.describe_plan(torch.bfloat16, 4096, 131072, 256, 4, 256)
+    assert st == atk.OK and text.startswith("fused lists32"), text
+    atk.set_option("packed", 0)
+    try:
+        st, text = atk.describe_plan(torch.bfloat16, 4096, 131072, 256, 4, 256)
+        assert st == atk.OK and text.startswith("fused deferred"), text
+    finally:
+        atk.set_option("packed", -1)
+    st, text = atk.describe_plan(torch.float16, 3, 1 << 23, 64, 4, 64)        # more than 65535 steps
+    assert st == atk.OK and "lists32" not in text, text
     # few rows: stage 2 by ranking on the slab route and on survivors beyond LDS
     assert "rank_finish=32x128" in plan(8, 262144, 1024, 4, 1024)
     assert "rank_finish=32x1024" in plan(64, 1 << 20, 1024, 4, 8192) and plan(64, 1 << 20, 1024, 4, 8192).startswith("unfused")

@@ -153,12 +153,16 @@ def test_bucket_counts_that_are_not_powers_of_two_and_tiny_rows(atk, N, B, Kp, K
 
 
 @pytest.mark.parametrize("N,B,Kp,K", [(65536, 256, 4, 300), (65536, 1024, 1, 1000), (65536, 64, 16, 1024),
-                                      (65536, 512, 2, 512), (131072, 256, 4, 300), (32768, 128, 6, 700)])
+                                      (65536, 512, 2, 512), (131072, 256, 4, 300), (32768, 128, 6, 700),
+                                      (1 << 21, 64, 8, 300), (1 << 23, 128, 3, 200), (1 << 23, 64, 4, 100)])
 def test_bf16_packed_key_limits(atk, N, B, Kp, K):
     # rows of up to 65536 bf16 elements run on packed 32-bit keys (positions 0..65535 must all
-    # be representable), longer rows on the general lists; ties are dense in bf16
+    # be representable); longer rows keep packed keys of value and step in their lists and build
+    # the general keys from them (lists of up to 8 entries, up to 65535 steps: the very last step
+    # must be representable too), beyond that the general lists; ties are dense in bf16
     st, text = atk.describe_plan(torch.bfloat16, 5, N, K, Kp, B)
     assert st == atk.OK and (" packed" in text) == (N <= 65536), text
+    assert (" lists32" in text) == (N > 65536 and Kp <= 8 and N // B <= 65535), text
     x = workloads.gaussian(5, N, seed=500 + B + Kp, dtype=torch.bfloat16)
     x[0, N - 1] = 100.0        # the very last position must be able to win
     x[1, :] = 1.5              # one value everywhere: the index alone decides
