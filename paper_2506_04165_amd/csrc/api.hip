@@ -444,8 +444,10 @@ static Plan compute_plan(const void* values, int dtype, int64_t rows, int64_t N,
             // LDS reads per thread of a placing workgroup, half of every head being in play
             const int64_t reads = (int64_t)per_wg * ((int64_t)1 << log_head) / 2 * nruns * (log_head + 1) / 256;
             const size_t ws_runs = (size_t)rows * nruns * run_len * 8;
+            // (LDS of a placing workgroup: the heads, a rank word per key of its own runs)
+            const size_t rank_lds = ((size_t)nruns << log_head) * 8 + (size_t)per_wg * run_len * 4 + 256;
             if ((nruns << log_head) <= kRankMaxHeadKeys && reads <= 1024 && ws_runs <= ws_avail &&
-                (size_t)pl.block * per_lane * 8 <= kLdsBudget) {
+                rank_lds <= kLdsBudget && (size_t)pl.block * per_lane * 8 <= kLdsBudget) {
                 pl.run_len = run_len;
                 pl.rank_runs_per_wg = per_wg;
                 pl.lds = (size_t)pl.block * per_lane * 8;
