@@ -196,6 +196,15 @@ int atk_approx_topk_recall(const void* values, int dtype, int64_t rows, int64_t 
                            void* stream, int* Kprime_used, int* B_used);
 
 /*
+ * The same for the mirrored problem (atk_approx_mink with K' and B chosen by atk_recall_params;
+ * Theorem 1 does not depend on which end of the order is asked for).
+ */
+int atk_approx_mink_recall(const void* values, int dtype, int64_t rows, int64_t N,
+                           int64_t row_stride, int K, double recall_target, void* out_vals,
+                           int32_t* out_idx, void* workspace, size_t workspace_bytes,
+                           void* stream, int* Kprime_used, int* B_used);
+
+/*
  * One-line description of how atk_topk / atk_mink run the given problem when handed the workspace
  * atk_workspace_bytes(ATK_OP_TOPK, ...) asks for: "certified B=... K'=... workspace=..." or
  * "radix threads=...".  Host only; for logs and tests.

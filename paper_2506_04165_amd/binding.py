@@ -26,7 +26,7 @@ SIZE_MAX = ctypes.c_size_t(-1).value
 
 EXPORTS = [
     "atk_approx_topk", "atk_approx_mink", "atk_mink", "atk_approx_topk_noalloc", "atk_topk", "atk_approx_topk_stage1", "atk_workspace_bytes",
-    "atk_expected_recall", "atk_select_params", "atk_recall_params", "atk_set_option", "atk_approx_topk_recall", "atk_describe_plan", "atk_describe_topk_plan", "atk_valu_probe", "atk_read_probe",
+    "atk_expected_recall", "atk_select_params", "atk_recall_params", "atk_set_option", "atk_approx_topk_recall", "atk_approx_mink_recall", "atk_describe_plan", "atk_describe_topk_plan", "atk_valu_probe", "atk_read_probe",
     "atk_mips_approx_topk", "atk_mips_workspace_bytes", "atk_mips_describe_plan", "atk_mips_select_params", "atk_mips_approx_topk_recall", "atk_status_string", "atk_last_hip_error",
     "atk_version",
 ]
@@ -72,6 +72,8 @@ def _load() -> ctypes.CDLL:
     lib.atk_set_option.restype = ci
     lib.atk_approx_topk_recall.argtypes = [vp, ci, i64, i64, i64, ci, ctypes.c_double, vp, vp, vp, sz, vp, ip, ip]
     lib.atk_approx_topk_recall.restype = ci
+    lib.atk_approx_mink_recall.argtypes = lib.atk_approx_topk_recall.argtypes
+    lib.atk_approx_mink_recall.restype = ci
     lib.atk_valu_probe.argtypes = [ci, vp, vp, vp, sz, ci, vp]
     lib.atk_valu_probe.restype = ci
     lib.atk_read_probe.argtypes = [vp, sz, vp, vp]
@@ -209,26 +211,28 @@ def _workspace_ptr(workspace, device):
     return workspace.data_ptr(), workspace.numel() * workspace.element_size()
 
 
-def approx_topk_recall(values: torch.Tensor, K: int, recall_target: float, workspace=None):
-    """approx_top_k(array, K, recall_target): returns (vals, idx, K' used, B used)."""
+def approx_topk_recall(values: torch.Tensor, K: int, recall_target: float, workspace=None, smallest: bool = False):
+    """approx_top_k(array, K, recall_target) (smallest: the K smallest): returns (vals, idx, K' used, B used)."""
     rows, N, stride = _check_input(values)
     code = _dtype_code(values)
     kp, b, _ = recall_params(values.dtype, rows, N, K, recall_target)
     out_vals = torch.empty((rows, K), dtype=values.dtype, device=values.device)
     out_idx = torch.empty((rows, K), dtype=torch.int32, device=values.device)
     ws_ptr, ws_bytes = None, 0
-    if not (kp == K and b == 1):
-        need = lib.atk_workspace_bytes(OP_APPROX_TOPK, code, rows, N, K, kp, b)
-        if need != SIZE_MAX and need > 0:
-            if workspace is None or workspace.numel() * workspace.element_size() < need:
-                workspace = torch.empty(need, dtype=torch.uint8, device=values.device)
-            ws_ptr, ws_bytes = _workspace_ptr(workspace, values.device)
+    # (K' = K, B = 1 -- the exact fallback -- is sized like the exact entry)
+    need = (lib.atk_workspace_bytes(OP_TOPK, code, rows, N, K, 0, 0) if (kp == K and b == 1)
+            else lib.atk_workspace_bytes(OP_APPROX_TOPK, code, rows, N, K, kp, b))
+    if need != SIZE_MAX and need > 0:
+        if workspace is None or workspace.numel() * workspace.element_size() < need:
+            workspace = torch.empty(need, dtype=torch.uint8, device=values.device)
+        ws_ptr, ws_bytes = _workspace_ptr(workspace, values.device)
     kp_used, b_used = ctypes.c_int(0), ctypes.c_int(0)
-    st = lib.atk_approx_topk_recall(values.data_ptr(), code, rows, N, stride, K, recall_target,
-                                    out_vals.data_ptr(), out_idx.data_ptr(), ws_ptr, ws_bytes,
-                                    _stream_ptr(values.device), ctypes.byref(kp_used), ctypes.byref(b_used))
+    entry = lib.atk_approx_mink_recall if smallest else lib.atk_approx_topk_recall
+    st = entry(values.data_ptr(), code, rows, N, stride, K, recall_target,
+               out_vals.data_ptr(), out_idx.data_ptr(), ws_ptr, ws_bytes,
+               _stream_ptr(values.device), ctypes.byref(kp_used), ctypes.byref(b_used))
     if st != OK:
-        raise AtkError(st, "atk_approx_topk_recall")
+        raise AtkError(st, "atk_approx_mink_recall" if smallest else "atk_approx_topk_recall")
     return out_vals, out_idx, kp_used.value, b_used.value
 
 

@@ -1165,20 +1165,39 @@ int atk_recall_params(int dtype, int64_t rows, int64_t N, int K, double recall_t
     return ATK_OK;
 }
 
-int atk_approx_topk_recall(const void* values, int dtype, int64_t rows, int64_t N,
-                           int64_t row_stride, int K, double recall_target, void* out_vals,
-                           int32_t* out_idx, void* workspace, size_t workspace_bytes,
-                           void* stream, int* Kprime_used, int* B_used) {
+static int exact_impl(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride, int K,
+                      void* out_vals, int32_t* out_idx, void* workspace, size_t workspace_bytes,
+                      void* stream, bool smallest);
+
+static int recall_impl(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride, int K,
+                       double recall_target, void* out_vals, int32_t* out_idx, void* workspace,
+                       size_t workspace_bytes, void* stream, int* Kprime_used, int* B_used, bool smallest) {
     int kp = 0, b = 0;
     int rc = atk_recall_params(dtype, rows, N, K, recall_target, &kp, &b, nullptr);
     if (rc) return rc;
     if (Kprime_used) *Kprime_used = kp;
     if (B_used) *B_used = b;
-    if (kp == K && b == 1)   // nothing approximate reaches the target: exact Top-K
-        return atk_topk(values, dtype, rows, N, row_stride, K, out_vals, out_idx, workspace,
-                        workspace_bytes, stream);
-    return atk_approx_topk(values, dtype, rows, N, row_stride, K, kp, b, out_vals, out_idx,
-                           workspace, workspace_bytes, stream);
+    if (kp == K && b == 1)   // nothing approximate reaches the target: the exact result
+        return exact_impl(values, dtype, rows, N, row_stride, K, out_vals, out_idx, workspace, workspace_bytes,
+                          stream, smallest);
+    return approx_impl(values, dtype, rows, N, row_stride, K, kp, b, out_vals, out_idx, workspace,
+                       workspace_bytes, stream, smallest);
+}
+
+int atk_approx_topk_recall(const void* values, int dtype, int64_t rows, int64_t N,
+                           int64_t row_stride, int K, double recall_target, void* out_vals,
+                           int32_t* out_idx, void* workspace, size_t workspace_bytes,
+                           void* stream, int* Kprime_used, int* B_used) {
+    return recall_impl(values, dtype, rows, N, row_stride, K, recall_target, out_vals, out_idx, workspace,
+                       workspace_bytes, stream, Kprime_used, B_used, false);
+}
+
+int atk_approx_mink_recall(const void* values, int dtype, int64_t rows, int64_t N,
+                           int64_t row_stride, int K, double recall_target, void* out_vals,
+                           int32_t* out_idx, void* workspace, size_t workspace_bytes,
+                           void* stream, int* Kprime_used, int* B_used) {
+    return recall_impl(values, dtype, rows, N, row_stride, K, recall_target, out_vals, out_idx, workspace,
+                       workspace_bytes, stream, Kprime_used, B_used, true);
 }
 
 static int exact_impl(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride, int K,

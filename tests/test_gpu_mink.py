@@ -114,3 +114,19 @@ def test_min_k_is_top_k_of_the_reversed_values(atk):
     v2, i2 = atk.topk(~y, 500)
     torch.cuda.synchronize()
     assert torch.equal(i, i2) and torch.equal(v, ~v2)
+
+
+def test_min_k_for_a_recall_target(atk):
+    # atk_approx_mink_recall: the library's (K', B) for the target, the K smallest; the same bits
+    # as the oracle's mirrored problem at those parameters; the exact fallback as well
+    for dtype, rows, N, K, target in [(torch.float32, 6, 65536, 256, 0.95), (torch.bfloat16, 9, 14336, 287, 0.99),
+                                      (torch.int32, 4, 262144, 100, 0.9), (torch.float32, 5, 30000, 50, 0.9)]:
+        x = ints(rows, N, seed=K) if dtype == torch.int32 else workloads.gaussian(rows, N, seed=K, dtype=dtype)
+        v, i, kp, B = atk.approx_topk_recall(x.to(DEV), K, target, smallest=True)
+        torch.cuda.synchronize()
+        assert (kp, B) == atk.recall_params(dtype, rows, N, K, target)[:2]
+        xh = workloads.to_numpy_bits(x)
+        ov, oi = (oracle.topk(xh, K, smallest=True) if (kp, B) == (K, 1)
+                  else oracle.approx_topk(xh, K, kp, B, smallest=True))
+        assert np.array_equal(i.cpu().numpy(), oi), (dtype, N, K, kp, B)
+        assert np.array_equal(raw(v), oracle_raw(ov)), (dtype, N, K, kp, B)
