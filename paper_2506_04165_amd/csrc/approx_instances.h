@@ -81,26 +81,30 @@
     ATK_PACKED_NL8(X, 8, 1) ATK_PACKED_NL16(X, 8, 2)
 
 // value+step lists with deferred insertion (REP 4), for long buckets: lists of 2 to 8 entries,
-// aligned vector loads
+// aligned vector loads; lists of 16 entries with one or two lists per lane (with 32 entries the
+// variant spills: 380 -> 1100 us)
 #define ATK_DEFER_NL1(X, TAG, T, V, R) \
     X(TAG, T, 2, V, R, 4) X(TAG, T, 3, V, R, 4) X(TAG, T, 4, V, R, 4) X(TAG, T, 6, V, R, 4) X(TAG, T, 8, V, R, 4)
 #define ATK_DEFER_NL8(X, TAG, T, V, R) X(TAG, T, 2, V, R, 4) X(TAG, T, 3, V, R, 4) X(TAG, T, 4, V, R, 4)
 #define ATK_INSTANCES_F32_DEFER(X) \
     ATK_DEFER_NL1(X, 0, float, 1, 1) ATK_DEFER_NL1(X, 0, float, 2, 1) ATK_DEFER_NL1(X, 0, float, 4, 1) \
-    ATK_DEFER_NL8(X, 0, float, 4, 2) X(0, float, 2, 4, 4, 4)
+    ATK_DEFER_NL8(X, 0, float, 4, 2) X(0, float, 2, 4, 4, 4) \
+    X(0, float, 16, 1, 1, 4) X(0, float, 16, 2, 1, 4)
 #define ATK_INSTANCES_BF16_DEFER(X) \
     ATK_DEFER_NL1(X, 1, bf16_t, 1, 1) ATK_DEFER_NL1(X, 1, bf16_t, 2, 1) ATK_DEFER_NL1(X, 1, bf16_t, 4, 1) \
-    ATK_DEFER_NL8(X, 1, bf16_t, 8, 1) X(1, bf16_t, 2, 8, 2, 4)
+    ATK_DEFER_NL8(X, 1, bf16_t, 8, 1) X(1, bf16_t, 2, 8, 2, 4) \
+    X(1, bf16_t, 16, 1, 1, 4) X(1, bf16_t, 16, 2, 1, 4)
 
 // 16-bit rows of any length (at most 65535 steps): lists of packed 32-bit keys, 64-bit keys from
-// the lists on (REP 5); lists of up to 8 entries
+// the lists on (REP 5); lists of up to 8 entries, of 16 and 32 with one or two lists per lane
 #define ATK_LONG16_NL(X, V, R) \
     X(1, bf16_t, 1, V, R, 5) X(1, bf16_t, 2, V, R, 5) X(1, bf16_t, 3, V, R, 5) X(1, bf16_t, 4, V, R, 5)
 #define ATK_INSTANCES_BF16_LONG(X) \
     ATK_LONG16_NL(X, 1, 1) X(1, bf16_t, 6, 1, 1, 5) X(1, bf16_t, 8, 1, 1, 5) \
     ATK_LONG16_NL(X, 2, 1) X(1, bf16_t, 6, 2, 1, 5) X(1, bf16_t, 8, 2, 1, 5) \
     ATK_LONG16_NL(X, 4, 1) X(1, bf16_t, 6, 4, 1, 5) X(1, bf16_t, 8, 4, 1, 5) \
-    ATK_LONG16_NL(X, 8, 1) X(1, bf16_t, 1, 8, 2, 5) X(1, bf16_t, 2, 8, 2, 5)
+    ATK_LONG16_NL(X, 8, 1) X(1, bf16_t, 1, 8, 2, 5) X(1, bf16_t, 2, 8, 2, 5) \
+    X(1, bf16_t, 16, 1, 1, 5) X(1, bf16_t, 32, 1, 1, 5) X(1, bf16_t, 16, 2, 1, 5)
 
 // large K', at most 256 buckets: sorted batches of 64-bit keys, one list per lane
 #define ATK_INSTANCES_BATCHED(X) \

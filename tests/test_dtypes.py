@@ -138,7 +138,7 @@ ROUTES = [
     (8, 262144, 1024, 4, 1024, "split"),
     (4, 131072, 128, 16, 2048, "chunked"),     # survivors beyond LDS: every chunk's K greatest through memory
     (4, 131072, 128, 16, 2048, "unfused"),     # ... or all survivors
-    (6, 65536, 256, 32, 256, "fused"),         # long lists: sorted batches
+    (6, 65536, 256, 32, 256, "fused"),        # long lists: sorted batches (16-bit rows: packed lists, few-row route)
     (5, 8192, 40, 40, 8, "exact"),             # K' = K beyond the register lists
 ]
 
@@ -163,6 +163,13 @@ def test_half_rows_every_route(atk, rows, N, K, Kp, B, route, knobs):
         knobs.set("segments", 4)
     if route == "chunked":
         knobs.set("chunked", 1)
+    if (Kp, B) == (32, 256):
+        # 16-bit rows keep packed keys in long lists as well (instead of sorted batches), which
+        # opens the few-row route to them; the sorted batches with the packed keys switched off
+        for kind in ("patterns", "gauss"):
+            check(atk, half_rows(rows, N, seed=32, kind=kind), K, Kp, B, "slab lists32")
+        knobs.set("packed", 0)
+        route = "fused batched"
     for kind in ("patterns", "gauss"):
         check(atk, half_rows(rows, N, seed=32, kind=kind), K, Kp, B, route)
 
