@@ -980,8 +980,8 @@ def test_seeded_random_shapes_many_buckets_large_k_and_options(atk, knobs, seed,
             x = x.to(dt)
         status, plan = atk.describe_plan(dt, rows, N, K, Kp, B)
         assert status == atk.OK, plan
-        print(f"case {case}: {dt} rows={rows} N={N} B={B} K'={Kp} K={K} style={style} {opts} {plan.split()[0]}"
-              f"{' ranked' if 'rank_finish' in plan else ''}", flush=True)
+        print(f"case {case}: {dt} rows={rows} N={N} B={B} K'={Kp} K={K} style={style} {opts} "
+              f"{plan.split(' KP=')[0]}{' ranked' if 'rank_finish' in plan else ''}", flush=True)
         xh, xd = workloads.to_numpy_bits(x), x.to(DEV)
         gv, gi = atk.approx_topk(xd, K, Kp, B)
         torch.cuda.synchronize()
