@@ -77,8 +77,8 @@ typedef enum atk_op { ATK_OP_APPROX_TOPK = 0, ATK_OP_TOPK = 1, ATK_OP_STAGE1 = 2
  *              workgroups share, go through this buffer and a second launch finishes.  A
  *              buffer that is too small for the shared-row routes only switches them off)
  *              More than 16384 survivors per row (any B): stage 1 writes them to the workspace,
- *              rows cut along the bucket axis over several workgroups, and the exact kernel
- *              selects among them (the unfused implementation of the paper's appendix).
+ *              rows cut along the bucket axis over several workgroups, and a second launch
+ *              runs stage 2 on them (the unfused implementation of the paper's appendix).
  * ATK_UNSUPPORTED: K' > 32 unless K' == K (then the exact kernel runs); K > 8192 on the exact and
  * unfused routes; B > 2^24.
  */
@@ -124,12 +124,15 @@ int atk_approx_topk_noalloc(const void* values, int dtype, int64_t rows, int64_t
  * what the method reduces to at K' = K or B = 1).  Arguments as above.  ATK_UNSUPPORTED: K > 8192.
  *
  * workspace: optional device memory, 8-byte aligned.  With atk_workspace_bytes(ATK_OP_TOPK, ...)
- * bytes (0 where it does not apply: short rows, K < 8, K > 1024) rows that are long against K are
+ * bytes (0 where it does not apply: short rows, K > 1024) rows that are long against K are
  * done by the two-stage kernels at a (B, K' = 4) chosen by the library, followed by a kernel that
  * certifies each row exact (no bucket contributes K' elements to the result) or repairs it from
  * the buckets in doubt: one pass over the input at the approximate method's speed, the result is
- * the exact Top-K bit for bit.  Without it (null, or too small) a radix-selection kernel runs,
- * which needs no workspace.  Workspace contents need not be initialised and are not preserved.
+ * the exact Top-K bit for bit.  K < 8: the two-stage kernels with K' = K, exact by construction
+ * (the workspace then is what atk_approx_topk takes for those parameters: only few, long rows
+ * need one, and without it the single fused launch runs).  Otherwise, and without a workspace
+ * (null, or too small), a radix-selection kernel runs, which needs none.  Workspace contents need
+ * not be initialised and are not preserved.  atk_describe_topk_plan says which of these a call takes.
  */
 int atk_topk(const void* values, int dtype, int64_t rows, int64_t N, int64_t row_stride, int K,
              void* out_vals, int32_t* out_idx, void* workspace, size_t workspace_bytes,
