@@ -108,8 +108,9 @@ int atk_mink(const void* values, int dtype, int64_t rows, int64_t N, int64_t row
  * routes, survivors beyond LDS) this entry uses an array of ATK_NOALLOC_SCRATCH_BYTES that is part
  * of the library's code object (each GPU the library runs on holds its copy until the process
  * ends); it calls no allocating routine.  Problems whose survivors need more than that
- * (rows * B * K' * (element size + 4) bytes when B*K' > 16384) are refused with
- * ATK_WORKSPACE_TOO_SMALL; the few-row routes simply fall back to the single fused launch.
+ * (rows * B * K' * (element size + 4) bytes when B*K' > 16384, or 8 bytes per survivor, a lane's
+ * share padded to a power of two, where the second launch ranks sorted runs; atk_workspace_bytes
+ * gives the figure) are refused with ATK_WORKSPACE_TOO_SMALL; the few-row routes simply fall back to the single fused launch.
  * Nothing in the array has to start at zero (every word read was written by the same call), so
  * nothing is cleared.  All calls on one GPU share the array: calls that may overlap on one GPU
  * (different streams, other host threads) race on it -- serialise them, or use atk_approx_topk
